@@ -1,0 +1,446 @@
+"""CPU oracle for the per-chunk streaming sparse-attention step of Ltri-LLM.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the HIP
+library is checked against.  Only tests, the smoke check and the benchmark's
+`cpu_baseline` leg may import it; the product path never does.  It shares no
+code with the HIP path and imports nothing from it.  All arithmetic is fp64
+numpy; a library matmul / cumsum / sort may serve as a step, nothing is
+blocked, fused or reordered beyond what the paper's definitions state.
+
+Notation follows the paper: N (here L) tokens of a chunk, H heads summed,
+A the causal attention map (Eq. 1-3), S*_{xy} / S_{xy} the Triangle-Attention
+score of the span [x, y] (Eq. 4 / Eq. 5), theta the map threshold, phi the
+NMS IoU threshold, index (representative) vectors K^R / Q^R (Sec. 3.3),
+sim_{ij} (Eq. 8), Top-K retrieval (Eq. 9), and the attended set
+initial | retrieved | window | current (Sec. 3.4, third step).
+
+Readings taken where the paper is silent (each is listed in the design notes):
+  * the map that is segmented is the appended chunk's own L x L causal map;
+  * theta is an absolute per-head value (it sits inside the head sum in Eq. 5);
+  * NMS boxes are 1-D token intervals, IoU on inclusive token counts;
+  * kept intervals are turned into a tiling by cutting at all their end points;
+  * the representative vector of a span is the mean of its rows (mean pooling,
+    Sec. 3.3.1); by bilinearity Eq. 8 only needs one vector per span;
+  * retrieval works on spans under a token budget (longest fitting prefix of
+    the score order), not on fixed 128-token blocks;
+  * LOGIT map kind (masked scaled scores without the softmax) exists next to
+    the paper's SOFTMAX kind because row-normalised maps of planted keys do
+    not carry mixed-length triangles.
+
+Pinned by tests/test_oracle_pins.py (brute-force triple sums, ideal-map and
+planted-key boundary recovery, NMS brute force, top-k vs full sort, the
+select-everything == full causal attention invariant, brute-force softmax
+attention, LSE-merge identity, decode == one-row prefill).
+Parity unpinned: the SOFTMAX map kind on planted keys has no ground truth for
+which spans are "right"; it is pinned only through Eq. 4/5 and the NMS pins.
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass, field
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+MAP_SOFTMAX = 0
+MAP_LOGIT = 1
+
+
+# ----------------------------------------------------------------------------
+# rounding helper (representative vectors are stored in the stream's dtype)
+# ----------------------------------------------------------------------------
+def round_to_dtype(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round fp64 values once, to nearest-even, to `dtype` ("f32" | "bf16" | "f64")."""
+    x = np.asarray(x, dtype=np.float64)
+    if dtype == "f64":
+        return x.copy()
+    if dtype == "f32":
+        return x.astype(np.float32).astype(np.float64)
+    if dtype == "bf16":
+        m, e = np.frexp(x)                 # x = m * 2**e, 0.5 <= |m| < 1
+        q = np.rint(m * 256.0) / 256.0     # keep 8 significant bits, ties to even
+        return np.ldexp(q, e)
+    raise ValueError(dtype)
+
+
+# ----------------------------------------------------------------------------
+# step 1a: causal map of one chunk (Eq. 1-3), summed over the heads (Eq. 4)
+# ----------------------------------------------------------------------------
+def chunk_map(K: np.ndarray, Q: Optional[np.ndarray], kind: int) -> Tuple[np.ndarray, int]:
+    """Head-summed lower-triangular map of one chunk for one KV head.
+
+    K: [L, d] keys of the chunk.  Q: [G, L, d] queries of the KV head's group,
+    or None, in which case the keys play the role of the queries (one head).
+    Returns (M [L, L] with zeros above the diagonal, n_h = heads summed).
+    """
+    K = np.asarray(K, dtype=np.float64)
+    L, d = K.shape
+    Qs = K[None] if Q is None else np.asarray(Q, dtype=np.float64)
+    n_h = Qs.shape[0]
+    low = np.tril(np.ones((L, L), dtype=bool))           # mask P of Eq. 2
+    M = np.zeros((L, L), dtype=np.float64)
+    for g in range(n_h):
+        z = (Qs[g] @ K.T) / math.sqrt(d)
+        if kind == MAP_SOFTMAX:
+            z = np.where(low, z, -np.inf)
+            z = z - z.max(axis=1, keepdims=True)
+            e = np.exp(z)
+            a = e / e.sum(axis=1, keepdims=True)           # Eq. 1 restricted by Eq. 3
+        elif kind == MAP_LOGIT:
+            a = z
+        else:
+            raise ValueError(kind)
+        M += np.where(low, a, 0.0)
+    return M, n_h
+
+
+# ----------------------------------------------------------------------------
+# step 1b: Triangle-Attention score of every span (Eq. 4, Eq. 5)
+# ----------------------------------------------------------------------------
+def ta_scores(M: np.ndarray, theta: float, n_h: int) -> np.ndarray:
+    """S[x, y] for 0 <= x <= y < L; entries with x > y are -inf.
+
+    Second form of Eq. 4: rows 0..y, columns x..L-1 of the lower-triangular
+    map, i.e. a cumulative sum from the right along each row followed by a
+    cumulative sum down each column.  Eq. 5 subtracts theta on every cell of
+    the mask inside the head sum, i.e. theta * n_h * (#cells of the triangle).
+    """
+    L = M.shape[0]
+    R = np.cumsum(M[:, ::-1], axis=1)[:, ::-1]           # R[i, x] = sum_{j >= x} M[i, j]
+    C = np.cumsum(R, axis=0)                             # C[y, x] = sum_{i <= y} R[i, x]
+    x = np.arange(L)[:, None]
+    y = np.arange(L)[None, :]
+    n = y - x + 1
+    tri = n * (n + 1) // 2
+    S = C.T - theta * n_h * tri
+    return np.where(x <= y, S, -np.inf)
+
+
+# ----------------------------------------------------------------------------
+# step 1c: candidate filter (appendix "NMS Input Filtration")
+# ----------------------------------------------------------------------------
+def antidiagonal_candidates(S: np.ndarray) -> List[Tuple[float, int, int]]:
+    """Best-scoring span on each anti-diagonal x + y = s, kept only if its score is > 0.
+
+    Ties go to the larger x (the shorter span)."""
+    L = S.shape[0]
+    out = []
+    for s in range(2 * L - 1):
+        x_lo = max(0, s - (L - 1))
+        x_hi = s // 2
+        xs = np.arange(x_lo, x_hi + 1)
+        vals = S[xs, s - xs]
+        best = vals.max()
+        if not best > 0.0:
+            continue
+        x = int(xs[np.nonzero(vals == best)[0][-1]])
+        out.append((float(best), x, s - x))
+    return out
+
+
+# ----------------------------------------------------------------------------
+# step 1d: greedy NMS on 1-D intervals (Sec. 3.2)
+# ----------------------------------------------------------------------------
+def nms_1d(cands: Sequence[Tuple[float, int, int]], phi: float,
+           max_keep: int = 0) -> List[Tuple[float, int, int]]:
+    """Greedy non-maximum suppression.
+
+    Candidates are visited by decreasing score (ties: smaller x, then smaller
+    y).  A candidate is dropped when some already kept interval overlaps it
+    with intersection > phi * union, both counted in tokens (inclusive ends);
+    the comparison is done in fp32 with a single multiply so it can be
+    reproduced exactly elsewhere.  `max_keep` > 0 stops after that many keeps.
+    """
+    order = sorted(cands, key=lambda c: (-c[0], c[1], c[2]))
+    phi32 = np.float32(phi)
+    kept: List[Tuple[float, int, int]] = []
+    for (s, x, y) in order:
+        ok = True
+        for (_, a, b) in kept:
+            inter = min(y, b) - max(x, a) + 1
+            if inter <= 0:
+                continue
+            union = (y - x + 1) + (b - a + 1) - inter
+            if np.float32(inter) > phi32 * np.float32(union):
+                ok = False
+                break
+        if ok:
+            kept.append((s, x, y))
+            if max_keep and len(kept) >= max_keep:
+                break
+    return kept
+
+
+def partition_from_kept(kept: Sequence[Tuple[float, int, int]], L: int) -> np.ndarray:
+    """Cut [0, L) at every kept interval's x and y+1; returns the sorted cuts incl. 0 and L."""
+    cuts = {0, L}
+    for (_, x, y) in kept:
+        cuts.add(x)
+        cuts.add(y + 1)
+    return np.asarray(sorted(cuts), dtype=np.int64)
+
+
+def segment_chunk(K: np.ndarray, Q: Optional[np.ndarray], kind: int, theta: float,
+                  phi: float, max_keep: int = 0, z_perturb: Optional[np.ndarray] = None
+                  ) -> np.ndarray:
+    """Boundaries (chunk-local, first 0, last L) of the spans of one chunk (Sec. 3.4, first step)."""
+    M, n_h = chunk_map(K, Q, kind)
+    if z_perturb is not None:
+        M = M * (1.0 + z_perturb)
+    S = ta_scores(M, theta, n_h)
+    cands = antidiagonal_candidates(S)
+    kept = nms_1d(cands, phi, max_keep)
+    return partition_from_kept(kept, K.shape[0])
+
+
+def segmentation_is_stable(K: np.ndarray, Q: Optional[np.ndarray], kind: int, theta: float,
+                           phi: float, max_keep: int = 0, rel: float = 2.0 ** -18,
+                           draws: int = 2, seed: int = 0) -> bool:
+    """Audit of one chunk: do the boundaries survive relative perturbations of every map
+    cell that are ~32x larger than fp32 rounding?  Bit-exact parity with an fp32
+    map is only asserted on chunks that pass."""
+    base = segment_chunk(K, Q, kind, theta, phi, max_keep)
+    rng = np.random.default_rng(seed)
+    L = K.shape[0]
+    for _ in range(draws):
+        p = rng.uniform(-rel, rel, size=(L, L))
+        b = segment_chunk(K, Q, kind, theta, phi, max_keep, z_perturb=p)
+        if len(b) != len(base) or np.any(b != base):
+            return False
+    return True
+
+
+# ----------------------------------------------------------------------------
+# representative vectors (mean pooling, Sec. 3.3.1) and similarity (Eq. 8)
+# ----------------------------------------------------------------------------
+def span_means(X: np.ndarray, bounds: np.ndarray, dtype: str) -> np.ndarray:
+    """Mean of the rows of X [L, d] over each span [bounds[s], bounds[s+1]); rounded once to dtype."""
+    X = np.asarray(X, dtype=np.float64)
+    out = np.empty((len(bounds) - 1, X.shape[1]), dtype=np.float64)
+    for s in range(len(bounds) - 1):
+        a, b = int(bounds[s]), int(bounds[s + 1])
+        out[s] = X[a:b].sum(axis=0) / float(b - a)
+    return round_to_dtype(out, dtype)
+
+
+def span_scores(Qrep: np.ndarray, Krep: np.ndarray) -> np.ndarray:
+    """score_i = max_j Qrep_j . Krep_i  (Eq. 8 with one vector per span, max over the
+    query spans as in Eq. 9)."""
+    sim = np.asarray(Qrep, np.float64) @ np.asarray(Krep, np.float64).T     # [n_q_spans, n_spans]
+    return sim.max(axis=0)
+
+
+def clipped_ranges(starts: np.ndarray, lens: np.ndarray, n_sink: int, win_start: int
+                   ) -> Tuple[np.ndarray, np.ndarray]:
+    """Part of every stored span that lies in the evicted region [n_sink, win_start)."""
+    a = np.maximum(starts, n_sink)
+    b = np.minimum(starts + lens, win_start)
+    return a, b
+
+
+def select_spans(scores: np.ndarray, clip_len: np.ndarray, eligible: np.ndarray,
+                 k_max: int, budget_tokens: int) -> np.ndarray:
+    """Top-K of Eq. 9 at span granularity: eligible spans by (-score, id); the longest
+    prefix with sum(clipped length) <= budget (if > 0) and count <= k_max (if > 0).
+    Returns the selected ids in ascending order."""
+    ids = [int(i) for i in np.nonzero(eligible)[0]]
+    ids.sort(key=lambda i: (-float(scores[i]), i))
+    sel: List[int] = []
+    total = 0
+    for i in ids:
+        if k_max and len(sel) >= k_max:
+            break
+        if budget_tokens and total + int(clip_len[i]) > budget_tokens:
+            break
+        sel.append(i)
+        total += int(clip_len[i])
+    return np.asarray(sorted(sel), dtype=np.int64)
+
+
+# ----------------------------------------------------------------------------
+# exact attention over an explicit key set (Sec. 3.4, third step)
+# ----------------------------------------------------------------------------
+def attend_rows(Q: np.ndarray, K: np.ndarray, V: np.ndarray, ctx_idx: np.ndarray,
+                c0: int, rows: Optional[Sequence[int]] = None
+                ) -> Tuple[np.ndarray, np.ndarray]:
+    """softmax(q K^T / sqrt(d)) V for query rows of the chunk starting at c0.
+
+    Q: [L, d] (one query head), K/V: [T, d] (its KV head), ctx_idx: token ids of the
+    non-current part (initial | retrieved | window), shared by all rows; row i also
+    sees the current tokens c0..c0+i.  Returns (O [len(rows), d], lse [len(rows)]).
+    """
+    Q = np.asarray(Q, np.float64)
+    K = np.asarray(K, np.float64)
+    V = np.asarray(V, np.float64)
+    L, d = Q.shape
+    rows = list(range(L)) if rows is None else list(rows)
+    Kc, Vc = K[ctx_idx], V[ctx_idx]
+    zc = (Q[rows] @ Kc.T) / math.sqrt(d)                   # [r, n_ctx]
+    O = np.empty((len(rows), d))
+    lse = np.empty(len(rows))
+    for r, i in enumerate(rows):
+        zl = (K[c0:c0 + i + 1] @ Q[i]) / math.sqrt(d)
+        z = np.concatenate([zc[r], zl])
+        m = z.max()
+        p = np.exp(z - m)
+        den = p.sum()
+        O[r] = (p[:len(ctx_idx)] @ Vc + p[len(ctx_idx):] @ V[c0:c0 + i + 1]) / den
+        lse[r] = m + math.log(den)
+    return O, lse
+
+
+# ----------------------------------------------------------------------------
+# the streaming step for one (layer, sequence): all KV heads
+# ----------------------------------------------------------------------------
+@dataclass
+class OracleConfig:
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    dtype: str                 # "f32" | "bf16": dtype the representative vectors are stored in
+    n_sink: int
+    window: int
+    k_max: int = 0
+    budget_tokens: int = 0
+    seg_map: int = MAP_LOGIT
+    theta: float = 0.0
+    phi: float = 0.0
+    max_spans_per_chunk: int = 0
+
+    @property
+    def group(self) -> int:
+        return self.n_q_heads // self.n_kv_heads
+
+
+class OracleStream:
+    """Index memory + the three steps for one sequence of one layer.
+
+    K, V: [Hkv][T][d] full streams (only tokens already appended are read),
+    held by reference."""
+
+    def __init__(self, cfg: OracleConfig, K: np.ndarray, V: np.ndarray):
+        self.cfg = cfg
+        self.K = np.asarray(K, np.float64)
+        self.V = np.asarray(V, np.float64)
+        H = cfg.n_kv_heads
+        self.n_tokens = 0
+        self.starts: List[List[int]] = [[] for _ in range(H)]
+        self.lens: List[List[int]] = [[] for _ in range(H)]
+        self.krep: List[List[np.ndarray]] = [[] for _ in range(H)]
+        self.last_chunk: Tuple[int, int] = (0, 0)                  # (c0, L)
+        self.last_bounds: List[np.ndarray] = [np.zeros(0, np.int64) for _ in range(H)]
+        self.sel: List[np.ndarray] = [np.zeros(0, np.int64) for _ in range(H)]
+        self.sel_scores: List[np.ndarray] = [np.zeros(0) for _ in range(H)]
+
+    # -- step 1 -------------------------------------------------------------
+    def append_chunk(self, n_new: int, q_seg: Optional[np.ndarray] = None,
+                     bounds: Optional[Sequence[np.ndarray]] = None) -> None:
+        """Segment tokens [T, T+n_new), store spans and representative keys.
+
+        q_seg: [n_new][Hq][d] queries used to build the map, or None (keys are used).
+        bounds: per KV head chunk-local boundaries to use instead of segmenting."""
+        c = self.cfg
+        c0 = self.n_tokens
+        for h in range(c.n_kv_heads):
+            Kc = self.K[h, c0:c0 + n_new]
+            if bounds is not None:
+                b = np.asarray(bounds[h], np.int64)
+            else:
+                Qg = None
+                if q_seg is not None:
+                    Qg = np.asarray(q_seg, np.float64)[:, h * c.group:(h + 1) * c.group, :]
+                    Qg = np.transpose(Qg, (1, 0, 2))
+                b = segment_chunk(Kc, Qg, c.seg_map, c.theta, c.phi, c.max_spans_per_chunk)
+            reps = span_means(Kc, b, c.dtype)
+            for s in range(len(b) - 1):
+                self.starts[h].append(c0 + int(b[s]))
+                self.lens[h].append(int(b[s + 1] - b[s]))
+                self.krep[h].append(reps[s])
+            self.last_bounds[h] = b
+        self.last_chunk = (c0, n_new)
+        self.n_tokens = c0 + n_new
+
+    def win_start(self, c0: int) -> int:
+        return max(min(self.cfg.n_sink, c0), c0 - self.cfg.window)
+
+    # -- step 2 -------------------------------------------------------------
+    def retrieve(self, q: np.ndarray) -> List[np.ndarray]:
+        """q: [L][Hq][d] queries of the last appended chunk.  Selected span ids per KV head."""
+        c = self.cfg
+        c0, L = self.last_chunk
+        q = np.asarray(q, np.float64)
+        assert q.shape[0] == L
+        ws = self.win_start(c0)
+        out = []
+        for h in range(c.n_kv_heads):
+            qsum = q[:, h * c.group:(h + 1) * c.group, :].sum(axis=1)        # sum over the group's heads
+            Qrep = span_means(qsum, self.last_bounds[h], c.dtype)
+            starts = np.asarray(self.starts[h], np.int64)
+            lens = np.asarray(self.lens[h], np.int64)
+            a, b = clipped_ranges(starts, lens, min(c.n_sink, c0), ws)
+            eligible = a < b
+            if eligible.any():
+                Krep = np.stack(self.krep[h])
+                scores = span_scores(Qrep, Krep)
+            else:
+                scores = np.zeros(len(starts))
+            sel = select_spans(scores, b - a, eligible, c.k_max, c.budget_tokens)
+            self.sel[h] = sel
+            self.sel_scores[h] = scores
+            out.append(sel)
+        return out
+
+    def force_selection(self, h: int, ids: Sequence[int]) -> None:
+        self.sel[h] = np.asarray(sorted(int(i) for i in ids), np.int64)
+
+    # -- step 3 -------------------------------------------------------------
+    def context_tokens(self, h: int) -> np.ndarray:
+        """Token ids of initial | retrieved (clipped) | window for the last chunk, ascending."""
+        c = self.cfg
+        c0, _ = self.last_chunk
+        n_sink = min(c.n_sink, c0)
+        ws = self.win_start(c0)
+        parts = [np.arange(0, n_sink)]
+        for i in self.sel[h]:
+            a = max(self.starts[h][i], n_sink)
+            b = min(self.starts[h][i] + self.lens[h][i], ws)
+            if a < b:
+                parts.append(np.arange(a, b))
+        parts.append(np.arange(ws, c0))
+        return np.concatenate(parts).astype(np.int64)
+
+    def attend(self, q: np.ndarray, rows: Optional[Sequence[int]] = None,
+               heads: Optional[Sequence[int]] = None) -> Tuple[np.ndarray, np.ndarray]:
+        """q: [L][Hq][d].  Returns O [len(rows)][len(heads)][d], lse [len(rows)][len(heads)]."""
+        c = self.cfg
+        c0, L = self.last_chunk
+        q = np.asarray(q, np.float64)
+        rows = list(range(L)) if rows is None else list(rows)
+        heads = list(range(c.n_q_heads)) if heads is None else list(heads)
+        O = np.empty((len(rows), len(heads), c.head_dim))
+        lse = np.empty((len(rows), len(heads)))
+        ctx_cache = {}
+        for k, g in enumerate(heads):
+            h = g // c.group
+            if h not in ctx_cache:
+                ctx_cache[h] = self.context_tokens(h)
+            o, l = attend_rows(q[:, g, :], self.K[h], self.V[h], ctx_cache[h], c0, rows)
+            O[:, k, :] = o
+            lse[:, k] = l
+        return O, lse
+
+
+def full_causal_attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, pos: Sequence[int]
+                          ) -> np.ndarray:
+    """Textbook causal softmax attention for query positions `pos` (one head):
+    row t attends keys 0..t.  Q: [T, d] indexed by absolute position."""
+    Q = np.asarray(Q, np.float64)
+    K = np.asarray(K, np.float64)
+    V = np.asarray(V, np.float64)
+    d = Q.shape[1]
+    out = np.empty((len(pos), d))
+    for r, t in enumerate(pos):
+        z = (K[:t + 1] @ Q[t]) / math.sqrt(d)
+        p = np.exp(z - z.max())
+        out[r] = (p @ V[:t + 1]) / p.sum()
+    return out

@@ -1,0 +1,398 @@
+"""Pins of the CPU oracle against things other than itself: brute-force sums written
+straight from the equations, closed forms, planted inputs whose answer is known by
+construction, characterisations that any correct result must satisfy, and library
+routines (sort, torch rounding) on special cases."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ltri_oracle as O
+from workloads import CONFIGS, planted_stream, theta_default, draw_span_lengths
+
+
+# ---------------------------------------------------------------- rounding
+def test_round_bf16_matches_torch_and_ties_to_even():
+    rng = np.random.default_rng(0)
+    x = (rng.standard_normal(20000) * np.exp(rng.uniform(-8, 8, 20000))).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).to(torch.float64).numpy()
+    got = O.round_to_dtype(x.astype(np.float64), "bf16")
+    assert np.array_equal(got, want)
+    # exact ties: 1 + 2^-8 is halfway between 1 and 1 + 2^-7 -> even mantissa (1.0)
+    assert O.round_to_dtype(np.array([1 + 2.0 ** -8]), "bf16")[0] == 1.0
+    assert O.round_to_dtype(np.array([1 + 3 * 2.0 ** -8]), "bf16")[0] == 1 + 2.0 ** -6
+    # a value just above the tie, not representable in fp32, must round up (no double rounding)
+    assert O.round_to_dtype(np.array([1 + 2.0 ** -8 + 2.0 ** -40]), "bf16")[0] == 1 + 2.0 ** -7
+    assert O.round_to_dtype(np.array([-(1 + 2.0 ** -8 + 2.0 ** -40)]), "bf16")[0] == -(1 + 2.0 ** -7)
+
+
+# ---------------------------------------------------------------- P1: Eq. 4 / Eq. 5
+def _brute_S(Ah, theta):
+    """Literal first form of Eq. 4 with the threshold of Eq. 5: sum over heads and over
+    the cells x <= j <= i <= y of (A_hij - theta)."""
+    H, N, _ = Ah.shape
+    S = np.full((N, N), -np.inf)
+    for x in range(N):
+        for y in range(x, N):
+            acc = 0.0
+            for h in range(H):
+                for i in range(x, y + 1):
+                    for j in range(x, i + 1):
+                        acc += Ah[h, i, j] - theta
+            S[x, y] = acc
+    return S
+
+
+@pytest.mark.parametrize("N,H,theta", [(1, 1, 0.0), (7, 1, 0.3), (12, 3, 0.05), (17, 2, 0.0)])
+def test_ta_scores_equal_literal_triple_sum(N, H, theta):
+    rng = np.random.default_rng(N * 31 + H)
+    Ah = np.tril(rng.uniform(0.0, 1.0, size=(H, N, N)))
+    S = O.ta_scores(Ah.sum(axis=0), theta, H)
+    want = _brute_S(Ah, theta)
+    mask = np.isfinite(want)
+    assert np.array_equal(np.isfinite(S), mask)
+    np.testing.assert_allclose(S[mask], want[mask], rtol=0, atol=1e-10)
+
+
+def test_ta_closed_forms():
+    # constant map c on the whole lower triangle: S_xy = (c - theta) * n_h * tri(y - x + 1)
+    N, c, theta, H = 9, 0.7, 0.2, 2
+    M = np.tril(np.full((N, N), c * H))
+    S = O.ta_scores(M, theta, H)
+    for x in range(N):
+        for y in range(x, N):
+            n = y - x + 1
+            assert abs(S[x, y] - (c - theta) * H * n * (n + 1) / 2) < 1e-12
+    # positive map, theta = 0: the largest score is the whole-chunk span (Sec. 3.2)
+    rng = np.random.default_rng(3)
+    M = np.tril(rng.uniform(0.01, 1, (N, N)))
+    S = O.ta_scores(M, 0.0, 1)
+    assert np.unravel_index(np.argmax(S), S.shape) == (0, N - 1)
+    # row-stochastic map (what Eq. 1-3 produce): S*_{0,n-1} = n for every prefix
+    M, n_h = O.chunk_map(rng.standard_normal((N, 4)), None, O.MAP_SOFTMAX)
+    S = O.ta_scores(M, 0.0, n_h)
+    np.testing.assert_allclose(S[0, :], np.arange(1, N + 1), atol=1e-12)
+
+
+def test_chunk_map_against_loops():
+    rng = np.random.default_rng(5)
+    L, d, G = 6, 4, 3
+    K = rng.standard_normal((L, d))
+    Q = rng.standard_normal((G, L, d))
+    Ms, nh = O.chunk_map(K, Q, O.MAP_SOFTMAX)
+    Ml, _ = O.chunk_map(K, Q, O.MAP_LOGIT)
+    assert nh == G
+    for i in range(L):
+        for j in range(L):
+            want_s = 0.0
+            want_l = 0.0
+            if j <= i:
+                for g in range(G):
+                    z = [sum(Q[g, i, c] * K[jj, c] for c in range(d)) / math.sqrt(d) for jj in range(i + 1)]
+                    den = sum(math.exp(v) for v in z)
+                    want_s += math.exp(z[j]) / den
+                    want_l += z[j]
+            assert abs(Ms[i, j] - want_s) < 1e-12
+            assert abs(Ml[i, j] - want_l) < 1e-12
+    Mk, nh = O.chunk_map(K, None, O.MAP_LOGIT)
+    assert nh == 1
+    np.testing.assert_allclose(Mk, np.tril(K @ K.T / math.sqrt(d)), atol=1e-14)
+
+
+# ---------------------------------------------------------------- P2: ideal maps
+def _ideal_map(bounds, L, c):
+    M = np.zeros((L, L))
+    for a, b in zip(bounds[:-1], bounds[1:]):
+        M[a:b, a:b] = c
+    return np.tril(M)
+
+
+@pytest.mark.parametrize("dist,lo,hi", [("uniform", 1, 40), ("loguniform", 2, 256), ("uniform", 16, 128)])
+@pytest.mark.parametrize("frac", [0.5, 0.6, 0.7])
+def test_ideal_map_recovers_planted_boundaries(dist, lo, hi, frac):
+    L, c = 384, 1.7
+    for seed in range(6):
+        rng = np.random.default_rng([seed, lo, hi])
+        lens = draw_span_lengths(rng, L, dist, lo, hi)
+        bounds = np.concatenate([[0], np.cumsum(lens)])
+        M = _ideal_map(bounds, L, c)
+        S = O.ta_scores(M, frac * c, 1)
+        kept = O.nms_1d(O.antidiagonal_candidates(S), 0.0)
+        cuts = O.partition_from_kept(kept, L)
+        assert list(cuts) == list(bounds)
+        # the kept intervals are exactly the planted spans (appendix on candidate filtering:
+        # the score rises up to the planted span and falls beyond it)
+        assert sorted((x, y + 1) for _, x, y in kept) == list(zip(bounds[:-1], bounds[1:]))
+
+
+def test_antidiagonal_filter_rule():
+    # one candidate per anti-diagonal at most, positive only, shortest on ties
+    S = np.full((4, 4), -np.inf)
+    for x in range(4):
+        for y in range(x, 4):
+            S[x, y] = 1.0          # all tied -> largest x wins on every anti-diagonal
+    c = O.antidiagonal_candidates(S)
+    assert [(x, y) for _, x, y in c] == [(0, 0), (0, 1), (1, 1), (1, 2), (2, 2), (2, 3), (3, 3)]
+    S[:] = np.where(np.isfinite(S), -1.0, S)
+    S[1, 2] = 0.0                  # not > 0: dropped
+    assert O.antidiagonal_candidates(S) == []
+    S[0, 3] = 2.0
+    assert O.antidiagonal_candidates(S) == [(2.0, 0, 3)]
+
+
+# ---------------------------------------------------------------- P3: planted keys
+SHIPPED_SEEDS = {"cfg1": [1, 2, 3], "cfg2": [1], "cfg3": [1]}
+
+
+@pytest.mark.parametrize("name,ctx", [("cfg1", 4096), ("cfg2", 2048), ("cfg3", 4096)])
+def test_planted_keys_recovered(name, ctx):
+    w = CONFIGS[name]
+    for seed in SHIPPED_SEEDS[name]:
+        K, _, _, bounds = planted_stream(w, seed, context=ctx, with_q=False)
+        Kn = K.to(torch.float64).numpy()
+        heads = range(w.n_kv_heads) if name == "cfg1" else range(2)
+        n_ok = n_tot = 0
+        for c0 in range(0, ctx, w.chunk):
+            for h in heads:
+                b = O.segment_chunk(Kn[h, c0:c0 + w.chunk], None, O.MAP_LOGIT,
+                                    theta_default(w.head_dim), 0.0)
+                want = sorted({0, w.chunk} | {int(x - c0) for x in bounds[h] if c0 < x < c0 + w.chunk})
+                n_tot += 1
+                n_ok += list(b) == want
+                # whatever is found must at least be a tiling of the chunk
+                assert b[0] == 0 and b[-1] == w.chunk and np.all(np.diff(b) > 0)
+        # two adjacent planted spans with similar means may merge; that is a property of the
+        # random input.  The recovery rate over chunks stays high.
+        assert n_ok >= 0.9 * n_tot, (name, seed, n_ok, n_tot)
+
+
+# ---------------------------------------------------------------- P4: NMS
+def _suppresses(a, b, phi):
+    inter = min(a[2], b[2]) - max(a[1], b[1]) + 1
+    if inter <= 0:
+        return False
+    union = (a[2] - a[1] + 1) + (b[2] - b[1] + 1) - inter
+    return np.float32(inter) > np.float32(phi) * np.float32(union)
+
+
+@pytest.mark.parametrize("phi", [0.0, 0.1, 0.5, 0.9])
+def test_nms_characterisation(phi):
+    """Greedy NMS is the unique set in which (i) no kept interval is suppressed by a
+    better kept one and (ii) every dropped interval is suppressed by a better kept one."""
+    for seed in range(30):
+        rng = np.random.default_rng(seed)
+        n = int(rng.integers(1, 17))
+        cands = []
+        seen = set()
+        while len(cands) < n:
+            x = int(rng.integers(0, 30)); y = int(rng.integers(x, 30))
+            if (x, y) in seen:
+                continue
+            seen.add((x, y))
+            cands.append((float(rng.integers(1, 6)), x, y))     # many score ties on purpose
+        kept = O.nms_1d(cands, phi)
+        key = lambda c: (-c[0], c[1], c[2])
+        kept_set = set(kept)
+        assert len(kept_set) == len(kept)
+        for c in cands:
+            better_kept = [k for k in kept if key(k) < key(c)]
+            sup = any(_suppresses(k, c, phi) for k in better_kept)
+            assert (c in kept_set) == (not sup)
+        # invariance to the order the candidates are given in
+        perm = [cands[i] for i in rng.permutation(n)]
+        assert O.nms_1d(perm, phi) == kept
+
+
+def test_nms_special_cases():
+    rng = np.random.default_rng(1)
+    cands = [(float(rng.uniform(0.1, 5)), 3 * i, 3 * i + int(rng.integers(0, 9))) for i in range(12)]
+    # phi >= 1: intersection can never exceed the union -> everything is kept, best first
+    kept = O.nms_1d(cands, 1.0)
+    assert kept == sorted(cands, key=lambda c: (-c[0], c[1], c[2]))
+    # phi = 0: any overlap suppresses -> kept intervals are pairwise disjoint, and the best one is kept
+    kept0 = O.nms_1d(cands, 0.0)
+    iv = sorted((x, y) for _, x, y in kept0)
+    assert all(iv[i][1] < iv[i + 1][0] for i in range(len(iv) - 1))
+    assert max(cands) [0] == kept0[0][0]
+    assert len(O.nms_1d(cands, 1.0, max_keep=5)) == 5
+    assert O.nms_1d([], 0.3) == []
+    assert list(O.partition_from_kept([(1.0, 2, 4), (0.5, 4, 6)], 10)) == [0, 2, 4, 5, 7, 10]
+
+
+# ---------------------------------------------------------------- P5: representatives, Eq. 8, selection
+def test_eq8_double_sum_is_dot_of_sums_and_means_are_loops():
+    rng = np.random.default_rng(2)
+    d = 5
+    Qv = rng.standard_normal((3, d))     # N index vectors of a query span
+    Kv = rng.standard_normal((4, d))     # M index vectors of a stored span
+    double = sum(float(Qv[n] @ Kv[m]) for m in range(4) for n in range(3))
+    assert abs(double - float(Qv.sum(0) @ Kv.sum(0))) < 1e-12
+    X = rng.standard_normal((10, d))
+    b = np.array([0, 3, 4, 10])
+    got = O.span_means(X, b, "f64")
+    for s in range(3):
+        for c in range(d):
+            want = sum(X[t, c] for t in range(b[s], b[s + 1])) / (b[s + 1] - b[s])
+            assert abs(got[s, c] - want) < 1e-14
+    # scores: max over query spans of the dot product
+    Qrep = rng.standard_normal((3, d)); Krep = rng.standard_normal((6, d))
+    sc = O.span_scores(Qrep, Krep)
+    for i in range(6):
+        assert abs(sc[i] - max(float(Qrep[j] @ Krep[i]) for j in range(3))) < 1e-14
+
+
+def test_select_spans_against_sort_and_limits():
+    rng = np.random.default_rng(4)
+    for trial in range(50):
+        n = int(rng.integers(1, 40))
+        scores = rng.integers(0, 6, n).astype(np.float64)      # ties on purpose
+        clip = rng.integers(1, 50, n)
+        elig = rng.uniform(size=n) < 0.8
+        k_max = int(rng.integers(0, 8)); budget = int(rng.integers(0, 200))
+        got = O.select_spans(scores, clip, elig, k_max, budget)
+        order = [i for i in np.lexsort((np.arange(n), -scores)) if elig[i]]   # library sort: (-score, id)
+        best_m = 0
+        for m in range(len(order) + 1):
+            if k_max and m > k_max:
+                break
+            if budget and clip[order[:m]].sum() > budget:
+                break
+            best_m = m
+        assert list(got) == sorted(order[:best_m])
+    # no limits -> every eligible span, ascending
+    got = O.select_spans(scores, clip, elig, 0, 0)
+    assert list(got) == list(np.nonzero(elig)[0])
+
+
+def test_planted_needle_is_ranked_first():
+    """A query chunk whose mean equals a stored span's mean ranks that span first."""
+    w = CONFIGS["cfg1"]
+    K, V, Q, bounds = planted_stream(w, 7, context=2048)
+    Kn, Vn, Qn = (t.to(torch.float64).numpy() for t in (K, V, Q))
+    cfg = O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, "f32", w.n_sink, 256, k_max=1,
+                         theta=theta_default(w.head_dim))
+    st = O.OracleStream(cfg, Kn, Vn)
+    for c0 in range(0, 2048, 256):
+        st.append_chunk(256)
+    target = 5                                      # some stored span well before the window
+    mu = np.stack(st.krep[0])[target]
+    q = np.repeat((mu / w.group)[None, None, :], 256, axis=0).repeat(w.n_q_heads, axis=1)
+    sel = st.retrieve(q)
+    assert list(sel[0]) == [target]
+
+
+# ---------------------------------------------------------------- P6: everything selected == full causal attention
+@pytest.mark.parametrize("window,n_sink,chunk", [(0, 0, 16), (0, 4, 16), (8, 4, 16), (40, 4, 16),
+                                                 (1000, 4, 16), (16, 3, 7), (5, 4, 1)])
+def test_select_all_equals_full_causal_attention(window, n_sink, chunk):
+    rng = np.random.default_rng(window + 7 * n_sink + chunk)
+    Hq, Hkv, d, T = 4, 2, 8, 61
+    K = rng.standard_normal((Hkv, T, d)); V = rng.standard_normal((Hkv, T, d))
+    Q = rng.standard_normal((T, Hq, d))
+    cfg = O.OracleConfig(Hq, Hkv, d, "f64", n_sink, window, seg_map=O.MAP_LOGIT, theta=0.3, phi=0.0)
+    st = O.OracleStream(cfg, K, V)
+    c0 = 0
+    while c0 < T:
+        n = min(chunk, T - c0)
+        st.append_chunk(n)                      # spans straddle the sink and window edges freely
+        q = Q[c0:c0 + n]
+        sel = st.retrieve(q)                    # no k_max, no budget -> all eligible spans
+        Oo, _ = st.attend(q)
+        for g in range(Hq):
+            want = O.full_causal_attention(Q[:, g], K[g // 2], V[g // 2], range(c0, c0 + n))
+            np.testing.assert_allclose(Oo[:, g], want, rtol=0, atol=1e-12)
+        # the context set is exactly [0, c0), each token once
+        for h in range(Hkv):
+            assert list(st.context_tokens(h)) == list(range(c0))
+        c0 += n
+
+
+# ---------------------------------------------------------------- P7: brute-force attention, special cases
+def test_attend_rows_against_python_loops():
+    rng = np.random.default_rng(9)
+    T, d, L, c0 = 23, 4, 5, 18
+    K = rng.standard_normal((T, d)); V = rng.standard_normal((T, d)); Q = rng.standard_normal((L, d))
+    ctx = np.array([0, 1, 5, 6, 7, 12, 17])
+    Oo, lse = O.attend_rows(Q, K, V, ctx, c0)
+    for i in range(L):
+        keys = list(ctx) + list(range(c0, c0 + i + 1))
+        z = [sum(Q[i, c] * K[t, c] for c in range(d)) / math.sqrt(d) for t in keys]
+        m = max(z)
+        p = [math.exp(v - m) for v in z]
+        den = sum(p)
+        for c in range(d):
+            assert abs(Oo[i, c] - sum(p[k] * V[t, c] for k, t in enumerate(keys)) / den) < 1e-13
+        assert abs(lse[i] - (m + math.log(den))) < 1e-13
+
+
+def test_attention_special_cases():
+    rng = np.random.default_rng(10)
+    d = 6
+    K = rng.standard_normal((9, d)); V = rng.standard_normal((9, d))
+    # a single key -> the output is that key's value
+    Oo, _ = O.attend_rows(rng.standard_normal((1, d)), K, V, np.array([], dtype=np.int64), 4)
+    np.testing.assert_allclose(Oo[0], V[4], atol=1e-14)
+    # zero query -> uniform weights -> mean of the values
+    Oo, lse = O.attend_rows(np.zeros((1, d)), K, V, np.array([0, 2, 3]), 8)
+    np.testing.assert_allclose(Oo[0], V[[0, 2, 3, 8]].mean(0), atol=1e-14)
+    assert abs(lse[0] - math.log(4)) < 1e-14
+
+
+# ---------------------------------------------------------------- P8: sparse vs full differ by the LSE-merge identity
+def test_sparse_and_rest_merge_to_full():
+    rng = np.random.default_rng(11)
+    T, d = 200, 8
+    K = rng.standard_normal((T, d)); V = rng.standard_normal((T, d)); Q = rng.standard_normal((1, d))
+    c0 = T - 1
+    sel = np.sort(rng.choice(c0, 60, replace=False))
+    rest = np.setdiff1d(np.arange(c0), sel)
+    o1, l1 = O.attend_rows(Q, K, V, sel, c0)
+    # the rest alone: attend over the rest plus the current token, then remove the current token's
+    # weight through the identity  O_full = (Z1 O1 + Z2 O2) / (Z1 + Z2)
+    z_rest = (K[rest] @ Q[0]) / math.sqrt(d)
+    Z2 = np.exp(z_rest).sum(); O2 = (np.exp(z_rest) @ V[rest]) / Z2
+    Z1 = math.exp(l1[0])
+    merged = (Z1 * o1[0] + Z2 * O2) / (Z1 + Z2)
+    full = O.full_causal_attention(np.repeat(Q, T, 0), K, V, [c0])[0]
+    np.testing.assert_allclose(merged, full, atol=1e-13)
+    assert np.abs(o1[0] - full).max() > 1e-3          # and sparse alone is not full
+
+
+# ---------------------------------------------------------------- P9: decode
+def test_decode_is_a_chunk_of_one():
+    w = CONFIGS["cfg1"]
+    K, V, Q, _ = planted_stream(w, 3, context=1025)
+    Kn, Vn, Qn = (t.to(torch.float64).numpy() for t in (K, V, Q))
+    cfg = O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, "f32", 4, 128, k_max=3,
+                         theta=theta_default(w.head_dim))
+    st = O.OracleStream(cfg, Kn, Vn)
+    for c0 in range(0, 1024, 256):
+        st.append_chunk(256)
+    st.append_chunk(1)
+    q = Qn[1024:1025]
+    sel = st.retrieve(q)
+    assert len(sel[0]) == 3 and st.lens[0][-1] == 1
+    Oo, _ = st.attend(q)
+    # same thing written out: sink + clipped selected spans + window + itself
+    keys = list(range(4))
+    for i in sel[0]:
+        a = max(st.starts[0][i], 4); b = min(st.starts[0][i] + st.lens[0][i], 1024 - 128)
+        keys += list(range(a, b))
+    keys += list(range(1024 - 128, 1025))
+    assert len(set(keys)) == len(keys)
+    for g in range(4):
+        z = (Kn[0][keys] @ q[0, g]) / math.sqrt(w.head_dim)
+        p = np.exp(z - z.max()); p /= p.sum()
+        np.testing.assert_allclose(Oo[0, g], p @ Vn[0][keys], atol=1e-12)
+
+
+def test_stability_audit_flags_a_planted_near_tie():
+    """The audit must reject a chunk whose decision hangs on a near-tie."""
+    L = 8
+    K = np.zeros((L, 2)); K[:, 0] = 1.0
+    # constant map -> every anti-diagonal is tied up to the threshold term; theta chosen so S hovers at 0
+    assert O.segmentation_is_stable(K * 3.0, None, O.MAP_LOGIT, 0.1, 0.0)
+    theta = float((K @ K.T / math.sqrt(2))[0, 0])          # S == 0 exactly everywhere: unstable under noise
+    assert not O.segmentation_is_stable(K, None, O.MAP_LOGIT, theta * (1 - 1e-9), 0.0)
