@@ -1,0 +1,187 @@
+/*
+ * ltri.h — C ABI of libltri: the per-chunk streaming sparse-attention step of
+ * Ltri-LLM on one AMD MI355X (gfx950).
+ *
+ * The three verbs follow the paper's three steps (Sec. 3.4 "Overall Framework"):
+ *   step 1  ltri_append_chunk   segment the new tokens into spans at the borders of the
+ *                               triangular regions of their attention map (Sec. 3.2,
+ *                               Eq. 1-5, NMS; appendix "NMS Input Filtration") and store
+ *                               one representative key per span (Sec. 3.3.1);
+ *   step 2  ltri_retrieve       score the stored spans against the query chunk's span
+ *                               representatives (Eq. 8) and pick the top spans (Eq. 9);
+ *   step 3  ltri_attend         exact attention of the query chunk over
+ *                               initial | retrieved | window | current tokens.
+ *
+ * Conventions
+ *   - Every function returns an int32 status: 0 = LTRI_OK, negative = error. Nothing
+ *     throws. ltri_strerror() names a status, ltri_last_error() gives the detail text
+ *     of the last failing call on a context.
+ *   - "device" pointers are HIP device addresses of the current device, "host" pointers
+ *     are ordinary process memory. The library never allocates or frees device memory:
+ *     the caller sizes buffers with ltri_workspace_bytes(), allocates them (with any
+ *     allocator) and keeps them alive until ltri_destroy(). The library owns only the
+ *     host-side ltri_ctx.
+ *   - All device work is enqueued on the stream given at creation and the call returns
+ *     without waiting, except the introspection calls marked "synchronises".
+ *   - Tensors are dense, row-major, in the configured dtype (fp32 or bf16):
+ *       KV arenas  [n_layers][n_seqs][n_kv_heads][max_tokens][head_dim]
+ *       queries    [seq_count][n_q][n_q_heads][head_dim]
+ *       outputs    [seq_count][n_q][n_q_heads][head_dim]
+ *     Query head g belongs to KV head g / (n_q_heads / n_kv_heads).
+ *   - Calls on one context must not overlap (one stream, one scratch buffer).
+ */
+#ifndef LTRI_H
+#define LTRI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* status codes */
+#define LTRI_OK          0
+#define LTRI_EINVAL     -1   /* bad argument / unsupported configuration            */
+#define LTRI_ESTATE     -2   /* calls out of order (e.g. retrieve before append)     */
+#define LTRI_ECAPACITY  -3   /* token or span capacity exceeded                       */
+#define LTRI_EHIP       -4   /* a HIP runtime call failed                             */
+
+/* dtypes */
+#define LTRI_F32   0
+#define LTRI_BF16  1
+
+/* kinds of segmentation map */
+#define LTRI_MAP_SOFTMAX 0   /* Eq. 1-3: causal softmax over the chunk's own keys      */
+#define LTRI_MAP_LOGIT   1   /* masked scaled scores q.k/sqrt(d), no softmax           */
+
+/* representative vector of a span */
+#define LTRI_REP_MEAN    0   /* mean of the span's rows (Sec. 3.3.1, mean pooling)     */
+
+#define LTRI_MAX_BATCH   64  /* most sequences one call can take                        */
+
+typedef struct ltri_ctx ltri_ctx;
+
+typedef struct {
+  int32_t n_q_heads, n_kv_heads, head_dim;  /* head_dim 64 or 128 (bf16: 128 only)       */
+  int32_t dtype;                            /* LTRI_F32 | LTRI_BF16                       */
+  int32_t n_layers, n_seqs;
+  int64_t max_tokens;                       /* capacity per sequence                      */
+  int32_t chunk_max;                        /* most tokens one append may bring, <= 2048  */
+  int32_t n_sink, window;                   /* initial tokens, local window               */
+  int32_t k_max;                            /* cap on retrieved spans, 0 = none           */
+  int64_t budget_tokens;                    /* cap on retrieved tokens, 0 = none          */
+  int32_t seg_map;                          /* LTRI_MAP_*                                 */
+  float   theta, phi;                       /* Eq. 5 threshold (absolute, per head and
+                                               cell); NMS IoU threshold                   */
+  int32_t max_spans_per_chunk;              /* cap on NMS keeps per chunk, 0 = none       */
+  int32_t rep_mode;                         /* LTRI_REP_MEAN                              */
+  int32_t max_spans;                        /* span capacity per (layer, seq, KV head);
+                                               0 = max_tokens / 32 + 64                   */
+} ltri_config;
+
+/* Sizes (bytes) of the two device buffers a context needs: `state` holds the index
+ * memory (span table, representative keys, selections, token lists; lives as long as
+ * the context; ltri_create enqueues a kernel that zero-fills it), `scratch` holds per-call
+ * temporaries. EINVAL on an unsupported configuration. */
+int32_t ltri_workspace_bytes(const ltri_config* cfg, size_t* state_bytes, size_t* scratch_bytes);
+
+/* Creates a context. k_arena / v_arena / state / scratch are device pointers owned by the
+ * caller (256-byte aligned), hip_stream is a hipStream_t (NULL = default stream). The call
+ * enqueues a kernel that clears `state`. */
+int32_t ltri_create(const ltri_config* cfg, void* k_arena, void* v_arena, void* state, void* scratch,
+                    void* hip_stream, ltri_ctx** out);
+int32_t ltri_destroy(ltri_ctx* ctx);
+/* Forget all layers of one sequence (span table, selections, token count). */
+int32_t ltri_reset(ltri_ctx* ctx, int32_t seq);
+/* A context without device buffers: every call validates its arguments and advances the
+ * host-side state exactly as a real context would, but enqueues nothing; introspection calls
+ * return ESTATE. Used to test the host logic on a machine without a GPU. */
+int32_t ltri_create_dry(const ltri_config* cfg, ltri_ctx** out);
+
+/* Step 1 (Sec. 3.4 first step; Sec. 3.2; Sec. 3.3.1). For each sequence s in
+ * [seq_begin, seq_begin + seq_count): tokens [T_s, T_s + n_new) of `layer` are appended.
+ *   k_chunk, v_chunk  device [seq_count][n_kv_heads][n_new][head_dim], copied into the
+ *                     arenas first; both NULL = the caller already wrote them in place.
+ *   q_seg             device [seq_count][n_new][n_q_heads][head_dim]: queries whose map is
+ *                     segmented (Eq. 1), summed over each KV head's group (Eq. 4); NULL =
+ *                     the keys are used as queries (one head per KV head).
+ * The chunk's causal map is scored (Eq. 4-5), the best span on every anti-diagonal is kept
+ * if its score is > 0 (ties: shorter span), greedy NMS on 1-D token intervals with IoU
+ * threshold phi removes overlaps (ties: smaller start, then smaller end), the kept
+ * intervals' end points cut the chunk into consecutive spans, and every span's mean key is
+ * stored, rounded once to the dtype.
+ * ECAPACITY if T_s + n_new > max_tokens; EINVAL if n_new < 1 or > chunk_max. Overflow of
+ * the span table is detected on the device and reported by ltri_sync_status(). */
+int32_t ltri_append_chunk(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count,
+                          const void* k_chunk, const void* v_chunk, const void* q_seg, int32_t n_new);
+
+/* Same for one sequence, with the span boundaries supplied by the caller instead of
+ * segmenting: bounds_host holds, for each KV head h, n_bounds_host[h] strictly increasing
+ * chunk-local offsets, the first 0 and the last n_new, heads back to back. */
+int32_t ltri_append_chunk_with_spans(ltri_ctx* ctx, int32_t layer, int32_t seq,
+                                     const void* k_chunk, const void* v_chunk, int32_t n_new,
+                                     const int32_t* bounds_host, const int32_t* n_bounds_host);
+
+/* Step 2 (Sec. 3.4 second step, Eq. 8-9). q: device [seq_count][n_q][n_q_heads][head_dim],
+ * the queries of the chunk appended last (n_q must equal its length, else ESTATE).
+ * Per KV head: query-span representatives = mean over each of the chunk's spans of the
+ * group-summed queries; score of a stored span = max over query spans of the dot product
+ * with its representative key; spans that reach into the evicted region
+ * [n_sink, chunk_start - window) are eligible and count with their part inside it; they
+ * are ordered by (-score, id) and the longest prefix with at most k_max spans and at most
+ * budget_tokens tokens is selected. The ascending ids are kept in the context and, if
+ * sel_ids / sel_cnt are not NULL, also written to device [seq_count][n_kv_heads][sel_cap]
+ * and [seq_count][n_kv_heads] (sel_cap from ltri_sel_capacity()). */
+int32_t ltri_retrieve(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count,
+                      const void* q, int32_t n_q, int32_t* sel_ids, int32_t* sel_cnt);
+int32_t ltri_sel_capacity(const ltri_ctx* ctx);
+
+/* Replace the selection of one KV head by ids_host[0..n) (stored span ids, any order,
+ * ineligible ones contribute no tokens). Test seam and "mandatory injection". */
+int32_t ltri_force_selection(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,
+                             const int32_t* ids_host, int32_t n);
+
+/* Step 3 (Sec. 3.4 third step). out: device [seq_count][n_q][n_q_heads][head_dim] in the
+ * dtype; lse: device fp32 [seq_count][n_q][n_q_heads] (natural-log sum of exponentials of
+ * the scaled scores) or NULL. Query row i of the chunk attends the initial tokens, the
+ * selected spans' evicted parts, the window and the chunk's tokens 0..i, with weights
+ * softmax(q.k / sqrt(head_dim)). ESTATE unless ltri_retrieve (or ltri_force_selection for
+ * every head) ran for this chunk. */
+int32_t ltri_attend(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count,
+                    const void* q, int32_t n_q, void* out, float* lse);
+
+/* The gather on its own: copies the K and V rows of the attended context set
+ * (initial | retrieved | window, in that order) of every KV head of one sequence into
+ * k_packed / v_packed, device [n_kv_heads][list_cap][head_dim] (list_cap from
+ * ltri_list_capacity()); n_tokens: device int32 [n_kv_heads] or NULL. */
+int32_t ltri_gather_pack(ltri_ctx* ctx, int32_t layer, int32_t seq, void* k_packed, void* v_packed,
+                         int32_t* n_tokens);
+int32_t ltri_list_capacity(const ltri_ctx* ctx);
+
+/* Introspection; these synchronise the stream. */
+int32_t ltri_sync_status(ltri_ctx* ctx);   /* LTRI_OK or the first error raised on the device */
+int32_t ltri_token_count(ltri_ctx* ctx, int32_t layer, int32_t seq, int64_t* n);
+int32_t ltri_span_count(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head, int32_t* n);
+int32_t ltri_get_spans(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,
+                       int32_t* starts_host, int32_t* lens_host, int32_t cap);
+/* reps_host: [cap][head_dim] in the dtype. */
+int32_t ltri_get_rep_keys(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,
+                          void* reps_host, int32_t cap);
+/* Selection of the last retrieve: ids_host[cap], *n = count; scores_host (may be NULL):
+ * fp64 score of every stored span, [span count]. */
+int32_t ltri_get_selection(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,
+                           int32_t* ids_host, int32_t cap, int32_t* n, double* scores_host);
+/* Context token list of the last retrieve: tokens_host[cap], *n = length. */
+int32_t ltri_get_token_list(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,
+                            int32_t* tokens_host, int32_t cap, int32_t* n);
+
+const char* ltri_strerror(int32_t status);
+const char* ltri_last_error(const ltri_ctx* ctx);
+/* "libltri <version> gfx950" */
+const char* ltri_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LTRI_H */

@@ -379,11 +379,7 @@ class OracleStream:
             lens = np.asarray(self.lens[h], np.int64)
             a, b = clipped_ranges(starts, lens, min(c.n_sink, c0), ws)
             eligible = a < b
-            if eligible.any():
-                Krep = np.stack(self.krep[h])
-                scores = span_scores(Qrep, Krep)
-            else:
-                scores = np.zeros(len(starts))
+            scores = span_scores(Qrep, np.stack(self.krep[h]))
             sel = select_spans(scores, b - a, eligible, c.k_max, c.budget_tokens)
             self.sel[h] = sel
             self.sel_scores[h] = scores

@@ -1,0 +1,267 @@
+"""ctypes binding of libltri.so.
+
+The functions carry the names of the C ABI (include/ltri.h).  torch is used only to
+allocate device memory and to name the stream; nothing here computes.  If the shared
+library is missing the import of any entry point fails loudly: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB: Optional[C.CDLL] = None
+
+LTRI_F32, LTRI_BF16 = 0, 1
+MAP_SOFTMAX, MAP_LOGIT = 0, 1
+
+EXPORTED_SYMBOLS = [
+    "ltri_workspace_bytes", "ltri_create", "ltri_create_dry", "ltri_destroy", "ltri_reset",
+    "ltri_append_chunk", "ltri_append_chunk_with_spans", "ltri_retrieve", "ltri_sel_capacity",
+    "ltri_force_selection", "ltri_attend", "ltri_gather_pack", "ltri_list_capacity",
+    "ltri_sync_status", "ltri_token_count", "ltri_span_count", "ltri_get_spans",
+    "ltri_get_rep_keys", "ltri_get_selection", "ltri_get_token_list", "ltri_strerror",
+    "ltri_last_error", "ltri_version",
+]
+
+
+class LtriError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"libltri status {status}: {text}")
+        self.status = status
+
+
+class LtriConfig(C.Structure):
+    _fields_ = [
+        ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("dtype", C.c_int32), ("n_layers", C.c_int32), ("n_seqs", C.c_int32),
+        ("max_tokens", C.c_int64), ("chunk_max", C.c_int32), ("n_sink", C.c_int32),
+        ("window", C.c_int32), ("k_max", C.c_int32), ("budget_tokens", C.c_int64),
+        ("seg_map", C.c_int32), ("theta", C.c_float), ("phi", C.c_float),
+        ("max_spans_per_chunk", C.c_int32), ("rep_mode", C.c_int32), ("max_spans", C.c_int32),
+    ]
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libltri.so")
+
+
+def load_library() -> C.CDLL:
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python __graft_entry__.py` "
+                          "(there is no fallback implementation)")
+    lib = C.CDLL(path)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    pi32 = C.POINTER(C.c_int32)
+    sig = {
+        "ltri_workspace_bytes": [C.POINTER(LtriConfig), C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)],
+        "ltri_create": [C.POINTER(LtriConfig), vp, vp, vp, vp, vp, C.POINTER(vp)],
+        "ltri_create_dry": [C.POINTER(LtriConfig), C.POINTER(vp)],
+        "ltri_destroy": [vp],
+        "ltri_reset": [vp, i32],
+        "ltri_append_chunk": [vp, i32, i32, i32, vp, vp, vp, i32],
+        "ltri_append_chunk_with_spans": [vp, i32, i32, vp, vp, i32, pi32, pi32],
+        "ltri_retrieve": [vp, i32, i32, i32, vp, i32, vp, vp],
+        "ltri_sel_capacity": [vp],
+        "ltri_force_selection": [vp, i32, i32, i32, pi32, i32],
+        "ltri_attend": [vp, i32, i32, i32, vp, i32, vp, vp],
+        "ltri_gather_pack": [vp, i32, i32, vp, vp, vp],
+        "ltri_list_capacity": [vp],
+        "ltri_sync_status": [vp],
+        "ltri_token_count": [vp, i32, i32, C.POINTER(i64)],
+        "ltri_span_count": [vp, i32, i32, i32, pi32],
+        "ltri_get_spans": [vp, i32, i32, i32, pi32, pi32, i32],
+        "ltri_get_rep_keys": [vp, i32, i32, i32, vp, i32],
+        "ltri_get_selection": [vp, i32, i32, i32, pi32, i32, pi32, C.POINTER(C.c_double)],
+        "ltri_get_token_list": [vp, i32, i32, i32, pi32, i32, pi32],
+    }
+    for name, args in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = C.c_int32
+    lib.ltri_strerror.argtypes = [i32]
+    lib.ltri_strerror.restype = C.c_char_p
+    lib.ltri_last_error.argtypes = [vp]
+    lib.ltri_last_error.restype = C.c_char_p
+    lib.ltri_version.argtypes = []
+    lib.ltri_version.restype = C.c_char_p
+    _LIB = lib
+    return lib
+
+
+def config_from_workload(w, max_tokens: Optional[int] = None, theta: float = 0.0, phi: float = 0.0,
+                         seg_map: int = MAP_LOGIT, n_layers: Optional[int] = None,
+                         n_seqs: Optional[int] = None, max_spans: int = 0,
+                         max_spans_per_chunk: int = 0, window: Optional[int] = None,
+                         n_sink: Optional[int] = None, k_max: Optional[int] = None,
+                         budget_tokens: Optional[int] = None, chunk_max: Optional[int] = None) -> LtriConfig:
+    return LtriConfig(
+        n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
+        dtype=LTRI_F32 if w.dtype == "f32" else LTRI_BF16,
+        n_layers=w.n_layers if n_layers is None else n_layers,
+        n_seqs=w.n_seqs if n_seqs is None else n_seqs,
+        max_tokens=w.context if max_tokens is None else max_tokens,
+        chunk_max=w.chunk if chunk_max is None else chunk_max,
+        n_sink=w.n_sink if n_sink is None else n_sink,
+        window=w.window if window is None else window,
+        k_max=w.k_max if k_max is None else k_max,
+        budget_tokens=w.budget_tokens if budget_tokens is None else budget_tokens,
+        seg_map=seg_map, theta=theta, phi=phi, max_spans_per_chunk=max_spans_per_chunk,
+        rep_mode=0, max_spans=max_spans)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+class LtriContext:
+    """Owns the device buffers (torch tensors) and the ltri_ctx handle."""
+
+    def __init__(self, cfg: LtriConfig, device: Optional[torch.device], dry: bool = False,
+                 stream: Optional[torch.cuda.Stream] = None):
+        self.lib = load_library()
+        self.cfg = cfg
+        self.dry = dry
+        self.handle = C.c_void_p()
+        self.tdtype = torch.float32 if cfg.dtype == LTRI_F32 else torch.bfloat16
+        sb, cb = C.c_size_t(), C.c_size_t()
+        self._check(self.lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)), None)
+        self.state_bytes, self.scratch_bytes = sb.value, cb.value
+        if dry:
+            self._check(self.lib.ltri_create_dry(C.byref(cfg), C.byref(self.handle)), None)
+            return
+        self.device = device
+        n_arena = cfg.n_layers * cfg.n_seqs * cfg.n_kv_heads * cfg.max_tokens * cfg.head_dim
+        self.k_arena = torch.empty(n_arena, dtype=self.tdtype, device=device)
+        self.v_arena = torch.empty(n_arena, dtype=self.tdtype, device=device)
+        self.state = torch.empty(self.state_bytes, dtype=torch.uint8, device=device)
+        self.scratch = torch.empty(self.scratch_bytes, dtype=torch.uint8, device=device)
+        self.stream = stream if stream is not None else torch.cuda.current_stream(device)
+        self._check(self.lib.ltri_create(C.byref(cfg), self.k_arena.data_ptr(), self.v_arena.data_ptr(),
+                                         self.state.data_ptr(), self.scratch.data_ptr(),
+                                         self.stream.cuda_stream, C.byref(self.handle)), None)
+        self.sel_cap = self.lib.ltri_sel_capacity(self.handle)
+        self.list_cap = self.lib.ltri_list_capacity(self.handle)
+
+    def _check(self, status: int, _unused) -> None:
+        if status != 0:
+            detail = ""
+            if self.handle:
+                detail = self.lib.ltri_last_error(self.handle).decode()
+            raise LtriError(status, f"{self.lib.ltri_strerror(status).decode()}: {detail}")
+
+    def close(self) -> None:
+        if self.handle:
+            self.lib.ltri_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # arenas viewed as [n_layers][n_seqs][n_kv_heads][max_tokens][head_dim]
+    def arena_views(self) -> Tuple[torch.Tensor, torch.Tensor]:
+        c = self.cfg
+        shape = (c.n_layers, c.n_seqs, c.n_kv_heads, c.max_tokens, c.head_dim)
+        return self.k_arena.view(shape), self.v_arena.view(shape)
+
+    # ---- the C ABI, same names ----
+    def reset(self, seq: int) -> None:
+        self._check(self.lib.ltri_reset(self.handle, seq), None)
+
+    def append_chunk(self, layer: int, seq_begin: int, seq_count: int, n_new: int,
+                     k_chunk: Optional[torch.Tensor] = None, v_chunk: Optional[torch.Tensor] = None,
+                     q_seg: Optional[torch.Tensor] = None) -> None:
+        self._check(self.lib.ltri_append_chunk(self.handle, layer, seq_begin, seq_count, _ptr(k_chunk),
+                                               _ptr(v_chunk), _ptr(q_seg), n_new), None)
+
+    def append_chunk_with_spans(self, layer: int, seq: int, n_new: int, bounds: List[np.ndarray],
+                                k_chunk: Optional[torch.Tensor] = None,
+                                v_chunk: Optional[torch.Tensor] = None) -> None:
+        flat = np.concatenate([np.asarray(b, np.int32) for b in bounds]).astype(np.int32)
+        nb = np.asarray([len(b) for b in bounds], np.int32)
+        self._check(self.lib.ltri_append_chunk_with_spans(
+            self.handle, layer, seq, _ptr(k_chunk), _ptr(v_chunk), n_new,
+            flat.ctypes.data_as(C.POINTER(C.c_int32)), nb.ctypes.data_as(C.POINTER(C.c_int32))), None)
+
+    def retrieve(self, layer: int, seq_begin: int, seq_count: int, q: torch.Tensor,
+                 sel_ids: Optional[torch.Tensor] = None, sel_cnt: Optional[torch.Tensor] = None) -> None:
+        n_q = q.shape[-3]
+        self._check(self.lib.ltri_retrieve(self.handle, layer, seq_begin, seq_count, q.data_ptr(), n_q,
+                                           _ptr(sel_ids), _ptr(sel_cnt)), None)
+
+    def force_selection(self, layer: int, seq: int, kv_head: int, ids) -> None:
+        arr = np.asarray(list(ids), np.int32)
+        self._check(self.lib.ltri_force_selection(self.handle, layer, seq, kv_head,
+                                                  arr.ctypes.data_as(C.POINTER(C.c_int32)), len(arr)), None)
+
+    def attend(self, layer: int, seq_begin: int, seq_count: int, q: torch.Tensor,
+               out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None) -> torch.Tensor:
+        n_q = q.shape[-3]
+        if out is None and not self.dry:
+            out = torch.empty((seq_count, n_q, self.cfg.n_q_heads, self.cfg.head_dim), dtype=self.tdtype,
+                              device=q.device)
+        self._check(self.lib.ltri_attend(self.handle, layer, seq_begin, seq_count, q.data_ptr(), n_q,
+                                         _ptr(out) if out is not None else 1, _ptr(lse)), None)
+        return out
+
+    def gather_pack(self, layer: int, seq: int, k_packed: torch.Tensor, v_packed: torch.Tensor,
+                    n_tokens: Optional[torch.Tensor] = None) -> None:
+        self._check(self.lib.ltri_gather_pack(self.handle, layer, seq, k_packed.data_ptr(),
+                                              v_packed.data_ptr(), _ptr(n_tokens)), None)
+
+    def sync_status(self) -> int:
+        return int(self.lib.ltri_sync_status(self.handle))
+
+    def token_count(self, layer: int, seq: int) -> int:
+        n = C.c_int64()
+        self._check(self.lib.ltri_token_count(self.handle, layer, seq, C.byref(n)), None)
+        return n.value
+
+    def span_count(self, layer: int, seq: int, kv_head: int) -> int:
+        n = C.c_int32()
+        self._check(self.lib.ltri_span_count(self.handle, layer, seq, kv_head, C.byref(n)), None)
+        return n.value
+
+    def get_spans(self, layer: int, seq: int, kv_head: int) -> Tuple[np.ndarray, np.ndarray]:
+        n = self.span_count(layer, seq, kv_head)
+        s = np.zeros(max(n, 1), np.int32)
+        l = np.zeros(max(n, 1), np.int32)
+        self._check(self.lib.ltri_get_spans(self.handle, layer, seq, kv_head,
+                                            s.ctypes.data_as(C.POINTER(C.c_int32)),
+                                            l.ctypes.data_as(C.POINTER(C.c_int32)), n), None)
+        return s[:n], l[:n]
+
+    def get_rep_keys(self, layer: int, seq: int, kv_head: int) -> torch.Tensor:
+        n = self.span_count(layer, seq, kv_head)
+        buf = torch.zeros((max(n, 1), self.cfg.head_dim), dtype=self.tdtype)
+        self._check(self.lib.ltri_get_rep_keys(self.handle, layer, seq, kv_head, buf.data_ptr(), n), None)
+        return buf[:n]
+
+    def get_selection(self, layer: int, seq: int, kv_head: int) -> Tuple[np.ndarray, np.ndarray]:
+        n_sp = self.span_count(layer, seq, kv_head)
+        ids = np.zeros(max(self.sel_cap, 1), np.int32)
+        scores = np.zeros(max(n_sp, 1), np.float64)
+        n = C.c_int32()
+        self._check(self.lib.ltri_get_selection(self.handle, layer, seq, kv_head,
+                                                ids.ctypes.data_as(C.POINTER(C.c_int32)), self.sel_cap,
+                                                C.byref(n), scores.ctypes.data_as(C.POINTER(C.c_double))), None)
+        return ids[:n.value], scores[:n_sp]
+
+    def get_token_list(self, layer: int, seq: int, kv_head: int) -> np.ndarray:
+        toks = np.zeros(max(self.list_cap, 1), np.int32)
+        n = C.c_int32()
+        self._check(self.lib.ltri_get_token_list(self.handle, layer, seq, kv_head,
+                                                 toks.ctypes.data_as(C.POINTER(C.c_int32)), self.list_cap,
+                                                 C.byref(n)), None)
+        return toks[:n.value]

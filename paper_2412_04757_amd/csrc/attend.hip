@@ -1,0 +1,389 @@
+// Step 3 on the device (Sec. 3.4 third step): exact attention of the query chunk over
+// initial | retrieved | window tokens (read through the context token list built by step 2)
+// and the chunk's own tokens (causal), plus the standalone gather of that context set.
+//
+// bf16 kernel: flash-style streaming over 64-key tiles on the matrix cores. A workgroup is four
+// wavefronts that share every K/V tile through LDS; the four are the query heads of one KV
+// head's group (GQA), each with QW query rows held in registers. Scores are computed
+// transposed (S^T = K Q^T) so that one lane owns one query: the softmax statistics need a
+// single cross-lane exchange and the probabilities are already laid out as the B operand of
+// O^T = V^T P^T. V is transposed on its way into LDS, with the keys permuted inside each block
+// of 32 to the order in which the score accumulators hold them.
+#include "device_common.h"
+
+namespace ltri {
+
+struct AttArgs {
+  Dims D; DevState st; const void* k_arena; const void* v_arena; const void* q;
+  void* out; float* lse; int layer; int seq_count; int n_q;
+  BatchPos bp;
+};
+
+constexpr int KS_STRIDE = 136;   // bf16 elements per K row in LDS (128 + 8 pad)
+constexpr int VT_STRIDE = 72;    // bf16 elements per V^T row in LDS (64 keys + 8 pad)
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// NQB = 32-query blocks per wavefront.
+template <int NQB>
+__global__ __launch_bounds__(256) void attend_bf16_kernel(AttArgs a) {
+  constexpr int QW = 32 * NQB;
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * KS_STRIDE];
+  __shared__ __attribute__((aligned(16))) uint16_t Vt[128 * VT_STRIDE];
+  const Dims& D = a.D;
+  const int HG = D.G < 4 ? D.G : 4;                 // heads of the group handled by this block
+  const int RS = 4 / HG;                            // row sub-tiles per block
+  const int RPB = QW * RS;                          // query rows per block
+  const int gpk = D.G / HG;                         // blocks per KV head along y
+  const int bi = blockIdx.z, h = blockIdx.y / gpk, gsub = blockIdx.y - h * gpk;
+  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
+  const int L = a.n_q, d = 128;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int head = h * D.G + gsub * HG + (wave % HG);
+  const int rb0 = blockIdx.x * RPB;                 // first row of the block
+  const int r0 = rb0 + (wave / HG) * QW;            // first row of this wave
+  const int slot = slot_of(D, a.layer, seq, h);
+  const uint16_t* Kb = reinterpret_cast<const uint16_t*>(a.k_arena) + arena_off(D, slot);
+  const uint16_t* Vb = reinterpret_cast<const uint16_t*>(a.v_arena) + arena_off(D, slot);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int list_len = meta[META_LIST_LEN];
+  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
+  const int n_ctx_tiles = (list_len + 63) / 64;
+  const int rb_end = min(L, rb0 + RPB);
+  const int n_chunk_tiles = (rb_end + 63) / 64;
+  const int n_tiles = n_ctx_tiles + n_chunk_tiles;
+
+  // query fragments: B operand of S^T = K Q^T; lane (l32, hf) holds Q[row l32][16 kk + 8 hf ..]
+  uint4 qf[NQB][8];
+  {
+    const uint16_t* Qb = reinterpret_cast<const uint16_t*>(a.q) + (size_t)bi * L * D.Hq * d;
+#pragma unroll
+    for (int nq = 0; nq < NQB; ++nq) {
+      const int row = min(r0 + nq * 32 + l32, L - 1);
+      const uint16_t* qrow = Qb + ((size_t)row * D.Hq + head) * d;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) qf[nq][kk] = *reinterpret_cast<const uint4*>(qrow + kk * 16 + hf * 8);
+    }
+  }
+  f32x16_t o[4][NQB];
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int nq = 0; nq < NQB; ++nq)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[mb][nq][v] = 0.f;
+  float m_run[NQB], l_run[NQB];
+#pragma unroll
+  for (int nq = 0; nq < NQB; ++nq) { m_run[nq] = -1e30f; l_run[nq] = 0.f; }
+  const float sc = 1.4426950408889634f / sqrtf((float)d);     // log2(e) / sqrt(d)
+
+  // loader roles
+  const int lrow = tid >> 4, lcc = tid & 15;                  // K: rows lrow + 16 rr; 16-byte chunk lcc
+  const int kg = tid >> 4;                                    // V: keys 4 kg .. 4 kg + 3
+  const int vkb = kg >> 3, va = (kg & 7) >> 1, vhf = kg & 1;
+  const int vpos = 4 * (8 * vkb + 4 * (va >> 1) + 2 * vhf + (va & 1));
+  uint4 kreg[4], vreg[4];
+
+  auto tile_token = [&](int t, int r) -> int {                 // token of key r of tile t, -1 = none
+    if (t < n_ctx_tiles) return list[t * 64 + r];
+    const int kp = (t - n_ctx_tiles) * 64 + r;
+    return kp < L ? c0 + kp : -1;
+  };
+  auto issue_loads = [&](int t) {
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      int tok = tile_token(t, lrow + 16 * rr);
+      tok = tok < 0 ? 0 : tok;
+      kreg[rr] = *reinterpret_cast<const uint4*>(Kb + (size_t)tok * d + lcc * 8);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      int tok = tile_token(t, 4 * kg + kk);
+      tok = tok < 0 ? 0 : tok;
+      vreg[kk] = *reinterpret_cast<const uint4*>(Vb + (size_t)tok * d + lcc * 8);
+    }
+  };
+  auto store_lds = [&]() {
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr)
+      *reinterpret_cast<uint4*>(&Ks[(lrow + 16 * rr) * KS_STRIDE + lcc * 8]) = kreg[rr];
+    const uint32_t w[4][4] = {{vreg[0].x, vreg[0].y, vreg[0].z, vreg[0].w},
+                              {vreg[1].x, vreg[1].y, vreg[1].z, vreg[1].w},
+                              {vreg[2].x, vreg[2].y, vreg[2].z, vreg[2].w},
+                              {vreg[3].x, vreg[3].y, vreg[3].z, vreg[3].w}};
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {        // columns 8 lcc + 2 e2 (low halves) and + 1 (high halves)
+      uint2 lo, hi;
+      lo.x = (w[0][e2] & 0xFFFFu) | (w[1][e2] << 16);
+      lo.y = (w[2][e2] & 0xFFFFu) | (w[3][e2] << 16);
+      hi.x = (w[0][e2] >> 16) | (w[1][e2] & 0xFFFF0000u);
+      hi.y = (w[2][e2] >> 16) | (w[3][e2] & 0xFFFF0000u);
+      *reinterpret_cast<uint2*>(&Vt[(lcc * 8 + 2 * e2) * VT_STRIDE + vpos]) = lo;
+      *reinterpret_cast<uint2*>(&Vt[(lcc * 8 + 2 * e2 + 1) * VT_STRIDE + vpos]) = hi;
+    }
+  };
+
+  if (n_tiles > 0) issue_loads(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    __syncthreads();                        // everyone is done reading the previous tile
+    store_lds();
+    __syncthreads();
+    if (t + 1 < n_tiles) issue_loads(t + 1);
+    const bool is_chunk = t >= n_ctx_tiles;
+    const int k0 = is_chunk ? (t - n_ctx_tiles) * 64 : 0;      // chunk-local position of key 0
+    if (is_chunk && k0 > r0 + QW - 1) continue;                // nothing visible for this wave
+    if (r0 >= L) continue;
+    // ---- S^T = K Q^T ----
+    f32x16_t s[2][NQB];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int nq = 0; nq < NQB; ++nq)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[kb][nq][v] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const uint4 kf = *reinterpret_cast<const uint4*>(&Ks[(kb * 32 + l32) * KS_STRIDE + kk * 16 + hf * 8]);
+#pragma unroll
+        for (int nq = 0; nq < NQB; ++nq)
+          s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf),
+                                                              __builtin_bit_cast(bf16x8_t, qf[nq][kk]),
+                                                              s[kb][nq], 0, 0, 0);
+      }
+    }
+    // ---- masks ----
+    if (is_chunk) {
+#pragma unroll
+      for (int nq = 0; nq < NQB; ++nq) {
+        const int qi = r0 + nq * 32 + l32;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int kp = k0 + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+            if (kp > qi) s[kb][nq][v] = -INFINITY;
+          }
+      }
+    } else if (t == n_ctx_tiles - 1 && (list_len & 63)) {
+      const int nvalid = list_len - t * 64;
+#pragma unroll
+      for (int nq = 0; nq < NQB; ++nq)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int kr = kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+            if (kr >= nvalid) s[kb][nq][v] = -INFINITY;
+          }
+    }
+    // ---- online softmax (one query per lane pair) ----
+    uint4 pf[NQB][2][2];
+#pragma unroll
+    for (int nq = 0; nq < NQB; ++nq) {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][nq][v]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run[nq], mx * sc);
+      const float alpha = exp2f(m_run[nq] - m_new);
+      m_run[nq] = m_new;
+      float ps = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        float pv[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { pv[v] = exp2f(s[kb][nq][v] * sc - m_new); ps += pv[v]; }
+#pragma unroll
+        for (int a2 = 0; a2 < 2; ++a2) {
+          uint4 u;
+          u.x = pack_bf16x2(pv[8 * a2 + 0], pv[8 * a2 + 1]);
+          u.y = pack_bf16x2(pv[8 * a2 + 2], pv[8 * a2 + 3]);
+          u.z = pack_bf16x2(pv[8 * a2 + 4], pv[8 * a2 + 5]);
+          u.w = pack_bf16x2(pv[8 * a2 + 6], pv[8 * a2 + 7]);
+          pf[nq][kb][a2] = u;
+        }
+      }
+      l_run[nq] = l_run[nq] * alpha + ps;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[mb][nq][v] *= alpha;
+    }
+    // ---- O^T += V^T P^T ----
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int a2 = 0; a2 < 2; ++a2)
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+          const uint4 vf = *reinterpret_cast<const uint4*>(&Vt[(mb * 32 + l32) * VT_STRIDE + kb * 32 + a2 * 16 + hf * 8]);
+#pragma unroll
+          for (int nq = 0; nq < NQB; ++nq)
+            o[mb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf),
+                                                                __builtin_bit_cast(bf16x8_t, pf[nq][kb][a2]),
+                                                                o[mb][nq], 0, 0, 0);
+        }
+  }
+  // ---- epilogue ----
+  uint16_t* Ob = reinterpret_cast<uint16_t*>(a.out) + (size_t)bi * L * D.Hq * d;
+#pragma unroll
+  for (int nq = 0; nq < NQB; ++nq) {
+    const int qi = r0 + nq * 32 + l32;
+    const float lt = l_run[nq] + __shfl_xor(l_run[nq], 32, 64);
+    if (qi < L) {
+      const float inv = 1.f / lt;
+      uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4) {
+          uint2 u;
+          u.x = pack_bf16x2(o[mb][nq][4 * a4 + 0] * inv, o[mb][nq][4 * a4 + 1] * inv);
+          u.y = pack_bf16x2(o[mb][nq][4 * a4 + 2] * inv, o[mb][nq][4 * a4 + 3] * inv);
+          *reinterpret_cast<uint2*>(orow + mb * 32 + 8 * a4 + 4 * hf) = u;
+        }
+      if (a.lse && hf == 0)
+        a.lse[((size_t)bi * L + qi) * D.Hq + head] = (m_run[nq] + log2f(lt)) * 0.6931471805599453f;
+    }
+  }
+}
+
+// ---- fp32 kernel: one wavefront per (query row, head); keys across lanes ----
+template <int DT>
+__global__ __launch_bounds__(64) void attend_simple_kernel(AttArgs a) {
+  typedef typename Elt<DT>::type T;
+  __shared__ float qs[128];
+  __shared__ float ps[64];
+  __shared__ int toks[64];
+  const Dims& D = a.D;
+  const int qi = blockIdx.x, head = blockIdx.y, bi = blockIdx.z;
+  const int h = head / D.G, d = D.d, per = d / 64;
+  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi], L = a.n_q;
+  const int lane = threadIdx.x;
+  const int slot = slot_of(D, a.layer, seq, h);
+  const T* Kb = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot);
+  const T* Vb = reinterpret_cast<const T*>(a.v_arena) + arena_off(D, slot);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int list_len = meta[META_LIST_LEN];
+  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
+  const T* qrow = reinterpret_cast<const T*>(a.q) + (((size_t)bi * L + qi) * D.Hq + head) * d;
+  for (int c = lane; c < d; c += 64) qs[c] = Elt<DT>::to_f32(qrow[c]);
+  __syncthreads();
+  const float scale = 1.0f / sqrtf((float)d);
+  const int n_keys = list_len + qi + 1;
+  float m_run = -1e30f, l_run = 0.f, o0 = 0.f, o1 = 0.f;
+  for (int k0 = 0; k0 < n_keys; k0 += 64) {
+    const int k = k0 + lane;
+    int tok = -1;
+    if (k < list_len) tok = list[k];
+    else if (k < n_keys) tok = c0 + (k - list_len);
+    float z = -INFINITY;
+    if (tok >= 0) {
+      const T* krow = Kb + (size_t)tok * d;
+      float acc = 0.f;
+      for (int c = 0; c < d; ++c) acc = fmaf(qs[c], Elt<DT>::to_f32(krow[c]), acc);
+      z = acc * scale;
+    }
+    float mx = z;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = expf(m_run - m_new);
+    const float pz = expf(z - m_new);
+    float sum = pz;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    l_run = l_run * alpha + sum;
+    m_run = m_new;
+    __syncthreads();
+    ps[lane] = pz;
+    toks[lane] = tok;
+    __syncthreads();
+    o0 *= alpha; o1 *= alpha;
+    const int cnt = min(64, n_keys - k0);
+    for (int kk = 0; kk < cnt; ++kk) {
+      const int tk = toks[kk];
+      if (tk < 0) continue;
+      const T* vrow = Vb + (size_t)tk * d + lane * per;
+      o0 = fmaf(ps[kk], Elt<DT>::to_f32(vrow[0]), o0);
+      if (per == 2) o1 = fmaf(ps[kk], Elt<DT>::to_f32(vrow[1]), o1);
+    }
+  }
+  T* orow = reinterpret_cast<T*>(a.out) + (((size_t)bi * L + qi) * D.Hq + head) * d + lane * per;
+  const float inv = 1.f / l_run;
+  orow[0] = Elt<DT>::from_f32(o0 * inv);
+  if (per == 2) orow[1] = Elt<DT>::from_f32(o1 * inv);
+  if (a.lse && lane == 0) a.lse[((size_t)bi * L + qi) * D.Hq + head] = m_run + logf(l_run);
+}
+
+// ---- standalone gather: K/V rows of the context list into packed buffers ----
+struct GatherArgs { Dims D; DevState st; const void* k_arena; const void* v_arena; int layer, seq;
+                    void* k_packed; void* v_packed; int32_t* n_tokens; };
+
+__global__ __launch_bounds__(256) void gather_pack_kernel(GatherArgs a) {
+  const Dims& D = a.D;
+  const int h = blockIdx.y;
+  const int slot = slot_of(D, a.layer, a.seq, h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int list_len = meta[META_LIST_LEN];
+  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
+  const int row16 = D.d * D.elt / 16;                        // 16-byte pieces per row
+  const int rows_per_pass = 256 / row16;
+  const int r_in = threadIdx.x / row16, piece = threadIdx.x - r_in * row16;
+  const uint4* Kb = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.k_arena) + arena_off(D, slot) * D.elt);
+  const uint4* Vb = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.v_arena) + arena_off(D, slot) * D.elt);
+  uint4* Kp = reinterpret_cast<uint4*>(a.k_packed) + (size_t)h * D.list_cap * row16;
+  uint4* Vp = reinterpret_cast<uint4*>(a.v_packed) + (size_t)h * D.list_cap * row16;
+  for (int r = blockIdx.x * rows_per_pass + r_in; r < list_len; r += gridDim.x * rows_per_pass) {
+    const int tok = list[r];
+    const uint4 kv = Kb[(size_t)tok * row16 + piece];
+    const uint4 vv = Vb[(size_t)tok * row16 + piece];
+    Kp[(size_t)r * row16 + piece] = kv;
+    Vp[(size_t)r * row16 + piece] = vv;
+  }
+  if (a.n_tokens && blockIdx.x == 0 && threadIdx.x == 0) a.n_tokens[h] = list_len;
+}
+
+hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
+                         const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
+                         void* out, float* lse, hipStream_t s) {
+  AttArgs a;
+  a.D = D; a.st = st; a.k_arena = k_arena; a.v_arena = v_arena; a.q = q; a.out = out; a.lse = lse;
+  a.layer = layer; a.seq_count = seq_count; a.n_q = n_q; a.bp = bp;
+  const bool mfma_ok = D.dtype == LTRI_BF16 && D.d == 128 && (D.G == 1 || D.G == 2 || D.G % 4 == 0);
+  if (mfma_ok) {
+    const int HG = D.G < 4 ? D.G : 4;
+    const int gpk = D.G / HG;
+    constexpr int NQB = 2;
+    const int RPB = 32 * NQB * (4 / HG);
+    dim3 g((n_q + RPB - 1) / RPB, D.Hkv * gpk, seq_count);
+    attend_bf16_kernel<NQB><<<g, 256, 0, s>>>(a);
+  } else {
+    dim3 g(n_q, D.Hq, seq_count);
+    if (D.dtype == LTRI_BF16) attend_simple_kernel<LTRI_BF16><<<g, 64, 0, s>>>(a);
+    else                      attend_simple_kernel<LTRI_F32><<<g, 64, 0, s>>>(a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_pack(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
+                              int layer, int seq, void* k_packed, void* v_packed, int32_t* n_tokens,
+                              hipStream_t s) {
+  GatherArgs a{D, st, k_arena, v_arena, layer, seq, k_packed, v_packed, n_tokens};
+  const int row16 = D.d * D.elt / 16;
+  const int rows_per_pass = 256 / row16;
+  int gx = (D.list_cap + rows_per_pass * 4 - 1) / (rows_per_pass * 4);
+  if (gx < 1) gx = 1;
+  dim3 g(gx, D.Hkv);
+  gather_pack_kernel<<<g, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace ltri

@@ -1,0 +1,549 @@
+// Host side of libltri: context, argument checks, buffer layout, kernel sequencing.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "ltri_internal.h"
+
+using namespace ltri;
+
+struct ltri_ctx {
+  ltri_config cfg;
+  Dims D;
+  StateLayout SL;
+  ScratchLayout CL;
+  char* k_arena; char* v_arena; char* state; char* scratch;
+  hipStream_t stream;
+  DevState ds;
+  DevScratch dc;
+  bool dry;
+  // host mirror of the stream positions, per (layer, seq)
+  std::vector<long long> n_tokens;       // tokens appended
+  std::vector<int> last_len;             // length of the chunk appended last (0 = none)
+  std::vector<long long> span_bound;     // upper bound on the spans stored per KV head
+  std::vector<uint32_t> have_sel;        // bit h set: KV head h has a selection for the last chunk
+  std::string err;
+};
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int32_t fail(ltri_ctx* c, int32_t code, const char* fmt, ...) {
+  if (c) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    c->err = buf;
+  }
+  return code;
+}
+
+static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchLayout& CL) {
+  if (!cfg) return LTRI_EINVAL;
+  const ltri_config& c = *cfg;
+  if (c.n_q_heads < 1 || c.n_kv_heads < 1 || c.n_q_heads % c.n_kv_heads) return LTRI_EINVAL;
+  if (c.dtype != LTRI_F32 && c.dtype != LTRI_BF16) return LTRI_EINVAL;
+  if (c.head_dim != 64 && c.head_dim != 128) return LTRI_EINVAL;
+  if (c.dtype == LTRI_BF16 && c.head_dim != 128) return LTRI_EINVAL;
+  if (c.n_layers < 1 || c.n_seqs < 1 || c.max_tokens < 1 || c.max_tokens > (1ll << 30)) return LTRI_EINVAL;
+  if (c.chunk_max < 1 || c.chunk_max > SEG_MAX_L) return LTRI_EINVAL;
+  if (c.n_sink < 0 || c.window < 0 || c.k_max < 0 || c.budget_tokens < 0) return LTRI_EINVAL;
+  if (c.seg_map != LTRI_MAP_SOFTMAX && c.seg_map != LTRI_MAP_LOGIT) return LTRI_EINVAL;
+  if (!(c.phi >= 0.0f) || !(c.theta == c.theta)) return LTRI_EINVAL;
+  if (c.max_spans_per_chunk < 0 || c.rep_mode != LTRI_REP_MEAN || c.max_spans < 0) return LTRI_EINVAL;
+  const int G = c.n_q_heads / c.n_kv_heads;
+  if (c.dtype == LTRI_BF16 && !(G == 1 || G == 2 || G % 4 == 0)) return LTRI_EINVAL;
+  D.Hq = c.n_q_heads; D.Hkv = c.n_kv_heads; D.G = G; D.d = c.head_dim; D.dtype = c.dtype;
+  D.n_layers = c.n_layers; D.n_seqs = c.n_seqs; D.max_tokens = c.max_tokens;
+  D.chunk_max = c.chunk_max; D.n_sink = c.n_sink; D.window = c.window; D.k_max = c.k_max;
+  D.budget = c.budget_tokens; D.seg_map = c.seg_map; D.theta = c.theta; D.phi = c.phi;
+  D.max_keep = c.max_spans_per_chunk;
+  if (c.max_spans > 65536) return LTRI_EINVAL;
+  long long ms = c.max_spans ? c.max_spans : std::min<long long>(c.max_tokens / 32 + 64, 65536);
+  if (ms > c.max_tokens) ms = c.max_tokens;
+  if (ms < 1 || ms > 65536) return LTRI_EINVAL;
+  D.max_spans = (int)ms;
+  long long sel = ms;
+  if (c.k_max) sel = std::min<long long>(sel, c.k_max);
+  if (c.budget_tokens) sel = std::min<long long>(sel, c.budget_tokens);
+  D.sel_cap = (int)std::max<long long>(sel, 1);
+  long long ret = c.max_tokens;
+  if (c.budget_tokens) ret = std::min<long long>(ret, c.budget_tokens);
+  if (c.k_max) ret = std::min<long long>(ret, (long long)c.k_max * c.chunk_max);
+  long long lc = std::min<long long>(c.max_tokens, (long long)c.n_sink + ret + c.window);
+  lc = (long long)align_up((size_t)lc, ATT_BN) + ATT_BN;
+  if (lc > (1ll << 30)) return LTRI_EINVAL;
+  D.list_cap = (int)lc;
+  D.elt = c.dtype == LTRI_F32 ? 4 : 2;
+
+  const size_t n_slots = (size_t)c.n_layers * c.n_seqs * c.n_kv_heads;
+  size_t o = 0;
+  SL.meta = o;       o = align_up(o + n_slots * META_WORDS * 4, 256);
+  SL.span_start = o; o = align_up(o + n_slots * D.max_spans * 4, 256);
+  SL.span_len = o;   o = align_up(o + n_slots * D.max_spans * 4, 256);
+  SL.krep = o;       o = align_up(o + n_slots * D.max_spans * (size_t)D.d * D.elt, 256);
+  SL.scores = o;     o = align_up(o + n_slots * D.max_spans * 8, 256);
+  SL.sel_ids = o;    o = align_up(o + n_slots * D.sel_cap * 4, 256);
+  SL.tok_list = o;   o = align_up(o + n_slots * (size_t)D.list_cap * 4, 256);
+  SL.err = o;        o = align_up(o + 16, 256);
+  SL.total = o;
+
+  // scratch: segmentation temporaries for up to 4 sequences at a time
+  const int P = std::min(c.n_seqs, 4) * c.n_kv_heads;
+  const size_t nb = (c.chunk_max + SEG_TB - 1) / SEG_TB, Lp = nb * SEG_TB, nt = nb * (nb + 1) / 2;
+  o = 0;
+  CL.rowsum = o; o = align_up(o + (size_t)P * nb * Lp * 8, 256);
+  CL.csuf = o;   o = align_up(o + (size_t)P * nb * Lp * 8, 256);
+  CL.tsum = o;   o = align_up(o + (size_t)P * nb * nb * 8, 256);
+  CL.rcar = o;   o = align_up(o + (size_t)P * nb * Lp * 8, 256);
+  CL.ccar = o;   o = align_up(o + (size_t)P * nb * Lp * 8, 256);
+  CL.pscore = o; o = align_up(o + (size_t)P * nt * 128 * 8, 256);
+  CL.px = o;     o = align_up(o + (size_t)P * nt * 128 * 4, 256);
+  CL.lse = o;    o = align_up(o + (size_t)P * G * Lp * 8, 256);
+  // query-span representatives are needed for every sequence of a batched retrieve
+  CL.qrep = o;   o = align_up(o + (size_t)c.n_seqs * c.n_kv_heads * Lp * D.d * D.elt, 256);
+  CL.bounds = o; o = align_up(o + (size_t)c.n_kv_heads * (c.chunk_max + 2) * 4, 256);
+  CL.total = o;
+  CL.max_problems = P;
+  return LTRI_OK;
+}
+
+extern "C" {
+
+const char* ltri_version(void) { return "libltri 0.1 gfx950"; }
+
+const char* ltri_strerror(int32_t s) {
+  switch (s) {
+    case LTRI_OK: return "ok";
+    case LTRI_EINVAL: return "invalid argument or unsupported configuration";
+    case LTRI_ESTATE: return "call out of order";
+    case LTRI_ECAPACITY: return "token or span capacity exceeded";
+    case LTRI_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* ltri_last_error(const ltri_ctx* c) { return c ? c->err.c_str() : ""; }
+
+int32_t ltri_workspace_bytes(const ltri_config* cfg, size_t* state_bytes, size_t* scratch_bytes) {
+  Dims D; StateLayout SL; ScratchLayout CL;
+  const int32_t r = derive(cfg, D, SL, CL);
+  if (r != LTRI_OK) return r;
+  if (state_bytes) *state_bytes = SL.total;
+  if (scratch_bytes) *scratch_bytes = CL.total;
+  return LTRI_OK;
+}
+
+static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena, void* state, void* scratch,
+                           void* hip_stream, bool dry, ltri_ctx** out) {
+  if (!out) return LTRI_EINVAL;
+  *out = nullptr;
+  Dims D; StateLayout SL; ScratchLayout CL;
+  const int32_t r = derive(cfg, D, SL, CL);
+  if (r != LTRI_OK) return r;
+  if (!dry) {
+    if (!k_arena || !v_arena || !state || !scratch) return LTRI_EINVAL;
+    if (((uintptr_t)k_arena | (uintptr_t)v_arena | (uintptr_t)state | (uintptr_t)scratch) & 255) return LTRI_EINVAL;
+  }
+  ltri_ctx* c = new (std::nothrow) ltri_ctx();
+  if (!c) return LTRI_EINVAL;
+  c->cfg = *cfg; c->D = D; c->SL = SL; c->CL = CL;
+  c->k_arena = (char*)k_arena; c->v_arena = (char*)v_arena; c->state = (char*)state; c->scratch = (char*)scratch;
+  c->stream = (hipStream_t)hip_stream;
+  c->dry = dry;
+  char* s = c->state;
+  c->ds = DevState{(int32_t*)(s + SL.meta), (int32_t*)(s + SL.span_start), (int32_t*)(s + SL.span_len),
+                   (void*)(s + SL.krep), (double*)(s + SL.scores), (int32_t*)(s + SL.sel_ids),
+                   (int32_t*)(s + SL.tok_list), (int32_t*)(s + SL.err)};
+  char* t = c->scratch;
+  c->dc = DevScratch{(double*)(t + CL.rowsum), (double*)(t + CL.csuf), (double*)(t + CL.tsum),
+                     (double*)(t + CL.rcar), (double*)(t + CL.ccar), (double*)(t + CL.pscore),
+                     (int32_t*)(t + CL.px), (double*)(t + CL.lse), (void*)(t + CL.qrep),
+                     (int32_t*)(t + CL.bounds)};
+  const size_t n = (size_t)D.n_layers * D.n_seqs;
+  c->n_tokens.assign(n, 0);
+  c->last_len.assign(n, 0);
+  c->span_bound.assign(n, 0);
+  c->have_sel.assign(n, 0u);
+  if (!dry) {
+    const hipError_t e = launch_fill_zero(c->state, SL.total, c->stream);
+    if (e != hipSuccess) { delete c; return LTRI_EHIP; }
+  }
+  *out = c;
+  return LTRI_OK;
+}
+
+int32_t ltri_create(const ltri_config* cfg, void* k_arena, void* v_arena, void* state, void* scratch,
+                    void* hip_stream, ltri_ctx** out) {
+  return create_impl(cfg, k_arena, v_arena, state, scratch, hip_stream, false, out);
+}
+
+int32_t ltri_create_dry(const ltri_config* cfg, ltri_ctx** out) {
+  return create_impl(cfg, nullptr, nullptr, nullptr, nullptr, nullptr, true, out);
+}
+
+int32_t ltri_destroy(ltri_ctx* c) {
+  if (!c) return LTRI_EINVAL;
+  delete c;
+  return LTRI_OK;
+}
+
+int32_t ltri_sel_capacity(const ltri_ctx* c) { return c ? c->D.sel_cap : LTRI_EINVAL; }
+int32_t ltri_list_capacity(const ltri_ctx* c) { return c ? c->D.list_cap : LTRI_EINVAL; }
+
+}  // extern "C"
+
+// ------------------------------------------------------------------------------------------
+static int32_t check_hip(ltri_ctx* c, hipError_t e, const char* what) {
+  if (e == hipSuccess) return LTRI_OK;
+  return fail(c, LTRI_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+static int32_t check_range(ltri_ctx* c, int layer, int seq_begin, int seq_count) {
+  if (!c) return LTRI_EINVAL;
+  if (layer < 0 || layer >= c->D.n_layers) return fail(c, LTRI_EINVAL, "layer %d out of range", layer);
+  if (seq_count < 1 || seq_count > LTRI_MAX_BATCH || seq_begin < 0 || seq_begin + seq_count > c->D.n_seqs)
+    return fail(c, LTRI_EINVAL, "sequence range [%d, %d) invalid", seq_begin, seq_begin + seq_count);
+  return LTRI_OK;
+}
+
+static size_t ls_index(const ltri_ctx* c, int layer, int seq) { return (size_t)layer * c->D.n_seqs + seq; }
+
+extern "C" {
+
+int32_t ltri_reset(ltri_ctx* c, int32_t seq) {
+  if (!c) return LTRI_EINVAL;
+  if (seq < 0 || seq >= c->D.n_seqs) return fail(c, LTRI_EINVAL, "sequence %d out of range", seq);
+  for (int l = 0; l < c->D.n_layers; ++l) {
+    const size_t i = ls_index(c, l, seq);
+    c->n_tokens[i] = 0; c->last_len[i] = 0; c->span_bound[i] = 0; c->have_sel[i] = 0;
+    if (!c->dry) {
+      const size_t off = c->SL.meta + ((size_t)(l * c->D.n_seqs + seq) * c->D.Hkv) * META_WORDS * 4;
+      // META_WORDS * 4 = 32 bytes per slot: the slots of one (layer, seq) are contiguous
+      const int32_t r = check_hip(c, launch_fill_zero(c->state + off, (size_t)c->D.Hkv * META_WORDS * 4, c->stream),
+                                  "reset");
+      if (r != LTRI_OK) return r;
+    }
+  }
+  return LTRI_OK;
+}
+
+static int32_t append_common(ltri_ctx* c, int layer, int seq_begin, int seq_count, const void* k_chunk,
+                             const void* v_chunk, int n_new, BatchPos& bp) {
+  int32_t r = check_range(c, layer, seq_begin, seq_count);
+  if (r != LTRI_OK) return r;
+  if (n_new < 1 || n_new > c->D.chunk_max)
+    return fail(c, LTRI_EINVAL, "n_new %d outside [1, chunk_max %d]", n_new, c->D.chunk_max);
+  if ((k_chunk == nullptr) != (v_chunk == nullptr))
+    return fail(c, LTRI_EINVAL, "k_chunk and v_chunk must both be given or both be NULL");
+  for (int s = 0; s < seq_count; ++s) {
+    const size_t i = ls_index(c, layer, seq_begin + s);
+    if (c->n_tokens[i] + n_new > c->D.max_tokens)
+      return fail(c, LTRI_ECAPACITY, "sequence %d: %lld + %d tokens exceed max_tokens %lld", seq_begin + s,
+                  c->n_tokens[i], n_new, c->D.max_tokens);
+    bp.seq[s] = seq_begin + s;
+    bp.c0[s] = (int32_t)c->n_tokens[i];
+  }
+  if (k_chunk && !c->dry) {
+    r = check_hip(c, launch_copy_chunk(c->D, c->k_arena, c->v_arena, k_chunk, v_chunk, layer, bp, seq_count,
+                                       n_new, c->stream), "copy chunk");
+    if (r != LTRI_OK) return r;
+  }
+  return LTRI_OK;
+}
+
+static void append_commit(ltri_ctx* c, int layer, int seq_begin, int seq_count, int n_new) {
+  for (int s = 0; s < seq_count; ++s) {
+    const size_t i = ls_index(c, layer, seq_begin + s);
+    c->n_tokens[i] += n_new;
+    c->last_len[i] = n_new;
+    c->span_bound[i] = std::min<long long>(c->span_bound[i] + n_new, c->D.max_spans);
+    c->have_sel[i] = 0;
+  }
+}
+
+int32_t ltri_append_chunk(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count,
+                          const void* k_chunk, const void* v_chunk, const void* q_seg, int32_t n_new) {
+  BatchPos bp;
+  memset(&bp, 0, sizeof bp);
+  int32_t r = append_common(c, layer, seq_begin, seq_count, k_chunk, v_chunk, n_new, bp);
+  if (r != LTRI_OK) return r;
+  if (!c->dry) {
+    if (n_new == 1) {
+      r = check_hip(c, launch_append_single(c->D, c->ds, c->k_arena, layer, bp, seq_count, c->stream),
+                    "append (single token)");
+      if (r != LTRI_OK) return r;
+    } else {
+      const int per = c->CL.max_problems / c->D.Hkv;     // sequences per segmentation launch
+      for (int off = 0; off < seq_count; off += per) {
+        const int cnt = std::min(per, seq_count - off);
+        r = check_hip(c, launch_segment(c->D, c->ds, c->dc, c->k_arena, q_seg, layer, bp, off, cnt, n_new,
+                                        c->stream), "segment");
+        if (r != LTRI_OK) return r;
+      }
+      r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, seq_count, n_new, c->stream),
+                    "representative keys");
+      if (r != LTRI_OK) return r;
+    }
+  }
+  append_commit(c, layer, seq_begin, seq_count, n_new);
+  return LTRI_OK;
+}
+
+int32_t ltri_append_chunk_with_spans(ltri_ctx* c, int32_t layer, int32_t seq, const void* k_chunk,
+                                     const void* v_chunk, int32_t n_new, const int32_t* bounds_host,
+                                     const int32_t* n_bounds_host) {
+  BatchPos bp;
+  memset(&bp, 0, sizeof bp);
+  if (!c) return LTRI_EINVAL;
+  if (!bounds_host || !n_bounds_host) return fail(c, LTRI_EINVAL, "bounds missing");
+  // validate the boundaries before anything is enqueued
+  if (n_new < 1 || n_new > c->D.chunk_max)
+    return fail(c, LTRI_EINVAL, "n_new %d outside [1, chunk_max %d]", n_new, c->D.chunk_max);
+  std::vector<int32_t> staged((size_t)c->D.Hkv * (c->D.chunk_max + 1) + c->D.Hkv, 0);
+  size_t pos = 0;
+  for (int h = 0; h < c->D.Hkv; ++h) {
+    const int nbh = n_bounds_host[h];
+    if (nbh < 2 || nbh > n_new + 1) return fail(c, LTRI_EINVAL, "head %d: %d boundaries", h, nbh);
+    const int32_t* b = bounds_host + pos;
+    if (b[0] != 0 || b[nbh - 1] != n_new) return fail(c, LTRI_EINVAL, "head %d: boundaries must run from 0 to n_new", h);
+    for (int k = 1; k < nbh; ++k)
+      if (b[k] <= b[k - 1]) return fail(c, LTRI_EINVAL, "head %d: boundaries not strictly increasing", h);
+    memcpy(&staged[(size_t)h * (c->D.chunk_max + 1)], b, (size_t)nbh * 4);
+    staged[(size_t)c->D.Hkv * (c->D.chunk_max + 1) + h] = nbh;
+    pos += nbh;
+  }
+  int32_t r = append_common(c, layer, seq, 1, k_chunk, v_chunk, n_new, bp);
+  if (r != LTRI_OK) return r;
+  if (!c->dry) {
+    r = check_hip(c, hipMemcpyAsync(c->dc.bounds, staged.data(), staged.size() * 4, hipMemcpyHostToDevice,
+                                    c->stream), "copy boundaries");
+    if (r != LTRI_OK) return r;
+    r = check_hip(c, hipStreamSynchronize(c->stream), "copy boundaries (sync)");   // staged is a local
+    if (r != LTRI_OK) return r;
+    r = check_hip(c, launch_append_bounds(c->D, c->ds, c->dc, layer, seq, bp.c0[0], n_new, c->stream),
+                  "append (given spans)");
+    if (r != LTRI_OK) return r;
+    r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, 1, n_new, c->stream),
+                  "representative keys");
+    if (r != LTRI_OK) return r;
+  }
+  append_commit(c, layer, seq, 1, n_new);
+  return LTRI_OK;
+}
+
+static int32_t check_query_chunk(ltri_ctx* c, int layer, int seq_begin, int seq_count, const void* q, int n_q,
+                                 BatchPos& bp) {
+  int32_t r = check_range(c, layer, seq_begin, seq_count);
+  if (r != LTRI_OK) return r;
+  if (!q) return fail(c, LTRI_EINVAL, "q is NULL");
+  for (int s = 0; s < seq_count; ++s) {
+    const size_t i = ls_index(c, layer, seq_begin + s);
+    if (c->last_len[i] == 0) return fail(c, LTRI_ESTATE, "sequence %d: no chunk appended yet", seq_begin + s);
+    if (c->last_len[i] != n_q)
+      return fail(c, LTRI_ESTATE, "sequence %d: n_q %d differs from the last appended chunk (%d tokens)",
+                  seq_begin + s, n_q, c->last_len[i]);
+    bp.seq[s] = seq_begin + s;
+    bp.c0[s] = (int32_t)(c->n_tokens[i] - n_q);
+  }
+  return LTRI_OK;
+}
+
+int32_t ltri_retrieve(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q,
+                      int32_t n_q, int32_t* sel_ids, int32_t* sel_cnt) {
+  BatchPos bp;
+  memset(&bp, 0, sizeof bp);
+  int32_t r = check_query_chunk(c, layer, seq_begin, seq_count, q, n_q, bp);
+  if (r != LTRI_OK) return r;
+  if (!c->dry) {
+    long long bound = 0;
+    for (int s = 0; s < seq_count; ++s) bound = std::max(bound, c->span_bound[ls_index(c, layer, seq_begin + s)]);
+    r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, q, layer, bp, seq_count, n_q, (int)bound, sel_ids,
+                                     sel_cnt, c->stream), "retrieve");
+    if (r != LTRI_OK) return r;
+  }
+  for (int s = 0; s < seq_count; ++s) c->have_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
+  return LTRI_OK;
+}
+
+int32_t ltri_force_selection(ltri_ctx* c, int32_t layer, int32_t seq, int32_t kv_head, const int32_t* ids_host,
+                             int32_t n) {
+  int32_t r = check_range(c, layer, seq, 1);
+  if (r != LTRI_OK) return r;
+  if (kv_head < 0 || kv_head >= c->D.Hkv) return fail(c, LTRI_EINVAL, "kv_head %d out of range", kv_head);
+  if (n < 0 || (n > 0 && !ids_host)) return fail(c, LTRI_EINVAL, "bad id list");
+  const size_t i = ls_index(c, layer, seq);
+  if (c->last_len[i] == 0) return fail(c, LTRI_ESTATE, "no chunk appended yet");
+  std::vector<int32_t> ids(ids_host, ids_host + n);
+  std::sort(ids.begin(), ids.end());
+  ids.erase(std::unique(ids.begin(), ids.end()), ids.end());
+  if (!ids.empty() && ids.front() < 0) return fail(c, LTRI_EINVAL, "negative span id");
+  if ((long long)ids.size() > c->D.sel_cap)
+    return fail(c, LTRI_ECAPACITY, "%zu ids exceed the selection capacity %d", ids.size(), c->D.sel_cap);
+  if (!c->dry) {
+    const int slot = (layer * c->D.n_seqs + seq) * c->D.Hkv + kv_head;
+    if (!ids.empty()) {
+      r = check_hip(c, hipMemcpyAsync(c->ds.sel_ids + (size_t)slot * c->D.sel_cap, ids.data(), ids.size() * 4,
+                                      hipMemcpyHostToDevice, c->stream), "copy ids");
+      if (r != LTRI_OK) return r;
+      r = check_hip(c, hipStreamSynchronize(c->stream), "copy ids (sync)");
+      if (r != LTRI_OK) return r;
+    }
+    r = check_hip(c, launch_force_list(c->D, c->ds, layer, seq, kv_head, (int)ids.size(), c->stream),
+                  "forced selection");
+    if (r != LTRI_OK) return r;
+  }
+  c->have_sel[i] |= 1u << (kv_head & 31);
+  return LTRI_OK;
+}
+
+int32_t ltri_attend(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q, int32_t n_q,
+                    void* out, float* lse) {
+  BatchPos bp;
+  memset(&bp, 0, sizeof bp);
+  int32_t r = check_query_chunk(c, layer, seq_begin, seq_count, q, n_q, bp);
+  if (r != LTRI_OK) return r;
+  if (!out) return fail(c, LTRI_EINVAL, "out is NULL");
+  const uint32_t need = c->D.Hkv >= 32 ? 0xFFFFFFFFu : ((1u << c->D.Hkv) - 1u);
+  for (int s = 0; s < seq_count; ++s)
+    if ((c->have_sel[ls_index(c, layer, seq_begin + s)] & need) != need)
+      return fail(c, LTRI_ESTATE, "sequence %d: no selection for the last chunk (call ltri_retrieve first)",
+                  seq_begin + s);
+  if (!c->dry) {
+    r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_q, out, lse,
+                                   c->stream), "attend");
+    if (r != LTRI_OK) return r;
+  }
+  return LTRI_OK;
+}
+
+int32_t ltri_gather_pack(ltri_ctx* c, int32_t layer, int32_t seq, void* k_packed, void* v_packed,
+                         int32_t* n_tokens) {
+  int32_t r = check_range(c, layer, seq, 1);
+  if (r != LTRI_OK) return r;
+  if (!k_packed || !v_packed) return fail(c, LTRI_EINVAL, "packed buffers missing");
+  const size_t i = ls_index(c, layer, seq);
+  const uint32_t need = c->D.Hkv >= 32 ? 0xFFFFFFFFu : ((1u << c->D.Hkv) - 1u);
+  if (c->last_len[i] == 0 || (c->have_sel[i] & need) != need) return fail(c, LTRI_ESTATE, "no selection to gather");
+  if (!c->dry) {
+    r = check_hip(c, launch_gather_pack(c->D, c->ds, c->k_arena, c->v_arena, layer, seq, k_packed, v_packed,
+                                        n_tokens, c->stream), "gather");
+    if (r != LTRI_OK) return r;
+  }
+  return LTRI_OK;
+}
+
+// ---- introspection ----
+static int32_t check_slot(ltri_ctx* c, int layer, int seq, int h) {
+  int32_t r = check_range(c, layer, seq, 1);
+  if (r != LTRI_OK) return r;
+  if (h < 0 || h >= c->D.Hkv) return fail(c, LTRI_EINVAL, "kv_head %d out of range", h);
+  if (c->dry) return fail(c, LTRI_ESTATE, "no device data in dry-run mode");
+  return check_hip(c, hipStreamSynchronize(c->stream), "synchronise");
+}
+
+static int32_t read_dev(ltri_ctx* c, void* dst, const void* src, size_t bytes) {
+  if (bytes == 0) return LTRI_OK;
+  return check_hip(c, hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost), "read back");
+}
+
+int32_t ltri_sync_status(ltri_ctx* c) {
+  if (!c) return LTRI_EINVAL;
+  if (c->dry) return LTRI_OK;
+  int32_t r = check_hip(c, hipStreamSynchronize(c->stream), "synchronise");
+  if (r != LTRI_OK) return r;
+  int32_t e[4] = {0, 0, 0, 0};
+  r = read_dev(c, e, c->ds.err, sizeof e);
+  if (r != LTRI_OK) return r;
+  if (e[0] != 0) return fail(c, e[0], "raised on the device: %s", ltri_strerror(e[0]));
+  return LTRI_OK;
+}
+
+int32_t ltri_token_count(ltri_ctx* c, int32_t layer, int32_t seq, int64_t* n) {
+  int32_t r = check_range(c, layer, seq, 1);
+  if (r != LTRI_OK) return r;
+  if (!n) return LTRI_EINVAL;
+  *n = c->n_tokens[ls_index(c, layer, seq)];
+  return LTRI_OK;
+}
+
+static int32_t read_meta(ltri_ctx* c, int layer, int seq, int h, int32_t* meta) {
+  const int slot = (layer * c->D.n_seqs + seq) * c->D.Hkv + h;
+  return read_dev(c, meta, c->ds.meta + (size_t)slot * META_WORDS, META_WORDS * 4);
+}
+
+int32_t ltri_span_count(ltri_ctx* c, int32_t layer, int32_t seq, int32_t h, int32_t* n) {
+  int32_t r = check_slot(c, layer, seq, h);
+  if (r != LTRI_OK) return r;
+  if (!n) return LTRI_EINVAL;
+  int32_t meta[META_WORDS];
+  r = read_meta(c, layer, seq, h, meta);
+  if (r != LTRI_OK) return r;
+  *n = meta[META_N_SPANS];
+  return LTRI_OK;
+}
+
+int32_t ltri_get_spans(ltri_ctx* c, int32_t layer, int32_t seq, int32_t h, int32_t* starts_host,
+                       int32_t* lens_host, int32_t cap) {
+  int32_t r = check_slot(c, layer, seq, h);
+  if (r != LTRI_OK) return r;
+  int32_t meta[META_WORDS];
+  r = read_meta(c, layer, seq, h, meta);
+  if (r != LTRI_OK) return r;
+  const int n = std::min(meta[META_N_SPANS], cap);
+  if (n < 0) return LTRI_EINVAL;
+  const int slot = (layer * c->D.n_seqs + seq) * c->D.Hkv + h;
+  if (starts_host) { r = read_dev(c, starts_host, c->ds.span_start + (size_t)slot * c->D.max_spans, (size_t)n * 4); if (r) return r; }
+  if (lens_host) { r = read_dev(c, lens_host, c->ds.span_len + (size_t)slot * c->D.max_spans, (size_t)n * 4); if (r) return r; }
+  return LTRI_OK;
+}
+
+int32_t ltri_get_rep_keys(ltri_ctx* c, int32_t layer, int32_t seq, int32_t h, void* reps_host, int32_t cap) {
+  int32_t r = check_slot(c, layer, seq, h);
+  if (r != LTRI_OK) return r;
+  if (!reps_host) return LTRI_EINVAL;
+  int32_t meta[META_WORDS];
+  r = read_meta(c, layer, seq, h, meta);
+  if (r != LTRI_OK) return r;
+  const int n = std::min(meta[META_N_SPANS], cap);
+  if (n < 0) return LTRI_EINVAL;
+  const int slot = (layer * c->D.n_seqs + seq) * c->D.Hkv + h;
+  const size_t row = (size_t)c->D.d * c->D.elt;
+  return read_dev(c, reps_host, (char*)c->ds.krep + (size_t)slot * c->D.max_spans * row, (size_t)n * row);
+}
+
+int32_t ltri_get_selection(ltri_ctx* c, int32_t layer, int32_t seq, int32_t h, int32_t* ids_host, int32_t cap,
+                           int32_t* n, double* scores_host) {
+  int32_t r = check_slot(c, layer, seq, h);
+  if (r != LTRI_OK) return r;
+  int32_t meta[META_WORDS];
+  r = read_meta(c, layer, seq, h, meta);
+  if (r != LTRI_OK) return r;
+  const int slot = (layer * c->D.n_seqs + seq) * c->D.Hkv + h;
+  const int cnt = meta[META_SEL_CNT];
+  if (n) *n = cnt;
+  if (ids_host) { r = read_dev(c, ids_host, c->ds.sel_ids + (size_t)slot * c->D.sel_cap, (size_t)std::max(0, std::min(cnt, cap)) * 4); if (r) return r; }
+  if (scores_host) { r = read_dev(c, scores_host, c->ds.scores + (size_t)slot * c->D.max_spans, (size_t)meta[META_N_SPANS] * 8); if (r) return r; }
+  return LTRI_OK;
+}
+
+int32_t ltri_get_token_list(ltri_ctx* c, int32_t layer, int32_t seq, int32_t h, int32_t* tokens_host, int32_t cap,
+                            int32_t* n) {
+  int32_t r = check_slot(c, layer, seq, h);
+  if (r != LTRI_OK) return r;
+  int32_t meta[META_WORDS];
+  r = read_meta(c, layer, seq, h, meta);
+  if (r != LTRI_OK) return r;
+  const int slot = (layer * c->D.n_seqs + seq) * c->D.Hkv + h;
+  const int len = meta[META_LIST_LEN];
+  if (n) *n = len;
+  if (tokens_host) return read_dev(c, tokens_host, c->ds.tok_list + (size_t)slot * c->D.list_cap, (size_t)std::max(0, std::min(len, cap)) * 4);
+  return LTRI_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,110 @@
+// Internal declarations shared by the host API and the HIP kernels of libltri.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "ltri.h"
+
+namespace ltri {
+
+// ---- per-slot metadata words (slot = (layer * n_seqs + seq) * n_kv_heads + kv_head) ----
+enum : int {
+  META_N_SPANS = 0,      // spans stored so far
+  META_CHUNK_FIRST = 1,  // id of the first span of the chunk appended last
+  META_CHUNK_NSP = 2,    // number of spans of that chunk
+  META_CHUNK_START = 3,  // absolute position of that chunk's first token
+  META_CHUNK_LEN = 4,    // its length
+  META_SEL_CNT = 5,      // spans selected by the last retrieve
+  META_LIST_LEN = 6,     // tokens in the context list (initial | retrieved | window)
+  META_RESERVED = 7,
+  META_WORDS = 8
+};
+
+constexpr int SEG_TB = 64;          // side of a segmentation tile
+constexpr int SEG_MAX_L = 2048;     // longest chunk the segmentation kernels take
+constexpr int SEG_MAX_NB = SEG_MAX_L / SEG_TB;
+constexpr int ATT_BN = 64;          // keys per attention tile; token lists are padded to it
+
+// Byte offsets of the arrays inside the caller's `state` buffer.
+struct StateLayout {
+  size_t meta;        // int32  [n_slots][META_WORDS]
+  size_t span_start;  // int32  [n_slots][max_spans]
+  size_t span_len;    // int32  [n_slots][max_spans]
+  size_t krep;        // dtype  [n_slots][max_spans][d]
+  size_t scores;      // double [n_slots][max_spans]
+  size_t sel_ids;     // int32  [n_slots][sel_cap]
+  size_t tok_list;    // int32  [n_slots][list_cap]
+  size_t err;         // int32  [4]
+  size_t total;
+};
+
+// Byte offsets inside `scratch` for one batch of segmentation problems.
+struct ScratchLayout {
+  size_t rowsum;   // double [P][nb][Lp]   tile row sums, indexed [J][i]
+  size_t csuf;     // double [P][nb][Lp]   suffix-scanned tile column sums, indexed [I][x]
+  size_t tsum;     // double [P][nb][nb]
+  size_t rcar;     // double [P][nb][Lp]   row carry  RC[J][i]
+  size_t ccar;     // double [P][nb][Lp]   column carry A[I][x]
+  size_t pscore;   // double [P][ntiles][128]
+  size_t px;       // int32  [P][ntiles][128]
+  size_t lse;      // double [P][G][Lp]    (SOFTMAX map only)
+  size_t qrep;     // dtype  [P][Lp][d]
+  size_t bounds;   // int32  [Hkv][chunk_max + 1] + int32 [Hkv]  (append_with_spans)
+  size_t total;
+  int    max_problems;  // P the buffer was sized for
+};
+
+struct Dims {
+  int Hq, Hkv, G, d, dtype, n_layers, n_seqs;
+  long long max_tokens;
+  int chunk_max, n_sink, window, k_max;
+  long long budget;
+  int seg_map;
+  float theta, phi;
+  int max_keep;
+  int max_spans, sel_cap, list_cap;
+  int elt;  // bytes per element
+};
+
+struct BatchPos {            // per-sequence values of one batched call
+  int32_t seq[LTRI_MAX_BATCH];
+  int32_t c0[LTRI_MAX_BATCH];   // chunk start (tokens already in the stream)
+};
+
+// Raw device views handed to the kernels.
+struct DevState {
+  int32_t* meta; int32_t* span_start; int32_t* span_len; void* krep; double* scores;
+  int32_t* sel_ids; int32_t* tok_list; int32_t* err;
+};
+struct DevScratch {
+  double* rowsum; double* csuf; double* tsum; double* rcar; double* ccar;
+  double* pscore; int32_t* px; double* lse; void* qrep; int32_t* bounds;
+};
+
+// ---- launchers (each returns the hipError_t of the launch) ----
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_copy_chunk(const Dims& D, void* k_arena, void* v_arena, const void* k_chunk,
+                             const void* v_chunk, int layer, const BatchPos& bp, int seq_count,
+                             int n_new, hipStream_t s);
+hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& sc, const void* k_arena,
+                          const void* q_seg, int layer, const BatchPos& bp, int batch_off, int seq_count,
+                          int n_new, hipStream_t s);
+hipError_t launch_append_single(const Dims& D, const DevState& st, const void* k_arena, int layer,
+                                const BatchPos& bp, int seq_count, hipStream_t s);
+hipError_t launch_append_bounds(const Dims& D, const DevState& st, const DevScratch& sc, int layer,
+                                int seq, int c0, int n_new, hipStream_t s);
+hipError_t launch_rep_keys(const Dims& D, const DevState& st, const void* k_arena, int layer,
+                           const BatchPos& bp, int seq_count, int n_new, hipStream_t s);
+hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, const void* q,
+                           int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
+                           int32_t* sel_ids_out, int32_t* sel_cnt_out, hipStream_t s);
+hipError_t launch_force_list(const Dims& D, const DevState& st, int layer, int seq, int kv_head,
+                             int n_ids, hipStream_t s);
+hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
+                         const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
+                         void* out, float* lse, hipStream_t s);
+hipError_t launch_gather_pack(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
+                              int layer, int seq, void* k_packed, void* v_packed, int32_t* n_tokens,
+                              hipStream_t s);
+
+}  // namespace ltri

@@ -1,0 +1,278 @@
+// Step 2 on the device (Sec. 3.4 second step): query-span representatives, similarity of
+// every stored span with them (Eq. 8 with one vector per span, max over the query spans as in
+// Eq. 9), budgeted top-k selection, and the flat list of context tokens
+// (initial | retrieved | window) that step 3 reads.
+//
+// Scores are accumulated in fp64: products of bf16 (or fp32) values are exact in fp64, so the
+// order of the selection does not depend on the summation order of any implementation.
+#include "device_common.h"
+
+namespace ltri {
+
+struct RetArgs {
+  Dims D; DevState st; DevScratch sc; const void* q;
+  int layer; int seq_count; int n_q; int Lp;
+  int32_t* sel_ids_out; int32_t* sel_cnt_out;
+  BatchPos bp;
+};
+
+// ---- Q^R: mean over each query span of the group-summed query rows ----
+template <int DT>
+__global__ __launch_bounds__(256) void qrep_kernel(RetArgs a) {
+  typedef typename Elt<DT>::type T;
+  __shared__ double part[4][128];
+  const Dims& D = a.D;
+  const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP], c0 = meta[META_CHUNK_START];
+  const int d = D.d, per = d / 64;
+  const int lane = threadIdx.x & 63, rg = threadIdx.x >> 6;
+  const T* Qb = reinterpret_cast<const T*>(a.q) + (size_t)bi * a.n_q * D.Hq * d;
+  T* out = reinterpret_cast<T*>(a.sc.qrep) + (size_t)p * a.Lp * d;
+  for (int qs = blockIdx.x; qs < nsp; qs += gridDim.x) {
+    const int sid = first + qs;
+    const int start = a.st.span_start[(size_t)slot * D.max_spans + sid] - c0;   // chunk-local
+    const int len = a.st.span_len[(size_t)slot * D.max_spans + sid];
+    double s0 = 0.0, s1 = 0.0;
+    for (int t = rg; t < len; t += 4) {
+      for (int g = 0; g < D.G; ++g) {
+        const T* row = Qb + ((size_t)(start + t) * D.Hq + h * D.G + g) * d + lane * per;
+        s0 += Elt<DT>::to_f64(row[0]);
+        if (per == 2) s1 += Elt<DT>::to_f64(row[1]);
+      }
+    }
+    part[rg][lane * per] = s0;
+    if (per == 2) part[rg][lane * per + 1] = s1;
+    __syncthreads();
+    if (threadIdx.x < d) {
+      const int c = threadIdx.x;
+      const double s = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
+      out[(size_t)qs * d + c] = Elt<DT>::from_f64(s / (double)len);
+    }
+    __syncthreads();
+  }
+}
+
+// ---- score_i = max_j Qrep_j . Krep_i for every stored span ----
+template <int DT>
+__global__ __launch_bounds__(256) void score_kernel(RetArgs a) {
+  typedef typename Elt<DT>::type T;
+  const Dims& D = a.D;
+  const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int n = meta[META_N_SPANS], nqs = meta[META_CHUNK_NSP];
+  const int d = D.d, per = d / 64;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const T* qrep = reinterpret_cast<const T*>(a.sc.qrep) + (size_t)p * a.Lp * d;
+  const T* krep = reinterpret_cast<const T*>(a.st.krep) + (size_t)slot * D.max_spans * d;
+  double* scores = a.st.scores + (size_t)slot * D.max_spans;
+  for (int i = blockIdx.x * 4 + wave; i < n; i += gridDim.x * 4) {
+    const double k0 = Elt<DT>::to_f64(krep[(size_t)i * d + lane * per]);
+    const double k1 = per == 2 ? Elt<DT>::to_f64(krep[(size_t)i * d + lane * per + 1]) : 0.0;
+    double best = -INFINITY;
+    for (int j = 0; j < nqs; ++j) {
+      double v = Elt<DT>::to_f64(qrep[(size_t)j * d + lane * per]) * k0;
+      if (per == 2) v += Elt<DT>::to_f64(qrep[(size_t)j * d + lane * per + 1]) * k1;
+      v = wave_sum_f64(v);
+      best = fmax(best, v);
+    }
+    if (lane == 0) scores[i] = best;
+  }
+}
+
+// Evicted part [a, b) of a stored span for a chunk starting at c0.
+__device__ __forceinline__ void clip_span(const Dims& D, int c0, int start, int len, int& a, int& b) {
+  const int ns = min(D.n_sink, c0);
+  const int ws = max(ns, c0 - D.window);
+  a = max(start, ns);
+  b = min(start + len, ws);
+}
+
+// Given the selection as a bit mask over span ids, writes the ascending id list, the token
+// list and their lengths. Called by all 1024 threads of the block.
+__device__ void emit_selection(const Dims& D, const DevState& st, int slot, const uint32_t* selmask,
+                               int n, int32_t* ids_out, int32_t* cnt_out) {
+  __shared__ int s_wcnt[16], s_wtok[16], s_base_cnt, s_base_tok;
+  int32_t* meta = st.meta + (size_t)slot * META_WORDS;
+  const int c0 = meta[META_CHUNK_START];
+  const int ns = min(D.n_sink, c0), ws = max(ns, c0 - D.window);
+  const int32_t* sstart = st.span_start + (size_t)slot * D.max_spans;
+  const int32_t* slen = st.span_len + (size_t)slot * D.max_spans;
+  int32_t* sel = st.sel_ids + (size_t)slot * D.sel_cap;
+  int32_t* list = st.tok_list + (size_t)slot * D.list_cap;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) { s_base_cnt = 0; s_base_tok = 0; }
+  for (int t = tid; t < ns; t += blockDim.x) list[t] = t;
+  __syncthreads();
+  for (int i0 = 0; i0 < n; i0 += blockDim.x) {
+    const int i = i0 + tid;
+    const bool f = i < n && ((selmask[i >> 5] >> (i & 31)) & 1u);
+    int a = 0, b = 0;
+    if (f) clip_span(D, c0, sstart[i], slen[i], a, b);
+    const int w = f ? max(b - a, 0) : 0;
+    // wave-level inclusive scans of (flag, tokens)
+    int cs = f ? 1 : 0, ts = w;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int c2 = __shfl_up(cs, o, 64), t2 = __shfl_up(ts, o, 64);
+      if (lane >= o) { cs += c2; ts += t2; }
+    }
+    if (lane == 63) { s_wcnt[wave] = cs; s_wtok[wave] = ts; }
+    __syncthreads();
+    int coff = s_base_cnt, toff = s_base_tok;
+    for (int w2 = 0; w2 < wave; ++w2) { coff += s_wcnt[w2]; toff += s_wtok[w2]; }
+    if (f) {
+      const int pos = coff + cs - 1;
+      if (pos < D.sel_cap) {
+        sel[pos] = i;
+        if (ids_out) ids_out[pos] = i;
+      }
+      int o = ns + toff + ts - w;
+      for (int t = a; t < b; ++t) {
+        if (o < D.list_cap) list[o] = t;
+        ++o;
+      }
+    }
+    __syncthreads();
+    if (tid == 0) {
+      int c = 0, t = 0;
+      for (int w2 = 0; w2 < 16; ++w2) { c += s_wcnt[w2]; t += s_wtok[w2]; }
+      s_base_cnt += c; s_base_tok += t;
+    }
+    __syncthreads();
+  }
+  const int n_sel = s_base_cnt, n_ret = s_base_tok;
+  const int n_win = c0 - ws;
+  const int len = ns + n_ret + n_win;
+  const bool fits = n_sel <= D.sel_cap && len <= D.list_cap;
+  if (fits) {
+    for (int t = tid; t < n_win; t += blockDim.x) list[ns + n_ret + t] = ws + t;
+    const int padded = min(D.list_cap, (len + ATT_BN - 1) / ATT_BN * ATT_BN);
+    for (int t = len + tid; t < padded; t += blockDim.x) list[t] = -1;
+  }
+  if (tid == 0) {
+    if (!fits) atomicCAS(&st.err[0], 0, LTRI_ECAPACITY);
+    meta[META_SEL_CNT] = fits ? n_sel : 0;
+    meta[META_LIST_LEN] = fits ? len : 0;
+    if (cnt_out) *cnt_out = fits ? n_sel : 0;
+  }
+}
+
+// ---- top spans under the count cap and the token budget ----
+constexpr int SEL_MAX_SPANS = 65536;
+
+__global__ __launch_bounds__(1024) void select_kernel(RetArgs a) {
+  __shared__ double t_score[1024];
+  __shared__ int t_clip[1024];
+  __shared__ uint32_t selmask[SEL_MAX_SPANS / 32];
+  const Dims& D = a.D;
+  const int p = blockIdx.x, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int n = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
+  const double* scores = a.st.scores + (size_t)slot * D.max_spans;
+  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
+  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
+  const int tid = threadIdx.x;
+  for (int w = tid; w < (n + 31) / 32; w += blockDim.x) selmask[w] = 0u;
+  __syncthreads();
+  for (int i0 = 0; i0 < n; i0 += blockDim.x) {
+    const int i = i0 + tid;
+    double si = 0.0;
+    int ci = 0;
+    if (i < n) {
+      int lo, hi;
+      clip_span(D, c0, sstart[i], slen[i], lo, hi);
+      ci = max(hi - lo, 0);
+      si = scores[i];
+    }
+    // rank and cumulated tokens of span i in the order (-score, id) among eligible spans
+    int rank = 0;
+    long long cum = ci;
+    for (int j0 = 0; j0 < n; j0 += 1024) {
+      __syncthreads();
+      const int j = j0 + tid;
+      if (j < n) {
+        int lo, hi;
+        clip_span(D, c0, sstart[j], slen[j], lo, hi);
+        t_clip[tid] = max(hi - lo, 0);
+        t_score[tid] = scores[j];
+      }
+      __syncthreads();
+      const int m = min(1024, n - j0);
+      if (ci > 0) {
+        for (int jj = 0; jj < m; ++jj) {
+          const int cj = t_clip[jj];
+          const double sj = t_score[jj];
+          const bool before = cj > 0 && (sj > si || (sj == si && (j0 + jj) < i));
+          if (before) { ++rank; cum += cj; }
+        }
+      }
+    }
+    const bool sel = ci > 0 && (D.k_max == 0 || rank < D.k_max) && (D.budget == 0 || cum <= D.budget);
+    if (sel) atomicOr(&selmask[i >> 5], 1u << (i & 31));
+  }
+  __syncthreads();
+  int32_t* ids_out = a.sel_ids_out ? a.sel_ids_out + (size_t)p * D.sel_cap : nullptr;
+  int32_t* cnt_out = a.sel_cnt_out ? a.sel_cnt_out + p : nullptr;
+  emit_selection(D, a.st, slot, selmask, n, ids_out, cnt_out);
+}
+
+// ---- caller-forced selection: ids already copied (ascending, unique) into sel_ids ----
+struct ForceArgs { Dims D; DevState st; int layer, seq, h, n_ids; };
+
+__global__ __launch_bounds__(1024) void force_list_kernel(ForceArgs a) {
+  __shared__ uint32_t selmask[SEL_MAX_SPANS / 32];
+  const Dims& D = a.D;
+  const int slot = slot_of(D, a.layer, a.seq, a.h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int n = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
+  const int tid = threadIdx.x;
+  for (int w = tid; w < (n + 31) / 32; w += blockDim.x) selmask[w] = 0u;
+  __syncthreads();
+  const int32_t* ids = a.st.sel_ids + (size_t)slot * D.sel_cap;
+  for (int k = tid; k < a.n_ids; k += blockDim.x) {
+    const int i = ids[k];
+    if (i >= 0 && i < n) {
+      int lo, hi;
+      clip_span(D, c0, a.st.span_start[(size_t)slot * D.max_spans + i],
+                a.st.span_len[(size_t)slot * D.max_spans + i], lo, hi);
+      if (hi > lo) atomicOr(&selmask[i >> 5], 1u << (i & 31));
+    }
+  }
+  __syncthreads();
+  emit_selection(D, a.st, slot, selmask, n, nullptr, nullptr);
+}
+
+hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, const void* q,
+                           int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
+                           int32_t* sel_ids_out, int32_t* sel_cnt_out, hipStream_t s) {
+  RetArgs a;
+  a.D = D; a.st = st; a.sc = sc; a.q = q; a.layer = layer; a.seq_count = seq_count; a.n_q = n_q;
+  a.Lp = (n_q + SEG_TB - 1) / SEG_TB * SEG_TB;
+  a.sel_ids_out = sel_ids_out; a.sel_cnt_out = sel_cnt_out; a.bp = bp;
+  const int P = seq_count * D.Hkv;
+  const bool bf = D.dtype == LTRI_BF16;
+  dim3 gq(n_q < 64 ? n_q : 64, P);
+  if (bf) qrep_kernel<LTRI_BF16><<<gq, 256, 0, s>>>(a);
+  else    qrep_kernel<LTRI_F32><<<gq, 256, 0, s>>>(a);
+  int gx = (span_bound + 3) / 4;
+  if (gx < 1) gx = 1;
+  if (gx > 256) gx = 256;
+  dim3 gs(gx, P);
+  if (bf) score_kernel<LTRI_BF16><<<gs, 256, 0, s>>>(a);
+  else    score_kernel<LTRI_F32><<<gs, 256, 0, s>>>(a);
+  select_kernel<<<P, 1024, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_force_list(const Dims& D, const DevState& st, int layer, int seq, int kv_head,
+                             int n_ids, hipStream_t s) {
+  ForceArgs a{D, st, layer, seq, kv_head, n_ids};
+  force_list_kernel<<<1, 1024, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace ltri

@@ -1,0 +1,622 @@
+// Step 1 on the device: segmentation of a chunk into spans (Sec. 3.2, Eq. 1-5; appendix
+// "NMS Input Filtration"; greedy NMS) and the spans' representative keys (Sec. 3.3.1).
+//
+// The chunk's L x L causal map M is never written to memory. It is cut into 64 x 64 tiles;
+// each tile is computed on the matrix cores from the chunk's K (and Q) rows whenever it is
+// needed, which is cheaper than storing L^2 doubles. The Triangle-Attention score (Eq. 4,
+// second form)
+//     S*[x][y] = sum_{i <= y} sum_{j >= x} M[i][j]
+// is a 2-D cumulative sum from the top-right corner. It is assembled per tile (I, J) from
+//   - the tile-local corner sum,
+//   - a row carry    RC[J][i] = sum of row i over the tiles to the right of J,
+//   - a column carry  A[I][x] = sum over all rows above block I of their sum from column x on.
+// Pass 1 emits per-tile row sums / suffix-scanned column sums / totals, pass 2 turns them into
+// the carries, pass 3 recomputes each tile, finishes S = S* - theta * n_h * tri(y - x + 1)
+// (Eq. 5) and reduces every anti-diagonal x + y = s inside the tile; pass 4 merges the tile
+// results per anti-diagonal, sorts the candidates, runs the greedy NMS and cuts the chunk.
+// All sums are fp64 in a fixed order, so the result is deterministic.
+#include "device_common.h"
+
+namespace ltri {
+
+struct SegArgs {
+  Dims D; DevState st; DevScratch sc;
+  const void* k_arena; const void* q_seg;
+  int layer; int batch_off; int n_new; int nb; int Lp; int ntiles;
+  BatchPos bp;
+};
+
+__device__ __forceinline__ void tile_decode(int t, int& I, int& J) {
+  int i = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
+  while ((i + 1) * (i + 2) / 2 <= t) ++i;
+  while (i * (i + 1) / 2 > t) --i;
+  I = i; J = t - i * (i + 1) / 2;
+}
+
+// 32 x 32 block of dot products on the matrix cores: acc[v] += sum_k A[r(v)][k] * B[c][k] with
+// c = lane % 32 and r(v) = 8 * (v / 4) + 4 * (lane / 32) + v % 4. arow / brow point at the
+// lane's own row (row lane % 32 of the A block / of the B block).
+template <int DT> struct TileDot;
+template <> struct TileDot<LTRI_BF16> {
+  __device__ static __forceinline__ void run(const uint16_t* arow, const uint16_t* brow, int d, int hf,
+                                             f32x16_t& acc) {
+    for (int kk = 0; kk < d; kk += 16) {
+      uint4 av = *reinterpret_cast<const uint4*>(arow + kk + 8 * hf);
+      uint4 bv = *reinterpret_cast<const uint4*>(brow + kk + 8 * hf);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av),
+                                                    __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
+    }
+  }
+};
+template <> struct TileDot<LTRI_F32> {
+  __device__ static __forceinline__ void run(const float* arow, const float* brow, int d, int hf,
+                                             f32x16_t& acc) {
+    for (int kk = 0; kk < d; kk += 2)
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(arow[kk + hf], brow[kk + hf], acc, 0, 0, 0);
+  }
+};
+
+// Leaves the head-summed map tile (rows I*64.., columns J*64..) in Ms[r * 65 + c] as doubles;
+// cells above the diagonal or outside the chunk are 0. Called by all 256 threads.
+template <int DT>
+__device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int J, double* Ms) {
+  typedef typename Elt<DT>::type T;
+  const Dims& D = a.D;
+  const int sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
+  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
+  const int L = a.n_new, d = D.d;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wi = wave >> 1, wj = wave & 1, hf = lane >> 5, l32 = lane & 31;
+  const int slot = slot_of(D, a.layer, seq, h);
+  const T* Kc = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * d;
+  const int irow = min(I * 64 + wi * 32 + l32, L - 1);   // lane's A row (clamped; masked below)
+  const int jrow = min(J * 64 + wj * 32 + l32, L - 1);   // lane's B row
+  const T* brow = Kc + (size_t)jrow * d;
+  const double scale = 1.0 / sqrt((double)d);
+  const int jcol = J * 64 + wj * 32 + l32;
+  double m[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) m[v] = 0.0;
+  if (a.q_seg == nullptr) {
+    f32x16_t acc = {0};
+    TileDot<DT>::run(Kc + (size_t)irow * d, brow, d, hf, acc);
+    if (D.seg_map == LTRI_MAP_LOGIT) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) m[v] = (double)acc[v] * scale;
+    } else {
+      const double* lse = a.sc.lse + ((size_t)p * 1) * a.Lp;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        int i = I * 64 + wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+        m[v] = exp((double)acc[v] * scale - lse[min(i, L - 1)]);
+      }
+    }
+  } else {
+    const T* Qb = reinterpret_cast<const T*>(a.q_seg) + (size_t)bi * L * D.Hq * d;
+    if (D.seg_map == LTRI_MAP_LOGIT) {
+      f32x16_t acc = {0};
+      for (int g = 0; g < D.G; ++g)
+        TileDot<DT>::run(Qb + ((size_t)irow * D.Hq + h * D.G + g) * d, brow, d, hf, acc);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) m[v] = (double)acc[v] * scale;
+    } else {
+      for (int g = 0; g < D.G; ++g) {
+        f32x16_t acc = {0};
+        TileDot<DT>::run(Qb + ((size_t)irow * D.Hq + h * D.G + g) * d, brow, d, hf, acc);
+        const double* lse = a.sc.lse + ((size_t)p * D.G + g) * a.Lp;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          int i = I * 64 + wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+          m[v] += exp((double)acc[v] * scale - lse[min(i, L - 1)]);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    int rl = wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+    int i = I * 64 + rl;
+    bool ok = (jcol <= i) && (i < L);
+    Ms[rl * 65 + wj * 32 + l32] = ok ? m[v] : 0.0;
+  }
+}
+
+// ---- pass 0 (SOFTMAX map only): log-sum-exp of every causal row of every head ----
+template <int DT>
+__global__ __launch_bounds__(256) void seg_row_lse_kernel(SegArgs a) {
+  typedef typename Elt<DT>::type T;
+  const Dims& D = a.D;
+  const int p = blockIdx.y, sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
+  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
+  const int L = a.n_new, d = D.d;
+  const int n_h = a.q_seg ? D.G : 1;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row_id = blockIdx.x * 4 + wave;            // (g, i) flattened
+  if (row_id >= n_h * L) return;
+  const int g = row_id / L, i = row_id - g * L;
+  const int slot = slot_of(D, a.layer, seq, h);
+  const T* Kc = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * d;
+  const T* qrow = a.q_seg ? reinterpret_cast<const T*>(a.q_seg) + (((size_t)bi * L + i) * D.Hq + h * D.G + g) * d
+                          : Kc + (size_t)i * d;
+  const double scale = 1.0 / sqrt((double)d);
+  double mx = -INFINITY, sm = 0.0;
+  for (int j = lane; j <= i; j += 64) {
+    const T* krow = Kc + (size_t)j * d;
+    double z = 0.0;
+    for (int c = 0; c < d; ++c) z += Elt<DT>::to_f64(qrow[c]) * Elt<DT>::to_f64(krow[c]);
+    z *= scale;
+    if (z > mx) { sm = sm * exp(mx - z) + 1.0; mx = z; } else { sm += exp(z - mx); }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    double omx = __shfl_xor(mx, o, 64), osm = __shfl_xor(sm, o, 64);
+    double nm = fmax(mx, omx);
+    double s1 = (mx == -INFINITY) ? 0.0 : sm * exp(mx - nm);
+    double s2 = (omx == -INFINITY) ? 0.0 : osm * exp(omx - nm);
+    mx = nm; sm = s1 + s2;
+  }
+  if (lane == 0) a.sc.lse[((size_t)p * n_h + g) * a.Lp + i] = mx + log(sm);
+}
+
+// ---- pass 1: per-tile row sums, suffix-scanned column sums, total ----
+template <int DT>
+__global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
+  __shared__ double Ms[64 * 65];
+  __shared__ double colsum[64];
+  const int p = blockIdx.y;
+  int I, J;
+  tile_decode(blockIdx.x, I, J);
+  compute_tile<DT>(a, p, I, J, Ms);
+  __syncthreads();
+  const int tid = threadIdx.x;
+  if (tid < 64) {
+    double s = 0.0;
+    for (int c = 0; c < 64; ++c) s += Ms[tid * 65 + c];
+    a.sc.rowsum[((size_t)p * a.nb + J) * a.Lp + I * 64 + tid] = s;
+  } else if (tid < 128) {
+    int c = tid - 64;
+    double s = 0.0;
+    for (int r = 0; r < 64; ++r) s += Ms[r * 65 + c];
+    colsum[c] = s;
+  }
+  __syncthreads();
+  if (tid < 64) {
+    double s = 0.0;
+    for (int c = 63; c >= tid; --c) s += colsum[c];
+    // csuf is indexed [I][x]: block-row I's contribution restricted to this column block
+    a.sc.csuf[((size_t)p * a.nb + I) * a.Lp + J * 64 + tid] = s;
+    if (tid == 0) a.sc.tsum[((size_t)p * a.nb + I) * a.nb + J] = s;
+  }
+}
+
+// ---- pass 2: carries ----
+__global__ __launch_bounds__(1024) void seg_carries_kernel(SegArgs a) {
+  __shared__ double TS[SEG_MAX_NB * SEG_MAX_NB];   // TS[I][J] = sum_{J < J' <= I} tsum[I][J']
+  const int p = blockIdx.x, nb = a.nb, Lp = a.Lp;
+  const double* rowsum = a.sc.rowsum + (size_t)p * nb * Lp;
+  const double* csuf = a.sc.csuf + (size_t)p * nb * Lp;
+  const double* tsum = a.sc.tsum + (size_t)p * nb * nb;
+  double* rcar = a.sc.rcar + (size_t)p * nb * Lp;
+  double* ccar = a.sc.ccar + (size_t)p * nb * Lp;
+  for (int i = threadIdx.x; i < Lp; i += blockDim.x) {
+    double run = 0.0;
+    for (int J = i / 64; J >= 0; --J) {
+      rcar[(size_t)J * Lp + i] = run;
+      run += rowsum[(size_t)J * Lp + i];
+    }
+  }
+  for (int I = threadIdx.x; I < nb; I += blockDim.x) {
+    double run = 0.0;
+    for (int J = I; J >= 0; --J) {
+      TS[I * SEG_MAX_NB + J] = run;
+      run += tsum[I * nb + J];
+    }
+  }
+  __syncthreads();
+  for (int x = threadIdx.x; x < Lp; x += blockDim.x) {
+    const int J = x / 64;
+    double run = 0.0;
+    for (int I = J; I < nb; ++I) {
+      ccar[(size_t)I * Lp + x] = run;
+      run += csuf[(size_t)I * Lp + x] + TS[I * SEG_MAX_NB + J];
+    }
+  }
+}
+
+// ---- pass 3: finish S inside each tile, reduce its anti-diagonals ----
+template <int DT>
+__global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
+  __shared__ double Ms[64 * 65];
+  __shared__ double rc[64];
+  const int p = blockIdx.y;
+  int I, J;
+  tile_decode(blockIdx.x, I, J);
+  compute_tile<DT>(a, p, I, J, Ms);
+  const int tid = threadIdx.x, L = a.n_new;
+  if (tid < 64) rc[tid] = a.sc.rcar[((size_t)p * a.nb + J) * a.Lp + I * 64 + tid];
+  __syncthreads();
+  if (tid < 64) {                       // row r: suffix sums towards the left
+    double run = 0.0;
+    for (int c = 63; c >= 0; --c) { run += Ms[tid * 65 + c]; Ms[tid * 65 + c] = run; }
+  }
+  __syncthreads();
+  if (tid < 64) {                       // column c: prefix sums downwards, then Eq. 5
+    const int x = J * 64 + tid;
+    const int n_h = a.q_seg ? a.D.G : 1;
+    const double th = (double)a.D.theta * (double)n_h;
+    double run = a.sc.ccar[((size_t)p * a.nb + I) * a.Lp + x];
+    for (int r = 0; r < 64; ++r) {
+      const int y = I * 64 + r;
+      run += Ms[r * 65 + tid] + rc[r];
+      const long long n = (long long)y - x + 1;
+      double s = run - th * (double)(n * (n + 1) / 2);
+      Ms[r * 65 + tid] = (x <= y && y < L) ? s : -INFINITY;
+    }
+  }
+  __syncthreads();
+  if (tid < 128) {                      // anti-diagonal xl + yl = tid of the tile
+    double best = -INFINITY;
+    int bx = -1;
+    if (tid < 127) {
+      const int lo = max(0, tid - 63), hi = min(63, tid);
+      for (int xl = lo; xl <= hi; ++xl) {
+        double v = Ms[(tid - xl) * 65 + xl];
+        if (v >= best && v > -INFINITY) { best = v; bx = J * 64 + xl; }   // ties: larger x
+      }
+    }
+    a.sc.pscore[((size_t)p * a.ntiles + blockIdx.x) * 128 + tid] = best;
+    a.sc.px[((size_t)p * a.ntiles + blockIdx.x) * 128 + tid] = bx;
+  }
+}
+
+// ---- pass 4: candidates -> sort -> greedy NMS -> cuts -> span table ----
+__device__ __forceinline__ bool nms_suppressed(int x, int y, int kx, int ky, float phi) {
+  const int inter = min(y, ky) - max(x, kx) + 1;
+  if (inter <= 0) return false;
+  const int uni = (y - x + 1) + (ky - kx + 1) - inter;
+  return (float)inter > __fmul_rn(phi, (float)uni);
+}
+
+__device__ __forceinline__ bool key_less(uint64_t a1, uint32_t a2, uint64_t b1, uint32_t b2) {
+  return (a1 < b1) || (a1 == b1 && a2 < b2);
+}
+
+// Appends the spans cut at cutlist[0..n_cuts) (chunk-local, first 0, last L) to the slot's table.
+__device__ void append_spans(const Dims& D, const DevState& st, int slot, int c0, int L,
+                             const int* cutlist, int n_cuts) {
+  int32_t* meta = st.meta + (size_t)slot * META_WORDS;
+  const int base = meta[META_N_SPANS];
+  const int n_sp = n_cuts - 1;
+  const bool fits = base + n_sp <= D.max_spans;
+  if (fits) {
+    for (int k = threadIdx.x; k < n_sp; k += blockDim.x) {
+      st.span_start[(size_t)slot * D.max_spans + base + k] = c0 + cutlist[k];
+      st.span_len[(size_t)slot * D.max_spans + base + k] = cutlist[k + 1] - cutlist[k];
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (!fits) atomicCAS(&st.err[0], 0, LTRI_ECAPACITY);
+    meta[META_N_SPANS] = fits ? base + n_sp : base;
+    meta[META_CHUNK_FIRST] = base;
+    meta[META_CHUNK_NSP] = fits ? n_sp : 0;
+    meta[META_CHUNK_START] = c0;
+    meta[META_CHUNK_LEN] = L;
+    meta[META_SEL_CNT] = 0;
+    meta[META_LIST_LEN] = 0;
+  }
+}
+
+__global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
+  __shared__ uint64_t k1[4096];
+  __shared__ uint32_t k2[4096];
+  __shared__ int s_ncand, s_nkept, s_wtot[16];
+  const Dims& D = a.D;
+  const int p = blockIdx.x, sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
+  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
+  const int L = a.n_new, nb = a.nb, tid = threadIdx.x;
+  const int n_diag = 2 * L - 1;
+  int n_sort = 64;
+  while (n_sort < n_diag) n_sort <<= 1;
+  if (tid == 0) { s_ncand = 0; s_nkept = 0; }
+  __syncthreads();
+  // merge the tiles' results per anti-diagonal (ties: larger x = shorter span); keep if S > 0
+  const double* pscore = a.sc.pscore + (size_t)p * a.ntiles * 128;
+  const int32_t* px = a.sc.px + (size_t)p * a.ntiles * 128;
+  for (int s = tid; s < n_sort; s += blockDim.x) {
+    double best = -INFINITY;
+    int bx = -1;
+    if (s < n_diag) {
+      const int b = s >> 6;
+      for (int bb = b; bb >= b - 1 && bb >= 0; --bb) {
+        const int sloc = s - 64 * bb;
+        if (sloc > 126) continue;
+        for (int J = max(0, bb - (nb - 1)); 2 * J <= bb; ++J) {
+          const int I = bb - J;
+          const int t = I * (I + 1) / 2 + J;
+          const double v = pscore[(size_t)t * 128 + sloc];
+          const int x = px[(size_t)t * 128 + sloc];
+          if (x >= 0 && (v > best || (v == best && x > bx))) { best = v; bx = x; }
+        }
+      }
+    }
+    if (bx >= 0 && best > 0.0) {
+      k1[s] = ~(uint64_t)__double_as_longlong(best);     // positive doubles order like their bits
+      k2[s] = ((uint32_t)bx << 16) | (uint32_t)(s - bx);
+      atomicAdd(&s_ncand, 1);
+    } else {
+      k1[s] = ~0ull;
+      k2[s] = 0xFFFFFFFFu;
+    }
+  }
+  __syncthreads();
+  // bitonic sort by (score descending, x ascending, y ascending)
+  for (int k = 2; k <= n_sort; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < n_sort; i += blockDim.x) {
+        const int ixj = i ^ j;
+        if (ixj > i) {
+          const uint64_t a1 = k1[i], b1 = k1[ixj];
+          const uint32_t a2 = k2[i], b2 = k2[ixj];
+          const bool up = (i & k) == 0;
+          const bool sw = up ? key_less(b1, b2, a1, a2) : key_less(a1, a2, b1, b2);
+          if (sw) { k1[i] = b1; k1[ixj] = a1; k2[i] = b2; k2[ixj] = a2; }
+        }
+      }
+      __syncthreads();
+    }
+  }
+  // greedy NMS by the first wavefront; the kept list overwrites k1 (scores are no longer needed)
+  volatile uint32_t* kept = reinterpret_cast<volatile uint32_t*>(k1);
+  if (tid < 64) {
+    const int lane = tid, ncand = s_ncand, max_keep = D.max_keep;
+    const float phi = D.phi;
+    int nkept = 0;
+    bool done = false;
+    for (int base = 0; base < ncand && !done; base += 64) {
+      const int idx = base + lane;
+      const bool valid = idx < ncand;
+      const uint32_t xy = valid ? k2[idx] : 0u;
+      const int x = (int)(xy >> 16), y = (int)(xy & 0xFFFFu);
+      bool alive = valid;
+      for (int q = 0; q < nkept; ++q) {
+        const uint32_t kk = kept[q];
+        if (alive && nms_suppressed(x, y, (int)(kk >> 16), (int)(kk & 0xFFFFu), phi)) alive = false;
+      }
+      uint64_t m = __ballot(alive);
+      while (m) {
+        const int b = __ffsll((unsigned long long)m) - 1;
+        const int bx = __shfl(x, b, 64), by = __shfl(y, b, 64);
+        if (lane == 0) kept[nkept] = ((uint32_t)bx << 16) | (uint32_t)by;
+        ++nkept;
+        if (max_keep > 0 && nkept >= max_keep) { done = true; break; }
+        if (alive && lane > b && nms_suppressed(x, y, bx, by, phi)) alive = false;
+        const uint64_t upto = (b == 63) ? ~0ull : ((2ull << b) - 1ull);
+        m = __ballot(alive) & ~upto;
+      }
+    }
+    if (lane == 0) s_nkept = nkept;
+  }
+  __syncthreads();
+  // cuts: 0, L and both ends of every kept interval
+  uint8_t* flags = reinterpret_cast<uint8_t*>(k2);
+  int* cutlist = reinterpret_cast<int*>(reinterpret_cast<uint8_t*>(k2) + 2304);
+  const int nkept = s_nkept;
+  uint32_t my_kept[4];
+  // k1 (kept list) and k2 (flags) are distinct arrays, so reading kept while writing flags is safe
+  for (int i = tid; i <= L; i += blockDim.x) flags[i] = (i == 0 || i == L) ? 1 : 0;
+  __syncthreads();
+  for (int q = tid; q < nkept; q += blockDim.x) {
+    const uint32_t kk = kept[q];
+    flags[kk >> 16] = 1;
+    flags[(kk & 0xFFFFu) + 1] = 1;
+  }
+  (void)my_kept;
+  __syncthreads();
+  // enumerate the set flags in increasing order: each wave scans a contiguous segment
+  const int lane = tid & 63, wave = tid >> 6;
+  const int seg = (L + 1 + 15) / 16, s0 = wave * seg, s1 = min(L + 1, s0 + seg);
+  int cnt = 0;
+  for (int i0 = s0; i0 < s1; i0 += 64) {
+    const int i = i0 + lane;
+    const bool f = i < s1 && flags[i];
+    cnt += __popcll(__ballot(f));
+  }
+  if (lane == 0) s_wtot[wave] = cnt;
+  __syncthreads();
+  int off = 0, total = 0;
+  for (int w = 0; w < 16; ++w) { if (w < wave) off += s_wtot[w]; total += s_wtot[w]; }
+  for (int i0 = s0; i0 < s1; i0 += 64) {
+    const int i = i0 + lane;
+    const bool f = i < s1 && flags[i];
+    const uint64_t m = __ballot(f);
+    if (f) cutlist[off + __popcll(m & ((1ull << lane) - 1ull))] = i;
+    off += __popcll(m);
+  }
+  __syncthreads();
+  append_spans(D, a.st, slot_of(D, a.layer, seq, h), c0, L, cutlist, total);
+}
+
+// ---- chunks of one token: a single span, its key is its own representative ----
+struct SingleArgs { Dims D; DevState st; const void* k_arena; int layer; int seq_count; BatchPos bp; };
+
+template <int DT>
+__global__ __launch_bounds__(64) void append_single_kernel(SingleArgs a) {
+  typedef typename Elt<DT>::type T;
+  const Dims& D = a.D;
+  const int p = blockIdx.x, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
+  const int slot = slot_of(D, a.layer, seq, h);
+  int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int base = meta[META_N_SPANS];
+  const bool fits = base + 1 <= D.max_spans;
+  if (fits) {
+    const T* krow = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * D.d;
+    T* rep = reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + base) * D.d;
+    for (int c = threadIdx.x; c < D.d; c += 64) rep[c] = krow[c];
+  }
+  if (threadIdx.x == 0) {
+    if (fits) {
+      a.st.span_start[(size_t)slot * D.max_spans + base] = c0;
+      a.st.span_len[(size_t)slot * D.max_spans + base] = 1;
+    } else {
+      atomicCAS(&a.st.err[0], 0, LTRI_ECAPACITY);
+    }
+    meta[META_N_SPANS] = fits ? base + 1 : base;
+    meta[META_CHUNK_FIRST] = base;
+    meta[META_CHUNK_NSP] = fits ? 1 : 0;
+    meta[META_CHUNK_START] = c0;
+    meta[META_CHUNK_LEN] = 1;
+    meta[META_SEL_CNT] = 0;
+    meta[META_LIST_LEN] = 0;
+  }
+}
+
+// ---- caller-supplied boundaries ----
+struct BoundsArgs { Dims D; DevState st; const int32_t* bounds; int layer, seq, c0, n_new; };
+
+__global__ __launch_bounds__(256) void append_bounds_kernel(BoundsArgs a) {
+  const Dims& D = a.D;
+  const int h = blockIdx.x;
+  const int32_t* cut = a.bounds + (size_t)h * (D.chunk_max + 1);
+  const int n_cuts = a.bounds[(size_t)D.Hkv * (D.chunk_max + 1) + h];
+  append_spans(D, a.st, slot_of(D, a.layer, a.seq, h), a.c0, a.n_new, cut, n_cuts);
+}
+
+// ---- representative keys: mean of the span's K rows, rounded once to the dtype ----
+struct RepArgs { Dims D; DevState st; const void* k_arena; int layer; int seq_count; BatchPos bp; };
+
+template <int DT>
+__global__ __launch_bounds__(256) void rep_keys_kernel(RepArgs a) {
+  typedef typename Elt<DT>::type T;
+  __shared__ double part[4][128];
+  const Dims& D = a.D;
+  const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP];
+  const int d = D.d, per = d / 64;                      // 1 or 2 columns per lane
+  const int lane = threadIdx.x & 63, rg = threadIdx.x >> 6;
+  const T* Kb = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot);
+  for (int q = blockIdx.x; q < nsp; q += gridDim.x) {
+    const int sid = first + q;
+    const int start = a.st.span_start[(size_t)slot * D.max_spans + sid];
+    const int len = a.st.span_len[(size_t)slot * D.max_spans + sid];
+    double s0 = 0.0, s1 = 0.0;
+    for (int t = rg; t < len; t += 4) {
+      const T* row = Kb + (size_t)(start + t) * d + lane * per;
+      s0 += Elt<DT>::to_f64(row[0]);
+      if (per == 2) s1 += Elt<DT>::to_f64(row[1]);
+    }
+    part[rg][lane * per] = s0;
+    if (per == 2) part[rg][lane * per + 1] = s1;
+    __syncthreads();
+    if (threadIdx.x < d) {
+      const int c = threadIdx.x;
+      const double s = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
+      T* rep = reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + sid) * d;
+      rep[c] = Elt<DT>::from_f64(s / (double)len);
+    }
+    __syncthreads();
+  }
+}
+
+// ---- copies of a caller's chunk into the arenas ----
+struct CopyArgs { Dims D; void* k_arena; void* v_arena; const void* k_chunk; const void* v_chunk;
+                  int layer; int seq_count; int n_new; BatchPos bp; };
+
+__global__ __launch_bounds__(256) void copy_chunk_kernel(CopyArgs a) {
+  const Dims& D = a.D;
+  const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const size_t row_bytes = (size_t)D.d * D.elt;
+  const size_t n16 = (size_t)a.n_new * row_bytes / 16;
+  const size_t dst_off = (arena_off(D, slot) + (size_t)a.bp.c0[bi] * D.d) * D.elt;
+  const size_t src_off = (size_t)p * a.n_new * row_bytes;
+  const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.k_chunk) + src_off);
+  const uint4* vs = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.v_chunk) + src_off);
+  uint4* kd = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.k_arena) + dst_off);
+  uint4* vd = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.v_arena) + dst_off);
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) {
+    kd[i] = ks[i];
+    vd[i] = vs[i];
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* p, size_t n16) {
+  const uint4 z = {0, 0, 0, 0};
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x)
+    p[i] = z;
+}
+
+// ============================================================================ launchers
+hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  const int blocks = (int)((n16 + 255) / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+  fill_zero_kernel<<<blocks, 256, 0, s>>>(reinterpret_cast<uint4*>(p), n16);
+  return hipGetLastError();
+}
+
+hipError_t launch_copy_chunk(const Dims& D, void* k_arena, void* v_arena, const void* k_chunk,
+                             const void* v_chunk, int layer, const BatchPos& bp, int seq_count,
+                             int n_new, hipStream_t s) {
+  CopyArgs a{D, k_arena, v_arena, k_chunk, v_chunk, layer, seq_count, n_new, bp};
+  const size_t n16 = (size_t)n_new * D.d * D.elt / 16;
+  const int bx = (int)((n16 + 255) / 256 < 64 ? (n16 + 255) / 256 : 64);
+  copy_chunk_kernel<<<dim3(bx > 0 ? bx : 1, seq_count * D.Hkv), 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& sc, const void* k_arena,
+                          const void* q_seg, int layer, const BatchPos& bp, int batch_off, int seq_count,
+                          int n_new, hipStream_t s) {
+  SegArgs a;
+  a.D = D; a.st = st; a.sc = sc; a.k_arena = k_arena; a.q_seg = q_seg; a.layer = layer;
+  a.batch_off = batch_off; a.n_new = n_new;
+  a.nb = (n_new + SEG_TB - 1) / SEG_TB; a.Lp = a.nb * SEG_TB; a.ntiles = a.nb * (a.nb + 1) / 2;
+  a.bp = bp;
+  const int P = seq_count * D.Hkv;
+  const bool bf = D.dtype == LTRI_BF16;
+  if (D.seg_map == LTRI_MAP_SOFTMAX) {
+    const int n_h = q_seg ? D.G : 1;
+    dim3 g0((n_h * n_new + 3) / 4, P);
+    if (bf) seg_row_lse_kernel<LTRI_BF16><<<g0, 256, 0, s>>>(a);
+    else    seg_row_lse_kernel<LTRI_F32><<<g0, 256, 0, s>>>(a);
+  }
+  dim3 gt(a.ntiles, P);
+  if (bf) seg_tile_sums_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
+  else    seg_tile_sums_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
+  seg_carries_kernel<<<P, 1024, 0, s>>>(a);
+  if (bf) seg_tile_scan_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
+  else    seg_tile_scan_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
+  seg_select_kernel<<<P, 1024, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_append_single(const Dims& D, const DevState& st, const void* k_arena, int layer,
+                                const BatchPos& bp, int seq_count, hipStream_t s) {
+  SingleArgs a{D, st, k_arena, layer, seq_count, bp};
+  if (D.dtype == LTRI_BF16) append_single_kernel<LTRI_BF16><<<seq_count * D.Hkv, 64, 0, s>>>(a);
+  else                      append_single_kernel<LTRI_F32><<<seq_count * D.Hkv, 64, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_append_bounds(const Dims& D, const DevState& st, const DevScratch& sc, int layer,
+                                int seq, int c0, int n_new, hipStream_t s) {
+  BoundsArgs a{D, st, sc.bounds, layer, seq, c0, n_new};
+  append_bounds_kernel<<<D.Hkv, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_rep_keys(const Dims& D, const DevState& st, const void* k_arena, int layer,
+                           const BatchPos& bp, int seq_count, int n_new, hipStream_t s) {
+  RepArgs a{D, st, k_arena, layer, seq_count, bp};
+  const int gx = n_new < 64 ? n_new : 64;
+  dim3 g(gx, seq_count * D.Hkv);
+  if (D.dtype == LTRI_BF16) rep_keys_kernel<LTRI_BF16><<<g, 256, 0, s>>>(a);
+  else                      rep_keys_kernel<LTRI_F32><<<g, 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+}  // namespace ltri

@@ -1,0 +1,123 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header
+declares, sizes its buffers, and rejects bad arguments / out-of-order calls (dry context)."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2412_04757_amd import (LtriConfig, LtriContext, LtriError, config_from_workload,
+                                  load_library, library_path, EXPORTED_SYMBOLS)
+from workloads import CONFIGS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ltri.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ltri_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = load_library()
+    declared = _declared_symbols()
+    assert len(declared) >= 20
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert sorted(EXPORTED_SYMBOLS) == declared
+    assert b"gfx950" in lib.ltri_version()
+
+
+def test_workspace_sizes_and_bad_configs():
+    lib = load_library()
+    for name in ("cfg1", "cfg2", "cfg3"):
+        cfg = config_from_workload(CONFIGS[name], theta=1.0)
+        sb, cb = C.c_size_t(), C.c_size_t()
+        assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == 0
+        assert sb.value > 0 and cb.value > 0 and sb.value % 256 == 0
+    # cfg4: 32 layers of index memory stay modest next to the KV arenas
+    cfg = config_from_workload(CONFIGS["cfg4"], theta=1.0)
+    sb, cb = C.c_size_t(), C.c_size_t()
+    assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == 0
+    kv = 2 * 32 * 8 * 262144 * 128 * 2
+    assert sb.value < kv / 8
+    bad = [dict(head_dim=96), dict(dtype=7), dict(n_kv_heads=3), dict(chunk_max=4096), dict(chunk_max=0),
+           dict(max_tokens=0), dict(seg_map=3), dict(phi=-0.1), dict(window=-1), dict(n_layers=0),
+           dict(max_spans=70000)]
+    for kw in bad:
+        cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0)
+        for k, v in kw.items():
+            setattr(cfg, k, v)
+        assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == -1, kw
+    cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0)
+    cfg.dtype = 1            # bf16 with head_dim 64 is not supported
+    assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == -1
+    out = C.c_void_p()
+    assert lib.ltri_create(C.byref(cfg), None, None, None, None, None, C.byref(out)) == -1
+    assert lib.ltri_strerror(-3).decode().startswith("token or span capacity")
+
+
+class _FakeQ:
+    """Stands in for a device tensor in dry mode: only the shape and a non-null address are used."""
+    def __init__(self, n_q):
+        self.shape = (1, n_q, 4, 64)
+
+    def data_ptr(self):
+        return 4096
+
+
+def test_call_order_and_limits_in_dry_mode():
+    cfg = config_from_workload(CONFIGS["cfg1"], max_tokens=1000, theta=1.0)
+    ctx = LtriContext(cfg, None, dry=True)
+    with pytest.raises(LtriError) as e:
+        ctx.retrieve(0, 0, 1, _FakeQ(256))
+    assert e.value.status == -2                      # retrieve before any append
+    with pytest.raises(LtriError) as e:
+        ctx.append_chunk(0, 0, 1, 257)
+    assert e.value.status == -1                      # n_new > chunk_max
+    with pytest.raises(LtriError) as e:
+        ctx.append_chunk(0, 0, 1, 0)
+    assert e.value.status == -1
+    with pytest.raises(LtriError) as e:
+        ctx.append_chunk(1, 0, 1, 16)
+    assert e.value.status == -1                      # layer out of range
+    with pytest.raises(LtriError) as e:
+        ctx.append_chunk(0, 0, 2, 16)
+    assert e.value.status == -1                      # sequence range
+    ctx.append_chunk(0, 0, 1, 256)
+    assert ctx.token_count(0, 0) == 256
+    with pytest.raises(LtriError) as e:
+        ctx.attend(0, 0, 1, _FakeQ(256))
+    assert e.value.status == -2                      # attend before retrieve
+    with pytest.raises(LtriError) as e:
+        ctx.retrieve(0, 0, 1, _FakeQ(128))
+    assert e.value.status == -2                      # n_q differs from the appended chunk
+    ctx.retrieve(0, 0, 1, _FakeQ(256))
+    ctx.attend(0, 0, 1, _FakeQ(256))
+    ctx.append_chunk(0, 0, 1, 256)
+    with pytest.raises(LtriError) as e:
+        ctx.attend(0, 0, 1, _FakeQ(256))             # the selection belongs to the previous chunk
+    assert e.value.status == -2
+    ctx.force_selection(0, 0, 0, [3, 1, 1])
+    ctx.attend(0, 0, 1, _FakeQ(256))                 # one KV head: forced selection is enough
+    ctx.append_chunk(0, 0, 1, 256)
+    with pytest.raises(LtriError) as e:
+        ctx.append_chunk(0, 0, 1, 256)               # 768 + 256 > 1000
+    assert e.value.status == -3 and "max_tokens" in str(e.value)
+    ctx.append_chunk(0, 0, 1, 232)
+    assert ctx.token_count(0, 0) == 1000
+    ctx.reset(0)
+    assert ctx.token_count(0, 0) == 0
+    with pytest.raises(LtriError) as e:
+        ctx.span_count(0, 0, 0)                      # no device data in a dry context
+    assert e.value.status == -2
+    # caller-supplied boundaries are validated on the host
+    for bad in ([0, 5, 5, 16], [1, 16], [0, 8], [0, 16, 8]):
+        with pytest.raises(LtriError) as e:
+            ctx.append_chunk_with_spans(0, 0, 16, [np.array(bad)])
+        assert e.value.status == -1, bad
+    ctx.append_chunk_with_spans(0, 0, 16, [np.array([0, 4, 16])])
+    assert ctx.token_count(0, 0) == 16
+    ctx.close()
