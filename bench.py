@@ -1,0 +1,225 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-chunk streaming sparse-attention step on one MI355X.
+
+One "step" streams a whole synthetic context through one attention layer: for every chunk,
+append (segment + index) -> retrieve (score + select) -> attend.  Inputs are resident in HBM
+before the timed region starts.  Prints one JSON line:
+  metric  = prefill tokens/s per layer (the context length is in config.workload),
+  roofline = the attend kernel's achieved bf16 matrix-core rate against the published peak,
+  cpu_baseline = the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix rate
+PEAK_HBM_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def attend_flops(w, n_q, list_lens):
+    """Algorithmic work of one attend launch: 4 * d * (group size) * n_q * (N_att + (n_q + 1) / 2)
+    per KV head, N_att = that head's context-list length; causal part counted at half."""
+    g = w.n_q_heads // w.n_kv_heads
+    return sum(4.0 * w.head_dim * g * n_q * (n + (n_q + 1) / 2.0) for n in list_lens)
+
+
+def cpu_baseline(w, K, V, Q, bounds, theta, rows_sampled=128):
+    """The oracle, as it stands, on the last (full-context) chunk of the workload."""
+    import numpy as np
+    import torch
+    from oracle import ltri_oracle as O
+    T, L = w.context, w.chunk
+    t_setup = time.time()
+    Kn = K.double().cpu().numpy()
+    Vn = V.double().cpu().numpy()
+    cfg = O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.n_sink, w.window,
+                         k_max=w.k_max, budget_tokens=w.budget_tokens, seg_map=O.MAP_LOGIT,
+                         theta=float(np.float32(theta)), phi=0.0)
+    st = O.OracleStream(cfg, Kn, Vn)
+    # history: the planted boundaries (cut at chunk edges) stand in for the earlier chunks' spans;
+    # building them is not part of the timed chunk
+    for c0 in range(0, T - L, L):
+        b = [np.asarray(sorted({0, L} | {int(x - c0) for x in bounds[h][(bounds[h] > c0) & (bounds[h] < c0 + L)]}),
+                        np.int64) for h in range(w.n_kv_heads)]
+        st.append_chunk(L, bounds=b)
+    qn = Q[T - L:].double().cpu().numpy()
+    log(f"[cpu_baseline] setup {time.time() - t_setup:.1f}s; timing the last chunk")
+    t0 = time.time()
+    st.append_chunk(L)
+    t1 = time.time()
+    st.retrieve(qn)
+    t2 = time.time()
+    rows = list(range(0, L, L // rows_sampled))[:rows_sampled]
+    st.attend(qn, rows=rows)
+    t3 = time.time()
+    t_att = (t3 - t2) * (L / len(rows))
+    total = (t1 - t0) + (t2 - t1) + t_att
+    try:
+        import threadpoolctl
+        cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    log(f"[cpu_baseline] segment {t1 - t0:.2f}s retrieve {t2 - t1:.2f}s attend({len(rows)} rows) {t3 - t2:.2f}s "
+        f"-> {total:.1f}s per chunk")
+    return {"value": L / total, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"last chunk of {w.name} (tokens {T - L}..{T}, full context): segmentation and retrieval of all "
+                      f"{w.n_kv_heads} KV heads timed whole, attention timed on {len(rows)} of {L} query rows x "
+                      f"{w.n_q_heads} heads and scaled by {L // len(rows)}; earlier chunks' spans taken from the planted "
+                      f"boundaries (setup, untimed); fp64 numpy"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--context", type=int, default=0, help="override the context length (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path has no collective; see DESIGN.md for how it "
+              "would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2412_04757_amd import LtriContext, config_from_workload
+    from workloads import CONFIGS, planted_stream, theta_default
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    w = CONFIGS[args.workload]
+    if args.context:
+        from dataclasses import replace
+        w = replace(w, context=args.context)
+    T, L = w.context, w.chunk
+    n_chunks = T // L
+    theta = theta_default(w.head_dim)
+    log(f"[bench] workload {w.name}: T={T} L={L} Hq={w.n_q_heads} Hkv={w.n_kv_heads} d={w.head_dim} {w.dtype}")
+    t0 = time.time()
+    K, V, Q, bounds = planted_stream(w, args.seed, device="cuda:0")
+    torch.cuda.synchronize()
+    log(f"[bench] inputs generated in {time.time() - t0:.1f}s")
+    cfg = config_from_workload(w, theta=theta, n_layers=1, n_seqs=1)
+    ctx = LtriContext(cfg, dev)
+    ka, va = ctx.arena_views()
+    ka[0, 0].copy_(K)
+    va[0, 0].copy_(V)
+    out = torch.empty((1, L, w.n_q_heads, w.head_dim), dtype=w.torch_dtype, device=dev)
+    qs = [Q[c * L:(c + 1) * L] for c in range(n_chunks)]          # contiguous views
+
+    list_lens = []          # per chunk: context-list length of every KV head
+
+    def one_stream(record_lens=False, events=None):
+        ctx.reset(0)
+        for c in range(n_chunks):
+            ctx.append_chunk(0, 0, 1, L)
+            ctx.retrieve(0, 0, 1, qs[c])
+            if events is not None:
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+            ctx.attend(0, 0, 1, qs[c], out=out)
+            if events is not None:
+                e1.record()
+                events.append((e0, e1))
+            if record_lens:
+                list_lens.append([len(ctx.get_token_list(0, 0, h)) for h in range(w.n_kv_heads)])
+
+    # warmup (the first pass also records the list lengths, which need a synchronising read-back)
+    one_stream(record_lens=True)
+    for _ in range(max(0, args.warmup - 1)):
+        one_stream()
+    status = ctx.sync_status()
+    if status != 0:
+        print(f"bench.py: device status {status}", file=sys.stderr)
+        sys.exit(1)
+    n_spans = [ctx.span_count(0, 0, h) for h in range(w.n_kv_heads)]
+    log(f"[bench] spans per KV head: {n_spans}; last chunk list lengths {list_lens[-1]}")
+
+    events = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_stream(events=events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    value = T * args.steps / elapsed
+
+    # attend kernel: algorithmic flops per launch / measured launch duration
+    att_ms = [e0.elapsed_time(e1) for e0, e1 in events]
+    flops = [attend_flops(w, L, list_lens[i % n_chunks]) for i in range(len(events))]
+    tot_flops, tot_ms = sum(flops), sum(att_ms)
+    achieved = tot_flops / (tot_ms * 1e-3) / 1e12
+    last = [i for i in range(len(events)) if i % n_chunks == n_chunks - 1]
+    last_tflops = sum(flops[i] for i in last) / (sum(att_ms[i] for i in last) * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "attend_bf16_kernel", "achieved": round(achieved, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                "traffic": None,
+                "avg_launch_us": round(tot_ms / len(events) * 1e3, 1),
+                "full_context_launch_us": round(sum(att_ms[i] for i in last) / len(last) * 1e3, 1),
+                "full_context_achieved": round(last_tflops, 2)}
+
+    # the gather on its own (HBM-bound): context set of the last chunk into packed buffers
+    kp = torch.empty((w.n_kv_heads, ctx.list_cap, w.head_dim), dtype=w.torch_dtype, device=dev)
+    vp = torch.empty_like(kp)
+    for _ in range(3):
+        ctx.gather_pack(0, 0, kp, vp)
+    g0 = torch.cuda.Event(enable_timing=True)
+    g1 = torch.cuda.Event(enable_timing=True)
+    reps = 20
+    g0.record()
+    for _ in range(reps):
+        ctx.gather_pack(0, 0, kp, vp)
+    g1.record()
+    torch.cuda.synchronize()
+    g_us = g0.elapsed_time(g1) / reps * 1e3
+    elt = 2 if w.dtype == "bf16" else 4
+    g_bytes = sum(list_lens[-1]) * w.head_dim * elt * 2 * 2            # K and V, read + write
+    gather = {"bound": "hbm", "kernel": "gather_pack_kernel", "achieved": round(g_bytes / g_us / 1e3, 1),
+              "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g_bytes / g_us / 1e3 / PEAK_HBM_GBPS, 4),
+              "launch_us": round(g_us, 2), "bytes": g_bytes}
+
+    # share of the step spent outside attend (append + retrieve + launch gaps)
+    other_ms = ms_per_step - tot_ms / args.steps
+    log(f"[bench] {ms_per_step:.2f} ms per stream; attend {tot_ms / args.steps:.2f} ms, rest {other_ms:.2f} ms")
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, K, V, Q, bounds, theta)
+
+    result = {
+        "metric": "prefill tokens/s per layer", "value": round(value, 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: Llama-3-8B layer shape, {w.n_q_heads} query / {w.n_kv_heads} KV heads, "
+                               f"head_dim {w.head_dim}, {w.dtype}, context {T} streamed in chunks of {L}, "
+                               f"{w.n_sink} sink tokens, window {w.window}, retrieval budget {w.budget_tokens} tokens, "
+                               f"planted-span keys ({w.len_dist} lengths in [{w.len_lo},{w.len_hi}]), seed {args.seed}",
+                   "step": "one full stream through one layer (append + retrieve + attend per chunk)",
+                   "seg_map": "logit", "theta": theta, "phi": 0.0},
+        "roofline": roofline, "gather": gather, "cpu_baseline": cpu,
+        "breakdown_ms": {"attend": round(tot_ms / args.steps, 3), "append_retrieve_and_gaps": round(other_ms, 3)},
+    }
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
