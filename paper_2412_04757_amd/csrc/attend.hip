@@ -22,8 +22,13 @@ struct AttArgs {
 constexpr int KS_STRIDE = 136;   // bf16 elements per K row in LDS (128 + 8 pad)
 constexpr int VT_STRIDE = 72;    // bf16 elements per V^T row in LDS (64 keys + 8 pad)
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // NQB = 32-query blocks per wavefront.
@@ -156,18 +161,20 @@ __global__ __launch_bounds__(256) void attend_bf16_kernel(AttArgs a) {
                                                               s[kb][nq], 0, 0, 0);
       }
     }
-    // ---- masks ----
+    // ---- masks (only tiles that reach past the wave's first row, or the ragged last list tile) ----
     if (is_chunk) {
+      if (k0 + 63 > r0) {
 #pragma unroll
-      for (int nq = 0; nq < NQB; ++nq) {
-        const int qi = r0 + nq * 32 + l32;
+        for (int nq = 0; nq < NQB; ++nq) {
+          const int qi = r0 + nq * 32 + l32;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+          for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int kp = k0 + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-            if (kp > qi) s[kb][nq][v] = -INFINITY;
-          }
+            for (int v = 0; v < 16; ++v) {
+              const int kp = k0 + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+              if (kp > qi) s[kb][nq][v] = -INFINITY;
+            }
+        }
       }
     } else if (t == n_ctx_tiles - 1 && (list_len & 63)) {
       const int nvalid = list_len - t * 64;
@@ -185,21 +192,25 @@ __global__ __launch_bounds__(256) void attend_bf16_kernel(AttArgs a) {
     uint4 pf[NQB][2][2];
 #pragma unroll
     for (int nq = 0; nq < NQB; ++nq) {
-      float mx = -INFINITY;
+      float mx = s[0][nq][0];
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int v = 1; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[0][nq][v]), s[0][nq][(v + 1) & 15]);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][nq][v]);
+      for (int v = 0; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[1][nq][v]), s[1][nq][v + 1]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float m_new = fmaxf(m_run[nq], mx * sc);
-      const float alpha = exp2f(m_run[nq] - m_new);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
+      const bool changed = m_new != m_run[nq];
       m_run[nq] = m_new;
       float ps = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         float pv[16];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { pv[v] = exp2f(s[kb][nq][v] * sc - m_new); ps += pv[v]; }
+        for (int v = 0; v < 16; ++v) {
+          pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][v], sc, -m_new));
+          ps += pv[v];
+        }
 #pragma unroll
         for (int a2 = 0; a2 < 2; ++a2) {
           uint4 u;
@@ -211,10 +222,12 @@ __global__ __launch_bounds__(256) void attend_bf16_kernel(AttArgs a) {
         }
       }
       l_run[nq] = l_run[nq] * alpha + ps;
+      if (__any(changed)) {                 // the running maximum rarely moves after the first tiles
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
+        for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[mb][nq][v] *= alpha;
+          for (int v = 0; v < 16; ++v) o[mb][nq][v] *= alpha;
+      }
     }
     // ---- O^T += V^T P^T ----
 #pragma unroll
@@ -224,6 +237,296 @@ __global__ __launch_bounds__(256) void attend_bf16_kernel(AttArgs a) {
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
           const uint4 vf = *reinterpret_cast<const uint4*>(&Vt[(mb * 32 + l32) * VT_STRIDE + kb * 32 + a2 * 16 + hf * 8]);
+#pragma unroll
+          for (int nq = 0; nq < NQB; ++nq)
+            o[mb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf),
+                                                                __builtin_bit_cast(bf16x8_t, pf[nq][kb][a2]),
+                                                                o[mb][nq], 0, 0, 0);
+        }
+  }
+  // ---- epilogue ----
+  uint16_t* Ob = reinterpret_cast<uint16_t*>(a.out) + (size_t)bi * L * D.Hq * d;
+#pragma unroll
+  for (int nq = 0; nq < NQB; ++nq) {
+    const int qi = r0 + nq * 32 + l32;
+    const float lt = l_run[nq] + __shfl_xor(l_run[nq], 32, 64);
+    if (qi < L) {
+      const float inv = 1.f / lt;
+      uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4) {
+          uint2 u;
+          u.x = pack_bf16x2(o[mb][nq][4 * a4 + 0] * inv, o[mb][nq][4 * a4 + 1] * inv);
+          u.y = pack_bf16x2(o[mb][nq][4 * a4 + 2] * inv, o[mb][nq][4 * a4 + 3] * inv);
+          *reinterpret_cast<uint2*>(orow + mb * 32 + 8 * a4 + 4 * hf) = u;
+        }
+      if (a.lse && hf == 0)
+        a.lse[((size_t)bi * L + qi) * D.Hq + head] = (m_run[nq] + log2f(lt)) * 0.6931471805599453f;
+    }
+  }
+}
+
+// ---- bf16 kernel, LDS-DMA version ----
+// K and V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane, no
+// registers in between) through a ring of NS stages, so several tiles are in flight while one is
+// being consumed and a single barrier per tile suffices. Both tiles keep the row-major [key][d]
+// layout of the arena; inside a 256-byte row the sixteen 16-byte pieces are permuted (XOR with a
+// function of the row) so that the fragment reads are free of bank conflicts; the permutation is
+// applied by choosing which piece each lane fetches. V^T fragments (A operand of
+// O^T = V^T P^T) are read with the transposing LDS load: lane j of a 16-lane group passes the
+// address of 4 consecutive d-columns of key row0 + j / 4, lane i receives column i of keys
+// row0 .. row0 + 3.
+// The DMA is issued through inline assembly because the compiler would otherwise wait for ALL
+// outstanding DMA before any LDS read; completion is awaited by hand with s_waitcnt vmcnt(n),
+// n = DMA loads issued later than the tile about to be used (8 per tile and lane).
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int DMA_NS = 4;                       // ring stages
+constexpr int DMA_STAGE_BYTES = 32768;          // K tile 16 KB + V tile 16 KB
+
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_wave_base), "v"(gptr) : "m0");
+}
+
+__device__ __forceinline__ void dma4(const void* gptr, uint32_t lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_wave_base), "v"(gptr) : "m0");
+}
+
+constexpr int TOK_SLOTS = 8;                    // ring of 64-entry token tiles
+constexpr int TOK_AHEAD = 6;                    // token tile t + 6 is requested while tile t is consumed
+
+// NQB = 32-query blocks per wavefront, NW = wavefronts per workgroup (4 or 8).
+template <int NQB, int NW>
+__global__ __launch_bounds__(64 * NW) void attend_bf16_dma_kernel(AttArgs a) {
+  constexpr int QW = 32 * NQB;
+  constexpr int NI = 16 / NW;                       // DMA row groups per wave and tile
+  constexpr int LPT = 2 * NI;                       // DMA loads per lane and tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
+  const Dims& D = a.D;
+  const int HG = D.G < 4 ? D.G : 4;
+  const int RS = NW / HG;
+  const int RPB = QW * RS;
+  const int gpk = D.G / HG;
+  const int bi = blockIdx.z, h = blockIdx.y / gpk, gsub = blockIdx.y - h * gpk;
+  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
+  const int L = a.n_q, d = 128;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int head = h * D.G + gsub * HG + (wave % HG);
+  const int rb0 = blockIdx.x * RPB;
+  const int r0 = rb0 + (wave / HG) * QW;
+  const int slot = slot_of(D, a.layer, seq, h);
+  const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.k_arena) + arena_off(D, slot) * 2;
+  const unsigned char* Vb = reinterpret_cast<const unsigned char*>(a.v_arena) + arena_off(D, slot) * 2;
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int list_len = meta[META_LIST_LEN];
+  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
+  const int n_ctx_tiles = (list_len + 63) / 64;
+  const int rb_end = min(L, rb0 + RPB);
+  const int n_chunk_tiles = (rb_end + 63) / 64;
+  const int n_tiles = n_ctx_tiles + n_chunk_tiles;
+  const uint32_t ring0 = (uint32_t)(uintptr_t)ring;
+
+  // loader role of this lane: rows 4 NW i + 4 wave + lq (i < NI), LDS piece lp of the row
+  const int lq = lane >> 4, lp = lane & 15;
+  const uint32_t tok0 = ring0 + DMA_NS * DMA_STAGE_BYTES;
+  const int32_t* tokring = reinterpret_cast<const int32_t*>(ring + DMA_NS * DMA_STAGE_BYTES);
+  // The context tiles' token ids travel through LDS as well: wavefront 0 requests the 64 list
+  // entries of tile u while tile u - 6 is consumed, always before the K/V request of the same
+  // iteration, so they have landed (and passed a barrier) when tile u's K/V rows are requested
+  // three iterations later. Tiles past the list read a dummy address to keep the count of
+  // outstanding loads the same in every iteration.
+  auto request_tokens = [&](int u) {
+    if (wave == 0) {
+      const int32_t* src = list + (u < n_ctx_tiles ? u * 64 : 0) + lane;
+      dma4(src, tok0 + (uint32_t)(u % TOK_SLOTS) * 256);
+    }
+  };
+  auto issue_tile = [&](int t) {
+    const uint32_t sbase = ring0 + (uint32_t)(t % DMA_NS) * DMA_STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      const int rw = 4 * NW * i + 4 * wave;           // first of the wave's four rows (uniform)
+      int tok;
+      if (t < n_ctx_tiles) tok = max(tokring[(t % TOK_SLOTS) * 64 + rw + lq], 0);
+      else                 tok = c0 + min((t - n_ctx_tiles) * 64 + rw + lq, L - 1);
+      const int row = rw + lq;
+      const size_t off = (size_t)tok * 256;
+      dma16(Kb + off + ((lp ^ (row & 7)) << 4), sbase + (uint32_t)rw * 256);
+      dma16(Vb + off + ((lp ^ ((row & 3) << 1)) << 4), sbase + 16384u + (uint32_t)rw * 256);
+    }
+  };
+
+  // query fragments (B operand of S^T = K Q^T)
+  uint4 qf[NQB][8];
+  {
+    const uint16_t* Qb = reinterpret_cast<const uint16_t*>(a.q) + (size_t)bi * L * D.Hq * d;
+#pragma unroll
+    for (int nq = 0; nq < NQB; ++nq) {
+      const int row = min(r0 + nq * 32 + l32, L - 1);
+      const uint16_t* qrow = Qb + ((size_t)row * D.Hq + head) * d;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) qf[nq][kk] = *reinterpret_cast<const uint4*>(qrow + kk * 16 + hf * 8);
+    }
+  }
+  f32x16_t o[4][NQB];
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+    for (int nq = 0; nq < NQB; ++nq)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[mb][nq][v] = 0.f;
+  float m_run[NQB], l_run[NQB];
+#pragma unroll
+  for (int nq = 0; nq < NQB; ++nq) { m_run[nq] = -1e30f; l_run[nq] = 0.f; }
+  const float sc = 1.4426950408889634f / sqrtf((float)d);
+
+  // per-lane pieces of the fragment addresses that do not depend on the tile
+  const int krow_sw = l32 & 7;                                   // K: piece ^ (row & 7), row = 32 kb + l32
+  const int vj = lane & 15, vgq = (lane >> 4) & 1;
+  const int vrow_in = 4 * hf + (vj >> 2);                        // row inside the 8-row group
+  const int vsw = (vrow_in & 3) << 1;
+  const int vpiece = 2 * vgq + ((vj & 3) >> 1), vhalf = vj & 1;
+
+  static_assert(DMA_NS == 4 && TOK_AHEAD == 6, "the vmcnt ladder below is written for four stages");
+  // prologue: tokens of tiles 0..2, then the steady-state pattern (tokens u + 6, K/V tile u + 3)
+  // for u = -3, -2, -1
+  for (int u = 0; u < 3; ++u) request_tokens(u);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  for (int u = 0; u < 3; ++u) {
+    request_tokens(u + 3);
+    if (u < n_tiles) issue_tile(u);
+  }
+  for (int t = 0; t < n_tiles; ++t) {
+    // loads requested after tile t's: those of the two following iterations
+    const int later = min(DMA_NS - 2, n_tiles - 1 - t);
+    if (wave == 0) {
+      if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT + 2) : "memory");
+      else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT + 2) : "memory");
+      else                 asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    } else {
+      if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT) : "memory");
+      else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT) : "memory");
+      else                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();            // tile t has landed for every wave; tile t-1's stage is free
+    request_tokens(t + TOK_AHEAD);
+    if (t + DMA_NS - 1 < n_tiles) issue_tile(t + DMA_NS - 1);
+    const bool is_chunk = t >= n_ctx_tiles;
+    const int k0 = is_chunk ? (t - n_ctx_tiles) * 64 : 0;
+    if (is_chunk && k0 > r0 + QW - 1) continue;
+    if (r0 >= L) continue;
+    const unsigned char* Ks = ring + (t % DMA_NS) * DMA_STAGE_BYTES;
+    const unsigned char* Vs = Ks + 16384;
+    // ---- S^T = K Q^T ----
+    f32x16_t s[2][NQB];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int nq = 0; nq < NQB; ++nq)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[kb][nq][v] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        const uint4 kf = *reinterpret_cast<const uint4*>(Ks + (kb * 32 + l32) * 256 + (((2 * kk + hf) ^ krow_sw) << 4));
+#pragma unroll
+        for (int nq = 0; nq < NQB; ++nq)
+          s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf),
+                                                              __builtin_bit_cast(bf16x8_t, qf[nq][kk]),
+                                                              s[kb][nq], 0, 0, 0);
+      }
+    }
+    // ---- masks ----
+    if (is_chunk) {
+      if (k0 + 63 > r0) {
+#pragma unroll
+        for (int nq = 0; nq < NQB; ++nq) {
+          const int qi = r0 + nq * 32 + l32;
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int kp = k0 + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+              if (kp > qi) s[kb][nq][v] = -INFINITY;
+            }
+        }
+      }
+    } else if (t == n_ctx_tiles - 1 && (list_len & 63)) {
+      const int nvalid = list_len - t * 64;
+#pragma unroll
+      for (int nq = 0; nq < NQB; ++nq)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int kr = kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+            if (kr >= nvalid) s[kb][nq][v] = -INFINITY;
+          }
+    }
+    // ---- online softmax (one query per lane pair) ----
+    uint4 pf[NQB][2][2];
+#pragma unroll
+    for (int nq = 0; nq < NQB; ++nq) {
+      float mx = s[0][nq][0];
+#pragma unroll
+      for (int v = 1; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[0][nq][v]), s[0][nq][(v + 1) & 15]);
+#pragma unroll
+      for (int v = 0; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[1][nq][v]), s[1][nq][v + 1]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run[nq], mx * sc);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
+      const bool changed = m_new != m_run[nq];
+      m_run[nq] = m_new;
+      float ps = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        float pv[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][v], sc, -m_new));
+          ps += pv[v];
+        }
+#pragma unroll
+        for (int a2 = 0; a2 < 2; ++a2) {
+          uint4 u;
+          u.x = pack_bf16x2(pv[8 * a2 + 0], pv[8 * a2 + 1]);
+          u.y = pack_bf16x2(pv[8 * a2 + 2], pv[8 * a2 + 3]);
+          u.z = pack_bf16x2(pv[8 * a2 + 4], pv[8 * a2 + 5]);
+          u.w = pack_bf16x2(pv[8 * a2 + 6], pv[8 * a2 + 7]);
+          pf[nq][kb][a2] = u;
+        }
+      }
+      l_run[nq] = l_run[nq] * alpha + ps;
+      if (__any(changed)) {
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[mb][nq][v] *= alpha;
+      }
+    }
+    // ---- O^T += V^T P^T ----
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int a2 = 0; a2 < 2; ++a2)
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb) {
+          const int rowb = kb * 32 + a2 * 16 + vrow_in;            // rd = 0; rd = 1 adds 8 rows
+          const int pc = ((4 * mb + vpiece) ^ vsw) << 4;
+          typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
+          const s16x4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s16x4_ptr)(Vs + rowb * 256 + pc + vhalf * 8));
+          const s16x4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s16x4_ptr)(Vs + (rowb + 8) * 256 + pc + vhalf * 8));
+          uint4 vf;
+          const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
+          vf.x = u0.x; vf.y = u0.y; vf.z = u1.x; vf.w = u1.y;
 #pragma unroll
           for (int nq = 0; nq < NQB; ++nq)
             o[mb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf),
@@ -361,10 +664,18 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
   if (mfma_ok) {
     const int HG = D.G < 4 ? D.G : 4;
     const int gpk = D.G / HG;
-    constexpr int NQB = 2;
-    const int RPB = 32 * NQB * (4 / HG);
+    constexpr int NQB = 1, NW = 8;
+    const int RPB = 32 * NQB * (NW / HG);
     dim3 g((n_q + RPB - 1) / RPB, D.Hkv * gpk, seq_count);
-    attend_bf16_kernel<NQB><<<g, 256, 0, s>>>(a);
+    static bool attr_set = false;
+    if (!attr_set) {
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_dma_kernel<NQB, NW>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,
+                                               DMA_NS * DMA_STAGE_BYTES + TOK_SLOTS * 256);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    attend_bf16_dma_kernel<NQB, NW><<<g, 64 * NW, DMA_NS * DMA_STAGE_BYTES + TOK_SLOTS * 256, s>>>(a);
   } else {
     dim3 g(n_q, D.Hq, seq_count);
     if (D.dtype == LTRI_BF16) attend_simple_kernel<LTRI_BF16><<<g, 64, 0, s>>>(a);

@@ -6,6 +6,7 @@
 // Scores are accumulated in fp64: products of bf16 (or fp32) values are exact in fp64, so the
 // order of the selection does not depend on the summation order of any implementation.
 #include "device_common.h"
+#include "span_mean.h"
 
 namespace ltri {
 
@@ -18,39 +19,22 @@ struct RetArgs {
 
 // ---- Q^R: mean over each query span of the group-summed query rows ----
 template <int DT>
-__global__ __launch_bounds__(256) void qrep_kernel(RetArgs a) {
+__global__ __launch_bounds__(1024) void qrep_kernel(RetArgs a) {
   typedef typename Elt<DT>::type T;
-  __shared__ double part[4][128];
+  __shared__ double part[16][128];
   const Dims& D = a.D;
   const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP], c0 = meta[META_CHUNK_START];
-  const int d = D.d, per = d / 64;
-  const int lane = threadIdx.x & 63, rg = threadIdx.x >> 6;
-  const T* Qb = reinterpret_cast<const T*>(a.q) + (size_t)bi * a.n_q * D.Hq * d;
+  const int d = D.d;
+  const T* Qb = reinterpret_cast<const T*>(a.q) + (size_t)bi * a.n_q * D.Hq * d + (size_t)h * D.G * d;
   T* out = reinterpret_cast<T*>(a.sc.qrep) + (size_t)p * a.Lp * d;
   for (int qs = blockIdx.x; qs < nsp; qs += gridDim.x) {
     const int sid = first + qs;
     const int start = a.st.span_start[(size_t)slot * D.max_spans + sid] - c0;   // chunk-local
     const int len = a.st.span_len[(size_t)slot * D.max_spans + sid];
-    double s0 = 0.0, s1 = 0.0;
-    for (int t = rg; t < len; t += 4) {
-      for (int g = 0; g < D.G; ++g) {
-        const T* row = Qb + ((size_t)(start + t) * D.Hq + h * D.G + g) * d + lane * per;
-        s0 += Elt<DT>::to_f64(row[0]);
-        if (per == 2) s1 += Elt<DT>::to_f64(row[1]);
-      }
-    }
-    part[rg][lane * per] = s0;
-    if (per == 2) part[rg][lane * per + 1] = s1;
-    __syncthreads();
-    if (threadIdx.x < d) {
-      const int c = threadIdx.x;
-      const double s = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
-      out[(size_t)qs * d + c] = Elt<DT>::from_f64(s / (double)len);
-    }
-    __syncthreads();
+    span_mean_block<DT>(Qb + (size_t)start * D.Hq * d, (size_t)D.Hq * d, D.G, len, d, out + (size_t)qs * d, part);
   }
 }
 
@@ -92,9 +76,12 @@ __device__ __forceinline__ void clip_span(const Dims& D, int c0, int start, int 
 
 // Given the selection as a bit mask over span ids, writes the ascending id list, the token
 // list and their lengths. Called by all 1024 threads of the block.
+constexpr int EMIT_CAP = 2048;     // selected spans whose tokens are written cooperatively
+
 __device__ void emit_selection(const Dims& D, const DevState& st, int slot, const uint32_t* selmask,
                                int n, int32_t* ids_out, int32_t* cnt_out) {
   __shared__ int s_wcnt[16], s_wtok[16], s_base_cnt, s_base_tok;
+  __shared__ int e_a[EMIT_CAP], e_len[EMIT_CAP], e_off[EMIT_CAP];
   int32_t* meta = st.meta + (size_t)slot * META_WORDS;
   const int c0 = meta[META_CHUNK_START];
   const int ns = min(D.n_sink, c0), ws = max(ns, c0 - D.window);
@@ -129,10 +116,12 @@ __device__ void emit_selection(const Dims& D, const DevState& st, int slot, cons
         sel[pos] = i;
         if (ids_out) ids_out[pos] = i;
       }
-      int o = ns + toff + ts - w;
-      for (int t = a; t < b; ++t) {
-        if (o < D.list_cap) list[o] = t;
-        ++o;
+      const int o = ns + toff + ts - w;
+      if (pos < EMIT_CAP) {
+        e_a[pos] = a; e_len[pos] = w; e_off[pos] = o;
+      } else {
+        for (int t = 0; t < w; ++t)
+          if (o + t < D.list_cap) list[o + t] = a + t;
       }
     }
     __syncthreads();
@@ -147,6 +136,12 @@ __device__ void emit_selection(const Dims& D, const DevState& st, int slot, cons
   const int n_win = c0 - ws;
   const int len = ns + n_ret + n_win;
   const bool fits = n_sel <= D.sel_cap && len <= D.list_cap;
+  // tokens of the recorded spans: one wavefront per span, lanes along the span
+  for (int k = wave; k < min(n_sel, EMIT_CAP); k += 16) {
+    const int a = e_a[k], w = e_len[k], o = e_off[k];
+    for (int t = lane; t < w; t += 64)
+      if (o + t < D.list_cap) list[o + t] = a + t;
+  }
   if (fits) {
     for (int t = tid; t < n_win; t += blockDim.x) list[ns + n_ret + t] = ws + t;
     const int padded = min(D.list_cap, (len + ATT_BN - 1) / ATT_BN * ATT_BN);
@@ -256,8 +251,8 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
   const int P = seq_count * D.Hkv;
   const bool bf = D.dtype == LTRI_BF16;
   dim3 gq(n_q < 64 ? n_q : 64, P);
-  if (bf) qrep_kernel<LTRI_BF16><<<gq, 256, 0, s>>>(a);
-  else    qrep_kernel<LTRI_F32><<<gq, 256, 0, s>>>(a);
+  if (bf) qrep_kernel<LTRI_BF16><<<gq, 1024, 0, s>>>(a);
+  else    qrep_kernel<LTRI_F32><<<gq, 1024, 0, s>>>(a);
   int gx = (span_bound + 3) / 4;
   if (gx < 1) gx = 1;
   if (gx > 256) gx = 256;

@@ -16,6 +16,7 @@
 // results per anti-diagonal, sorts the candidates, runs the greedy NMS and cuts the chunk.
 // All sums are fp64 in a fixed order, so the result is deterministic.
 #include "device_common.h"
+#include "span_mean.h"
 
 namespace ltri {
 
@@ -162,30 +163,40 @@ __global__ __launch_bounds__(256) void seg_row_lse_kernel(SegArgs a) {
 template <int DT>
 __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
   __shared__ double Ms[64 * 65];
-  __shared__ double colsum[64];
+  __shared__ double cpart[4][64];
   const int p = blockIdx.y;
   int I, J;
   tile_decode(blockIdx.x, I, J);
   compute_tile<DT>(a, p, I, J, Ms);
   __syncthreads();
   const int tid = threadIdx.x;
-  if (tid < 64) {
+  {                                       // row sums: four threads per row, 16 columns each
+    const int r = tid >> 2, qd = tid & 3;
     double s = 0.0;
-    for (int c = 0; c < 64; ++c) s += Ms[tid * 65 + c];
-    a.sc.rowsum[((size_t)p * a.nb + J) * a.Lp + I * 64 + tid] = s;
-  } else if (tid < 128) {
-    int c = tid - 64;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) s += Ms[r * 65 + qd * 16 + c];
+    s += __shfl_xor(s, 1, 64);
+    s += __shfl_xor(s, 2, 64);
+    if (qd == 0) a.sc.rowsum[((size_t)p * a.nb + J) * a.Lp + I * 64 + r] = s;
+  }
+  {                                       // column sums: four threads per column, 16 rows each
+    const int c = tid & 63, qd = tid >> 6;
     double s = 0.0;
-    for (int r = 0; r < 64; ++r) s += Ms[r * 65 + c];
-    colsum[c] = s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += Ms[(qd * 16 + r) * 65 + c];
+    cpart[qd][c] = s;
   }
   __syncthreads();
-  if (tid < 64) {
-    double s = 0.0;
-    for (int c = 63; c >= tid; --c) s += colsum[c];
+  if (tid < 64) {                         // suffix scan over the 64 columns inside one wavefront
+    double v = ((cpart[0][tid] + cpart[1][tid]) + cpart[2][tid]) + cpart[3][tid];
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const double w = __shfl_down(v, o, 64);
+      if (tid + o < 64) v += w;
+    }
     // csuf is indexed [I][x]: block-row I's contribution restricted to this column block
-    a.sc.csuf[((size_t)p * a.nb + I) * a.Lp + J * 64 + tid] = s;
-    if (tid == 0) a.sc.tsum[((size_t)p * a.nb + I) * a.nb + J] = s;
+    a.sc.csuf[((size_t)p * a.nb + I) * a.Lp + J * 64 + tid] = v;
+    if (tid == 0) a.sc.tsum[((size_t)p * a.nb + I) * a.nb + J] = v;
   }
 }
 
@@ -199,10 +210,14 @@ __global__ __launch_bounds__(1024) void seg_carries_kernel(SegArgs a) {
   double* rcar = a.sc.rcar + (size_t)p * nb * Lp;
   double* ccar = a.sc.ccar + (size_t)p * nb * Lp;
   for (int i = threadIdx.x; i < Lp; i += blockDim.x) {
+    const int I = i / 64;
+    double v[SEG_MAX_NB];
+#pragma unroll
+    for (int J = 0; J < SEG_MAX_NB; ++J) v[J] = (J <= I) ? rowsum[(size_t)J * Lp + i] : 0.0;   // loads in flight together
     double run = 0.0;
-    for (int J = i / 64; J >= 0; --J) {
-      rcar[(size_t)J * Lp + i] = run;
-      run += rowsum[(size_t)J * Lp + i];
+#pragma unroll
+    for (int J = SEG_MAX_NB - 1; J >= 0; --J) {
+      if (J <= I) { rcar[(size_t)J * Lp + i] = run; run += v[J]; }
     }
   }
   for (int I = threadIdx.x; I < nb; I += blockDim.x) {
@@ -215,10 +230,13 @@ __global__ __launch_bounds__(1024) void seg_carries_kernel(SegArgs a) {
   __syncthreads();
   for (int x = threadIdx.x; x < Lp; x += blockDim.x) {
     const int J = x / 64;
+    double v[SEG_MAX_NB];
+#pragma unroll
+    for (int I = 0; I < SEG_MAX_NB; ++I) v[I] = (I >= J && I < nb) ? csuf[(size_t)I * Lp + x] : 0.0;
     double run = 0.0;
-    for (int I = J; I < nb; ++I) {
-      ccar[(size_t)I * Lp + x] = run;
-      run += csuf[(size_t)I * Lp + x] + TS[I * SEG_MAX_NB + J];
+#pragma unroll
+    for (int I = 0; I < SEG_MAX_NB; ++I) {
+      if (I >= J && I < nb) { ccar[(size_t)I * Lp + x] = run; run += v[I] + TS[I * SEG_MAX_NB + J]; }
     }
   }
 }
@@ -228,6 +246,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   __shared__ double Ms[64 * 65];
   __shared__ double rc[64];
+  __shared__ double qsum[64][4];       // sums of the four 16-wide pieces of a row / of a column
   const int p = blockIdx.y;
   int I, J;
   tile_decode(blockIdx.x, I, J);
@@ -235,37 +254,63 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   const int tid = threadIdx.x, L = a.n_new;
   if (tid < 64) rc[tid] = a.sc.rcar[((size_t)p * a.nb + J) * a.Lp + I * 64 + tid];
   __syncthreads();
-  if (tid < 64) {                       // row r: suffix sums towards the left
+  {                                     // rows: suffix sums towards the left, four threads per row
+    const int r = tid >> 2, qd = tid & 3;
+    double s = 0.0;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) s += Ms[r * 65 + qd * 16 + c];
+    qsum[r][qd] = s;
+    __syncthreads();
     double run = 0.0;
-    for (int c = 63; c >= 0; --c) { run += Ms[tid * 65 + c]; Ms[tid * 65 + c] = run; }
+    for (int q2 = 3; q2 > qd; --q2) run += qsum[r][q2];
+#pragma unroll
+    for (int c = 15; c >= 0; --c) { run += Ms[r * 65 + qd * 16 + c]; Ms[r * 65 + qd * 16 + c] = run; }
   }
   __syncthreads();
-  if (tid < 64) {                       // column c: prefix sums downwards, then Eq. 5
-    const int x = J * 64 + tid;
+  {                                     // columns: prefix sums downwards, four threads per column
+    const int c = tid & 63, qd = tid >> 6;
+    double s = 0.0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += Ms[(qd * 16 + r) * 65 + c] + rc[qd * 16 + r];
+    qsum[c][qd] = s;
+    __syncthreads();
+    const int x = J * 64 + c;
     const int n_h = a.q_seg ? a.D.G : 1;
     const double th = (double)a.D.theta * (double)n_h;
     double run = a.sc.ccar[((size_t)p * a.nb + I) * a.Lp + x];
-    for (int r = 0; r < 64; ++r) {
-      const int y = I * 64 + r;
-      run += Ms[r * 65 + tid] + rc[r];
+    for (int q2 = 0; q2 < qd; ++q2) run += qsum[c][q2];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int rl = qd * 16 + r, y = I * 64 + rl;
+      run += Ms[rl * 65 + c] + rc[rl];
       const long long n = (long long)y - x + 1;
-      double s = run - th * (double)(n * (n + 1) / 2);
-      Ms[r * 65 + tid] = (x <= y && y < L) ? s : -INFINITY;
+      const double sv = run - th * (double)(n * (n + 1) / 2);       // Eq. 5
+      Ms[rl * 65 + c] = (x <= y && y < L) ? sv : -INFINITY;
     }
   }
   __syncthreads();
-  if (tid < 128) {                      // anti-diagonal xl + yl = tid of the tile
+  {                                     // anti-diagonal xl + yl = s of the tile, two threads each
+    const int sd = tid >> 1, half = tid & 1;
     double best = -INFINITY;
     int bx = -1;
-    if (tid < 127) {
-      const int lo = max(0, tid - 63), hi = min(63, tid);
-      for (int xl = lo; xl <= hi; ++xl) {
-        double v = Ms[(tid - xl) * 65 + xl];
+    if (sd < 127) {
+      const int lo = max(0, sd - 63), hi = min(63, sd);
+      const int mid = (lo + hi + 1) >> 1;
+      const int b0 = half ? mid : lo, b1 = half ? hi : mid - 1;
+      for (int xl = b0; xl <= b1; ++xl) {
+        const double v = Ms[(sd - xl) * 65 + xl];
         if (v >= best && v > -INFINITY) { best = v; bx = J * 64 + xl; }   // ties: larger x
       }
     }
-    a.sc.pscore[((size_t)p * a.ntiles + blockIdx.x) * 128 + tid] = best;
-    a.sc.px[((size_t)p * a.ntiles + blockIdx.x) * 128 + tid] = bx;
+    const double ob = __shfl_xor(best, 1, 64);
+    const int ox = __shfl_xor(bx, 1, 64);
+    if (half == 0) {                    // the partner holds the larger x: it wins ties
+      if (ox >= 0 && (bx < 0 || ob >= best)) { best = ob; bx = ox; }
+      if (sd < 128) {
+        a.sc.pscore[((size_t)p * a.ntiles + blockIdx.x) * 128 + sd] = best;
+        a.sc.px[((size_t)p * a.ntiles + blockIdx.x) * 128 + sd] = bx;
+      }
+    }
   }
 }
 
@@ -350,22 +395,71 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
     }
   }
   __syncthreads();
-  // bitonic sort by (score descending, x ascending, y ascending)
-  for (int k = 2; k <= n_sort; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      for (int i = tid; i < n_sort; i += blockDim.x) {
-        const int ixj = i ^ j;
-        if (ixj > i) {
-          const uint64_t a1 = k1[i], b1 = k1[ixj];
-          const uint32_t a2 = k2[i], b2 = k2[ixj];
-          const bool up = (i & k) == 0;
-          const bool sw = up ? key_less(b1, b2, a1, a2) : key_less(a1, a2, b1, b2);
-          if (sw) { k1[i] = b1; k1[ixj] = a1; k2[i] = b2; k2[ixj] = a2; }
+  // Bitonic sort of 4096 (key1, key2) pairs by (score descending, x ascending, y ascending):
+  // thread t owns elements 4t..4t+3 in registers; partners at distance < 4 are exchanged in
+  // registers, < 256 by wavefront shuffles, >= 256 through LDS.
+  {
+    uint64_t e1[4];
+    uint32_t e2[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int e = tid * 4 + r;
+      e1[r] = e < n_sort ? k1[e] : ~0ull;
+      e2[r] = e < n_sort ? k2[e] : 0xFFFFFFFFu;
+    }
+    __syncthreads();
+    for (int k = 2; k <= 4096; k <<= 1) {
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        if (j >= 256) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) { k1[tid * 4 + r] = e1[r]; k2[tid * 4 + r] = e2[r]; }
+          __syncthreads();
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int e = tid * 4 + r, pe = e ^ j;
+            const uint64_t o1 = k1[pe];
+            const uint32_t o2 = k2[pe];
+            const bool asc = (e & k) == 0, lower = (e & j) == 0;
+            const bool mine_less = key_less(e1[r], e2[r], o1, o2);
+            const bool keep = (lower == asc) ? mine_less : !mine_less;   // lower slot of an ascending pair keeps the min
+            if (!keep) { e1[r] = o1; e2[r] = o2; }
+          }
+          __syncthreads();
+        } else if (j >= 4) {
+          const int lj = j >> 2;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int e = tid * 4 + r;
+            const uint32_t lo = __shfl_xor((uint32_t)e1[r], lj, 64);
+            const uint32_t hi = __shfl_xor((uint32_t)(e1[r] >> 32), lj, 64);
+            const uint32_t o2 = __shfl_xor(e2[r], lj, 64);
+            const uint64_t o1 = ((uint64_t)hi << 32) | lo;
+            const bool asc = (e & k) == 0, lower = (e & j) == 0;
+            const bool mine_less = key_less(e1[r], e2[r], o1, o2);
+            const bool keep = (lower == asc) ? mine_less : !mine_less;
+            if (!keep) { e1[r] = o1; e2[r] = o2; }
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int pr = r ^ j;
+            if (pr > r) {
+              const int e = tid * 4 + r;
+              const bool asc = (e & k) == 0;
+              const bool less = key_less(e1[pr], e2[pr], e1[r], e2[r]);   // partner < mine
+              if (less == asc) {
+                const uint64_t t1 = e1[r]; e1[r] = e1[pr]; e1[pr] = t1;
+                const uint32_t t2 = e2[r]; e2[r] = e2[pr]; e2[pr] = t2;
+              }
+            }
+          }
         }
       }
-      __syncthreads();
     }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) k2[tid * 4 + r] = e2[r];
   }
+  __syncthreads();
   // greedy NMS by the first wavefront; the kept list overwrites k1 (scores are no longer needed)
   volatile uint32_t* kept = reinterpret_cast<volatile uint32_t*>(k1);
   if (tid < 64) {
@@ -487,37 +581,21 @@ __global__ __launch_bounds__(256) void append_bounds_kernel(BoundsArgs a) {
 struct RepArgs { Dims D; DevState st; const void* k_arena; int layer; int seq_count; BatchPos bp; };
 
 template <int DT>
-__global__ __launch_bounds__(256) void rep_keys_kernel(RepArgs a) {
+__global__ __launch_bounds__(1024) void rep_keys_kernel(RepArgs a) {
   typedef typename Elt<DT>::type T;
-  __shared__ double part[4][128];
+  __shared__ double part[16][128];
   const Dims& D = a.D;
   const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP];
-  const int d = D.d, per = d / 64;                      // 1 or 2 columns per lane
-  const int lane = threadIdx.x & 63, rg = threadIdx.x >> 6;
   const T* Kb = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot);
   for (int q = blockIdx.x; q < nsp; q += gridDim.x) {
     const int sid = first + q;
     const int start = a.st.span_start[(size_t)slot * D.max_spans + sid];
     const int len = a.st.span_len[(size_t)slot * D.max_spans + sid];
-    double s0 = 0.0, s1 = 0.0;
-    for (int t = rg; t < len; t += 4) {
-      const T* row = Kb + (size_t)(start + t) * d + lane * per;
-      s0 += Elt<DT>::to_f64(row[0]);
-      if (per == 2) s1 += Elt<DT>::to_f64(row[1]);
-    }
-    part[rg][lane * per] = s0;
-    if (per == 2) part[rg][lane * per + 1] = s1;
-    __syncthreads();
-    if (threadIdx.x < d) {
-      const int c = threadIdx.x;
-      const double s = ((part[0][c] + part[1][c]) + part[2][c]) + part[3][c];
-      T* rep = reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + sid) * d;
-      rep[c] = Elt<DT>::from_f64(s / (double)len);
-    }
-    __syncthreads();
+    T* rep = reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + sid) * D.d;
+    span_mean_block<DT>(Kb + (size_t)start * D.d, (size_t)D.d, 1, len, D.d, rep, part);
   }
 }
 
@@ -614,8 +692,8 @@ hipError_t launch_rep_keys(const Dims& D, const DevState& st, const void* k_aren
   RepArgs a{D, st, k_arena, layer, seq_count, bp};
   const int gx = n_new < 64 ? n_new : 64;
   dim3 g(gx, seq_count * D.Hkv);
-  if (D.dtype == LTRI_BF16) rep_keys_kernel<LTRI_BF16><<<g, 256, 0, s>>>(a);
-  else                      rep_keys_kernel<LTRI_F32><<<g, 256, 0, s>>>(a);
+  if (D.dtype == LTRI_BF16) rep_keys_kernel<LTRI_BF16><<<g, 1024, 0, s>>>(a);
+  else                      rep_keys_kernel<LTRI_F32><<<g, 1024, 0, s>>>(a);
   return hipGetLastError();
 }
 
