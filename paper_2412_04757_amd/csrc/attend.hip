@@ -2,13 +2,12 @@
 // initial | retrieved | window tokens (read through the context token list built by step 2)
 // and the chunk's own tokens (causal), plus the standalone gather of that context set.
 //
-// bf16 kernel: flash-style streaming over 64-key tiles on the matrix cores. A workgroup is four
-// wavefronts that share every K/V tile through LDS; the four are the query heads of one KV
-// head's group (GQA), each with QW query rows held in registers. Scores are computed
-// transposed (S^T = K Q^T) so that one lane owns one query: the softmax statistics need a
-// single cross-lane exchange and the probabilities are already laid out as the B operand of
-// O^T = V^T P^T. V is transposed on its way into LDS, with the keys permuted inside each block
-// of 32 to the order in which the score accumulators hold them.
+// bf16 kernel: flash-style streaming over 64-key tiles on the matrix cores. A workgroup is
+// eight wavefronts that share every K/V tile through LDS: the query heads of one KV head's
+// group (GQA) times two 32-row sub-tiles, each wavefront with its 32 query rows in registers.
+// Scores are computed transposed (S^T = K Q^T) so that one lane owns one query: the softmax
+// statistics need a single cross-lane exchange and the probabilities are already laid out as
+// the B operand of O^T = V^T P^T.
 #include "device_common.h"
 
 namespace ltri {
@@ -19,9 +18,6 @@ struct AttArgs {
   BatchPos bp;
 };
 
-constexpr int KS_STRIDE = 136;   // bf16 elements per K row in LDS (128 + 8 pad)
-constexpr int VT_STRIDE = 72;    // bf16 elements per V^T row in LDS (64 keys + 8 pad)
-
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
 
@@ -31,246 +27,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
-// NQB = 32-query blocks per wavefront.
-template <int NQB>
-__global__ __launch_bounds__(256) void attend_bf16_kernel(AttArgs a) {
-  constexpr int QW = 32 * NQB;
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * KS_STRIDE];
-  __shared__ __attribute__((aligned(16))) uint16_t Vt[128 * VT_STRIDE];
-  const Dims& D = a.D;
-  const int HG = D.G < 4 ? D.G : 4;                 // heads of the group handled by this block
-  const int RS = 4 / HG;                            // row sub-tiles per block
-  const int RPB = QW * RS;                          // query rows per block
-  const int gpk = D.G / HG;                         // blocks per KV head along y
-  const int bi = blockIdx.z, h = blockIdx.y / gpk, gsub = blockIdx.y - h * gpk;
-  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
-  const int L = a.n_q, d = 128;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l32 = lane & 31, hf = lane >> 5;
-  const int head = h * D.G + gsub * HG + (wave % HG);
-  const int rb0 = blockIdx.x * RPB;                 // first row of the block
-  const int r0 = rb0 + (wave / HG) * QW;            // first row of this wave
-  const int slot = slot_of(D, a.layer, seq, h);
-  const uint16_t* Kb = reinterpret_cast<const uint16_t*>(a.k_arena) + arena_off(D, slot);
-  const uint16_t* Vb = reinterpret_cast<const uint16_t*>(a.v_arena) + arena_off(D, slot);
-  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
-  const int list_len = meta[META_LIST_LEN];
-  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
-  const int n_ctx_tiles = (list_len + 63) / 64;
-  const int rb_end = min(L, rb0 + RPB);
-  const int n_chunk_tiles = (rb_end + 63) / 64;
-  const int n_tiles = n_ctx_tiles + n_chunk_tiles;
-
-  // query fragments: B operand of S^T = K Q^T; lane (l32, hf) holds Q[row l32][16 kk + 8 hf ..]
-  uint4 qf[NQB][8];
-  {
-    const uint16_t* Qb = reinterpret_cast<const uint16_t*>(a.q) + (size_t)bi * L * D.Hq * d;
-#pragma unroll
-    for (int nq = 0; nq < NQB; ++nq) {
-      const int row = min(r0 + nq * 32 + l32, L - 1);
-      const uint16_t* qrow = Qb + ((size_t)row * D.Hq + head) * d;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) qf[nq][kk] = *reinterpret_cast<const uint4*>(qrow + kk * 16 + hf * 8);
-    }
-  }
-  f32x16_t o[4][NQB];
-#pragma unroll
-  for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-    for (int nq = 0; nq < NQB; ++nq)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[mb][nq][v] = 0.f;
-  float m_run[NQB], l_run[NQB];
-#pragma unroll
-  for (int nq = 0; nq < NQB; ++nq) { m_run[nq] = -1e30f; l_run[nq] = 0.f; }
-  const float sc = 1.4426950408889634f / sqrtf((float)d);     // log2(e) / sqrt(d)
-
-  // loader roles
-  const int lrow = tid >> 4, lcc = tid & 15;                  // K: rows lrow + 16 rr; 16-byte chunk lcc
-  const int kg = tid >> 4;                                    // V: keys 4 kg .. 4 kg + 3
-  const int vkb = kg >> 3, va = (kg & 7) >> 1, vhf = kg & 1;
-  const int vpos = 4 * (8 * vkb + 4 * (va >> 1) + 2 * vhf + (va & 1));
-  uint4 kreg[4], vreg[4];
-
-  auto tile_token = [&](int t, int r) -> int {                 // token of key r of tile t, -1 = none
-    if (t < n_ctx_tiles) return list[t * 64 + r];
-    const int kp = (t - n_ctx_tiles) * 64 + r;
-    return kp < L ? c0 + kp : -1;
-  };
-  auto issue_loads = [&](int t) {
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      int tok = tile_token(t, lrow + 16 * rr);
-      tok = tok < 0 ? 0 : tok;
-      kreg[rr] = *reinterpret_cast<const uint4*>(Kb + (size_t)tok * d + lcc * 8);
-    }
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      int tok = tile_token(t, 4 * kg + kk);
-      tok = tok < 0 ? 0 : tok;
-      vreg[kk] = *reinterpret_cast<const uint4*>(Vb + (size_t)tok * d + lcc * 8);
-    }
-  };
-  auto store_lds = [&]() {
-#pragma unroll
-    for (int rr = 0; rr < 4; ++rr)
-      *reinterpret_cast<uint4*>(&Ks[(lrow + 16 * rr) * KS_STRIDE + lcc * 8]) = kreg[rr];
-    const uint32_t w[4][4] = {{vreg[0].x, vreg[0].y, vreg[0].z, vreg[0].w},
-                              {vreg[1].x, vreg[1].y, vreg[1].z, vreg[1].w},
-                              {vreg[2].x, vreg[2].y, vreg[2].z, vreg[2].w},
-                              {vreg[3].x, vreg[3].y, vreg[3].z, vreg[3].w}};
-#pragma unroll
-    for (int e2 = 0; e2 < 4; ++e2) {        // columns 8 lcc + 2 e2 (low halves) and + 1 (high halves)
-      uint2 lo, hi;
-      lo.x = (w[0][e2] & 0xFFFFu) | (w[1][e2] << 16);
-      lo.y = (w[2][e2] & 0xFFFFu) | (w[3][e2] << 16);
-      hi.x = (w[0][e2] >> 16) | (w[1][e2] & 0xFFFF0000u);
-      hi.y = (w[2][e2] >> 16) | (w[3][e2] & 0xFFFF0000u);
-      *reinterpret_cast<uint2*>(&Vt[(lcc * 8 + 2 * e2) * VT_STRIDE + vpos]) = lo;
-      *reinterpret_cast<uint2*>(&Vt[(lcc * 8 + 2 * e2 + 1) * VT_STRIDE + vpos]) = hi;
-    }
-  };
-
-  if (n_tiles > 0) issue_loads(0);
-  for (int t = 0; t < n_tiles; ++t) {
-    __syncthreads();                        // everyone is done reading the previous tile
-    store_lds();
-    __syncthreads();
-    if (t + 1 < n_tiles) issue_loads(t + 1);
-    const bool is_chunk = t >= n_ctx_tiles;
-    const int k0 = is_chunk ? (t - n_ctx_tiles) * 64 : 0;      // chunk-local position of key 0
-    if (is_chunk && k0 > r0 + QW - 1) continue;                // nothing visible for this wave
-    if (r0 >= L) continue;
-    // ---- S^T = K Q^T ----
-    f32x16_t s[2][NQB];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int nq = 0; nq < NQB; ++nq)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[kb][nq][v] = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const uint4 kf = *reinterpret_cast<const uint4*>(&Ks[(kb * 32 + l32) * KS_STRIDE + kk * 16 + hf * 8]);
-#pragma unroll
-        for (int nq = 0; nq < NQB; ++nq)
-          s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf),
-                                                              __builtin_bit_cast(bf16x8_t, qf[nq][kk]),
-                                                              s[kb][nq], 0, 0, 0);
-      }
-    }
-    // ---- masks (only tiles that reach past the wave's first row, or the ragged last list tile) ----
-    if (is_chunk) {
-      if (k0 + 63 > r0) {
-#pragma unroll
-        for (int nq = 0; nq < NQB; ++nq) {
-          const int qi = r0 + nq * 32 + l32;
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int kp = k0 + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-              if (kp > qi) s[kb][nq][v] = -INFINITY;
-            }
-        }
-      }
-    } else if (t == n_ctx_tiles - 1 && (list_len & 63)) {
-      const int nvalid = list_len - t * 64;
-#pragma unroll
-      for (int nq = 0; nq < NQB; ++nq)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int kr = kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-            if (kr >= nvalid) s[kb][nq][v] = -INFINITY;
-          }
-    }
-    // ---- online softmax (one query per lane pair) ----
-    uint4 pf[NQB][2][2];
-#pragma unroll
-    for (int nq = 0; nq < NQB; ++nq) {
-      float mx = s[0][nq][0];
-#pragma unroll
-      for (int v = 1; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[0][nq][v]), s[0][nq][(v + 1) & 15]);
-#pragma unroll
-      for (int v = 0; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[1][nq][v]), s[1][nq][v + 1]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[nq], mx * sc);
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
-      const bool changed = m_new != m_run[nq];
-      m_run[nq] = m_new;
-      float ps = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        float pv[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][v], sc, -m_new));
-          ps += pv[v];
-        }
-#pragma unroll
-        for (int a2 = 0; a2 < 2; ++a2) {
-          uint4 u;
-          u.x = pack_bf16x2(pv[8 * a2 + 0], pv[8 * a2 + 1]);
-          u.y = pack_bf16x2(pv[8 * a2 + 2], pv[8 * a2 + 3]);
-          u.z = pack_bf16x2(pv[8 * a2 + 4], pv[8 * a2 + 5]);
-          u.w = pack_bf16x2(pv[8 * a2 + 6], pv[8 * a2 + 7]);
-          pf[nq][kb][a2] = u;
-        }
-      }
-      l_run[nq] = l_run[nq] * alpha + ps;
-      if (__any(changed)) {                 // the running maximum rarely moves after the first tiles
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) o[mb][nq][v] *= alpha;
-      }
-    }
-    // ---- O^T += V^T P^T ----
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int a2 = 0; a2 < 2; ++a2)
-#pragma unroll
-        for (int mb = 0; mb < 4; ++mb) {
-          const uint4 vf = *reinterpret_cast<const uint4*>(&Vt[(mb * 32 + l32) * VT_STRIDE + kb * 32 + a2 * 16 + hf * 8]);
-#pragma unroll
-          for (int nq = 0; nq < NQB; ++nq)
-            o[mb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf),
-                                                                __builtin_bit_cast(bf16x8_t, pf[nq][kb][a2]),
-                                                                o[mb][nq], 0, 0, 0);
-        }
-  }
-  // ---- epilogue ----
-  uint16_t* Ob = reinterpret_cast<uint16_t*>(a.out) + (size_t)bi * L * D.Hq * d;
-#pragma unroll
-  for (int nq = 0; nq < NQB; ++nq) {
-    const int qi = r0 + nq * 32 + l32;
-    const float lt = l_run[nq] + __shfl_xor(l_run[nq], 32, 64);
-    if (qi < L) {
-      const float inv = 1.f / lt;
-      uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int a4 = 0; a4 < 4; ++a4) {
-          uint2 u;
-          u.x = pack_bf16x2(o[mb][nq][4 * a4 + 0] * inv, o[mb][nq][4 * a4 + 1] * inv);
-          u.y = pack_bf16x2(o[mb][nq][4 * a4 + 2] * inv, o[mb][nq][4 * a4 + 3] * inv);
-          *reinterpret_cast<uint2*>(orow + mb * 32 + 8 * a4 + 4 * hf) = u;
-        }
-      if (a.lse && hf == 0)
-        a.lse[((size_t)bi * L + qi) * D.Hq + head] = (m_run[nq] + log2f(lt)) * 0.6931471805599453f;
-    }
-  }
-}
-
-// ---- bf16 kernel, LDS-DMA version ----
+// ---- bf16 kernel ----
 // K and V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane, no
-// registers in between) through a ring of NS stages, so several tiles are in flight while one is
+// registers in between) through a ring of four stages, so two tiles are in flight while one is
 // being consumed and a single barrier per tile suffices. Both tiles keep the row-major [key][d]
 // layout of the arena; inside a 256-byte row the sixteen 16-byte pieces are permuted (XOR with a
 // function of the row) so that the fragment reads are free of bank conflicts; the permutation is
@@ -280,44 +39,49 @@ __global__ __launch_bounds__(256) void attend_bf16_kernel(AttArgs a) {
 // row0 .. row0 + 3.
 // The DMA is issued through inline assembly because the compiler would otherwise wait for ALL
 // outstanding DMA before any LDS read; completion is awaited by hand with s_waitcnt vmcnt(n),
-// n = DMA loads issued later than the tile about to be used (8 per tile and lane).
+// n = DMA loads requested later than the tile about to be used.
+// The eight wavefronts form two groups that share the SIMDs pairwise. Group A runs
+// scores -> softmax -> PV on tile t between two barriers; group B runs softmax and PV of tile
+// t - 1 first and the scores of tile t last. While one group is in its softmax (vector ALU) the
+// other is on the matrix cores.
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
+constexpr int ATT_NW = 8;                       // wavefronts per workgroup
 constexpr int DMA_NS = 4;                       // ring stages
 constexpr int DMA_STAGE_BYTES = 32768;          // K tile 16 KB + V tile 16 KB
-
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_wave_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_wave_base), "v"(gptr) : "m0");
-}
-
-__device__ __forceinline__ void dma4(const void* gptr, uint32_t lds_wave_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_wave_base), "v"(gptr) : "m0");
-}
-
+constexpr int DMA_LPT = 4;                      // K/V requests per lane and tile
 constexpr int TOK_SLOTS = 8;                    // ring of 64-entry token tiles
-constexpr int TOK_AHEAD = 6;                    // token tile t + 6 is requested while tile t is consumed
+constexpr int ATT_LDS_BYTES = DMA_NS * DMA_STAGE_BYTES + TOK_SLOTS * 256;
 
-// NQB = 32-query blocks per wavefront, NW = wavefronts per workgroup (4 or 8).
-template <int NQB, int NW>
-__global__ __launch_bounds__(64 * NW) void attend_bf16_dma_kernel(AttArgs a) {
-  constexpr int QW = 32 * NQB;
-  constexpr int NI = 16 / NW;                       // DMA row groups per wave and tile
-  constexpr int LPT = 2 * NI;                       // DMA loads per lane and tile
+// 16 bytes per lane from base + off into LDS at lds_wave_base + 16 * lane
+__device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_wave_base), "v"(off), "s"(base) : "m0");
+}
+// 4 bytes per lane
+__device__ __forceinline__ void dma4(const void* base, uint32_t off, uint32_t lds_wave_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_wave_base), "v"(off), "s"(base) : "m0");
+}
+
+__global__ __launch_bounds__(64 * ATT_NW) void attend_bf16_kernel(AttArgs a) {
+  constexpr int NW = ATT_NW;
   extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
   const Dims& D = a.D;
-  const int HG = D.G < 4 ? D.G : 4;
-  const int RS = NW / HG;
-  const int RPB = QW * RS;
-  const int gpk = D.G / HG;
-  const int bi = blockIdx.z, h = blockIdx.y / gpk, gsub = blockIdx.y - h * gpk;
+  const int HG = D.G < 4 ? D.G : 4;                 // heads of the group handled by this block
+  const int RS = NW / HG;                           // 32-row sub-tiles per block
+  const int RPB = 32 * RS;                          // query rows per block
+  const int gpk = D.G / HG;                         // blocks per KV head
+  // KV head along x: consecutive workgroup ids go to different XCDs, so all query tiles of one
+  // KV head run on one XCD and share its K/V rows in that XCD's L2
+  const int bi = blockIdx.z, h = blockIdx.x / gpk, gsub = blockIdx.x - h * gpk;
   const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
   const int L = a.n_q, d = 128;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
   const int head = h * D.G + gsub * HG + (wave % HG);
-  const int rb0 = blockIdx.x * RPB;
-  const int r0 = rb0 + (wave / HG) * QW;
+  const int rb0 = blockIdx.y * RPB;                 // first row of the block
+  const int r0 = rb0 + (wave / HG) * 32;            // first row of this wave
+  const bool group_b = wave >= NW / 2;
   const int slot = slot_of(D, a.layer, seq, h);
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.k_arena) + arena_off(D, slot) * 2;
   const unsigned char* Vb = reinterpret_cast<const unsigned char*>(a.v_arena) + arena_off(D, slot) * 2;
@@ -329,232 +93,251 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_dma_kernel(AttArgs a) {
   const int n_chunk_tiles = (rb_end + 63) / 64;
   const int n_tiles = n_ctx_tiles + n_chunk_tiles;
   const uint32_t ring0 = (uint32_t)(uintptr_t)ring;
-
-  // loader role of this lane: rows 4 NW i + 4 wave + lq (i < NI), LDS piece lp of the row
-  const int lq = lane >> 4, lp = lane & 15;
   const uint32_t tok0 = ring0 + DMA_NS * DMA_STAGE_BYTES;
   const int32_t* tokring = reinterpret_cast<const int32_t*>(ring + DMA_NS * DMA_STAGE_BYTES);
-  // The context tiles' token ids travel through LDS as well: wavefront 0 requests the 64 list
-  // entries of tile u while tile u - 6 is consumed, always before the K/V request of the same
-  // iteration, so they have landed (and passed a barrier) when tile u's K/V rows are requested
-  // three iterations later. Tiles past the list read a dummy address to keep the count of
-  // outstanding loads the same in every iteration.
+
+  // ---- requests ----
+  // Token ids of the context tiles travel through LDS as well: wavefront 0 requests the 64 list
+  // entries of tile u while tile u - 4 is consumed, before that iteration's K/V request, so they
+  // have landed (and passed a barrier) when tile u's rows are requested two iterations later.
+  // Tiles past the list read a dummy address: every iteration requests the same number of loads.
   auto request_tokens = [&](int u) {
-    if (wave == 0) {
-      const int32_t* src = list + (u < n_ctx_tiles ? u * 64 : 0) + lane;
-      dma4(src, tok0 + (uint32_t)(u % TOK_SLOTS) * 256);
-    }
+    if (wave == 0) dma4(list, (uint32_t)((u < n_ctx_tiles ? u * 64 : 0) + lane) * 4u, tok0 + (uint32_t)(u % TOK_SLOTS) * 256);
   };
-  auto issue_tile = [&](int t) {
+  // rows 32 i + 4 wave + lq (i = 0, 1) of the tile, LDS piece lp of the row
+  const int lq = lane >> 4, lp = lane & 15;
+  auto request_tile = [&](int t) {
     const uint32_t sbase = ring0 + (uint32_t)(t % DMA_NS) * DMA_STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int rw = 4 * NW * i + 4 * wave;           // first of the wave's four rows (uniform)
+    for (int i = 0; i < 2; ++i) {
+      const int rw = 32 * i + 4 * wave;              // first of the wave's four rows (uniform)
       int tok;
       if (t < n_ctx_tiles) tok = max(tokring[(t % TOK_SLOTS) * 64 + rw + lq], 0);
       else                 tok = c0 + min((t - n_ctx_tiles) * 64 + rw + lq, L - 1);
       const int row = rw + lq;
-      const size_t off = (size_t)tok * 256;
-      dma16(Kb + off + ((lp ^ (row & 7)) << 4), sbase + (uint32_t)rw * 256);
-      dma16(Vb + off + ((lp ^ ((row & 3) << 1)) << 4), sbase + 16384u + (uint32_t)rw * 256);
+      const uint32_t off = (uint32_t)tok * 256u;
+      dma16(Kb, off + (uint32_t)((lp ^ (row & 15)) << 4), sbase + (uint32_t)rw * 256);
+      dma16(Vb, off + (uint32_t)((lp ^ ((row & 3) << 1)) << 4), sbase + 16384u + (uint32_t)rw * 256);
     }
   };
 
-  // query fragments (B operand of S^T = K Q^T)
-  uint4 qf[NQB][8];
+  // ---- query fragments: B operand of S^T = K Q^T; lane (l32, hf) holds Q[row l32][16 kk + 8 hf ..] ----
+  uint4 qf[8];
   {
     const uint16_t* Qb = reinterpret_cast<const uint16_t*>(a.q) + (size_t)bi * L * D.Hq * d;
+    const int row = min(r0 + l32, L - 1);
+    const uint16_t* qrow = Qb + ((size_t)row * D.Hq + head) * d;
 #pragma unroll
-    for (int nq = 0; nq < NQB; ++nq) {
-      const int row = min(r0 + nq * 32 + l32, L - 1);
-      const uint16_t* qrow = Qb + ((size_t)row * D.Hq + head) * d;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) qf[nq][kk] = *reinterpret_cast<const uint4*>(qrow + kk * 16 + hf * 8);
-    }
+    for (int kk = 0; kk < 8; ++kk) qf[kk] = *reinterpret_cast<const uint4*>(qrow + kk * 16 + hf * 8);
   }
-  f32x16_t o[4][NQB];
+  // The fragments are "used" here so that the compiler's wait for these loads sits before the
+  // loop: a wait for them inside the loop would also wait for every DMA request in flight.
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) asm volatile("" ::"v"(qf[kk].x), "v"(qf[kk].y), "v"(qf[kk].z), "v"(qf[kk].w));
+
+  f32x16_t o[4];
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-    for (int nq = 0; nq < NQB; ++nq)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[mb][nq][v] = 0.f;
-  float m_run[NQB], l_run[NQB];
-#pragma unroll
-  for (int nq = 0; nq < NQB; ++nq) { m_run[nq] = -1e30f; l_run[nq] = 0.f; }
-  const float sc = 1.4426950408889634f / sqrtf((float)d);
+    for (int v = 0; v < 16; ++v) o[mb][v] = 0.f;
+  float m_run = -1e30f, l_run = 0.f;
+  const float sc = 1.4426950408889634f / sqrtf((float)d);     // log2(e) / sqrt(d)
 
-  // per-lane pieces of the fragment addresses that do not depend on the tile
-  const int krow_sw = l32 & 7;                                   // K: piece ^ (row & 7), row = 32 kb + l32
+  // per-lane parts of the fragment addresses
+  // K: row l32 (+ 32 kb), piece (2 kk + hf) ^ (row & 15) = ((2 kk) ^ (row & 14)) | (hf ^ (row & 1))
+  const uint32_t kbase = (uint32_t)(l32 * 256 + ((hf ^ (l32 & 1)) << 4));
+  const uint32_t kswz = (uint32_t)((l32 & 14) << 4);
   const int vj = lane & 15, vgq = (lane >> 4) & 1;
-  const int vrow_in = 4 * hf + (vj >> 2);                        // row inside the 8-row group
+  const int vrow_in = 4 * hf + (vj >> 2);           // key row inside a group of 8
   const int vsw = (vrow_in & 3) << 1;
-  const int vpiece = 2 * vgq + ((vj & 3) >> 1), vhalf = vj & 1;
+  // V: d-block mb, piece (4 mb + p) ^ swizzle with p = 2 gq + (j & 3) / 2 < 4 and swizzle in bits 1..2
+  const uint32_t vbase = (uint32_t)(vrow_in * 256 + (((2 * vgq + ((vj & 3) >> 1)) ^ (vsw & 3)) << 4) + (vj & 1) * 8);
+  const uint32_t vswz = (uint32_t)((vsw & 4) << 4);
 
-  static_assert(DMA_NS == 4 && TOK_AHEAD == 6, "the vmcnt ladder below is written for four stages");
-  // prologue: tokens of tiles 0..2, then the steady-state pattern (tokens u + 6, K/V tile u + 3)
-  // for u = -3, -2, -1
-  for (int u = 0; u < 3; ++u) request_tokens(u);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  for (int u = 0; u < 3; ++u) {
-    request_tokens(u + 3);
-    if (u < n_tiles) issue_tile(u);
-  }
-  for (int t = 0; t < n_tiles; ++t) {
-    // loads requested after tile t's: those of the two following iterations
-    const int later = min(DMA_NS - 2, n_tiles - 1 - t);
-    if (wave == 0) {
-      if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT + 2) : "memory");
-      else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT + 2) : "memory");
-      else                 asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-    } else {
-      if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * LPT) : "memory");
-      else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LPT) : "memory");
-      else                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    __syncthreads();            // tile t has landed for every wave; tile t-1's stage is free
-    request_tokens(t + TOK_AHEAD);
-    if (t + DMA_NS - 1 < n_tiles) issue_tile(t + DMA_NS - 1);
-    const bool is_chunk = t >= n_ctx_tiles;
-    const int k0 = is_chunk ? (t - n_ctx_tiles) * 64 : 0;
-    if (is_chunk && k0 > r0 + QW - 1) continue;
-    if (r0 >= L) continue;
+  auto tile_visible = [&](int t) -> bool {          // uniform over the wave
+    if (r0 >= L) return false;
+    return !(t >= n_ctx_tiles && (t - n_ctx_tiles) * 64 > r0 + 31);
+  };
+
+  f32x16_t s[2];
+  // ---- S^T = K Q^T for tile t ----
+  auto scores = [&](int t) {
+    if (!tile_visible(t)) return;
     const unsigned char* Ks = ring + (t % DMA_NS) * DMA_STAGE_BYTES;
-    const unsigned char* Vs = Ks + 16384;
-    // ---- S^T = K Q^T ----
-    f32x16_t s[2][NQB];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int nq = 0; nq < NQB; ++nq)
+      for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+    // fragments in four batches (two kk each); two batches are in flight ahead of the products
+    uint4 kf[4][2][2];
+    auto read_batch = [&](int bt) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[kb][nq][v] = 0.f;
+      for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
+        for (int kb = 0; kb < 2; ++kb)
+          kf[bt][k2][kb] = *reinterpret_cast<const uint4*>(Ks + (kbase + (kswz ^ (uint32_t)((2 * (2 * bt + k2)) << 4))) + kb * 8192);
+    };
+    auto mfma_batch = [&](int bt) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const uint4 kf = *reinterpret_cast<const uint4*>(Ks + (kb * 32 + l32) * 256 + (((2 * kk + hf) ^ krow_sw) << 4));
+      for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-        for (int nq = 0; nq < NQB; ++nq)
-          s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf),
-                                                              __builtin_bit_cast(bf16x8_t, qf[nq][kk]),
-                                                              s[kb][nq], 0, 0, 0);
-      }
-    }
-    // ---- masks ----
+        for (int kb = 0; kb < 2; ++kb)
+          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[bt][k2][kb]),
+                                                          __builtin_bit_cast(bf16x8_t, qf[2 * bt + k2]), s[kb], 0, 0, 0);
+    };
+    read_batch(0);
+    read_batch(1);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_batch(0);
+    read_batch(2);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_batch(1);
+    read_batch(3);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_batch(2);
+    mfma_batch(3);
+  };
+  // ---- masks, online softmax (one query per lane pair), O^T += V^T P^T for tile t ----
+  auto softmax_pv = [&](int t) {
+    if (!tile_visible(t)) return;
+    const unsigned char* Vs = ring + (t % DMA_NS) * DMA_STAGE_BYTES + 16384;
+    const bool is_chunk = t >= n_ctx_tiles;
     if (is_chunk) {
-      if (k0 + 63 > r0) {
-#pragma unroll
-        for (int nq = 0; nq < NQB; ++nq) {
-          const int qi = r0 + nq * 32 + l32;
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int kp = k0 + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-              if (kp > qi) s[kb][nq][v] = -INFINITY;
-            }
-        }
-      }
-    } else if (t == n_ctx_tiles - 1 && (list_len & 63)) {
-      const int nvalid = list_len - t * 64;
-#pragma unroll
-      for (int nq = 0; nq < NQB; ++nq)
+      const int k0 = (t - n_ctx_tiles) * 64;
+      if (k0 + 63 > r0) {                           // the tile reaches past the wave's first row
+        const int qi = r0 + l32;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
-            const int kr = kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-            if (kr >= nvalid) s[kb][nq][v] = -INFINITY;
+            const int kp = k0 + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+            if (kp > qi) s[kb][v] = -INFINITY;
           }
-    }
-    // ---- online softmax (one query per lane pair) ----
-    uint4 pf[NQB][2][2];
+      }
+    } else if (t == n_ctx_tiles - 1 && (list_len & 63)) {       // ragged end of the list
+      const int nvalid = list_len - t * 64;
 #pragma unroll
-    for (int nq = 0; nq < NQB; ++nq) {
-      float mx = s[0][nq][0];
-#pragma unroll
-      for (int v = 1; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[0][nq][v]), s[0][nq][(v + 1) & 15]);
-#pragma unroll
-      for (int v = 0; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[1][nq][v]), s[1][nq][v + 1]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[nq], mx * sc);
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
-      const bool changed = m_new != m_run[nq];
-      m_run[nq] = m_new;
-      float ps = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        float pv[16];
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][v], sc, -m_new));
-          ps += pv[v];
+          const int kr = kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+          if (kr >= nvalid) s[kb][v] = -INFINITY;
         }
+    }
+    float mx = s[0][0];
 #pragma unroll
-        for (int a2 = 0; a2 < 2; ++a2) {
-          uint4 u;
-          u.x = pack_bf16x2(pv[8 * a2 + 0], pv[8 * a2 + 1]);
-          u.y = pack_bf16x2(pv[8 * a2 + 2], pv[8 * a2 + 3]);
-          u.z = pack_bf16x2(pv[8 * a2 + 4], pv[8 * a2 + 5]);
-          u.w = pack_bf16x2(pv[8 * a2 + 6], pv[8 * a2 + 7]);
-          pf[nq][kb][a2] = u;
-        }
+    for (int v = 1; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[0][v]), s[0][(v + 1) & 15]);
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[1][v]), s[1][v + 1]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx * sc);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const bool changed = m_new != m_run;
+    m_run = m_new;
+    float ps = 0.f;
+    uint4 pf[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      float pv[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][v], sc, -m_new));
+        ps += pv[v];
       }
-      l_run[nq] = l_run[nq] * alpha + ps;
-      if (__any(changed)) {
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) o[mb][nq][v] *= alpha;
+      for (int a2 = 0; a2 < 2; ++a2) {
+        uint4 u;
+        u.x = pack_bf16x2(pv[8 * a2 + 0], pv[8 * a2 + 1]);
+        u.y = pack_bf16x2(pv[8 * a2 + 2], pv[8 * a2 + 3]);
+        u.z = pack_bf16x2(pv[8 * a2 + 4], pv[8 * a2 + 5]);
+        u.w = pack_bf16x2(pv[8 * a2 + 6], pv[8 * a2 + 7]);
+        pf[kb][a2] = u;
       }
     }
-    // ---- O^T += V^T P^T ----
+    l_run = l_run * alpha + ps;
+    if (__any(changed)) {                           // the running maximum rarely moves after the first tiles
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[mb][v] *= alpha;
+    }
+    typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int a2 = 0; a2 < 2; ++a2)
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
-          const int rowb = kb * 32 + a2 * 16 + vrow_in;            // rd = 0; rd = 1 adds 8 rows
-          const int pc = ((4 * mb + vpiece) ^ vsw) << 4;
-          typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
-          const s16x4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4_ptr)(Vs + rowb * 256 + pc + vhalf * 8));
-          const s16x4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4_ptr)(Vs + (rowb + 8) * 256 + pc + vhalf * 8));
-          uint4 vf;
+          const unsigned char* pa = Vs + (vbase + (vswz ^ (uint32_t)((4 * mb) << 4))) + (kb * 32 + a2 * 16) * 256;
+          const s16x4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pa));
+          const s16x4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pa + 8 * 256));
           const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
+          uint4 vf;
           vf.x = u0.x; vf.y = u0.y; vf.z = u1.x; vf.w = u1.y;
-#pragma unroll
-          for (int nq = 0; nq < NQB; ++nq)
-            o[mb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf),
-                                                                __builtin_bit_cast(bf16x8_t, pf[nq][kb][a2]),
-                                                                o[mb][nq], 0, 0, 0);
+          o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf),
+                                                          __builtin_bit_cast(bf16x8_t, pf[kb][a2]), o[mb], 0, 0, 0);
         }
+  };
+
+  // ---- prologue: tokens of tiles 0 and 1, then the steady-state request pattern
+  //      (tokens u + 4, K/V tile u + 2) for u = -2, -1 ----
+  request_tokens(0);
+  request_tokens(1);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  request_tokens(2);
+  if (n_tiles > 0) request_tile(0);
+  request_tokens(3);
+  if (n_tiles > 1) request_tile(1);
+
+  // between two barriers: wait for tile t, then request tokens t + 4 and tile t + 2
+  auto advance = [&](int t) {
+    // requests issued after tile t's: wavefront 0's token request and tile t + 1
+    if (t + 1 < n_tiles) {
+      if (wave == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT + 1) : "memory");
+      else           asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT) : "memory");
+    } else {
+      if (wave == 0) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
+      else           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();            // tile t has landed for every wave; tile t - 2's stage is free
+    request_tokens(t + 4);
+    if (t + 2 < n_tiles) request_tile(t + 2);
+  };
+  if (!group_b) {
+    for (int t = 0; t < n_tiles; ++t) {
+      advance(t);
+      scores(t);
+      softmax_pv(t);
+    }
+  } else {
+    for (int t = 0; t < n_tiles; ++t) {
+      advance(t);
+      if (t > 0) softmax_pv(t - 1);
+      scores(t);
+    }
+    if (n_tiles > 0) softmax_pv(n_tiles - 1);
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the dummy token requests of the last iterations
+
   // ---- epilogue ----
   uint16_t* Ob = reinterpret_cast<uint16_t*>(a.out) + (size_t)bi * L * D.Hq * d;
+  const int qi = r0 + l32;
+  const float lt = l_run + __shfl_xor(l_run, 32, 64);
+  if (qi < L) {
+    const float inv = 1.f / lt;
+    uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
 #pragma unroll
-  for (int nq = 0; nq < NQB; ++nq) {
-    const int qi = r0 + nq * 32 + l32;
-    const float lt = l_run[nq] + __shfl_xor(l_run[nq], 32, 64);
-    if (qi < L) {
-      const float inv = 1.f / lt;
-      uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
+    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int a4 = 0; a4 < 4; ++a4) {
-          uint2 u;
-          u.x = pack_bf16x2(o[mb][nq][4 * a4 + 0] * inv, o[mb][nq][4 * a4 + 1] * inv);
-          u.y = pack_bf16x2(o[mb][nq][4 * a4 + 2] * inv, o[mb][nq][4 * a4 + 3] * inv);
-          *reinterpret_cast<uint2*>(orow + mb * 32 + 8 * a4 + 4 * hf) = u;
-        }
-      if (a.lse && hf == 0)
-        a.lse[((size_t)bi * L + qi) * D.Hq + head] = (m_run[nq] + log2f(lt)) * 0.6931471805599453f;
-    }
+      for (int a4 = 0; a4 < 4; ++a4) {
+        uint2 u;
+        u.x = pack_bf16x2(o[mb][4 * a4 + 0] * inv, o[mb][4 * a4 + 1] * inv);
+        u.y = pack_bf16x2(o[mb][4 * a4 + 2] * inv, o[mb][4 * a4 + 3] * inv);
+        *reinterpret_cast<uint2*>(orow + mb * 32 + 8 * a4 + 4 * hf) = u;
+      }
+    if (a.lse && hf == 0)
+      a.lse[((size_t)bi * L + qi) * D.Hq + head] = (m_run + log2f(lt)) * 0.6931471805599453f;
   }
 }
 
@@ -664,18 +447,16 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
   if (mfma_ok) {
     const int HG = D.G < 4 ? D.G : 4;
     const int gpk = D.G / HG;
-    constexpr int NQB = 1, NW = 8;
-    const int RPB = 32 * NQB * (NW / HG);
-    dim3 g((n_q + RPB - 1) / RPB, D.Hkv * gpk, seq_count);
+    const int RPB = 32 * (ATT_NW / HG);
+    dim3 g(D.Hkv * gpk, (n_q + RPB - 1) / RPB, seq_count);
     static bool attr_set = false;
     if (!attr_set) {
-      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_dma_kernel<NQB, NW>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,
-                                               DMA_NS * DMA_STAGE_BYTES + TOK_SLOTS * 256);
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, ATT_LDS_BYTES);
       if (e != hipSuccess) return e;
       attr_set = true;
     }
-    attend_bf16_dma_kernel<NQB, NW><<<g, 64 * NW, DMA_NS * DMA_STAGE_BYTES + TOK_SLOTS * 256, s>>>(a);
+    attend_bf16_kernel<<<g, 64 * ATT_NW, ATT_LDS_BYTES, s>>>(a);
   } else {
     dim3 g(n_q, D.Hq, seq_count);
     if (D.dtype == LTRI_BF16) attend_simple_kernel<LTRI_BF16><<<g, 64, 0, s>>>(a);

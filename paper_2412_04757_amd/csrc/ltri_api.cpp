@@ -50,6 +50,8 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   if (c.dtype != LTRI_F32 && c.dtype != LTRI_BF16) return LTRI_EINVAL;
   if (c.head_dim != 64 && c.head_dim != 128) return LTRI_EINVAL;
   if (c.dtype == LTRI_BF16 && c.head_dim != 128) return LTRI_EINVAL;
+  // the bf16 attention kernel addresses a KV head's rows with 32-bit byte offsets
+  if (c.dtype == LTRI_BF16 && c.max_tokens >= (1ll << 24)) return LTRI_EINVAL;
   if (c.n_layers < 1 || c.n_seqs < 1 || c.max_tokens < 1 || c.max_tokens > (1ll << 30)) return LTRI_EINVAL;
   if (c.chunk_max < 1 || c.chunk_max > SEG_MAX_L) return LTRI_EINVAL;
   if (c.n_sink < 0 || c.window < 0 || c.k_max < 0 || c.budget_tokens < 0) return LTRI_EINVAL;
@@ -107,6 +109,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.lse = o;    o = align_up(o + (size_t)P * G * Lp * 8, 256);
   // query-span representatives are needed for every sequence of a batched retrieve
   CL.qrep = o;   o = align_up(o + (size_t)c.n_seqs * c.n_kv_heads * Lp * D.d * D.elt, 256);
+  CL.qpart = o;  o = align_up(o + (size_t)P * (Lp / 128 + Lp) * D.d * 8, 256);
   CL.bounds = o; o = align_up(o + (size_t)c.n_kv_heads * (c.chunk_max + 2) * 4, 256);
   CL.total = o;
   CL.max_problems = P;
@@ -164,7 +167,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->dc = DevScratch{(double*)(t + CL.rowsum), (double*)(t + CL.csuf), (double*)(t + CL.tsum),
                      (double*)(t + CL.rcar), (double*)(t + CL.ccar), (double*)(t + CL.pscore),
                      (int32_t*)(t + CL.px), (double*)(t + CL.lse), (void*)(t + CL.qrep),
-                     (int32_t*)(t + CL.bounds)};
+                     (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds)};
   const size_t n = (size_t)D.n_layers * D.n_seqs;
   c->n_tokens.assign(n, 0);
   c->last_len.assign(n, 0);
@@ -363,7 +366,7 @@ int32_t ltri_retrieve(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq
   if (!c->dry) {
     long long bound = 0;
     for (int s = 0; s < seq_count; ++s) bound = std::max(bound, c->span_bound[ls_index(c, layer, seq_begin + s)]);
-    r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, q, layer, bp, seq_count, n_q, (int)bound, sel_ids,
+    r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound, sel_ids,
                                      sel_cnt, c->stream), "retrieve");
     if (r != LTRI_OK) return r;
   }

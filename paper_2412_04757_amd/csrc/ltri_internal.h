@@ -48,7 +48,8 @@ struct ScratchLayout {
   size_t pscore;   // double [P][ntiles][128]
   size_t px;       // int32  [P][ntiles][128]
   size_t lse;      // double [P][G][Lp]    (SOFTMAX map only)
-  size_t qrep;     // dtype  [P][Lp][d]
+  size_t qrep;     // dtype  [n_seqs * Hkv][Lp][d]
+  size_t qpart;    // double [P][Lp / 128 + Lp][d]  sums of 128-token pieces of query spans
   size_t bounds;   // int32  [Hkv][chunk_max + 1] + int32 [Hkv]  (append_with_spans)
   size_t total;
   int    max_problems;  // P the buffer was sized for
@@ -78,7 +79,7 @@ struct DevState {
 };
 struct DevScratch {
   double* rowsum; double* csuf; double* tsum; double* rcar; double* ccar;
-  double* pscore; int32_t* px; double* lse; void* qrep; int32_t* bounds;
+  double* pscore; int32_t* px; double* lse; void* qrep; double* qpart; int32_t* bounds;
 };
 
 // ---- launchers (each returns the hipError_t of the launch) ----
@@ -95,8 +96,8 @@ hipError_t launch_append_bounds(const Dims& D, const DevState& st, const DevScra
                                 int seq, int c0, int n_new, hipStream_t s);
 hipError_t launch_rep_keys(const Dims& D, const DevState& st, const void* k_arena, int layer,
                            const BatchPos& bp, int seq_count, int n_new, hipStream_t s);
-hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, const void* q,
-                           int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
+hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,
+                           const void* q, int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
                            int32_t* sel_ids_out, int32_t* sel_cnt_out, hipStream_t s);
 hipError_t launch_force_list(const Dims& D, const DevState& st, int layer, int seq, int kv_head,
                              int n_ids, hipStream_t s);

@@ -13,6 +13,7 @@ namespace ltri {
 struct RetArgs {
   Dims D; DevState st; DevScratch sc; const void* q;
   int layer; int seq_count; int n_q; int Lp;
+  int batch_off; int units_cap;          // two-stage query representatives (long chunks)
   int32_t* sel_ids_out; int32_t* sel_cnt_out;
   BatchPos bp;
 };
@@ -35,6 +36,74 @@ __global__ __launch_bounds__(1024) void qrep_kernel(RetArgs a) {
     const int start = a.st.span_start[(size_t)slot * D.max_spans + sid] - c0;   // chunk-local
     const int len = a.st.span_len[(size_t)slot * D.max_spans + sid];
     span_mean_block<DT>(Qb + (size_t)start * D.Hq * d, (size_t)D.Hq * d, D.G, len, d, out + (size_t)qs * d, part);
+  }
+}
+
+// Long chunks: a query span is cut into pieces of QREP_PIECE tokens, one workgroup per piece
+// (so that a 1024-token span is read by eight compute units instead of one); a second kernel
+// adds the pieces of every span in ascending order.
+constexpr int QREP_PIECE = 128;
+
+// Piece u of the chunk's spans -> (span q, first token, token count); returns false past the end.
+__device__ __forceinline__ bool qrep_unit(const int32_t* slen, int nsp, int u, int& q, int& t0, int& nt) {
+  int acc = 0;
+  for (q = 0; q < nsp; ++q) {
+    const int len = slen[q];
+    const int parts = (len + QREP_PIECE - 1) / QREP_PIECE;
+    if (u < acc + parts) {
+      t0 = (u - acc) * QREP_PIECE;
+      nt = min(QREP_PIECE, len - t0);
+      return true;
+    }
+    acc += parts;
+  }
+  return false;
+}
+
+template <int DT>
+__global__ __launch_bounds__(1024) void qrep_partial_kernel(RetArgs a) {
+  typedef typename Elt<DT>::type T;
+  __shared__ double part[16][128];
+  const Dims& D = a.D;
+  const int p = blockIdx.y, bi = a.batch_off + p / D.Hkv, h = p % D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP], c0 = meta[META_CHUNK_START];
+  const int d = D.d;
+  const T* Qb = reinterpret_cast<const T*>(a.q) + (size_t)bi * a.n_q * D.Hq * d + (size_t)h * D.G * d;
+  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans + first;
+  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans + first;
+  double* psum = a.sc.qpart + (size_t)p * a.units_cap * d;
+  for (int u = blockIdx.x; u < a.units_cap; u += gridDim.x) {
+    int q, t0, nt;
+    if (!qrep_unit(slen, nsp, u, q, t0, nt)) break;            // uniform over the block
+    const int start = sstart[q] - c0 + t0;                      // chunk-local
+    span_mean_block<DT>(Qb + (size_t)start * D.Hq * d, (size_t)D.Hq * d, D.G, nt, d, nullptr, part,
+                        psum + (size_t)u * d);
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(128) void qrep_final_kernel(RetArgs a) {
+  typedef typename Elt<DT>::type T;
+  const Dims& D = a.D;
+  const int p = blockIdx.y, bi = a.batch_off + p / D.Hkv, h = p % D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP];
+  const int d = D.d, c = threadIdx.x;
+  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans + first;
+  const double* psum = a.sc.qpart + (size_t)p * a.units_cap * d;
+  T* out = reinterpret_cast<T*>(a.sc.qrep) + (size_t)(bi * D.Hkv + h) * a.Lp * d;
+  if (c >= d) return;
+  for (int q = blockIdx.x; q < nsp; q += gridDim.x) {
+    int u0 = 0;
+    for (int q2 = 0; q2 < q; ++q2) u0 += (slen[q2] + QREP_PIECE - 1) / QREP_PIECE;
+    const int len = slen[q];
+    const int parts = (len + QREP_PIECE - 1) / QREP_PIECE;
+    double s = 0.0;
+    for (int k = 0; k < parts; ++k) s += psum[(size_t)(u0 + k) * d + c];
+    out[(size_t)q * d + c] = Elt<DT>::from_f64(s / (double)len);
   }
 }
 
@@ -241,8 +310,8 @@ __global__ __launch_bounds__(1024) void force_list_kernel(ForceArgs a) {
   emit_selection(D, a.st, slot, selmask, n, nullptr, nullptr);
 }
 
-hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, const void* q,
-                           int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
+hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,
+                           const void* q, int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
                            int32_t* sel_ids_out, int32_t* sel_cnt_out, hipStream_t s) {
   RetArgs a;
   a.D = D; a.st = st; a.sc = sc; a.q = q; a.layer = layer; a.seq_count = seq_count; a.n_q = n_q;
@@ -250,9 +319,23 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
   a.sel_ids_out = sel_ids_out; a.sel_cnt_out = sel_cnt_out; a.bp = bp;
   const int P = seq_count * D.Hkv;
   const bool bf = D.dtype == LTRI_BF16;
-  dim3 gq(n_q < 64 ? n_q : 64, P);
-  if (bf) qrep_kernel<LTRI_BF16><<<gq, 1024, 0, s>>>(a);
-  else    qrep_kernel<LTRI_F32><<<gq, 1024, 0, s>>>(a);
+  a.batch_off = 0;
+  a.units_cap = n_q / QREP_PIECE + n_q;                  // pieces of all spans of a chunk, at most
+  if (n_q > QREP_PIECE) {
+    const int per = sc_max_problems / D.Hkv;               // sequences the piece buffer holds
+    for (int off = 0; off < seq_count; off += per) {
+      const int cnt = seq_count - off < per ? seq_count - off : per;
+      a.batch_off = off;
+      dim3 gp(64, cnt * D.Hkv), gf(n_q < 64 ? n_q : 64, cnt * D.Hkv);
+      if (bf) { qrep_partial_kernel<LTRI_BF16><<<gp, 1024, 0, s>>>(a); qrep_final_kernel<LTRI_BF16><<<gf, 128, 0, s>>>(a); }
+      else    { qrep_partial_kernel<LTRI_F32><<<gp, 1024, 0, s>>>(a);  qrep_final_kernel<LTRI_F32><<<gf, 128, 0, s>>>(a); }
+    }
+    a.batch_off = 0;
+  } else {
+    dim3 gq(n_q < 64 ? n_q : 64, P);
+    if (bf) qrep_kernel<LTRI_BF16><<<gq, 1024, 0, s>>>(a);
+    else    qrep_kernel<LTRI_F32><<<gq, 1024, 0, s>>>(a);
+  }
   int gx = (span_bound + 3) / 4;
   if (gx < 1) gx = 1;
   if (gx > 256) gx = 256;

@@ -250,9 +250,12 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   const int p = blockIdx.y;
   int I, J;
   tile_decode(blockIdx.x, I, J);
-  compute_tile<DT>(a, p, I, J, Ms);
   const int tid = threadIdx.x, L = a.n_new;
-  if (tid < 64) rc[tid] = a.sc.rcar[((size_t)p * a.nb + J) * a.Lp + I * 64 + tid];
+  // carries are requested before the tile is computed so that their latency hides behind it
+  const double rc_pre = tid < 64 ? a.sc.rcar[((size_t)p * a.nb + J) * a.Lp + I * 64 + tid] : 0.0;
+  const double cc_pre = a.sc.ccar[((size_t)p * a.nb + I) * a.Lp + J * 64 + (tid & 63)];
+  compute_tile<DT>(a, p, I, J, Ms);
+  if (tid < 64) rc[tid] = rc_pre;
   __syncthreads();
   {                                     // rows: suffix sums towards the left, four threads per row
     const int r = tid >> 2, qd = tid & 3;
@@ -277,7 +280,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
     const int x = J * 64 + c;
     const int n_h = a.q_seg ? a.D.G : 1;
     const double th = (double)a.D.theta * (double)n_h;
-    double run = a.sc.ccar[((size_t)p * a.nb + I) * a.Lp + x];
+    double run = cc_pre;
     for (int q2 = 0; q2 < qd; ++q2) run += qsum[c][q2];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -376,11 +379,24 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
       for (int bb = b; bb >= b - 1 && bb >= 0; --bb) {
         const int sloc = s - 64 * bb;
         if (sloc > 126) continue;
-        for (int J = max(0, bb - (nb - 1)); 2 * J <= bb; ++J) {
-          const int I = bb - J;
-          const int t = I * (I + 1) / 2 + J;
-          const double v = pscore[(size_t)t * 128 + sloc];
-          const int x = px[(size_t)t * 128 + sloc];
+        // at most 16 tiles lie on one block anti-diagonal; all their entries are loaded before
+        // the comparison chain so that the loads are in flight together
+        const int J0 = max(0, bb - (nb - 1));
+        double vs[SEG_MAX_NB / 2];
+        int xs[SEG_MAX_NB / 2];
+#pragma unroll
+        for (int q = 0; q < SEG_MAX_NB / 2; ++q) {
+          const int J = J0 + q;
+          const bool ok = 2 * J <= bb;
+          const int Jc = ok ? J : J0, I = bb - Jc;
+          const size_t idx = (size_t)(I * (I + 1) / 2 + Jc) * 128 + sloc;
+          vs[q] = pscore[idx];
+          xs[q] = ok ? px[idx] : -1;
+        }
+#pragma unroll
+        for (int q = 0; q < SEG_MAX_NB / 2; ++q) {
+          const double v = vs[q];
+          const int x = xs[q];
           if (x >= 0 && (v > best || (v == best && x > bx))) { best = v; bx = x; }
         }
       }

@@ -10,11 +10,13 @@ namespace ltri {
 
 // Accumulates rows r = 0 .. n_rows-1, row r = `inner` consecutive d-vectors of token r / inner:
 // address base + (r / inner) * tok_stride + (r % inner) * d. Writes mean over tokens (sum over
-// all rows divided by n_tokens) to out[0..d). Called by all 1024 threads of a workgroup.
+// all rows divided by n_tokens) to out[0..d), or, when out_sum is given, the undivided fp64
+// sums to out_sum[0..d). Called by all 1024 threads of a workgroup.
 template <int DT>
 __device__ __forceinline__ void span_mean_block(const typename Elt<DT>::type* base, size_t tok_stride,
                                                 int inner, int n_tokens, int d,
-                                                typename Elt<DT>::type* out, double (*part)[128]) {
+                                                typename Elt<DT>::type* out, double (*part)[128],
+                                                double* out_sum = nullptr) {
   typedef typename Elt<DT>::type T;
   constexpr int EPP = 16 / (int)sizeof(T);           // elements per 16-byte piece
   const int R = d / EPP;                             // lanes per d-vector (16 or 32)
@@ -59,7 +61,8 @@ __device__ __forceinline__ void span_mean_block(const typename Elt<DT>::type* ba
     double s = 0.0;
 #pragma unroll
     for (int w = 0; w < 16; ++w) s += part[w][threadIdx.x];
-    out[threadIdx.x] = Elt<DT>::from_f64(s / (double)n_tokens);
+    if (out_sum) out_sum[threadIdx.x] = s;          // raw sum of a piece of a span
+    else         out[threadIdx.x] = Elt<DT>::from_f64(s / (double)n_tokens);
   }
   __syncthreads();
 }
