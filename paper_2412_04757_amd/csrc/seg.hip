@@ -358,7 +358,7 @@ __device__ void append_spans(const Dims& D, const DevState& st, int slot, int c0
 __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
   __shared__ uint64_t k1[4096];
   __shared__ uint32_t k2[4096];
-  __shared__ int s_ncand, s_nkept, s_wtot[16];
+  __shared__ int s_ncand, s_nkept, s_done, s_wtot[16];
   const Dims& D = a.D;
   const int p = blockIdx.x, sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
   const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
@@ -476,43 +476,73 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
     for (int r = 0; r < 4; ++r) k2[tid * 4 + r] = e2[r];
   }
   __syncthreads();
-  // greedy NMS by the first wavefront; the kept list overwrites k1 (scores are no longer needed)
+  // Greedy NMS in rounds of 1024 candidates (in sorted order). All threads test their candidate
+  // against the intervals kept so far; the survivors are compacted in order and the first
+  // wavefront resolves them among themselves, 64 at a time. With few, large spans almost every
+  // candidate dies in the parallel test. The kept list and the survivor list overwrite k1
+  // (the scores are no longer needed).
   volatile uint32_t* kept = reinterpret_cast<volatile uint32_t*>(k1);
-  if (tid < 64) {
-    const int lane = tid, ncand = s_ncand, max_keep = D.max_keep;
+  volatile uint32_t* alist = kept + 4096;
+  {
+    const int lane = tid & 63, wave = tid >> 6;
+    const int ncand = s_ncand, max_keep = D.max_keep;
     const float phi = D.phi;
-    int nkept = 0;
-    bool done = false;
-    for (int base = 0; base < ncand && !done; base += 64) {
-      const int idx = base + lane;
+    if (tid == 0) s_done = 0;
+    __syncthreads();
+    for (int base = 0; base < ncand; base += 1024) {
+      if (s_done) break;                                   // uniform: written before the last barrier
+      const int idx = base + tid;
       const bool valid = idx < ncand;
       const uint32_t xy = valid ? k2[idx] : 0u;
       const int x = (int)(xy >> 16), y = (int)(xy & 0xFFFFu);
       bool alive = valid;
-      for (int q = 0; q < nkept; ++q) {
+      const int nk0 = s_nkept;
+      for (int q = 0; q < nk0; ++q) {
         const uint32_t kk = kept[q];
         if (alive && nms_suppressed(x, y, (int)(kk >> 16), (int)(kk & 0xFFFFu), phi)) alive = false;
       }
-      uint64_t m = __ballot(alive);
-      while (m) {
-        const int b = __ffsll((unsigned long long)m) - 1;
-        const int bx = __shfl(x, b, 64), by = __shfl(y, b, 64);
-        if (lane == 0) kept[nkept] = ((uint32_t)bx << 16) | (uint32_t)by;
-        ++nkept;
-        if (max_keep > 0 && nkept >= max_keep) { done = true; break; }
-        if (alive && lane > b && nms_suppressed(x, y, bx, by, phi)) alive = false;
-        const uint64_t upto = (b == 63) ? ~0ull : ((2ull << b) - 1ull);
-        m = __ballot(alive) & ~upto;
+      const uint64_t am = __ballot(alive);
+      if (lane == 0) s_wtot[wave] = __popcll(am);
+      __syncthreads();
+      int off = 0, total = 0;
+      for (int w = 0; w < 16; ++w) { if (w < wave) off += s_wtot[w]; total += s_wtot[w]; }
+      if (alive) alist[off + __popcll(am & ((1ull << lane) - 1ull))] = xy;
+      __syncthreads();
+      if (tid < 64) {
+        int nkept = nk0;
+        bool done = false;
+        for (int cb = 0; cb < total && !done; cb += 64) {
+          const int i = cb + lane;
+          const bool v2 = i < total;
+          const uint32_t xy2 = v2 ? alist[i] : 0u;
+          const int x2 = (int)(xy2 >> 16), y2 = (int)(xy2 & 0xFFFFu);
+          bool al = v2;
+          for (int q = nk0; q < nkept; ++q) {              // intervals kept earlier in this round
+            const uint32_t kk = kept[q];
+            if (al && nms_suppressed(x2, y2, (int)(kk >> 16), (int)(kk & 0xFFFFu), phi)) al = false;
+          }
+          uint64_t m = __ballot(al);
+          while (m) {
+            const int b2 = __ffsll((unsigned long long)m) - 1;
+            const int bx = __shfl(x2, b2, 64), by = __shfl(y2, b2, 64);
+            if (lane == 0) kept[nkept] = ((uint32_t)bx << 16) | (uint32_t)by;
+            ++nkept;
+            if (max_keep > 0 && nkept >= max_keep) { done = true; break; }
+            if (al && lane > b2 && nms_suppressed(x2, y2, bx, by, phi)) al = false;
+            const uint64_t upto = (b2 == 63) ? ~0ull : ((2ull << b2) - 1ull);
+            m = __ballot(al) & ~upto;
+          }
+        }
+        if (lane == 0) { s_nkept = nkept; s_done = done ? 1 : 0; }
       }
+      __syncthreads();
     }
-    if (lane == 0) s_nkept = nkept;
   }
   __syncthreads();
   // cuts: 0, L and both ends of every kept interval
   uint8_t* flags = reinterpret_cast<uint8_t*>(k2);
   int* cutlist = reinterpret_cast<int*>(reinterpret_cast<uint8_t*>(k2) + 2304);
   const int nkept = s_nkept;
-  uint32_t my_kept[4];
   // k1 (kept list) and k2 (flags) are distinct arrays, so reading kept while writing flags is safe
   for (int i = tid; i <= L; i += blockDim.x) flags[i] = (i == 0 || i == L) ? 1 : 0;
   __syncthreads();
@@ -521,7 +551,6 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
     flags[kk >> 16] = 1;
     flags[(kk & 0xFFFFu) + 1] = 1;
   }
-  (void)my_kept;
   __syncthreads();
   // enumerate the set flags in increasing order: each wave scans a contiguous segment
   const int lane = tid & 63, wave = tid >> 6;
