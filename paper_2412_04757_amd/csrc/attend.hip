@@ -9,6 +9,7 @@
 // statistics need a single cross-lane exchange and the probabilities are already laid out as
 // the B operand of O^T = V^T P^T.
 #include "device_common.h"
+#include <type_traits>
 
 namespace ltri {
 
@@ -29,7 +30,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 // ---- bf16 kernel ----
 // K and V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane, no
-// registers in between) through a ring of four stages, so two tiles are in flight while one is
+// registers in between) through a ring of four stages, so three tiles are in flight while one is
 // being consumed and a single barrier per tile suffices. Both tiles keep the row-major [key][d]
 // layout of the arena; inside a 256-byte row the sixteen 16-byte pieces are permuted (XOR with a
 // function of the row) so that the fragment reads are free of bank conflicts; the permutation is
@@ -40,16 +41,19 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // The DMA is issued through inline assembly because the compiler would otherwise wait for ALL
 // outstanding DMA before any LDS read; completion is awaited by hand with s_waitcnt vmcnt(n),
 // n = DMA loads requested later than the tile about to be used.
-// The eight wavefronts form two groups that share the SIMDs pairwise. Group A runs
-// scores -> softmax -> PV on tile t between two barriers; group B runs softmax and PV of tile
-// t - 1 first and the scores of tile t last. While one group is in its softmax (vector ALU) the
-// other is on the matrix cores.
+// The tile loop is cut into segments (context tiles, the ragged last context tile, chunk tiles
+// below the diagonal, chunk tiles on the diagonal, tiles this wavefront cannot see) so that the
+// body of each segment is straight-line code, with the masks compiled in or out.
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
-constexpr int ATT_NW = 8;                       // wavefronts per workgroup
+#ifndef ATT_NQB
+#define ATT_NQB 1
+#endif
+#ifndef ATT_NW
+#define ATT_NW 8
+#endif
 constexpr int DMA_NS = 4;                       // ring stages
 constexpr int DMA_STAGE_BYTES = 32768;          // K tile 16 KB + V tile 16 KB
-constexpr int DMA_LPT = 4;                      // K/V requests per lane and tile
 constexpr int TOK_SLOTS = 8;                    // ring of 64-entry token tiles
 constexpr int ATT_LDS_BYTES = DMA_NS * DMA_STAGE_BYTES + TOK_SLOTS * 256;
 
@@ -62,13 +66,26 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t off, uint32_t ld
   asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_wave_base), "v"(off), "s"(base) : "m0");
 }
 
-__global__ __launch_bounds__(64 * ATT_NW) void attend_bf16_kernel(AttArgs a) {
-  constexpr int NW = ATT_NW;
+enum : int { MASK_NONE = 0, MASK_LIST_END = 1, MASK_CAUSAL = 2 };
+
+// max over lanes l and l ^ 32 without an LDS round trip: the swap leaves the low half of v in
+// both halves of r[0] and the high half in both halves of r[1]
+__device__ __forceinline__ float pair_max(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// NW wavefronts per workgroup, each with NQB blocks of 32 query rows.
+template <int NQB, int NW>
+__global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
+  constexpr int QW = 32 * NQB;
+  constexpr int NI = 16 / NW;                       // DMA row groups per wave and tile
+  constexpr int DMA_LPT = 2 * NI;                   // K/V requests per lane and tile
   extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
   const Dims& D = a.D;
   const int HG = D.G < 4 ? D.G : 4;                 // heads of the group handled by this block
-  const int RS = NW / HG;                           // 32-row sub-tiles per block
-  const int RPB = 32 * RS;                          // query rows per block
+  const int RS = NW / HG;                           // row sub-tiles per block
+  const int RPB = QW * RS;                          // query rows per block
   const int gpk = D.G / HG;                         // blocks per KV head
   // KV head along x: consecutive workgroup ids go to different XCDs, so all query tiles of one
   // KV head run on one XCD and share its K/V rows in that XCD's L2
@@ -80,8 +97,7 @@ __global__ __launch_bounds__(64 * ATT_NW) void attend_bf16_kernel(AttArgs a) {
   const int l32 = lane & 31, hf = lane >> 5;
   const int head = h * D.G + gsub * HG + (wave % HG);
   const int rb0 = blockIdx.y * RPB;                 // first row of the block
-  const int r0 = rb0 + (wave / HG) * 32;            // first row of this wave
-  const bool group_b = wave >= NW / 2;
+  const int r0 = rb0 + (wave / HG) * QW;            // first row of this wave
   const int slot = slot_of(D, a.layer, seq, h);
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.k_arena) + arena_off(D, slot) * 2;
   const unsigned char* Vb = reinterpret_cast<const unsigned char*>(a.v_arena) + arena_off(D, slot) * 2;
@@ -98,19 +114,19 @@ __global__ __launch_bounds__(64 * ATT_NW) void attend_bf16_kernel(AttArgs a) {
 
   // ---- requests ----
   // Token ids of the context tiles travel through LDS as well: wavefront 0 requests the 64 list
-  // entries of tile u while tile u - 4 is consumed, before that iteration's K/V request, so they
-  // have landed (and passed a barrier) when tile u's rows are requested two iterations later.
+  // entries of tile u in iteration u - 6, before that iteration's K/V request, so they have
+  // landed (and passed a barrier) when tile u's rows are requested three iterations later.
   // Tiles past the list read a dummy address: every iteration requests the same number of loads.
   auto request_tokens = [&](int u) {
     if (wave == 0) dma4(list, (uint32_t)((u < n_ctx_tiles ? u * 64 : 0) + lane) * 4u, tok0 + (uint32_t)(u % TOK_SLOTS) * 256);
   };
-  // rows 32 i + 4 wave + lq (i = 0, 1) of the tile, LDS piece lp of the row
+  // rows 4 NW i + 4 wave + lq (i < NI) of the tile, LDS piece lp of the row
   const int lq = lane >> 4, lp = lane & 15;
   auto request_tile = [&](int t) {
     const uint32_t sbase = ring0 + (uint32_t)(t % DMA_NS) * DMA_STAGE_BYTES;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int rw = 32 * i + 4 * wave;              // first of the wave's four rows (uniform)
+    for (int i = 0; i < NI; ++i) {
+      const int rw = 4 * NW * i + 4 * wave;          // first of the wave's four rows (uniform)
       int tok;
       if (t < n_ctx_tiles) tok = max(tokring[(t % TOK_SLOTS) * 64 + rw + lq], 0);
       else                 tok = c0 + min((t - n_ctx_tiles) * 64 + rw + lq, L - 1);
@@ -120,27 +136,53 @@ __global__ __launch_bounds__(64 * ATT_NW) void attend_bf16_kernel(AttArgs a) {
       dma16(Vb, off + (uint32_t)((lp ^ ((row & 3) << 1)) << 4), sbase + 16384u + (uint32_t)rw * 256);
     }
   };
+  // top of iteration t: wait until tile t has landed, barrier, request tokens t + 6 and tile t + 3
+  auto advance = [&](int t) {
+    const int later = min(DMA_NS - 2, n_tiles - 1 - t);         // tiles requested after tile t
+    if (wave == 0) {                                             // also one token request per iteration
+      if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_LPT + 2) : "memory");
+      else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT + 2) : "memory");
+      else                 asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    } else {
+      if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_LPT) : "memory");
+      else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT) : "memory");
+      else                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    __syncthreads();            // tile t is in LDS for every wave; tile t - 1's stage is free
+    request_tokens(t + 6);
+    if (t + DMA_NS - 1 < n_tiles) request_tile(t + DMA_NS - 1);
+  };
 
   // ---- query fragments: B operand of S^T = K Q^T; lane (l32, hf) holds Q[row l32][16 kk + 8 hf ..] ----
-  uint4 qf[8];
+  uint4 qf[NQB][8];
   {
     const uint16_t* Qb = reinterpret_cast<const uint16_t*>(a.q) + (size_t)bi * L * D.Hq * d;
-    const int row = min(r0 + l32, L - 1);
-    const uint16_t* qrow = Qb + ((size_t)row * D.Hq + head) * d;
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) qf[kk] = *reinterpret_cast<const uint4*>(qrow + kk * 16 + hf * 8);
+    for (int nq = 0; nq < NQB; ++nq) {
+      const int row = min(r0 + nq * 32 + l32, L - 1);
+      const uint16_t* qrow = Qb + ((size_t)row * D.Hq + head) * d;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) qf[nq][kk] = *reinterpret_cast<const uint4*>(qrow + kk * 16 + hf * 8);
+    }
   }
   // The fragments are "used" here so that the compiler's wait for these loads sits before the
   // loop: a wait for them inside the loop would also wait for every DMA request in flight.
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) asm volatile("" ::"v"(qf[kk].x), "v"(qf[kk].y), "v"(qf[kk].z), "v"(qf[kk].w));
+  for (int nq = 0; nq < NQB; ++nq)
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+      asm volatile("" ::"v"(qf[nq][kk].x), "v"(qf[nq][kk].y), "v"(qf[nq][kk].z), "v"(qf[nq][kk].w));
 
-  f32x16_t o[4];
+  f32x16_t o[4][NQB];
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) o[mb][v] = 0.f;
-  float m_run = -1e30f, l_run = 0.f;
+    for (int nq = 0; nq < NQB; ++nq)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[mb][nq][v] = 0.f;
+  float m_run[NQB], l_run[NQB];
+#pragma unroll
+  for (int nq = 0; nq < NQB; ++nq) { m_run[nq] = -1e30f; l_run[nq] = 0.f; }
   const float sc = 1.4426950408889634f / sqrtf((float)d);     // log2(e) / sqrt(d)
 
   // per-lane parts of the fragment addresses
@@ -154,112 +196,108 @@ __global__ __launch_bounds__(64 * ATT_NW) void attend_bf16_kernel(AttArgs a) {
   const uint32_t vbase = (uint32_t)(vrow_in * 256 + (((2 * vgq + ((vj & 3) >> 1)) ^ (vsw & 3)) << 4) + (vj & 1) * 8);
   const uint32_t vswz = (uint32_t)((vsw & 4) << 4);
 
-  auto tile_visible = [&](int t) -> bool {          // uniform over the wave
-    if (r0 >= L) return false;
-    return !(t >= n_ctx_tiles && (t - n_ctx_tiles) * 64 > r0 + 31);
-  };
-
-  f32x16_t s[2];
-  // ---- S^T = K Q^T for tile t ----
-  auto scores = [&](int t) {
-    if (!tile_visible(t)) return;
+  // ---- one tile: S^T = K Q^T, masks, online softmax (one query per lane pair), O^T += V^T P^T ----
+  auto tile = [&](int t, auto mask_kind) {
+    constexpr int MK = decltype(mask_kind)::value;
     const unsigned char* Ks = ring + (t % DMA_NS) * DMA_STAGE_BYTES;
+    const unsigned char* Vs = Ks + 16384;
+    f32x16_t s[2][NQB];
+    {
+      // fragments in four batches (two kk each); two batches are in flight ahead of the products
+      uint4 kf[4][2][2];
+      auto read_batch = [&](int bt) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+        for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-    // fragments in four batches (two kk each); two batches are in flight ahead of the products
-    uint4 kf[4][2][2];
-    auto read_batch = [&](int bt) {
+          for (int kb = 0; kb < 2; ++kb)
+            kf[bt][k2][kb] = *reinterpret_cast<const uint4*>(Ks + (kbase + (kswz ^ (uint32_t)((2 * (2 * bt + k2)) << 4))) + kb * 8192);
+      };
+      read_batch(0);
+      read_batch(1);
+      const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2)
+      for (int bt = 0; bt < 4; ++bt) {
+        if (bt + 2 < 4) read_batch(bt + 2);
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-          kf[bt][k2][kb] = *reinterpret_cast<const uint4*>(Ks + (kbase + (kswz ^ (uint32_t)((2 * (2 * bt + k2)) << 4))) + kb * 8192);
-    };
-    auto mfma_batch = [&](int bt) {
+        for (int k2 = 0; k2 < 2; ++k2)
 #pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2)
+          for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-          s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[bt][k2][kb]),
-                                                          __builtin_bit_cast(bf16x8_t, qf[2 * bt + k2]), s[kb], 0, 0, 0);
-    };
-    read_batch(0);
-    read_batch(1);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_batch(0);
-    read_batch(2);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_batch(1);
-    read_batch(3);
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_batch(2);
-    mfma_batch(3);
-  };
-  // ---- masks, online softmax (one query per lane pair), O^T += V^T P^T for tile t ----
-  auto softmax_pv = [&](int t) {
-    if (!tile_visible(t)) return;
-    const unsigned char* Vs = ring + (t % DMA_NS) * DMA_STAGE_BYTES + 16384;
-    const bool is_chunk = t >= n_ctx_tiles;
-    if (is_chunk) {
+            for (int nq = 0; nq < NQB; ++nq)
+              s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[bt][k2][kb]),
+                                                                  __builtin_bit_cast(bf16x8_t, qf[nq][2 * bt + k2]),
+                                                                  (bt == 0 && k2 == 0) ? zero : s[kb][nq], 0, 0, 0);
+      }
+    }
+    if constexpr (MK == MASK_CAUSAL) {
       const int k0 = (t - n_ctx_tiles) * 64;
-      if (k0 + 63 > r0) {                           // the tile reaches past the wave's first row
-        const int qi = r0 + l32;
+#pragma unroll
+      for (int nq = 0; nq < NQB; ++nq) {
+        const int qi = r0 + nq * 32 + l32;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
           for (int v = 0; v < 16; ++v) {
             const int kp = k0 + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-            if (kp > qi) s[kb][v] = -INFINITY;
+            if (kp > qi) s[kb][nq][v] = -INFINITY;
           }
       }
-    } else if (t == n_ctx_tiles - 1 && (list_len & 63)) {       // ragged end of the list
+    } else if constexpr (MK == MASK_LIST_END) {
       const int nvalid = list_len - t * 64;
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+      for (int nq = 0; nq < NQB; ++nq)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int kr = kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+            if (kr >= nvalid) s[kb][nq][v] = -INFINITY;
+          }
+    }
+    uint4 pf[NQB][2][2];
+#pragma unroll
+    for (int nq = 0; nq < NQB; ++nq) {
+      float m4[4];                                   // four independent max chains, then a tree
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const int kb = c >> 1, v0 = (c & 1) * 8;
+        m4[c] = fmaxf(fmaxf(s[kb][nq][v0], s[kb][nq][v0 + 1]), s[kb][nq][v0 + 2]);
+        m4[c] = fmaxf(fmaxf(m4[c], s[kb][nq][v0 + 3]), s[kb][nq][v0 + 4]);
+        m4[c] = fmaxf(fmaxf(m4[c], s[kb][nq][v0 + 5]), s[kb][nq][v0 + 6]);
+        m4[c] = fmaxf(m4[c], s[kb][nq][v0 + 7]);
+      }
+      float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+      mx = pair_max(mx);
+      const float m_new = fmaxf(m_run[nq], mx * sc);
+      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
+      const bool changed = m_new != m_run[nq];
+      m_run[nq] = m_new;
+      float ps = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        float pv[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int kr = kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-          if (kr >= nvalid) s[kb][v] = -INFINITY;
+          pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][v], sc, -m_new));
+          ps += pv[v];
         }
-    }
-    float mx = s[0][0];
 #pragma unroll
-    for (int v = 1; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[0][v]), s[0][(v + 1) & 15]);
-#pragma unroll
-    for (int v = 0; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[1][v]), s[1][v + 1]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx * sc);
-    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-    const bool changed = m_new != m_run;
-    m_run = m_new;
-    float ps = 0.f;
-    uint4 pf[2][2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      float pv[16];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][v], sc, -m_new));
-        ps += pv[v];
+        for (int a2 = 0; a2 < 2; ++a2) {
+          uint4 u;
+          u.x = pack_bf16x2(pv[8 * a2 + 0], pv[8 * a2 + 1]);
+          u.y = pack_bf16x2(pv[8 * a2 + 2], pv[8 * a2 + 3]);
+          u.z = pack_bf16x2(pv[8 * a2 + 4], pv[8 * a2 + 5]);
+          u.w = pack_bf16x2(pv[8 * a2 + 6], pv[8 * a2 + 7]);
+          pf[nq][kb][a2] = u;
+        }
       }
+      l_run[nq] = l_run[nq] * alpha + ps;
+      if (__any(changed)) {                         // the running maximum rarely moves after the first tiles
 #pragma unroll
-      for (int a2 = 0; a2 < 2; ++a2) {
-        uint4 u;
-        u.x = pack_bf16x2(pv[8 * a2 + 0], pv[8 * a2 + 1]);
-        u.y = pack_bf16x2(pv[8 * a2 + 2], pv[8 * a2 + 3]);
-        u.z = pack_bf16x2(pv[8 * a2 + 4], pv[8 * a2 + 5]);
-        u.w = pack_bf16x2(pv[8 * a2 + 6], pv[8 * a2 + 7]);
-        pf[kb][a2] = u;
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[mb][nq][v] *= alpha;
       }
-    }
-    l_run = l_run * alpha + ps;
-    if (__any(changed)) {                           // the running maximum rarely moves after the first tiles
-#pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[mb][v] *= alpha;
     }
     typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
 #pragma unroll
@@ -274,70 +312,63 @@ __global__ __launch_bounds__(64 * ATT_NW) void attend_bf16_kernel(AttArgs a) {
           const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
           uint4 vf;
           vf.x = u0.x; vf.y = u0.y; vf.z = u1.x; vf.w = u1.y;
-          o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf),
-                                                          __builtin_bit_cast(bf16x8_t, pf[kb][a2]), o[mb], 0, 0, 0);
+#pragma unroll
+          for (int nq = 0; nq < NQB; ++nq)
+            o[mb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf),
+                                                                __builtin_bit_cast(bf16x8_t, pf[nq][kb][a2]),
+                                                                o[mb][nq], 0, 0, 0);
         }
   };
 
-  // ---- prologue: tokens of tiles 0 and 1, then the steady-state request pattern
-  //      (tokens u + 4, K/V tile u + 2) for u = -2, -1 ----
+  // ---- prologue: tokens of tiles 0..2, then the steady-state request pattern
+  //      (tokens u + 6, K/V tile u + 3) for u = -3, -2, -1 ----
   request_tokens(0);
   request_tokens(1);
+  request_tokens(2);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  request_tokens(2);
-  if (n_tiles > 0) request_tile(0);
-  request_tokens(3);
-  if (n_tiles > 1) request_tile(1);
-
-  // between two barriers: wait for tile t, then request tokens t + 4 and tile t + 2
-  auto advance = [&](int t) {
-    // requests issued after tile t's: wavefront 0's token request and tile t + 1
-    if (t + 1 < n_tiles) {
-      if (wave == 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT + 1) : "memory");
-      else           asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT) : "memory");
-    } else {
-      if (wave == 0) asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
-      else           asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    __syncthreads();            // tile t has landed for every wave; tile t - 2's stage is free
-    request_tokens(t + 4);
-    if (t + 2 < n_tiles) request_tile(t + 2);
-  };
-  if (!group_b) {
-    for (int t = 0; t < n_tiles; ++t) {
-      advance(t);
-      scores(t);
-      softmax_pv(t);
-    }
-  } else {
-    for (int t = 0; t < n_tiles; ++t) {
-      advance(t);
-      if (t > 0) softmax_pv(t - 1);
-      scores(t);
-    }
-    if (n_tiles > 0) softmax_pv(n_tiles - 1);
+  for (int u = 0; u < 3; ++u) {
+    request_tokens(u + 3);
+    if (u < n_tiles) request_tile(u);
   }
+
+  // ---- tile segments of this wavefront ----
+  const bool active = r0 < L;
+  const int t_list_end = (list_len & 63) ? n_ctx_tiles - 1 : n_ctx_tiles;       // first masked context tile
+  // chunk tile kt (keys 64 kt ..) is fully visible to the wave iff 64 kt + 63 <= r0, visible iff 64 kt <= r0 + QW - 1
+  const int t_diag = n_ctx_tiles + (active ? min(n_chunk_tiles, (r0 + 1) / 64) : 0);
+  const int t_end = active ? n_ctx_tiles + min(n_chunk_tiles, (r0 + QW - 1) / 64 + 1) : 0;
+  int t = 0;
+  if (active) {
+    for (; t < t_list_end; ++t) { advance(t); tile(t, std::integral_constant<int, MASK_NONE>{}); }
+    for (; t < n_ctx_tiles; ++t) { advance(t); tile(t, std::integral_constant<int, MASK_LIST_END>{}); }
+    for (; t < t_diag; ++t) { advance(t); tile(t, std::integral_constant<int, MASK_NONE>{}); }
+    for (; t < t_end; ++t) { advance(t); tile(t, std::integral_constant<int, MASK_CAUSAL>{}); }
+  }
+  for (; t < n_tiles; ++t) advance(t);               // tiles this wavefront cannot see: barriers and requests only
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the dummy token requests of the last iterations
 
   // ---- epilogue ----
   uint16_t* Ob = reinterpret_cast<uint16_t*>(a.out) + (size_t)bi * L * D.Hq * d;
-  const int qi = r0 + l32;
-  const float lt = l_run + __shfl_xor(l_run, 32, 64);
-  if (qi < L) {
-    const float inv = 1.f / lt;
-    uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+  for (int nq = 0; nq < NQB; ++nq) {
+    const int qi = r0 + nq * 32 + l32;
+    const float lt = l_run[nq] + __shfl_xor(l_run[nq], 32, 64);
+    if (qi < L) {
+      const float inv = 1.f / lt;
+      uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
 #pragma unroll
-      for (int a4 = 0; a4 < 4; ++a4) {
-        uint2 u;
-        u.x = pack_bf16x2(o[mb][4 * a4 + 0] * inv, o[mb][4 * a4 + 1] * inv);
-        u.y = pack_bf16x2(o[mb][4 * a4 + 2] * inv, o[mb][4 * a4 + 3] * inv);
-        *reinterpret_cast<uint2*>(orow + mb * 32 + 8 * a4 + 4 * hf) = u;
-      }
-    if (a.lse && hf == 0)
-      a.lse[((size_t)bi * L + qi) * D.Hq + head] = (m_run + log2f(lt)) * 0.6931471805599453f;
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4) {
+          uint2 u;
+          u.x = pack_bf16x2(o[mb][nq][4 * a4 + 0] * inv, o[mb][nq][4 * a4 + 1] * inv);
+          u.y = pack_bf16x2(o[mb][nq][4 * a4 + 2] * inv, o[mb][nq][4 * a4 + 3] * inv);
+          *reinterpret_cast<uint2*>(orow + mb * 32 + 8 * a4 + 4 * hf) = u;
+        }
+      if (a.lse && hf == 0)
+        a.lse[((size_t)bi * L + qi) * D.Hq + head] = (m_run[nq] + log2f(lt)) * 0.6931471805599453f;
+    }
   }
 }
 
@@ -447,16 +478,17 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
   if (mfma_ok) {
     const int HG = D.G < 4 ? D.G : 4;
     const int gpk = D.G / HG;
-    const int RPB = 32 * (ATT_NW / HG);
+    constexpr int NQB = ATT_NQB, NW = ATT_NW;
+    const int RPB = 32 * NQB * (NW / HG);
     dim3 g(D.Hkv * gpk, (n_q + RPB - 1) / RPB, seq_count);
     static bool attr_set = false;
     if (!attr_set) {
-      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel),
+      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<NQB, NW>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, ATT_LDS_BYTES);
       if (e != hipSuccess) return e;
       attr_set = true;
     }
-    attend_bf16_kernel<<<g, 64 * ATT_NW, ATT_LDS_BYTES, s>>>(a);
+    attend_bf16_kernel<NQB, NW><<<g, 64 * NW, ATT_LDS_BYTES, s>>>(a);
   } else {
     dim3 g(n_q, D.Hq, seq_count);
     if (D.dtype == LTRI_BF16) attend_simple_kernel<LTRI_BF16><<<g, 64, 0, s>>>(a);
