@@ -52,9 +52,13 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 #ifndef ATT_NW
 #define ATT_NW 8
 #endif
-constexpr int DMA_NS = 4;                       // ring stages
+#ifndef ATT_NS
+#define ATT_NS 4
+#endif
+constexpr int DMA_NS = ATT_NS;                  // ring stages
 constexpr int DMA_STAGE_BYTES = 32768;          // K tile 16 KB + V tile 16 KB
-constexpr int TOK_SLOTS = 8;                    // ring of 64-entry token tiles
+constexpr int TOK_AHEAD = 2 * (DMA_NS - 1);     // token tile t + TOK_AHEAD is requested in iteration t
+constexpr int TOK_SLOTS = 8;                    // ring of 64-entry token tiles (> TOK_AHEAD)
 constexpr int ATT_LDS_BYTES = DMA_NS * DMA_STAGE_BYTES + TOK_SLOTS * 256;
 
 // 16 bytes per lane from base + off into LDS at lds_wave_base + 16 * lane
@@ -114,8 +118,8 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
 
   // ---- requests ----
   // Token ids of the context tiles travel through LDS as well: wavefront 0 requests the 64 list
-  // entries of tile u in iteration u - 6, before that iteration's K/V request, so they have
-  // landed (and passed a barrier) when tile u's rows are requested three iterations later.
+  // entries of tile u in iteration u - TOK_AHEAD, before that iteration's K/V request, so they
+  // have landed (and passed a barrier) when tile u's rows are requested NS - 1 iterations later.
   // Tiles past the list read a dummy address: every iteration requests the same number of loads.
   auto request_tokens = [&](int u) {
     if (wave == 0) dma4(list, (uint32_t)((u < n_ctx_tiles ? u * 64 : 0) + lane) * 4u, tok0 + (uint32_t)(u % TOK_SLOTS) * 256);
@@ -136,20 +140,22 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
       dma16(Vb, off + (uint32_t)((lp ^ ((row & 3) << 1)) << 4), sbase + 16384u + (uint32_t)rw * 256);
     }
   };
-  // top of iteration t: wait until tile t has landed, barrier, request tokens t + 6 and tile t + 3
+  // top of iteration t: wait until tile t has landed, barrier, request tokens t + TOK_AHEAD and
+  // tile t + NS - 1. Requested after tile t: the NS - 2 following iterations' token requests
+  // (wavefront 0 only) and those of their tiles that exist.
   auto advance = [&](int t) {
-    const int later = min(DMA_NS - 2, n_tiles - 1 - t);         // tiles requested after tile t
-    if (wave == 0) {                                             // also one token request per iteration
-      if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_LPT + 2) : "memory");
-      else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT + 2) : "memory");
-      else                 asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    const int later = min(DMA_NS - 2, n_tiles - 1 - t);
+    if (wave == 0) {
+      if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_LPT + DMA_NS - 2) : "memory");
+      else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT + DMA_NS - 2) : "memory");
+      else                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_NS - 2) : "memory");
     } else {
       if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_LPT) : "memory");
       else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT) : "memory");
       else                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
     __syncthreads();            // tile t is in LDS for every wave; tile t - 1's stage is free
-    request_tokens(t + 6);
+    request_tokens(t + TOK_AHEAD);
     if (t + DMA_NS - 1 < n_tiles) request_tile(t + DMA_NS - 1);
   };
 
@@ -320,15 +326,14 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
         }
   };
 
-  // ---- prologue: tokens of tiles 0..2, then the steady-state request pattern
-  //      (tokens u + 6, K/V tile u + 3) for u = -3, -2, -1 ----
-  request_tokens(0);
-  request_tokens(1);
-  request_tokens(2);
+  // ---- prologue: tokens of the first NS - 1 tiles, then the steady-state request pattern
+  //      (tokens u + TOK_AHEAD, K/V tile u + NS - 1) for u = -(NS - 1) .. -1 ----
+  static_assert(DMA_NS >= 2 && DMA_NS <= 4 && TOK_AHEAD < TOK_SLOTS, "vmcnt ladder and token ring sizes");
+  for (int u = 0; u < DMA_NS - 1; ++u) request_tokens(u);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  for (int u = 0; u < 3; ++u) {
-    request_tokens(u + 3);
+  for (int u = 0; u < DMA_NS - 1; ++u) {
+    request_tokens(u + DMA_NS - 1);
     if (u < n_tiles) request_tile(u);
   }
 
