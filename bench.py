@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--context", type=int, default=0, help="override the context length (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--overlap", action="store_true",
+                    help="segment chunk c+1 on a second stream next to attend(c) (measured: no gain, the kernels\n"
+                         "compete for the same compute units)")
     ap.add_argument("--seed", type=int, default=1)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -125,21 +128,44 @@ def main():
 
     list_lens = []          # per chunk: context-list length of every KV head
 
+    # The segmentation of chunk c + 1 does not depend on the attention of chunk c; with --overlap it is
+    # enqueued on a second stream between retrieve(c) and retrieve(c + 1) and runs next to attend(c).
+    overlap = args.overlap
+    main = torch.cuda.current_stream(dev)
+    side = torch.cuda.Stream(dev) if overlap else None
+    ev_r = [torch.cuda.Event() for _ in range(n_chunks)]
+    ev_a = [torch.cuda.Event() for _ in range(n_chunks)]
+    if overlap:
+        ctx.set_attend_stages(3)          # leaves LDS for the segmentation kernels on every compute unit
+
     def one_stream(record_lens=False, events=None):
         ctx.reset(0)
+        ctx.append_chunk(0, 0, 1, L)
         for c in range(n_chunks):
-            ctx.append_chunk(0, 0, 1, L)
             ctx.retrieve(0, 0, 1, qs[c])
+            nxt = c + 1 < n_chunks
+            if nxt and overlap:
+                ev_r[c].record(main)
             if events is not None:
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
-                e0.record()
+                e0.record(main)
             ctx.attend(0, 0, 1, qs[c], out=out)
             if events is not None:
-                e1.record()
+                e1.record(main)
                 events.append((e0, e1))
             if record_lens:
                 list_lens.append([len(ctx.get_token_list(0, 0, h)) for h in range(w.n_kv_heads)])
+            if nxt:
+                if overlap:
+                    side.wait_event(ev_r[c])
+                    ctx.set_stream(side)
+                    ctx.append_chunk(0, 0, 1, L)
+                    ev_a[c].record(side)
+                    ctx.set_stream(main)
+                    main.wait_event(ev_a[c])
+                else:
+                    ctx.append_chunk(0, 0, 1, L)
 
     # warmup (the first pass also records the list lengths, which need a synchronising read-back)
     one_stream(record_lens=True)
@@ -214,7 +240,8 @@ def main():
                                f"{w.n_sink} sink tokens, window {w.window}, retrieval budget {w.budget_tokens} tokens, "
                                f"planted-span keys ({w.len_dist} lengths in [{w.len_lo},{w.len_hi}]), seed {args.seed}",
                    "step": "one full stream through one layer (append + retrieve + attend per chunk)",
-                   "seg_map": "logit", "theta": theta, "phi": 0.0},
+                   "seg_map": "logit", "theta": theta, "phi": 0.0,
+                   "schedule": "append(c+1) on a second stream next to attend(c)" if overlap else "serial"},
         "roofline": roofline, "gather": gather, "cpu_baseline": cpu,
         "breakdown_ms": {"attend": round(tot_ms / args.steps, 3), "append_retrieve_and_gaps": round(other_ms, 3)},
     }

@@ -28,7 +28,10 @@
  *       queries    [seq_count][n_q][n_q_heads][head_dim]
  *       outputs    [seq_count][n_q][n_q_heads][head_dim]
  *     Query head g belongs to KV head g / (n_q_heads / n_kv_heads).
- *   - Calls on one context must not overlap (one stream, one scratch buffer).
+ *   - Calls on one context must not overlap (one scratch buffer, one index memory), with one
+ *     exception: ltri_append_chunk for chunk t+1 touches nothing that ltri_attend for chunk t
+ *     reads, so the two may run concurrently on different streams (see ltri_set_stream); the
+ *     caller orders append(t+1) after retrieve(t) and retrieve(t+1) after append(t+1).
  */
 #ifndef LTRI_H
 #define LTRI_H
@@ -94,6 +97,13 @@ int32_t ltri_create(const ltri_config* cfg, void* k_arena, void* v_arena, void* 
 int32_t ltri_destroy(ltri_ctx* ctx);
 /* Forget all layers of one sequence (span table, selections, token count). */
 int32_t ltri_reset(ltri_ctx* ctx, int32_t seq);
+/* Stream on which the following calls enqueue their work (hipStream_t; NULL = default stream).
+ * Ordering between work on different streams is the caller's business (events). */
+int32_t ltri_set_stream(ltri_ctx* ctx, void* hip_stream);
+/* LDS ring depth of the bf16 attention kernel: 4 (default, 130 KB of LDS per compute unit, fastest
+ * on its own) or 3 (98 KB, leaves room for the segmentation kernels of the next chunk to run next
+ * to it). EINVAL otherwise. */
+int32_t ltri_set_attend_stages(ltri_ctx* ctx, int32_t stages);
 /* A context without device buffers: every call validates its arguments and advances the
  * host-side state exactly as a real context would, but enqueues nothing; introspection calls
  * return ESTATE. Used to test the host logic on a machine without a GPU. */

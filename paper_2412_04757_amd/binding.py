@@ -21,6 +21,7 @@ MAP_SOFTMAX, MAP_LOGIT = 0, 1
 
 EXPORTED_SYMBOLS = [
     "ltri_workspace_bytes", "ltri_create", "ltri_create_dry", "ltri_destroy", "ltri_reset",
+    "ltri_set_stream", "ltri_set_attend_stages",
     "ltri_append_chunk", "ltri_append_chunk_with_spans", "ltri_retrieve", "ltri_sel_capacity",
     "ltri_force_selection", "ltri_attend", "ltri_gather_pack", "ltri_list_capacity",
     "ltri_sync_status", "ltri_token_count", "ltri_span_count", "ltri_get_spans",
@@ -67,6 +68,8 @@ def load_library() -> C.CDLL:
         "ltri_create_dry": [C.POINTER(LtriConfig), C.POINTER(vp)],
         "ltri_destroy": [vp],
         "ltri_reset": [vp, i32],
+        "ltri_set_stream": [vp, vp],
+        "ltri_set_attend_stages": [vp, i32],
         "ltri_append_chunk": [vp, i32, i32, i32, vp, vp, vp, i32],
         "ltri_append_chunk_with_spans": [vp, i32, i32, vp, vp, i32, pi32, pi32],
         "ltri_retrieve": [vp, i32, i32, i32, vp, i32, vp, vp],
@@ -176,6 +179,13 @@ class LtriContext:
         return self.k_arena.view(shape), self.v_arena.view(shape)
 
     # ---- the C ABI, same names ----
+    def set_stream(self, stream: "torch.cuda.Stream") -> None:
+        self._check(self.lib.ltri_set_stream(self.handle, stream.cuda_stream), None)
+        self.stream = stream
+
+    def set_attend_stages(self, stages: int) -> None:
+        self._check(self.lib.ltri_set_attend_stages(self.handle, stages), None)
+
     def reset(self, seq: int) -> None:
         self._check(self.lib.ltri_reset(self.handle, seq), None)
 

@@ -52,14 +52,9 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 #ifndef ATT_NW
 #define ATT_NW 8
 #endif
-#ifndef ATT_NS
-#define ATT_NS 4
-#endif
-constexpr int DMA_NS = ATT_NS;                  // ring stages
 constexpr int DMA_STAGE_BYTES = 32768;          // K tile 16 KB + V tile 16 KB
-constexpr int TOK_AHEAD = 2 * (DMA_NS - 1);     // token tile t + TOK_AHEAD is requested in iteration t
 constexpr int TOK_SLOTS = 8;                    // ring of 64-entry token tiles (> TOK_AHEAD)
-constexpr int ATT_LDS_BYTES = DMA_NS * DMA_STAGE_BYTES + TOK_SLOTS * 256;
+constexpr int att_lds_bytes(int ns) { return ns * DMA_STAGE_BYTES + TOK_SLOTS * 256; }
 
 // 16 bytes per lane from base + off into LDS at lds_wave_base + 16 * lane
 __device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_wave_base) {
@@ -79,9 +74,10 @@ __device__ __forceinline__ float pair_max(float v) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-// NW wavefronts per workgroup, each with NQB blocks of 32 query rows.
-template <int NQB, int NW>
+// NW wavefronts per workgroup, each with NQB blocks of 32 query rows; DMA_NS ring stages.
+template <int NQB, int NW, int DMA_NS>
 __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
+  constexpr int TOK_AHEAD = 2 * (DMA_NS - 1);       // token tile t + TOK_AHEAD is requested in iteration t
   constexpr int QW = 32 * NQB;
   constexpr int NI = 16 / NW;                       // DMA row groups per wave and tile
   constexpr int DMA_LPT = 2 * NI;                   // K/V requests per lane and tile
@@ -475,7 +471,7 @@ __global__ __launch_bounds__(256) void gather_pack_kernel(GatherArgs a) {
 
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
-                         void* out, float* lse, hipStream_t s) {
+                         void* out, float* lse, int stages, hipStream_t s) {
   AttArgs a;
   a.D = D; a.st = st; a.k_arena = k_arena; a.v_arena = v_arena; a.q = q; a.out = out; a.lse = lse;
   a.layer = layer; a.seq_count = seq_count; a.n_q = n_q; a.bp = bp;
@@ -488,12 +484,16 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
     dim3 g(D.Hkv * gpk, (n_q + RPB - 1) / RPB, seq_count);
     static bool attr_set = false;
     if (!attr_set) {
-      const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<NQB, NW>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, ATT_LDS_BYTES);
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<NQB, NW, 4>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, att_lds_bytes(4));
+      if (e != hipSuccess) return e;
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<NQB, NW, 3>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, att_lds_bytes(3));
       if (e != hipSuccess) return e;
       attr_set = true;
     }
-    attend_bf16_kernel<NQB, NW><<<g, 64 * NW, ATT_LDS_BYTES, s>>>(a);
+    if (stages == 3) attend_bf16_kernel<NQB, NW, 3><<<g, 64 * NW, att_lds_bytes(3), s>>>(a);
+    else             attend_bf16_kernel<NQB, NW, 4><<<g, 64 * NW, att_lds_bytes(4), s>>>(a);
   } else {
     dim3 g(n_q, D.Hq, seq_count);
     if (D.dtype == LTRI_BF16) attend_simple_kernel<LTRI_BF16><<<g, 64, 0, s>>>(a);

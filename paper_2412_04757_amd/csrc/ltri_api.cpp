@@ -21,6 +21,7 @@ struct ltri_ctx {
   DevState ds;
   DevScratch dc;
   bool dry;
+  int attend_stages;                     // LDS ring depth of the bf16 attention kernel (3 or 4)
   // host mirror of the stream positions, per (layer, seq)
   std::vector<long long> n_tokens;       // tokens appended
   std::vector<int> last_len;             // length of the chunk appended last (0 = none)
@@ -159,6 +160,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->k_arena = (char*)k_arena; c->v_arena = (char*)v_arena; c->state = (char*)state; c->scratch = (char*)scratch;
   c->stream = (hipStream_t)hip_stream;
   c->dry = dry;
+  c->attend_stages = 4;
   char* s = c->state;
   c->ds = DevState{(int32_t*)(s + SL.meta), (int32_t*)(s + SL.span_start), (int32_t*)(s + SL.span_len),
                    (void*)(s + SL.krep), (double*)(s + SL.scores), (int32_t*)(s + SL.sel_ids),
@@ -193,6 +195,19 @@ int32_t ltri_create_dry(const ltri_config* cfg, ltri_ctx** out) {
 int32_t ltri_destroy(ltri_ctx* c) {
   if (!c) return LTRI_EINVAL;
   delete c;
+  return LTRI_OK;
+}
+
+int32_t ltri_set_stream(ltri_ctx* c, void* hip_stream) {
+  if (!c) return LTRI_EINVAL;
+  c->stream = (hipStream_t)hip_stream;
+  return LTRI_OK;
+}
+
+int32_t ltri_set_attend_stages(ltri_ctx* c, int32_t stages) {
+  if (!c) return LTRI_EINVAL;
+  if (stages != 3 && stages != 4) return fail(c, LTRI_EINVAL, "attend stages must be 3 or 4");
+  c->attend_stages = stages;
   return LTRI_OK;
 }
 
@@ -419,7 +434,7 @@ int32_t ltri_attend(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_c
                   seq_begin + s);
   if (!c->dry) {
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_q, out, lse,
-                                   c->stream), "attend");
+                                   c->attend_stages, c->stream), "attend");
     if (r != LTRI_OK) return r;
   }
   return LTRI_OK;

@@ -103,7 +103,7 @@ hipError_t launch_force_list(const Dims& D, const DevState& st, int layer, int s
                              int n_ids, hipStream_t s);
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
-                         void* out, float* lse, hipStream_t s);
+                         void* out, float* lse, int stages, hipStream_t s);
 hipError_t launch_gather_pack(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                               int layer, int seq, void* k_packed, void* v_packed, int32_t* n_tokens,
                               hipStream_t s);

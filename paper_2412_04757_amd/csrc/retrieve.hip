@@ -227,8 +227,16 @@ __device__ void emit_selection(const Dims& D, const DevState& st, int slot, cons
 // ---- top spans under the count cap and the token budget ----
 constexpr int SEL_MAX_SPANS = 65536;
 
+// Order key of a span: smaller key = earlier in the order (-score, id). The score's bit pattern
+// is mapped to an unsigned integer that grows with the score, then complemented.
+__device__ __forceinline__ uint64_t score_key(double s) {
+  const uint64_t u = (uint64_t)__double_as_longlong(s + 0.0);          // -0.0 -> +0.0: they compare equal
+  const uint64_t up = (u >> 63) ? ~u : (u | 0x8000000000000000ull);   // monotone in s
+  return ~up;
+}
+
 __global__ __launch_bounds__(1024) void select_kernel(RetArgs a) {
-  __shared__ double t_score[1024];
+  __shared__ uint64_t t_key[1024];
   __shared__ int t_clip[1024];
   __shared__ uint32_t selmask[SEL_MAX_SPANS / 32];
   const Dims& D = a.D;
@@ -244,17 +252,17 @@ __global__ __launch_bounds__(1024) void select_kernel(RetArgs a) {
   __syncthreads();
   for (int i0 = 0; i0 < n; i0 += blockDim.x) {
     const int i = i0 + tid;
-    double si = 0.0;
+    uint64_t ki = 0;
     int ci = 0;
     if (i < n) {
       int lo, hi;
       clip_span(D, c0, sstart[i], slen[i], lo, hi);
       ci = max(hi - lo, 0);
-      si = scores[i];
+      ki = score_key(scores[i]);
     }
-    // rank and cumulated tokens of span i in the order (-score, id) among eligible spans
-    int rank = 0;
-    long long cum = ci;
+    // rank and cumulated tokens of span i in the order (-score, id) among eligible spans: span j
+    // comes before span i iff key_j < key_i, or the keys are equal and j < i
+    int rank = 0, cum = ci;
     for (int j0 = 0; j0 < n; j0 += 1024) {
       __syncthreads();
       const int j = j0 + tid;
@@ -262,20 +270,28 @@ __global__ __launch_bounds__(1024) void select_kernel(RetArgs a) {
         int lo, hi;
         clip_span(D, c0, sstart[j], slen[j], lo, hi);
         t_clip[tid] = max(hi - lo, 0);
-        t_score[tid] = scores[j];
+        t_key[tid] = score_key(scores[j]);
       }
       __syncthreads();
       const int m = min(1024, n - j0);
       if (ci > 0) {
-        for (int jj = 0; jj < m; ++jj) {
+        // entries below i (j < i) win ties, entries above lose them
+        const int split = min(max(i - j0, 0), m);
+        for (int jj = 0; jj < split; ++jj) {
           const int cj = t_clip[jj];
-          const double sj = t_score[jj];
-          const bool before = cj > 0 && (sj > si || (sj == si && (j0 + jj) < i));
-          if (before) { ++rank; cum += cj; }
+          const bool before = t_key[jj] <= ki;
+          rank += (before && cj > 0) ? 1 : 0;
+          cum += before ? cj : 0;
+        }
+        for (int jj = split; jj < m; ++jj) {
+          const int cj = t_clip[jj];
+          const bool before = t_key[jj] < ki && (j0 + jj) != i;
+          rank += (before && cj > 0) ? 1 : 0;
+          cum += before ? cj : 0;
         }
       }
     }
-    const bool sel = ci > 0 && (D.k_max == 0 || rank < D.k_max) && (D.budget == 0 || cum <= D.budget);
+    const bool sel = ci > 0 && (D.k_max == 0 || rank < D.k_max) && (D.budget == 0 || (long long)cum <= D.budget);
     if (sel) atomicOr(&selmask[i >> 5], 1u << (i & 31));
   }
   __syncthreads();

@@ -16,6 +16,7 @@
 // results per anti-diagonal, sorts the candidates, runs the greedy NMS and cuts the chunk.
 // All sums are fp64 in a fixed order, so the result is deterministic.
 #include "device_common.h"
+#include <type_traits>
 #include "span_mean.h"
 
 namespace ltri {
@@ -34,31 +35,61 @@ __device__ __forceinline__ void tile_decode(int t, int& I, int& J) {
   I = i; J = t - i * (i + 1) / 2;
 }
 
-// 32 x 32 block of dot products on the matrix cores: acc[v] += sum_k A[r(v)][k] * B[c][k] with
-// c = lane % 32 and r(v) = 8 * (v / 4) + 4 * (lane / 32) + v % 4. arow / brow point at the
-// lane's own row (row lane % 32 of the A block / of the B block).
+// Operand staging: 64 rows x 256 bytes (the kc-th 256-byte piece of every row's d-vector) are
+// copied global -> LDS with full-row coalescing; inside a row the sixteen 16-byte pieces are
+// XOR-permuted with the row number so that the fragment reads below are free of bank conflicts.
+template <typename T>
+__device__ __forceinline__ void stage_rows(unsigned char* dst, const T* base, size_t row_stride, int row0,
+                                           int L, int kc) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int q = threadIdx.x + 256 * i;
+    const int row = q >> 4, piece = q & 15;
+    const int grow = min(row0 + row, L - 1);                 // clamped; masked by the caller
+    const uint4 v = *(reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(base + (size_t)grow * row_stride) + kc * 256) + piece);
+    *reinterpret_cast<uint4*>(dst + row * 256 + ((piece ^ (row & 15)) << 4)) = v;
+  }
+}
+
+// 32 x 32 block of dot products on the matrix cores over one staged 256-byte piece:
+// acc[v] += sum_k A[r(v)][k] * B[c][k] with c = lane % 32 and
+// r(v) = 8 * (v / 4) + 4 * (lane / 32) + v % 4. abuf / bbuf are the staged 64-row operands,
+// arow0 / brow0 the first of the wave's 32 rows in them.
 template <int DT> struct TileDot;
 template <> struct TileDot<LTRI_BF16> {
-  __device__ static __forceinline__ void run(const uint16_t* arow, const uint16_t* brow, int d, int hf,
-                                             f32x16_t& acc) {
-    for (int kk = 0; kk < d; kk += 16) {
-      uint4 av = *reinterpret_cast<const uint4*>(arow + kk + 8 * hf);
-      uint4 bv = *reinterpret_cast<const uint4*>(brow + kk + 8 * hf);
+  __device__ static __forceinline__ void run(const unsigned char* abuf, const unsigned char* bbuf, int arow0,
+                                             int brow0, int l32, int hf, f32x16_t& acc) {
+    const unsigned char* ar = abuf + (arow0 + l32) * 256;
+    const unsigned char* br = bbuf + (brow0 + l32) * 256;
+    const int sw = l32 & 15;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const uint4 av = *reinterpret_cast<const uint4*>(ar + (((2 * kk + hf) ^ sw) << 4));
+      const uint4 bv = *reinterpret_cast<const uint4*>(br + (((2 * kk + hf) ^ sw) << 4));
       acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, av),
                                                     __builtin_bit_cast(bf16x8_t, bv), acc, 0, 0, 0);
     }
   }
 };
 template <> struct TileDot<LTRI_F32> {
-  __device__ static __forceinline__ void run(const float* arow, const float* brow, int d, int hf,
-                                             f32x16_t& acc) {
-    for (int kk = 0; kk < d; kk += 2)
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(arow[kk + hf], brow[kk + hf], acc, 0, 0, 0);
+  __device__ static __forceinline__ void run(const unsigned char* abuf, const unsigned char* bbuf, int arow0,
+                                             int brow0, int l32, int hf, f32x16_t& acc) {
+    const unsigned char* ar = abuf + (arow0 + l32) * 256;
+    const unsigned char* br = bbuf + (brow0 + l32) * 256;
+    const int sw = l32 & 15;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {                  // four floats per piece: two steps of k = 2
+      const float4 av = *reinterpret_cast<const float4*>(ar + ((c ^ sw) << 4));
+      const float4 bv = *reinterpret_cast<const float4*>(br + ((c ^ sw) << 4));
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(hf ? av.y : av.x, hf ? bv.y : bv.x, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(hf ? av.w : av.z, hf ? bv.w : bv.z, acc, 0, 0, 0);
+    }
   }
 };
 
 // Leaves the head-summed map tile (rows I*64.., columns J*64..) in Ms[r * 65 + c] as doubles;
-// cells above the diagonal or outside the chunk are 0. Called by all 256 threads.
+// cells above the diagonal or outside the chunk are 0. Called by all 256 threads; Ms doubles as
+// the staging area of the operands (2 x 16 KB) before the tile values are written.
 template <int DT>
 __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int J, double* Ms) {
   typedef typename Elt<DT>::type T;
@@ -70,54 +101,49 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
   const int wi = wave >> 1, wj = wave & 1, hf = lane >> 5, l32 = lane & 31;
   const int slot = slot_of(D, a.layer, seq, h);
   const T* Kc = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * d;
-  const int irow = min(I * 64 + wi * 32 + l32, L - 1);   // lane's A row (clamped; masked below)
-  const int jrow = min(J * 64 + wj * 32 + l32, L - 1);   // lane's B row
-  const T* brow = Kc + (size_t)jrow * d;
+  const T* Qb = a.q_seg ? reinterpret_cast<const T*>(a.q_seg) + (size_t)bi * L * D.Hq * d + (size_t)h * D.G * d : nullptr;
+  const int n_h = a.q_seg ? D.G : 1;
+  const int nkc = d * (int)sizeof(T) / 256;                  // 256-byte pieces per row
+  unsigned char* abuf = reinterpret_cast<unsigned char*>(Ms);
+  unsigned char* bbuf = abuf + 16384;
   const double scale = 1.0 / sqrt((double)d);
   const int jcol = J * 64 + wj * 32 + l32;
+  const bool logit = D.seg_map == LTRI_MAP_LOGIT;
   double m[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) m[v] = 0.0;
-  if (a.q_seg == nullptr) {
-    f32x16_t acc = {0};
-    TileDot<DT>::run(Kc + (size_t)irow * d, brow, d, hf, acc);
-    if (D.seg_map == LTRI_MAP_LOGIT) {
+  f32x16_t acc = {0};
+  for (int g = 0; g < n_h; ++g) {
+    if (!logit) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) m[v] = (double)acc[v] * scale;
-    } else {
-      const double* lse = a.sc.lse + ((size_t)p * 1) * a.Lp;
+      for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    }
+    for (int kc = 0; kc < nkc; ++kc) {
+      if (Qb) stage_rows<T>(abuf, Qb + (size_t)g * d, (size_t)D.Hq * d, I * 64, L, kc);
+      else    stage_rows<T>(abuf, Kc, (size_t)d, I * 64, L, kc);
+      stage_rows<T>(bbuf, Kc, (size_t)d, J * 64, L, kc);
+      __syncthreads();
+      TileDot<DT>::run(abuf, bbuf, wi * 32, wj * 32, l32, hf, acc);
+      __syncthreads();
+    }
+    if (!logit) {
+      const double* lse = a.sc.lse + ((size_t)p * n_h + g) * a.Lp;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        int i = I * 64 + wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-        m[v] = exp((double)acc[v] * scale - lse[min(i, L - 1)]);
-      }
-    }
-  } else {
-    const T* Qb = reinterpret_cast<const T*>(a.q_seg) + (size_t)bi * L * D.Hq * d;
-    if (D.seg_map == LTRI_MAP_LOGIT) {
-      f32x16_t acc = {0};
-      for (int g = 0; g < D.G; ++g)
-        TileDot<DT>::run(Qb + ((size_t)irow * D.Hq + h * D.G + g) * d, brow, d, hf, acc);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) m[v] = (double)acc[v] * scale;
-    } else {
-      for (int g = 0; g < D.G; ++g) {
-        f32x16_t acc = {0};
-        TileDot<DT>::run(Qb + ((size_t)irow * D.Hq + h * D.G + g) * d, brow, d, hf, acc);
-        const double* lse = a.sc.lse + ((size_t)p * D.G + g) * a.Lp;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          int i = I * 64 + wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-          m[v] += exp((double)acc[v] * scale - lse[min(i, L - 1)]);
-        }
+        const int i = I * 64 + wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+        m[v] += exp((double)acc[v] * scale - lse[min(i, L - 1)]);
       }
     }
   }
+  if (logit) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) m[v] = (double)acc[v] * scale;
+  }
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
-    int rl = wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-    int i = I * 64 + rl;
-    bool ok = (jcol <= i) && (i < L);
+    const int rl = wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+    const int i = I * 64 + rl;
+    const bool ok = (jcol <= i) && (i < L);
     Ms[rl * 65 + wj * 32 + l32] = ok ? m[v] : 0.0;
   }
 }
@@ -325,6 +351,28 @@ __device__ __forceinline__ bool nms_suppressed(int x, int y, int kx, int ky, flo
   return (float)inter > __fmul_rn(phi, (float)uni);
 }
 
+// Value of lane (lane ^ M) for M = 1 .. 32, on the vector ALU (DPP / lane-swap instructions)
+// instead of the LDS crossbar that __shfl_xor goes through.
+template <int M>
+__device__ __forceinline__ uint32_t lane_xor_c(uint32_t v) {
+  if constexpr (M == 1) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);          // quad_perm [1,0,3,2]
+  } else if constexpr (M == 2) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);          // quad_perm [2,3,0,1]
+  } else if constexpr (M == 4) {
+    int r = __builtin_amdgcn_update_dpp(0, (int)v, 0x104, 0xF, 0x5, false);           // banks 0, 2 <- lane + 4
+    r = __builtin_amdgcn_update_dpp(r, (int)v, 0x114, 0xF, 0xA, false);               // banks 1, 3 <- lane - 4
+    return (uint32_t)r;
+  } else if constexpr (M == 8) {
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x128, 0xF, 0xF, true);         // row_ror:8
+  } else if constexpr (M == 16) {
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return (threadIdx.x & 16) ? r[0] : r[1];
+  } else {
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return (threadIdx.x & 32) ? r[0] : r[1];
+  }
+}
 __device__ __forceinline__ bool key_less(uint64_t a1, uint32_t a2, uint64_t b1, uint32_t b2) {
   return (a1 < b1) || (a1 == b1 && a2 < b2);
 }
@@ -350,8 +398,9 @@ __device__ void append_spans(const Dims& D, const DevState& st, int slot, int c0
     meta[META_CHUNK_NSP] = fits ? n_sp : 0;
     meta[META_CHUNK_START] = c0;
     meta[META_CHUNK_LEN] = L;
-    meta[META_SEL_CNT] = 0;
-    meta[META_LIST_LEN] = 0;
+    // META_SEL_CNT / META_LIST_LEN / the token list stay as they are: the attention of the previous
+    // chunk may still be reading them on another stream; the host refuses to attend before the
+    // next retrieve has rewritten them
   }
 }
 
@@ -401,14 +450,16 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
         }
       }
     }
-    if (bx >= 0 && best > 0.0) {
+    const bool is_cand = bx >= 0 && best > 0.0;
+    if (is_cand) {
       k1[s] = ~(uint64_t)__double_as_longlong(best);     // positive doubles order like their bits
       k2[s] = ((uint32_t)bx << 16) | (uint32_t)(s - bx);
-      atomicAdd(&s_ncand, 1);
     } else {
       k1[s] = ~0ull;
       k2[s] = 0xFFFFFFFFu;
     }
+    const uint64_t cm = __ballot(is_cand);               // one LDS atomic per wavefront, not per candidate
+    if ((tid & 63) == 0 && cm) atomicAdd(&s_ncand, __popcll(cm));
   }
   __syncthreads();
   // Bitonic sort of 4096 (key1, key2) pairs by (score descending, x ascending, y ascending):
@@ -424,53 +475,62 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
       e2[r] = e < n_sort ? k2[e] : 0xFFFFFFFFu;
     }
     __syncthreads();
-    for (int k = 2; k <= 4096; k <<= 1) {
-      for (int j = k >> 1; j > 0; j >>= 1) {
-        if (j >= 256) {
+    // one compare-exchange stage with partners at distance J (compile time) inside the wavefront
+    auto wave_stage = [&](auto jc, int k) {
+      constexpr int J = decltype(jc)::value;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) { k1[tid * 4 + r] = e1[r]; k2[tid * 4 + r] = e2[r]; }
-          __syncthreads();
+      for (int r = 0; r < 4; ++r) {
+        const int e = tid * 4 + r;
+        const uint32_t lo = lane_xor_c<J / 4>((uint32_t)e1[r]);
+        const uint32_t hi = lane_xor_c<J / 4>((uint32_t)(e1[r] >> 32));
+        const uint32_t o2 = lane_xor_c<J / 4>(e2[r]);
+        const uint64_t o1 = ((uint64_t)hi << 32) | lo;
+        const bool asc = (e & k) == 0, lower = (e & J) == 0;
+        const bool mine_less = key_less(e1[r], e2[r], o1, o2);
+        const bool keep = (lower == asc) ? mine_less : !mine_less;   // lower slot of an ascending pair keeps the min
+        if (!keep) { e1[r] = o1; e2[r] = o2; }
+      }
+    };
+    auto reg_stage = [&](int j, int k) {                  // partners inside the thread (j = 2 or 1)
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int e = tid * 4 + r, pe = e ^ j;
-            const uint64_t o1 = k1[pe];
-            const uint32_t o2 = k2[pe];
-            const bool asc = (e & k) == 0, lower = (e & j) == 0;
-            const bool mine_less = key_less(e1[r], e2[r], o1, o2);
-            const bool keep = (lower == asc) ? mine_less : !mine_less;   // lower slot of an ascending pair keeps the min
-            if (!keep) { e1[r] = o1; e2[r] = o2; }
-          }
-          __syncthreads();
-        } else if (j >= 4) {
-          const int lj = j >> 2;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int e = tid * 4 + r;
-            const uint32_t lo = __shfl_xor((uint32_t)e1[r], lj, 64);
-            const uint32_t hi = __shfl_xor((uint32_t)(e1[r] >> 32), lj, 64);
-            const uint32_t o2 = __shfl_xor(e2[r], lj, 64);
-            const uint64_t o1 = ((uint64_t)hi << 32) | lo;
-            const bool asc = (e & k) == 0, lower = (e & j) == 0;
-            const bool mine_less = key_less(e1[r], e2[r], o1, o2);
-            const bool keep = (lower == asc) ? mine_less : !mine_less;
-            if (!keep) { e1[r] = o1; e2[r] = o2; }
-          }
-        } else {
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const int pr = r ^ j;
-            if (pr > r) {
-              const int e = tid * 4 + r;
-              const bool asc = (e & k) == 0;
-              const bool less = key_less(e1[pr], e2[pr], e1[r], e2[r]);   // partner < mine
-              if (less == asc) {
-                const uint64_t t1 = e1[r]; e1[r] = e1[pr]; e1[pr] = t1;
-                const uint32_t t2 = e2[r]; e2[r] = e2[pr]; e2[pr] = t2;
-              }
-            }
+      for (int r = 0; r < 4; ++r) {
+        const int pr = r ^ j;
+        if (pr > r) {
+          const int e = tid * 4 + r;
+          const bool asc = (e & k) == 0;
+          const bool less = key_less(e1[pr], e2[pr], e1[r], e2[r]);   // partner < mine
+          if (less == asc) {
+            const uint64_t t1 = e1[r]; e1[r] = e1[pr]; e1[pr] = t1;
+            const uint32_t t2 = e2[r]; e2[r] = e2[pr]; e2[pr] = t2;
           }
         }
       }
+    };
+    for (int k = 2; k <= 4096; k <<= 1) {
+      for (int j = k >> 1; j >= 256; j >>= 1) {           // partners in other wavefronts: through LDS
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { k1[tid * 4 + r] = e1[r]; k2[tid * 4 + r] = e2[r]; }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int e = tid * 4 + r, pe = e ^ j;
+          const uint64_t o1 = k1[pe];
+          const uint32_t o2 = k2[pe];
+          const bool asc = (e & k) == 0, lower = (e & j) == 0;
+          const bool mine_less = key_less(e1[r], e2[r], o1, o2);
+          const bool keep = (lower == asc) ? mine_less : !mine_less;
+          if (!keep) { e1[r] = o1; e2[r] = o2; }
+        }
+        __syncthreads();
+      }
+      if (k > 128) wave_stage(std::integral_constant<int, 128>{}, k);
+      if (k > 64) wave_stage(std::integral_constant<int, 64>{}, k);
+      if (k > 32) wave_stage(std::integral_constant<int, 32>{}, k);
+      if (k > 16) wave_stage(std::integral_constant<int, 16>{}, k);
+      if (k > 8) wave_stage(std::integral_constant<int, 8>{}, k);
+      if (k > 4) wave_stage(std::integral_constant<int, 4>{}, k);
+      if (k > 2) reg_stage(2, k);
+      reg_stage(1, k);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) k2[tid * 4 + r] = e2[r];
@@ -606,8 +666,6 @@ __global__ __launch_bounds__(64) void append_single_kernel(SingleArgs a) {
     meta[META_CHUNK_NSP] = fits ? 1 : 0;
     meta[META_CHUNK_START] = c0;
     meta[META_CHUNK_LEN] = 1;
-    meta[META_SEL_CNT] = 0;
-    meta[META_LIST_LEN] = 0;
   }
 }
 
