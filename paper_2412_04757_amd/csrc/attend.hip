@@ -67,11 +67,24 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t off, uint32_t ld
 
 enum : int { MASK_NONE = 0, MASK_LIST_END = 1, MASK_CAUSAL = 2 };
 
+// max of three without the NaN-quieting copies fmaxf() carries (scores are never NaN here)
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+// acc + lo + hi of a packed bf16 pair (one v_dot2c_f32_bf16)
+__device__ __forceinline__ float pair_sum(uint32_t packed, float acc) {
+  const bf16x2_t one = {(__bf16)1.0f, (__bf16)1.0f};
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, packed), one, acc, false);
+}
+
 // max over lanes l and l ^ 32 without an LDS round trip: the swap leaves the low half of v in
 // both halves of r[0] and the high half in both halves of r[1]
 __device__ __forceinline__ float pair_max(float v) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  return max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1]));
 }
 
 // NW wavefronts per workgroup, each with NQB blocks of 32 query rows; DMA_NS ring stages.
@@ -120,20 +133,26 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   auto request_tokens = [&](int u) {
     if (wave == 0) dma4(list, (uint32_t)((u < n_ctx_tiles ? u * 64 : 0) + lane) * 4u, tok0 + (uint32_t)(u % TOK_SLOTS) * 256);
   };
-  // rows 4 NW i + 4 wave + lq (i < NI) of the tile, LDS piece lp of the row
+  // rows 4 NW i + 4 wave + lq (i < NI) of the tile, LDS piece lp of the row; the byte offset of
+  // the piece a lane fetches inside its row does not depend on the tile
   const int lq = lane >> 4, lp = lane & 15;
+  uint32_t kpiece[NI], vpiece[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int row = 4 * NW * i + 4 * wave + lq;
+    kpiece[i] = (uint32_t)((lp ^ (row & 15)) << 4);
+    vpiece[i] = (uint32_t)((lp ^ ((row & 3) << 1)) << 4);
+  }
   auto request_tile = [&](int t) {
     const uint32_t sbase = ring0 + (uint32_t)(t % DMA_NS) * DMA_STAGE_BYTES;
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const int rw = 4 * NW * i + 4 * wave;          // first of the wave's four rows (uniform)
-      int tok;
-      if (t < n_ctx_tiles) tok = max(tokring[(t % TOK_SLOTS) * 64 + rw + lq], 0);
+      int tok;                                       // list padding is token 0 (masked by position)
+      if (t < n_ctx_tiles) tok = tokring[(t % TOK_SLOTS) * 64 + rw + lq];
       else                 tok = c0 + min((t - n_ctx_tiles) * 64 + rw + lq, L - 1);
-      const int row = rw + lq;
-      const uint32_t off = (uint32_t)tok * 256u;
-      dma16(Kb, off + (uint32_t)((lp ^ (row & 15)) << 4), sbase + (uint32_t)rw * 256);
-      dma16(Vb, off + (uint32_t)((lp ^ ((row & 3) << 1)) << 4), sbase + 16384u + (uint32_t)rw * 256);
+      dma16(Kb, ((uint32_t)tok << 8) + kpiece[i], sbase + (uint32_t)rw * 256);
+      dma16(Vb, ((uint32_t)tok << 8) + vpiece[i], sbase + 16384u + (uint32_t)rw * 256);
     }
   };
   // top of iteration t: wait until tile t has landed, barrier, request tokens t + TOK_AHEAD and
@@ -216,6 +235,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
       };
       read_batch(0);
       read_batch(1);
+      __builtin_amdgcn_s_setprio(2);               // matrix-core phases go first when both waves of a SIMD are ready
       const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int bt = 0; bt < 4; ++bt) {
@@ -230,6 +250,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
                                                                   __builtin_bit_cast(bf16x8_t, qf[nq][2 * bt + k2]),
                                                                   (bt == 0 && k2 == 0) ? zero : s[kb][nq], 0, 0, 0);
       }
+      __builtin_amdgcn_s_setprio(0);
     }
     if constexpr (MK == MASK_CAUSAL) {
       const int k0 = (t - n_ctx_tiles) * 64;
@@ -263,26 +284,24 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
         const int kb = c >> 1, v0 = (c & 1) * 8;
-        m4[c] = fmaxf(fmaxf(s[kb][nq][v0], s[kb][nq][v0 + 1]), s[kb][nq][v0 + 2]);
-        m4[c] = fmaxf(fmaxf(m4[c], s[kb][nq][v0 + 3]), s[kb][nq][v0 + 4]);
-        m4[c] = fmaxf(fmaxf(m4[c], s[kb][nq][v0 + 5]), s[kb][nq][v0 + 6]);
-        m4[c] = fmaxf(m4[c], s[kb][nq][v0 + 7]);
+        m4[c] = max3(s[kb][nq][v0], s[kb][nq][v0 + 1], s[kb][nq][v0 + 2]);
+        m4[c] = max3(m4[c], s[kb][nq][v0 + 3], s[kb][nq][v0 + 4]);
+        m4[c] = max3(m4[c], s[kb][nq][v0 + 5], s[kb][nq][v0 + 6]);
       }
-      float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+      float mx = max3(max3(m4[0], s[0][nq][7], s[0][nq][15]), max3(m4[1], s[1][nq][7], s[1][nq][15]), max3(m4[2], m4[3], m4[2]));
       mx = pair_max(mx);
-      const float m_new = fmaxf(m_run[nq], mx * sc);
+      const float m_new = max3(m_run[nq], mx * sc, mx * sc);
       const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
       const bool changed = m_new != m_run[nq];
       m_run[nq] = m_new;
+      // the row sum is taken over the bf16-rounded probabilities (the values PV multiplies),
+      // two per instruction
       float ps = 0.f;
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         float pv[16];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][v], sc, -m_new));
-          ps += pv[v];
-        }
+        for (int v = 0; v < 16; ++v) pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][v], sc, -m_new));
 #pragma unroll
         for (int a2 = 0; a2 < 2; ++a2) {
           uint4 u;
@@ -291,6 +310,10 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
           u.z = pack_bf16x2(pv[8 * a2 + 4], pv[8 * a2 + 5]);
           u.w = pack_bf16x2(pv[8 * a2 + 6], pv[8 * a2 + 7]);
           pf[nq][kb][a2] = u;
+          ps = pair_sum(u.x, ps);
+          ps = pair_sum(u.y, ps);
+          ps = pair_sum(u.z, ps);
+          ps = pair_sum(u.w, ps);
         }
       }
       l_run[nq] = l_run[nq] * alpha + ps;
@@ -302,15 +325,21 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
       }
     }
     typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
+    // one LDS address per d-block; the (kb, a2, row group) part is a constant offset of the read
+    const uint32_t vs32 = ring0 + (uint32_t)(t % DMA_NS) * DMA_STAGE_BYTES + 16384u + vbase;
+    lds_s16x4_ptr vptr[4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+      vptr[mb] = (lds_s16x4_ptr)(uintptr_t)(vs32 + (vswz ^ (uint32_t)((4 * mb) << 4)));
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int a2 = 0; a2 < 2; ++a2)
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb) {
-          const unsigned char* pa = Vs + (vbase + (vswz ^ (uint32_t)((4 * mb) << 4))) + (kb * 32 + a2 * 16) * 256;
-          const s16x4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pa));
-          const s16x4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(pa + 8 * 256));
+          constexpr int ROWB = 256 / 8;                       // one key row in units of s16x4
+          const s16x4_t v0 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(vptr[mb] + (kb * 32 + a2 * 16) * ROWB);
+          const s16x4_t v1 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(vptr[mb] + (kb * 32 + a2 * 16 + 8) * ROWB);
           const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
           uint4 vf;
           vf.x = u0.x; vf.y = u0.y; vf.z = u1.x; vf.w = u1.y;

@@ -214,7 +214,7 @@ __device__ void emit_selection(const Dims& D, const DevState& st, int slot, cons
   if (fits) {
     for (int t = tid; t < n_win; t += blockDim.x) list[ns + n_ret + t] = ws + t;
     const int padded = min(D.list_cap, (len + ATT_BN - 1) / ATT_BN * ATT_BN);
-    for (int t = len + tid; t < padded; t += blockDim.x) list[t] = -1;
+    for (int t = len + tid; t < padded; t += blockDim.x) list[t] = 0;      // padding: a valid token, masked by position
   }
   if (tid == 0) {
     if (!fits) atomicCAS(&st.err[0], 0, LTRI_ECAPACITY);
