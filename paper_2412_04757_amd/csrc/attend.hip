@@ -141,7 +141,9 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   for (int i = 0; i < NI; ++i) {
     const int row = 4 * NW * i + 4 * wave + lq;
     kpiece[i] = (uint32_t)((lp ^ (row & 15)) << 4);
-    vpiece[i] = (uint32_t)((lp ^ ((row & 3) << 1)) << 4);
+    // V: LDS piece p' of a row holds global piece swap13(p' ^ ((row & 3) << 1)), swap13 = exchange of bits 1 and 3
+    const int vp = lp ^ ((row & 3) << 1);
+    vpiece[i] = (uint32_t)(((vp & 5) | ((vp & 2) << 2) | ((vp & 8) >> 2)) << 4);
   }
   auto request_tile = [&](int t) {
     const uint32_t sbase = ring0 + (uint32_t)(t % DMA_NS) * DMA_STAGE_BYTES;
@@ -213,9 +215,12 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   const int vj = lane & 15, vgq = (lane >> 4) & 1;
   const int vrow_in = 4 * hf + (vj >> 2);           // key row inside a group of 8
   const int vsw = (vrow_in & 3) << 1;
-  // V: d-block mb, piece (4 mb + p) ^ swizzle with p = 2 gq + (j & 3) / 2 < 4 and swizzle in bits 1..2
-  const uint32_t vbase = (uint32_t)(vrow_in * 256 + (((2 * vgq + ((vj & 3) >> 1)) ^ (vsw & 3)) << 4) + (vj & 1) * 8);
-  const uint32_t vswz = (uint32_t)((vsw & 4) << 4);
+  // V: the fragment of d-block mb needs global piece 4 mb + 2 gq + x (x = (j & 3) / 2). In LDS it sits at
+  // piece swap13(.) ^ swizzle = (gq << 3 | x) | ((mb & 1) << 2 | (mb >> 1) << 1) ^ swizzle: the two
+  // 16-lane groups of a half-wave read different 128-byte halves of their rows (no bank conflicts
+  // between them), and the four key rows of a group are spread by the swizzle in bits 1..2.
+  const uint32_t vbase = (uint32_t)(vrow_in * 256 + (((vgq << 3) | ((vj & 3) >> 1)) << 4) + (vj & 1) * 8);
+  const uint32_t vswz = (uint32_t)(vsw << 4);
 
   // ---- one tile: S^T = K Q^T, masks, online softmax (one query per lane pair), O^T += V^T P^T ----
   auto tile = [&](int t, auto mask_kind) {
@@ -330,7 +335,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
     lds_s16x4_ptr vptr[4];
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
-      vptr[mb] = (lds_s16x4_ptr)(uintptr_t)(vs32 + (vswz ^ (uint32_t)((4 * mb) << 4)));
+      vptr[mb] = (lds_s16x4_ptr)(uintptr_t)(vs32 + (vswz ^ (uint32_t)((((mb & 1) << 2) | ((mb >> 1) << 1)) << 4)));
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
