@@ -22,6 +22,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix rate
 PEAK_HBM_GBPS = 8000.0
+# HBM bytes per attend launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters
+# calibrated against copy kernels (profiles/attend_gather_hbm_traffic_cfg3.txt): (35428.9 * 2.00 + 16384.0) KiB
+ATTEND_TRAFFIC_BYTES_CFG3 = int((35428.9 * 2.00 + 16384.0) * 1024)
 
 
 def log(*a):
@@ -197,7 +200,7 @@ def main():
     last_tflops = sum(flops[i] for i in last) / (sum(att_ms[i] for i in last) * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "attend_bf16_kernel", "achieved": round(achieved, 2),
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                "traffic": None,
+                "traffic": ATTEND_TRAFFIC_BYTES_CFG3 if (args.workload == "cfg3" and not args.context) else None,
                 "avg_launch_us": round(tot_ms / len(events) * 1e3, 1),
                 "full_context_launch_us": round(sum(att_ms[i] for i in last) / len(last) * 1e3, 1),
                 "full_context_achieved": round(last_tflops, 2)}
