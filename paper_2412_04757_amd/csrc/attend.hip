@@ -30,7 +30,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 // ---- bf16 kernel ----
 // K and V tiles go from global memory straight into LDS (global_load_lds, 16 bytes per lane, no
-// registers in between) through a ring of four stages, so three tiles are in flight while one is
+// registers in between) through a ring of NS stages, so NS - 1 tiles are in flight while one is
 // being consumed and a single barrier per tile suffices. Both tiles keep the row-major [key][d]
 // layout of the arena; inside a 256-byte row the sixteen 16-byte pieces are permuted (XOR with a
 // function of the row) so that the fragment reads are free of bank conflicts; the permutation is
@@ -40,21 +40,25 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // row0 .. row0 + 3.
 // The DMA is issued through inline assembly because the compiler would otherwise wait for ALL
 // outstanding DMA before any LDS read; completion is awaited by hand with s_waitcnt vmcnt(n),
-// n = DMA loads requested later than the tile about to be used.
+// n = DMA loads requested later than the tile about to be used. Every wavefront issues the same
+// number of requests in every iteration (its rows of one K/V tile and the token ids of its rows
+// of a later tile; past the last tile the requests fetch the chunk's last row into a free stage),
+// so n is one constant.
+// The K fragments of a tile are requested together by hand (the compiler would serialise them
+// once registers are tight) and consumed in four groups; the DMA requests of a later tile are
+// issued between the groups, under the matrix products. The rescale of O is skipped while no
+// lane's running maximum moves.
 // The tile loop is cut into segments (context tiles, the ragged last context tile, chunk tiles
 // below the diagonal, chunk tiles on the diagonal, tiles this wavefront cannot see) so that the
 // body of each segment is straight-line code, with the masks compiled in or out.
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
-#ifndef ATT_NQB
-#define ATT_NQB 1
-#endif
 #ifndef ATT_NW
 #define ATT_NW 8
 #endif
 constexpr int DMA_STAGE_BYTES = 32768;          // K tile 16 KB + V tile 16 KB
-constexpr int TOK_SLOTS = 8;                    // ring of 64-entry token tiles (> TOK_AHEAD)
-constexpr int att_lds_bytes(int ns) { return ns * DMA_STAGE_BYTES + TOK_SLOTS * 256; }
+constexpr int TOK_SLOTS = 8;                    // ring of token-id tiles (> tokens-ahead distance)
+constexpr int att_lds_bytes(int ns, int nw) { return ns * DMA_STAGE_BYTES + TOK_SLOTS * nw * 32; }
 
 // 16 bytes per lane from base + off into LDS at lds_wave_base + 16 * lane
 __device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_wave_base) {
@@ -87,18 +91,34 @@ __device__ __forceinline__ float pair_max(float v) {
   return max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1]));
 }
 
-// NW wavefronts per workgroup, each with NQB blocks of 32 query rows; DMA_NS ring stages.
-template <int NQB, int NW, int DMA_NS>
+// 16-byte LDS read issued by hand; LDS reads return in order, and the loop holds no scalar loads
+// that could disturb the count awaited below
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+template <int OFF>
+__device__ __forceinline__ u32x4_t lds_read16(uint32_t addr) {
+  u32x4_t r;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
+// at most N LDS reads still outstanding; ties the four fragments about to be used to the wait
+template <int N>
+__device__ __forceinline__ void lds_wait(u32x4_t& a, u32x4_t& b, u32x4_t& c, u32x4_t& d) {
+  asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : "n"(N));
+}
+
+// NW wavefronts per workgroup, each with 32 query rows of one head; NS ring stages.
+template <int NW, int NS>
 __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
-  constexpr int TOK_AHEAD = 2 * (DMA_NS - 1);       // token tile t + TOK_AHEAD is requested in iteration t
-  constexpr int QW = 32 * NQB;
+  constexpr int TOK_AHEAD = 2 * (NS - 1) + 1;       // token ids of tile t + TOK_AHEAD are requested in iteration t
   constexpr int NI = 16 / NW;                       // DMA row groups per wave and tile
-  constexpr int DMA_LPT = 2 * NI;                   // K/V requests per lane and tile
+  constexpr int LPT = 2 * NI;                       // K/V requests per lane and tile
+  constexpr int IN_FLIGHT = (NS - 2) * (LPT + 1);   // requests that may be pending when a tile is used
+  static_assert(NS >= 3 && NS <= 4 && TOK_AHEAD < TOK_SLOTS && NI == 2, "request pattern");
   extern __shared__ __attribute__((aligned(16))) unsigned char ring[];
   const Dims& D = a.D;
   const int HG = D.G < 4 ? D.G : 4;                 // heads of the group handled by this block
   const int RS = NW / HG;                           // row sub-tiles per block
-  const int RPB = QW * RS;                          // query rows per block
+  const int RPB = 32 * RS;                          // query rows per block
   const int gpk = D.G / HG;                         // blocks per KV head
   // KV head along x: consecutive workgroup ids go to different XCDs, so all query tiles of one
   // KV head run on one XCD and share its K/V rows in that XCD's L2
@@ -110,7 +130,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   const int l32 = lane & 31, hf = lane >> 5;
   const int head = h * D.G + gsub * HG + (wave % HG);
   const int rb0 = blockIdx.y * RPB;                 // first row of the block
-  const int r0 = rb0 + (wave / HG) * QW;            // first row of this wave
+  const int r0 = rb0 + (wave / HG) * 32;            // first row of this wave
   const int slot = slot_of(D, a.layer, seq, h);
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.k_arena) + arena_off(D, slot) * 2;
   const unsigned char* Vb = reinterpret_cast<const unsigned char*>(a.v_arena) + arena_off(D, slot) * 2;
@@ -122,19 +142,20 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   const int n_chunk_tiles = (rb_end + 63) / 64;
   const int n_tiles = n_ctx_tiles + n_chunk_tiles;
   const uint32_t ring0 = (uint32_t)(uintptr_t)ring;
-  const uint32_t tok0 = ring0 + DMA_NS * DMA_STAGE_BYTES;
-  const int32_t* tokring = reinterpret_cast<const int32_t*>(ring + DMA_NS * DMA_STAGE_BYTES);
+  const uint32_t tok0 = ring0 + NS * DMA_STAGE_BYTES + (uint32_t)wave * 32;       // this wave's 8 ids of slot 0
+  const int32_t* tokring = reinterpret_cast<const int32_t*>(ring + NS * DMA_STAGE_BYTES) + wave * 8;
 
   // ---- requests ----
-  // Token ids of the context tiles travel through LDS as well: wavefront 0 requests the 64 list
-  // entries of tile u in iteration u - TOK_AHEAD, before that iteration's K/V request, so they
-  // have landed (and passed a barrier) when tile u's rows are requested NS - 1 iterations later.
-  // Tiles past the list read a dummy address: every iteration requests the same number of loads.
+  // A wavefront fetches rows 4 NW i + 4 wave + lq (i < NI, lq = lane / 16) of every tile, lane
+  // piece lp = lane % 16 of the row. The token ids of its own eight rows travel through LDS the
+  // same way (lanes 0 .. 7, id j = 4 i + lq), TOK_AHEAD tiles ahead; no other wave reads them, so
+  // the wave's own wait makes them visible. Tiles past the list read a dummy entry.
   auto request_tokens = [&](int u) {
-    if (wave == 0) dma4(list, (uint32_t)((u < n_ctx_tiles ? u * 64 : 0) + lane) * 4u, tok0 + (uint32_t)(u % TOK_SLOTS) * 256);
+    if (lane < 8) {
+      const int row = 4 * NW * (lane >> 2) + 4 * wave + (lane & 3);
+      dma4(list, (uint32_t)((u < n_ctx_tiles ? u * 64 : 0) + row) * 4u, tok0 + (uint32_t)(u % TOK_SLOTS) * (NW * 32));
+    }
   };
-  // rows 4 NW i + 4 wave + lq (i < NI) of the tile, LDS piece lp of the row; the byte offset of
-  // the piece a lane fetches inside its row does not depend on the tile
   const int lq = lane >> 4, lp = lane & 15;
   uint32_t kpiece[NI], vpiece[NI];
 #pragma unroll
@@ -145,197 +166,189 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
     const int vp = lp ^ ((row & 3) << 1);
     vpiece[i] = (uint32_t)(((vp & 5) | ((vp & 2) << 2) | ((vp & 8) >> 2)) << 4);
   }
-  auto request_tile = [&](int t) {
-    const uint32_t sbase = ring0 + (uint32_t)(t % DMA_NS) * DMA_STAGE_BYTES;
+  // tokens of the rows this lane fetches in tile t (list padding is token 0, masked by position;
+  // past the last tile: the chunk's last token)
+  auto tile_tokens = [&](int t, int (&tok)[NI]) {
+    if (t < n_ctx_tiles) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int rw = 4 * NW * i + 4 * wave;          // first of the wave's four rows (uniform)
-      int tok;                                       // list padding is token 0 (masked by position)
-      if (t < n_ctx_tiles) tok = tokring[(t % TOK_SLOTS) * 64 + rw + lq];
-      else                 tok = c0 + min((t - n_ctx_tiles) * 64 + rw + lq, L - 1);
-      dma16(Kb, ((uint32_t)tok << 8) + kpiece[i], sbase + (uint32_t)rw * 256);
-      dma16(Vb, ((uint32_t)tok << 8) + vpiece[i], sbase + 16384u + (uint32_t)rw * 256);
+      for (int i = 0; i < NI; ++i) tok[i] = tokring[(t % TOK_SLOTS) * (NW * 8) + 4 * i + lq];
+    } else {
+#pragma unroll
+      for (int i = 0; i < NI; ++i) tok[i] = c0 + min((t - n_ctx_tiles) * 64 + 4 * NW * i + 4 * wave + lq, L - 1);
     }
   };
-  // top of iteration t: wait until tile t has landed, barrier, request tokens t + TOK_AHEAD and
-  // tile t + NS - 1. Requested after tile t: the NS - 2 following iterations' token requests
-  // (wavefront 0 only) and those of their tiles that exist.
-  auto advance = [&](int t) {
-    const int later = min(DMA_NS - 2, n_tiles - 1 - t);
-    if (wave == 0) {
-      if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_LPT + DMA_NS - 2) : "memory");
-      else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT + DMA_NS - 2) : "memory");
-      else                 asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_NS - 2) : "memory");
-    } else {
-      if (later >= 2)      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_LPT) : "memory");
-      else if (later == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(DMA_LPT) : "memory");
-      else                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    __syncthreads();            // tile t is in LDS for every wave; tile t - 1's stage is free
-    request_tokens(t + TOK_AHEAD);
-    if (t + DMA_NS - 1 < n_tiles) request_tile(t + DMA_NS - 1);
+  auto request_rows = [&](int t, int i, int tok) {
+    const uint32_t dst = ring0 + (uint32_t)(t % NS) * DMA_STAGE_BYTES + (uint32_t)(4 * NW * i + 4 * wave) * 256;
+    dma16(Kb, ((uint32_t)tok << 8) + kpiece[i], dst);
+    dma16(Vb, ((uint32_t)tok << 8) + vpiece[i], dst + 16384u);
   };
 
   // ---- query fragments: B operand of S^T = K Q^T; lane (l32, hf) holds Q[row l32][16 kk + 8 hf ..] ----
-  uint4 qf[NQB][8];
+  uint4 qf[8];
   {
     const uint16_t* Qb = reinterpret_cast<const uint16_t*>(a.q) + (size_t)bi * L * D.Hq * d;
+    const int row = min(r0 + l32, L - 1);
+    const uint16_t* qrow = Qb + ((size_t)row * D.Hq + head) * d;
 #pragma unroll
-    for (int nq = 0; nq < NQB; ++nq) {
-      const int row = min(r0 + nq * 32 + l32, L - 1);
-      const uint16_t* qrow = Qb + ((size_t)row * D.Hq + head) * d;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) qf[nq][kk] = *reinterpret_cast<const uint4*>(qrow + kk * 16 + hf * 8);
-    }
+    for (int kk = 0; kk < 8; ++kk) qf[kk] = *reinterpret_cast<const uint4*>(qrow + kk * 16 + hf * 8);
   }
   // The fragments are "used" here so that the compiler's wait for these loads sits before the
   // loop: a wait for them inside the loop would also wait for every DMA request in flight.
 #pragma unroll
-  for (int nq = 0; nq < NQB; ++nq)
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk)
-      asm volatile("" ::"v"(qf[nq][kk].x), "v"(qf[nq][kk].y), "v"(qf[nq][kk].z), "v"(qf[nq][kk].w));
+  for (int kk = 0; kk < 8; ++kk)
+    asm volatile("" ::"v"(qf[kk].x), "v"(qf[kk].y), "v"(qf[kk].z), "v"(qf[kk].w));
 
-  f32x16_t o[4][NQB];
+  f32x16_t o[4];
 #pragma unroll
   for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-    for (int nq = 0; nq < NQB; ++nq)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[mb][nq][v] = 0.f;
-  float m_run[NQB], l_run[NQB];
-#pragma unroll
-  for (int nq = 0; nq < NQB; ++nq) { m_run[nq] = -1e30f; l_run[nq] = 0.f; }
+    for (int v = 0; v < 16; ++v) o[mb][v] = 0.f;
+  float m_run = -1e30f, l_run = 0.f;                // running maximum (log2 domain) and sum
   const float sc = 1.4426950408889634f / sqrtf((float)d);     // log2(e) / sqrt(d)
 
   // per-lane parts of the fragment addresses
   // K: row l32 (+ 32 kb), piece (2 kk + hf) ^ (row & 15) = ((2 kk) ^ (row & 14)) | (hf ^ (row & 1))
   const uint32_t kbase = (uint32_t)(l32 * 256 + ((hf ^ (l32 & 1)) << 4));
   const uint32_t kswz = (uint32_t)((l32 & 14) << 4);
+  uint32_t koff[8];                                 // fragment kk of rows l32 and l32 + 32 (+ 8192)
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) koff[kk] = ring0 + kbase + (kswz ^ (uint32_t)(kk << 5));
   const int vj = lane & 15, vgq = (lane >> 4) & 1;
   const int vrow_in = 4 * hf + (vj >> 2);           // key row inside a group of 8
-  const int vsw = (vrow_in & 3) << 1;
   // V: the fragment of d-block mb needs global piece 4 mb + 2 gq + x (x = (j & 3) / 2). In LDS it sits at
   // piece swap13(.) ^ swizzle = (gq << 3 | x) | ((mb & 1) << 2 | (mb >> 1) << 1) ^ swizzle: the two
   // 16-lane groups of a half-wave read different 128-byte halves of their rows (no bank conflicts
   // between them), and the four key rows of a group are spread by the swizzle in bits 1..2.
   const uint32_t vbase = (uint32_t)(vrow_in * 256 + (((vgq << 3) | ((vj & 3) >> 1)) << 4) + (vj & 1) * 8);
-  const uint32_t vswz = (uint32_t)(vsw << 4);
+  const uint32_t vswz = (uint32_t)(((vrow_in & 3) << 1) << 4);
+  uint32_t voff[4];                                 // d-block mb
+#pragma unroll
+  for (int mb = 0; mb < 4; ++mb)
+    voff[mb] = ring0 + 16384u + vbase + (vswz ^ (uint32_t)((((mb & 1) << 2) | ((mb >> 1) << 1)) << 4));
 
-  // ---- one tile: S^T = K Q^T, masks, online softmax (one query per lane pair), O^T += V^T P^T ----
-  auto tile = [&](int t, auto mask_kind) {
+  int tokreg[NI];                                   // tokens of the rows of the next tile to request
+
+  // ---- one iteration: wait for tile t, barrier, S^T = K Q^T with the requests of tile t + NS - 1
+  //      between the products, masks, online softmax (one query per lane pair), O^T += V^T P^T.
+  //      compute = false: a tile this wavefront cannot see (requests, wait and barrier only) ----
+  auto tile = [&](int t, auto mask_kind, auto compute_kind) {
     constexpr int MK = decltype(mask_kind)::value;
-    const unsigned char* Ks = ring + (t % DMA_NS) * DMA_STAGE_BYTES;
-    const unsigned char* Vs = Ks + 16384;
-    f32x16_t s[2][NQB];
-    {
-      // fragments in four batches (two kk each); two batches are in flight ahead of the products
-      uint4 kf[4][2][2];
-      auto read_batch = [&](int bt) {
+    constexpr bool COMPUTE = decltype(compute_kind)::value;
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(IN_FLIGHT) : "memory");
+    __syncthreads();            // tile t is in LDS for every wave; tile t - 1's stage is free
+    const uint32_t sbase = (uint32_t)(t % NS) * DMA_STAGE_BYTES;
+    int toknext[NI];
+    tile_tokens(t + NS, toknext);
+    f32x16_t s[2];
+    if constexpr (COMPUTE) {
+      // all sixteen K fragments are requested at once (index 2 kk + kb) and used in groups of four
+      u32x4_t kf[16];
 #pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-            kf[bt][k2][kb] = *reinterpret_cast<const uint4*>(Ks + (kbase + (kswz ^ (uint32_t)((2 * (2 * bt + k2)) << 4))) + kb * 8192);
-      };
-      read_batch(0);
-      read_batch(1);
-      __builtin_amdgcn_s_setprio(2);               // matrix-core phases go first when both waves of a SIMD are ready
-      const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int bt = 0; bt < 4; ++bt) {
-        if (bt + 2 < 4) read_batch(bt + 2);
-#pragma unroll
-        for (int k2 = 0; k2 < 2; ++k2)
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int nq = 0; nq < NQB; ++nq)
-              s[kb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[bt][k2][kb]),
-                                                                  __builtin_bit_cast(bf16x8_t, qf[nq][2 * bt + k2]),
-                                                                  (bt == 0 && k2 == 0) ? zero : s[kb][nq], 0, 0, 0);
+      for (int kk = 0; kk < 8; ++kk) {
+        kf[2 * kk] = lds_read16<0>(sbase + koff[kk]);
+        kf[2 * kk + 1] = lds_read16<8192>(sbase + koff[kk]);
       }
+#ifndef ATT_NOPRIO
+      __builtin_amdgcn_s_setprio(2);               // matrix-core phases go first when both waves of a SIMD are ready
+#endif
+      const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      auto group = [&](int g) {
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, kf[4 * g + 2 * k2 + kb]),
+                                                            __builtin_bit_cast(bf16x8_t, qf[2 * g + k2]),
+                                                            (g == 0 && k2 == 0) ? zero : s[kb], 0, 0, 0);
+      };
+      // the scheduling barriers keep each group's products between its wait and the next one
+      lds_wait<12>(kf[0], kf[1], kf[2], kf[3]);     group(0); __builtin_amdgcn_sched_barrier(0);
+      request_tokens(t + TOK_AHEAD);
+      request_rows(t + NS - 1, 0, tokreg[0]);
+      lds_wait<8>(kf[4], kf[5], kf[6], kf[7]);      group(1); __builtin_amdgcn_sched_barrier(0);
+      request_rows(t + NS - 1, 1, tokreg[1]);
+      lds_wait<4>(kf[8], kf[9], kf[10], kf[11]);    group(2); __builtin_amdgcn_sched_barrier(0);
+      lds_wait<0>(kf[12], kf[13], kf[14], kf[15]);  group(3);
+#ifndef ATT_NOPRIO
       __builtin_amdgcn_s_setprio(0);
+#endif
+    } else {
+      request_tokens(t + TOK_AHEAD);
+      request_rows(t + NS - 1, 0, tokreg[0]);
+      request_rows(t + NS - 1, 1, tokreg[1]);
     }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) tokreg[i] = toknext[i];
+    if constexpr (!COMPUTE) return;
     if constexpr (MK == MASK_CAUSAL) {
       const int k0 = (t - n_ctx_tiles) * 64;
+      const int qi = r0 + l32;
 #pragma unroll
-      for (int nq = 0; nq < NQB; ++nq) {
-        const int qi = r0 + nq * 32 + l32;
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int kp = k0 + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-            if (kp > qi) s[kb][nq][v] = -INFINITY;
-          }
-      }
+        for (int v = 0; v < 16; ++v) {
+          const int kp = k0 + kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+          if (kp > qi) s[kb][v] = -INFINITY;
+        }
     } else if constexpr (MK == MASK_LIST_END) {
       const int nvalid = list_len - t * 64;
 #pragma unroll
-      for (int nq = 0; nq < NQB; ++nq)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int kr = kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-            if (kr >= nvalid) s[kb][nq][v] = -INFINITY;
-          }
-    }
-    uint4 pf[NQB][2][2];
-#pragma unroll
-    for (int nq = 0; nq < NQB; ++nq) {
-      float m4[4];                                   // four independent max chains, then a tree
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        const int kb = c >> 1, v0 = (c & 1) * 8;
-        m4[c] = max3(s[kb][nq][v0], s[kb][nq][v0 + 1], s[kb][nq][v0 + 2]);
-        m4[c] = max3(m4[c], s[kb][nq][v0 + 3], s[kb][nq][v0 + 4]);
-        m4[c] = max3(m4[c], s[kb][nq][v0 + 5], s[kb][nq][v0 + 6]);
-      }
-      float mx = max3(max3(m4[0], s[0][nq][7], s[0][nq][15]), max3(m4[1], s[1][nq][7], s[1][nq][15]), max3(m4[2], m4[3], m4[2]));
-      mx = pair_max(mx);
-      const float m_new = max3(m_run[nq], mx * sc, mx * sc);
-      const float alpha = __builtin_amdgcn_exp2f(m_run[nq] - m_new);
-      const bool changed = m_new != m_run[nq];
-      m_run[nq] = m_new;
-      // the row sum is taken over the bf16-rounded probabilities (the values PV multiplies),
-      // two per instruction
-      float ps = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        float pv[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][nq][v], sc, -m_new));
-#pragma unroll
-        for (int a2 = 0; a2 < 2; ++a2) {
-          uint4 u;
-          u.x = pack_bf16x2(pv[8 * a2 + 0], pv[8 * a2 + 1]);
-          u.y = pack_bf16x2(pv[8 * a2 + 2], pv[8 * a2 + 3]);
-          u.z = pack_bf16x2(pv[8 * a2 + 4], pv[8 * a2 + 5]);
-          u.w = pack_bf16x2(pv[8 * a2 + 6], pv[8 * a2 + 7]);
-          pf[nq][kb][a2] = u;
-          ps = pair_sum(u.x, ps);
-          ps = pair_sum(u.y, ps);
-          ps = pair_sum(u.z, ps);
-          ps = pair_sum(u.w, ps);
+        for (int v = 0; v < 16; ++v) {
+          const int kr = kb * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+          if (kr >= nvalid) s[kb][v] = -INFINITY;
         }
-      }
-      l_run[nq] = l_run[nq] * alpha + ps;
-      if (__any(changed)) {                         // the running maximum rarely moves after the first tiles
+    }
+    float m4[4];                                     // four independent max chains, then a tree
 #pragma unroll
-        for (int mb = 0; mb < 4; ++mb)
+    for (int c = 0; c < 4; ++c) {
+      const int kb = c >> 1, v0 = (c & 1) * 8;
+      m4[c] = max3(s[kb][v0], s[kb][v0 + 1], s[kb][v0 + 2]);
+      m4[c] = max3(m4[c], s[kb][v0 + 3], s[kb][v0 + 4]);
+      m4[c] = max3(m4[c], s[kb][v0 + 5], s[kb][v0 + 6]);
+    }
+    float mx = max3(max3(m4[0], s[0][7], s[0][15]), max3(m4[1], s[1][7], s[1][15]), max3(m4[2], m4[3], m4[2]));
+    mx = pair_max(mx);
+    const float m_new = max3(m_run, mx * sc, mx * sc);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const bool changed = m_new != m_run;
+    m_run = m_new;
+    // probabilities, rounded to bf16 in B-operand order; the row sum is taken over the rounded
+    // values (the ones PV multiplies), two per instruction
+    uint4 pf[2][2];
+    float ps = 0.f;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) o[mb][nq][v] *= alpha;
+    for (int kb = 0; kb < 2; ++kb) {
+      float pv[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) pv[v] = __builtin_amdgcn_exp2f(fmaf(s[kb][v], sc, -m_new));
+#pragma unroll
+      for (int a2 = 0; a2 < 2; ++a2) {
+        uint4 u;
+        u.x = pack_bf16x2(pv[8 * a2 + 0], pv[8 * a2 + 1]);
+        u.y = pack_bf16x2(pv[8 * a2 + 2], pv[8 * a2 + 3]);
+        u.z = pack_bf16x2(pv[8 * a2 + 4], pv[8 * a2 + 5]);
+        u.w = pack_bf16x2(pv[8 * a2 + 6], pv[8 * a2 + 7]);
+        pf[kb][a2] = u;
+        ps = pair_sum(u.x, ps);
+        ps = pair_sum(u.y, ps);
+        ps = pair_sum(u.z, ps);
+        ps = pair_sum(u.w, ps);
       }
+    }
+    l_run = l_run * alpha + ps;
+    if (__any(changed)) {                           // the running maximum rarely moves after the first tiles
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[mb][v] *= alpha;
     }
     typedef s16x4_t __attribute__((address_space(3))) * lds_s16x4_ptr;
     // one LDS address per d-block; the (kb, a2, row group) part is a constant offset of the read
-    const uint32_t vs32 = ring0 + (uint32_t)(t % DMA_NS) * DMA_STAGE_BYTES + 16384u + vbase;
     lds_s16x4_ptr vptr[4];
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
-      vptr[mb] = (lds_s16x4_ptr)(uintptr_t)(vs32 + (vswz ^ (uint32_t)((((mb & 1) << 2) | ((mb >> 1) << 1)) << 4)));
+    for (int mb = 0; mb < 4; ++mb) vptr[mb] = (lds_s16x4_ptr)(uintptr_t)(sbase + voff[mb]);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -348,62 +361,60 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
           const uint2 u0 = __builtin_bit_cast(uint2, v0), u1 = __builtin_bit_cast(uint2, v1);
           uint4 vf;
           vf.x = u0.x; vf.y = u0.y; vf.z = u1.x; vf.w = u1.y;
-#pragma unroll
-          for (int nq = 0; nq < NQB; ++nq)
-            o[mb][nq] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf),
-                                                                __builtin_bit_cast(bf16x8_t, pf[nq][kb][a2]),
-                                                                o[mb][nq], 0, 0, 0);
+          o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, vf),
+                                                          __builtin_bit_cast(bf16x8_t, pf[kb][a2]), o[mb], 0, 0, 0);
         }
   };
 
-  // ---- prologue: tokens of the first NS - 1 tiles, then the steady-state request pattern
-  //      (tokens u + TOK_AHEAD, K/V tile u + NS - 1) for u = -(NS - 1) .. -1 ----
-  static_assert(DMA_NS >= 2 && DMA_NS <= 4 && TOK_AHEAD < TOK_SLOTS, "vmcnt ladder and token ring sizes");
-  for (int u = 0; u < DMA_NS - 1; ++u) request_tokens(u);
+  // ---- prologue: token ids of the first NS tiles, then the steady-state request pattern
+  //      (ids of tile u + TOK_AHEAD, K/V tile u + NS - 1) for u = -(NS - 1) .. -1 ----
+  for (int u = 0; u < NS; ++u) request_tokens(u);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
-  for (int u = 0; u < DMA_NS - 1; ++u) {
-    request_tokens(u + DMA_NS - 1);
-    if (u < n_tiles) request_tile(u);
+  for (int u = 0; u < NS - 1; ++u) {
+    request_tokens(u + NS);
+    tile_tokens(u, tokreg);
+    request_rows(u, 0, tokreg[0]);
+    request_rows(u, 1, tokreg[1]);
   }
+  tile_tokens(NS - 1, tokreg);
 
   // ---- tile segments of this wavefront ----
   const bool active = r0 < L;
   const int t_list_end = (list_len & 63) ? n_ctx_tiles - 1 : n_ctx_tiles;       // first masked context tile
-  // chunk tile kt (keys 64 kt ..) is fully visible to the wave iff 64 kt + 63 <= r0, visible iff 64 kt <= r0 + QW - 1
+  // chunk tile kt (keys 64 kt ..) is fully visible to the wave iff 64 kt + 63 <= r0, visible iff 64 kt <= r0 + 31
   const int t_diag = n_ctx_tiles + (active ? min(n_chunk_tiles, (r0 + 1) / 64) : 0);
-  const int t_end = active ? n_ctx_tiles + min(n_chunk_tiles, (r0 + QW - 1) / 64 + 1) : 0;
+  const int t_end = active ? n_ctx_tiles + min(n_chunk_tiles, (r0 + 31) / 64 + 1) : 0;
+  using std::integral_constant;
+  using std::true_type;
+  using std::false_type;
   int t = 0;
   if (active) {
-    for (; t < t_list_end; ++t) { advance(t); tile(t, std::integral_constant<int, MASK_NONE>{}); }
-    for (; t < n_ctx_tiles; ++t) { advance(t); tile(t, std::integral_constant<int, MASK_LIST_END>{}); }
-    for (; t < t_diag; ++t) { advance(t); tile(t, std::integral_constant<int, MASK_NONE>{}); }
-    for (; t < t_end; ++t) { advance(t); tile(t, std::integral_constant<int, MASK_CAUSAL>{}); }
+    for (; t < t_list_end; ++t) tile(t, integral_constant<int, MASK_NONE>{}, true_type{});
+    for (; t < n_ctx_tiles; ++t) tile(t, integral_constant<int, MASK_LIST_END>{}, true_type{});
+    for (; t < t_diag; ++t) tile(t, integral_constant<int, MASK_NONE>{}, true_type{});
+    for (; t < t_end; ++t) tile(t, integral_constant<int, MASK_CAUSAL>{}, true_type{});
   }
-  for (; t < n_tiles; ++t) advance(t);               // tiles this wavefront cannot see: barriers and requests only
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the dummy token requests of the last iterations
+  for (; t < n_tiles; ++t) tile(t, integral_constant<int, MASK_NONE>{}, false_type{});
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests past the last tile
 
   // ---- epilogue ----
   uint16_t* Ob = reinterpret_cast<uint16_t*>(a.out) + (size_t)bi * L * D.Hq * d;
+  const int qi = r0 + l32;
+  const float lt = l_run + __shfl_xor(l_run, 32, 64);
+  if (qi < L) {
+    const float inv = 1.f / lt;
+    uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
 #pragma unroll
-  for (int nq = 0; nq < NQB; ++nq) {
-    const int qi = r0 + nq * 32 + l32;
-    const float lt = l_run[nq] + __shfl_xor(l_run[nq], 32, 64);
-    if (qi < L) {
-      const float inv = 1.f / lt;
-      uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
+    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-      for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-        for (int a4 = 0; a4 < 4; ++a4) {
-          uint2 u;
-          u.x = pack_bf16x2(o[mb][nq][4 * a4 + 0] * inv, o[mb][nq][4 * a4 + 1] * inv);
-          u.y = pack_bf16x2(o[mb][nq][4 * a4 + 2] * inv, o[mb][nq][4 * a4 + 3] * inv);
-          *reinterpret_cast<uint2*>(orow + mb * 32 + 8 * a4 + 4 * hf) = u;
-        }
-      if (a.lse && hf == 0)
-        a.lse[((size_t)bi * L + qi) * D.Hq + head] = (m_run[nq] + log2f(lt)) * 0.6931471805599453f;
-    }
+      for (int a4 = 0; a4 < 4; ++a4) {
+        uint2 u;
+        u.x = pack_bf16x2(o[mb][4 * a4 + 0] * inv, o[mb][4 * a4 + 1] * inv);
+        u.y = pack_bf16x2(o[mb][4 * a4 + 2] * inv, o[mb][4 * a4 + 3] * inv);
+        *reinterpret_cast<uint2*>(orow + mb * 32 + 8 * a4 + 4 * hf) = u;
+      }
+    if (a.lse && hf == 0)
+      a.lse[((size_t)bi * L + qi) * D.Hq + head] = (m_run + log2f(lt)) * 0.6931471805599453f;
   }
 }
 
@@ -513,21 +524,21 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
   if (mfma_ok) {
     const int HG = D.G < 4 ? D.G : 4;
     const int gpk = D.G / HG;
-    constexpr int NQB = ATT_NQB, NW = ATT_NW;
-    const int RPB = 32 * NQB * (NW / HG);
+    constexpr int NW = ATT_NW;
+    const int RPB = 32 * (NW / HG);
     dim3 g(D.Hkv * gpk, (n_q + RPB - 1) / RPB, seq_count);
     static bool attr_set = false;
     if (!attr_set) {
-      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<NQB, NW, 4>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, att_lds_bytes(4));
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<NW, 4>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, att_lds_bytes(4, NW));
       if (e != hipSuccess) return e;
-      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<NQB, NW, 3>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, att_lds_bytes(3));
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<NW, 3>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, att_lds_bytes(3, NW));
       if (e != hipSuccess) return e;
       attr_set = true;
     }
-    if (stages == 3) attend_bf16_kernel<NQB, NW, 3><<<g, 64 * NW, att_lds_bytes(3), s>>>(a);
-    else             attend_bf16_kernel<NQB, NW, 4><<<g, 64 * NW, att_lds_bytes(4), s>>>(a);
+    if (stages == 3) attend_bf16_kernel<NW, 3><<<g, 64 * NW, att_lds_bytes(3, NW), s>>>(a);
+    else             attend_bf16_kernel<NW, 4><<<g, 64 * NW, att_lds_bytes(4, NW), s>>>(a);
   } else {
     dim3 g(n_q, D.Hq, seq_count);
     if (D.dtype == LTRI_BF16) attend_simple_kernel<LTRI_BF16><<<g, 64, 0, s>>>(a);
