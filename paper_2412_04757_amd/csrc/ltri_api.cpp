@@ -107,6 +107,8 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.ccar = o;   o = align_up(o + (size_t)P * nb * Lp * 8, 256);
   CL.pscore = o; o = align_up(o + (size_t)P * nt * 128 * 8, 256);
   CL.px = o;     o = align_up(o + (size_t)P * nt * 128 * 4, 256);
+  CL.ckey = o;   o = align_up(o + (size_t)P * SEG_MAX_DIAG * 8, 256);
+  CL.cxy = o;    o = align_up(o + (size_t)P * SEG_MAX_DIAG * 4, 256);
   CL.lse = o;    o = align_up(o + (size_t)P * G * Lp * 8, 256);
   // query-span representatives are needed for every sequence of a batched retrieve
   CL.qrep = o;   o = align_up(o + (size_t)c.n_seqs * c.n_kv_heads * Lp * D.d * D.elt, 256);
@@ -168,7 +170,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   char* t = c->scratch;
   c->dc = DevScratch{(double*)(t + CL.rowsum), (double*)(t + CL.csuf), (double*)(t + CL.tsum),
                      (double*)(t + CL.rcar), (double*)(t + CL.ccar), (double*)(t + CL.pscore),
-                     (int32_t*)(t + CL.px), (double*)(t + CL.lse), (void*)(t + CL.qrep),
+                     (int32_t*)(t + CL.px), (uint64_t*)(t + CL.ckey), (uint32_t*)(t + CL.cxy), (double*)(t + CL.lse), (void*)(t + CL.qrep),
                      (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds)};
   const size_t n = (size_t)D.n_layers * D.n_seqs;
   c->n_tokens.assign(n, 0);

@@ -23,6 +23,7 @@ enum : int {
 constexpr int SEG_TB = 64;          // side of a segmentation tile
 constexpr int SEG_MAX_L = 2048;     // longest chunk the segmentation kernels take
 constexpr int SEG_MAX_NB = SEG_MAX_L / SEG_TB;
+constexpr int SEG_MAX_DIAG = 2 * SEG_MAX_L;   // anti-diagonals of the largest map (2 L - 1), rounded up
 constexpr int ATT_BN = 64;          // keys per attention tile; token lists are padded to it
 
 // Byte offsets of the arrays inside the caller's `state` buffer.
@@ -47,6 +48,8 @@ struct ScratchLayout {
   size_t ccar;     // double [P][nb][Lp]   column carry A[I][x]
   size_t pscore;   // double [P][ntiles][128]
   size_t px;       // int32  [P][ntiles][128]
+  size_t ckey;     // uint64 [P][SEG_MAX_DIAG]  merged candidates: order key per anti-diagonal
+  size_t cxy;      // uint32 [P][SEG_MAX_DIAG]  x << 16 | y
   size_t lse;      // double [P][G][Lp]    (SOFTMAX map only)
   size_t qrep;     // dtype  [n_seqs * Hkv][Lp][d]
   size_t qpart;    // double [P][Lp / 128 + Lp][d]  sums of 128-token pieces of query spans
@@ -79,7 +82,7 @@ struct DevState {
 };
 struct DevScratch {
   double* rowsum; double* csuf; double* tsum; double* rcar; double* ccar;
-  double* pscore; int32_t* px; double* lse; void* qrep; double* qpart; int32_t* bounds;
+  double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds;
 };
 
 // ---- launchers (each returns the hipError_t of the launch) ----

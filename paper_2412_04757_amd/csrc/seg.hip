@@ -13,7 +13,7 @@
 // Pass 1 emits per-tile row sums / suffix-scanned column sums / totals, pass 2 turns them into
 // the carries, pass 3 recomputes each tile, finishes S = S* - theta * n_h * tri(y - x + 1)
 // (Eq. 5) and reduces every anti-diagonal x + y = s inside the tile; pass 4 merges the tile
-// results per anti-diagonal, sorts the candidates, runs the greedy NMS and cuts the chunk.
+// results per anti-diagonal, runs the greedy NMS (best live candidate first) and cuts the chunk.
 // All sums are fp64 in a fixed order, so the result is deterministic.
 #include "device_common.h"
 #include <type_traits>
@@ -343,13 +343,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   }
 }
 
-// ---- pass 4: candidates -> sort -> greedy NMS -> cuts -> span table ----
-__device__ __forceinline__ bool nms_suppressed(int x, int y, int kx, int ky, float phi) {
-  const int inter = min(y, ky) - max(x, kx) + 1;
-  if (inter <= 0) return false;
-  const int uni = (y - x + 1) + (ky - kx + 1) - inter;
-  return (float)inter > __fmul_rn(phi, (float)uni);
-}
+// ---- pass 4: candidates -> greedy NMS -> cuts -> span table ----
 
 // Value of lane (lane ^ M) for M = 1 .. 32, on the vector ALU (DPP / lane-swap instructions)
 // instead of the LDS crossbar that __shfl_xor goes through.
@@ -404,206 +398,128 @@ __device__ void append_spans(const Dims& D, const DevState& st, int slot, int c0
   }
 }
 
+// Pass 4a: per anti-diagonal s = x + y, merge the tiles' partial results (ties: larger x =
+// shorter span) and keep the span if S > 0 (appendix "NMS Input Filtration"). One thread per
+// anti-diagonal, many workgroups per problem: the partial results are ~100 bytes per
+// anti-diagonal and tile, far more than one CU reads quickly. Output: an order key (ascending
+// key = descending score: positive doubles order like their bit patterns) and x << 16 | y.
+__global__ __launch_bounds__(256) void seg_merge_kernel(SegArgs a) {
+  const int p = blockIdx.y, nb = a.nb, L = a.n_new;
+  const int n_diag = 2 * L - 1;
+  const int s = blockIdx.x * 256 + threadIdx.x;
+  if (s >= n_diag) return;
+  const double* pscore = a.sc.pscore + (size_t)p * a.ntiles * 128;
+  const int32_t* px = a.sc.px + (size_t)p * a.ntiles * 128;
+  double best = -INFINITY;
+  int bx = -1;
+  const int b = s >> 6;
+  for (int bb = b; bb >= b - 1 && bb >= 0; --bb) {
+    const int sloc = s - 64 * bb;
+    if (sloc > 126) continue;
+    // at most 16 tiles lie on one block anti-diagonal; all their entries are loaded before
+    // the comparison chain so that the loads are in flight together
+    const int J0 = max(0, bb - (nb - 1));
+    double vs[SEG_MAX_NB / 2];
+    int xs[SEG_MAX_NB / 2];
+#pragma unroll
+    for (int q = 0; q < SEG_MAX_NB / 2; ++q) {
+      const int J = J0 + q;
+      const bool ok = 2 * J <= bb;
+      const int Jc = ok ? J : J0, I = bb - Jc;
+      const size_t idx = (size_t)(I * (I + 1) / 2 + Jc) * 128 + sloc;
+      vs[q] = pscore[idx];
+      xs[q] = ok ? px[idx] : -1;
+    }
+#pragma unroll
+    for (int q = 0; q < SEG_MAX_NB / 2; ++q) {
+      const double v = vs[q];
+      const int x = xs[q];
+      if (x >= 0 && (v > best || (v == best && x > bx))) { best = v; bx = x; }
+    }
+  }
+  const bool is_cand = bx >= 0 && best > 0.0;
+  a.sc.ckey[(size_t)p * SEG_MAX_DIAG + s] = is_cand ? ~(uint64_t)__double_as_longlong(best) : ~0ull;
+  a.sc.cxy[(size_t)p * SEG_MAX_DIAG + s] = is_cand ? (((uint32_t)bx << 16) | (uint32_t)(s - bx)) : 0xFFFFFFFFu;
+}
+
+// Pass 4b: greedy NMS (Sec. 3.2) over the candidates in the order (score descending, x ascending,
+// y ascending), then the partition. Taking the candidates in sorted order and skipping the
+// suppressed ones is the same as repeatedly taking the best candidate still alive, and the number
+// of kept spans is small, so no sort is done: every thread holds four candidates in registers;
+// one round = a workgroup-wide minimum of the order key over the live candidates, the winner is
+// kept, every candidate it suppresses (and the winner itself) dies. One workgroup per problem.
 __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
-  __shared__ uint64_t k1[4096];
-  __shared__ uint32_t k2[4096];
-  __shared__ int s_ncand, s_nkept, s_done, s_wtot[16];
+  __shared__ uint32_t kept[SEG_MAX_DIAG + 1];
+  __shared__ uint64_t s_w1[2][16];
+  __shared__ uint32_t s_w2[2][16];
+  __shared__ uint8_t flags[SEG_MAX_L + 64];
+  __shared__ int cutlist[SEG_MAX_L + 1];
+  __shared__ int s_wtot[16];
   const Dims& D = a.D;
   const int p = blockIdx.x, sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
   const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
-  const int L = a.n_new, nb = a.nb, tid = threadIdx.x;
+  const int L = a.n_new, tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
   const int n_diag = 2 * L - 1;
-  int n_sort = 64;
-  while (n_sort < n_diag) n_sort <<= 1;
-  if (tid == 0) { s_ncand = 0; s_nkept = 0; }
-  __syncthreads();
-  // merge the tiles' results per anti-diagonal (ties: larger x = shorter span); keep if S > 0
-  const double* pscore = a.sc.pscore + (size_t)p * a.ntiles * 128;
-  const int32_t* px = a.sc.px + (size_t)p * a.ntiles * 128;
-  for (int s = tid; s < n_sort; s += blockDim.x) {
-    double best = -INFINITY;
-    int bx = -1;
-    if (s < n_diag) {
-      const int b = s >> 6;
-      for (int bb = b; bb >= b - 1 && bb >= 0; --bb) {
-        const int sloc = s - 64 * bb;
-        if (sloc > 126) continue;
-        // at most 16 tiles lie on one block anti-diagonal; all their entries are loaded before
-        // the comparison chain so that the loads are in flight together
-        const int J0 = max(0, bb - (nb - 1));
-        double vs[SEG_MAX_NB / 2];
-        int xs[SEG_MAX_NB / 2];
+  uint64_t e1[4];
+  uint32_t e2[4];
 #pragma unroll
-        for (int q = 0; q < SEG_MAX_NB / 2; ++q) {
-          const int J = J0 + q;
-          const bool ok = 2 * J <= bb;
-          const int Jc = ok ? J : J0, I = bb - Jc;
-          const size_t idx = (size_t)(I * (I + 1) / 2 + Jc) * 128 + sloc;
-          vs[q] = pscore[idx];
-          xs[q] = ok ? px[idx] : -1;
-        }
-#pragma unroll
-        for (int q = 0; q < SEG_MAX_NB / 2; ++q) {
-          const double v = vs[q];
-          const int x = xs[q];
-          if (x >= 0 && (v > best || (v == best && x > bx))) { best = v; bx = x; }
-        }
-      }
-    }
-    const bool is_cand = bx >= 0 && best > 0.0;
-    if (is_cand) {
-      k1[s] = ~(uint64_t)__double_as_longlong(best);     // positive doubles order like their bits
-      k2[s] = ((uint32_t)bx << 16) | (uint32_t)(s - bx);
-    } else {
-      k1[s] = ~0ull;
-      k2[s] = 0xFFFFFFFFu;
-    }
-    const uint64_t cm = __ballot(is_cand);               // one LDS atomic per wavefront, not per candidate
-    if ((tid & 63) == 0 && cm) atomicAdd(&s_ncand, __popcll(cm));
+  for (int r = 0; r < 4; ++r) {
+    const int sd = tid + 1024 * r;
+    e1[r] = sd < n_diag ? a.sc.ckey[(size_t)p * SEG_MAX_DIAG + sd] : ~0ull;
+    e2[r] = sd < n_diag ? a.sc.cxy[(size_t)p * SEG_MAX_DIAG + sd] : 0xFFFFFFFFu;
   }
-  __syncthreads();
-  // Bitonic sort of 4096 (key1, key2) pairs by (score descending, x ascending, y ascending):
-  // thread t owns elements 4t..4t+3 in registers; partners at distance < 4 are exchanged in
-  // registers, < 256 by wavefront shuffles, >= 256 through LDS.
-  {
-    uint64_t e1[4];
-    uint32_t e2[4];
+  const int max_keep = D.max_keep;
+  const float phi = D.phi;
+  int nkept = 0;
+  for (int round = 0;; ++round) {
+    // best live candidate of the thread, the wavefront, the workgroup
+    uint64_t b1 = e1[0];
+    uint32_t b2 = e2[0];
+#pragma unroll
+    for (int r = 1; r < 4; ++r)
+      if (key_less(e1[r], e2[r], b1, b2)) { b1 = e1[r]; b2 = e2[r]; }
+    auto step = [&](auto mc) {
+      constexpr int M = decltype(mc)::value;
+      const uint32_t lo = lane_xor_c<M>((uint32_t)b1), hi = lane_xor_c<M>((uint32_t)(b1 >> 32));
+      const uint32_t o2 = lane_xor_c<M>(b2);
+      const uint64_t o1 = ((uint64_t)hi << 32) | lo;
+      if (key_less(o1, o2, b1, b2)) { b1 = o1; b2 = o2; }
+    };
+    step(std::integral_constant<int, 1>{});
+    step(std::integral_constant<int, 2>{});
+    step(std::integral_constant<int, 4>{});
+    step(std::integral_constant<int, 8>{});
+    step(std::integral_constant<int, 16>{});
+    step(std::integral_constant<int, 32>{});
+    const int buf = round & 1;                   // two buffers: one barrier per round
+    if (lane == 0) { s_w1[buf][wave] = b1; s_w2[buf][wave] = b2; }
+    __syncthreads();
+    uint64_t w1 = s_w1[buf][0];
+    uint32_t w2 = s_w2[buf][0];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) {
+      const uint64_t o1 = s_w1[buf][w];
+      const uint32_t o2 = s_w2[buf][w];
+      if (key_less(o1, o2, w1, w2)) { w1 = o1; w2 = o2; }
+    }
+    if (w1 == ~0ull) break;                      // nothing alive (uniform)
+    if (tid == 0) kept[nkept] = w2;
+    ++nkept;
+    if (max_keep > 0 && nkept >= max_keep) break;
+    const int kx = (int)(w2 >> 16), ky = (int)(w2 & 0xFFFFu);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int e = tid * 4 + r;
-      e1[r] = e < n_sort ? k1[e] : ~0ull;
-      e2[r] = e < n_sort ? k2[e] : 0xFFFFFFFFu;
-    }
-    __syncthreads();
-    // one compare-exchange stage with partners at distance J (compile time) inside the wavefront
-    auto wave_stage = [&](auto jc, int k) {
-      constexpr int J = decltype(jc)::value;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int e = tid * 4 + r;
-        const uint32_t lo = lane_xor_c<J / 4>((uint32_t)e1[r]);
-        const uint32_t hi = lane_xor_c<J / 4>((uint32_t)(e1[r] >> 32));
-        const uint32_t o2 = lane_xor_c<J / 4>(e2[r]);
-        const uint64_t o1 = ((uint64_t)hi << 32) | lo;
-        const bool asc = (e & k) == 0, lower = (e & J) == 0;
-        const bool mine_less = key_less(e1[r], e2[r], o1, o2);
-        const bool keep = (lower == asc) ? mine_less : !mine_less;   // lower slot of an ascending pair keeps the min
-        if (!keep) { e1[r] = o1; e2[r] = o2; }
-      }
-    };
-    auto reg_stage = [&](int j, int k) {                  // partners inside the thread (j = 2 or 1)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int pr = r ^ j;
-        if (pr > r) {
-          const int e = tid * 4 + r;
-          const bool asc = (e & k) == 0;
-          const bool less = key_less(e1[pr], e2[pr], e1[r], e2[r]);   // partner < mine
-          if (less == asc) {
-            const uint64_t t1 = e1[r]; e1[r] = e1[pr]; e1[pr] = t1;
-            const uint32_t t2 = e2[r]; e2[r] = e2[pr]; e2[pr] = t2;
-          }
-        }
-      }
-    };
-    for (int k = 2; k <= 4096; k <<= 1) {
-      for (int j = k >> 1; j >= 256; j >>= 1) {           // partners in other wavefronts: through LDS
-#pragma unroll
-        for (int r = 0; r < 4; ++r) { k1[tid * 4 + r] = e1[r]; k2[tid * 4 + r] = e2[r]; }
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const int e = tid * 4 + r, pe = e ^ j;
-          const uint64_t o1 = k1[pe];
-          const uint32_t o2 = k2[pe];
-          const bool asc = (e & k) == 0, lower = (e & j) == 0;
-          const bool mine_less = key_less(e1[r], e2[r], o1, o2);
-          const bool keep = (lower == asc) ? mine_less : !mine_less;
-          if (!keep) { e1[r] = o1; e2[r] = o2; }
-        }
-        __syncthreads();
-      }
-      if (k > 128) wave_stage(std::integral_constant<int, 128>{}, k);
-      if (k > 64) wave_stage(std::integral_constant<int, 64>{}, k);
-      if (k > 32) wave_stage(std::integral_constant<int, 32>{}, k);
-      if (k > 16) wave_stage(std::integral_constant<int, 16>{}, k);
-      if (k > 8) wave_stage(std::integral_constant<int, 8>{}, k);
-      if (k > 4) wave_stage(std::integral_constant<int, 4>{}, k);
-      if (k > 2) reg_stage(2, k);
-      reg_stage(1, k);
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) k2[tid * 4 + r] = e2[r];
-  }
-  __syncthreads();
-  // Greedy NMS in rounds of 1024 candidates (in sorted order). All threads test their candidate
-  // against the intervals kept so far; the survivors are compacted in order and the first
-  // wavefront resolves them among themselves, 64 at a time. With few, large spans almost every
-  // candidate dies in the parallel test. The kept list and the survivor list overwrite k1
-  // (the scores are no longer needed).
-  volatile uint32_t* kept = reinterpret_cast<volatile uint32_t*>(k1);
-  volatile uint32_t* alist = kept + 4096;
-  {
-    const int lane = tid & 63, wave = tid >> 6;
-    const int ncand = s_ncand, max_keep = D.max_keep;
-    const float phi = D.phi;
-    if (tid == 0) s_done = 0;
-    __syncthreads();
-    for (int base = 0; base < ncand; base += 1024) {
-      if (s_done) break;                                   // uniform: written before the last barrier
-      const int idx = base + tid;
-      const bool valid = idx < ncand;
-      const uint32_t xy = valid ? k2[idx] : 0u;
-      const int x = (int)(xy >> 16), y = (int)(xy & 0xFFFFu);
-      bool alive = valid;
-      const int nk0 = s_nkept;
-      for (int q = 0; q < nk0; ++q) {
-        const uint32_t kk = kept[q];
-        if (alive && nms_suppressed(x, y, (int)(kk >> 16), (int)(kk & 0xFFFFu), phi)) alive = false;
-      }
-      const uint64_t am = __ballot(alive);
-      if (lane == 0) s_wtot[wave] = __popcll(am);
-      __syncthreads();
-      int off = 0, total = 0;
-      for (int w = 0; w < 16; ++w) { if (w < wave) off += s_wtot[w]; total += s_wtot[w]; }
-      if (alive) alist[off + __popcll(am & ((1ull << lane) - 1ull))] = xy;
-      __syncthreads();
-      if (tid < 64) {
-        int nkept = nk0;
-        bool done = false;
-        for (int cb = 0; cb < total && !done; cb += 64) {
-          const int i = cb + lane;
-          const bool v2 = i < total;
-          const uint32_t xy2 = v2 ? alist[i] : 0u;
-          const int x2 = (int)(xy2 >> 16), y2 = (int)(xy2 & 0xFFFFu);
-          bool al = v2;
-          for (int q = nk0; q < nkept; ++q) {              // intervals kept earlier in this round
-            const uint32_t kk = kept[q];
-            if (al && nms_suppressed(x2, y2, (int)(kk >> 16), (int)(kk & 0xFFFFu), phi)) al = false;
-          }
-          uint64_t m = __ballot(al);
-          while (m) {
-            const int b2 = __ffsll((unsigned long long)m) - 1;
-            const int bx = __shfl(x2, b2, 64), by = __shfl(y2, b2, 64);
-            if (lane == 0) kept[nkept] = ((uint32_t)bx << 16) | (uint32_t)by;
-            ++nkept;
-            if (max_keep > 0 && nkept >= max_keep) { done = true; break; }
-            if (al && lane > b2 && nms_suppressed(x2, y2, bx, by, phi)) al = false;
-            const uint64_t upto = (b2 == 63) ? ~0ull : ((2ull << b2) - 1ull);
-            m = __ballot(al) & ~upto;
-          }
-        }
-        if (lane == 0) { s_nkept = nkept; s_done = done ? 1 : 0; }
-      }
-      __syncthreads();
+      const int x = (int)(e2[r] >> 16), y = (int)(e2[r] & 0xFFFFu);
+      // suppressed iff inter > phi * union on inclusive token counts, compared in fp32 with one
+      // multiply (the host-side definition does the same); branch-free: one select per candidate
+      const int inter = min(y, ky) - max(x, kx) + 1;
+      const int uni = (y - x + 1) + (ky - kx + 1) - inter;
+      const bool kill = (e2[r] == w2) | ((inter > 0) & ((float)inter > __fmul_rn(phi, (float)uni)));
+      e1[r] = kill ? ~0ull : e1[r];
     }
   }
-  __syncthreads();
   // cuts: 0, L and both ends of every kept interval
-  uint8_t* flags = reinterpret_cast<uint8_t*>(k2);
-  int* cutlist = reinterpret_cast<int*>(reinterpret_cast<uint8_t*>(k2) + 2304);
-  const int nkept = s_nkept;
-  // k1 (kept list) and k2 (flags) are distinct arrays, so reading kept while writing flags is safe
   for (int i = tid; i <= L; i += blockDim.x) flags[i] = (i == 0 || i == L) ? 1 : 0;
   __syncthreads();
   for (int q = tid; q < nkept; q += blockDim.x) {
@@ -613,7 +529,6 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
   }
   __syncthreads();
   // enumerate the set flags in increasing order: each wave scans a contiguous segment
-  const int lane = tid & 63, wave = tid >> 6;
   const int seg = (L + 1 + 15) / 16, s0 = wave * seg, s1 = min(L + 1, s0 + seg);
   int cnt = 0;
   for (int i0 = s0; i0 < s1; i0 += 64) {
@@ -771,6 +686,8 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
   seg_carries_kernel<<<P, 1024, 0, s>>>(a);
   if (bf) seg_tile_scan_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
   else    seg_tile_scan_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
+  dim3 gm((2 * n_new - 1 + 255) / 256, P);
+  seg_merge_kernel<<<gm, 256, 0, s>>>(a);
   seg_select_kernel<<<P, 1024, 0, s>>>(a);
   return hipGetLastError();
 }
