@@ -54,6 +54,7 @@ struct ScratchLayout {
   size_t qrep;     // dtype  [n_seqs * Hkv][Lp][d]
   size_t qpart;    // double [P][Lp / 128 + Lp][d]  sums of 128-token pieces of query spans
   size_t bounds;   // int32  [Hkv][chunk_max + 1] + int32 [Hkv]  (append_with_spans)
+  size_t selflag;  // uint8  [n_seqs * Hkv][max_spans]  1 = span selected (between the two selection kernels)
   size_t total;
   int    max_problems;  // P the buffer was sized for
 };
@@ -82,7 +83,7 @@ struct DevState {
 };
 struct DevScratch {
   double* rowsum; double* csuf; double* tsum; double* rcar; double* ccar;
-  double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds;
+  double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds; uint8_t* selflag;
 };
 
 // ---- launchers (each returns the hipError_t of the launch) ----

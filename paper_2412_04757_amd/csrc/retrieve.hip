@@ -235,64 +235,85 @@ __device__ __forceinline__ uint64_t score_key(double s) {
   return ~up;
 }
 
-__global__ __launch_bounds__(1024) void select_kernel(RetArgs a) {
-  __shared__ uint64_t t_key[1024];
-  __shared__ int t_clip[1024];
+// Budgeted top-k (Eq. 9 at span granularity): a span is selected iff it is eligible (its clipped
+// part is non-empty) and, in the order (score descending, id ascending) over the eligible spans,
+// its rank is below k_max and the clipped tokens up to and including it fit the budget. Clipped
+// lengths are positive, so this is exactly the longest prefix of that order that fits.
+// Rank and cumulated tokens come from all pairs: 32 spans per workgroup, eight threads per span,
+// each over an eighth of the other spans (staged through LDS 256 at a time). A span j comes
+// before span i iff key_j < key_i, or the keys are equal and j < i.
+constexpr int SEL_SPANS_PER_BLOCK = 32;
+__global__ __launch_bounds__(256) void select_rank_kernel(RetArgs a) {
+  __shared__ uint64_t t_key[256];
+  __shared__ int t_clip[256];
+  const Dims& D = a.D;
+  const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int n = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
+  if (blockIdx.x * SEL_SPANS_PER_BLOCK >= n) return;                   // uniform
+  const double* scores = a.st.scores + (size_t)slot * D.max_spans;
+  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
+  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
+  const int tid = threadIdx.x, jp = tid & 7;
+  const int i = blockIdx.x * SEL_SPANS_PER_BLOCK + (tid >> 3);
+  uint64_t ki = 0;
+  int ci = 0;
+  if (i < n) {
+    int lo, hi;
+    clip_span(D, c0, sstart[i], slen[i], lo, hi);
+    ci = max(hi - lo, 0);
+    ki = score_key(scores[i]);
+  }
+  int rank = 0, cum = 0;
+  for (int j0 = 0; j0 < n; j0 += 256) {
+    __syncthreads();
+    const int j = j0 + tid;
+    if (j < n) {
+      int lo, hi;
+      clip_span(D, c0, sstart[j], slen[j], lo, hi);
+      t_clip[tid] = max(hi - lo, 0);
+      t_key[tid] = score_key(scores[j]);
+    }
+    __syncthreads();
+    const int m = min(256, n - j0);
+    for (int jj = jp; jj < m; jj += 8) {
+      const int cj = t_clip[jj];
+      const uint64_t kj = t_key[jj];
+      const bool before = (kj < ki) | ((kj == ki) & (j0 + jj < i));
+      rank += (before & (cj > 0)) ? 1 : 0;
+      cum += before ? cj : 0;
+    }
+  }
+#pragma unroll
+  for (int o = 1; o < 8; o <<= 1) {
+    rank += __shfl_xor(rank, o, 64);
+    cum += __shfl_xor(cum, o, 64);
+  }
+  cum += ci;
+  if (jp == 0 && i < n) {
+    const bool sel = ci > 0 && (D.k_max == 0 || rank < D.k_max) && (D.budget == 0 || (long long)cum <= D.budget);
+    a.sc.selflag[(size_t)p * D.max_spans + i] = sel ? 1 : 0;
+  }
+}
+
+// Selected ids in ascending order, their count, and the context token list (one workgroup per
+// KV head).
+__global__ __launch_bounds__(1024) void select_emit_kernel(RetArgs a) {
   __shared__ uint32_t selmask[SEL_MAX_SPANS / 32];
   const Dims& D = a.D;
   const int p = blockIdx.x, bi = p / D.Hkv, h = p - bi * D.Hkv;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
-  const int n = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
-  const double* scores = a.st.scores + (size_t)slot * D.max_spans;
-  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
-  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
-  const int tid = threadIdx.x;
-  for (int w = tid; w < (n + 31) / 32; w += blockDim.x) selmask[w] = 0u;
-  __syncthreads();
+  const int n = meta[META_N_SPANS];
+  const uint8_t* flag = a.sc.selflag + (size_t)p * D.max_spans;
   for (int i0 = 0; i0 < n; i0 += blockDim.x) {
-    const int i = i0 + tid;
-    uint64_t ki = 0;
-    int ci = 0;
-    if (i < n) {
-      int lo, hi;
-      clip_span(D, c0, sstart[i], slen[i], lo, hi);
-      ci = max(hi - lo, 0);
-      ki = score_key(scores[i]);
+    const int i = i0 + threadIdx.x;
+    const uint64_t m = __ballot(i < n && flag[i]);
+    if ((threadIdx.x & 63) == 0 && i < ((n + 63) & ~63)) {
+      selmask[i >> 5] = (uint32_t)m;
+      selmask[(i >> 5) + 1] = (uint32_t)(m >> 32);
     }
-    // rank and cumulated tokens of span i in the order (-score, id) among eligible spans: span j
-    // comes before span i iff key_j < key_i, or the keys are equal and j < i
-    int rank = 0, cum = ci;
-    for (int j0 = 0; j0 < n; j0 += 1024) {
-      __syncthreads();
-      const int j = j0 + tid;
-      if (j < n) {
-        int lo, hi;
-        clip_span(D, c0, sstart[j], slen[j], lo, hi);
-        t_clip[tid] = max(hi - lo, 0);
-        t_key[tid] = score_key(scores[j]);
-      }
-      __syncthreads();
-      const int m = min(1024, n - j0);
-      if (ci > 0) {
-        // entries below i (j < i) win ties, entries above lose them
-        const int split = min(max(i - j0, 0), m);
-        for (int jj = 0; jj < split; ++jj) {
-          const int cj = t_clip[jj];
-          const bool before = t_key[jj] <= ki;
-          rank += (before && cj > 0) ? 1 : 0;
-          cum += before ? cj : 0;
-        }
-        for (int jj = split; jj < m; ++jj) {
-          const int cj = t_clip[jj];
-          const bool before = t_key[jj] < ki && (j0 + jj) != i;
-          rank += (before && cj > 0) ? 1 : 0;
-          cum += before ? cj : 0;
-        }
-      }
-    }
-    const bool sel = ci > 0 && (D.k_max == 0 || rank < D.k_max) && (D.budget == 0 || (long long)cum <= D.budget);
-    if (sel) atomicOr(&selmask[i >> 5], 1u << (i & 31));
   }
   __syncthreads();
   int32_t* ids_out = a.sel_ids_out ? a.sel_ids_out + (size_t)p * D.sel_cap : nullptr;
@@ -358,7 +379,10 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
   dim3 gs(gx, P);
   if (bf) score_kernel<LTRI_BF16><<<gs, 256, 0, s>>>(a);
   else    score_kernel<LTRI_F32><<<gs, 256, 0, s>>>(a);
-  select_kernel<<<P, 1024, 0, s>>>(a);
+  int gr = (span_bound + SEL_SPANS_PER_BLOCK - 1) / SEL_SPANS_PER_BLOCK;
+  if (gr < 1) gr = 1;
+  select_rank_kernel<<<dim3(gr, P), 256, 0, s>>>(a);
+  select_emit_kernel<<<P, 1024, 0, s>>>(a);
   return hipGetLastError();
 }
 

@@ -227,15 +227,19 @@ __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
 }
 
 // ---- pass 2: carries ----
-__global__ __launch_bounds__(1024) void seg_carries_kernel(SegArgs a) {
+// One thread per row (row carries) or column (column carries); SEG_CARRY_PARTS workgroups per
+// problem share the rows and columns, each rebuilds the small table of tile-total sums it needs.
+constexpr int SEG_CARRY_PARTS = 8;
+__global__ __launch_bounds__(256) void seg_carries_kernel(SegArgs a) {
   __shared__ double TS[SEG_MAX_NB * SEG_MAX_NB];   // TS[I][J] = sum_{J < J' <= I} tsum[I][J']
-  const int p = blockIdx.x, nb = a.nb, Lp = a.Lp;
+  const int p = blockIdx.y, nb = a.nb, Lp = a.Lp;
   const double* rowsum = a.sc.rowsum + (size_t)p * nb * Lp;
   const double* csuf = a.sc.csuf + (size_t)p * nb * Lp;
   const double* tsum = a.sc.tsum + (size_t)p * nb * nb;
   double* rcar = a.sc.rcar + (size_t)p * nb * Lp;
   double* ccar = a.sc.ccar + (size_t)p * nb * Lp;
-  for (int i = threadIdx.x; i < Lp; i += blockDim.x) {
+  const int first = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
+  for (int i = first; i < Lp; i += stride) {
     const int I = i / 64;
     double v[SEG_MAX_NB];
 #pragma unroll
@@ -254,7 +258,7 @@ __global__ __launch_bounds__(1024) void seg_carries_kernel(SegArgs a) {
     }
   }
   __syncthreads();
-  for (int x = threadIdx.x; x < Lp; x += blockDim.x) {
+  for (int x = first; x < Lp; x += stride) {
     const int J = x / 64;
     double v[SEG_MAX_NB];
 #pragma unroll
@@ -683,7 +687,7 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
   dim3 gt(a.ntiles, P);
   if (bf) seg_tile_sums_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
   else    seg_tile_sums_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
-  seg_carries_kernel<<<P, 1024, 0, s>>>(a);
+  seg_carries_kernel<<<dim3(SEG_CARRY_PARTS, P), 256, 0, s>>>(a);
   if (bf) seg_tile_scan_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
   else    seg_tile_scan_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
   dim3 gm((2 * n_new - 1 + 255) / 256, P);
