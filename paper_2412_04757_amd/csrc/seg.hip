@@ -289,22 +289,28 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   __syncthreads();
   {                                     // rows: suffix sums towards the left, four threads per row
     const int r = tid >> 2, qd = tid & 3;
+    double v[16];                       // the thread's cells stay in registers between the two steps
+#pragma unroll
+    for (int c = 0; c < 16; ++c) v[c] = Ms[r * 65 + qd * 16 + c];
     double s = 0.0;
 #pragma unroll
-    for (int c = 0; c < 16; ++c) s += Ms[r * 65 + qd * 16 + c];
+    for (int c = 0; c < 16; ++c) s += v[c];
     qsum[r][qd] = s;
     __syncthreads();
     double run = 0.0;
     for (int q2 = 3; q2 > qd; --q2) run += qsum[r][q2];
 #pragma unroll
-    for (int c = 15; c >= 0; --c) { run += Ms[r * 65 + qd * 16 + c]; Ms[r * 65 + qd * 16 + c] = run; }
+    for (int c = 15; c >= 0; --c) { run += v[c]; Ms[r * 65 + qd * 16 + c] = run; }
   }
   __syncthreads();
   {                                     // columns: prefix sums downwards, four threads per column
     const int c = tid & 63, qd = tid >> 6;
+    double w[16];                       // cell + row carry, kept in registers between the two steps
+#pragma unroll
+    for (int r = 0; r < 16; ++r) w[r] = Ms[(qd * 16 + r) * 65 + c] + rc[qd * 16 + r];
     double s = 0.0;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s += Ms[(qd * 16 + r) * 65 + c] + rc[qd * 16 + r];
+    for (int r = 0; r < 16; ++r) s += w[r];
     qsum[c][qd] = s;
     __syncthreads();
     const int x = J * 64 + c;
@@ -315,7 +321,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int rl = qd * 16 + r, y = I * 64 + rl;
-      run += Ms[rl * 65 + c] + rc[rl];
+      run += w[r];
       const long long n = (long long)y - x + 1;
       const double sv = run - th * (double)(n * (n + 1) / 2);       // Eq. 5
       Ms[rl * 65 + c] = (x <= y && y < L) ? sv : -INFINITY;
