@@ -23,8 +23,8 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 matrix rate
 PEAK_HBM_GBPS = 8000.0
 # HBM bytes per attend launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters
-# calibrated against copy kernels (profiles/attend_gather_hbm_traffic_cfg3.txt): (35428.9 * 2.00 + 16384.0) KiB
-ATTEND_TRAFFIC_BYTES_CFG3 = int((35428.9 * 2.00 + 16384.0) * 1024)
+# calibrated against copy kernels (profiles/attend_gather_hbm_traffic_cfg3.txt): (35419.5 * 2.00 + 16384.0) KiB
+ATTEND_TRAFFIC_BYTES_CFG3 = int((35419.5 * 2.00 + 16384.0) * 1024)
 
 
 def log(*a):
