@@ -10,6 +10,7 @@ import torch
 
 from oracle import ltri_oracle as O
 from workloads import CONFIGS, planted_stream, theta_default, Workload
+from paper_2412_04757_amd import LtriContext, config_from_workload
 from tests.gpu_util import make_pair, spans_equal, rep_keys_diff
 
 pytestmark = pytest.mark.gpu
@@ -179,3 +180,40 @@ def test_span_table_overflow_is_reported(gpu_device):
         ctx.append_chunk(0, 0, 1, 256)
     assert ctx.sync_status() == -3
     assert ctx.span_count(0, 0, 0) <= 6
+
+
+def test_gpu_matches_stored_oracle_fixture(gpu_device):
+    """The HIP path against values the oracle stored earlier (tests/golden): boundaries and
+    selections exactly, sampled attention rows and LSE within the fp32 tolerance."""
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "oracle_stream_cfg1.json")) as f:
+        g = json.load(f)
+    w = CONFIGS[g["config"]]
+    T, L = g["tokens"], g["chunk"]
+    K, V, Q, _ = planted_stream(w, g["seed"], device="cpu", context=T)     # the fixture's inputs: CPU generator
+    K, V, Q = K.to(gpu_device), V.to(gpu_device), Q.to(gpu_device)
+    cfg = config_from_workload(w, max_tokens=T, theta=theta_default(w.head_dim), n_layers=1, n_seqs=1)
+    ctx = LtriContext(cfg, gpu_device)
+    ka, va = ctx.arena_views()
+    ka[0, 0, :, :T].copy_(K)
+    va[0, 0, :, :T].copy_(V)
+    for ch in g["chunks"]:
+        c0 = ch["chunk_start"]
+        q = Q[c0:c0 + L].contiguous()
+        ctx.append_chunk(0, 0, 1, L)
+        ctx.retrieve(0, 0, 1, q)
+        lse = torch.empty((1, L, w.n_q_heads), dtype=torch.float32, device=gpu_device)
+        out = ctx.attend(0, 0, 1, q, lse=lse)
+        for h in range(w.n_kv_heads):
+            s, l = ctx.get_spans(0, 0, h)
+            got = [int(a) - c0 for a in s if a >= c0] + [L]
+            assert got == ch["bounds"][h], f"chunk at {c0}: {got} != {ch['bounds'][h]}"
+            ids, _ = ctx.get_selection(0, 0, h)
+            assert list(ids) == ch["selected"][h]
+            assert len(ctx.get_token_list(0, 0, h)) == ch["context_tokens"][h]
+        rows = ch["out_rows"]
+        got = out[0, rows, 0, :8].double().cpu().numpy()
+        np.testing.assert_allclose(got, np.asarray(ch["out_head0_first8"]), rtol=0, atol=TOL[w.dtype])
+        np.testing.assert_allclose(lse[0, rows, 0].double().cpu().numpy(), np.asarray(ch["lse_head0"]), rtol=0, atol=2e-3)
+    assert ctx.sync_status() == 0

@@ -396,3 +396,49 @@ def test_stability_audit_flags_a_planted_near_tie():
     assert O.segmentation_is_stable(K * 3.0, None, O.MAP_LOGIT, 0.1, 0.0)
     theta = float((K @ K.T / math.sqrt(2))[0, 0])          # S == 0 exactly everywhere: unstable under noise
     assert not O.segmentation_is_stable(K, None, O.MAP_LOGIT, theta * (1 - 1e-9), 0.0)
+
+
+# ---------------------------------------------------------------- stored fixtures (tests/golden)
+def _golden(name):
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)) as f:
+        return json.load(f)
+
+
+def test_hand_worked_example_of_the_segmentation():
+    """A 4-token map whose scores, candidates, NMS survivors and cuts were worked by hand from
+    Eq. 4 / Eq. 5, the anti-diagonal filter and the greedy NMS (derivation in the fixture)."""
+    g = _golden("ta_hand_example.json")
+    M = np.asarray(g["map"], np.float64)
+    S = O.ta_scores(M, g["theta"], g["n_heads"])
+    for x in range(4):
+        for y in range(4):
+            if g["S"][x][y] is None:
+                assert S[x, y] == -np.inf
+            else:
+                assert S[x, y] == g["S"][x][y]
+    cands = O.antidiagonal_candidates(S)
+    assert [(s, x, y) for s, x, y in cands] == [tuple(c) for c in g["candidates"]]
+    for phi in ("0", "0.5"):
+        kept = O.nms_1d(cands, float(phi))
+        assert [(x, y) for _, x, y in kept] == [tuple(k) for k in g[f"kept_phi_{phi}"]]
+        assert list(O.partition_from_kept(kept, 4)) == g[f"cuts_phi_{phi}"]
+
+
+def test_oracle_reproduces_its_stored_stream():
+    """The oracle's arithmetic has not drifted: boundaries, selections and sampled attention rows of
+    a small seeded stream equal the values its committed script stored."""
+    import importlib.util
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "make_oracle_stream_fixture.py")
+    spec = importlib.util.spec_from_file_location("make_oracle_stream_fixture", path)
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    now, stored = mod.build(), _golden("oracle_stream_cfg1.json")
+    assert len(now["chunks"]) == len(stored["chunks"])
+    for a, b in zip(now["chunks"], stored["chunks"]):
+        assert a["bounds"] == b["bounds"] and a["selected"] == b["selected"]
+        assert a["context_tokens"] == b["context_tokens"]
+        np.testing.assert_allclose(a["out_head0_first8"], b["out_head0_first8"], rtol=0, atol=1e-10)
+        np.testing.assert_allclose(a["lse_head0"], b["lse_head0"], rtol=0, atol=1e-10)
