@@ -225,6 +225,21 @@ def main():
               "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g_bytes / g_us / 1e3 / PEAK_HBM_GBPS, 4),
               "launch_us": round(g_us, 2), "bytes": g_bytes}
 
+    # measured ceilings of this GPU next to the published ones: back-to-back bf16 matrix-core
+    # products, and a plain 1 GiB device copy
+    from paper_2412_04757_amd import measure_mfma_peak, measure_copy_peak
+    mfma_meas = measure_mfma_peak(dev)
+    mfma_meas_rnd = measure_mfma_peak(dev, random_operands=True)
+    copy_meas = measure_copy_peak(dev)
+    roofline["measured_peak"] = round(mfma_meas, 1)
+    roofline["frac_of_measured"] = round(achieved / mfma_meas, 4)
+    roofline["measured_peak_random_operands"] = round(mfma_meas_rnd, 1)
+    roofline["frac_of_measured_random_operands"] = round(achieved / mfma_meas_rnd, 4)
+    gather["measured_peak"] = round(copy_meas, 1)
+    gather["frac_of_measured"] = round(g_bytes / g_us / 1e3 / copy_meas, 4)
+    log(f"[bench] measured ceilings: {mfma_meas:.0f} TFLOP/s bf16 matrix products ({mfma_meas_rnd:.0f} with random operands), "
+        f"{copy_meas:.0f} GB/s copy")
+
     # share of the step spent outside attend (append + retrieve + launch gaps)
     other_ms = ms_per_step - tot_ms / args.steps
     log(f"[bench] {ms_per_step:.2f} ms per stream; attend {tot_ms / args.steps:.2f} ms, rest {other_ms:.2f} ms")

@@ -186,6 +186,20 @@ int32_t ltri_get_selection(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv
 int32_t ltri_get_token_list(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,
                             int32_t* tokens_host, int32_t cap, int32_t* n);
 
+/* Measured ceilings of this GPU, to be read next to the published peaks (the attend step is a
+ * dense bf16 contraction, Sec. 3.4 third step; the gather is a pure copy). Both launch a small
+ * kernel on hip_stream, time it with events and synchronise; no context is needed.
+ * ltri_measure_mfma_peak: rate of back-to-back v_mfma_f32_32x32x16_bf16 on every SIMD, in
+ *   TFLOP/s. sink: device buffer of at least 512 KiB that the kernel may overwrite.
+ *   random_operands: 0 = all operands 1.0, 1 = pseudo-random operands; the clock the chip
+ *   sustains depends on the operand data, real inputs behave like the random case.
+ * ltri_measure_copy_peak: read + write rate of a plain 16-byte-per-lane copy of `bytes` bytes
+ *   (a multiple of 16, at least 1 MiB) from src to dst (device, disjoint), in GB/s.
+ * Errors: LTRI_EINVAL (NULL pointers, sizes), LTRI_EHIP. */
+int32_t ltri_measure_mfma_peak(void* sink, size_t sink_bytes, int32_t random_operands, void* hip_stream,
+                               double* tflops);
+int32_t ltri_measure_copy_peak(void* dst, const void* src, size_t bytes, void* hip_stream, double* gbps);
+
 const char* ltri_strerror(int32_t status);
 const char* ltri_last_error(const ltri_ctx* ctx);
 /* "libltri <version> gfx950" */

@@ -1,6 +1,6 @@
 """Python binding of libltri (argument marshalling only; every step runs in the HIP kernels)."""
 from .binding import (LtriConfig, LtriContext, LtriError, config_from_workload, load_library,
-                      library_path, EXPORTED_SYMBOLS)
+                      library_path, EXPORTED_SYMBOLS, measure_mfma_peak, measure_copy_peak)
 
 __all__ = ["LtriConfig", "LtriContext", "LtriError", "config_from_workload", "load_library",
-           "library_path", "EXPORTED_SYMBOLS"]
+           "library_path", "EXPORTED_SYMBOLS", "measure_mfma_peak", "measure_copy_peak"]

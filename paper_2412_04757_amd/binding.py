@@ -26,7 +26,7 @@ EXPORTED_SYMBOLS = [
     "ltri_force_selection", "ltri_attend", "ltri_gather_pack", "ltri_list_capacity",
     "ltri_sync_status", "ltri_token_count", "ltri_span_count", "ltri_get_spans",
     "ltri_get_rep_keys", "ltri_get_selection", "ltri_get_token_list", "ltri_strerror",
-    "ltri_last_error", "ltri_version",
+    "ltri_last_error", "ltri_version", "ltri_measure_mfma_peak", "ltri_measure_copy_peak",
 ]
 
 
@@ -85,6 +85,8 @@ def load_library() -> C.CDLL:
         "ltri_get_rep_keys": [vp, i32, i32, i32, vp, i32],
         "ltri_get_selection": [vp, i32, i32, i32, pi32, i32, pi32, C.POINTER(C.c_double)],
         "ltri_get_token_list": [vp, i32, i32, i32, pi32, i32, pi32],
+        "ltri_measure_mfma_peak": [vp, C.c_size_t, i32, vp, C.POINTER(C.c_double)],
+        "ltri_measure_copy_peak": [vp, vp, C.c_size_t, vp, C.POINTER(C.c_double)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -275,3 +277,30 @@ class LtriContext:
                                                  toks.ctypes.data_as(C.POINTER(C.c_int32)), self.list_cap,
                                                  C.byref(n)), None)
         return toks[:n.value]
+
+
+def measure_mfma_peak(device, random_operands: bool = False) -> float:
+    """TFLOP/s of back-to-back bf16 matrix-core products on `device` (ltri_measure_mfma_peak)."""
+    lib = load_library()
+    sink = torch.empty(1 << 17, dtype=torch.float32, device=device)
+    out = C.c_double()
+    st = lib.ltri_measure_mfma_peak(sink.data_ptr(), sink.numel() * 4, int(random_operands),
+                                    torch.cuda.current_stream(device).cuda_stream,
+                                    C.byref(out))
+    if st != 0:
+        raise LtriError(st, lib.ltri_strerror(st).decode())
+    return out.value
+
+
+def measure_copy_peak(device, n_bytes: int = 1 << 30) -> float:
+    """GB/s (read + write) of a plain device copy of n_bytes on `device` (ltri_measure_copy_peak)."""
+    lib = load_library()
+    src = torch.empty(n_bytes, dtype=torch.uint8, device=device)
+    dst = torch.empty_like(src)
+    src.zero_()
+    out = C.c_double()
+    st = lib.ltri_measure_copy_peak(dst.data_ptr(), src.data_ptr(), n_bytes, torch.cuda.current_stream(device).cuda_stream,
+                                    C.byref(out))
+    if st != 0:
+        raise LtriError(st, lib.ltri_strerror(st).decode())
+    return out.value

@@ -1,0 +1,98 @@
+// Two measured ceilings to price the hot kernels against, next to the published ones: the rate
+// of back-to-back bf16 matrix-core products (what the attend kernel is bounded by) and the rate
+// of a plain streaming copy (what the gather is bounded by). Each launch is timed with events on
+// the stream it runs on.
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include "../../include/ltri.h"
+
+namespace {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+// 32 products per iteration on four independent accumulators, two wavefronts per SIMD. The
+// clock the chip sustains depends on how many operand bits toggle, so the operands are either
+// all ones or four different pseudo-random fragments per side (values in [1, 2), both signs).
+__global__ __launch_bounds__(512) void mfma_peak_kernel(float* sink, int iters, int random_operands) {
+  f32x16_t acc[4];
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[c][i] = 0.f;
+  uint4 ra[4], rb[4];
+  uint32_t h = 0x9e3779b9u * (threadIdx.x + 1u);
+  auto next = [&]() {                                 // two bf16 values: sign and mantissa random, exponent of 1.0
+    h ^= h << 13; h ^= h >> 17; h ^= h << 5;
+    return random_operands ? ((h & 0x807f807fu) | 0x3f803f80u) : 0x3f803f80u;
+  };
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    ra[i] = make_uint4(next(), next(), next(), next());
+    rb[i] = make_uint4(next(), next(), next(), next());
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int r = 0; r < 32; ++r)
+      acc[r & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, ra[r & 3]), __builtin_bit_cast(bf16x8_t, rb[(r >> 2) & 3]),
+                                                           acc[r & 3], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[c][i];
+  sink[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+__global__ __launch_bounds__(256) void copy_peak_kernel(uint4* dst, const uint4* src, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+template <typename F>
+int32_t timed(hipStream_t s, int reps, F launch, double* ms_per_launch) {
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess) return LTRI_EHIP;
+  if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return LTRI_EHIP; }
+  launch();                                           // warm-up
+  int32_t r = LTRI_OK;
+  if (hipEventRecord(e0, s) != hipSuccess) r = LTRI_EHIP;
+  for (int i = 0; i < reps && r == LTRI_OK; ++i) launch();
+  if (r == LTRI_OK && (hipGetLastError() != hipSuccess || hipEventRecord(e1, s) != hipSuccess ||
+                       hipEventSynchronize(e1) != hipSuccess)) r = LTRI_EHIP;
+  float ms = 0.f;
+  if (r == LTRI_OK && hipEventElapsedTime(&ms, e0, e1) != hipSuccess) r = LTRI_EHIP;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  *ms_per_launch = (double)ms / reps;
+  return r;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t ltri_measure_mfma_peak(void* sink, size_t sink_bytes, int32_t random_operands, void* hip_stream, double* tflops) {
+  constexpr int BLOCKS = 256, THREADS = 512, ITERS = 8000, REPS = 5;
+  if (!sink || !tflops || sink_bytes < (size_t)BLOCKS * THREADS * sizeof(float)) return LTRI_EINVAL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  double ms = 0.0;
+  const int32_t r = timed(s, REPS, [&] { mfma_peak_kernel<<<BLOCKS, THREADS, 0, s>>>((float*)sink, ITERS, random_operands); }, &ms);
+  if (r != LTRI_OK) return r;
+  const double flop = (double)BLOCKS * (THREADS / 64) * ITERS * 32.0 * (2.0 * 32 * 32 * 16);
+  *tflops = flop / (ms * 1e-3) / 1e12;
+  return LTRI_OK;
+}
+
+int32_t ltri_measure_copy_peak(void* dst, const void* src, size_t bytes, void* hip_stream, double* gbps) {
+  if (!dst || !src || !gbps || bytes < (1u << 20) || (bytes & 15)) return LTRI_EINVAL;
+  hipStream_t s = (hipStream_t)hip_stream;
+  double ms = 0.0;
+  const int32_t r = timed(s, 10, [&] { copy_peak_kernel<<<256 * 16, 256, 0, s>>>((uint4*)dst, (const uint4*)src, bytes / 16); }, &ms);
+  if (r != LTRI_OK) return r;
+  *gbps = 2.0 * (double)bytes / (ms * 1e-3) / 1e9;       // read + write
+  return LTRI_OK;
+}
+
+}  // extern "C"
