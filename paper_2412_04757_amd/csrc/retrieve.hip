@@ -108,31 +108,68 @@ __global__ __launch_bounds__(128) void qrep_final_kernel(RetArgs a) {
 }
 
 // ---- score_i = max_j Qrep_j . Krep_i for every stored span ----
+// Four lanes per stored span, each over a quarter of the 16-byte pieces of its representative key;
+// the query representatives are staged in LDS as doubles, sixteen at a time. Products of the stored values are exact in
+// fp64 and 128 of them are summed, so the order of the sum does not matter at the 1e-12 level
+// the selection is compared at.
+constexpr int SCORE_QBATCH = 16;
 template <int DT>
 __global__ __launch_bounds__(256) void score_kernel(RetArgs a) {
   typedef typename Elt<DT>::type T;
+  constexpr int N = 16 / (int)sizeof(T);                // elements per 16-byte piece
+  extern __shared__ double qs[];                      // [SCORE_QBATCH][d]
   const Dims& D = a.D;
   const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int n = meta[META_N_SPANS], nqs = meta[META_CHUNK_NSP];
-  const int d = D.d, per = d / 64;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if ((int)(blockIdx.x * (blockDim.x / 4)) >= n) return;    // uniform
+  const int d = D.d;
   const T* qrep = reinterpret_cast<const T*>(a.sc.qrep) + (size_t)p * a.Lp * d;
   const T* krep = reinterpret_cast<const T*>(a.st.krep) + (size_t)slot * D.max_spans * d;
   double* scores = a.st.scores + (size_t)slot * D.max_spans;
-  for (int i = blockIdx.x * 4 + wave; i < n; i += gridDim.x * 4) {
-    const double k0 = Elt<DT>::to_f64(krep[(size_t)i * d + lane * per]);
-    const double k1 = per == 2 ? Elt<DT>::to_f64(krep[(size_t)i * d + lane * per + 1]) : 0.0;
-    double best = -INFINITY;
-    for (int j = 0; j < nqs; ++j) {
-      double v = Elt<DT>::to_f64(qrep[(size_t)j * d + lane * per]) * k0;
-      if (per == 2) v += Elt<DT>::to_f64(qrep[(size_t)j * d + lane * per + 1]) * k1;
-      v = wave_sum_f64(v);
-      best = fmax(best, v);
+  const int i = blockIdx.x * (blockDim.x / 4) + (threadIdx.x >> 2), part = threadIdx.x & 3;
+  const uint4* krow = reinterpret_cast<const uint4*>(krep + (size_t)min(i, n - 1) * d);
+  double best = -INFINITY;
+  for (int j0 = 0; j0 < nqs; j0 += SCORE_QBATCH) {
+    const int nj = min(SCORE_QBATCH, nqs - j0);
+    __syncthreads();
+    for (int q = threadIdx.x; q < nj * d; q += blockDim.x) qs[q] = Elt<DT>::to_f64(qrep[(size_t)j0 * d + q]);
+    __syncthreads();
+    double acc[SCORE_QBATCH];
+#pragma unroll
+    for (int jj = 0; jj < SCORE_QBATCH; ++jj) acc[jj] = 0.0;
+    for (int pc = part; pc < d / N; pc += 4) {
+      const uint4 kv = krow[pc];
+      double k[8];
+      if constexpr (DT == LTRI_BF16) {
+        const uint32_t w[4] = {kv.x, kv.y, kv.z, kv.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          k[2 * u] = (double)__uint_as_float(w[u] << 16);
+          k[2 * u + 1] = (double)__uint_as_float(w[u] & 0xffff0000u);
+        }
+      } else {
+        k[0] = (double)__uint_as_float(kv.x); k[1] = (double)__uint_as_float(kv.y);
+        k[2] = (double)__uint_as_float(kv.z); k[3] = (double)__uint_as_float(kv.w);
+      }
+#pragma unroll
+      for (int jj = 0; jj < SCORE_QBATCH; ++jj) {
+        if (jj < nj) {
+#pragma unroll
+          for (int u = 0; u < N; ++u) acc[jj] = fma(k[u], qs[jj * d + pc * N + u], acc[jj]);
+        }
+      }
     }
-    if (lane == 0) scores[i] = best;
+#pragma unroll
+    for (int jj = 0; jj < SCORE_QBATCH; ++jj) {
+      double v = acc[jj];
+      v += __shfl_xor(v, 1, 64);
+      v += __shfl_xor(v, 2, 64);
+      if (jj < nj) best = fmax(best, v);
+    }
   }
+  if (i < n && part == 0) scores[i] = best;
 }
 
 // Evicted part [a, b) of a stored span for a chunk starting at c0.
@@ -240,12 +277,14 @@ __device__ __forceinline__ uint64_t score_key(double s) {
 // its rank is below k_max and the clipped tokens up to and including it fit the budget. Clipped
 // lengths are positive, so this is exactly the longest prefix of that order that fits.
 // Rank and cumulated tokens come from all pairs: 32 spans per workgroup, eight threads per span,
-// each over an eighth of the other spans (staged through LDS 256 at a time). A span j comes
+// each over an eighth of the other spans (staged through LDS 1024 at a time). A span j comes
 // before span i iff key_j < key_i, or the keys are equal and j < i.
 constexpr int SEL_SPANS_PER_BLOCK = 32;
+constexpr int SEL_PARTS = 256 / SEL_SPANS_PER_BLOCK;      // threads per span
+constexpr int SEL_STAGE = 1024;                           // spans staged in LDS at a time
 __global__ __launch_bounds__(256) void select_rank_kernel(RetArgs a) {
-  __shared__ uint64_t t_key[256];
-  __shared__ int t_clip[256];
+  __shared__ uint64_t t_key[SEL_STAGE];
+  __shared__ int t_clip[SEL_STAGE];
   const Dims& D = a.D;
   const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
@@ -255,8 +294,8 @@ __global__ __launch_bounds__(256) void select_rank_kernel(RetArgs a) {
   const double* scores = a.st.scores + (size_t)slot * D.max_spans;
   const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
   const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
-  const int tid = threadIdx.x, jp = tid & 7;
-  const int i = blockIdx.x * SEL_SPANS_PER_BLOCK + (tid >> 3);
+  const int tid = threadIdx.x, jp = tid % SEL_PARTS;
+  const int i = blockIdx.x * SEL_SPANS_PER_BLOCK + tid / SEL_PARTS;
   uint64_t ki = 0;
   int ci = 0;
   if (i < n) {
@@ -266,18 +305,17 @@ __global__ __launch_bounds__(256) void select_rank_kernel(RetArgs a) {
     ki = score_key(scores[i]);
   }
   int rank = 0, cum = 0;
-  for (int j0 = 0; j0 < n; j0 += 256) {
+  for (int j0 = 0; j0 < n; j0 += SEL_STAGE) {
     __syncthreads();
-    const int j = j0 + tid;
-    if (j < n) {
+    for (int q = tid; q < SEL_STAGE && j0 + q < n; q += blockDim.x) {
       int lo, hi;
-      clip_span(D, c0, sstart[j], slen[j], lo, hi);
-      t_clip[tid] = max(hi - lo, 0);
-      t_key[tid] = score_key(scores[j]);
+      clip_span(D, c0, sstart[j0 + q], slen[j0 + q], lo, hi);
+      t_clip[q] = max(hi - lo, 0);
+      t_key[q] = score_key(scores[j0 + q]);
     }
     __syncthreads();
-    const int m = min(256, n - j0);
-    for (int jj = jp; jj < m; jj += 8) {
+    const int m = min(SEL_STAGE, n - j0);
+    for (int jj = jp; jj < m; jj += SEL_PARTS) {
       const int cj = t_clip[jj];
       const uint64_t kj = t_key[jj];
       const bool before = (kj < ki) | ((kj == ki) & (j0 + jj < i));
@@ -286,7 +324,7 @@ __global__ __launch_bounds__(256) void select_rank_kernel(RetArgs a) {
     }
   }
 #pragma unroll
-  for (int o = 1; o < 8; o <<= 1) {
+  for (int o = 1; o < SEL_PARTS; o <<= 1) {
     rank += __shfl_xor(rank, o, 64);
     cum += __shfl_xor(cum, o, 64);
   }
@@ -373,12 +411,12 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
     if (bf) qrep_kernel<LTRI_BF16><<<gq, 1024, 0, s>>>(a);
     else    qrep_kernel<LTRI_F32><<<gq, 1024, 0, s>>>(a);
   }
-  int gx = (span_bound + 3) / 4;
+  int gx = (span_bound + 63) / 64;
   if (gx < 1) gx = 1;
-  if (gx > 256) gx = 256;
   dim3 gs(gx, P);
-  if (bf) score_kernel<LTRI_BF16><<<gs, 256, 0, s>>>(a);
-  else    score_kernel<LTRI_F32><<<gs, 256, 0, s>>>(a);
+  const size_t qs_bytes = (size_t)SCORE_QBATCH * D.d * sizeof(double);
+  if (bf) score_kernel<LTRI_BF16><<<gs, 256, qs_bytes, s>>>(a);
+  else    score_kernel<LTRI_F32><<<gs, 256, qs_bytes, s>>>(a);
   int gr = (span_bound + SEL_SPANS_PER_BLOCK - 1) / SEL_SPANS_PER_BLOCK;
   if (gr < 1) gr = 1;
   select_rank_kernel<<<dim3(gr, P), 256, 0, s>>>(a);
