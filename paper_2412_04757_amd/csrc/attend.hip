@@ -16,6 +16,7 @@ namespace ltri {
 struct AttArgs {
   Dims D; DevState st; const void* k_arena; const void* v_arena; const void* q;
   void* out; float* lse; int layer; int seq_count; int n_q;
+  int n_splits; float* part;             // short query blocks: the key range is split over workgroups
   BatchPos bp;
 };
 
@@ -129,7 +130,8 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
   const int head = h * D.G + gsub * HG + (wave % HG);
-  const int rb0 = blockIdx.y * RPB;                 // first row of the block
+  const int split = a.n_splits > 1 ? blockIdx.y : 0;
+  const int rb0 = a.n_splits > 1 ? 0 : blockIdx.y * RPB;   // first row of the block
   const int r0 = rb0 + (wave / HG) * 32;            // first row of this wave
   const int slot = slot_of(D, a.layer, seq, h);
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.k_arena) + arena_off(D, slot) * 2;
@@ -141,6 +143,9 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   const int rb_end = min(L, rb0 + RPB);
   const int n_chunk_tiles = (rb_end + 63) / 64;
   const int n_tiles = n_ctx_tiles + n_chunk_tiles;
+  // with splits, this workgroup takes the context tiles [tile0, tile1); the last split also takes the chunk's tiles
+  const int tile0 = a.n_splits > 1 ? (int)((long long)split * n_ctx_tiles / a.n_splits) : 0;
+  const int tile1 = (a.n_splits > 1 && split + 1 < a.n_splits) ? (int)((long long)(split + 1) * n_ctx_tiles / a.n_splits) : n_tiles;
   const uint32_t ring0 = (uint32_t)(uintptr_t)ring;
   const uint32_t tok0 = ring0 + NS * DMA_STAGE_BYTES + (uint32_t)wave * 32;       // this wave's 8 ids of slot 0
   const int32_t* tokring = reinterpret_cast<const int32_t*>(ring + NS * DMA_STAGE_BYTES) + wave * 8;
@@ -368,15 +373,15 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
 
   // ---- prologue: token ids of the first NS tiles, then the steady-state request pattern
   //      (ids of tile u + TOK_AHEAD, K/V tile u + NS - 1) for u = -(NS - 1) .. -1 ----
-  for (int u = 0; u < NS; ++u) request_tokens(u);
+  for (int u = 0; u < NS; ++u) request_tokens(tile0 + u);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   for (int u = 0; u < NS - 1; ++u) {
-    request_tokens(u + NS);
-    tile_tokens(u, tokreg);
-    request_rows(u, 0, tokreg[0]);
-    request_rows(u, 1, tokreg[1]);
+    request_tokens(tile0 + u + NS);
+    tile_tokens(tile0 + u, tokreg);
+    request_rows(tile0 + u, 0, tokreg[0]);
+    request_rows(tile0 + u, 1, tokreg[1]);
   }
-  tile_tokens(NS - 1, tokreg);
+  tile_tokens(tile0 + NS - 1, tokreg);
 
   // ---- tile segments of this wavefront ----
   const bool active = r0 < L;
@@ -387,20 +392,34 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   using std::integral_constant;
   using std::true_type;
   using std::false_type;
-  int t = 0;
+  int t = tile0;
   if (active) {
-    for (; t < t_list_end; ++t) tile(t, integral_constant<int, MASK_NONE>{}, true_type{});
-    for (; t < n_ctx_tiles; ++t) tile(t, integral_constant<int, MASK_LIST_END>{}, true_type{});
-    for (; t < t_diag; ++t) tile(t, integral_constant<int, MASK_NONE>{}, true_type{});
-    for (; t < t_end; ++t) tile(t, integral_constant<int, MASK_CAUSAL>{}, true_type{});
+    for (; t < min(t_list_end, tile1); ++t) tile(t, integral_constant<int, MASK_NONE>{}, true_type{});
+    for (; t < min(n_ctx_tiles, tile1); ++t) tile(t, integral_constant<int, MASK_LIST_END>{}, true_type{});
+    for (; t < min(t_diag, tile1); ++t) tile(t, integral_constant<int, MASK_NONE>{}, true_type{});
+    for (; t < min(t_end, tile1); ++t) tile(t, integral_constant<int, MASK_CAUSAL>{}, true_type{});
   }
-  for (; t < n_tiles; ++t) tile(t, integral_constant<int, MASK_NONE>{}, false_type{});
+  for (; t < tile1; ++t) tile(t, integral_constant<int, MASK_NONE>{}, false_type{});
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the requests past the last tile
 
   // ---- epilogue ----
   uint16_t* Ob = reinterpret_cast<uint16_t*>(a.out) + (size_t)bi * L * D.Hq * d;
   const int qi = r0 + l32;
   const float lt = l_run + __shfl_xor(l_run, 32, 64);
+  if (a.n_splits > 1) {
+    // unnormalised O, running maximum and sum of this split: [seq][head][split][row][d + 2] fp32
+    if (qi < L) {
+      float* pr = a.part + ((((size_t)bi * D.Hq + head) * a.n_splits + split) * L + qi) * (d + 2);
+#pragma unroll
+      for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int a4 = 0; a4 < 4; ++a4)
+          *reinterpret_cast<float4*>(pr + mb * 32 + 8 * a4 + 4 * hf) =
+              make_float4(o[mb][4 * a4 + 0], o[mb][4 * a4 + 1], o[mb][4 * a4 + 2], o[mb][4 * a4 + 3]);
+      if (hf == 0) { pr[d] = m_run; pr[d + 1] = lt; }
+    }
+    return;
+  }
   if (qi < L) {
     const float inv = 1.f / lt;
     uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
@@ -416,6 +435,26 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
     if (a.lse && hf == 0)
       a.lse[((size_t)bi * L + qi) * D.Hq + head] = (m_run + log2f(lt)) * 0.6931471805599453f;
   }
+}
+
+// ---- merge of the splits of a short query block: O = sum_s w_s O_s / sum_s w_s l_s,
+//      w_s = 2^(m_s - max m) (the log-sum-exp identity), one workgroup per (row, head, sequence) ----
+__global__ __launch_bounds__(128) void attend_merge_kernel(AttArgs a) {
+  const Dims& D = a.D;
+  const int qi = blockIdx.x, head = blockIdx.y, bi = blockIdx.z, d = 128, L = a.n_q, c = threadIdx.x;
+  const float* pr = a.part + ((size_t)bi * D.Hq + head) * a.n_splits * L * (d + 2);
+  float mmax = -1e30f;
+  for (int s = 0; s < a.n_splits; ++s) mmax = fmaxf(mmax, pr[((size_t)s * L + qi) * (d + 2) + d]);
+  float acc = 0.f, l = 0.f;
+  for (int s = 0; s < a.n_splits; ++s) {
+    const float* q = pr + ((size_t)s * L + qi) * (d + 2);
+    const float w = __builtin_amdgcn_exp2f(q[d] - mmax);
+    acc = fmaf(w, q[c], acc);
+    l = fmaf(w, q[d + 1], l);
+  }
+  uint16_t* orow = reinterpret_cast<uint16_t*>(a.out) + (((size_t)bi * L + qi) * D.Hq + head) * d;
+  orow[c] = f32_to_bf16(acc / l);
+  if (a.lse && c == 0) a.lse[((size_t)bi * L + qi) * D.Hq + head] = (mmax + log2f(l)) * 0.6931471805599453f;
 }
 
 // ---- fp32 kernel: one wavefront per (query row, head); keys across lanes ----
@@ -516,10 +555,11 @@ __global__ __launch_bounds__(256) void gather_pack_kernel(GatherArgs a) {
 
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
-                         void* out, float* lse, int stages, hipStream_t s) {
+                         void* out, float* lse, int stages, float* part, hipStream_t s) {
   AttArgs a;
   a.D = D; a.st = st; a.k_arena = k_arena; a.v_arena = v_arena; a.q = q; a.out = out; a.lse = lse;
   a.layer = layer; a.seq_count = seq_count; a.n_q = n_q; a.bp = bp;
+  a.n_splits = 1; a.part = part;
   const bool mfma_ok = D.dtype == LTRI_BF16 && D.d == 128 && (D.G == 1 || D.G == 2 || D.G % 4 == 0);
   if (mfma_ok) {
     const int HG = D.G < 4 ? D.G : 4;
@@ -527,6 +567,14 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
     constexpr int NW = ATT_NW;
     const int RPB = 32 * (NW / HG);
     dim3 g(D.Hkv * gpk, (n_q + RPB - 1) / RPB, seq_count);
+    // a short query block (decode) on few workgroups: split the key range so that every compute
+    // unit streams a share of it; the partial results are merged by a second kernel
+    const int blocks = D.Hkv * gpk * seq_count;
+    if (n_q <= ATT_SPLIT_MAX_ROWS && part && blocks < 256) {
+      int ns = 256 / blocks;
+      a.n_splits = ns > ATT_MAX_SPLITS ? ATT_MAX_SPLITS : ns;
+      if (a.n_splits > 1) g.y = a.n_splits;
+    }
     static bool attr_set = false;
     if (!attr_set) {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attend_bf16_kernel<NW, 4>),
@@ -539,6 +587,7 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
     }
     if (stages == 3) attend_bf16_kernel<NW, 3><<<g, 64 * NW, att_lds_bytes(3, NW), s>>>(a);
     else             attend_bf16_kernel<NW, 4><<<g, 64 * NW, att_lds_bytes(4, NW), s>>>(a);
+    if (a.n_splits > 1) attend_merge_kernel<<<dim3(n_q, D.Hq, seq_count), 128, 0, s>>>(a);
   } else {
     dim3 g(n_q, D.Hq, seq_count);
     if (D.dtype == LTRI_BF16) attend_simple_kernel<LTRI_BF16><<<g, 64, 0, s>>>(a);

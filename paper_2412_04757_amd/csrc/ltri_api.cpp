@@ -115,6 +115,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.qpart = o;  o = align_up(o + (size_t)P * (Lp / 128 + Lp) * D.d * 8, 256);
   CL.bounds = o; o = align_up(o + (size_t)c.n_kv_heads * (c.chunk_max + 2) * 4, 256);
   CL.selflag = o; o = align_up(o + (size_t)c.n_seqs * c.n_kv_heads * D.max_spans, 256);
+  CL.att_part = o; o = align_up(o + (size_t)c.n_seqs * c.n_q_heads * ATT_MAX_SPLITS * ATT_SPLIT_MAX_ROWS * (D.d + 2) * 4, 256);
   CL.total = o;
   CL.max_problems = P;
   return LTRI_OK;
@@ -172,7 +173,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->dc = DevScratch{(double*)(t + CL.rowsum), (double*)(t + CL.csuf), (double*)(t + CL.tsum),
                      (double*)(t + CL.rcar), (double*)(t + CL.ccar), (double*)(t + CL.pscore),
                      (int32_t*)(t + CL.px), (uint64_t*)(t + CL.ckey), (uint32_t*)(t + CL.cxy), (double*)(t + CL.lse), (void*)(t + CL.qrep),
-                     (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds), (uint8_t*)(t + CL.selflag)};
+                     (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds), (uint8_t*)(t + CL.selflag), (float*)(t + CL.att_part)};
   const size_t n = (size_t)D.n_layers * D.n_seqs;
   c->n_tokens.assign(n, 0);
   c->last_len.assign(n, 0);
@@ -437,7 +438,7 @@ int32_t ltri_attend(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_c
                   seq_begin + s);
   if (!c->dry) {
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_q, out, lse,
-                                   c->attend_stages, c->stream), "attend");
+                                   c->attend_stages, c->dc.att_part, c->stream), "attend");
     if (r != LTRI_OK) return r;
   }
   return LTRI_OK;

@@ -24,7 +24,9 @@ constexpr int SEG_TB = 64;          // side of a segmentation tile
 constexpr int SEG_MAX_L = 2048;     // longest chunk the segmentation kernels take
 constexpr int SEG_MAX_NB = SEG_MAX_L / SEG_TB;
 constexpr int SEG_MAX_DIAG = 2 * SEG_MAX_L;   // anti-diagonals of the largest map (2 L - 1), rounded up
-constexpr int ATT_BN = 64;          // keys per attention tile; token lists are padded to it
+constexpr int ATT_BN = 64;
+constexpr int ATT_MAX_SPLITS = 8;        // key-range splits of a short query block (decode)
+constexpr int ATT_SPLIT_MAX_ROWS = 4;    // longest query block that is split          // keys per attention tile; token lists are padded to it
 
 // Byte offsets of the arrays inside the caller's `state` buffer.
 struct StateLayout {
@@ -55,6 +57,7 @@ struct ScratchLayout {
   size_t qpart;    // double [P][Lp / 128 + Lp][d]  sums of 128-token pieces of query spans
   size_t bounds;   // int32  [Hkv][chunk_max + 1] + int32 [Hkv]  (append_with_spans)
   size_t selflag;  // uint8  [n_seqs * Hkv][max_spans]  1 = span selected (between the two selection kernels)
+  size_t att_part; // float  [n_seqs][Hq][ATT_MAX_SPLITS][ATT_SPLIT_MAX_ROWS][d + 2]  partial attention results
   size_t total;
   int    max_problems;  // P the buffer was sized for
 };
@@ -83,7 +86,7 @@ struct DevState {
 };
 struct DevScratch {
   double* rowsum; double* csuf; double* tsum; double* rcar; double* ccar;
-  double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds; uint8_t* selflag;
+  double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds; uint8_t* selflag; float* att_part;
 };
 
 // ---- launchers (each returns the hipError_t of the launch) ----
@@ -107,7 +110,7 @@ hipError_t launch_force_list(const Dims& D, const DevState& st, int layer, int s
                              int n_ids, hipStream_t s);
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
-                         void* out, float* lse, int stages, hipStream_t s);
+                         void* out, float* lse, int stages, float* part, hipStream_t s);
 hipError_t launch_gather_pack(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                               int layer, int seq, void* k_packed, void* v_packed, int32_t* n_tokens,
                               hipStream_t s);
