@@ -83,6 +83,124 @@ def cpu_baseline(w, K, V, Q, bounds, theta, rows_sampled=128):
                       f"boundaries (setup, untimed); fp64 numpy"}
 
 
+def run_decode(args, torch, dev):
+    """Batched decode at the cfg5 shape (not the headline line): 16 sequences with `context` tokens
+    each, one new token per step; every step appends, re-scores all stored spans, selects under the
+    budget and attends. The index is built from the planted boundaries (the prefill path measures
+    the segmentation). Prints one JSON line of its own."""
+    import numpy as np
+    from paper_2412_04757_amd import LtriContext, config_from_workload
+    from workloads import CONFIGS, planted_stream, theta_default
+    w = CONFIGS["cfg5"]
+    T0 = args.context or w.context
+    n_seqs, L, steps, warm = 16, 2048, max(8, args.steps * 8), 4
+    T = T0 + steps + warm
+    cfg = config_from_workload(w, max_tokens=T, theta=theta_default(w.head_dim), n_layers=1, n_seqs=n_seqs)
+    ctx = LtriContext(cfg, dev)
+    ka, va = ctx.arena_views()
+    Qs = []
+    for s in range(n_seqs):
+        K, V, Q, bounds = planted_stream(w, args.seed, device="cuda:0", context=T, seq=s)
+        ka[0, s, :, :T].copy_(K)
+        va[0, s, :, :T].copy_(V)
+        Qs.append(Q[T0:T].clone())
+        for c0 in range(0, T0, L):
+            n = min(L, T0 - c0)
+            b = [np.asarray(sorted({0, n} | {int(x - c0) for x in bounds[h][(bounds[h] > c0) & (bounds[h] < c0 + n)]}), np.int32)
+                 for h in range(w.n_kv_heads)]
+            ctx.append_chunk_with_spans(0, s, n, b)
+        del K, V, Q
+    out = torch.empty((n_seqs, 1, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+    qsteps = [torch.stack([Qs[s][k:k + 1] for s in range(n_seqs)]).contiguous() for k in range(steps + warm)]
+    for k in range(warm):
+        ctx.append_chunk(0, 0, n_seqs, 1)
+        ctx.retrieve(0, 0, n_seqs, qsteps[k])
+        ctx.attend(0, 0, n_seqs, qsteps[k], out=out)
+    torch.cuda.synchronize()
+    n_att = sum(len(ctx.get_token_list(0, s, h)) for s in range(n_seqs) for h in range(w.n_kv_heads))
+    evs = []
+    for k in range(warm, warm + steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+        e[0].record(); ctx.append_chunk(0, 0, n_seqs, 1)
+        e[1].record(); ctx.retrieve(0, 0, n_seqs, qsteps[k])
+        e[2].record(); ctx.attend(0, 0, n_seqs, qsteps[k], out=out)
+        e[3].record(); evs.append(e)
+    torch.cuda.synchronize()
+    if ctx.sync_status() != 0:
+        print("bench.py: device status", ctx.sync_status(), file=sys.stderr)
+        sys.exit(1)
+    med = lambda i: float(np.median([e[i].elapsed_time(e[i + 1]) for e in evs]) * 1e3)
+    ap_us, rt_us, at_us = med(0), med(1), med(2)
+    kv_bytes = n_att * w.head_dim * 2 * 2
+    step_us = ap_us + rt_us + at_us
+    print(json.dumps({
+        "metric": "decode step time per layer", "value": round(step_us, 1), "unit": "us", "n_gpus": 1, "steps": steps,
+        "warmup": warm, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg5: 16 sequences x {T0} tokens, 32 query / 8 KV heads, head_dim 128, bf16, 4 sink tokens, "
+                               f"window {w.window}, retrieval budget {w.budget_tokens} tokens, one token per step"},
+        "breakdown_us": {"append": round(ap_us, 1), "retrieve": round(rt_us, 1), "attend": round(at_us, 1)},
+        "roofline": {"bound": "hbm", "kernel": "attend_bf16_kernel (split keys) + attend_merge_kernel",
+                     "achieved": round(kv_bytes / at_us / 1e3, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                     "frac": round(kv_bytes / at_us / 1e3 / PEAK_HBM_GBPS, 4), "kv_bytes_per_step": kv_bytes,
+                     "whole_step_GBps": round(kv_bytes / step_us / 1e3, 1)}}))
+
+
+def run_layers(args, torch, dev):
+    """All layers resident at the cfg4 shape (not the headline line): 32 layers x 256K tokens of K/V
+    (34 GB) plus every layer's span index stay in HBM; the last chunk of the stream is run through
+    every layer in turn (real segmentation, retrieval, attention). Prints one JSON line of its own:
+    per-chunk time per layer, its spread over the layers, and the resident bytes."""
+    import numpy as np
+    from paper_2412_04757_amd import LtriContext, config_from_workload
+    from workloads import CONFIGS, planted_stream, theta_default
+    w = CONFIGS["cfg4"]
+    T = args.context or w.context
+    L, n_layers = w.chunk, w.n_layers
+    cfg = config_from_workload(w, max_tokens=T, theta=theta_default(w.head_dim), n_layers=n_layers, n_seqs=1)
+    ctx = LtriContext(cfg, dev)
+    ka, va = ctx.arena_views()
+    T0 = T - L                                  # history through the planted boundaries, last chunk for real
+    qs = []
+    for layer in range(n_layers):
+        K, V, Q, bounds = planted_stream(w, args.seed, device="cuda:0", context=T, layer=layer)
+        ka[layer, 0].copy_(K)
+        va[layer, 0].copy_(V)
+        qs.append(Q[T0:T].clone())
+        for c0 in range(0, T0, L):
+            b = [np.asarray(sorted({0, L} | {int(x - c0) for x in bounds[h][(bounds[h] > c0) & (bounds[h] < c0 + L)]}), np.int32)
+                 for h in range(w.n_kv_heads)]
+            ctx.append_chunk_with_spans(layer, 0, L, b)
+        del K, V, Q
+        log(f"[bench] layer {layer} resident")
+    out = torch.empty((1, L, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+    times = []
+    for layer in range(n_layers):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ctx.append_chunk(layer, 0, 1, L)
+        ctx.retrieve(layer, 0, 1, qs[layer])
+        ctx.attend(layer, 0, 1, qs[layer], out=out)
+        e1.record()
+        times.append((e0, e1))
+    torch.cuda.synchronize()
+    if ctx.sync_status() != 0:
+        print("bench.py: device status", ctx.sync_status(), file=sys.stderr)
+        sys.exit(1)
+    us = np.asarray([a.elapsed_time(b) * 1e3 for a, b in times])
+    spans = [ctx.span_count(layer, 0, 0) for layer in (0, n_layers - 1)]
+    print(json.dumps({
+        "metric": "last-chunk time per layer with all layers resident", "value": round(float(np.median(us[1:])), 1), "unit": "us",
+        "n_gpus": 1, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg4: {n_layers} layers x {T} tokens resident, 32 query / 8 KV heads, head_dim 128, bf16, "
+                               f"chunk {L}, window {w.window}, budget {w.budget_tokens}"},
+        "per_layer_us": {"first_layer_incl_warmup": round(float(us[0]), 1), "min": round(float(us[1:].min()), 1),
+                         "median": round(float(np.median(us[1:])), 1), "max": round(float(us[1:].max()), 1)},
+        "resident_bytes": {"kv_arenas": int(ka.numel() * ka.element_size() * 2), "index_state": int(ctx.state.numel()),
+                           "scratch": int(ctx.scratch.numel())},
+        "spans_kv_head0": {"layer0": spans[0], f"layer{n_layers - 1}": spans[1]}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,6 +227,12 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
+    if args.workload == "cfg5":
+        run_decode(args, torch, dev)
+        return
+    if args.workload == "cfg4":
+        run_layers(args, torch, dev)
+        return
     w = CONFIGS[args.workload]
     if args.context:
         from dataclasses import replace
