@@ -201,6 +201,63 @@ def run_layers(args, torch, dev):
         "spans_kv_head0": {"layer0": spans[0], f"layer{n_layers - 1}": spans[1]}}))
 
 
+def run_attend_occupancy(args, torch, dev):
+    """The attend kernel of the default workload with fewer and fewer compute units busy (not the
+    headline line): the last chunk of the cfg3 stream is cut to 2048, 1024, 512 and 256 queries, which
+    gives 256, 128, 64 and 32 workgroups (one per compute unit) over the same ~12K-key context. If the
+    rate per busy compute unit rises as the chip empties, the full launch is held back by a chip-wide
+    limit (power, clocks) and not by the kernel's instruction schedule. Prints one JSON line of its own."""
+    import numpy as np
+    from paper_2412_04757_amd import LtriContext, config_from_workload
+    from workloads import CONFIGS, planted_stream, theta_default
+    w = CONFIGS["cfg3"]
+    T, L = w.context, w.chunk
+    K, V, Q, bounds = planted_stream(w, args.seed, device="cuda:0")
+    rows = []
+    for n_q in (2048, 1024, 512, 256):
+        cfg = config_from_workload(w, theta=theta_default(w.head_dim), n_layers=1, n_seqs=1)
+        ctx = LtriContext(cfg, dev)
+        ka, va = ctx.arena_views()
+        ka[0, 0].copy_(K)
+        va[0, 0].copy_(V)
+        T0 = T - L
+        for c0 in list(range(0, T0, L)) + [T0]:
+            n = L if c0 < T0 else n_q
+            b = [np.asarray(sorted({0, n} | {int(x - c0) for x in bounds[h][(bounds[h] > c0) & (bounds[h] < c0 + n)]}), np.int32)
+                 for h in range(w.n_kv_heads)]
+            ctx.append_chunk_with_spans(0, 0, n, b)
+        q = Q[T0:T0 + n_q].contiguous()
+        ctx.retrieve(0, 0, 1, q)
+        out = torch.empty((1, n_q, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+        lens = [len(ctx.get_token_list(0, 0, h)) for h in range(w.n_kv_heads)]
+        flops = attend_flops(w, n_q, lens)
+        reps = 10 * max(1, args.steps)
+        for _ in range(3):
+            ctx.attend(0, 0, 1, q, out=out)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            ctx.attend(0, 0, 1, q, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        if ctx.sync_status() != 0:
+            print("bench.py: device status", ctx.sync_status(), file=sys.stderr)
+            sys.exit(1)
+        us = e0.elapsed_time(e1) / reps * 1e3
+        groups = w.n_kv_heads * (n_q // 64)
+        rows.append({"queries": n_q, "workgroups": groups, "us": round(us, 1), "tflops": round(flops / us / 1e6, 1),
+                     "tflops_per_workgroup": round(flops / us / 1e6 / groups, 3)})
+        log(f"[bench] attend, {n_q} queries on {groups} workgroups: {us:.1f} us, {flops / us / 1e6:.1f} TFLOP/s")
+        del ctx
+    full, least = rows[0], rows[-1]
+    print(json.dumps({
+        "metric": "attend rate per busy compute unit, 32 workgroups over 256", "unit": "ratio",
+        "value": round(least["tflops_per_workgroup"] / full["tflops_per_workgroup"], 3),
+        "n_gpus": 1, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg3, last chunk cut to 2048 / 1024 / 512 / 256 queries over the full 128K stream's index"},
+        "launches": rows}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -232,6 +289,9 @@ def main():
         return
     if args.workload == "cfg4":
         run_layers(args, torch, dev)
+        return
+    if args.workload == "attend-occupancy":
+        run_attend_occupancy(args, torch, dev)
         return
     w = CONFIGS[args.workload]
     if args.context:
