@@ -5,6 +5,7 @@
 //
 // Scores are accumulated in fp64: products of bf16 (or fp32) values are exact in fp64, so the
 // order of the selection does not depend on the summation order of any implementation.
+#include <type_traits>
 #include "device_common.h"
 #include "span_mean.h"
 
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(256) void score_kernel(RetArgs a) {
   const T* krep = reinterpret_cast<const T*>(a.st.krep) + (size_t)slot * D.max_spans * d;
   double* scores = a.st.scores + (size_t)slot * D.max_spans;
   const int i = blockIdx.x * (blockDim.x / 4) + (threadIdx.x >> 2), part = threadIdx.x & 3;
-  const uint4* krow = reinterpret_cast<const uint4*>(krep + (size_t)min(i, n - 1) * d);
+  const uint4* krow = reinterpret_cast<const uint4*>(krep + (size_t)max(min(i, n - 1), 0) * d);
   double best = -INFINITY;
   for (int j0 = 0; j0 < nqs; j0 += SCORE_QBATCH) {
     const int nj = min(SCORE_QBATCH, nqs - j0);
@@ -359,6 +360,198 @@ __global__ __launch_bounds__(1024) void select_emit_kernel(RetArgs a) {
   emit_selection(D, a.st, slot, selmask, n, ids_out, cnt_out);
 }
 
+// ---- step 2 for a one-token chunk (decode) in one launch: one workgroup per (sequence, KV head) ----
+// The chunk is its own single query span, so Q^R is the group-summed query row rounded to the
+// stored precision. Scores as in score_kernel. The selection rule is the one of select_rank_kernel,
+// reached by sorting: eligible spans are sorted by (key, id) in LDS (bitonic network over the next
+// power of two), their clipped lengths are scanned in that order, and the selected set is the
+// prefix that fits. Spans: at most RT1_MAX_SPANS (the launcher checks its bound).
+constexpr int RT1_MAX_SPANS = 8192;
+constexpr uint32_t RT1_PAD = 0xffffffffu;
+__host__ __device__ constexpr int rt1_pow2(int n) { int m = 64; while (m < n) m <<= 1; return m; }
+// dynamic LDS: keys, ids, clipped lengths
+__host__ __device__ constexpr size_t rt1_lds_bytes(int bound) { return (size_t)rt1_pow2(bound) * 12 + (size_t)bound * 4; }
+
+template <int DT>
+__global__ __launch_bounds__(1024) void retrieve_one_token_kernel(RetArgs a, int bound) {
+  typedef typename Elt<DT>::type T;
+  constexpr int N = 16 / (int)sizeof(T);                // elements per 16-byte piece
+  extern __shared__ __attribute__((aligned(16))) unsigned char rt1_lds[];
+  __shared__ double qv[128];
+  __shared__ uint32_t selmask[RT1_MAX_SPANS / 32 + 2];
+  __shared__ long long wave_tot[16];
+  const Dims& D = a.D;
+  const int p = blockIdx.x, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int n = min(meta[META_N_SPANS], bound), c0 = meta[META_CHUNK_START];
+  const int d = D.d, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int npow = rt1_pow2(n);
+  uint64_t* skey = reinterpret_cast<uint64_t*>(rt1_lds);
+  uint32_t* sidx = reinterpret_cast<uint32_t*>(rt1_lds + (size_t)rt1_pow2(bound) * 8);
+  int* clip = reinterpret_cast<int*>(rt1_lds + (size_t)rt1_pow2(bound) * 12);
+  // scores, order keys and clipped lengths: four lanes per span
+  const T* krep = reinterpret_cast<const T*>(a.st.krep) + (size_t)slot * D.max_spans * d;
+  double* scores = a.st.scores + (size_t)slot * D.max_spans;
+  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
+  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
+  constexpr int PPL = 128 / N / 4;                      // 16-byte pieces per lane (d = 128)
+  constexpr int PASSES = DT == LTRI_BF16 ? 3 : 1;       // spans per thread whose loads are in flight together
+  const int part = tid & 3;
+  uint4 kv[PASSES][PPL];
+  int ss[PASSES], sl[PASSES];                           // the spans' extents travel with their keys
+  auto load_batch = [&](int i00) {
+#pragma unroll
+    for (int u = 0; u < PASSES; ++u) {
+      const int ic = max(min(i00 + 256 * u + (tid >> 2), n - 1), 0);
+      const uint4* krow = reinterpret_cast<const uint4*>(krep + (size_t)ic * d);
+#pragma unroll
+      for (int q = 0; q < PPL; ++q) kv[u][q] = krow[part + 4 * q];
+      ss[u] = sstart[ic];
+      sl[u] = slen[ic];
+    }
+  };
+  load_batch(0);                                        // in flight while the query row is fetched
+  // Q^R of the chunk's one span
+  if (tid < d) {
+    const T* Qb = reinterpret_cast<const T*>(a.q) + (size_t)bi * D.Hq * d + (size_t)h * D.G * d;
+    double sum = 0.0;
+    for (int g = 0; g < D.G; ++g) sum += Elt<DT>::to_f64(Qb[(size_t)g * d + tid]);
+    const T r = Elt<DT>::from_f64(sum);
+    reinterpret_cast<T*>(a.sc.qrep)[(size_t)p * a.Lp * d + tid] = r;
+    qv[tid] = Elt<DT>::to_f64(r);
+  }
+  for (int w = tid; w < (n + 31) / 32 + 2; w += blockDim.x) selmask[w] = 0u;
+  __syncthreads();
+  for (int i00 = 0; i00 < npow; i00 += 256 * PASSES) {
+    if (i00 > 0) load_batch(i00);
+#pragma unroll
+    for (int u = 0; u < PASSES; ++u) {
+      const int i = i00 + 256 * u + (tid >> 2);
+      double acc = 0.0;
+#pragma unroll
+      for (int q = 0; q < PPL; ++q) {
+        const int pc = part + 4 * q;
+        double k[8];
+        if constexpr (DT == LTRI_BF16) {
+          const uint32_t w[4] = {kv[u][q].x, kv[u][q].y, kv[u][q].z, kv[u][q].w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            k[2 * e] = (double)__uint_as_float(w[e] << 16);
+            k[2 * e + 1] = (double)__uint_as_float(w[e] & 0xffff0000u);
+          }
+        } else {
+          k[0] = (double)__uint_as_float(kv[u][q].x); k[1] = (double)__uint_as_float(kv[u][q].y);
+          k[2] = (double)__uint_as_float(kv[u][q].z); k[3] = (double)__uint_as_float(kv[u][q].w);
+        }
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc = fma(k[e], qv[pc * N + e], acc);
+      }
+      acc += __shfl_xor(acc, 1, 64);
+      acc += __shfl_xor(acc, 2, 64);
+      if (part == 0 && i < npow) {
+        int c = 0;
+        if (i < n) {
+          int lo, hi;
+          clip_span(D, c0, ss[u], sl[u], lo, hi);
+          c = max(hi - lo, 0);
+          scores[i] = acc;
+          clip[i] = c;
+        }
+        // spans that cannot be retrieved go to the end of the order with the padding
+        skey[i] = c > 0 ? score_key(acc) : ~0ull;
+        sidx[i] = c > 0 ? (uint32_t)i : RT1_PAD;
+      }
+    }
+  }
+  __syncthreads();
+  // bitonic network, ascending in (key, id)
+  if (npow <= (int)blockDim.x) {
+    // one position per thread, held in registers; partners at distance < 64 are reached by lane
+    // exchanges on the vector ALU, the others through LDS
+    const bool live = tid < npow;
+    uint64_t key = live ? skey[tid] : ~0ull;
+    uint32_t id = live ? sidx[tid] : RT1_PAD;
+    // (key, id) pairs are distinct apart from the padding, whose copies are interchangeable
+    auto merge = [&](int k, int j, uint64_t pk, uint32_t pid) {
+      const bool keep_less = ((tid & j) == 0) == ((tid & k) == 0);
+      const bool take = key_less(pk, pid, key, id) == keep_less;
+      key = take ? pk : key;
+      id = take ? pid : id;
+    };
+    auto lanes = [&](int k, auto jc) {
+      constexpr int J = decltype(jc)::value;
+      const uint32_t lo = lane_xor_c<J>((uint32_t)key), hi = lane_xor_c<J>((uint32_t)(key >> 32));
+      merge(k, J, ((uint64_t)hi << 32) | lo, lane_xor_c<J>(id));
+    };
+    using std::integral_constant;
+    for (int k = 2; k <= npow; k <<= 1) {
+      for (int j = k >> 1; j >= 64; j >>= 1) {
+        __syncthreads();
+        if (live) { skey[tid] = key; sidx[tid] = id; }
+        __syncthreads();
+        if (live) merge(k, j, skey[tid ^ j], sidx[tid ^ j]);
+      }
+      if (k >= 64) lanes(k, integral_constant<int, 32>{});
+      if (k >= 32) lanes(k, integral_constant<int, 16>{});
+      if (k >= 16) lanes(k, integral_constant<int, 8>{});
+      if (k >= 8) lanes(k, integral_constant<int, 4>{});
+      if (k >= 4) lanes(k, integral_constant<int, 2>{});
+      lanes(k, integral_constant<int, 1>{});
+    }
+    __syncthreads();
+    if (live) { skey[tid] = key; sidx[tid] = id; }
+    __syncthreads();
+  } else {
+    for (int k = 2; k <= npow; k <<= 1) {
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        for (int t = tid; t < npow / 2; t += blockDim.x) {
+          const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+          const uint64_t ka = skey[lo], kb = skey[hi];
+          const uint32_t ia = sidx[lo], ib = sidx[hi];
+          const bool a_after_b = (ka > kb) | ((ka == kb) & (ia > ib));
+          if (a_after_b == ((lo & k) == 0)) {
+            skey[lo] = kb; skey[hi] = ka;
+            sidx[lo] = ib; sidx[hi] = ia;
+          }
+        }
+        __syncthreads();
+      }
+    }
+  }
+  // clipped tokens up to and including each position of the order; the prefix that fits is selected
+  const int E = max(npow / (int)blockDim.x, 1);           // consecutive positions per thread
+  long long mine = 0;
+  for (int e = 0; e < E; ++e) {
+    const int r = tid * E + e;
+    const uint32_t id = r < npow ? sidx[r] : RT1_PAD;
+    mine += id != RT1_PAD ? clip[id] : 0;
+  }
+  long long incl = mine;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const long long v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  long long cum = incl - mine;
+  for (int w2 = 0; w2 < wave; ++w2) cum += wave_tot[w2];
+  for (int e = 0; e < E; ++e) {
+    const int r = tid * E + e;
+    const uint32_t id = r < npow ? sidx[r] : RT1_PAD;
+    if (id != RT1_PAD) {
+      cum += clip[id];
+      const bool sel = (D.k_max == 0 || r < D.k_max) && (D.budget == 0 || cum <= D.budget);
+      if (sel) atomicOr(&selmask[id >> 5], 1u << (id & 31));
+    }
+  }
+  __syncthreads();
+  int32_t* ids_out = a.sel_ids_out ? a.sel_ids_out + (size_t)p * D.sel_cap : nullptr;
+  int32_t* cnt_out = a.sel_cnt_out ? a.sel_cnt_out + p : nullptr;
+  emit_selection(D, a.st, slot, selmask, n, ids_out, cnt_out);
+}
+
 // ---- caller-forced selection: ids already copied (ascending, unique) into sel_ids ----
 struct ForceArgs { Dims D; DevState st; int layer, seq, h, n_ids; };
 
@@ -395,6 +588,23 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
   const int P = seq_count * D.Hkv;
   const bool bf = D.dtype == LTRI_BF16;
   a.batch_off = 0;
+  if (n_q == 1 && span_bound >= 1 && span_bound <= RT1_MAX_SPANS && D.d == 128) {
+    // decode: the whole step in one launch
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&retrieve_one_token_kernel<LTRI_BF16>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)rt1_lds_bytes(RT1_MAX_SPANS));
+      if (e != hipSuccess) return e;
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&retrieve_one_token_kernel<LTRI_F32>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)rt1_lds_bytes(RT1_MAX_SPANS));
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    const size_t lds = rt1_lds_bytes(span_bound);
+    if (bf) retrieve_one_token_kernel<LTRI_BF16><<<P, 1024, lds, s>>>(a, span_bound);
+    else    retrieve_one_token_kernel<LTRI_F32><<<P, 1024, lds, s>>>(a, span_bound);
+    return hipGetLastError();
+  }
   a.units_cap = n_q / QREP_PIECE + n_q;                  // pieces of all spans of a chunk, at most
   if (n_q > QREP_PIECE) {
     const int per = sc_max_problems / D.Hkv;               // sequences the piece buffer holds

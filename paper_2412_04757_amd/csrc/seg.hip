@@ -355,32 +355,6 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
 
 // ---- pass 4: candidates -> greedy NMS -> cuts -> span table ----
 
-// Value of lane (lane ^ M) for M = 1 .. 32, on the vector ALU (DPP / lane-swap instructions)
-// instead of the LDS crossbar that __shfl_xor goes through.
-template <int M>
-__device__ __forceinline__ uint32_t lane_xor_c(uint32_t v) {
-  if constexpr (M == 1) {
-    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0xB1, 0xF, 0xF, true);          // quad_perm [1,0,3,2]
-  } else if constexpr (M == 2) {
-    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x4E, 0xF, 0xF, true);          // quad_perm [2,3,0,1]
-  } else if constexpr (M == 4) {
-    int r = __builtin_amdgcn_update_dpp(0, (int)v, 0x104, 0xF, 0x5, false);           // banks 0, 2 <- lane + 4
-    r = __builtin_amdgcn_update_dpp(r, (int)v, 0x114, 0xF, 0xA, false);               // banks 1, 3 <- lane - 4
-    return (uint32_t)r;
-  } else if constexpr (M == 8) {
-    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x128, 0xF, 0xF, true);         // row_ror:8
-  } else if constexpr (M == 16) {
-    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-    return (threadIdx.x & 16) ? r[0] : r[1];
-  } else {
-    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-    return (threadIdx.x & 32) ? r[0] : r[1];
-  }
-}
-__device__ __forceinline__ bool key_less(uint64_t a1, uint32_t a2, uint64_t b1, uint32_t b2) {
-  return (a1 < b1) || (a1 == b1 && a2 < b2);
-}
-
 // Appends the spans cut at cutlist[0..n_cuts) (chunk-local, first 0, last L) to the slot's table.
 __device__ void append_spans(const Dims& D, const DevState& st, int slot, int c0, int L,
                              const int* cutlist, int n_cuts) {
