@@ -172,6 +172,43 @@ def test_given_spans_forced_selection_and_gather(gpu_device):
     assert ctx.sync_status() == 0
 
 
+def test_one_token_step_edges(gpu_device):
+    """Decode (one-token chunks) over indexes that stress the selection: more than 1024 stored spans,
+    exactly tied scores (identical spans: the lower id goes first), a count cap, a token budget, and no
+    limit at all. Ids, scores, token lists and outputs against the oracle on every step."""
+    w = Workload("mini-decode", 8, 2, 128, "bf16", 3072 + 8, 1024, 4, 64, 0, 0, "uniform", 16, 64)
+    T0, L, steps = 3072, 1024, 3
+    K, V, Q, _ = planted_stream(w, 13, device=str(gpu_device), context=T0 + steps)
+    # tokens 1024 .. 1535 repeat with period 4: the two-token spans there come in identical pairs
+    K[:, 1028:1536] = K[:, 1024:1028].repeat(1, 127, 1)
+    cases = [dict(k_max=0, budget_tokens=200), dict(k_max=7, budget_tokens=0), dict(k_max=0, budget_tokens=0),
+             dict(k_max=900, budget_tokens=1500)]
+    for kw in cases:
+        ctx, st = make_pair(w, K, V, gpu_device, max_tokens=T0 + steps, max_spans=2048, **kw)
+        for c0 in range(0, T0, L):
+            b = [np.arange(0, L + 1, 2, dtype=np.int64) for _ in range(w.n_kv_heads)]     # 512 spans of two tokens
+            ctx.append_chunk_with_spans(0, 0, L, b)
+            st.append_chunk(L, bounds=b)
+        for k in range(steps):
+            pos = T0 + k
+            q = Q[pos:pos + 1].contiguous()
+            qn = q.double().cpu().numpy()
+            ctx.append_chunk(0, 0, 1, 1)
+            st.append_chunk(1)
+            ctx.retrieve(0, 0, 1, q)
+            sel = st.retrieve(qn)
+            for h in range(w.n_kv_heads):
+                ids, scores = ctx.get_selection(0, 0, h)
+                np.testing.assert_allclose(scores, st.sel_scores[h], rtol=1e-12, atol=1e-12)
+                assert list(ids) == list(sel[h]), f"{kw}, step {k}, head {h}"
+                assert list(ctx.get_token_list(0, 0, h)) == list(st.context_tokens(h))
+            out = ctx.attend(0, 0, 1, q)[0].double().cpu().numpy()
+            want, _ = st.attend(qn)
+            assert np.abs(out - want).max() <= 2e-2
+        assert ctx.span_count(0, 0, 0) == 1536 + steps
+        assert ctx.sync_status() == 0
+
+
 def test_span_table_overflow_is_reported(gpu_device):
     w = CONFIGS["cfg1"]
     K, V, Q, _ = planted_stream(w, 1, device=str(gpu_device), context=1024)
