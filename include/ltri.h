@@ -147,6 +147,15 @@ int32_t ltri_retrieve(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t s
                       const void* q, int32_t n_q, int32_t* sel_ids, int32_t* sel_cnt);
 int32_t ltri_sel_capacity(const ltri_ctx* ctx);
 
+/* Persistent selection (Sec. 3.5, Persistent Mechanism): step 2 without scoring. The span ids
+ * selected by the most recent ltri_retrieve / ltri_force_selection of each (sequence, KV head)
+ * are kept, and the context set of the last appended chunk is rebuilt from them: initial
+ * tokens, the kept spans' parts inside the evicted region as it is now, the window. Meant for
+ * decoding with the evidence found by the last prefill chunk. No device arguments; work is
+ * enqueued on the context's stream. ESTATE if a sequence has no chunk or never had a
+ * selection since its last reset. */
+int32_t ltri_retrieve_persistent(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count);
+
 /* Replace the selection of one KV head by ids_host[0..n) (stored span ids, any order,
  * ineligible ones contribute no tokens). Test seam and "mandatory injection". */
 int32_t ltri_force_selection(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,

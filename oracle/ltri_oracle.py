@@ -389,6 +389,12 @@ class OracleStream:
     def force_selection(self, h: int, ids: Sequence[int]) -> None:
         self.sel[h] = np.asarray(sorted(int(i) for i in ids), np.int64)
 
+    def retrieve_persistent(self) -> List[np.ndarray]:
+        """Sec. 3.5, Persistent Mechanism: no scoring; the spans selected earlier (for the last
+        prefill chunk) stay selected for the chunk appended last. The context set follows from
+        them and from where the window is now (context_tokens)."""
+        return [s.copy() for s in self.sel]
+
     # -- step 3 -------------------------------------------------------------
     def context_tokens(self, h: int) -> np.ndarray:
         """Token ids of initial | retrieved (clipped) | window for the last chunk, ascending."""

@@ -22,7 +22,8 @@ MAP_SOFTMAX, MAP_LOGIT = 0, 1
 EXPORTED_SYMBOLS = [
     "ltri_workspace_bytes", "ltri_create", "ltri_create_dry", "ltri_destroy", "ltri_reset",
     "ltri_set_stream", "ltri_set_attend_stages",
-    "ltri_append_chunk", "ltri_append_chunk_with_spans", "ltri_retrieve", "ltri_sel_capacity",
+    "ltri_append_chunk", "ltri_append_chunk_with_spans", "ltri_retrieve", "ltri_retrieve_persistent",
+    "ltri_sel_capacity",
     "ltri_force_selection", "ltri_attend", "ltri_gather_pack", "ltri_list_capacity",
     "ltri_sync_status", "ltri_token_count", "ltri_span_count", "ltri_get_spans",
     "ltri_get_rep_keys", "ltri_get_selection", "ltri_get_token_list", "ltri_strerror",
@@ -74,6 +75,7 @@ def load_library() -> C.CDLL:
         "ltri_append_chunk_with_spans": [vp, i32, i32, vp, vp, i32, pi32, pi32],
         "ltri_retrieve": [vp, i32, i32, i32, vp, i32, vp, vp],
         "ltri_sel_capacity": [vp],
+        "ltri_retrieve_persistent": [vp, i32, i32, i32],
         "ltri_force_selection": [vp, i32, i32, i32, pi32, i32],
         "ltri_attend": [vp, i32, i32, i32, vp, i32, vp, vp],
         "ltri_gather_pack": [vp, i32, i32, vp, vp, vp],
@@ -211,6 +213,9 @@ class LtriContext:
         n_q = q.shape[-3]
         self._check(self.lib.ltri_retrieve(self.handle, layer, seq_begin, seq_count, q.data_ptr(), n_q,
                                            _ptr(sel_ids), _ptr(sel_cnt)), None)
+
+    def retrieve_persistent(self, layer: int, seq_begin: int, seq_count: int) -> None:
+        self._check(self.lib.ltri_retrieve_persistent(self.handle, layer, seq_begin, seq_count), None)
 
     def force_selection(self, layer: int, seq: int, kv_head: int, ids) -> None:
         arr = np.asarray(list(ids), np.int32)

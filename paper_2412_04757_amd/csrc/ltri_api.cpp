@@ -27,6 +27,7 @@ struct ltri_ctx {
   std::vector<int> last_len;             // length of the chunk appended last (0 = none)
   std::vector<long long> span_bound;     // upper bound on the spans stored per KV head
   std::vector<uint32_t> have_sel;        // bit h set: KV head h has a selection for the last chunk
+  std::vector<uint32_t> ever_sel;        // bit h set: KV head h has had a selection since the last reset
   std::string err;
 };
 
@@ -179,6 +180,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->last_len.assign(n, 0);
   c->span_bound.assign(n, 0);
   c->have_sel.assign(n, 0u);
+  c->ever_sel.assign(n, 0u);
   if (!dry) {
     const hipError_t e = launch_fill_zero(c->state, SL.total, c->stream);
     if (e != hipSuccess) { delete c; return LTRI_EHIP; }
@@ -243,7 +245,7 @@ int32_t ltri_reset(ltri_ctx* c, int32_t seq) {
   if (seq < 0 || seq >= c->D.n_seqs) return fail(c, LTRI_EINVAL, "sequence %d out of range", seq);
   for (int l = 0; l < c->D.n_layers; ++l) {
     const size_t i = ls_index(c, l, seq);
-    c->n_tokens[i] = 0; c->last_len[i] = 0; c->span_bound[i] = 0; c->have_sel[i] = 0;
+    c->n_tokens[i] = 0; c->last_len[i] = 0; c->span_bound[i] = 0; c->have_sel[i] = 0; c->ever_sel[i] = 0;
     if (!c->dry) {
       const size_t off = c->SL.meta + ((size_t)(l * c->D.n_seqs + seq) * c->D.Hkv) * META_WORDS * 4;
       // META_WORDS * 4 = 32 bytes per slot: the slots of one (layer, seq) are contiguous
@@ -389,6 +391,32 @@ int32_t ltri_retrieve(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq
                                      sel_cnt, c->stream), "retrieve");
     if (r != LTRI_OK) return r;
   }
+  for (int s = 0; s < seq_count; ++s) {
+    c->have_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
+    c->ever_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
+  }
+  return LTRI_OK;
+}
+
+int32_t ltri_retrieve_persistent(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count) {
+  int32_t r = check_range(c, layer, seq_begin, seq_count);
+  if (r != LTRI_OK) return r;
+  BatchPos bp;
+  memset(&bp, 0, sizeof bp);
+  const uint32_t need = c->D.Hkv >= 32 ? 0xFFFFFFFFu : ((1u << c->D.Hkv) - 1u);
+  for (int s = 0; s < seq_count; ++s) {
+    const size_t i = ls_index(c, layer, seq_begin + s);
+    if (c->last_len[i] == 0) return fail(c, LTRI_ESTATE, "sequence %d: no chunk appended yet", seq_begin + s);
+    if ((c->ever_sel[i] & need) != need)
+      return fail(c, LTRI_ESTATE, "sequence %d: no earlier selection to keep (call ltri_retrieve once first)",
+                  seq_begin + s);
+    bp.seq[s] = seq_begin + s;
+    bp.c0[s] = (int32_t)(c->n_tokens[i] - c->last_len[i]);
+  }
+  if (!c->dry) {
+    r = check_hip(c, launch_persist_list(c->D, c->ds, layer, bp, seq_count, c->stream), "persistent selection");
+    if (r != LTRI_OK) return r;
+  }
   for (int s = 0; s < seq_count; ++s) c->have_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
   return LTRI_OK;
 }
@@ -421,6 +449,7 @@ int32_t ltri_force_selection(ltri_ctx* c, int32_t layer, int32_t seq, int32_t kv
     if (r != LTRI_OK) return r;
   }
   c->have_sel[i] |= 1u << (kv_head & 31);
+  c->ever_sel[i] |= 1u << (kv_head & 31);
   return LTRI_OK;
 }
 

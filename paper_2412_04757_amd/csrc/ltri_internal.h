@@ -106,6 +106,8 @@ hipError_t launch_rep_keys(const Dims& D, const DevState& st, const void* k_aren
 hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,
                            const void* q, int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
                            int32_t* sel_ids_out, int32_t* sel_cnt_out, hipStream_t s);
+hipError_t launch_persist_list(const Dims& D, const DevState& st, int layer, const BatchPos& bp, int seq_count,
+                               hipStream_t s);
 hipError_t launch_force_list(const Dims& D, const DevState& st, int layer, int seq, int kv_head,
                              int n_ids, hipStream_t s);
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,

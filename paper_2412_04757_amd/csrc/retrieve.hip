@@ -5,6 +5,7 @@
 //
 // Scores are accumulated in fp64: products of bf16 (or fp32) values are exact in fp64, so the
 // order of the selection does not depend on the summation order of any implementation.
+#include <cstring>
 #include <type_traits>
 #include "device_common.h"
 #include "span_mean.h"
@@ -631,6 +632,42 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
   if (gr < 1) gr = 1;
   select_rank_kernel<<<dim3(gr, P), 256, 0, s>>>(a);
   select_emit_kernel<<<P, 1024, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+// ---- persistent selection (Sec. 3.5, Persistent Mechanism): the ids selected earlier stay, the
+//      token list is rebuilt for the slot's current chunk (the window has moved on) ----
+__global__ __launch_bounds__(1024) void persist_list_kernel(RetArgs a) {
+  __shared__ uint32_t selmask[SEL_MAX_SPANS / 32];
+  const Dims& D = a.D;
+  const int p = blockIdx.x, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int n = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
+  const int cnt = min(meta[META_SEL_CNT], D.sel_cap);
+  const int tid = threadIdx.x;
+  for (int w = tid; w < (n + 31) / 32; w += blockDim.x) selmask[w] = 0u;
+  __syncthreads();
+  const int32_t* ids = a.st.sel_ids + (size_t)slot * D.sel_cap;
+  for (int k = tid; k < cnt; k += blockDim.x) {
+    const int i = ids[k];
+    if (i >= 0 && i < n) {
+      int lo, hi;
+      clip_span(D, c0, a.st.span_start[(size_t)slot * D.max_spans + i],
+                a.st.span_len[(size_t)slot * D.max_spans + i], lo, hi);
+      if (hi > lo) atomicOr(&selmask[i >> 5], 1u << (i & 31));
+    }
+  }
+  __syncthreads();
+  emit_selection(D, a.st, slot, selmask, n, nullptr, nullptr);
+}
+
+hipError_t launch_persist_list(const Dims& D, const DevState& st, int layer, const BatchPos& bp, int seq_count,
+                               hipStream_t s) {
+  RetArgs a;
+  memset(&a, 0, sizeof a);
+  a.D = D; a.st = st; a.layer = layer; a.seq_count = seq_count; a.bp = bp;
+  persist_list_kernel<<<seq_count * D.Hkv, 1024, 0, s>>>(a);
   return hipGetLastError();
 }
 

@@ -86,11 +86,17 @@ def test_call_order_and_limits_in_dry_mode():
     with pytest.raises(LtriError) as e:
         ctx.append_chunk(0, 0, 2, 16)
     assert e.value.status == -1                      # sequence range
+    with pytest.raises(LtriError) as e:
+        ctx.retrieve_persistent(0, 0, 1)
+    assert e.value.status == -2                      # nothing appended
     ctx.append_chunk(0, 0, 1, 256)
     assert ctx.token_count(0, 0) == 256
     with pytest.raises(LtriError) as e:
         ctx.attend(0, 0, 1, _FakeQ(256))
     assert e.value.status == -2                      # attend before retrieve
+    with pytest.raises(LtriError) as e:
+        ctx.retrieve_persistent(0, 0, 1)
+    assert e.value.status == -2                      # no earlier selection to keep
     with pytest.raises(LtriError) as e:
         ctx.retrieve(0, 0, 1, _FakeQ(128))
     assert e.value.status == -2                      # n_q differs from the appended chunk
@@ -103,6 +109,8 @@ def test_call_order_and_limits_in_dry_mode():
     ctx.force_selection(0, 0, 0, [3, 1, 1])
     ctx.attend(0, 0, 1, _FakeQ(256))                 # one KV head: forced selection is enough
     ctx.append_chunk(0, 0, 1, 256)
+    ctx.retrieve_persistent(0, 0, 1)                 # the earlier selection is kept for the new chunk
+    ctx.attend(0, 0, 1, _FakeQ(256))
     with pytest.raises(LtriError) as e:
         ctx.append_chunk(0, 0, 1, 256)               # 768 + 256 > 1000
     assert e.value.status == -3 and "max_tokens" in str(e.value)

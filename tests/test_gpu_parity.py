@@ -209,6 +209,43 @@ def test_one_token_step_edges(gpu_device):
         assert ctx.sync_status() == 0
 
 
+def test_persistent_selection_decode(gpu_device):
+    """Decoding with the selection of the last prefill chunk kept (persistent mechanism): ids stay,
+    the token list follows the window, outputs match the oracle; a fresh retrieve afterwards still works."""
+    w = Workload("mini-persist", 8, 2, 128, "bf16", 1024 + 64, 256, 4, 100, 0, 300, "uniform", 16, 64)
+    T0, L, steps = 1024, 256, 40
+    K, V, Q, _ = planted_stream(w, 17, device=str(gpu_device), context=T0 + steps)
+    ctx, st = make_pair(w, K, V, gpu_device, max_tokens=T0 + steps)
+    for c0 in range(0, T0, L):
+        ctx.append_chunk(0, 0, 1, L)
+        st.append_chunk(L)
+    q = Q[T0 - L:T0].contiguous()
+    ctx.retrieve(0, 0, 1, q)
+    kept = st.retrieve(q.double().cpu().numpy())
+    for h in range(w.n_kv_heads):
+        assert spans_equal(ctx, st, h)
+        assert list(ctx.get_selection(0, 0, h)[0]) == list(kept[h]) and len(kept[h]) > 0
+    for k in range(steps):
+        pos = T0 + k
+        q = Q[pos:pos + 1].contiguous()
+        qn = q.double().cpu().numpy()
+        ctx.append_chunk(0, 0, 1, 1)
+        st.append_chunk(1)
+        ctx.retrieve_persistent(0, 0, 1)
+        st.retrieve_persistent()
+        for h in range(w.n_kv_heads):
+            assert list(ctx.get_selection(0, 0, h)[0]) == list(kept[h])
+            assert list(ctx.get_token_list(0, 0, h)) == list(st.context_tokens(h)), f"step {k}, head {h}"
+        out = ctx.attend(0, 0, 1, q)[0].double().cpu().numpy()
+        want, _ = st.attend(qn)
+        assert np.abs(out - want).max() <= 2e-2
+    ctx.retrieve(0, 0, 1, q)                              # scoring again replaces the kept selection
+    sel = st.retrieve(qn)
+    for h in range(w.n_kv_heads):
+        assert list(ctx.get_selection(0, 0, h)[0]) == list(sel[h])
+    assert ctx.sync_status() == 0
+
+
 def test_span_table_overflow_is_reported(gpu_device):
     w = CONFIGS["cfg1"]
     K, V, Q, _ = planted_stream(w, 1, device=str(gpu_device), context=1024)

@@ -388,6 +388,50 @@ def test_decode_is_a_chunk_of_one():
         np.testing.assert_allclose(Oo[0, g], p @ Vn[0][keys], atol=1e-12)
 
 
+def test_persistent_selection_is_the_kept_spans_under_a_moving_window():
+    """Sec. 3.5 (Persistent Mechanism): during decoding the spans selected for the last prefill
+    chunk stay. The context set is then fixed by set membership, written out here token by token;
+    with every stored span selected it misses exactly the tokens that sat in the window at prefill
+    time and have left it since."""
+    w = CONFIGS["cfg1"]
+    T0, steps = 1024, 150
+    K, V, Q, _ = planted_stream(w, 5, context=T0 + steps)
+    Kn, Vn, Qn = (t.to(torch.float64).numpy() for t in (K, V, Q))
+    for k_max in (3, 0):
+        cfg = O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, "f32", 4, 128, k_max=k_max,
+                             theta=theta_default(w.head_dim))
+        st = O.OracleStream(cfg, Kn, Vn)
+        for c0 in range(0, T0, 256):
+            st.append_chunk(256)
+        kept = st.retrieve(Qn[T0 - 256:T0])[0].copy()
+        ws0 = T0 - 256 - 128                                        # window start of the last prefill chunk
+        for k in range(steps):
+            st.append_chunk(1)
+            assert [list(x) for x in st.retrieve_persistent()] == [list(kept)]
+            c0 = T0 + k
+            ws = c0 - 128
+            member = np.zeros(c0, bool)
+            member[:4] = True
+            member[ws:] = True
+            for i in kept:
+                a, b = st.starts[0][i], st.starts[0][i] + st.lens[0][i]
+                member[max(a, 4):min(b, ws)] = True
+            assert list(st.context_tokens(0)) == list(np.flatnonzero(member))
+            if k_max == 0:
+                # all spans that reached into the evicted region at prefill time were kept
+                lost = [t for t in range(c0) if not member[t]]
+                assert all(ws0 <= t < ws for t in lost)
+                first_kept_end = max(st.starts[0][i] + st.lens[0][i] for i in kept)
+                assert lost == list(range(max(first_kept_end, ws0), ws))
+        # the output is plain attention over that set plus the token itself
+        q = Qn[T0 + steps - 1:T0 + steps]
+        Oo, _ = st.attend(q)
+        keys = list(st.context_tokens(0)) + [T0 + steps - 1]
+        z = (Kn[0][keys] @ q[0, 1]) / math.sqrt(w.head_dim)
+        pr = np.exp(z - z.max()); pr /= pr.sum()
+        np.testing.assert_allclose(Oo[0, 1], pr @ Vn[0][keys], atol=1e-12)
+
+
 def test_stability_audit_flags_a_planted_near_tie():
     """The audit must reject a chunk whose decision hangs on a near-tie."""
     L = 8
