@@ -31,8 +31,14 @@ Pinned by tests/test_oracle_pins.py (brute-force triple sums, ideal-map and
 planted-key boundary recovery, NMS brute force, top-k vs full sort, the
 select-everything == full causal attention invariant, brute-force softmax
 attention, LSE-merge identity, decode == one-row prefill).
+Dynamic index vectors (Sec. 3.3.2): votes, area ratios, Eq. 7 and the index
+tokens are pinned by closed forms on constant keys (harmonic numbers), by the
+row-sum identities of a softmax map, by Eq. 7's special values and by brute
+force for the top-count choice and for Eq. 8's double sum.
 Parity unpinned: the SOFTMAX map kind on planted keys has no ground truth for
 which spans are "right"; it is pinned only through Eq. 4/5 and the NMS pins.
+Likewise nothing outside this file says which tokens are the "right" index
+tokens of a span: beyond the pins above that part is parity unpinned.
 """
 from __future__ import annotations
 
@@ -44,6 +50,8 @@ import numpy as np
 
 MAP_SOFTMAX = 0
 MAP_LOGIT = 1
+REP_MEAN = 0
+REP_DYNAMIC = 1
 
 
 # ----------------------------------------------------------------------------
@@ -223,6 +231,93 @@ def span_means(X: np.ndarray, bounds: np.ndarray, dtype: str) -> np.ndarray:
     return round_to_dtype(out, dtype)
 
 
+# ----------------------------------------------------------------------------
+# dynamic span index vectors (Sec. 3.3.2): votes (Eq. 6), area ratios, Eq. 7
+# ----------------------------------------------------------------------------
+RATIO_ROW, RATIO_COL, RATIO_ROWCOL = 0, 1, 2
+
+
+def token_votes(A: np.ndarray) -> np.ndarray:
+    """Eq. 6: v_x = sum over heads and rows of A[., i, x]; A is the head-summed softmax map
+    of the chunk (the rows of the chunk play the role of the window)."""
+    return np.asarray(A, np.float64).sum(axis=0)
+
+
+def span_area_ratio(A: np.ndarray, a: int, b: int, mode: int) -> float:
+    """r_a of the span [a, b) (Sec. 3.3.2, the figure with Span1..Span4): area of the span's own
+    triangle over that area plus its neighbours' -- the cells of the same rows left of the span
+    (row), of the same columns below it (column), or both."""
+    A = np.asarray(A, np.float64)
+    tri = 0.0
+    for i in range(a, b):
+        tri += A[i, a:i + 1].sum()
+    row = A[a:b, :a].sum()
+    col = A[b:, a:b].sum()
+    if mode == RATIO_ROW:
+        den = tri + row
+    elif mode == RATIO_COL:
+        den = tri + col
+    elif mode == RATIO_ROWCOL:
+        den = tri + row + col
+    else:
+        raise ValueError(mode)
+    return tri / den
+
+
+def index_vector_count(length: int, r_a: float, lam: float, n_min: int, n_max: int) -> int:
+    """Eq. 7 and the sentence after it: r_v = 1 / e^(lam (1 - r_a)); the span keeps
+    round(length * r_v) index vectors (ties to even), clamped to [n_min, n_max] and to the
+    span itself (at least one, at most its length)."""
+    r_v = 1.0 / math.exp(lam * (1.0 - r_a))
+    n = int(np.rint(length * r_v))
+    n = max(n, n_min)
+    if n_max > 0:
+        n = min(n, n_max)
+    return max(1, min(n, length))
+
+
+def span_index_tokens(v: np.ndarray, a: int, b: int, count: int) -> np.ndarray:
+    """The `count` tokens of [a, b) with the most votes (ties: the earlier token), ascending."""
+    order = sorted(range(a, b), key=lambda t: (-v[t], t))
+    return np.asarray(sorted(order[:count]), np.int64)
+
+
+def dynamic_index_tokens(A: np.ndarray, bounds: np.ndarray, lam: float, n_min: int, n_max: int,
+                         mode: int) -> List[np.ndarray]:
+    """Index tokens (chunk-local, ascending) of every span of a chunk."""
+    v = token_votes(A)
+    out = []
+    for s in range(len(bounds) - 1):
+        a, b = int(bounds[s]), int(bounds[s + 1])
+        n = index_vector_count(b - a, span_area_ratio(A, a, b, mode), lam, n_min, n_max)
+        out.append(span_index_tokens(v, a, b, n))
+    return out
+
+
+def index_vector_sums(X: np.ndarray, tokens: Sequence[np.ndarray], dtype: str) -> np.ndarray:
+    """One stored vector per span: the sum of the rows of X at its index tokens. Eq. 8 sums the
+    dot products of all pairs of index vectors of two spans, which is the dot product of these
+    sums. Rounded once to dtype."""
+    X = np.asarray(X, np.float64)
+    out = np.empty((len(tokens), X.shape[1]), np.float64)
+    for s, t in enumerate(tokens):
+        out[s] = X[t].sum(axis=0)
+    return round_to_dtype(out, dtype)
+
+
+def dynamic_index_is_stable(A: np.ndarray, bounds: np.ndarray, lam: float, n_min: int, n_max: int,
+                            mode: int, rel: float = 2.0 ** -18, draws: int = 2, seed: int = 0) -> bool:
+    """Audit: are the index tokens the same when every map cell moves by a relative `rel`?"""
+    base = dynamic_index_tokens(A, bounds, lam, n_min, n_max, mode)
+    rng = np.random.default_rng(seed)
+    for _ in range(draws):
+        p = rng.uniform(-rel, rel, size=A.shape)
+        t = dynamic_index_tokens(A * (1.0 + p), bounds, lam, n_min, n_max, mode)
+        if any(len(x) != len(y) or np.any(x != y) for x, y in zip(base, t)):
+            return False
+    return True
+
+
 def span_scores(Qrep: np.ndarray, Krep: np.ndarray) -> np.ndarray:
     """score_i = max_j Qrep_j . Krep_i  (Eq. 8 with one vector per span, max over the
     query spans as in Eq. 9)."""
@@ -306,6 +401,11 @@ class OracleConfig:
     theta: float = 0.0
     phi: float = 0.0
     max_spans_per_chunk: int = 0
+    rep_mode: int = 0          # REP_MEAN | REP_DYNAMIC
+    lam: float = 3.0           # lambda of Eq. 7
+    n_min: int = 1             # fewest / most index vectors per span (0 = no upper limit)
+    n_max: int = 0
+    ratio_mode: int = RATIO_ROW
 
     @property
     def group(self) -> int:
@@ -329,6 +429,7 @@ class OracleStream:
         self.krep: List[List[np.ndarray]] = [[] for _ in range(H)]
         self.last_chunk: Tuple[int, int] = (0, 0)                  # (c0, L)
         self.last_bounds: List[np.ndarray] = [np.zeros(0, np.int64) for _ in range(H)]
+        self.last_index_tokens: List[List[np.ndarray]] = [[] for _ in range(H)]   # REP_DYNAMIC only
         self.sel: List[np.ndarray] = [np.zeros(0, np.int64) for _ in range(H)]
         self.sel_scores: List[np.ndarray] = [np.zeros(0) for _ in range(H)]
 
@@ -351,7 +452,16 @@ class OracleStream:
                     Qg = np.asarray(q_seg, np.float64)[:, h * c.group:(h + 1) * c.group, :]
                     Qg = np.transpose(Qg, (1, 0, 2))
                 b = segment_chunk(Kc, Qg, c.seg_map, c.theta, c.phi, c.max_spans_per_chunk)
-            reps = span_means(Kc, b, c.dtype)
+            if c.rep_mode == REP_DYNAMIC:
+                Qg = None
+                if q_seg is not None:
+                    Qg = np.transpose(np.asarray(q_seg, np.float64)[:, h * c.group:(h + 1) * c.group, :], (1, 0, 2))
+                A, _ = chunk_map(Kc, Qg, MAP_SOFTMAX)            # votes and areas come from the softmax map
+                toks = dynamic_index_tokens(A, b, c.lam, c.n_min, c.n_max, c.ratio_mode)
+                self.last_index_tokens[h] = toks
+                reps = index_vector_sums(Kc, toks, c.dtype)
+            else:
+                reps = span_means(Kc, b, c.dtype)
             for s in range(len(b) - 1):
                 self.starts[h].append(c0 + int(b[s]))
                 self.lens[h].append(int(b[s + 1] - b[s]))
@@ -374,7 +484,10 @@ class OracleStream:
         out = []
         for h in range(c.n_kv_heads):
             qsum = q[:, h * c.group:(h + 1) * c.group, :].sum(axis=1)        # sum over the group's heads
-            Qrep = span_means(qsum, self.last_bounds[h], c.dtype)
+            if c.rep_mode == REP_DYNAMIC:
+                Qrep = index_vector_sums(qsum, self.last_index_tokens[h], c.dtype)
+            else:
+                Qrep = span_means(qsum, self.last_bounds[h], c.dtype)
             starts = np.asarray(self.starts[h], np.int64)
             lens = np.asarray(self.lens[h], np.int64)
             a, b = clipped_ranges(starts, lens, min(c.n_sink, c0), ws)

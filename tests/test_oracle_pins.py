@@ -432,6 +432,133 @@ def test_persistent_selection_is_the_kept_spans_under_a_moving_window():
         np.testing.assert_allclose(Oo[0, 1], pr @ Vn[0][keys], atol=1e-12)
 
 
+def test_dynamic_index_vectors_closed_forms_and_identities():
+    """Sec. 3.3.2. Constant keys make every causal softmax row uniform, A[i][j] = 1/(i+1), so votes
+    and areas are harmonic sums; any softmax map has rows summing to one per head, which fixes
+    triangle + row neighbours and triangle + column neighbours."""
+    L = 96
+    A, n_h = O.chunk_map(np.ones((L, 8)), None, O.MAP_SOFTMAX)
+    Hn = np.concatenate([[0.0], np.cumsum(1.0 / np.arange(1, L + 1))])         # H_0 .. H_L
+    np.testing.assert_allclose(O.token_votes(A), Hn[L] - Hn[:L], atol=1e-13)   # v_x = sum_{i >= x} 1/(i+1)
+    for a, b in ((0, 1), (0, 96), (10, 20), (37, 96), (95, 96)):
+        tri = sum((i - a + 1) / (i + 1) for i in range(a, b))
+        row = sum(a / (i + 1) for i in range(a, b))
+        col = (b - a) * (Hn[L] - Hn[b])
+        assert abs(O.span_area_ratio(A, a, b, O.RATIO_ROW) - tri / (tri + row)) < 1e-13
+        assert abs(O.span_area_ratio(A, a, b, O.RATIO_COL) - tri / (tri + col)) < 1e-13
+        assert abs(O.span_area_ratio(A, a, b, O.RATIO_ROWCOL) - tri / (tri + row + col)) < 1e-13
+        assert abs(tri + row - (b - a)) < 1e-12
+    rng = np.random.default_rng(0)
+    K = rng.standard_normal((80, 16))
+    Q = rng.standard_normal((3, 80, 16))
+    A, n_h = O.chunk_map(K, Q, O.MAP_SOFTMAX)
+    v = O.token_votes(A)
+    assert n_h == 3 and abs(v.sum() - 3 * 80) < 1e-10
+    for a, b in ((0, 80), (0, 17), (17, 60), (60, 80)):
+        r_row, r_col = O.span_area_ratio(A, a, b, O.RATIO_ROW), O.span_area_ratio(A, a, b, O.RATIO_COL)
+        tri = sum(A[i, a:i + 1].sum() for i in range(a, b))
+        assert abs(tri / r_row - 3 * (b - a)) < 1e-10              # triangle + row neighbours = rows of the span
+        assert abs(tri / r_col - v[a:b].sum()) < 1e-10             # triangle + column neighbours = its votes
+        r_rc = O.span_area_ratio(A, a, b, O.RATIO_ROWCOL)
+        assert abs(1 / r_rc - (1 / r_row + 1 / r_col - 1)) < 1e-10
+    for mode in (O.RATIO_ROW, O.RATIO_COL, O.RATIO_ROWCOL):        # a chunk that is one span has no neighbours
+        assert abs(O.span_area_ratio(A, 0, 80, mode) - 1.0) < 1e-12
+
+
+def test_index_vector_count_is_eq7():
+    assert O.index_vector_count(50, 0.3, 0.0, 1, 0) == 50          # lambda = 0: r_v = 1
+    assert O.index_vector_count(50, 1.0, 20.0, 1, 0) == 50         # r_a = 1: r_v = 1
+    assert O.index_vector_count(100, 0.5, 3.0, 1, 0) == 22         # 100 e^-1.5 = 22.3
+    assert O.index_vector_count(100, 0.0, 3.0, 1, 0) == 5          # 100 e^-3 = 4.98
+    lam = math.log(4.0)                                            # r_a = 0: r_v = 1/4 exactly
+    assert O.index_vector_count(10, 0.0, lam, 1, 0) == 2           # 2.5 -> 2 (ties to even)
+    assert O.index_vector_count(14, 0.0, lam, 1, 0) == 4           # 3.5 -> 4
+    assert O.index_vector_count(100, 0.0, 3.0, 8, 0) == 8          # lower limit
+    assert O.index_vector_count(100, 0.9, 3.0, 1, 16) == 16        # upper limit
+    assert O.index_vector_count(3, 0.0, 20.0, 8, 0) == 3           # never more than the span
+    assert O.index_vector_count(40, 0.0, 20.0, 0, 0) == 1          # never fewer than one
+    prev = 0
+    for r in np.linspace(0, 1, 21):                                # more index vectors for higher ratios
+        n = O.index_vector_count(200, float(r), 3.0, 1, 0)
+        assert n >= prev
+        prev = n
+    assert [O.index_vector_count(200, 0.5, l, 1, 0) for l in (1, 3, 9)] == [121, 45, 2]
+
+
+def test_index_tokens_and_eq8_over_index_vectors():
+    rng = np.random.default_rng(4)
+    v = rng.integers(0, 6, size=40).astype(np.float64)             # many ties
+    for a, b, n in ((0, 40, 7), (5, 9, 4), (12, 30, 1), (12, 30, 18)):
+        left = list(range(a, b))
+        want = []
+        for _ in range(n):                                          # pick the best remaining token, earliest on ties
+            t = max(left, key=lambda u: (v[u], -u))
+            want.append(t)
+            left.remove(t)
+        assert list(O.span_index_tokens(v, a, b, n)) == sorted(want)
+    # Eq. 8 written out over all pairs of index vectors equals the dot of the stored sums
+    K = rng.standard_normal((40, 6))
+    Qs = rng.standard_normal((40, 6))
+    tk = [np.array([1, 4, 5]), np.array([20, 21])]
+    tq = [np.array([0, 2]), np.array([30, 31, 39])]
+    Ks, Qr = O.index_vector_sums(K, tk, "f64"), O.index_vector_sums(Qs, tq, "f64")
+    for i in range(2):
+        for j in range(2):
+            sim = sum(float(Qs[m] @ K[n]) for m in tq[j] for n in tk[i])
+            assert abs(sim - float(Qr[j] @ Ks[i])) < 1e-12
+    # every token an index token: the stored vector is length x mean
+    b = np.array([0, 7, 40])
+    np.testing.assert_allclose(O.index_vector_sums(K, [np.arange(0, 7), np.arange(7, 40)], "f64"),
+                               O.span_means(K, b, "f64") * np.array([[7.0], [33.0]]), atol=1e-12)
+
+
+def test_dynamic_index_on_planted_keys_and_in_the_stream():
+    """Spans whose keys share nothing with their neighbours keep (nearly) all their mass inside
+    their triangle: r_a close to 1, every token kept; a span that repeats its left neighbour's
+    mean gives about half of its rows' mass away. In the stream, index-vector sums take the place
+    of the means on both sides of Eq. 8."""
+    rng = np.random.default_rng(2)
+    d = 64
+    mu = rng.standard_normal((3, d)) * 3.0
+    mu[2] = mu[1]                                                   # span 2 repeats span 1
+    b = np.array([0, 40, 70, 100])
+    K = np.concatenate([mu[s] + 0.1 * rng.standard_normal((b[s + 1] - b[s], d)) for s in range(3)])
+    A, _ = O.chunk_map(K, None, O.MAP_SOFTMAX)
+    r = [O.span_area_ratio(A, b[s], b[s + 1], O.RATIO_ROW) for s in range(3)]
+    assert r[0] == 1.0 and r[1] > 0.999 and 0.3 < r[2] < 0.7
+    toks = O.dynamic_index_tokens(A, b, 3.0, 1, 0, O.RATIO_ROW)
+    assert len(toks[0]) == 40 and len(toks[1]) == 30 and len(toks[2]) < 12
+    assert O.dynamic_index_is_stable(A, b, 3.0, 1, 0, O.RATIO_ROW)
+    # stream: with lambda = 0 every token is an index token; sums are length x mean on both sides
+    w = CONFIGS["cfg1"]
+    Kt, Vt, Qt, _ = planted_stream(w, 6, context=768)
+    Kn, Vn, Qn = (t.to(torch.float64).numpy() for t in (Kt, Vt, Qt))
+    kw = dict(k_max=3, theta=theta_default(w.head_dim))
+    st_m = O.OracleStream(O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, "f64", 4, 128, **kw), Kn, Vn)
+    st_d = O.OracleStream(O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, "f64", 4, 128,
+                                         rep_mode=O.REP_DYNAMIC, lam=0.0, **kw), Kn, Vn)
+    for c0 in range(0, 768, 256):
+        st_m.append_chunk(256)
+        st_d.append_chunk(256)
+    assert st_m.starts == st_d.starts
+    q = Qn[512:768]
+    st_m.retrieve(q)
+    st_d.retrieve(q)
+    lens = np.asarray(st_m.lens[0], np.float64)
+    np.testing.assert_allclose(np.stack(st_d.krep[0]), np.stack(st_m.krep[0]) * lens[:, None], atol=1e-10)
+    qlen = np.diff(st_m.last_bounds[0]).astype(np.float64)
+    # sim of sums = (query span length) x (key span length) x sim of means, before the max over query spans
+    Qm = O.span_means(q[:, :4].sum(axis=1), st_m.last_bounds[0], "f64")
+    want = ((Qm * qlen[:, None]) @ (np.stack(st_m.krep[0]) * lens[:, None]).T).max(axis=0)
+    np.testing.assert_allclose(st_d.sel_scores[0], want, rtol=1e-10, atol=1e-9)
+    # with lambda = 3 spans keep fewer tokens and the stored vectors change accordingly
+    st_3 = O.OracleStream(O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, "f32", 4, 128,
+                                         rep_mode=O.REP_DYNAMIC, lam=3.0, n_max=16, **kw), Kn, Vn)
+    st_3.append_chunk(256)
+    for tk, a, ln in zip(st_3.last_index_tokens[0], st_3.starts[0], st_3.lens[0]):
+        assert 1 <= len(tk) <= min(16, ln) and tk.min() >= a and tk.max() < a + ln and np.all(np.diff(tk) > 0)
+
+
 def test_stability_audit_flags_a_planted_near_tie():
     """The audit must reject a chunk whose decision hangs on a near-tie."""
     L = 8
