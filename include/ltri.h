@@ -60,6 +60,10 @@ extern "C" {
 
 /* representative vector of a span */
 #define LTRI_REP_MEAN    0   /* mean of the span's rows (Sec. 3.3.1, mean pooling)     */
+#define LTRI_REP_DYNAMIC 1   /* dynamic span index vectors (Sec. 3.3.2), see ltri_config */
+#define LTRI_RATIO_ROW    0  /* area ratio of a span against its row neighbours (the paper's default) */
+#define LTRI_RATIO_COL    1  /* ... against its column neighbours                        */
+#define LTRI_RATIO_ROWCOL 2  /* ... against both                                         */
 
 #define LTRI_MAX_BATCH   64  /* most sequences one call can take                        */
 
@@ -78,9 +82,19 @@ typedef struct {
   float   theta, phi;                       /* Eq. 5 threshold (absolute, per head and
                                                cell); NMS IoU threshold                   */
   int32_t max_spans_per_chunk;              /* cap on NMS keeps per chunk, 0 = none       */
-  int32_t rep_mode;                         /* LTRI_REP_MEAN                              */
+  int32_t rep_mode;                         /* LTRI_REP_MEAN | LTRI_REP_DYNAMIC           */
   int32_t max_spans;                        /* span capacity per (layer, seq, KV head);
                                                0 = max_tokens / 32 + 64                   */
+  /* LTRI_REP_DYNAMIC only (Sec. 3.3.2). Votes v_x (Eq. 6) are the column sums of the chunk's
+   * head-summed softmax map; r_a is the area of a span's triangle over that area plus its
+   * neighbours' (ratio_mode); the span keeps round(len / e^(lambda (1 - r_a))) index tokens
+   * (Eq. 7; ties to even), at least index_min, at most index_max (0 = no limit), between 1 and
+   * len: the tokens with the most votes, earlier ones first on ties. One vector per span is
+   * stored, the sum of the keys of its index tokens (Eq. 8 is bilinear); the query side of
+   * step 2 sums the group's query rows over the same tokens of the chunk. */
+  float   lambda;
+  int32_t index_min, index_max;
+  int32_t ratio_mode;                       /* LTRI_RATIO_*                               */
 } ltri_config;
 
 /* Sizes (bytes) of the two device buffers a context needs: `state` holds the index
@@ -146,6 +160,13 @@ int32_t ltri_append_chunk_with_spans(ltri_ctx* ctx, int32_t layer, int32_t seq,
 int32_t ltri_retrieve(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count,
                       const void* q, int32_t n_q, int32_t* sel_ids, int32_t* sel_cnt);
 int32_t ltri_sel_capacity(const ltri_ctx* ctx);
+
+/* LTRI_REP_DYNAMIC, introspection (synchronises the stream): the index tokens of the chunk
+ * appended last to (layer, seq, kv_head) as a bit mask, bit t of word t / 32 = token t of the
+ * chunk; mask_host holds cap_words words, at least (chunk length + 31) / 32. ESTATE in a dry
+ * context or when the context stores mean representatives. */
+int32_t ltri_get_index_tokens(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,
+                              uint32_t* mask_host, int32_t cap_words);
 
 /* Persistent selection (Sec. 3.5, Persistent Mechanism): step 2 without scoring. The span ids
  * selected by the most recent ltri_retrieve / ltri_force_selection of each (sequence, KV head)

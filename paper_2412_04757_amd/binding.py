@@ -18,6 +18,8 @@ _LIB: Optional[C.CDLL] = None
 
 LTRI_F32, LTRI_BF16 = 0, 1
 MAP_SOFTMAX, MAP_LOGIT = 0, 1
+REP_MEAN, REP_DYNAMIC = 0, 1
+RATIO_ROW, RATIO_COL, RATIO_ROWCOL = 0, 1, 2
 
 EXPORTED_SYMBOLS = [
     "ltri_workspace_bytes", "ltri_create", "ltri_create_dry", "ltri_destroy", "ltri_reset",
@@ -26,7 +28,7 @@ EXPORTED_SYMBOLS = [
     "ltri_sel_capacity",
     "ltri_force_selection", "ltri_attend", "ltri_gather_pack", "ltri_list_capacity",
     "ltri_sync_status", "ltri_token_count", "ltri_span_count", "ltri_get_spans",
-    "ltri_get_rep_keys", "ltri_get_selection", "ltri_get_token_list", "ltri_strerror",
+    "ltri_get_rep_keys", "ltri_get_selection", "ltri_get_token_list", "ltri_get_index_tokens", "ltri_strerror",
     "ltri_last_error", "ltri_version", "ltri_measure_mfma_peak", "ltri_measure_copy_peak",
 ]
 
@@ -45,6 +47,7 @@ class LtriConfig(C.Structure):
         ("window", C.c_int32), ("k_max", C.c_int32), ("budget_tokens", C.c_int64),
         ("seg_map", C.c_int32), ("theta", C.c_float), ("phi", C.c_float),
         ("max_spans_per_chunk", C.c_int32), ("rep_mode", C.c_int32), ("max_spans", C.c_int32),
+        ("lam", C.c_float), ("index_min", C.c_int32), ("index_max", C.c_int32), ("ratio_mode", C.c_int32),
     ]
 
 
@@ -87,6 +90,7 @@ def load_library() -> C.CDLL:
         "ltri_get_rep_keys": [vp, i32, i32, i32, vp, i32],
         "ltri_get_selection": [vp, i32, i32, i32, pi32, i32, pi32, C.POINTER(C.c_double)],
         "ltri_get_token_list": [vp, i32, i32, i32, pi32, i32, pi32],
+        "ltri_get_index_tokens": [vp, i32, i32, i32, C.POINTER(C.c_uint32), i32],
         "ltri_measure_mfma_peak": [vp, C.c_size_t, i32, vp, C.POINTER(C.c_double)],
         "ltri_measure_copy_peak": [vp, vp, C.c_size_t, vp, C.POINTER(C.c_double)],
     }
@@ -109,7 +113,9 @@ def config_from_workload(w, max_tokens: Optional[int] = None, theta: float = 0.0
                          n_seqs: Optional[int] = None, max_spans: int = 0,
                          max_spans_per_chunk: int = 0, window: Optional[int] = None,
                          n_sink: Optional[int] = None, k_max: Optional[int] = None,
-                         budget_tokens: Optional[int] = None, chunk_max: Optional[int] = None) -> LtriConfig:
+                         budget_tokens: Optional[int] = None, chunk_max: Optional[int] = None,
+                         rep_mode: int = REP_MEAN, lam: float = 3.0, index_min: int = 1, index_max: int = 0,
+                         ratio_mode: int = RATIO_ROW) -> LtriConfig:
     return LtriConfig(
         n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
         dtype=LTRI_F32 if w.dtype == "f32" else LTRI_BF16,
@@ -122,7 +128,8 @@ def config_from_workload(w, max_tokens: Optional[int] = None, theta: float = 0.0
         k_max=w.k_max if k_max is None else k_max,
         budget_tokens=w.budget_tokens if budget_tokens is None else budget_tokens,
         seg_map=seg_map, theta=theta, phi=phi, max_spans_per_chunk=max_spans_per_chunk,
-        rep_mode=0, max_spans=max_spans)
+        rep_mode=rep_mode, max_spans=max_spans, lam=lam, index_min=index_min, index_max=index_max,
+        ratio_mode=ratio_mode)
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
@@ -282,6 +289,14 @@ class LtriContext:
                                                  toks.ctypes.data_as(C.POINTER(C.c_int32)), self.list_cap,
                                                  C.byref(n)), None)
         return toks[:n.value]
+
+    def get_index_tokens(self, layer: int, seq: int, kv_head: int, chunk_len: int) -> np.ndarray:
+        """Chunk-local positions of the index tokens of the chunk appended last (dynamic index vectors)."""
+        words = np.zeros((chunk_len + 31) // 32, np.uint32)
+        self._check(self.lib.ltri_get_index_tokens(self.handle, layer, seq, kv_head,
+                                                   words.ctypes.data_as(C.POINTER(C.c_uint32)), len(words)), None)
+        bits = np.unpackbits(words.view(np.uint8), bitorder="little")[:chunk_len]
+        return np.flatnonzero(bits).astype(np.int64)
 
 
 def measure_mfma_peak(device, random_operands: bool = False) -> float:

@@ -59,7 +59,12 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   if (c.n_sink < 0 || c.window < 0 || c.k_max < 0 || c.budget_tokens < 0) return LTRI_EINVAL;
   if (c.seg_map != LTRI_MAP_SOFTMAX && c.seg_map != LTRI_MAP_LOGIT) return LTRI_EINVAL;
   if (!(c.phi >= 0.0f) || !(c.theta == c.theta)) return LTRI_EINVAL;
-  if (c.max_spans_per_chunk < 0 || c.rep_mode != LTRI_REP_MEAN || c.max_spans < 0) return LTRI_EINVAL;
+  if (c.max_spans_per_chunk < 0 || c.max_spans < 0) return LTRI_EINVAL;
+  if (c.rep_mode != LTRI_REP_MEAN && c.rep_mode != LTRI_REP_DYNAMIC) return LTRI_EINVAL;
+  if (c.rep_mode == LTRI_REP_DYNAMIC &&
+      (!(c.lambda >= 0.0f) || c.index_min < 0 || c.index_max < 0 || (c.index_max && c.index_max < c.index_min) ||
+       c.ratio_mode < LTRI_RATIO_ROW || c.ratio_mode > LTRI_RATIO_ROWCOL))
+    return LTRI_EINVAL;
   const int G = c.n_q_heads / c.n_kv_heads;
   if (c.dtype == LTRI_BF16 && !(G == 1 || G == 2 || G % 4 == 0)) return LTRI_EINVAL;
   D.Hq = c.n_q_heads; D.Hkv = c.n_kv_heads; D.G = G; D.d = c.head_dim; D.dtype = c.dtype;
@@ -67,6 +72,8 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   D.chunk_max = c.chunk_max; D.n_sink = c.n_sink; D.window = c.window; D.k_max = c.k_max;
   D.budget = c.budget_tokens; D.seg_map = c.seg_map; D.theta = c.theta; D.phi = c.phi;
   D.max_keep = c.max_spans_per_chunk;
+  D.rep_mode = c.rep_mode; D.lambda = (double)c.lambda; D.index_min = c.index_min; D.index_max = c.index_max;
+  D.ratio_mode = c.ratio_mode;
   if (c.max_spans > 65536) return LTRI_EINVAL;
   long long ms = c.max_spans ? c.max_spans : std::min<long long>(c.max_tokens / 32 + 64, 65536);
   if (ms > c.max_tokens) ms = c.max_tokens;
@@ -95,6 +102,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   SL.sel_ids = o;    o = align_up(o + n_slots * D.sel_cap * 4, 256);
   SL.tok_list = o;   o = align_up(o + n_slots * (size_t)D.list_cap * 4, 256);
   SL.err = o;        o = align_up(o + 16, 256);
+  SL.idx_mask = o;   o = align_up(o + n_slots * IDX_MASK_WORDS * 4, 256);
   SL.total = o;
 
   // scratch: segmentation temporaries for up to 4 sequences at a time
@@ -117,6 +125,8 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.bounds = o; o = align_up(o + (size_t)c.n_kv_heads * (c.chunk_max + 2) * 4, 256);
   CL.selflag = o; o = align_up(o + (size_t)c.n_seqs * c.n_kv_heads * D.max_spans, 256);
   CL.att_part = o; o = align_up(o + (size_t)c.n_seqs * c.n_q_heads * ATT_MAX_SPLITS * ATT_SPLIT_MAX_ROWS * (D.d + 2) * 4, 256);
+  CL.tokspan = o; o = align_up(o + (size_t)P * Lp * 4, 256);
+  CL.dyn = o;     o = align_up(o + (size_t)P * 3 * Lp * 8, 256);
   CL.total = o;
   CL.max_problems = P;
   return LTRI_OK;
@@ -169,12 +179,13 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   char* s = c->state;
   c->ds = DevState{(int32_t*)(s + SL.meta), (int32_t*)(s + SL.span_start), (int32_t*)(s + SL.span_len),
                    (void*)(s + SL.krep), (double*)(s + SL.scores), (int32_t*)(s + SL.sel_ids),
-                   (int32_t*)(s + SL.tok_list), (int32_t*)(s + SL.err)};
+                   (int32_t*)(s + SL.tok_list), (int32_t*)(s + SL.err), (uint32_t*)(s + SL.idx_mask)};
   char* t = c->scratch;
   c->dc = DevScratch{(double*)(t + CL.rowsum), (double*)(t + CL.csuf), (double*)(t + CL.tsum),
                      (double*)(t + CL.rcar), (double*)(t + CL.ccar), (double*)(t + CL.pscore),
                      (int32_t*)(t + CL.px), (uint64_t*)(t + CL.ckey), (uint32_t*)(t + CL.cxy), (double*)(t + CL.lse), (void*)(t + CL.qrep),
-                     (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds), (uint8_t*)(t + CL.selflag), (float*)(t + CL.att_part)};
+                     (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds), (uint8_t*)(t + CL.selflag), (float*)(t + CL.att_part),
+                     (int32_t*)(t + CL.tokspan), (double*)(t + CL.dyn)};
   const size_t n = (size_t)D.n_layers * D.n_seqs;
   c->n_tokens.assign(n, 0);
   c->last_len.assign(n, 0);
@@ -309,10 +320,17 @@ int32_t ltri_append_chunk(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t
         r = check_hip(c, launch_segment(c->D, c->ds, c->dc, c->k_arena, q_seg, layer, bp, off, cnt, n_new,
                                         c->stream), "segment");
         if (r != LTRI_OK) return r;
+        if (c->D.rep_mode == LTRI_REP_DYNAMIC) {
+          r = check_hip(c, launch_dynamic_reps(c->D, c->ds, c->dc, c->k_arena, q_seg, layer, bp, off, cnt, n_new,
+                                               c->D.seg_map == LTRI_MAP_SOFTMAX, c->stream), "index vectors");
+          if (r != LTRI_OK) return r;
+        }
       }
-      r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, seq_count, n_new, c->stream),
-                    "representative keys");
-      if (r != LTRI_OK) return r;
+      if (c->D.rep_mode == LTRI_REP_MEAN) {
+        r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, seq_count, n_new, c->stream),
+                      "representative keys");
+        if (r != LTRI_OK) return r;
+      }
     }
   }
   append_commit(c, layer, seq_begin, seq_count, n_new);
@@ -353,8 +371,12 @@ int32_t ltri_append_chunk_with_spans(ltri_ctx* c, int32_t layer, int32_t seq, co
     r = check_hip(c, launch_append_bounds(c->D, c->ds, c->dc, layer, seq, bp.c0[0], n_new, c->stream),
                   "append (given spans)");
     if (r != LTRI_OK) return r;
-    r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, 1, n_new, c->stream),
-                  "representative keys");
+    if (c->D.rep_mode == LTRI_REP_DYNAMIC && n_new > 1)
+      r = check_hip(c, launch_dynamic_reps(c->D, c->ds, c->dc, c->k_arena, nullptr, layer, bp, 0, 1, n_new, false,
+                                           c->stream), "index vectors");
+    else
+      r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, 1, n_new, c->stream),
+                    "representative keys");
     if (r != LTRI_OK) return r;
   }
   append_commit(c, layer, seq, 1, n_new);
@@ -595,6 +617,20 @@ int32_t ltri_get_token_list(ltri_ctx* c, int32_t layer, int32_t seq, int32_t h, 
   if (n) *n = len;
   if (tokens_host) return read_dev(c, tokens_host, c->ds.tok_list + (size_t)slot * c->D.list_cap, (size_t)std::max(0, std::min(len, cap)) * 4);
   return LTRI_OK;
+}
+
+int32_t ltri_get_index_tokens(ltri_ctx* c, int32_t layer, int32_t seq, int32_t h, uint32_t* mask_host,
+                              int32_t cap_words) {
+  int32_t r = check_slot(c, layer, seq, h);
+  if (r != LTRI_OK) return r;
+  if (c->D.rep_mode != LTRI_REP_DYNAMIC) return fail(c, LTRI_ESTATE, "the context stores mean representatives");
+  const int len = c->last_len[ls_index(c, layer, seq)];
+  if (len == 0) return fail(c, LTRI_ESTATE, "no chunk appended yet");
+  const int words = (len + 31) / 32;
+  if (!mask_host || cap_words < words) return fail(c, LTRI_EINVAL, "mask_host holds %d words, %d needed", cap_words, words);
+  if (len == 1) { mask_host[0] = 1u; return LTRI_OK; }     // a one-token chunk is its own index token
+  const int slot = (layer * c->D.n_seqs + seq) * c->D.Hkv + h;
+  return read_dev(c, mask_host, c->ds.idx_mask + (size_t)slot * IDX_MASK_WORDS, (size_t)words * 4);
 }
 
 }  // extern "C"

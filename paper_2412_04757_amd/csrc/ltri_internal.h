@@ -24,6 +24,7 @@ constexpr int SEG_TB = 64;          // side of a segmentation tile
 constexpr int SEG_MAX_L = 2048;     // longest chunk the segmentation kernels take
 constexpr int SEG_MAX_NB = SEG_MAX_L / SEG_TB;
 constexpr int SEG_MAX_DIAG = 2 * SEG_MAX_L;   // anti-diagonals of the largest map (2 L - 1), rounded up
+constexpr int IDX_MASK_WORDS = SEG_MAX_L / 32;   // one bit per token of a chunk
 constexpr int ATT_BN = 64;
 constexpr int ATT_MAX_SPLITS = 8;        // key-range splits of a short query block (decode)
 constexpr int ATT_SPLIT_MAX_ROWS = 4;    // longest query block that is split          // keys per attention tile; token lists are padded to it
@@ -38,6 +39,7 @@ struct StateLayout {
   size_t sel_ids;     // int32  [n_slots][sel_cap]
   size_t tok_list;    // int32  [n_slots][list_cap]
   size_t err;         // int32  [4]
+  size_t idx_mask;    // uint32 [n_slots][IDX_MASK_WORDS]  index tokens of the chunk appended last (dynamic index vectors)
   size_t total;
 };
 
@@ -58,6 +60,8 @@ struct ScratchLayout {
   size_t bounds;   // int32  [Hkv][chunk_max + 1] + int32 [Hkv]  (append_with_spans)
   size_t selflag;  // uint8  [n_seqs * Hkv][max_spans]  1 = span selected (between the two selection kernels)
   size_t att_part; // float  [n_seqs][Hq][ATT_MAX_SPLITS][ATT_SPLIT_MAX_ROWS][d + 2]  partial attention results
+  size_t tokspan;  // int32  [P][Lp]      span (within the chunk) of every token (dynamic index vectors)
+  size_t dyn;      // double [P][3][Lp]   votes, in-span row sums, whole row sums of the softmax map
   size_t total;
   int    max_problems;  // P the buffer was sized for
 };
@@ -72,6 +76,8 @@ struct Dims {
   int max_keep;
   int max_spans, sel_cap, list_cap;
   int elt;  // bytes per element
+  int rep_mode, index_min, index_max, ratio_mode;   // dynamic index vectors (Sec. 3.3.2)
+  double lambda;
 };
 
 struct BatchPos {            // per-sequence values of one batched call
@@ -82,11 +88,12 @@ struct BatchPos {            // per-sequence values of one batched call
 // Raw device views handed to the kernels.
 struct DevState {
   int32_t* meta; int32_t* span_start; int32_t* span_len; void* krep; double* scores;
-  int32_t* sel_ids; int32_t* tok_list; int32_t* err;
+  int32_t* sel_ids; int32_t* tok_list; int32_t* err; uint32_t* idx_mask;
 };
 struct DevScratch {
   double* rowsum; double* csuf; double* tsum; double* rcar; double* ccar;
   double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds; uint8_t* selflag; float* att_part;
+  int32_t* tokspan; double* dyn;
 };
 
 // ---- launchers (each returns the hipError_t of the launch) ----
@@ -101,6 +108,9 @@ hipError_t launch_append_single(const Dims& D, const DevState& st, const void* k
                                 const BatchPos& bp, int seq_count, hipStream_t s);
 hipError_t launch_append_bounds(const Dims& D, const DevState& st, const DevScratch& sc, int layer,
                                 int seq, int c0, int n_new, hipStream_t s);
+hipError_t launch_dynamic_reps(const Dims& D, const DevState& st, const DevScratch& sc, const void* k_arena,
+                               const void* q_seg, int layer, const BatchPos& bp, int batch_off, int seq_count,
+                               int n_new, bool lse_ready, hipStream_t s);
 hipError_t launch_rep_keys(const Dims& D, const DevState& st, const void* k_arena, int layer,
                            const BatchPos& bp, int seq_count, int n_new, hipStream_t s);
 hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,

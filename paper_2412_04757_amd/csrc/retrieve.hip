@@ -20,7 +20,15 @@ struct RetArgs {
   BatchPos bp;
 };
 
-// ---- Q^R: mean over each query span of the group-summed query rows ----
+// Dynamic index vectors: the mask of the chunk's index tokens (bit = chunk-local token), or
+// nullptr when every token counts (mean representatives; a one-token chunk is its own index token).
+__device__ __forceinline__ const uint32_t* index_mask(const Dims& D, const DevState& st, int slot, const int32_t* meta) {
+  if (D.rep_mode != LTRI_REP_DYNAMIC || meta[META_CHUNK_LEN] <= 1) return nullptr;
+  return st.idx_mask + (size_t)slot * IDX_MASK_WORDS;
+}
+
+// ---- Q^R: mean over each query span of the group-summed query rows (dynamic index vectors:
+//      their sum over the span's index tokens) ----
 template <int DT>
 __global__ __launch_bounds__(1024) void qrep_kernel(RetArgs a) {
   typedef typename Elt<DT>::type T;
@@ -37,7 +45,8 @@ __global__ __launch_bounds__(1024) void qrep_kernel(RetArgs a) {
     const int sid = first + qs;
     const int start = a.st.span_start[(size_t)slot * D.max_spans + sid] - c0;   // chunk-local
     const int len = a.st.span_len[(size_t)slot * D.max_spans + sid];
-    span_mean_block<DT>(Qb + (size_t)start * D.Hq * d, (size_t)D.Hq * d, D.G, len, d, out + (size_t)qs * d, part);
+    span_mean_block<DT>(Qb + (size_t)start * D.Hq * d, (size_t)D.Hq * d, D.G, len, d, out + (size_t)qs * d, part,
+                        nullptr, index_mask(D, a.st, slot, meta), start);
   }
 }
 
@@ -81,7 +90,7 @@ __global__ __launch_bounds__(1024) void qrep_partial_kernel(RetArgs a) {
     if (!qrep_unit(slen, nsp, u, q, t0, nt)) break;            // uniform over the block
     const int start = sstart[q] - c0 + t0;                      // chunk-local
     span_mean_block<DT>(Qb + (size_t)start * D.Hq * d, (size_t)D.Hq * d, D.G, nt, d, nullptr, part,
-                        psum + (size_t)u * d);
+                        psum + (size_t)u * d, index_mask(D, a.st, slot, meta), start);
   }
 }
 
@@ -105,7 +114,7 @@ __global__ __launch_bounds__(128) void qrep_final_kernel(RetArgs a) {
     const int parts = (len + QREP_PIECE - 1) / QREP_PIECE;
     double s = 0.0;
     for (int k = 0; k < parts; ++k) s += psum[(size_t)(u0 + k) * d + c];
-    out[(size_t)q * d + c] = Elt<DT>::from_f64(s / (double)len);
+    out[(size_t)q * d + c] = Elt<DT>::from_f64(index_mask(D, a.st, slot, meta) ? s : s / (double)len);
   }
 }
 

@@ -91,7 +91,7 @@ template <> struct TileDot<LTRI_F32> {
 // cells above the diagonal or outside the chunk are 0. Called by all 256 threads; Ms doubles as
 // the staging area of the operands (2 x 16 KB) before the tile values are written.
 template <int DT>
-__device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int J, double* Ms) {
+__device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int J, double* Ms, int kind) {
   typedef typename Elt<DT>::type T;
   const Dims& D = a.D;
   const int sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
@@ -108,7 +108,7 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
   unsigned char* bbuf = abuf + 16384;
   const double scale = 1.0 / sqrt((double)d);
   const int jcol = J * 64 + wj * 32 + l32;
-  const bool logit = D.seg_map == LTRI_MAP_LOGIT;
+  const bool logit = kind == LTRI_MAP_LOGIT;
   double m[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) m[v] = 0.0;
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
   const int p = blockIdx.y;
   int I, J;
   tile_decode(blockIdx.x, I, J);
-  compute_tile<DT>(a, p, I, J, Ms);
+  compute_tile<DT>(a, p, I, J, Ms, a.D.seg_map);
   __syncthreads();
   const int tid = threadIdx.x;
   {                                       // row sums: four threads per row, 16 columns each
@@ -284,7 +284,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   // carries are requested before the tile is computed so that their latency hides behind it
   const double rc_pre = tid < 64 ? a.sc.rcar[((size_t)p * a.nb + J) * a.Lp + I * 64 + tid] : 0.0;
   const double cc_pre = a.sc.ccar[((size_t)p * a.nb + I) * a.Lp + J * 64 + (tid & 63)];
-  compute_tile<DT>(a, p, I, J, Ms);
+  compute_tile<DT>(a, p, I, J, Ms, a.D.seg_map);
   if (tid < 64) rc[tid] = rc_pre;
   __syncthreads();
   {                                     // rows: suffix sums towards the left, four threads per row
@@ -535,6 +535,195 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
   append_spans(D, a.st, slot_of(D, a.layer, seq, h), c0, L, cutlist, total);
 }
 
+// ============================================================================
+// Dynamic span index vectors (Sec. 3.3.2). After the chunk's spans are in the table:
+//   votes v_x (Eq. 6) = column sums of the chunk's head-summed softmax map,
+//   r_a = area of a span's triangle over that area plus its neighbours' (same rows to the left,
+//         same columns below, or both),
+//   index tokens = the round(len / e^(lambda (1 - r_a))) tokens of the span with the most votes
+//         (Eq. 7, clamped), stored vector = sum of their keys (Eq. 8 is bilinear).
+// The map is recomputed tile by tile as in the segmentation passes; all sums are fp64 in a fixed
+// order. The scratch arrays of the segmentation passes are free by then and are reused:
+// rowsum[J][i] = tile row sums, rcar[J][i] = tile row sums over the columns of row i's own span,
+// csuf[I][x] = tile column sums.
+// ============================================================================
+
+// span (within the chunk) of every token; clears the chunk's index-token mask
+__global__ __launch_bounds__(256) void dyn_token_span_kernel(SegArgs a) {
+  const Dims& D = a.D;
+  const int p = blockIdx.y, sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP], c0 = meta[META_CHUNK_START];
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < IDX_MASK_WORDS) a.st.idx_mask[(size_t)slot * IDX_MASK_WORDS + i] = 0u;
+  if (i >= a.Lp) return;
+  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans + first;
+  int lo = 0, hi = nsp - 1;                       // last span that starts at or before token i
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (sstart[mid] - c0 <= i) lo = mid; else hi = mid - 1;
+  }
+  a.sc.tokspan[(size_t)p * a.Lp + i] = (i < a.n_new && nsp > 0) ? lo : -1;
+}
+
+// per tile of the softmax map: row sums, row sums inside the row's own span, column sums
+template <int DT>
+__global__ __launch_bounds__(256) void dyn_tile_kernel(SegArgs a) {
+  __shared__ double Ms[64 * 65];
+  __shared__ double cpart[4][64];
+  __shared__ int rspan[64], cspan[64];
+  const int p = blockIdx.y;
+  int I, J;
+  tile_decode(blockIdx.x, I, J);
+  compute_tile<DT>(a, p, I, J, Ms, LTRI_MAP_SOFTMAX);
+  const int tid = threadIdx.x;
+  if (tid < 64) rspan[tid] = a.sc.tokspan[(size_t)p * a.Lp + I * 64 + tid];
+  else if (tid < 128) cspan[tid - 64] = a.sc.tokspan[(size_t)p * a.Lp + J * 64 + tid - 64];
+  __syncthreads();
+  {                                       // rows: four threads per row, 16 columns each
+    const int r = tid >> 2, qd = tid & 3;
+    const int mine = rspan[r];
+    double s = 0.0, sin = 0.0;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      const double v = Ms[r * 65 + qd * 16 + c];
+      s += v;
+      sin += cspan[qd * 16 + c] == mine ? v : 0.0;
+    }
+    s += __shfl_xor(s, 1, 64);   sin += __shfl_xor(sin, 1, 64);
+    s += __shfl_xor(s, 2, 64);   sin += __shfl_xor(sin, 2, 64);
+    if (qd == 0) {
+      a.sc.rowsum[((size_t)p * a.nb + J) * a.Lp + I * 64 + r] = s;
+      a.sc.rcar[((size_t)p * a.nb + J) * a.Lp + I * 64 + r] = sin;
+    }
+  }
+  {                                       // columns: four threads per column, 16 rows each
+    const int c = tid & 63, qd = tid >> 6;
+    double s = 0.0;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s += Ms[(qd * 16 + r) * 65 + c];
+    cpart[qd][c] = s;
+  }
+  __syncthreads();
+  if (tid < 64)
+    a.sc.csuf[((size_t)p * a.nb + I) * a.Lp + J * 64 + tid] =
+        ((cpart[0][tid] + cpart[1][tid]) + cpart[2][tid]) + cpart[3][tid];
+}
+
+// per token: vote (column sum over the tiles below), row sum inside its span, whole row sum
+__global__ __launch_bounds__(256) void dyn_reduce_kernel(SegArgs a) {
+  const int p = blockIdx.y, nb = a.nb, Lp = a.Lp;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= Lp) return;
+  const int B = i / 64;
+  double v = 0.0, rin = 0.0, rall = 0.0;
+  for (int I = B; I < nb; ++I) v += a.sc.csuf[((size_t)p * nb + I) * Lp + i];
+  for (int J = 0; J <= B; ++J) {
+    rin += a.sc.rcar[((size_t)p * nb + J) * Lp + i];
+    rall += a.sc.rowsum[((size_t)p * nb + J) * Lp + i];
+  }
+  double* dyn = a.sc.dyn + (size_t)p * 3 * Lp;
+  dyn[i] = v; dyn[Lp + i] = rin; dyn[2 * Lp + i] = rall;
+}
+
+// order key of a vote: smaller key = more votes
+__device__ __forceinline__ uint64_t vote_key(double s) {
+  const uint64_t u = (uint64_t)__double_as_longlong(s + 0.0);
+  const uint64_t up = (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+  return ~up;
+}
+
+// per span: area ratio, number of index tokens (Eq. 7), the tokens, the sum of their keys
+template <int DT>
+__global__ __launch_bounds__(1024) void dyn_span_kernel(SegArgs a) {
+  typedef typename Elt<DT>::type T;
+  __shared__ double part[16][128];
+  __shared__ uint64_t skey[SEG_MAX_L];
+  __shared__ uint16_t spos[SEG_MAX_L];
+  __shared__ uint32_t smask[IDX_MASK_WORDS + 1];
+  __shared__ double red[3][16];
+  __shared__ int s_count;
+  const Dims& D = a.D;
+  const int p = blockIdx.y, sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP], c0 = meta[META_CHUNK_START];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const double* dyn = a.sc.dyn + (size_t)p * 3 * a.Lp;
+  const T* Kb = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot);
+  uint32_t* gmask = a.st.idx_mask + (size_t)slot * IDX_MASK_WORDS;
+  for (int q = blockIdx.x; q < nsp; q += gridDim.x) {
+    const int sid = first + q;
+    const int start = a.st.span_start[(size_t)slot * D.max_spans + sid];
+    const int len = a.st.span_len[(size_t)slot * D.max_spans + sid];
+    const int a0 = start - c0;                          // chunk-local
+    // sums over the span's tokens in a fixed order: per thread, per wave, then over the waves
+    double sv = 0.0, sin = 0.0, sall = 0.0;
+    for (int t = tid; t < len; t += blockDim.x) {
+      sv += dyn[a0 + t]; sin += dyn[a.Lp + a0 + t]; sall += dyn[2 * a.Lp + a0 + t];
+    }
+    sv = wave_sum_f64(sv); sin = wave_sum_f64(sin); sall = wave_sum_f64(sall);
+    if (lane == 0) { red[0][wave] = sv; red[1][wave] = sin; red[2][wave] = sall; }
+    for (int w = tid; w < IDX_MASK_WORDS + 1; w += blockDim.x) smask[w] = 0u;
+    __syncthreads();
+    if (tid == 0) {
+      double votes = 0.0, tri = 0.0, rows = 0.0;
+      for (int w = 0; w < 16; ++w) { votes += red[0][w]; tri += red[1][w]; rows += red[2][w]; }
+      // triangle + row neighbours = the span's rows; triangle + column neighbours = its votes
+      const double den = D.ratio_mode == LTRI_RATIO_ROW ? rows
+                       : D.ratio_mode == LTRI_RATIO_COL ? votes : rows + votes - tri;
+      const double r_a = tri / den;
+      const double r_v = 1.0 / exp(D.lambda * (1.0 - r_a));
+      int n = (int)rint((double)len * r_v);
+      n = max(n, D.index_min);
+      if (D.index_max > 0) n = min(n, D.index_max);
+      s_count = max(1, min(n, len));
+    }
+    // tokens by votes: bitonic network over (key, position), ascending
+    int npow = 2;
+    while (npow < len) npow <<= 1;
+    for (int t = tid; t < npow; t += blockDim.x) {
+      skey[t] = t < len ? vote_key(dyn[a0 + t]) : ~0ull;
+      spos[t] = (uint16_t)t;
+    }
+    __syncthreads();
+    for (int k = 2; k <= npow; k <<= 1) {
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        for (int t = tid; t < npow / 2; t += blockDim.x) {
+          const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+          const uint64_t ka = skey[lo], kb = skey[hi];
+          const uint16_t pa = spos[lo], pb = spos[hi];
+          const bool a_after_b = (ka > kb) | ((ka == kb) & (pa > pb));
+          if (a_after_b == ((lo & k) == 0)) {
+            skey[lo] = kb; skey[hi] = ka;
+            spos[lo] = pb; spos[hi] = pa;
+          }
+        }
+        __syncthreads();
+      }
+    }
+    const int count = s_count;
+    for (int r = tid; r < count; r += blockDim.x) {
+      const int t = spos[r];
+      atomicOr(&smask[t >> 5], 1u << (t & 31));
+    }
+    __syncthreads();
+    // the chunk's mask (spans share words at their edges)
+    for (int w = tid; w <= (len - 1) >> 5; w += blockDim.x) {
+      const uint32_t m = smask[w];
+      if (m) {
+        const int bit = a0 + 32 * w;                    // chunk-local bit of smask word w, bit 0
+        const int sh = bit & 31;
+        atomicOr(&gmask[bit >> 5], m << sh);
+        if (sh && (bit >> 5) + 1 < IDX_MASK_WORDS) atomicOr(&gmask[(bit >> 5) + 1], m >> (32 - sh));
+      }
+    }
+    T* rep = reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + sid) * D.d;
+    span_mean_block<DT>(Kb + (size_t)start * D.d, (size_t)D.d, 1, len, D.d, rep, part, nullptr, smask, 0);
+  }
+}
+
 // ---- chunks of one token: a single span, its key is its own representative ----
 struct SingleArgs { Dims D; DevState st; const void* k_arena; int layer; int seq_count; BatchPos bp; };
 
@@ -645,6 +834,33 @@ hipError_t launch_copy_chunk(const Dims& D, void* k_arena, void* v_arena, const 
   const size_t n16 = (size_t)n_new * D.d * D.elt / 16;
   const int bx = (int)((n16 + 255) / 256 < 64 ? (n16 + 255) / 256 : 64);
   copy_chunk_kernel<<<dim3(bx > 0 ? bx : 1, seq_count * D.Hkv), 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_dynamic_reps(const Dims& D, const DevState& st, const DevScratch& sc, const void* k_arena,
+                               const void* q_seg, int layer, const BatchPos& bp, int batch_off, int seq_count,
+                               int n_new, bool lse_ready, hipStream_t s) {
+  SegArgs a;
+  a.D = D; a.st = st; a.sc = sc; a.k_arena = k_arena; a.q_seg = q_seg; a.layer = layer;
+  a.batch_off = batch_off; a.n_new = n_new;
+  a.nb = (n_new + SEG_TB - 1) / SEG_TB; a.Lp = a.nb * SEG_TB; a.ntiles = a.nb * (a.nb + 1) / 2;
+  a.bp = bp;
+  const int P = seq_count * D.Hkv;
+  const bool bf = D.dtype == LTRI_BF16;
+  if (!lse_ready) {
+    const int n_h = q_seg ? D.G : 1;
+    dim3 g0((n_h * n_new + 3) / 4, P);
+    if (bf) seg_row_lse_kernel<LTRI_BF16><<<g0, 256, 0, s>>>(a);
+    else    seg_row_lse_kernel<LTRI_F32><<<g0, 256, 0, s>>>(a);
+  }
+  dim3 gl((a.Lp + 255) / 256, P), gt(a.ntiles, P);
+  dyn_token_span_kernel<<<gl, 256, 0, s>>>(a);
+  if (bf) dyn_tile_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
+  else    dyn_tile_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
+  dyn_reduce_kernel<<<gl, 256, 0, s>>>(a);
+  dim3 gs(64, P);
+  if (bf) dyn_span_kernel<LTRI_BF16><<<gs, 1024, 0, s>>>(a);
+  else    dyn_span_kernel<LTRI_F32><<<gs, 1024, 0, s>>>(a);
   return hipGetLastError();
 }
 

@@ -12,11 +12,14 @@ namespace ltri {
 // address base + (r / inner) * tok_stride + (r % inner) * d. Writes mean over tokens (sum over
 // all rows divided by n_tokens) to out[0..d), or, when out_sum is given, the undivided fp64
 // sums to out_sum[0..d). Called by all 1024 threads of a workgroup.
+// With tokmask (global or LDS words, bit bit0 + t for token t) only the marked tokens are summed and
+// the result is their sum, not a mean (the stored vector of a span's index tokens, Sec. 3.3.2).
 template <int DT>
 __device__ __forceinline__ void span_mean_block(const typename Elt<DT>::type* base, size_t tok_stride,
                                                 int inner, int n_tokens, int d,
                                                 typename Elt<DT>::type* out, double (*part)[128],
-                                                double* out_sum = nullptr) {
+                                                double* out_sum = nullptr,
+                                                const uint32_t* tokmask = nullptr, int bit0 = 0) {
   typedef typename Elt<DT>::type T;
   constexpr int EPP = 16 / (int)sizeof(T);           // elements per 16-byte piece
   const int R = d / EPP;                             // lanes per d-vector (16 or 32)
@@ -37,6 +40,7 @@ __device__ __forceinline__ void span_mean_block(const typename Elt<DT>::type* ba
       ok[u] = r < n_rows;
       const int rr = ok[u] ? r : r0;
       const int tok = rr / inner, g = rr - tok * inner;
+      if (tokmask) ok[u] = ok[u] && ((tokmask[(bit0 + tok) >> 5] >> ((bit0 + tok) & 31)) & 1u);
       v[u] = *reinterpret_cast<const uint4*>(base + (size_t)tok * tok_stride + (size_t)g * d + piece * EPP);
     }
 #pragma unroll
@@ -62,7 +66,7 @@ __device__ __forceinline__ void span_mean_block(const typename Elt<DT>::type* ba
 #pragma unroll
     for (int w = 0; w < 16; ++w) s += part[w][threadIdx.x];
     if (out_sum) out_sum[threadIdx.x] = s;          // raw sum of a piece of a span
-    else         out[threadIdx.x] = Elt<DT>::from_f64(s / (double)n_tokens);
+    else         out[threadIdx.x] = Elt<DT>::from_f64(tokmask ? s : s / (double)n_tokens);
   }
   __syncthreads();
 }

@@ -246,6 +246,84 @@ def test_persistent_selection_decode(gpu_device):
     assert ctx.sync_status() == 0
 
 
+def _dynamic_stream(gpu_device, w, seed, T, L, q_seg, key_scale=0.35, given_spans=False, **kw):
+    """Streams T tokens in chunks of L with dynamic index vectors on both sides; index tokens,
+    stored vectors, selections and outputs against the oracle on every chunk. The planted keys are
+    scaled down (and theta with their square) so that attention leaks out of the spans and the
+    area ratios, hence the counts of Eq. 7, differ from span to span. A chunk whose index tokens
+    hang on a near-tie (audit) would fail: the shipped seeds are audited ones."""
+    K, V, Q, bounds = planted_stream(w, seed, device=str(gpu_device), context=T)
+    K = (K.float() * key_scale).to(K.dtype)
+    ctx, st = make_pair(w, K, V, gpu_device, max_tokens=T, rep_mode=O.REP_DYNAMIC,
+                        theta=theta_default(w.head_dim) * key_scale ** 2, **kw)
+    Kn = K.double().cpu().numpy()
+    n_audited = n_unstable = n_partial = 0
+    for c0 in range(0, T, L):
+        n = min(L, T - c0)
+        q = Q[c0:c0 + n].contiguous()
+        qn = q.double().cpu().numpy()
+        if given_spans:
+            b = [np.asarray(sorted({0, n} | {int(x - c0) for x in bounds[h] if c0 < x < c0 + n}), np.int64)
+                 for h in range(w.n_kv_heads)]
+            ctx.append_chunk_with_spans(0, 0, n, b)
+            st.append_chunk(n, bounds=b)
+        else:
+            ctx.append_chunk(0, 0, 1, n, q_seg=q if q_seg else None)
+            st.append_chunk(n, q_seg=qn if q_seg else None)
+        stable = True
+        counts = [len(t) for t in st.last_index_tokens[0]]
+        n_partial += sum(1 for c, ln in zip(counts, st.lens[0][-len(counts):]) if 1 < c < ln)
+        for h in range(w.n_kv_heads):
+            assert spans_equal(ctx, st, h)
+            got = ctx.get_index_tokens(0, 0, h, n)
+            want = np.concatenate(st.last_index_tokens[h])        # chunk-local, ascending
+            if list(got) != list(want):
+                Qg = None
+                if q_seg:
+                    g = w.n_q_heads // w.n_kv_heads
+                    Qg = np.transpose(qn[:, h * g:(h + 1) * g, :], (1, 0, 2))
+                A, _ = O.chunk_map(Kn[h, c0:c0 + n], Qg, O.MAP_SOFTMAX)
+                assert not O.dynamic_index_is_stable(A, st.last_bounds[h], st.cfg.lam, st.cfg.n_min, st.cfg.n_max,
+                                                     st.cfg.ratio_mode, rel=2.0 ** -16), f"chunk at {c0}, head {h}"
+                stable = False
+                n_unstable += 1
+            n_audited += 1
+        assert stable, "shipped seeds are audited ones"
+        for h in range(w.n_kv_heads):
+            assert rep_keys_diff(ctx, st, h) == 0.0
+        ctx.retrieve(0, 0, 1, q)
+        sel = st.retrieve(qn)
+        for h in range(w.n_kv_heads):
+            ids, scores = ctx.get_selection(0, 0, h)
+            np.testing.assert_allclose(scores, st.sel_scores[h], rtol=1e-12, atol=1e-9)
+            assert list(ids) == list(sel[h]), f"chunk at {c0}, head {h}"
+        rows = list(range(0, n, max(1, n // 16)))
+        out = ctx.attend(0, 0, 1, q)[0].double().cpu().numpy()[rows]
+        want, _ = st.attend(qn, rows=rows)
+        assert np.abs(out - want).max() <= (2e-2 if w.dtype == "bf16" else 1e-4)
+    assert ctx.sync_status() == 0
+    return n_audited, n_partial
+
+
+def test_dynamic_index_vectors_bf16(gpu_device):
+    """Sec. 3.3.2 on the device: votes, area ratios (all three kinds), Eq. 7 counts, index tokens and
+    the summed vectors on both sides of Eq. 8; ragged last chunk, query-driven map, count limits."""
+    w = Workload("mini-dyn", 8, 2, 128, "bf16", 1536, 512, 4, 128, 0, 300, "uniform", 16, 128)
+    for kw in (dict(lam=3.0, ratio_mode=0), dict(lam=1.0, ratio_mode=1, index_max=24),
+               dict(lam=2.0, ratio_mode=2, index_min=4)):
+        _, n_partial = _dynamic_stream(gpu_device, w, 5, 1536 - 100, 512, False, **kw)
+        assert n_partial >= 6                      # spans that keep some, not all, of their tokens
+    _dynamic_stream(gpu_device, w, 6, 1024, 512, True, lam=3.0, ratio_mode=0)
+    _, n_partial = _dynamic_stream(gpu_device, w, 7, 1024, 512, False, given_spans=True, lam=3.0, ratio_mode=0)
+    assert n_partial >= 6
+
+
+def test_dynamic_index_vectors_fp32(gpu_device):
+    w = CONFIGS["cfg1"]
+    _, n_partial = _dynamic_stream(gpu_device, w, 2, 1024 + 60, 256, False, lam=3.0, ratio_mode=0, index_max=16)
+    assert n_partial >= 6
+
+
 def test_span_table_overflow_is_reported(gpu_device):
     w = CONFIGS["cfg1"]
     K, V, Q, _ = planted_stream(w, 1, device=str(gpu_device), context=1024)
