@@ -279,6 +279,9 @@ def main():
     ap.add_argument("--overlap", action="store_true",
                     help="segment chunk c+1 on a second stream next to attend(c) (measured: no gain, the kernels\n"
                          "compete for the same compute units)")
+    ap.add_argument("--index-vectors", choices=["mean", "dynamic"], default="mean",
+                    help="what a span stores: the mean key (headline) or the sum of its index tokens' keys\n"
+                         "(dynamic span index vectors, row ratio, lambda 3); not the headline configuration")
     ap.add_argument("--seed", type=int, default=1)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -315,7 +318,8 @@ def main():
     K, V, Q, bounds = planted_stream(w, args.seed, device="cuda:0")
     torch.cuda.synchronize()
     log(f"[bench] inputs generated in {time.time() - t0:.1f}s")
-    cfg = config_from_workload(w, theta=theta, n_layers=1, n_seqs=1)
+    cfg = config_from_workload(w, theta=theta, n_layers=1, n_seqs=1,
+                               rep_mode=1 if args.index_vectors == "dynamic" else 0, lam=3.0)
     ctx = LtriContext(cfg, dev)
     ka, va = ctx.arena_views()
     ka[0, 0].copy_(K)
@@ -453,6 +457,8 @@ def main():
                                f"planted-span keys ({w.len_dist} lengths in [{w.len_lo},{w.len_hi}]), seed {args.seed}",
                    "step": "one full stream through one layer (append + retrieve + attend per chunk)",
                    "seg_map": "logit", "theta": theta, "phi": 0.0,
+                   "index_vectors": "mean key per span" if args.index_vectors == "mean"
+                   else "dynamic (row ratio, lambda 3): sum of the keys of each span's index tokens",
                    "schedule": "append(c+1) on a second stream next to attend(c)" if overlap else "serial"},
         "roofline": roofline, "gather": gather, "cpu_baseline": cpu,
         "breakdown_ms": {"attend": round(tot_ms / args.steps, 3), "append_retrieve_and_gaps": round(other_ms, 3)},

@@ -127,6 +127,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.att_part = o; o = align_up(o + (size_t)c.n_seqs * c.n_q_heads * ATT_MAX_SPLITS * ATT_SPLIT_MAX_ROWS * (D.d + 2) * 4, 256);
   CL.tokspan = o; o = align_up(o + (size_t)P * Lp * 4, 256);
   CL.dyn = o;     o = align_up(o + (size_t)P * 3 * Lp * 8, 256);
+  CL.lpart = o;   o = align_up(o + (c.rep_mode == LTRI_REP_DYNAMIC ? (size_t)P * G * nb * Lp * 16 : 0), 256);
   CL.total = o;
   CL.max_problems = P;
   return LTRI_OK;
@@ -185,7 +186,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
                      (double*)(t + CL.rcar), (double*)(t + CL.ccar), (double*)(t + CL.pscore),
                      (int32_t*)(t + CL.px), (uint64_t*)(t + CL.ckey), (uint32_t*)(t + CL.cxy), (double*)(t + CL.lse), (void*)(t + CL.qrep),
                      (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds), (uint8_t*)(t + CL.selflag), (float*)(t + CL.att_part),
-                     (int32_t*)(t + CL.tokspan), (double*)(t + CL.dyn)};
+                     (int32_t*)(t + CL.tokspan), (double*)(t + CL.dyn), (double*)(t + CL.lpart)};
   const size_t n = (size_t)D.n_layers * D.n_seqs;
   c->n_tokens.assign(n, 0);
   c->last_len.assign(n, 0);

@@ -62,6 +62,7 @@ struct ScratchLayout {
   size_t att_part; // float  [n_seqs][Hq][ATT_MAX_SPLITS][ATT_SPLIT_MAX_ROWS][d + 2]  partial attention results
   size_t tokspan;  // int32  [P][Lp]      span (within the chunk) of every token (dynamic index vectors)
   size_t dyn;      // double [P][3][Lp]   votes, in-span row sums, whole row sums of the softmax map
+  size_t lpart;    // double [P][G][nb][Lp][2]  per tile: row maximum and sum of exponentials (row log-sum-exp in pieces)
   size_t total;
   int    max_problems;  // P the buffer was sized for
 };
@@ -93,7 +94,7 @@ struct DevState {
 struct DevScratch {
   double* rowsum; double* csuf; double* tsum; double* rcar; double* ccar;
   double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds; uint8_t* selflag; float* att_part;
-  int32_t* tokspan; double* dyn;
+  int32_t* tokspan; double* dyn; double* lpart;
 };
 
 // ---- launchers (each returns the hipError_t of the launch) ----

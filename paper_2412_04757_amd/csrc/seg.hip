@@ -548,6 +548,89 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
 // csuf[I][x] = tile column sums.
 // ============================================================================
 
+// ---- row log-sum-exp of the chunk's causal scores from the same matrix-core tiles as the map ----
+// Per tile and head: the row maximum and the sum of exponentials relative to it (lpart[.][J][i][2]);
+// a second kernel merges the pieces of a row over its tiles.
+template <int DT>
+__global__ __launch_bounds__(256) void lse_tile_kernel(SegArgs a) {
+  typedef typename Elt<DT>::type T;
+  __shared__ double Ms[64 * 65];
+  const Dims& D = a.D;
+  const int p = blockIdx.y;
+  int I, J;
+  tile_decode(blockIdx.x, I, J);
+  const int sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
+  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
+  const int L = a.n_new, d = D.d;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wi = wave >> 1, wj = wave & 1, hf = lane >> 5, l32 = lane & 31;
+  const int slot = slot_of(D, a.layer, seq, h);
+  const T* Kc = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * d;
+  const T* Qb = a.q_seg ? reinterpret_cast<const T*>(a.q_seg) + (size_t)bi * L * D.Hq * d + (size_t)h * D.G * d : nullptr;
+  const int n_h = a.q_seg ? D.G : 1;
+  const int nkc = d * (int)sizeof(T) / 256;
+  unsigned char* abuf = reinterpret_cast<unsigned char*>(Ms);
+  unsigned char* bbuf = abuf + 16384;
+  const double scale = 1.0 / sqrt((double)d);
+  const int jcol = J * 64 + wj * 32 + l32;
+  for (int g = 0; g < n_h; ++g) {
+    f32x16_t acc = {0};
+    for (int kc = 0; kc < nkc; ++kc) {
+      if (Qb) stage_rows<T>(abuf, Qb + (size_t)g * d, (size_t)D.Hq * d, I * 64, L, kc);
+      else    stage_rows<T>(abuf, Kc, (size_t)d, I * 64, L, kc);
+      stage_rows<T>(bbuf, Kc, (size_t)d, J * 64, L, kc);
+      __syncthreads();
+      TileDot<DT>::run(abuf, bbuf, wi * 32, wj * 32, l32, hf, acc);
+      __syncthreads();
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int rl = wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+      const int i = I * 64 + rl;
+      Ms[rl * 65 + wj * 32 + l32] = (jcol <= i && i < L) ? (double)acc[v] * scale : -INFINITY;
+    }
+    __syncthreads();
+    {                                     // four threads per row, 16 columns each
+      const int r = tid >> 2, qd = tid & 3;
+      double z[16];
+      double mx = -INFINITY;
+#pragma unroll
+      for (int c = 0; c < 16; ++c) { z[c] = Ms[r * 65 + qd * 16 + c]; mx = fmax(mx, z[c]); }
+      mx = fmax(mx, __shfl_xor(mx, 1, 64));
+      mx = fmax(mx, __shfl_xor(mx, 2, 64));
+      double sm = 0.0;
+      if (mx > -INFINITY) {
+#pragma unroll
+        for (int c = 0; c < 16; ++c) sm += exp(z[c] - mx);
+      }
+      sm += __shfl_xor(sm, 1, 64);
+      sm += __shfl_xor(sm, 2, 64);
+      if (qd == 0) {
+        double* o = a.sc.lpart + ((((size_t)p * n_h + g) * a.nb + J) * a.Lp + I * 64 + r) * 2;
+        o[0] = mx; o[1] = sm;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void lse_reduce_kernel(SegArgs a) {
+  const int p = blockIdx.y, nb = a.nb, Lp = a.Lp;
+  const int n_h = a.q_seg ? a.D.G : 1;
+  const int id = blockIdx.x * blockDim.x + threadIdx.x;        // (g, i) flattened
+  if (id >= n_h * Lp) return;
+  const int g = id / Lp, i = id - g * Lp, B = i / 64;
+  const double* pr = a.sc.lpart + (((size_t)p * n_h + g) * nb * Lp + i) * 2;
+  double mx = -INFINITY;
+  for (int J = 0; J <= B; ++J) mx = fmax(mx, pr[(size_t)J * Lp * 2]);
+  double sm = 0.0;
+  for (int J = 0; J <= B; ++J) {
+    const double m = pr[(size_t)J * Lp * 2], s2 = pr[(size_t)J * Lp * 2 + 1];
+    if (m > -INFINITY) sm += s2 * exp(m - mx);
+  }
+  a.sc.lse[((size_t)p * n_h + g) * Lp + i] = i < a.n_new ? mx + log(sm) : 0.0;
+}
+
 // span (within the chunk) of every token; clears the chunk's index-token mask
 __global__ __launch_bounds__(256) void dyn_token_span_kernel(SegArgs a) {
   const Dims& D = a.D;
@@ -847,13 +930,13 @@ hipError_t launch_dynamic_reps(const Dims& D, const DevState& st, const DevScrat
   a.bp = bp;
   const int P = seq_count * D.Hkv;
   const bool bf = D.dtype == LTRI_BF16;
+  dim3 gl((a.Lp + 255) / 256, P), gt(a.ntiles, P);
   if (!lse_ready) {
     const int n_h = q_seg ? D.G : 1;
-    dim3 g0((n_h * n_new + 3) / 4, P);
-    if (bf) seg_row_lse_kernel<LTRI_BF16><<<g0, 256, 0, s>>>(a);
-    else    seg_row_lse_kernel<LTRI_F32><<<g0, 256, 0, s>>>(a);
+    if (bf) lse_tile_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
+    else    lse_tile_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
+    lse_reduce_kernel<<<dim3((n_h * a.Lp + 255) / 256, P), 256, 0, s>>>(a);
   }
-  dim3 gl((a.Lp + 255) / 256, P), gt(a.ntiles, P);
   dyn_token_span_kernel<<<gl, 256, 0, s>>>(a);
   if (bf) dyn_tile_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
   else    dyn_tile_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);

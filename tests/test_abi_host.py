@@ -51,6 +51,21 @@ def test_workspace_sizes_and_bad_configs():
         for k, v in kw.items():
             setattr(cfg, k, v)
         assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == -1, kw
+    # dynamic span index vectors: parameters are checked only in that mode
+    cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0, rep_mode=1, lam=3.0, index_min=2, index_max=16, ratio_mode=2)
+    assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == 0
+    mean_scratch = C.c_size_t()
+    cfg0 = config_from_workload(CONFIGS["cfg1"], theta=1.0)
+    assert lib.ltri_workspace_bytes(C.byref(cfg0), C.byref(sb), C.byref(mean_scratch)) == 0
+    assert cb.value > mean_scratch.value                       # the row log-sum-exp pieces
+    for kw in (dict(rep_mode=2), dict(lam=-1.0), dict(lam=float("nan")), dict(index_min=-1), dict(index_max=1),
+               dict(ratio_mode=3)):
+        cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0, rep_mode=1, lam=3.0, index_min=2, index_max=16)
+        for k, v in kw.items():
+            setattr(cfg, k, v)
+        assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == -1, kw
+    cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0, lam=-5.0, ratio_mode=9)    # ignored with mean keys
+    assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == 0
     cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0)
     cfg.dtype = 1            # bf16 with head_dim 64 is not supported
     assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == -1

@@ -125,6 +125,60 @@ def test_cfg3_full_size_retrieve_and_attend(gpu_device):
     assert ctx.sync_status() == 0
 
 
+def test_cfg3_dynamic_index_vectors_full_size(gpu_device):
+    """Dynamic span index vectors at the benchmark's sizes (chunks of 2048, 8 KV heads, the whole 128K
+    stream): on sampled chunks and heads the index tokens and the stored vectors of the chunk's spans
+    are recomputed by the oracle from the device's own boundaries; everywhere the counts obey Eq. 7's
+    limits. Keys are scaled down (theta with their square) so that the area ratios differ between spans."""
+    w = CONFIGS["cfg3"]
+    T, L = w.context, w.chunk
+    scale, lam, n_max = 0.35, 3.0, 64
+    K, V, Q, _ = planted_stream(w, 3, device=str(gpu_device))
+    K = (K.float() * scale).to(K.dtype)
+    theta = theta_default(w.head_dim) * scale ** 2
+    cfg = config_from_workload(w, theta=theta, n_layers=1, n_seqs=1, rep_mode=O.REP_DYNAMIC, lam=lam, index_max=n_max)
+    ctx = LtriContext(cfg, gpu_device)
+    ka, va = ctx.arena_views()
+    ka[0, 0].copy_(K)
+    va[0, 0].copy_(V)
+    out = torch.empty((1, L, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=gpu_device)
+    sampled = {0: (0, 5), 31: (3,), 63: (0, 7)}
+    n_partial = n_unstable = 0
+    for c in range(T // L):
+        c0 = c * L
+        q = Q[c0:c0 + L]
+        ctx.append_chunk(0, 0, 1, L)
+        for h in sampled.get(c, ()):
+            s, l = ctx.get_spans(0, 0, h)
+            mine = [(int(a), int(b)) for a, b in zip(s, l) if a >= c0]
+            bounds = np.asarray([a - c0 for a, _ in mine] + [L], np.int64)
+            Kc = K[h, c0:c0 + L].double().cpu().numpy()
+            A, _ = O.chunk_map(Kc, None, O.MAP_SOFTMAX)
+            want = O.dynamic_index_tokens(A, bounds, float(np.float32(lam)), 1, n_max, O.RATIO_ROW)
+            got = ctx.get_index_tokens(0, 0, h, L)
+            if list(got) != list(np.concatenate(want)):
+                assert not O.dynamic_index_is_stable(A, bounds, float(np.float32(lam)), 1, n_max, O.RATIO_ROW,
+                                                     rel=2.0 ** -16), f"chunk {c}, head {h}"
+                n_unstable += 1
+                continue
+            reps = ctx.get_rep_keys(0, 0, h).double().numpy()[-len(mine):]
+            np.testing.assert_array_equal(reps, O.index_vector_sums(Kc, want, "bf16"))
+            n_partial += sum(1 for t, (_, ln) in zip(want, mine) if 1 < len(t) < min(ln, n_max))
+        if c % 16 == 15:
+            for h in range(w.n_kv_heads):
+                got = ctx.get_index_tokens(0, 0, h, L)
+                s, l = ctx.get_spans(0, 0, h)
+                for a, ln in zip(s, l):
+                    if a >= c0:
+                        k = int(((got >= a - c0) & (got < a - c0 + ln)).sum())
+                        assert 1 <= k <= min(ln, n_max)
+        ctx.retrieve(0, 0, 1, q)
+        ctx.attend(0, 0, 1, q, out=out)
+    assert n_unstable == 0 and n_partial >= 5          # the shipped seed is an audited one
+    assert torch.isfinite(out.float()).all()
+    assert ctx.sync_status() == 0
+
+
 def test_decode_batch_cfg5_shape(gpu_device):
     """Batched decode: 16 sequences, one new token per step, re-scoring and retrieval every step
     (config 5 shape at 16K context). Prefill history with given boundaries, decode appends real."""
