@@ -127,7 +127,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.att_part = o; o = align_up(o + (size_t)c.n_seqs * c.n_q_heads * ATT_MAX_SPLITS * ATT_SPLIT_MAX_ROWS * (D.d + 2) * 4, 256);
   CL.tokspan = o; o = align_up(o + (size_t)P * Lp * 4, 256);
   CL.dyn = o;     o = align_up(o + (size_t)P * 3 * Lp * 8, 256);
-  CL.lpart = o;   o = align_up(o + (c.rep_mode == LTRI_REP_DYNAMIC ? (size_t)P * G * nb * Lp * 16 : 0), 256);
+  CL.lpart = o;   o = align_up(o + (c.rep_mode == LTRI_REP_DYNAMIC || c.seg_map == LTRI_MAP_SOFTMAX ? (size_t)P * G * nb * Lp * 16 : 0), 256);
   CL.total = o;
   CL.max_problems = P;
   return LTRI_OK;

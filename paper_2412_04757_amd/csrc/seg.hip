@@ -148,43 +148,6 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
   }
 }
 
-// ---- pass 0 (SOFTMAX map only): log-sum-exp of every causal row of every head ----
-template <int DT>
-__global__ __launch_bounds__(256) void seg_row_lse_kernel(SegArgs a) {
-  typedef typename Elt<DT>::type T;
-  const Dims& D = a.D;
-  const int p = blockIdx.y, sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
-  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
-  const int L = a.n_new, d = D.d;
-  const int n_h = a.q_seg ? D.G : 1;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int row_id = blockIdx.x * 4 + wave;            // (g, i) flattened
-  if (row_id >= n_h * L) return;
-  const int g = row_id / L, i = row_id - g * L;
-  const int slot = slot_of(D, a.layer, seq, h);
-  const T* Kc = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * d;
-  const T* qrow = a.q_seg ? reinterpret_cast<const T*>(a.q_seg) + (((size_t)bi * L + i) * D.Hq + h * D.G + g) * d
-                          : Kc + (size_t)i * d;
-  const double scale = 1.0 / sqrt((double)d);
-  double mx = -INFINITY, sm = 0.0;
-  for (int j = lane; j <= i; j += 64) {
-    const T* krow = Kc + (size_t)j * d;
-    double z = 0.0;
-    for (int c = 0; c < d; ++c) z += Elt<DT>::to_f64(qrow[c]) * Elt<DT>::to_f64(krow[c]);
-    z *= scale;
-    if (z > mx) { sm = sm * exp(mx - z) + 1.0; mx = z; } else { sm += exp(z - mx); }
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    double omx = __shfl_xor(mx, o, 64), osm = __shfl_xor(sm, o, 64);
-    double nm = fmax(mx, omx);
-    double s1 = (mx == -INFINITY) ? 0.0 : sm * exp(mx - nm);
-    double s2 = (omx == -INFINITY) ? 0.0 : osm * exp(omx - nm);
-    mx = nm; sm = s1 + s2;
-  }
-  if (lane == 0) a.sc.lse[((size_t)p * n_h + g) * a.Lp + i] = mx + log(sm);
-}
-
 // ---- pass 1: per-tile row sums, suffix-scanned column sums, total ----
 template <int DT>
 __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
@@ -548,7 +511,8 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
 // csuf[I][x] = tile column sums.
 // ============================================================================
 
-// ---- row log-sum-exp of the chunk's causal scores from the same matrix-core tiles as the map ----
+// ---- pass 0 (softmax map: SOFTMAX segmentation, dynamic index vectors): row log-sum-exp of the
+//      chunk's causal scores from the same matrix-core tiles as the map ----
 // Per tile and head: the row maximum and the sum of exponentials relative to it (lpart[.][J][i][2]);
 // a second kernel merges the pieces of a row over its tiles.
 template <int DT>
@@ -957,13 +921,13 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
   a.bp = bp;
   const int P = seq_count * D.Hkv;
   const bool bf = D.dtype == LTRI_BF16;
+  dim3 gt(a.ntiles, P);
   if (D.seg_map == LTRI_MAP_SOFTMAX) {
     const int n_h = q_seg ? D.G : 1;
-    dim3 g0((n_h * n_new + 3) / 4, P);
-    if (bf) seg_row_lse_kernel<LTRI_BF16><<<g0, 256, 0, s>>>(a);
-    else    seg_row_lse_kernel<LTRI_F32><<<g0, 256, 0, s>>>(a);
+    if (bf) lse_tile_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
+    else    lse_tile_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
+    lse_reduce_kernel<<<dim3((n_h * a.Lp + 255) / 256, P), 256, 0, s>>>(a);
   }
-  dim3 gt(a.ntiles, P);
   if (bf) seg_tile_sums_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
   else    seg_tile_sums_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
   seg_carries_kernel<<<dim3(SEG_CARRY_PARTS, P), 256, 0, s>>>(a);
