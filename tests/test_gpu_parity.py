@@ -246,15 +246,15 @@ def test_persistent_selection_decode(gpu_device):
     assert ctx.sync_status() == 0
 
 
-def _dynamic_stream(gpu_device, w, seed, T, L, q_seg, key_scale=0.35, given_spans=False, **kw):
+def _dynamic_stream(gpu_device, w, seed, T, L, q_seg, key_scale=0.35, given_spans=False, decode_steps=0, **kw):
     """Streams T tokens in chunks of L with dynamic index vectors on both sides; index tokens,
     stored vectors, selections and outputs against the oracle on every chunk. The planted keys are
     scaled down (and theta with their square) so that attention leaks out of the spans and the
     area ratios, hence the counts of Eq. 7, differ from span to span. A chunk whose index tokens
     hang on a near-tie (audit) would fail: the shipped seeds are audited ones."""
-    K, V, Q, bounds = planted_stream(w, seed, device=str(gpu_device), context=T)
+    K, V, Q, bounds = planted_stream(w, seed, device=str(gpu_device), context=T + decode_steps)
     K = (K.float() * key_scale).to(K.dtype)
-    ctx, st = make_pair(w, K, V, gpu_device, max_tokens=T, rep_mode=O.REP_DYNAMIC,
+    ctx, st = make_pair(w, K, V, gpu_device, max_tokens=T + decode_steps, rep_mode=O.REP_DYNAMIC,
                         theta=theta_default(w.head_dim) * key_scale ** 2, **kw)
     Kn = K.double().cpu().numpy()
     n_audited = n_unstable = n_partial = 0
@@ -301,6 +301,22 @@ def _dynamic_stream(gpu_device, w, seed, T, L, q_seg, key_scale=0.35, given_span
         out = ctx.attend(0, 0, 1, q)[0].double().cpu().numpy()[rows]
         want, _ = st.attend(qn, rows=rows)
         assert np.abs(out - want).max() <= (2e-2 if w.dtype == "bf16" else 1e-4)
+    for k in range(decode_steps):                  # one-token chunks: the token is its own index token
+        q = Q[T + k:T + k + 1].contiguous()
+        qn = q.double().cpu().numpy()
+        ctx.append_chunk(0, 0, 1, 1)
+        st.append_chunk(1)
+        assert list(ctx.get_index_tokens(0, 0, 0, 1)) == [0]
+        ctx.retrieve(0, 0, 1, q)
+        sel = st.retrieve(qn)
+        for h in range(w.n_kv_heads):
+            assert rep_keys_diff(ctx, st, h) == 0.0
+            ids, scores = ctx.get_selection(0, 0, h)
+            np.testing.assert_allclose(scores, st.sel_scores[h], rtol=1e-12, atol=1e-9)
+            assert list(ids) == list(sel[h])
+        out = ctx.attend(0, 0, 1, q)[0].double().cpu().numpy()
+        want, _ = st.attend(qn)
+        assert np.abs(out - want).max() <= (2e-2 if w.dtype == "bf16" else 1e-4)
     assert ctx.sync_status() == 0
     return n_audited, n_partial
 
@@ -313,14 +329,15 @@ def test_dynamic_index_vectors_bf16(gpu_device):
                dict(lam=2.0, ratio_mode=2, index_min=4)):
         _, n_partial = _dynamic_stream(gpu_device, w, 5, 1536 - 100, 512, False, **kw)
         assert n_partial >= 6                      # spans that keep some, not all, of their tokens
-    _dynamic_stream(gpu_device, w, 6, 1024, 512, True, lam=3.0, ratio_mode=0)
+    _dynamic_stream(gpu_device, w, 6, 1024, 512, True, decode_steps=3, lam=3.0, ratio_mode=0)
     _, n_partial = _dynamic_stream(gpu_device, w, 7, 1024, 512, False, given_spans=True, lam=3.0, ratio_mode=0)
     assert n_partial >= 6
 
 
 def test_dynamic_index_vectors_fp32(gpu_device):
     w = CONFIGS["cfg1"]
-    _, n_partial = _dynamic_stream(gpu_device, w, 2, 1024 + 60, 256, False, lam=3.0, ratio_mode=0, index_max=16)
+    _, n_partial = _dynamic_stream(gpu_device, w, 2, 1024 + 60, 256, False, decode_steps=2, lam=3.0, ratio_mode=0,
+                                   index_max=16)
     assert n_partial >= 6
 
 
