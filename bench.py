@@ -282,6 +282,9 @@ def main():
     ap.add_argument("--index-vectors", choices=["mean", "dynamic"], default="mean",
                     help="what a span stores: the mean key (headline) or the sum of its index tokens' keys\n"
                          "(dynamic span index vectors, row ratio, lambda 3); not the headline configuration")
+    ap.add_argument("--theta-quantile", type=float, default=0.0,
+                    help="take theta as this percentile of every chunk's map (e.g. 0.9) instead of the absolute\n"
+                         "value; not the headline configuration")
     ap.add_argument("--seed", type=int, default=1)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -319,7 +322,8 @@ def main():
     torch.cuda.synchronize()
     log(f"[bench] inputs generated in {time.time() - t0:.1f}s")
     cfg = config_from_workload(w, theta=theta, n_layers=1, n_seqs=1,
-                               rep_mode=1 if args.index_vectors == "dynamic" else 0, lam=3.0)
+                               rep_mode=1 if args.index_vectors == "dynamic" else 0, lam=3.0,
+                               theta_quantile=args.theta_quantile)
     ctx = LtriContext(cfg, dev)
     ka, va = ctx.arena_views()
     ka[0, 0].copy_(K)
@@ -456,7 +460,8 @@ def main():
                                f"{w.n_sink} sink tokens, window {w.window}, retrieval budget {w.budget_tokens} tokens, "
                                f"planted-span keys ({w.len_dist} lengths in [{w.len_lo},{w.len_hi}]), seed {args.seed}",
                    "step": "one full stream through one layer (append + retrieve + attend per chunk)",
-                   "seg_map": "logit", "theta": theta, "phi": 0.0,
+                   "seg_map": "logit", "theta": theta if not args.theta_quantile else f"percentile {args.theta_quantile}",
+                   "phi": 0.0,
                    "index_vectors": "mean key per span" if args.index_vectors == "mean"
                    else "dynamic (row ratio, lambda 3): sum of the keys of each span's index tokens",
                    "schedule": "append(c+1) on a second stream next to attend(c)" if overlap else "serial"},

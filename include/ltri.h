@@ -95,6 +95,11 @@ typedef struct {
   float   lambda;
   int32_t index_min, index_max;
   int32_t ratio_mode;                       /* LTRI_RATIO_*                               */
+  /* > 0: the threshold of Eq. 5 is this percentile of the chunk's map (Sec. 4, "Hyperparameter
+   * Tuning": typically the 90th, i.e. 0.9): the value of rank floor(q (n - 1)) among the n
+   * cells on and below the diagonal of the head-summed map, per head-summed cell; `theta` is
+   * then ignored. Must be below or equal to 1. */
+  float   theta_quantile;
 } ltri_config;
 
 /* Sizes (bytes) of the two device buffers a context needs: `state` holds the index

@@ -188,13 +188,26 @@ def partition_from_kept(kept: Sequence[Tuple[float, int, int]], L: int) -> np.nd
     return np.asarray(sorted(cuts), dtype=np.int64)
 
 
+def map_quantile(M: np.ndarray, q: float) -> float:
+    """The threshold as a percentile of the map (Sec. 4, "Hyperparameter Tuning": the typical
+    theta is the 90th percentile): the value of rank floor(q (n - 1)) among the n cells on and
+    below the diagonal of the head-summed map, in ascending order (nearest rank, no interpolation)."""
+    M = np.asarray(M, np.float64)
+    cells = np.sort(M[np.tril_indices(M.shape[0])])
+    return float(cells[int(math.floor(q * (len(cells) - 1)))])
+
+
 def segment_chunk(K: np.ndarray, Q: Optional[np.ndarray], kind: int, theta: float,
-                  phi: float, max_keep: int = 0, z_perturb: Optional[np.ndarray] = None
-                  ) -> np.ndarray:
-    """Boundaries (chunk-local, first 0, last L) of the spans of one chunk (Sec. 3.4, first step)."""
+                  phi: float, max_keep: int = 0, z_perturb: Optional[np.ndarray] = None,
+                  theta_quantile: float = 0.0) -> np.ndarray:
+    """Boundaries (chunk-local, first 0, last L) of the spans of one chunk (Sec. 3.4, first step).
+    theta_quantile > 0: theta is that percentile of the head-summed map's cells (then `theta` is
+    ignored); the value applies per head-summed cell, i.e. Eq. 5's theta is it over n_h."""
     M, n_h = chunk_map(K, Q, kind)
     if z_perturb is not None:
         M = M * (1.0 + z_perturb)
+    if theta_quantile > 0.0:
+        theta = map_quantile(M, theta_quantile) / n_h
     S = ta_scores(M, theta, n_h)
     cands = antidiagonal_candidates(S)
     kept = nms_1d(cands, phi, max_keep)
@@ -203,16 +216,16 @@ def segment_chunk(K: np.ndarray, Q: Optional[np.ndarray], kind: int, theta: floa
 
 def segmentation_is_stable(K: np.ndarray, Q: Optional[np.ndarray], kind: int, theta: float,
                            phi: float, max_keep: int = 0, rel: float = 2.0 ** -18,
-                           draws: int = 2, seed: int = 0) -> bool:
+                           draws: int = 2, seed: int = 0, theta_quantile: float = 0.0) -> bool:
     """Audit of one chunk: do the boundaries survive relative perturbations of every map
     cell that are ~32x larger than fp32 rounding?  Bit-exact parity with an fp32
     map is only asserted on chunks that pass."""
-    base = segment_chunk(K, Q, kind, theta, phi, max_keep)
+    base = segment_chunk(K, Q, kind, theta, phi, max_keep, theta_quantile=theta_quantile)
     rng = np.random.default_rng(seed)
     L = K.shape[0]
     for _ in range(draws):
         p = rng.uniform(-rel, rel, size=(L, L))
-        b = segment_chunk(K, Q, kind, theta, phi, max_keep, z_perturb=p)
+        b = segment_chunk(K, Q, kind, theta, phi, max_keep, z_perturb=p, theta_quantile=theta_quantile)
         if len(b) != len(base) or np.any(b != base):
             return False
     return True
@@ -401,6 +414,7 @@ class OracleConfig:
     theta: float = 0.0
     phi: float = 0.0
     max_spans_per_chunk: int = 0
+    theta_quantile: float = 0.0   # > 0: theta is this percentile of the chunk's map (theta is ignored)
     rep_mode: int = 0          # REP_MEAN | REP_DYNAMIC
     lam: float = 3.0           # lambda of Eq. 7
     n_min: int = 1             # fewest / most index vectors per span (0 = no upper limit)
@@ -451,7 +465,8 @@ class OracleStream:
                 if q_seg is not None:
                     Qg = np.asarray(q_seg, np.float64)[:, h * c.group:(h + 1) * c.group, :]
                     Qg = np.transpose(Qg, (1, 0, 2))
-                b = segment_chunk(Kc, Qg, c.seg_map, c.theta, c.phi, c.max_spans_per_chunk)
+                b = segment_chunk(Kc, Qg, c.seg_map, c.theta, c.phi, c.max_spans_per_chunk,
+                                  theta_quantile=c.theta_quantile)
             if c.rep_mode == REP_DYNAMIC:
                 Qg = None
                 if q_seg is not None:

@@ -61,6 +61,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   if (!(c.phi >= 0.0f) || !(c.theta == c.theta)) return LTRI_EINVAL;
   if (c.max_spans_per_chunk < 0 || c.max_spans < 0) return LTRI_EINVAL;
   if (c.rep_mode != LTRI_REP_MEAN && c.rep_mode != LTRI_REP_DYNAMIC) return LTRI_EINVAL;
+  if (!(c.theta_quantile >= 0.0f) || c.theta_quantile > 1.0f) return LTRI_EINVAL;
   if (c.rep_mode == LTRI_REP_DYNAMIC &&
       (!(c.lambda >= 0.0f) || c.index_min < 0 || c.index_max < 0 || (c.index_max && c.index_max < c.index_min) ||
        c.ratio_mode < LTRI_RATIO_ROW || c.ratio_mode > LTRI_RATIO_ROWCOL))
@@ -74,6 +75,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   D.max_keep = c.max_spans_per_chunk;
   D.rep_mode = c.rep_mode; D.lambda = (double)c.lambda; D.index_min = c.index_min; D.index_max = c.index_max;
   D.ratio_mode = c.ratio_mode;
+  D.theta_quantile = (double)c.theta_quantile;
   if (c.max_spans > 65536) return LTRI_EINVAL;
   long long ms = c.max_spans ? c.max_spans : std::min<long long>(c.max_tokens / 32 + 64, 65536);
   if (ms > c.max_tokens) ms = c.max_tokens;
@@ -127,6 +129,8 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.att_part = o; o = align_up(o + (size_t)c.n_seqs * c.n_q_heads * ATT_MAX_SPLITS * ATT_SPLIT_MAX_ROWS * (D.d + 2) * 4, 256);
   CL.tokspan = o; o = align_up(o + (size_t)P * Lp * 4, 256);
   CL.dyn = o;     o = align_up(o + (size_t)P * 3 * Lp * 8, 256);
+  CL.qhist = o;   o = align_up(o + (size_t)P * QUANT_BINS * 4, 256);
+  CL.qstate = o;  o = align_up(o + (size_t)P * 4 * 8, 256);
   CL.lpart = o;   o = align_up(o + (c.rep_mode == LTRI_REP_DYNAMIC || c.seg_map == LTRI_MAP_SOFTMAX ? (size_t)P * G * nb * Lp * 16 : 0), 256);
   CL.total = o;
   CL.max_problems = P;
@@ -186,7 +190,8 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
                      (double*)(t + CL.rcar), (double*)(t + CL.ccar), (double*)(t + CL.pscore),
                      (int32_t*)(t + CL.px), (uint64_t*)(t + CL.ckey), (uint32_t*)(t + CL.cxy), (double*)(t + CL.lse), (void*)(t + CL.qrep),
                      (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds), (uint8_t*)(t + CL.selflag), (float*)(t + CL.att_part),
-                     (int32_t*)(t + CL.tokspan), (double*)(t + CL.dyn), (double*)(t + CL.lpart)};
+                     (int32_t*)(t + CL.tokspan), (double*)(t + CL.dyn), (double*)(t + CL.lpart),
+                     (uint32_t*)(t + CL.qhist), (unsigned long long*)(t + CL.qstate)};
   const size_t n = (size_t)D.n_layers * D.n_seqs;
   c->n_tokens.assign(n, 0);
   c->last_len.assign(n, 0);

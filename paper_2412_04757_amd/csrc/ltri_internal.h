@@ -24,6 +24,8 @@ constexpr int SEG_TB = 64;          // side of a segmentation tile
 constexpr int SEG_MAX_L = 2048;     // longest chunk the segmentation kernels take
 constexpr int SEG_MAX_NB = SEG_MAX_L / SEG_TB;
 constexpr int SEG_MAX_DIAG = 2 * SEG_MAX_L;   // anti-diagonals of the largest map (2 L - 1), rounded up
+constexpr int QUANT_BITS = 11;               // digit width of the radix selection of the percentile theta
+constexpr int QUANT_BINS = 1 << QUANT_BITS;
 constexpr int IDX_MASK_WORDS = SEG_MAX_L / 32;   // one bit per token of a chunk
 constexpr int ATT_BN = 64;
 constexpr int ATT_MAX_SPLITS = 8;        // key-range splits of a short query block (decode)
@@ -62,6 +64,8 @@ struct ScratchLayout {
   size_t att_part; // float  [n_seqs][Hq][ATT_MAX_SPLITS][ATT_SPLIT_MAX_ROWS][d + 2]  partial attention results
   size_t tokspan;  // int32  [P][Lp]      span (within the chunk) of every token (dynamic index vectors)
   size_t dyn;      // double [P][3][Lp]   votes, in-span row sums, whole row sums of the softmax map
+  size_t qhist;    // uint32 [P][QUANT_BINS]  histogram of one digit of the map cells' order keys (percentile theta)
+  size_t qstate;   // uint64 [P][4]   key prefix found so far, rank still to go, theta (double bits), unused
   size_t lpart;    // double [P][G][nb][Lp][2]  per tile: row maximum and sum of exponentials (row log-sum-exp in pieces)
   size_t total;
   int    max_problems;  // P the buffer was sized for
@@ -79,6 +83,7 @@ struct Dims {
   int elt;  // bytes per element
   int rep_mode, index_min, index_max, ratio_mode;   // dynamic index vectors (Sec. 3.3.2)
   double lambda;
+  double theta_quantile;                            // > 0: theta is this percentile of the chunk's map
 };
 
 struct BatchPos {            // per-sequence values of one batched call
@@ -94,7 +99,7 @@ struct DevState {
 struct DevScratch {
   double* rowsum; double* csuf; double* tsum; double* rcar; double* ccar;
   double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds; uint8_t* selflag; float* att_part;
-  int32_t* tokspan; double* dyn; double* lpart;
+  int32_t* tokspan; double* dyn; double* lpart; uint32_t* qhist; unsigned long long* qstate;
 };
 
 // ---- launchers (each returns the hipError_t of the launch) ----

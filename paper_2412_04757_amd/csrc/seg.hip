@@ -148,6 +148,84 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
   }
 }
 
+// ---- theta as a percentile of the map (Sec. 4, "Hyperparameter Tuning") ----
+// Exact selection of the cell of a given rank by digits of an order-preserving 64-bit key, most
+// significant digit first: every pass recomputes the tiles, counts the cells that share the key
+// prefix found so far by their next digit (LDS histogram, then integer atomics, so the result does
+// not depend on the order of execution), and a one-workgroup kernel picks the digit that holds the
+// rank. qstate[p] = {prefix, rank still to go, theta as double bits, -}.
+__device__ __forceinline__ uint64_t ascending_key(double v) {
+  const uint64_t u = (uint64_t)__double_as_longlong(v + 0.0);        // -0.0 -> +0.0
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+__device__ __forceinline__ double key_to_double(uint64_t k) {
+  const uint64_t u = (k >> 63) ? (k & 0x7fffffffffffffffull) : ~k;
+  return __longlong_as_double((long long)u);
+}
+__host__ __device__ constexpr int quant_shift(int pass) { return 64 - QUANT_BITS * (pass + 1) > 0 ? 64 - QUANT_BITS * (pass + 1) : 0; }
+__host__ __device__ constexpr int quant_width(int pass) { return 64 - QUANT_BITS * pass >= QUANT_BITS ? QUANT_BITS : 64 - QUANT_BITS * pass; }
+constexpr int QUANT_PASSES = (64 + QUANT_BITS - 1) / QUANT_BITS;
+
+__global__ __launch_bounds__(256) void quant_init_kernel(SegArgs a, unsigned long long rank) {
+  const int p = blockIdx.x;
+  for (int b = threadIdx.x; b < QUANT_BINS; b += blockDim.x) a.sc.qhist[(size_t)p * QUANT_BINS + b] = 0u;
+  if (threadIdx.x == 0) {
+    a.sc.qstate[p * 4 + 0] = 0ull;
+    a.sc.qstate[p * 4 + 1] = rank;
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void quant_hist_kernel(SegArgs a, int pass) {
+  __shared__ double Ms[64 * 65];
+  __shared__ uint32_t hist[QUANT_BINS];
+  const int p = blockIdx.y;
+  int I, J;
+  tile_decode(blockIdx.x, I, J);
+  const int tid = threadIdx.x;
+  for (int b = tid; b < QUANT_BINS; b += blockDim.x) hist[b] = 0u;
+  compute_tile<DT>(a, p, I, J, Ms, a.D.seg_map);
+  __syncthreads();
+  const int shift = quant_shift(pass), width = quant_width(pass);
+  const uint64_t prefix = a.sc.qstate[p * 4 + 0];
+  const int hi = shift + width;                         // bits above the digit are the prefix
+  for (int q = tid; q < 64 * 64; q += blockDim.x) {
+    const int r = q >> 6, c = q & 63;
+    const int y = I * 64 + r, x = J * 64 + c;
+    if (x <= y && y < a.n_new) {
+      const uint64_t k = ascending_key(Ms[r * 65 + c]);
+      const bool match = hi >= 64 || (k >> hi) == (prefix >> hi);
+      if (match) atomicAdd(&hist[(uint32_t)(k >> shift) & ((1u << width) - 1u)], 1u);
+    }
+  }
+  __syncthreads();
+  for (int b = tid; b < QUANT_BINS; b += blockDim.x)
+    if (hist[b]) atomicAdd(&a.sc.qhist[(size_t)p * QUANT_BINS + b], hist[b]);
+}
+
+__global__ __launch_bounds__(256) void quant_pick_kernel(SegArgs a, int pass) {
+  __shared__ uint32_t h[QUANT_BINS];
+  __shared__ unsigned long long part[256];
+  const int p = blockIdx.x, tid = threadIdx.x;
+  constexpr int PER = QUANT_BINS / 256;
+  uint32_t* gh = a.sc.qhist + (size_t)p * QUANT_BINS;
+  unsigned long long mine = 0;
+  for (int e = 0; e < PER; ++e) { h[tid * PER + e] = gh[tid * PER + e]; mine += h[tid * PER + e]; gh[tid * PER + e] = 0u; }
+  part[tid] = mine;
+  __syncthreads();
+  if (tid == 0) {
+    unsigned long long rank = a.sc.qstate[p * 4 + 1], below = 0;
+    int t = 0;
+    while (t < 255 && below + part[t] <= rank) { below += part[t]; ++t; }
+    int b = t * PER;
+    while (b < QUANT_BINS - 1 && below + h[b] <= rank) { below += h[b]; ++b; }
+    const uint64_t prefix = a.sc.qstate[p * 4 + 0] | ((uint64_t)b << quant_shift(pass));
+    a.sc.qstate[p * 4 + 0] = prefix;
+    a.sc.qstate[p * 4 + 1] = rank - below;
+    if (pass == QUANT_PASSES - 1) a.sc.qstate[p * 4 + 2] = (unsigned long long)__double_as_longlong(key_to_double(prefix));
+  }
+}
+
 // ---- pass 1: per-tile row sums, suffix-scanned column sums, total ----
 template <int DT>
 __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
@@ -278,7 +356,9 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
     __syncthreads();
     const int x = J * 64 + c;
     const int n_h = a.q_seg ? a.D.G : 1;
-    const double th = (double)a.D.theta * (double)n_h;
+    // Eq. 5's theta per head, times the heads summed; a percentile of the map is already per summed cell
+    const double th = a.D.theta_quantile > 0.0 ? __longlong_as_double((long long)a.sc.qstate[p * 4 + 2])
+                                               : (double)a.D.theta * (double)n_h;
     double run = cc_pre;
     for (int q2 = 0; q2 < qd; ++q2) run += qsum[c][q2];
 #pragma unroll
@@ -927,6 +1007,16 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
     if (bf) lse_tile_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
     else    lse_tile_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
     lse_reduce_kernel<<<dim3((n_h * a.Lp + 255) / 256, P), 256, 0, s>>>(a);
+  }
+  if (D.theta_quantile > 0.0) {
+    const double n_cells = (double)n_new * (double)(n_new + 1) / 2.0;
+    const unsigned long long rank = (unsigned long long)floor(D.theta_quantile * (n_cells - 1.0));
+    quant_init_kernel<<<P, 256, 0, s>>>(a, rank);
+    for (int pass = 0; pass < QUANT_PASSES; ++pass) {
+      if (bf) quant_hist_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a, pass);
+      else    quant_hist_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a, pass);
+      quant_pick_kernel<<<P, 256, 0, s>>>(a, pass);
+    }
   }
   if (bf) seg_tile_sums_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
   else    seg_tile_sums_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);

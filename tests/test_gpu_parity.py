@@ -39,7 +39,8 @@ def _stream_parity(w, seed, T, device, *, seg_map=O.MAP_LOGIT, theta=None, phi=0
                 if use_q_seg:
                     Qg = np.transpose(qn[:, h * w.group:(h + 1) * w.group], (1, 0, 2))
                 stable = O.segmentation_is_stable(Kn[h, c0:c0 + n], Qg, seg_map, st.cfg.theta, st.cfg.phi,
-                                                  st.cfg.max_spans_per_chunk, rel=2.0 ** -16)
+                                                  st.cfg.max_spans_per_chunk, rel=2.0 ** -16,
+                                                  theta_quantile=st.cfg.theta_quantile)
                 s, l = ctx.get_spans(0, 0, h)
                 assert not stable, (f"chunk at {c0}, head {h}: spans differ on an audited chunk\n"
                                     f"gpu {list(zip(s, l))[-12:]}\noracle {list(zip(st.starts[h], st.lens[h]))[-12:]}")
@@ -339,6 +340,24 @@ def test_dynamic_index_vectors_fp32(gpu_device):
     _, n_partial = _dynamic_stream(gpu_device, w, 2, 1024 + 60, 256, False, decode_steps=2, lam=3.0, ratio_mode=0,
                                    index_max=16)
     assert n_partial >= 6
+
+
+def test_theta_as_a_percentile_of_the_map(gpu_device):
+    """The threshold taken as the 90th (and another) percentile of every chunk's map: exact selection
+    on the device, then the same spans, selections and outputs as the oracle. Softmax map with the
+    paper's typical IoU value, logit map, fp32 and bf16, a ragged last chunk."""
+    w = CONFIGS["cfg1"]
+    _, n_unstable, ctx, st = _stream_parity(w, 2, 1024, gpu_device, seg_map=O.MAP_SOFTMAX, theta=99.0, phi=0.1,
+                                            theta_quantile=0.9, rows=range(0, 256, 17), max_spans=1024)
+    assert n_unstable == 0 and len(st.starts[0]) > 8
+    _, n_unstable, ctx, st = _stream_parity(w, 3, 1024 + 100, gpu_device, theta=99.0, theta_quantile=0.75,
+                                            rows=range(0, 256, 17), max_spans=1024,
+                                            chunk_sizes=[256, 256, 256, 256, 100])
+    assert n_unstable == 0 and len(st.starts[0]) > 8
+    wb = Workload("mini-q", 8, 2, 128, "bf16", 2048, 512, 4, 128, 0, 300, "uniform", 16, 128)
+    _, n_unstable, ctx, st = _stream_parity(wb, 4, 2048, gpu_device, theta=99.0, theta_quantile=0.9,
+                                            rows=range(0, 512, 37), max_spans=2048)
+    assert n_unstable == 0 and len(st.starts[0]) > 8
 
 
 def test_span_table_overflow_is_reported(gpu_device):

@@ -559,6 +559,39 @@ def test_dynamic_index_on_planted_keys_and_in_the_stream():
         assert 1 <= len(tk) <= min(16, ln) and tk.min() >= a and tk.max() < a + ln and np.all(np.diff(tk) > 0)
 
 
+def test_theta_as_a_percentile_of_the_map():
+    """Nearest-rank percentile over the cells on and below the diagonal; closed form on constant keys,
+    where row i of the softmax map holds i + 1 copies of 1 / (i + 1)."""
+    rng = np.random.default_rng(1)
+    M = np.tril(rng.standard_normal((7, 7)))
+    cells = sorted(M[i, j] for i in range(7) for j in range(i + 1))
+    assert len(cells) == 28
+    for q, r in ((1e-9, 0), (0.5, 13), (0.9, 24), (1.0, 27), (0.037, 0), (0.038, 1)):
+        assert O.map_quantile(M, q) == cells[r]
+    assert O.map_quantile(np.tril(np.full((5, 5), 0.25)) + np.triu(np.full((5, 5), 9.0), 1), 0.7) == 0.25
+    L = 60
+    A, _ = O.chunk_map(np.ones((L, 4)), None, O.MAP_SOFTMAX)
+    n = L * (L + 1) // 2
+    for q in (0.1, 0.5, 0.9, 0.99):
+        # ascending order = rows from the last to the first; the cell of rank r lies in row i where
+        # the rows after i hold at most r cells in total
+        r = int(math.floor(q * (n - 1)))
+        below, i = 0, L - 1
+        while below + (i + 1) <= r:
+            below += i + 1
+            i -= 1
+        assert abs(O.map_quantile(A, q) - 1.0 / (i + 1)) < 1e-15
+    # in the segmentation: the same spans as with the absolute value it stands for
+    w = CONFIGS["cfg1"]
+    K, _, _, _ = planted_stream(w, 4, context=256)
+    Kn = K[0].to(torch.float64).numpy()
+    Mm, n_h = O.chunk_map(Kn, None, O.MAP_LOGIT)
+    th = O.map_quantile(Mm, 0.9)
+    a = O.segment_chunk(Kn, None, O.MAP_LOGIT, 123.0, 0.0, theta_quantile=0.9)
+    b = O.segment_chunk(Kn, None, O.MAP_LOGIT, th / n_h, 0.0)
+    assert list(a) == list(b) and len(a) > 2
+
+
 def test_stability_audit_flags_a_planted_near_tie():
     """The audit must reject a chunk whose decision hangs on a near-tie."""
     L = 8
