@@ -288,8 +288,8 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the path has no collective; see DESIGN.md for how it "
-              "would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (the path has no collective: KV heads, sequences and "
+              "layers would shard without any exchange); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
