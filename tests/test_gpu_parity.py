@@ -360,6 +360,39 @@ def test_theta_as_a_percentile_of_the_map(gpu_device):
     assert n_unstable == 0 and len(st.starts[0]) > 8
 
 
+def test_dynamic_index_vectors_batched_sequences(gpu_device):
+    """Six sequences appended in one call (the segmentation scratch holds four at a time): index
+    tokens and stored vectors of the first and the last sequence against the oracle."""
+    w = Workload("mini-dyn-batch", 8, 2, 128, "bf16", 512, 256, 4, 64, 0, 200, "uniform", 16, 96)
+    n_seqs, T, L = 6, 512, 256
+    theta = theta_default(w.head_dim) * 0.35 ** 2
+    cfg = config_from_workload(w, theta=theta, n_layers=1, n_seqs=n_seqs, rep_mode=O.REP_DYNAMIC, lam=3.0)
+    ctx = LtriContext(cfg, gpu_device)
+    ka, va = ctx.arena_views()
+    ocfg = O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.n_sink, w.window,
+                          budget_tokens=w.budget_tokens, theta=float(np.float32(theta)), rep_mode=O.REP_DYNAMIC,
+                          lam=3.0)
+    streams = {}
+    for s in range(n_seqs):
+        K, V, _, _ = planted_stream(w, 23, device=str(gpu_device), context=T, seq=s)
+        K = (K.float() * 0.35).to(K.dtype)
+        ka[0, s, :, :T].copy_(K)
+        va[0, s, :, :T].copy_(V)
+        if s in (0, 5):
+            streams[s] = O.OracleStream(ocfg, K.double().cpu().numpy(), V.double().cpu().numpy())
+    for c0 in range(0, T, L):
+        ctx.append_chunk(0, 0, n_seqs, L)
+        for s, st in streams.items():
+            st.append_chunk(L)
+            for h in range(w.n_kv_heads):
+                sp, ln = ctx.get_spans(0, s, h)
+                assert list(sp) == st.starts[h] and list(ln) == st.lens[h]
+                assert list(ctx.get_index_tokens(0, s, h, L)) == list(np.concatenate(st.last_index_tokens[h]))
+                got = ctx.get_rep_keys(0, s, h).double().numpy()
+                assert np.array_equal(got, np.stack(st.krep[h]))
+    assert ctx.sync_status() == 0
+
+
 def test_span_table_overflow_is_reported(gpu_device):
     w = CONFIGS["cfg1"]
     K, V, Q, _ = planted_stream(w, 1, device=str(gpu_device), context=1024)
