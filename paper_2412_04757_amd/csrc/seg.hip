@@ -666,8 +666,10 @@ __global__ __launch_bounds__(256) void lse_reduce_kernel(SegArgs a) {
   const int g = id / Lp, i = id - g * Lp, B = i / 64;
   const double* pr = a.sc.lpart + (((size_t)p * n_h + g) * nb * Lp + i) * 2;
   double mx = -INFINITY;
+#pragma unroll 8
   for (int J = 0; J <= B; ++J) mx = fmax(mx, pr[(size_t)J * Lp * 2]);
   double sm = 0.0;
+#pragma unroll 8
   for (int J = 0; J <= B; ++J) {
     const double m = pr[(size_t)J * Lp * 2], s2 = pr[(size_t)J * Lp * 2 + 1];
     if (m > -INFINITY) sm += s2 * exp(m - mx);
@@ -745,7 +747,9 @@ __global__ __launch_bounds__(256) void dyn_reduce_kernel(SegArgs a) {
   if (i >= Lp) return;
   const int B = i / 64;
   double v = 0.0, rin = 0.0, rall = 0.0;
+#pragma unroll 8
   for (int I = B; I < nb; ++I) v += a.sc.csuf[((size_t)p * nb + I) * Lp + i];
+#pragma unroll 8
   for (int J = 0; J <= B; ++J) {
     rin += a.sc.rcar[((size_t)p * nb + J) * Lp + i];
     rall += a.sc.rowsum[((size_t)p * nb + J) * Lp + i];
