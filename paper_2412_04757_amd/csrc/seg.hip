@@ -90,8 +90,8 @@ template <> struct TileDot<LTRI_F32> {
 // Leaves the head-summed map tile (rows I*64.., columns J*64..) in Ms[r * 65 + c] as doubles;
 // cells above the diagonal or outside the chunk are 0. Called by all 256 threads; Ms doubles as
 // the staging area of the operands (2 x 16 KB) before the tile values are written.
-template <int DT>
-__device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int J, double* Ms, int kind) {
+template <int DT, int KIND>
+__device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int J, double* Ms) {
   typedef typename Elt<DT>::type T;
   const Dims& D = a.D;
   const int sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
@@ -108,13 +108,13 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
   unsigned char* bbuf = abuf + 16384;
   const double scale = 1.0 / sqrt((double)d);
   const int jcol = J * 64 + wj * 32 + l32;
-  const bool logit = kind == LTRI_MAP_LOGIT;
+  constexpr bool logit = KIND == LTRI_MAP_LOGIT;
   double m[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) m[v] = 0.0;
   f32x16_t acc = {0};
   for (int g = 0; g < n_h; ++g) {
-    if (!logit) {
+    if constexpr (!logit) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[v] = 0.f;
     }
@@ -126,7 +126,7 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
       TileDot<DT>::run(abuf, bbuf, wi * 32, wj * 32, l32, hf, acc);
       __syncthreads();
     }
-    if (!logit) {
+    if constexpr (!logit) {
       const double* lse = a.sc.lse + ((size_t)p * n_h + g) * a.Lp;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -135,7 +135,7 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
       }
     }
   }
-  if (logit) {
+  if constexpr (logit) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) m[v] = (double)acc[v] * scale;
   }
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void quant_init_kernel(SegArgs a, unsigned lon
   }
 }
 
-template <int DT>
+template <int DT, int KIND>
 __global__ __launch_bounds__(256) void quant_hist_kernel(SegArgs a, int pass) {
   __shared__ double Ms[64 * 65];
   __shared__ uint32_t hist[QUANT_BINS];
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void quant_hist_kernel(SegArgs a, int pass) {
   tile_decode(blockIdx.x, I, J);
   const int tid = threadIdx.x;
   for (int b = tid; b < QUANT_BINS; b += blockDim.x) hist[b] = 0u;
-  compute_tile<DT>(a, p, I, J, Ms, a.D.seg_map);
+  compute_tile<DT, KIND>(a, p, I, J, Ms);
   __syncthreads();
   const int shift = quant_shift(pass), width = quant_width(pass);
   const uint64_t prefix = a.sc.qstate[p * 4 + 0];
@@ -227,14 +227,14 @@ __global__ __launch_bounds__(256) void quant_pick_kernel(SegArgs a, int pass) {
 }
 
 // ---- pass 1: per-tile row sums, suffix-scanned column sums, total ----
-template <int DT>
+template <int DT, int KIND>
 __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
   __shared__ double Ms[64 * 65];
   __shared__ double cpart[4][64];
   const int p = blockIdx.y;
   int I, J;
   tile_decode(blockIdx.x, I, J);
-  compute_tile<DT>(a, p, I, J, Ms, a.D.seg_map);
+  compute_tile<DT, KIND>(a, p, I, J, Ms);
   __syncthreads();
   const int tid = threadIdx.x;
   {                                       // row sums: four threads per row, 16 columns each
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(256) void seg_carries_kernel(SegArgs a) {
 }
 
 // ---- pass 3: finish S inside each tile, reduce its anti-diagonals ----
-template <int DT>
+template <int DT, int KIND>
 __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   __shared__ double Ms[64 * 65];
   __shared__ double rc[64];
@@ -325,7 +325,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   // carries are requested before the tile is computed so that their latency hides behind it
   const double rc_pre = tid < 64 ? a.sc.rcar[((size_t)p * a.nb + J) * a.Lp + I * 64 + tid] : 0.0;
   const double cc_pre = a.sc.ccar[((size_t)p * a.nb + I) * a.Lp + J * 64 + (tid & 63)];
-  compute_tile<DT>(a, p, I, J, Ms, a.D.seg_map);
+  compute_tile<DT, KIND>(a, p, I, J, Ms);
   if (tid < 64) rc[tid] = rc_pre;
   __syncthreads();
   {                                     // rows: suffix sums towards the left, four threads per row
@@ -705,7 +705,7 @@ __global__ __launch_bounds__(256) void dyn_tile_kernel(SegArgs a) {
   const int p = blockIdx.y;
   int I, J;
   tile_decode(blockIdx.x, I, J);
-  compute_tile<DT>(a, p, I, J, Ms, LTRI_MAP_SOFTMAX);
+  compute_tile<DT, LTRI_MAP_SOFTMAX>(a, p, I, J, Ms);
   const int tid = threadIdx.x;
   if (tid < 64) rspan[tid] = a.sc.tokspan[(size_t)p * a.Lp + I * 64 + tid];
   else if (tid < 128) cspan[tid - 64] = a.sc.tokspan[(size_t)p * a.Lp + J * 64 + tid - 64];
@@ -1012,21 +1012,28 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
     else    lse_tile_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
     lse_reduce_kernel<<<dim3((n_h * a.Lp + 255) / 256, P), 256, 0, s>>>(a);
   }
-  if (D.theta_quantile > 0.0) {
-    const double n_cells = (double)n_new * (double)(n_new + 1) / 2.0;
-    const unsigned long long rank = (unsigned long long)floor(D.theta_quantile * (n_cells - 1.0));
-    quant_init_kernel<<<P, 256, 0, s>>>(a, rank);
-    for (int pass = 0; pass < QUANT_PASSES; ++pass) {
-      if (bf) quant_hist_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a, pass);
-      else    quant_hist_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a, pass);
-      quant_pick_kernel<<<P, 256, 0, s>>>(a, pass);
+  // one instantiation per element type and map kind
+  auto tiles = [&](auto dt, auto kind) {
+    constexpr int DT = decltype(dt)::value, KIND = decltype(kind)::value;
+    if (D.theta_quantile > 0.0) {
+      const double n_cells = (double)n_new * (double)(n_new + 1) / 2.0;
+      const unsigned long long rank = (unsigned long long)floor(D.theta_quantile * (n_cells - 1.0));
+      quant_init_kernel<<<P, 256, 0, s>>>(a, rank);
+      for (int pass = 0; pass < QUANT_PASSES; ++pass) {
+        quant_hist_kernel<DT, KIND><<<gt, 256, 0, s>>>(a, pass);
+        quant_pick_kernel<<<P, 256, 0, s>>>(a, pass);
+      }
     }
-  }
-  if (bf) seg_tile_sums_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
-  else    seg_tile_sums_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
-  seg_carries_kernel<<<dim3(SEG_CARRY_PARTS, P), 256, 0, s>>>(a);
-  if (bf) seg_tile_scan_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
-  else    seg_tile_scan_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
+    seg_tile_sums_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
+    seg_carries_kernel<<<dim3(SEG_CARRY_PARTS, P), 256, 0, s>>>(a);
+    seg_tile_scan_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
+  };
+  using std::integral_constant;
+  const bool lg = D.seg_map == LTRI_MAP_LOGIT;
+  if (bf && lg)       tiles(integral_constant<int, LTRI_BF16>{}, integral_constant<int, LTRI_MAP_LOGIT>{});
+  else if (bf)        tiles(integral_constant<int, LTRI_BF16>{}, integral_constant<int, LTRI_MAP_SOFTMAX>{});
+  else if (lg)        tiles(integral_constant<int, LTRI_F32>{}, integral_constant<int, LTRI_MAP_LOGIT>{});
+  else                tiles(integral_constant<int, LTRI_F32>{}, integral_constant<int, LTRI_MAP_SOFTMAX>{});
   dim3 gm((2 * n_new - 1 + 255) / 256, P);
   seg_merge_kernel<<<gm, 256, 0, s>>>(a);
   seg_select_kernel<<<P, 1024, 0, s>>>(a);
