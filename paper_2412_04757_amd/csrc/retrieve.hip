@@ -141,6 +141,11 @@ __global__ __launch_bounds__(256) void score_kernel(RetArgs a) {
   double* scores = a.st.scores + (size_t)slot * D.max_spans;
   const int i = blockIdx.x * (blockDim.x / 4) + (threadIdx.x >> 2), part = threadIdx.x & 3;
   const uint4* krow = reinterpret_cast<const uint4*>(krep + (size_t)max(min(i, n - 1), 0) * d);
+  // the lane's pieces of the key are requested before the query representatives are staged
+  constexpr int MAXP = 128 / N / 4;                     // pieces per lane at d = 128
+  uint4 kv[MAXP];
+#pragma unroll
+  for (int q = 0; q < MAXP; ++q) kv[q] = (part + 4 * q < d / N) ? krow[part + 4 * q] : make_uint4(0u, 0u, 0u, 0u);
   double best = -INFINITY;
   for (int j0 = 0; j0 < nqs; j0 += SCORE_QBATCH) {
     const int nj = min(SCORE_QBATCH, nqs - j0);
@@ -150,25 +155,28 @@ __global__ __launch_bounds__(256) void score_kernel(RetArgs a) {
     double acc[SCORE_QBATCH];
 #pragma unroll
     for (int jj = 0; jj < SCORE_QBATCH; ++jj) acc[jj] = 0.0;
-    for (int pc = part; pc < d / N; pc += 4) {
-      const uint4 kv = krow[pc];
-      double k[8];
-      if constexpr (DT == LTRI_BF16) {
-        const uint32_t w[4] = {kv.x, kv.y, kv.z, kv.w};
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          k[2 * u] = (double)__uint_as_float(w[u] << 16);
-          k[2 * u + 1] = (double)__uint_as_float(w[u] & 0xffff0000u);
+    for (int q = 0; q < MAXP; ++q) {
+      const int pc = part + 4 * q;
+      if (pc < d / N) {
+        double k[8];
+        if constexpr (DT == LTRI_BF16) {
+          const uint32_t w[4] = {kv[q].x, kv[q].y, kv[q].z, kv[q].w};
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            k[2 * u] = (double)__uint_as_float(w[u] << 16);
+            k[2 * u + 1] = (double)__uint_as_float(w[u] & 0xffff0000u);
+          }
+        } else {
+          k[0] = (double)__uint_as_float(kv[q].x); k[1] = (double)__uint_as_float(kv[q].y);
+          k[2] = (double)__uint_as_float(kv[q].z); k[3] = (double)__uint_as_float(kv[q].w);
         }
-      } else {
-        k[0] = (double)__uint_as_float(kv.x); k[1] = (double)__uint_as_float(kv.y);
-        k[2] = (double)__uint_as_float(kv.z); k[3] = (double)__uint_as_float(kv.w);
-      }
 #pragma unroll
-      for (int jj = 0; jj < SCORE_QBATCH; ++jj) {
-        if (jj < nj) {
+        for (int jj = 0; jj < SCORE_QBATCH; ++jj) {
+          if (jj < nj) {
 #pragma unroll
-          for (int u = 0; u < N; ++u) acc[jj] = fma(k[u], qs[jj * d + pc * N + u], acc[jj]);
+            for (int u = 0; u < N; ++u) acc[jj] = fma(k[u], qs[jj * d + pc * N + u], acc[jj]);
+          }
         }
       }
     }

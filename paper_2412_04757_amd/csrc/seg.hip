@@ -268,8 +268,9 @@ __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
 }
 
 // ---- pass 2: carries ----
-// One thread per row (row carries) or column (column carries); SEG_CARRY_PARTS workgroups per
-// problem share the rows and columns, each rebuilds the small table of tile-total sums it needs.
+// One thread per row (row carries) or column (column carries); per problem SEG_CARRY_PARTS
+// workgroups share the rows and as many share the columns (they run side by side; each column
+// workgroup rebuilds the small table of tile-total sums it needs).
 constexpr int SEG_CARRY_PARTS = 8;
 __global__ __launch_bounds__(256) void seg_carries_kernel(SegArgs a) {
   __shared__ double TS[SEG_MAX_NB * SEG_MAX_NB];   // TS[I][J] = sum_{J < J' <= I} tsum[I][J']
@@ -279,8 +280,9 @@ __global__ __launch_bounds__(256) void seg_carries_kernel(SegArgs a) {
   const double* tsum = a.sc.tsum + (size_t)p * nb * nb;
   double* rcar = a.sc.rcar + (size_t)p * nb * Lp;
   double* ccar = a.sc.ccar + (size_t)p * nb * Lp;
-  const int first = blockIdx.x * blockDim.x + threadIdx.x, stride = gridDim.x * blockDim.x;
-  for (int i = first; i < Lp; i += stride) {
+  const bool rows = blockIdx.x < SEG_CARRY_PARTS;
+  const int first = (blockIdx.x % SEG_CARRY_PARTS) * blockDim.x + threadIdx.x, stride = SEG_CARRY_PARTS * blockDim.x;
+  for (int i = first; rows && i < Lp; i += stride) {
     const int I = i / 64;
     double v[SEG_MAX_NB];
 #pragma unroll
@@ -291,11 +293,15 @@ __global__ __launch_bounds__(256) void seg_carries_kernel(SegArgs a) {
       if (J <= I) { rcar[(size_t)J * Lp + i] = run; run += v[J]; }
     }
   }
+  if (rows) return;
   for (int I = threadIdx.x; I < nb; I += blockDim.x) {
+    double v[SEG_MAX_NB];
+#pragma unroll
+    for (int J = 0; J < SEG_MAX_NB; ++J) v[J] = (J <= I) ? tsum[I * nb + J] : 0.0;     // loads in flight together
     double run = 0.0;
-    for (int J = I; J >= 0; --J) {
-      TS[I * SEG_MAX_NB + J] = run;
-      run += tsum[I * nb + J];
+#pragma unroll
+    for (int J = SEG_MAX_NB - 1; J >= 0; --J) {
+      if (J <= I) { TS[I * SEG_MAX_NB + J] = run; run += v[J]; }
     }
   }
   __syncthreads();
@@ -1025,7 +1031,7 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
       }
     }
     seg_tile_sums_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
-    seg_carries_kernel<<<dim3(SEG_CARRY_PARTS, P), 256, 0, s>>>(a);
+    seg_carries_kernel<<<dim3(2 * SEG_CARRY_PARTS, P), 256, 0, s>>>(a);
     seg_tile_scan_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
   };
   using std::integral_constant;
