@@ -56,19 +56,47 @@ __global__ __launch_bounds__(1024) void qrep_kernel(RetArgs a) {
 constexpr int QREP_PIECE = 128;
 
 // Piece u of the chunk's spans -> (span q, first token, token count); returns false past the end.
+// Called by whole wavefronts with the same u: the spans' piece counts are scanned 64 at a time
+// across the lanes (one load per lane instead of a serial walk over the table).
 __device__ __forceinline__ bool qrep_unit(const int32_t* slen, int nsp, int u, int& q, int& t0, int& nt) {
-  int acc = 0;
-  for (q = 0; q < nsp; ++q) {
-    const int len = slen[q];
+  const int lane = threadIdx.x & 63;
+  int base = 0;
+  for (int q0 = 0; q0 < nsp; q0 += 64) {
+    const int ql = q0 + lane;
+    const int len = ql < nsp ? slen[ql] : 0;
     const int parts = (len + QREP_PIECE - 1) / QREP_PIECE;
-    if (u < acc + parts) {
-      t0 = (u - acc) * QREP_PIECE;
-      nt = min(QREP_PIECE, len - t0);
+    int incl = parts;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int v = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += v;
+    }
+    const int total = __shfl(incl, 63, 64);
+    if (u < base + total) {
+      const int src = __ffsll((long long)__ballot(u < base + incl)) - 1;    // first span whose pieces reach past u
+      q = q0 + src;
+      t0 = (u - base - __shfl(incl - parts, src, 64)) * QREP_PIECE;
+      nt = min(QREP_PIECE, __shfl(len, src, 64) - t0);
       return true;
     }
-    acc += parts;
+    base += total;
   }
   return false;
+}
+
+// Pieces before span q (same scan).
+__device__ __forceinline__ int qrep_first_unit(const int32_t* slen, int q) {
+  const int lane = threadIdx.x & 63;
+  int base = 0;
+  for (int q0 = 0; q0 < q; q0 += 64) {
+    const int ql = q0 + lane;
+    const int parts = ql < q ? (slen[ql] + QREP_PIECE - 1) / QREP_PIECE : 0;
+    int sum = parts;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    base += sum;
+  }
+  return base;
 }
 
 template <int DT>
@@ -108,8 +136,7 @@ __global__ __launch_bounds__(128) void qrep_final_kernel(RetArgs a) {
   T* out = reinterpret_cast<T*>(a.sc.qrep) + (size_t)(bi * D.Hkv + h) * a.Lp * d;
   if (c >= d) return;
   for (int q = blockIdx.x; q < nsp; q += gridDim.x) {
-    int u0 = 0;
-    for (int q2 = 0; q2 < q; ++q2) u0 += (slen[q2] + QREP_PIECE - 1) / QREP_PIECE;
+    const int u0 = qrep_first_unit(slen, q);
     const int len = slen[q];
     const int parts = (len + QREP_PIECE - 1) / QREP_PIECE;
     double s = 0.0;
