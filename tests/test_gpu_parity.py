@@ -247,7 +247,8 @@ def test_persistent_selection_decode(gpu_device):
     assert ctx.sync_status() == 0
 
 
-def _dynamic_stream(gpu_device, w, seed, T, L, q_seg, key_scale=0.35, given_spans=False, decode_steps=0, **kw):
+def _dynamic_stream(gpu_device, w, seed, T, L, q_seg, key_scale=0.35, given_spans=False, decode_steps=0,
+                    chunk_sizes=None, **kw):
     """Streams T tokens in chunks of L with dynamic index vectors on both sides; index tokens,
     stored vectors, selections and outputs against the oracle on every chunk. The planted keys are
     scaled down (and theta with their square) so that attention leaks out of the spans and the
@@ -259,8 +260,9 @@ def _dynamic_stream(gpu_device, w, seed, T, L, q_seg, key_scale=0.35, given_span
                         theta=theta_default(w.head_dim) * key_scale ** 2, **kw)
     Kn = K.double().cpu().numpy()
     n_audited = n_unstable = n_partial = 0
-    for c0 in range(0, T, L):
-        n = min(L, T - c0)
+    sizes = chunk_sizes or [min(L, T - c0) for c0 in range(0, T, L)]
+    assert sum(sizes) == T
+    for c0, n in zip([int(x) for x in np.cumsum([0] + sizes[:-1])], sizes):
         q = Q[c0:c0 + n].contiguous()
         qn = q.double().cpu().numpy()
         if given_spans:
@@ -391,6 +393,18 @@ def test_dynamic_index_vectors_batched_sequences(gpu_device):
                 got = ctx.get_rep_keys(0, s, h).double().numpy()
                 assert np.array_equal(got, np.stack(st.krep[h]))
     assert ctx.sync_status() == 0
+
+
+def test_dynamic_index_and_percentile_tiny_chunks(gpu_device):
+    """Chunks of 2 to 130 tokens (one tile, spans of one or two tokens, sorts over two slots) with
+    dynamic index vectors, and the percentile threshold on maps of three cells and up."""
+    w = Workload("mini-dyn", 8, 2, 128, "bf16", 1536, 512, 4, 128, 0, 300, "uniform", 16, 128)
+    sizes = [5, 64, 2, 130, 3, 65, 63, 512, 2]
+    _dynamic_stream(gpu_device, w, 8, sum(sizes), 512, False, chunk_sizes=sizes, lam=3.0, ratio_mode=0)
+    _dynamic_stream(gpu_device, w, 9, sum(sizes), 512, False, chunk_sizes=sizes, given_spans=True, lam=2.0, ratio_mode=2,
+                    index_max=8)
+    _stream_parity(w, 10, sum(sizes), gpu_device, theta=99.0, theta_quantile=0.9, chunk_sizes=sizes,
+                   rows=range(0, 512, 41), max_spans=2048)
 
 
 def test_span_table_overflow_is_reported(gpu_device):
