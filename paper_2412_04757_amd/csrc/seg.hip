@@ -371,7 +371,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
     for (int r = 0; r < 16; ++r) {
       const int rl = qd * 16 + r, y = I * 64 + rl;
       run += w[r];
-      const long long n = (long long)y - x + 1;
+      const int n = y - x + 1;                                      // |n| <= 2048: n (n + 1) / 2 fits 32 bits
       const double sv = run - th * (double)(n * (n + 1) / 2);       // Eq. 5
       Ms[rl * 65 + c] = (x <= y && y < L) ? sv : -INFINITY;
     }
