@@ -285,6 +285,9 @@ def main():
     ap.add_argument("--theta-quantile", type=float, default=0.0,
                     help="take theta as this percentile of every chunk's map (e.g. 0.9) instead of the absolute\n"
                          "value; not the headline configuration")
+    ap.add_argument("--unit-tokens", type=int, default=0,
+                    help="retrieve whole memory units of this many tokens (Eq. 9 as written) instead of spans;\n"
+                         "not the headline configuration")
     ap.add_argument("--seed", type=int, default=1)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -323,7 +326,7 @@ def main():
     log(f"[bench] inputs generated in {time.time() - t0:.1f}s")
     cfg = config_from_workload(w, theta=theta, n_layers=1, n_seqs=1,
                                rep_mode=1 if args.index_vectors == "dynamic" else 0, lam=3.0,
-                               theta_quantile=args.theta_quantile)
+                               theta_quantile=args.theta_quantile, unit_tokens=args.unit_tokens)
     ctx = LtriContext(cfg, dev)
     ka, va = ctx.arena_views()
     ka[0, 0].copy_(K)
@@ -462,6 +465,7 @@ def main():
                    "step": "one full stream through one layer (append + retrieve + attend per chunk)",
                    "seg_map": "logit", "theta": theta if not args.theta_quantile else f"percentile {args.theta_quantile}",
                    "phi": 0.0,
+                   "retrieval_unit": "span" if not args.unit_tokens else f"memory units of {args.unit_tokens} tokens",
                    "index_vectors": "mean key per span" if args.index_vectors == "mean"
                    else "dynamic (row ratio, lambda 3): sum of the keys of each span's index tokens",
                    "schedule": "append(c+1) on a second stream next to attend(c)" if overlap else "serial"},

@@ -100,6 +100,13 @@ typedef struct {
    * cells on and below the diagonal of the head-summed map, per head-summed cell; `theta` is
    * then ignored. Must be below or equal to 1. */
   float   theta_quantile;
+  /* > 0: retrieval by memory units as in Eq. 9. The stream is cut into units (blocks) of this
+   * many tokens at absolute positions; spans are also cut at unit edges, a unit scores the
+   * maximum over its spans, and step 2 orders units by (-score, id) and takes the longest prefix
+   * within k_max units and budget_tokens evicted tokens; selections (sel_ids, forced and
+   * persistent ones) then hold unit ids and the context set holds whole units' evicted parts.
+   * At most chunk_max, and max_tokens / unit_tokens + 1 <= 8192. 0: spans are retrieved. */
+  int32_t unit_tokens;
 } ltri_config;
 
 /* Sizes (bytes) of the two device buffers a context needs: `state` holds the index

@@ -179,12 +179,18 @@ def nms_1d(cands: Sequence[Tuple[float, int, int]], phi: float,
     return kept
 
 
-def partition_from_kept(kept: Sequence[Tuple[float, int, int]], L: int) -> np.ndarray:
-    """Cut [0, L) at every kept interval's x and y+1; returns the sorted cuts incl. 0 and L."""
+def partition_from_kept(kept: Sequence[Tuple[float, int, int]], L: int, unit: int = 0, c0: int = 0
+                        ) -> np.ndarray:
+    """Cut [0, L) at every kept interval's x and y+1; returns the sorted cuts incl. 0 and L.
+    unit > 0: the chunk starts at absolute position c0 and is also cut wherever a memory unit of
+    `unit` tokens ends, so that every span lies inside one unit (Eq. 9 speaks of the spans of
+    block b)."""
     cuts = {0, L}
     for (_, x, y) in kept:
         cuts.add(x)
         cuts.add(y + 1)
+    if unit > 0:
+        cuts.update(i for i in range(1, L) if (c0 + i) % unit == 0)
     return np.asarray(sorted(cuts), dtype=np.int64)
 
 
@@ -199,7 +205,7 @@ def map_quantile(M: np.ndarray, q: float) -> float:
 
 def segment_chunk(K: np.ndarray, Q: Optional[np.ndarray], kind: int, theta: float,
                   phi: float, max_keep: int = 0, z_perturb: Optional[np.ndarray] = None,
-                  theta_quantile: float = 0.0) -> np.ndarray:
+                  theta_quantile: float = 0.0, unit: int = 0, c0: int = 0) -> np.ndarray:
     """Boundaries (chunk-local, first 0, last L) of the spans of one chunk (Sec. 3.4, first step).
     theta_quantile > 0: theta is that percentile of the head-summed map's cells (then `theta` is
     ignored); the value applies per head-summed cell, i.e. Eq. 5's theta is it over n_h."""
@@ -211,21 +217,23 @@ def segment_chunk(K: np.ndarray, Q: Optional[np.ndarray], kind: int, theta: floa
     S = ta_scores(M, theta, n_h)
     cands = antidiagonal_candidates(S)
     kept = nms_1d(cands, phi, max_keep)
-    return partition_from_kept(kept, K.shape[0])
+    return partition_from_kept(kept, K.shape[0], unit, c0)
 
 
 def segmentation_is_stable(K: np.ndarray, Q: Optional[np.ndarray], kind: int, theta: float,
                            phi: float, max_keep: int = 0, rel: float = 2.0 ** -18,
-                           draws: int = 2, seed: int = 0, theta_quantile: float = 0.0) -> bool:
+                           draws: int = 2, seed: int = 0, theta_quantile: float = 0.0,
+                           unit: int = 0, c0: int = 0) -> bool:
     """Audit of one chunk: do the boundaries survive relative perturbations of every map
     cell that are ~32x larger than fp32 rounding?  Bit-exact parity with an fp32
     map is only asserted on chunks that pass."""
-    base = segment_chunk(K, Q, kind, theta, phi, max_keep, theta_quantile=theta_quantile)
+    base = segment_chunk(K, Q, kind, theta, phi, max_keep, theta_quantile=theta_quantile, unit=unit, c0=c0)
     rng = np.random.default_rng(seed)
     L = K.shape[0]
     for _ in range(draws):
         p = rng.uniform(-rel, rel, size=(L, L))
-        b = segment_chunk(K, Q, kind, theta, phi, max_keep, z_perturb=p, theta_quantile=theta_quantile)
+        b = segment_chunk(K, Q, kind, theta, phi, max_keep, z_perturb=p, theta_quantile=theta_quantile,
+                          unit=unit, c0=c0)
         if len(b) != len(base) or np.any(b != base):
             return False
     return True
@@ -365,6 +373,24 @@ def select_spans(scores: np.ndarray, clip_len: np.ndarray, eligible: np.ndarray,
     return np.asarray(sorted(sel), dtype=np.int64)
 
 
+def select_units(span_scores: np.ndarray, starts: np.ndarray, unit: int, n_tokens: int, n_sink: int,
+                 win_start: int, k_max: int, budget_tokens: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Eq. 9 as written: the stream is cut into memory units (blocks) of `unit` tokens, a unit
+    scores the maximum over its spans (a span belongs to the unit its first token lies in), and
+    the top units are retrieved whole: units whose part in the evicted region [n_sink,
+    win_start) is not empty, by (-score, id), the longest prefix with at most k_max units and at
+    most budget_tokens evicted tokens. Returns (selected unit ids ascending, score of every unit)."""
+    n_units = (n_tokens + unit - 1) // unit
+    uscore = np.full(n_units, -np.inf)
+    for s, a in zip(span_scores, starts):
+        u = int(a) // unit
+        uscore[u] = max(uscore[u], float(s))
+    lo = np.maximum(np.arange(n_units) * unit, n_sink)
+    hi = np.minimum(np.minimum((np.arange(n_units) + 1) * unit, n_tokens), win_start)
+    sel = select_spans(uscore, hi - lo, lo < hi, k_max, budget_tokens)
+    return sel, uscore
+
+
 # ----------------------------------------------------------------------------
 # exact attention over an explicit key set (Sec. 3.4, third step)
 # ----------------------------------------------------------------------------
@@ -415,6 +441,7 @@ class OracleConfig:
     phi: float = 0.0
     max_spans_per_chunk: int = 0
     theta_quantile: float = 0.0   # > 0: theta is this percentile of the chunk's map (theta is ignored)
+    unit_tokens: int = 0          # > 0: retrieval by memory units of this many tokens (Eq. 9), spans cut at their edges
     rep_mode: int = 0          # REP_MEAN | REP_DYNAMIC
     lam: float = 3.0           # lambda of Eq. 7
     n_min: int = 1             # fewest / most index vectors per span (0 = no upper limit)
@@ -466,7 +493,7 @@ class OracleStream:
                     Qg = np.asarray(q_seg, np.float64)[:, h * c.group:(h + 1) * c.group, :]
                     Qg = np.transpose(Qg, (1, 0, 2))
                 b = segment_chunk(Kc, Qg, c.seg_map, c.theta, c.phi, c.max_spans_per_chunk,
-                                  theta_quantile=c.theta_quantile)
+                                  theta_quantile=c.theta_quantile, unit=c.unit_tokens, c0=c0)
             if c.rep_mode == REP_DYNAMIC:
                 Qg = None
                 if q_seg is not None:
@@ -508,7 +535,11 @@ class OracleStream:
             a, b = clipped_ranges(starts, lens, min(c.n_sink, c0), ws)
             eligible = a < b
             scores = span_scores(Qrep, np.stack(self.krep[h]))
-            sel = select_spans(scores, b - a, eligible, c.k_max, c.budget_tokens)
+            if c.unit_tokens > 0:
+                sel, _ = select_units(scores, starts, c.unit_tokens, c0 + L, min(c.n_sink, c0), ws, c.k_max,
+                                      c.budget_tokens)
+            else:
+                sel = select_spans(scores, b - a, eligible, c.k_max, c.budget_tokens)
             self.sel[h] = sel
             self.sel_scores[h] = scores
             out.append(sel)
@@ -532,8 +563,12 @@ class OracleStream:
         ws = self.win_start(c0)
         parts = [np.arange(0, n_sink)]
         for i in self.sel[h]:
-            a = max(self.starts[h][i], n_sink)
-            b = min(self.starts[h][i] + self.lens[h][i], ws)
+            if c.unit_tokens > 0:                          # the selection holds unit ids
+                a = max(int(i) * c.unit_tokens, n_sink)
+                b = min((int(i) + 1) * c.unit_tokens, ws)
+            else:
+                a = max(self.starts[h][i], n_sink)
+                b = min(self.starts[h][i] + self.lens[h][i], ws)
             if a < b:
                 parts.append(np.arange(a, b))
         parts.append(np.arange(ws, c0))

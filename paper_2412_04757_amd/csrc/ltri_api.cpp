@@ -62,6 +62,8 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   if (c.max_spans_per_chunk < 0 || c.max_spans < 0) return LTRI_EINVAL;
   if (c.rep_mode != LTRI_REP_MEAN && c.rep_mode != LTRI_REP_DYNAMIC) return LTRI_EINVAL;
   if (!(c.theta_quantile >= 0.0f) || c.theta_quantile > 1.0f) return LTRI_EINVAL;
+  if (c.unit_tokens < 0 || c.unit_tokens > c.chunk_max) return LTRI_EINVAL;
+  if (c.unit_tokens > 0 && c.max_tokens / c.unit_tokens + 1 > 8192) return LTRI_EINVAL;
   if (c.rep_mode == LTRI_REP_DYNAMIC &&
       (!(c.lambda >= 0.0f) || c.index_min < 0 || c.index_max < 0 || (c.index_max && c.index_max < c.index_min) ||
        c.ratio_mode < LTRI_RATIO_ROW || c.ratio_mode > LTRI_RATIO_ROWCOL))
@@ -76,6 +78,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   D.rep_mode = c.rep_mode; D.lambda = (double)c.lambda; D.index_min = c.index_min; D.index_max = c.index_max;
   D.ratio_mode = c.ratio_mode;
   D.theta_quantile = (double)c.theta_quantile;
+  D.unit = c.unit_tokens;
   if (c.max_spans > 65536) return LTRI_EINVAL;
   long long ms = c.max_spans ? c.max_spans : std::min<long long>(c.max_tokens / 32 + 64, 65536);
   if (ms > c.max_tokens) ms = c.max_tokens;

@@ -84,6 +84,7 @@ struct Dims {
   int rep_mode, index_min, index_max, ratio_mode;   // dynamic index vectors (Sec. 3.3.2)
   double lambda;
   double theta_quantile;                            // > 0: theta is this percentile of the chunk's map
+  int unit;                                         // > 0: retrieval by memory units of this many tokens (Eq. 9)
 };
 
 struct BatchPos {            // per-sequence values of one batched call

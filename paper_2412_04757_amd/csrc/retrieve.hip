@@ -226,8 +226,27 @@ __device__ __forceinline__ void clip_span(const Dims& D, int c0, int start, int 
   b = min(start + len, ws);
 }
 
-// Given the selection as a bit mask over span ids, writes the ascending id list, the token
-// list and their lengths. Called by all 1024 threads of the block.
+// Items a selection ranges over: the stored spans, or (retrieval by memory units) the units that
+// hold the tokens stored so far.
+__device__ __forceinline__ int item_count(const Dims& D, const int32_t* meta) {
+  if (D.unit > 0) return (meta[META_CHUNK_START] + meta[META_CHUNK_LEN] + D.unit - 1) / D.unit;
+  return meta[META_N_SPANS];
+}
+
+// Token range of item i of the selection: a stored span, or (retrieval by memory units) unit i.
+__device__ __forceinline__ void item_range(const Dims& D, const int32_t* sstart, const int32_t* slen,
+                                           int n_tokens, int i, int& start, int& len) {
+  if (D.unit > 0) {
+    start = i * D.unit;
+    len = min(D.unit, n_tokens - start);
+  } else {
+    start = sstart[i];
+    len = slen[i];
+  }
+}
+
+// Given the selection as a bit mask over item ids (spans, or units), writes the ascending id list,
+// the token list and their lengths. Called by all 1024 threads of the block.
 constexpr int EMIT_CAP = 2048;     // selected spans whose tokens are written cooperatively
 
 __device__ void emit_selection(const Dims& D, const DevState& st, int slot, const uint32_t* selmask,
@@ -249,7 +268,11 @@ __device__ void emit_selection(const Dims& D, const DevState& st, int slot, cons
     const int i = i0 + tid;
     const bool f = i < n && ((selmask[i >> 5] >> (i & 31)) & 1u);
     int a = 0, b = 0;
-    if (f) clip_span(D, c0, sstart[i], slen[i], a, b);
+    if (f) {
+      int start, len;
+      item_range(D, sstart, slen, c0 + meta[META_CHUNK_LEN], i, start, len);
+      clip_span(D, c0, start, len, a, b);
+    }
     const int w = f ? max(b - a, 0) : 0;
     // wave-level inclusive scans of (flag, tokens)
     int cs = f ? 1 : 0, ts = w;
@@ -417,6 +440,97 @@ __host__ __device__ constexpr int rt1_pow2(int n) { int m = 64; while (m < n) m 
 // dynamic LDS: keys, ids, clipped lengths
 __host__ __device__ constexpr size_t rt1_lds_bytes(int bound) { return (size_t)rt1_pow2(bound) * 12 + (size_t)bound * 4; }
 
+// The selection rule by sorting (one workgroup of 1024 threads): skey / sidx[0..npow) hold the order
+// keys and ids of the eligible items (the others and the padding: key ~0, id RT1_PAD), clip[id]
+// their clipped lengths; npow is a power of two. Items are sorted by (key, id), the clipped
+// lengths are scanned in that order, and the longest prefix within k_max items and the token
+// budget is marked in selmask (zeroed by the caller). wave_tot: 16 words of LDS.
+__device__ void select_sorted_prefix(const Dims& D, uint64_t* skey, uint32_t* sidx, const int* clip, int npow,
+                                     uint32_t* selmask, long long* wave_tot) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // bitonic network, ascending in (key, id)
+  if (npow <= (int)blockDim.x) {
+    // one position per thread, held in registers; partners at distance < 64 are reached by lane
+    // exchanges on the vector ALU, the others through LDS
+    const bool live = tid < npow;
+    uint64_t key = live ? skey[tid] : ~0ull;
+    uint32_t id = live ? sidx[tid] : RT1_PAD;
+    // (key, id) pairs are distinct apart from the padding, whose copies are interchangeable
+    auto merge = [&](int k, int j, uint64_t pk, uint32_t pid) {
+      const bool keep_less = ((tid & j) == 0) == ((tid & k) == 0);
+      const bool take = key_less(pk, pid, key, id) == keep_less;
+      key = take ? pk : key;
+      id = take ? pid : id;
+    };
+    auto lanes = [&](int k, auto jc) {
+      constexpr int J = decltype(jc)::value;
+      const uint32_t lo = lane_xor_c<J>((uint32_t)key), hi = lane_xor_c<J>((uint32_t)(key >> 32));
+      merge(k, J, ((uint64_t)hi << 32) | lo, lane_xor_c<J>(id));
+    };
+    using std::integral_constant;
+    for (int k = 2; k <= npow; k <<= 1) {
+      for (int j = k >> 1; j >= 64; j >>= 1) {
+        __syncthreads();
+        if (live) { skey[tid] = key; sidx[tid] = id; }
+        __syncthreads();
+        if (live) merge(k, j, skey[tid ^ j], sidx[tid ^ j]);
+      }
+      if (k >= 64) lanes(k, integral_constant<int, 32>{});
+      if (k >= 32) lanes(k, integral_constant<int, 16>{});
+      if (k >= 16) lanes(k, integral_constant<int, 8>{});
+      if (k >= 8) lanes(k, integral_constant<int, 4>{});
+      if (k >= 4) lanes(k, integral_constant<int, 2>{});
+      lanes(k, integral_constant<int, 1>{});
+    }
+    __syncthreads();
+    if (live) { skey[tid] = key; sidx[tid] = id; }
+    __syncthreads();
+  } else {
+    for (int k = 2; k <= npow; k <<= 1) {
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        for (int t = tid; t < npow / 2; t += blockDim.x) {
+          const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+          const uint64_t ka = skey[lo], kb = skey[hi];
+          const uint32_t ia = sidx[lo], ib = sidx[hi];
+          const bool a_after_b = (ka > kb) | ((ka == kb) & (ia > ib));
+          if (a_after_b == ((lo & k) == 0)) {
+            skey[lo] = kb; skey[hi] = ka;
+            sidx[lo] = ib; sidx[hi] = ia;
+          }
+        }
+        __syncthreads();
+      }
+    }
+  }
+  // clipped tokens up to and including each position of the order; the prefix that fits is selected
+  const int E = max(npow / (int)blockDim.x, 1);           // consecutive positions per thread
+  long long mine = 0;
+  for (int e = 0; e < E; ++e) {
+    const int r = tid * E + e;
+    const uint32_t id = r < npow ? sidx[r] : RT1_PAD;
+    mine += id != RT1_PAD ? clip[id] : 0;
+  }
+  long long incl = mine;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const long long v = __shfl_up(incl, o, 64);
+    if (lane >= o) incl += v;
+  }
+  if (lane == 63) wave_tot[wave] = incl;
+  __syncthreads();
+  long long cum = incl - mine;
+  for (int w2 = 0; w2 < wave; ++w2) cum += wave_tot[w2];
+  for (int e = 0; e < E; ++e) {
+    const int r = tid * E + e;
+    const uint32_t id = r < npow ? sidx[r] : RT1_PAD;
+    if (id != RT1_PAD) {
+      cum += clip[id];
+      const bool sel = (D.k_max == 0 || r < D.k_max) && (D.budget == 0 || cum <= D.budget);
+      if (sel) atomicOr(&selmask[id >> 5], 1u << (id & 31));
+    }
+  }
+}
+
 template <int DT>
 __global__ __launch_bounds__(1024) void retrieve_one_token_kernel(RetArgs a, int bound) {
   typedef typename Elt<DT>::type T;
@@ -510,87 +624,54 @@ __global__ __launch_bounds__(1024) void retrieve_one_token_kernel(RetArgs a, int
     }
   }
   __syncthreads();
-  // bitonic network, ascending in (key, id)
-  if (npow <= (int)blockDim.x) {
-    // one position per thread, held in registers; partners at distance < 64 are reached by lane
-    // exchanges on the vector ALU, the others through LDS
-    const bool live = tid < npow;
-    uint64_t key = live ? skey[tid] : ~0ull;
-    uint32_t id = live ? sidx[tid] : RT1_PAD;
-    // (key, id) pairs are distinct apart from the padding, whose copies are interchangeable
-    auto merge = [&](int k, int j, uint64_t pk, uint32_t pid) {
-      const bool keep_less = ((tid & j) == 0) == ((tid & k) == 0);
-      const bool take = key_less(pk, pid, key, id) == keep_less;
-      key = take ? pk : key;
-      id = take ? pid : id;
-    };
-    auto lanes = [&](int k, auto jc) {
-      constexpr int J = decltype(jc)::value;
-      const uint32_t lo = lane_xor_c<J>((uint32_t)key), hi = lane_xor_c<J>((uint32_t)(key >> 32));
-      merge(k, J, ((uint64_t)hi << 32) | lo, lane_xor_c<J>(id));
-    };
-    using std::integral_constant;
-    for (int k = 2; k <= npow; k <<= 1) {
-      for (int j = k >> 1; j >= 64; j >>= 1) {
-        __syncthreads();
-        if (live) { skey[tid] = key; sidx[tid] = id; }
-        __syncthreads();
-        if (live) merge(k, j, skey[tid ^ j], sidx[tid ^ j]);
-      }
-      if (k >= 64) lanes(k, integral_constant<int, 32>{});
-      if (k >= 32) lanes(k, integral_constant<int, 16>{});
-      if (k >= 16) lanes(k, integral_constant<int, 8>{});
-      if (k >= 8) lanes(k, integral_constant<int, 4>{});
-      if (k >= 4) lanes(k, integral_constant<int, 2>{});
-      lanes(k, integral_constant<int, 1>{});
-    }
-    __syncthreads();
-    if (live) { skey[tid] = key; sidx[tid] = id; }
-    __syncthreads();
-  } else {
-    for (int k = 2; k <= npow; k <<= 1) {
-      for (int j = k >> 1; j > 0; j >>= 1) {
-        for (int t = tid; t < npow / 2; t += blockDim.x) {
-          const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
-          const uint64_t ka = skey[lo], kb = skey[hi];
-          const uint32_t ia = sidx[lo], ib = sidx[hi];
-          const bool a_after_b = (ka > kb) | ((ka == kb) & (ia > ib));
-          if (a_after_b == ((lo & k) == 0)) {
-            skey[lo] = kb; skey[hi] = ka;
-            sidx[lo] = ib; sidx[hi] = ia;
-          }
-        }
-        __syncthreads();
-      }
-    }
-  }
-  // clipped tokens up to and including each position of the order; the prefix that fits is selected
-  const int E = max(npow / (int)blockDim.x, 1);           // consecutive positions per thread
-  long long mine = 0;
-  for (int e = 0; e < E; ++e) {
-    const int r = tid * E + e;
-    const uint32_t id = r < npow ? sidx[r] : RT1_PAD;
-    mine += id != RT1_PAD ? clip[id] : 0;
-  }
-  long long incl = mine;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const long long v = __shfl_up(incl, o, 64);
-    if (lane >= o) incl += v;
-  }
-  if (lane == 63) wave_tot[wave] = incl;
+  select_sorted_prefix(D, skey, sidx, clip, npow, selmask, wave_tot);
   __syncthreads();
-  long long cum = incl - mine;
-  for (int w2 = 0; w2 < wave; ++w2) cum += wave_tot[w2];
-  for (int e = 0; e < E; ++e) {
-    const int r = tid * E + e;
-    const uint32_t id = r < npow ? sidx[r] : RT1_PAD;
-    if (id != RT1_PAD) {
-      cum += clip[id];
-      const bool sel = (D.k_max == 0 || r < D.k_max) && (D.budget == 0 || cum <= D.budget);
-      if (sel) atomicOr(&selmask[id >> 5], 1u << (id & 31));
+  int32_t* ids_out = a.sel_ids_out ? a.sel_ids_out + (size_t)p * D.sel_cap : nullptr;
+  int32_t* cnt_out = a.sel_cnt_out ? a.sel_cnt_out + p : nullptr;
+  emit_selection(D, a.st, slot, selmask, n, ids_out, cnt_out);
+}
+
+// ---- retrieval by memory units (Eq. 9 as written): a unit scores the maximum over its spans; the
+//      top units within k_max and the token budget are retrieved whole. One workgroup per
+//      (sequence, KV head); the spans' scores are already in place. ----
+__global__ __launch_bounds__(1024) void unit_select_kernel(RetArgs a, int unit_bound) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char rt1_lds[];
+  __shared__ uint32_t selmask[RT1_MAX_SPANS / 32 + 2];
+  __shared__ long long wave_tot[16];
+  const Dims& D = a.D;
+  const int p = blockIdx.x, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int n_spans = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
+  const int n_tokens = c0 + meta[META_CHUNK_LEN];
+  const int n = min(item_count(D, meta), unit_bound);
+  const int npow = rt1_pow2(n), tid = threadIdx.x;
+  uint64_t* skey = reinterpret_cast<uint64_t*>(rt1_lds);
+  uint32_t* sidx = reinterpret_cast<uint32_t*>(rt1_lds + (size_t)rt1_pow2(unit_bound) * 8);
+  int* clip = reinterpret_cast<int*>(rt1_lds + (size_t)rt1_pow2(unit_bound) * 12);
+  const double* scores = a.st.scores + (size_t)slot * D.max_spans;
+  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
+  for (int w = tid; w < (n + 31) / 32 + 2; w += blockDim.x) selmask[w] = 0u;
+  for (int u = tid; u < npow; u += blockDim.x) {
+    int c = 0;
+    double best = -INFINITY;
+    if (u < n) {
+      int lo, hi;
+      clip_span(D, c0, u * D.unit, min(D.unit, n_tokens - u * D.unit), lo, hi);
+      c = max(hi - lo, 0);
+      if (c > 0) {
+        // spans are stored in stream order: the unit's spans start in [u unit, (u + 1) unit)
+        int first = 0, last = n_spans;
+        while (first < last) { const int mid = (first + last) >> 1; if (sstart[mid] < u * D.unit) first = mid + 1; else last = mid; }
+        for (int i = first; i < n_spans && sstart[i] < (u + 1) * D.unit; ++i) best = fmax(best, scores[i]);
+      }
+      clip[u] = c;
     }
+    skey[u] = c > 0 ? score_key(best) : ~0ull;
+    sidx[u] = c > 0 ? (uint32_t)u : RT1_PAD;
   }
+  __syncthreads();
+  select_sorted_prefix(D, skey, sidx, clip, npow, selmask, wave_tot);
   __syncthreads();
   int32_t* ids_out = a.sel_ids_out ? a.sel_ids_out + (size_t)p * D.sel_cap : nullptr;
   int32_t* cnt_out = a.sel_cnt_out ? a.sel_cnt_out + p : nullptr;
@@ -605,7 +686,8 @@ __global__ __launch_bounds__(1024) void force_list_kernel(ForceArgs a) {
   const Dims& D = a.D;
   const int slot = slot_of(D, a.layer, a.seq, a.h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
-  const int n = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
+  const int c0 = meta[META_CHUNK_START];
+  const int n = item_count(D, meta);
   const int tid = threadIdx.x;
   for (int w = tid; w < (n + 31) / 32; w += blockDim.x) selmask[w] = 0u;
   __syncthreads();
@@ -613,9 +695,10 @@ __global__ __launch_bounds__(1024) void force_list_kernel(ForceArgs a) {
   for (int k = tid; k < a.n_ids; k += blockDim.x) {
     const int i = ids[k];
     if (i >= 0 && i < n) {
-      int lo, hi;
-      clip_span(D, c0, a.st.span_start[(size_t)slot * D.max_spans + i],
-                a.st.span_len[(size_t)slot * D.max_spans + i], lo, hi);
+      int start, len, lo, hi;
+      item_range(D, a.st.span_start + (size_t)slot * D.max_spans, a.st.span_len + (size_t)slot * D.max_spans,
+                 c0 + meta[META_CHUNK_LEN], i, start, len);
+      clip_span(D, c0, start, len, lo, hi);
       if (hi > lo) atomicOr(&selmask[i >> 5], 1u << (i & 31));
     }
   }
@@ -633,7 +716,7 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
   const int P = seq_count * D.Hkv;
   const bool bf = D.dtype == LTRI_BF16;
   a.batch_off = 0;
-  if (n_q == 1 && span_bound >= 1 && span_bound <= RT1_MAX_SPANS && D.d == 128) {
+  if (n_q == 1 && span_bound >= 1 && span_bound <= RT1_MAX_SPANS && D.d == 128 && D.unit == 0) {
     // decode: the whole step in one launch
     static bool attr_set = false;
     if (!attr_set) {
@@ -672,6 +755,18 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
   const size_t qs_bytes = (size_t)SCORE_QBATCH * D.d * sizeof(double);
   if (bf) score_kernel<LTRI_BF16><<<gs, 256, qs_bytes, s>>>(a);
   else    score_kernel<LTRI_F32><<<gs, 256, qs_bytes, s>>>(a);
+  if (D.unit > 0) {
+    const int unit_bound = (int)(D.max_tokens / D.unit) + 1;           // units a full stream has, at most
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&unit_select_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)rt1_lds_bytes(RT1_MAX_SPANS));
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+    unit_select_kernel<<<P, 1024, rt1_lds_bytes(unit_bound), s>>>(a, unit_bound);
+    return hipGetLastError();
+  }
   int gr = (span_bound + SEL_SPANS_PER_BLOCK - 1) / SEL_SPANS_PER_BLOCK;
   if (gr < 1) gr = 1;
   select_rank_kernel<<<dim3(gr, P), 256, 0, s>>>(a);
@@ -687,7 +782,8 @@ __global__ __launch_bounds__(1024) void persist_list_kernel(RetArgs a) {
   const int p = blockIdx.x, bi = p / D.Hkv, h = p - bi * D.Hkv;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
-  const int n = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
+  const int c0 = meta[META_CHUNK_START];
+  const int n = item_count(D, meta);
   const int cnt = min(meta[META_SEL_CNT], D.sel_cap);
   const int tid = threadIdx.x;
   for (int w = tid; w < (n + 31) / 32; w += blockDim.x) selmask[w] = 0u;
@@ -696,9 +792,10 @@ __global__ __launch_bounds__(1024) void persist_list_kernel(RetArgs a) {
   for (int k = tid; k < cnt; k += blockDim.x) {
     const int i = ids[k];
     if (i >= 0 && i < n) {
-      int lo, hi;
-      clip_span(D, c0, a.st.span_start[(size_t)slot * D.max_spans + i],
-                a.st.span_len[(size_t)slot * D.max_spans + i], lo, hi);
+      int start, len, lo, hi;
+      item_range(D, a.st.span_start + (size_t)slot * D.max_spans, a.st.span_len + (size_t)slot * D.max_spans,
+                 c0 + meta[META_CHUNK_LEN], i, start, len);
+      clip_span(D, c0, start, len, lo, hi);
       if (hi > lo) atomicOr(&selmask[i >> 5], 1u << (i & 31));
     }
   }

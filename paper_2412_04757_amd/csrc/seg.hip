@@ -552,8 +552,9 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
       e1[r] = kill ? ~0ull : e1[r];
     }
   }
-  // cuts: 0, L and both ends of every kept interval
-  for (int i = tid; i <= L; i += blockDim.x) flags[i] = (i == 0 || i == L) ? 1 : 0;
+  // cuts: 0, L, both ends of every kept interval, and (retrieval by memory units) every unit edge
+  for (int i = tid; i <= L; i += blockDim.x)
+    flags[i] = (i == 0 || i == L || (D.unit > 0 && (c0 + i) % D.unit == 0)) ? 1 : 0;
   __syncthreads();
   for (int q = tid; q < nkept; q += blockDim.x) {
     const uint32_t kk = kept[q];

@@ -64,6 +64,16 @@ def test_workspace_sizes_and_bad_configs():
         for k, v in kw.items():
             setattr(cfg, k, v)
         assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == -1, kw
+    # retrieval by memory units: at most a chunk long, at most 8192 units in a full stream
+    for ut, ok in ((0, True), (32, True), (256, True), (257, False), (-1, False)):
+        cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0, unit_tokens=ut)
+        assert (lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == 0) == ok, ut
+    cfg = config_from_workload(CONFIGS["cfg3"], theta=1.0, unit_tokens=16)            # 131072 / 16 units
+    assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == -1
+    cfg = config_from_workload(CONFIGS["cfg3"], theta=1.0, unit_tokens=128, theta_quantile=0.9)
+    assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == 0
+    cfg.theta_quantile = 1.5
+    assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == -1
     cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0, lam=-5.0, ratio_mode=9)    # ignored with mean keys
     assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == 0
     cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0)

@@ -40,7 +40,8 @@ def _stream_parity(w, seed, T, device, *, seg_map=O.MAP_LOGIT, theta=None, phi=0
                     Qg = np.transpose(qn[:, h * w.group:(h + 1) * w.group], (1, 0, 2))
                 stable = O.segmentation_is_stable(Kn[h, c0:c0 + n], Qg, seg_map, st.cfg.theta, st.cfg.phi,
                                                   st.cfg.max_spans_per_chunk, rel=2.0 ** -16,
-                                                  theta_quantile=st.cfg.theta_quantile)
+                                                  theta_quantile=st.cfg.theta_quantile,
+                                                  unit=st.cfg.unit_tokens, c0=c0)
                 s, l = ctx.get_spans(0, 0, h)
                 assert not stable, (f"chunk at {c0}, head {h}: spans differ on an audited chunk\n"
                                     f"gpu {list(zip(s, l))[-12:]}\noracle {list(zip(st.starts[h], st.lens[h]))[-12:]}")
@@ -405,6 +406,61 @@ def test_dynamic_index_and_percentile_tiny_chunks(gpu_device):
                     index_max=8)
     _stream_parity(w, 10, sum(sizes), gpu_device, theta=99.0, theta_quantile=0.9, chunk_sizes=sizes,
                    rows=range(0, 512, 41), max_spans=2048)
+
+
+def test_retrieval_by_memory_units(gpu_device):
+    """Eq. 9 as written: spans are cut at the edges of fixed units, a unit scores the maximum over its
+    spans and the top units are retrieved whole (count cap or token budget). Unit ids, token lists
+    and outputs against the oracle; forced and persistent selections hold unit ids too."""
+    w = CONFIGS["cfg1"]
+    _, n_unstable, ctx, st = _stream_parity(w, 2, 2048 + 70, gpu_device, unit_tokens=32, k_max=5,
+                                            chunk_sizes=[256] * 8 + [70], rows=range(0, 256, 23))
+    assert n_unstable == 0
+    assert all(a // 32 == (a + l - 1) // 32 for a, l in zip(st.starts[0], st.lens[0]))
+    assert len(st.sel[0]) == 5 and max(st.sel[0]) < (2048 + 70) // 32 + 1
+    wb = Workload("mini-units", 8, 2, 128, "bf16", 4096, 512, 4, 300, 0, 700, "uniform", 16, 128)
+    _, n_unstable, ctx, st = _stream_parity(wb, 3, 4096, gpu_device, unit_tokens=128, rows=range(0, 512, 37))
+    assert n_unstable == 0 and 1 <= len(st.sel[0]) <= 5
+    # forced and persistent selections in unit ids
+    K, V, Q, _ = planted_stream(wb, 3, device=str(gpu_device), context=4096 + 4)
+    ctx, st = make_pair(wb, K, V, gpu_device, max_tokens=4096 + 4, unit_tokens=128)
+    for c0 in range(0, 4096, 512):
+        ctx.append_chunk(0, 0, 1, 512)
+        st.append_chunk(512)
+    for h in range(wb.n_kv_heads):
+        ctx.force_selection(0, 0, h, [20, 3, 3, 11])
+        st.force_selection(h, [3, 11, 20])
+        assert list(ctx.get_token_list(0, 0, h)) == list(st.context_tokens(h))
+    for k in range(3):
+        ctx.append_chunk(0, 0, 1, 1)
+        st.append_chunk(1)
+        ctx.retrieve_persistent(0, 0, 1)
+        for h in range(wb.n_kv_heads):
+            assert list(ctx.get_selection(0, 0, h)[0]) == [3, 11, 20]
+            assert list(ctx.get_token_list(0, 0, h)) == list(st.context_tokens(h))
+        q = Q[4096 + k:4096 + k + 1].contiguous()
+        out = ctx.attend(0, 0, 1, q)[0].double().cpu().numpy()
+        want, _ = st.attend(q.double().cpu().numpy())
+        assert np.abs(out - want).max() <= 2e-2
+    ctx.retrieve(0, 0, 1, q)                             # a one-token chunk, scored per unit
+    sel = st.retrieve(q.double().cpu().numpy())
+    for h in range(wb.n_kv_heads):
+        assert list(ctx.get_selection(0, 0, h)[0]) == list(sel[h])
+    assert ctx.sync_status() == 0
+
+
+def test_paper_literal_configuration(gpu_device):
+    """Everything as the paper configures it, at a small scale: softmax map, theta = 90th percentile,
+    IoU threshold 0.1, chunks = memory units of 128 tokens with at most C = 4 kept intervals each,
+    dynamic index vectors (row ratio, lambda 3, at most 6 per span), retrieval of the top K = 3 units."""
+    w = Workload("paper-like", 4, 1, 64, "f32", 2048, 128, 4, 256, 3, 0, "uniform", 8, 48)
+    kw = dict(seg_map=O.MAP_SOFTMAX, theta=99.0, theta_quantile=0.9, phi=0.1, max_spans_per_chunk=4,
+              rep_mode=O.REP_DYNAMIC, lam=3.0, index_max=6, unit_tokens=128, max_spans=1024)
+    _, n_unstable, ctx, st = _stream_parity(w, 5, 2048, gpu_device, rows=range(0, 128, 9), **kw)
+    assert n_unstable == 0
+    assert len(st.sel[0]) == 3 and len(st.starts[0]) > 32
+    _, n_unstable, ctx, st = _stream_parity(w, 6, 1024, gpu_device, use_q_seg=True, rows=range(0, 128, 9), **kw)
+    assert n_unstable == 0
 
 
 def test_span_table_overflow_is_reported(gpu_device):

@@ -592,6 +592,51 @@ def test_theta_as_a_percentile_of_the_map():
     assert list(a) == list(b) and len(a) > 2
 
 
+def test_unit_retrieval_is_eq9():
+    """Eq. 9 as written: blocks score the maximum over their spans and the top blocks are taken
+    whole. Brute force on a small table; every block selected gives full causal attention."""
+    rng = np.random.default_rng(3)
+    U, T, n_sink, ws = 8, 61, 3, 50
+    starts = np.array(sorted(rng.choice(np.arange(1, T), size=14, replace=False).tolist() + [0]))
+    starts = np.array(sorted(set(starts.tolist()) | set(range(0, T, U))))          # spans never straddle a block edge
+    scores = rng.standard_normal(len(starts))
+    sel, uscore = O.select_units(scores, starts, U, T, n_sink, ws, 3, 0)
+    n_units = (T + U - 1) // U
+    want_score = [max([scores[i] for i, a in enumerate(starts) if a // U == u], default=-np.inf) for u in range(n_units)]
+    np.testing.assert_array_equal(uscore, want_score)
+    eligible = [u for u in range(n_units) if max(u * U, n_sink) < min((u + 1) * U, T, ws)]
+    assert eligible == list(range(0, 7))                                             # blocks 0..6 reach below the window start 50
+    order = sorted(eligible, key=lambda u: (-want_score[u], u))
+    assert list(sel) == sorted(order[:3])
+    sel_b, _ = O.select_units(scores, starts, U, T, n_sink, ws, 0, 13)               # budget: 13 evicted tokens
+    tot, pref = 0, []
+    for u in order:
+        ln = min((u + 1) * U, T, ws) - max(u * U, n_sink)
+        if tot + ln > 13:
+            break
+        pref.append(u); tot += ln
+    assert list(sel_b) == sorted(pref) and len(pref) >= 1
+    # in the stream: spans are cut at block edges, and selecting every block is full causal attention
+    w = CONFIGS["cfg1"]
+    Kt, Vt, Qt, _ = planted_stream(w, 7, context=1024)
+    Kn, Vn, Qn = (t.to(torch.float64).numpy() for t in (Kt, Vt, Qt))
+    cfg = O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, "f32", 4, 100, theta=theta_default(w.head_dim),
+                         unit_tokens=32)
+    st = O.OracleStream(cfg, Kn, Vn)
+    for c0 in range(0, 1024, 256):
+        st.append_chunk(256)
+        edges = {a for a in st.starts[0]}
+        assert all(e in edges for e in range(0, c0 + 256, 32))
+        assert all(a // 32 == (a + l - 1) // 32 for a, l in zip(st.starts[0], st.lens[0]))
+        q = Qn[c0:c0 + 256]
+        sel = st.retrieve(q)
+        assert list(sel[0]) == [u for u in range((c0 + 31) // 32) if max(u * 32, 4) < min((u + 1) * 32, c0 - 100)]
+        assert list(st.context_tokens(0)) == list(range(c0))
+        Oo, _ = st.attend(q, rows=[0, 100, 255], heads=[1])
+        want = O.full_causal_attention(Qn[:, 1], Kn[0], Vn[0], [c0, c0 + 100, c0 + 255])
+        np.testing.assert_allclose(Oo[:, 0], want, atol=1e-12)
+
+
 def test_stability_audit_flags_a_planted_near_tie():
     """The audit must reject a chunk whose decision hangs on a near-tie."""
     L = 8
