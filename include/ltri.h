@@ -180,6 +180,22 @@ int32_t ltri_sel_capacity(const ltri_ctx* ctx);
 int32_t ltri_get_index_tokens(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,
                               uint32_t* mask_host, int32_t cap_words);
 
+/* Collaborative voting (Sec. 3.5, Collaborative Voting), with retrieval by memory units
+ * (unit_tokens > 0, EINVAL otherwise). Step 2 of `layer` in which the earlier layers take part:
+ * the layer first selects units on its own as ltri_retrieve does; then every earlier layer l with
+ * layer_weights_host[l] > 0 gives that weight to each unit of its current selection (same
+ * sequence, same KV head index) and the layer gives layer_weights_host[layer] to each unit of its
+ * own; eligible units are ordered by (votes descending, own score descending, id ascending) and
+ * the longest prefix within k_max units and budget_tokens evicted tokens becomes the layer's
+ * selection. Votes are float32 sums, earlier layers in ascending order, the layer last.
+ * layer_weights_host: host array of at least layer + 1 non-negative weights (the paper uses the
+ * retrieval-head scores of the layers that have a retrieval head, 0 elsewhere). ESTATE if a
+ * voting layer has no selection for the same chunk of the sequence; EINVAL if max_tokens /
+ * unit_tokens + 1 exceeds 4096. Other arguments as ltri_retrieve. */
+int32_t ltri_retrieve_collaborative(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count,
+                                    const void* q, int32_t n_q, const float* layer_weights_host,
+                                    int32_t* sel_ids, int32_t* sel_cnt);
+
 /* Persistent selection (Sec. 3.5, Persistent Mechanism): step 2 without scoring. The span ids
  * selected by the most recent ltri_retrieve / ltri_force_selection of each (sequence, KV head)
  * are kept, and the context set of the last appended chunk is rebuilt from them: initial

@@ -391,6 +391,37 @@ def select_units(span_scores: np.ndarray, starts: np.ndarray, unit: int, n_token
     return sel, uscore
 
 
+def collaborative_units(own_scores: np.ndarray, clip_len: np.ndarray, eligible: np.ndarray,
+                        voters: Sequence[Tuple[float, Sequence[int]]], own_weight: float,
+                        k_max: int, budget_tokens: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Sec. 3.5, Collaborative Voting, on memory units. `voters` = (weight, selected unit ids) of
+    the preceding layers that take part, in layer order. The layer first selects on its own
+    (Eq. 9); every voter and the layer itself then give their weight to each unit they selected;
+    units are ordered by (-votes, -own score, id) and the longest prefix within k_max units and
+    the token budget is the layer's selection. Votes are added in float32, voters first in
+    their order, the layer last. Returns (selected unit ids ascending, votes)."""
+    own = select_spans(own_scores, clip_len, eligible, k_max, budget_tokens)
+    votes = np.zeros(len(own_scores), np.float32)
+    for w, ids in voters:
+        for u in ids:
+            if u < len(votes):
+                votes[u] = np.float32(votes[u] + np.float32(w))
+    for u in own:
+        votes[u] = np.float32(votes[u] + np.float32(own_weight))
+    ids = [int(i) for i in np.nonzero(eligible)[0]]
+    ids.sort(key=lambda i: (-float(votes[i]), -float(own_scores[i]), i))
+    sel: List[int] = []
+    total = 0
+    for i in ids:
+        if k_max and len(sel) >= k_max:
+            break
+        if budget_tokens and total + int(clip_len[i]) > budget_tokens:
+            break
+        sel.append(i)
+        total += int(clip_len[i])
+    return np.asarray(sorted(sel), dtype=np.int64), votes
+
+
 # ----------------------------------------------------------------------------
 # exact attention over an explicit key set (Sec. 3.4, third step)
 # ----------------------------------------------------------------------------
@@ -540,6 +571,38 @@ class OracleStream:
                                       c.budget_tokens)
             else:
                 sel = select_spans(scores, b - a, eligible, c.k_max, c.budget_tokens)
+            self.sel[h] = sel
+            self.sel_scores[h] = scores
+            out.append(sel)
+        return out
+
+    def retrieve_collaborative(self, q: np.ndarray, preceding: Sequence["OracleStream"],
+                               weights: Sequence[float], own_weight: float) -> List[np.ndarray]:
+        """Step 2 with the votes of the preceding layers (Sec. 3.5, Collaborative Voting); needs
+        retrieval by memory units. preceding[k] is the stream of an earlier layer of the same
+        sequence (its current selection votes with weights[k]; weight 0 = takes no part)."""
+        c = self.cfg
+        assert c.unit_tokens > 0
+        c0, L = self.last_chunk
+        q = np.asarray(q, np.float64)
+        ws = self.win_start(c0)
+        U = c.unit_tokens
+        n_units = (c0 + L + U - 1) // U
+        out = []
+        for h in range(c.n_kv_heads):
+            qsum = q[:, h * c.group:(h + 1) * c.group, :].sum(axis=1)
+            if c.rep_mode == REP_DYNAMIC:
+                Qrep = index_vector_sums(qsum, self.last_index_tokens[h], c.dtype)
+            else:
+                Qrep = span_means(qsum, self.last_bounds[h], c.dtype)
+            scores = span_scores(Qrep, np.stack(self.krep[h]))
+            uscore = np.full(n_units, -np.inf)
+            for sc_, a in zip(scores, self.starts[h]):
+                uscore[a // U] = max(uscore[a // U], float(sc_))
+            lo = np.maximum(np.arange(n_units) * U, min(c.n_sink, c0))
+            hi = np.minimum(np.minimum((np.arange(n_units) + 1) * U, c0 + L), ws)
+            voters = [(w, [int(u) for u in p.sel[h]]) for p, w in zip(preceding, weights) if w > 0]
+            sel, _ = collaborative_units(uscore, hi - lo, lo < hi, voters, own_weight, c.k_max, c.budget_tokens)
             self.sel[h] = sel
             self.sel_scores[h] = scores
             out.append(sel)

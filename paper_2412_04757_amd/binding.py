@@ -25,6 +25,7 @@ EXPORTED_SYMBOLS = [
     "ltri_workspace_bytes", "ltri_create", "ltri_create_dry", "ltri_destroy", "ltri_reset",
     "ltri_set_stream", "ltri_set_attend_stages",
     "ltri_append_chunk", "ltri_append_chunk_with_spans", "ltri_retrieve", "ltri_retrieve_persistent",
+    "ltri_retrieve_collaborative",
     "ltri_sel_capacity",
     "ltri_force_selection", "ltri_attend", "ltri_gather_pack", "ltri_list_capacity",
     "ltri_sync_status", "ltri_token_count", "ltri_span_count", "ltri_get_spans",
@@ -80,6 +81,7 @@ def load_library() -> C.CDLL:
         "ltri_retrieve": [vp, i32, i32, i32, vp, i32, vp, vp],
         "ltri_sel_capacity": [vp],
         "ltri_retrieve_persistent": [vp, i32, i32, i32],
+        "ltri_retrieve_collaborative": [vp, i32, i32, i32, vp, i32, C.POINTER(C.c_float), vp, vp],
         "ltri_force_selection": [vp, i32, i32, i32, pi32, i32],
         "ltri_attend": [vp, i32, i32, i32, vp, i32, vp, vp],
         "ltri_gather_pack": [vp, i32, i32, vp, vp, vp],
@@ -222,6 +224,14 @@ class LtriContext:
         n_q = q.shape[-3]
         self._check(self.lib.ltri_retrieve(self.handle, layer, seq_begin, seq_count, q.data_ptr(), n_q,
                                            _ptr(sel_ids), _ptr(sel_cnt)), None)
+
+    def retrieve_collaborative(self, layer: int, seq_begin: int, seq_count: int, q: torch.Tensor, layer_weights,
+                               sel_ids: Optional[torch.Tensor] = None, sel_cnt: Optional[torch.Tensor] = None) -> None:
+        w = np.asarray(list(layer_weights), np.float32)
+        n_q = q.shape[-3]
+        self._check(self.lib.ltri_retrieve_collaborative(self.handle, layer, seq_begin, seq_count, q.data_ptr(), n_q,
+                                                         w.ctypes.data_as(C.POINTER(C.c_float)), _ptr(sel_ids),
+                                                         _ptr(sel_cnt)), None)
 
     def retrieve_persistent(self, layer: int, seq_begin: int, seq_count: int) -> None:
         self._check(self.lib.ltri_retrieve_persistent(self.handle, layer, seq_begin, seq_count), None)

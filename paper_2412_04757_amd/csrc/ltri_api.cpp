@@ -419,7 +419,49 @@ int32_t ltri_retrieve(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq
     long long bound = 0;
     for (int s = 0; s < seq_count; ++s) bound = std::max(bound, c->span_bound[ls_index(c, layer, seq_begin + s)]);
     r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound, sel_ids,
-                                     sel_cnt, c->stream), "retrieve");
+                                     sel_cnt, nullptr, c->stream), "retrieve");
+    if (r != LTRI_OK) return r;
+  }
+  for (int s = 0; s < seq_count; ++s) {
+    c->have_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
+    c->ever_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
+  }
+  return LTRI_OK;
+}
+
+int32_t ltri_retrieve_collaborative(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q,
+                                    int32_t n_q, const float* layer_weights_host, int32_t* sel_ids, int32_t* sel_cnt) {
+  BatchPos bp;
+  memset(&bp, 0, sizeof bp);
+  int32_t r = check_query_chunk(c, layer, seq_begin, seq_count, q, n_q, bp);
+  if (r != LTRI_OK) return r;
+  if (c->D.unit <= 0) return fail(c, LTRI_EINVAL, "collaborative retrieval votes on memory units: unit_tokens is 0");
+  if (!layer_weights_host) return fail(c, LTRI_EINVAL, "layer_weights_host is NULL");
+  if (c->D.max_tokens / c->D.unit + 1 > VOTE_MAX_UNITS)
+    return fail(c, LTRI_EINVAL, "collaborative retrieval holds at most %d units (max_tokens / unit_tokens + 1)", VOTE_MAX_UNITS);
+  VoteArgs v;
+  memset(&v, 0, sizeof v);
+  const uint32_t need = c->D.Hkv >= 32 ? 0xFFFFFFFFu : ((1u << c->D.Hkv) - 1u);
+  for (int l = 0; l <= layer; ++l) {
+    const float w = layer_weights_host[l];
+    if (!(w >= 0.0f)) return fail(c, LTRI_EINVAL, "weight of layer %d is negative or not a number", l);
+    if (l == layer) { v.own_weight = w; break; }
+    if (w == 0.0f) continue;
+    if (v.n_voters == VOTE_MAX_LAYERS) return fail(c, LTRI_EINVAL, "more than %d voting layers", VOTE_MAX_LAYERS);
+    for (int s = 0; s < seq_count; ++s) {
+      const size_t iv = ls_index(c, l, seq_begin + s), io = ls_index(c, layer, seq_begin + s);
+      if ((c->have_sel[iv] & need) != need || c->n_tokens[iv] != c->n_tokens[io] || c->last_len[iv] != c->last_len[io])
+        return fail(c, LTRI_ESTATE, "layer %d has no selection for this chunk of sequence %d", l, seq_begin + s);
+    }
+    v.layer[v.n_voters] = l;
+    v.weight[v.n_voters] = w;
+    ++v.n_voters;
+  }
+  if (!c->dry) {
+    long long bound = 0;
+    for (int s = 0; s < seq_count; ++s) bound = std::max(bound, c->span_bound[ls_index(c, layer, seq_begin + s)]);
+    r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound,
+                                     sel_ids, sel_cnt, &v, c->stream), "collaborative retrieve");
     if (r != LTRI_OK) return r;
   }
   for (int s = 0; s < seq_count; ++s) {

@@ -92,6 +92,16 @@ struct BatchPos {            // per-sequence values of one batched call
   int32_t c0[LTRI_MAX_BATCH];   // chunk start (tokens already in the stream)
 };
 
+// Voters of a collaborative retrieval (Sec. 3.5): earlier layers and their weights, then the layer's own weight.
+constexpr int VOTE_MAX_LAYERS = 64;
+constexpr int VOTE_MAX_UNITS = 4096;     // units of a full stream the voting kernel holds in LDS
+struct VoteArgs {
+  int n_voters;
+  int layer[VOTE_MAX_LAYERS];
+  float weight[VOTE_MAX_LAYERS];
+  float own_weight;
+};
+
 // Raw device views handed to the kernels.
 struct DevState {
   int32_t* meta; int32_t* span_start; int32_t* span_len; void* krep; double* scores;
@@ -122,7 +132,7 @@ hipError_t launch_rep_keys(const Dims& D, const DevState& st, const void* k_aren
                            const BatchPos& bp, int seq_count, int n_new, hipStream_t s);
 hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,
                            const void* q, int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
-                           int32_t* sel_ids_out, int32_t* sel_cnt_out, hipStream_t s);
+                           int32_t* sel_ids_out, int32_t* sel_cnt_out, const VoteArgs* votes, hipStream_t s);
 hipError_t launch_persist_list(const Dims& D, const DevState& st, int layer, const BatchPos& bp, int seq_count,
                                hipStream_t s);
 hipError_t launch_force_list(const Dims& D, const DevState& st, int layer, int seq, int kv_head,

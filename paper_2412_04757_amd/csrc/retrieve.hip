@@ -678,6 +678,87 @@ __global__ __launch_bounds__(1024) void unit_select_kernel(RetArgs a, int unit_b
   emit_selection(D, a.st, slot, selmask, n, ids_out, cnt_out);
 }
 
+// ---- collaborative voting over memory units (Sec. 3.5): the layer selects on its own, then the
+//      units are re-ordered by the weighted votes of the earlier layers' selections and its own
+//      (votes descending, own score descending, id ascending) and the prefix that fits is kept ----
+__device__ __forceinline__ uint32_t float_key_desc(float v) {          // smaller key = larger value
+  const uint32_t u = __float_as_uint(v + 0.0f);
+  return ~((u >> 31) ? ~u : (u | 0x80000000u));
+}
+
+__global__ __launch_bounds__(1024) void unit_vote_select_kernel(RetArgs a, int unit_bound, VoteArgs v) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char rt1_lds[];
+  __shared__ uint32_t selmask[RT1_MAX_SPANS / 32 + 2], ownmask[RT1_MAX_SPANS / 32 + 2];
+  __shared__ long long wave_tot[16];
+  const Dims& D = a.D;
+  const int p = blockIdx.x, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int seq = a.bp.seq[bi];
+  const int slot = slot_of(D, a.layer, seq, h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int n_spans = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
+  const int n_tokens = c0 + meta[META_CHUNK_LEN];
+  const int n = min(item_count(D, meta), unit_bound);
+  const int npow = rt1_pow2(n), tid = threadIdx.x;
+  const size_t pw = (size_t)rt1_pow2(unit_bound);
+  uint64_t* skey = reinterpret_cast<uint64_t*>(rt1_lds);
+  uint32_t* sidx = reinterpret_cast<uint32_t*>(rt1_lds + pw * 8);
+  int* clip = reinterpret_cast<int*>(rt1_lds + pw * 12);
+  int* rank = clip + unit_bound;
+  float* vote = reinterpret_cast<float*>(rank + unit_bound);
+  const double* scores = a.st.scores + (size_t)slot * D.max_spans;
+  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
+  for (int w = tid; w < (n + 31) / 32 + 2; w += blockDim.x) { selmask[w] = 0u; ownmask[w] = 0u; }
+  for (int u = tid; u < npow; u += blockDim.x) {
+    int c = 0;
+    double best = -INFINITY;
+    if (u < n) {
+      int lo, hi;
+      clip_span(D, c0, u * D.unit, min(D.unit, n_tokens - u * D.unit), lo, hi);
+      c = max(hi - lo, 0);
+      if (c > 0) {
+        int first = 0, last = n_spans;
+        while (first < last) { const int mid = (first + last) >> 1; if (sstart[mid] < u * D.unit) first = mid + 1; else last = mid; }
+        for (int i = first; i < n_spans && sstart[i] < (u + 1) * D.unit; ++i) best = fmax(best, scores[i]);
+      }
+      clip[u] = c;
+      vote[u] = 0.f;
+      rank[u] = 0;
+    }
+    skey[u] = c > 0 ? score_key(best) : ~0ull;
+    sidx[u] = c > 0 ? (uint32_t)u : RT1_PAD;
+  }
+  __syncthreads();
+  select_sorted_prefix(D, skey, sidx, clip, npow, ownmask, wave_tot);      // the layer's own selection
+  __syncthreads();
+  for (int r = tid; r < npow; r += blockDim.x)
+    if (sidx[r] != RT1_PAD) rank[sidx[r]] = r;                            // position in the order of the own scores
+  // votes, one voter after the other (float32 sums in a fixed order); a voter lists a unit at most once
+  for (int k = 0; k < v.n_voters; ++k) {
+    const int vslot = slot_of(D, v.layer[k], seq, h);
+    const int cnt = min(a.st.meta[(size_t)vslot * META_WORDS + META_SEL_CNT], D.sel_cap);
+    const int32_t* ids = a.st.sel_ids + (size_t)vslot * D.sel_cap;
+    for (int j = tid; j < cnt; j += blockDim.x) {
+      const int u = ids[j];
+      if (u >= 0 && u < n) vote[u] += v.weight[k];
+    }
+    __syncthreads();
+  }
+  for (int u = tid; u < n; u += blockDim.x)
+    if ((ownmask[u >> 5] >> (u & 31)) & 1u) vote[u] += v.own_weight;
+  __syncthreads();
+  for (int u = tid; u < npow; u += blockDim.x) {
+    const bool ok = u < n && clip[u] > 0;
+    skey[u] = ok ? (((uint64_t)float_key_desc(vote[u]) << 32) | (uint32_t)rank[u]) : ~0ull;
+    sidx[u] = ok ? (uint32_t)u : RT1_PAD;
+  }
+  __syncthreads();
+  select_sorted_prefix(D, skey, sidx, clip, npow, selmask, wave_tot);
+  __syncthreads();
+  int32_t* ids_out = a.sel_ids_out ? a.sel_ids_out + (size_t)p * D.sel_cap : nullptr;
+  int32_t* cnt_out = a.sel_cnt_out ? a.sel_cnt_out + p : nullptr;
+  emit_selection(D, a.st, slot, selmask, n, ids_out, cnt_out);
+}
+
 // ---- caller-forced selection: ids already copied (ascending, unique) into sel_ids ----
 struct ForceArgs { Dims D; DevState st; int layer, seq, h, n_ids; };
 
@@ -708,7 +789,7 @@ __global__ __launch_bounds__(1024) void force_list_kernel(ForceArgs a) {
 
 hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,
                            const void* q, int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
-                           int32_t* sel_ids_out, int32_t* sel_cnt_out, hipStream_t s) {
+                           int32_t* sel_ids_out, int32_t* sel_cnt_out, const VoteArgs* votes, hipStream_t s) {
   RetArgs a;
   a.D = D; a.st = st; a.sc = sc; a.q = q; a.layer = layer; a.seq_count = seq_count; a.n_q = n_q;
   a.Lp = (n_q + SEG_TB - 1) / SEG_TB * SEG_TB;
@@ -762,9 +843,15 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&unit_select_kernel),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)rt1_lds_bytes(RT1_MAX_SPANS));
       if (e != hipSuccess) return e;
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&unit_vote_select_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)(rt1_lds_bytes(VOTE_MAX_UNITS) + 8 * VOTE_MAX_UNITS));
+      if (e != hipSuccess) return e;
       attr_set = true;
     }
-    unit_select_kernel<<<P, 1024, rt1_lds_bytes(unit_bound), s>>>(a, unit_bound);
+    if (votes && unit_bound > VOTE_MAX_UNITS) return hipErrorInvalidValue;     // the host API checks this first
+    if (votes) unit_vote_select_kernel<<<P, 1024, rt1_lds_bytes(unit_bound) + 8 * (size_t)unit_bound, s>>>(a, unit_bound, *votes);
+    else       unit_select_kernel<<<P, 1024, rt1_lds_bytes(unit_bound), s>>>(a, unit_bound);
     return hipGetLastError();
   }
   int gr = (span_bound + SEL_SPANS_PER_BLOCK - 1) / SEL_SPANS_PER_BLOCK;

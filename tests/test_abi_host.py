@@ -84,6 +84,41 @@ def test_workspace_sizes_and_bad_configs():
     assert lib.ltri_strerror(-3).decode().startswith("token or span capacity")
 
 
+def test_collaborative_retrieval_call_rules_in_dry_mode():
+    w = CONFIGS["cfg1"]
+    ctx = LtriContext(config_from_workload(w, max_tokens=1024, theta=1.0, n_layers=3), None, dry=True)
+    ctx.append_chunk(1, 0, 1, 256)
+    with pytest.raises(LtriError) as e:
+        ctx.retrieve_collaborative(1, 0, 1, _FakeQ(256), [1.0, 1.0])
+    assert e.value.status == -1                      # spans are retrieved: nothing to vote on
+    ctx.close()
+    ctx = LtriContext(config_from_workload(w, max_tokens=1024, theta=1.0, n_layers=3, unit_tokens=64), None, dry=True)
+    for layer in range(3):
+        ctx.append_chunk(layer, 0, 1, 256)
+    with pytest.raises(LtriError) as e:
+        ctx.retrieve_collaborative(1, 0, 1, _FakeQ(256), [0.5, 1.0])
+    assert e.value.status == -2                      # layer 0 votes but has no selection yet
+    ctx.retrieve_collaborative(1, 0, 1, _FakeQ(256), [0.0, 1.0])        # weight 0: layer 0 takes no part
+    ctx.retrieve(0, 0, 1, _FakeQ(256))
+    ctx.retrieve_collaborative(2, 0, 1, _FakeQ(256), [0.5, 0.25, 1.0])
+    ctx.attend(2, 0, 1, _FakeQ(256))
+    with pytest.raises(LtriError) as e:
+        ctx.retrieve_collaborative(2, 0, 1, _FakeQ(256), [0.5, -0.25, 1.0])
+    assert e.value.status == -1
+    ctx.append_chunk(0, 0, 1, 256)                   # layer 0 moves on: its selection is for another chunk
+    with pytest.raises(LtriError) as e:
+        ctx.retrieve_collaborative(2, 0, 1, _FakeQ(256), [0.5, 0.25, 1.0])
+    assert e.value.status == -2
+    ctx.close()
+    big = LtriContext(config_from_workload(CONFIGS["cfg3"], theta=1.0, n_layers=2, unit_tokens=16,
+                                           max_tokens=131072 - 64), None, dry=True)
+    big.append_chunk(1, 0, 1, 2048)
+    with pytest.raises(LtriError) as e:
+        big.retrieve_collaborative(1, 0, 1, _FakeQ(2048), [0.0, 1.0])   # 4096 units and more
+    assert e.value.status == -1
+    big.close()
+
+
 class _FakeQ:
     """Stands in for a device tensor in dry mode: only the shape and a non-null address are used."""
     def __init__(self, n_q):

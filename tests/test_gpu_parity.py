@@ -463,6 +463,54 @@ def test_paper_literal_configuration(gpu_device):
     assert n_unstable == 0
 
 
+def test_collaborative_voting_across_layers(gpu_device):
+    """Three layers of one sequence, retrieval by units of 64 tokens: layer 0 selects on its own,
+    layers 1 and 2 take the weighted votes of the layers before them (one of them with weight 0
+    for layer 2). Unit ids, token lists and outputs of every layer against the oracle."""
+    w = Workload("mini-vote", 8, 2, 128, "bf16", 2048, 256, 4, 200, 4, 0, "uniform", 16, 96)
+    n_layers, T, L, U = 3, 2048, 256, 64
+    cfg = config_from_workload(w, theta=theta_default(w.head_dim), n_layers=n_layers, n_seqs=1, unit_tokens=U)
+    ctx = LtriContext(cfg, gpu_device)
+    ka, va = ctx.arena_views()
+    ocfg = O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, w.n_sink, w.window, k_max=w.k_max,
+                          theta=float(np.float32(theta_default(w.head_dim))), unit_tokens=U)
+    Qs, sts = [], []
+    for layer in range(n_layers):
+        K, V, Q, _ = planted_stream(w, 31, device=str(gpu_device), layer=layer)
+        ka[layer, 0].copy_(K)
+        va[layer, 0].copy_(V)
+        Qs.append(Q)
+        sts.append(O.OracleStream(ocfg, K.double().cpu().numpy(), V.double().cpu().numpy()))
+    weights = {1: [0.7, 1.0], 2: [0.7, 0.0, 0.5]}
+    n_changed = 0
+    for c0 in range(0, T, L):
+        for layer in range(n_layers):
+            q = Qs[layer][c0:c0 + L].contiguous()
+            qn = q.double().cpu().numpy()
+            ctx.append_chunk(layer, 0, 1, L)
+            sts[layer].append_chunk(L)
+            if layer == 0:
+                ctx.retrieve(0, 0, 1, q)
+                sel = sts[0].retrieve(qn)
+            else:
+                wl = weights[layer]
+                ctx.retrieve_collaborative(layer, 0, 1, q, wl)
+                alone = O.OracleStream.retrieve(sts[layer], qn)
+                alone = [x.copy() for x in alone]
+                sel = sts[layer].retrieve_collaborative(qn, sts[:layer], wl[:layer], wl[layer])
+                n_changed += sum(list(x) != list(y) for x, y in zip(alone, sel))
+            for h in range(w.n_kv_heads):
+                assert list(ctx.get_spans(layer, 0, h)[0]) == sts[layer].starts[h]
+                assert list(ctx.get_selection(layer, 0, h)[0]) == list(sel[h]), f"chunk at {c0}, layer {layer}, head {h}"
+                assert list(ctx.get_token_list(layer, 0, h)) == list(sts[layer].context_tokens(h))
+            rows = list(range(0, L, 31))
+            out = ctx.attend(layer, 0, 1, q)[0].double().cpu().numpy()[rows]
+            want, _ = sts[layer].attend(qn, rows=rows)
+            assert np.abs(out - want).max() <= 2e-2
+    assert n_changed >= 4                              # the votes did change some selections
+    assert ctx.sync_status() == 0
+
+
 def test_span_table_overflow_is_reported(gpu_device):
     w = CONFIGS["cfg1"]
     K, V, Q, _ = planted_stream(w, 1, device=str(gpu_device), context=1024)

@@ -637,6 +637,26 @@ def test_unit_retrieval_is_eq9():
         np.testing.assert_allclose(Oo[:, 0], want, atol=1e-12)
 
 
+def test_collaborative_voting_on_units():
+    """Sec. 3.5: weighted votes of the preceding layers decide, the layer's own score breaks ties."""
+    scores = np.array([0.9, 0.1, 0.5, 0.7, 0.3, 0.8])
+    clip = np.array([8, 8, 8, 8, 8, 0])
+    elig = clip > 0
+    # no voters: the layer's own selection (it votes for its own top 2, which therefore stay on top)
+    sel, votes = O.collaborative_units(scores, clip, elig, [], 1.0, 2, 0)
+    assert list(sel) == [0, 3] and list(votes) == [1, 0, 0, 1, 0, 0]
+    # two earlier layers agree on unit 1 and outweigh the layer itself; unit 5 is not eligible
+    sel, votes = O.collaborative_units(scores, clip, elig, [(0.6, [1, 5]), (0.5, [1, 2])], 1.0, 2, 0)
+    assert list(votes) == [1.0, np.float32(0.6) + np.float32(0.5), 0.5, 1.0, 0.0, np.float32(0.6)]
+    assert list(sel) == [0, 1]                         # votes 1.1 (unit 1), then 1.0: units 0 and 3 tie, score 0.9 wins
+    # equal votes everywhere: the own scores order the units; the budget cuts the prefix
+    sel, _ = O.collaborative_units(scores, clip, elig, [(1.0, [0, 1, 2, 3, 4])], 0.0, 0, 20)
+    assert list(sel) == [0, 3]
+    # a zero own weight and one voter: the voter's units first, whatever the layer thinks
+    sel, _ = O.collaborative_units(scores, clip, elig, [(0.2, [4, 1])], 0.0, 2, 0)
+    assert list(sel) == [1, 4]
+
+
 def test_stability_audit_flags_a_planted_near_tie():
     """The audit must reject a chunk whose decision hangs on a near-tie."""
     L = 8
