@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256) void select_rank_kernel(RetArgs a) {
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int n = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
-  if (blockIdx.x * SEL_SPANS_PER_BLOCK >= n) return;                   // uniform
+  if ((int)blockIdx.x * SEL_SPANS_PER_BLOCK >= n) return;              // uniform
   const double* scores = a.st.scores + (size_t)slot * D.max_spans;
   const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
   const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
@@ -544,7 +544,7 @@ __global__ __launch_bounds__(1024) void retrieve_one_token_kernel(RetArgs a, int
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int n = min(meta[META_N_SPANS], bound), c0 = meta[META_CHUNK_START];
-  const int d = D.d, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int d = D.d, tid = threadIdx.x;
   const int npow = rt1_pow2(n);
   uint64_t* skey = reinterpret_cast<uint64_t*>(rt1_lds);
   uint32_t* sidx = reinterpret_cast<uint32_t*>(rt1_lds + (size_t)rt1_pow2(bound) * 8);
