@@ -279,6 +279,13 @@ def main():
     ap.add_argument("--overlap", action="store_true",
                     help="segment chunk c+1 on a second stream next to attend(c) (measured: no gain, the kernels\n"
                          "compete for the same compute units)")
+    ap.add_argument("--schedule", choices=["calls", "step"], default="step",
+                    help="calls: append, retrieve, attend one after the other; step: ltri_step per chunk (the "
+                         "attention over initial | window | chunk runs beside steps 1 and 2 on a second stream)")
+    ap.add_argument("--attend-stages", type=int, default=0, choices=[0, 3, 4],
+                    help="LDS ring depth of the attention kernel (default: the library's)")
+    ap.add_argument("--step-reserve", type=int, default=-1,
+                    help="compute units ltri_step keeps free for the small kernels (default: the library's)")
     ap.add_argument("--index-vectors", choices=["mean", "dynamic"], default="mean",
                     help="what a span stores: the mean key (headline) or the sum of its index tokens' keys\n"
                          "(dynamic span index vectors, row ratio, lambda 3); not the headline configuration")
@@ -335,6 +342,7 @@ def main():
     qs = [Q[c * L:(c + 1) * L] for c in range(n_chunks)]          # contiguous views
 
     list_lens = []          # per chunk: context-list length of every KV head
+    SEPARATE = []           # events of the pass that times the attention kernel alone (--schedule step)
 
     # The segmentation of chunk c + 1 does not depend on the attention of chunk c; with --overlap it is
     # enqueued on a second stream between retrieve(c) and retrieve(c + 1) and runs next to attend(c).
@@ -346,7 +354,21 @@ def main():
     if overlap:
         ctx.set_attend_stages(3)          # leaves LDS for the segmentation kernels on every compute unit
 
+    step_schedule = args.schedule == "step" and not overlap
+    if args.step_reserve >= 0:
+        ctx.set_step_reserve(args.step_reserve)
+    if args.attend_stages:
+        ctx.set_attend_stages(args.attend_stages)
+
+    def one_stream_steps():
+        ctx.reset(0)
+        for c in range(n_chunks):
+            ctx.step(0, 0, 1, None, None, qs[c], out=out)
+
     def one_stream(record_lens=False, events=None):
+        if step_schedule and events is not None and events is not SEPARATE:
+            one_stream_steps()
+            return
         ctx.reset(0)
         ctx.append_chunk(0, 0, 1, L)
         for c in range(n_chunks):
@@ -379,6 +401,8 @@ def main():
     one_stream(record_lens=True)
     for _ in range(max(0, args.warmup - 1)):
         one_stream()
+    if step_schedule:
+        one_stream_steps()
     status = ctx.sync_status()
     if status != 0:
         print(f"bench.py: device status {status}", file=sys.stderr)
@@ -396,6 +420,20 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     value = T * args.steps / elapsed
 
+    calls_ms_per_step = None
+    if step_schedule:
+        # Inside ltri_step the attention runs as two launches beside other kernels, one of them on a stream of
+        # the library's own, so no event pair of this script brackets it. Its launch duration is taken over the
+        # same number of further streams with the three plain calls (attend_bf16_kernel<8, 4> in a profile; the
+        # two parts of a step are the <8, 3> instantiation), every launch alone on its stream.
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            one_stream(events=SEPARATE)
+        torch.cuda.synchronize()
+        calls_ms_per_step = (time.perf_counter() - t1) / args.steps * 1e3
+        events = SEPARATE[:]
+
     # attend kernel: algorithmic flops per launch / measured launch duration
     att_ms = [e0.elapsed_time(e1) for e0, e1 in events]
     flops = [attend_flops(w, L, list_lens[i % n_chunks]) for i in range(len(events))]
@@ -407,6 +445,9 @@ def main():
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": ATTEND_TRAFFIC_BYTES_CFG3 if (args.workload == "cfg3" and not args.context) else None,
                 "avg_launch_us": round(tot_ms / len(events) * 1e3, 1),
+                "launches_timed": ("attend_bf16_kernel<8, 4>, one launch per chunk, over as many further streams with "
+                                   "the three plain calls (inside ltri_step the kernel runs as two launches beside "
+                                   "other kernels)") if step_schedule else "every launch of the timed streams",
                 "full_context_launch_us": round(sum(att_ms[i] for i in last) / len(last) * 1e3, 1),
                 "full_context_achieved": round(last_tflops, 2)}
 
@@ -446,8 +487,10 @@ def main():
         f"{copy_meas:.0f} GB/s copy")
 
     # share of the step spent outside attend (append + retrieve + launch gaps)
-    other_ms = ms_per_step - tot_ms / args.steps
-    log(f"[bench] {ms_per_step:.2f} ms per stream; attend {tot_ms / args.steps:.2f} ms, rest {other_ms:.2f} ms")
+    other_ms = (calls_ms_per_step or ms_per_step) - tot_ms / args.steps
+    log(f"[bench] {ms_per_step:.2f} ms per stream; " +
+        (f"with the three plain calls {calls_ms_per_step:.2f} ms: " if calls_ms_per_step else "") +
+        f"attend {tot_ms / args.steps:.2f} ms, rest {other_ms:.2f} ms")
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -468,9 +511,13 @@ def main():
                    "retrieval_unit": "span" if not args.unit_tokens else f"memory units of {args.unit_tokens} tokens",
                    "index_vectors": "mean key per span" if args.index_vectors == "mean"
                    else "dynamic (row ratio, lambda 3): sum of the keys of each span's index tokens",
-                   "schedule": "append(c+1) on a second stream next to attend(c)" if overlap else "serial"},
+                   "schedule": "append(c+1) on a second stream next to attend(c)" if overlap else
+                   ("ltri_step per chunk: attention over initial | window | chunk on a second stream beside "
+                    "steps 1 and 2, retrieved tokens after, merged" if step_schedule else "three calls per chunk, serial")},
         "roofline": roofline, "gather": gather, "cpu_baseline": cpu,
-        "breakdown_ms": {"attend": round(tot_ms / args.steps, 3), "append_retrieve_and_gaps": round(other_ms, 3)},
+        "breakdown_ms": {"attend": round(tot_ms / args.steps, 3), "append_retrieve_and_gaps": round(other_ms, 3),
+                         "measured_on": "further streams with the three plain calls" if step_schedule else "the timed streams",
+                         "ms_per_step_three_calls": round(calls_ms_per_step, 3) if calls_ms_per_step else None},
     }
     print(json.dumps(result), flush=True)
 

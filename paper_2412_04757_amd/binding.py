@@ -23,11 +23,11 @@ RATIO_ROW, RATIO_COL, RATIO_ROWCOL = 0, 1, 2
 
 EXPORTED_SYMBOLS = [
     "ltri_workspace_bytes", "ltri_create", "ltri_create_dry", "ltri_destroy", "ltri_reset",
-    "ltri_set_stream", "ltri_set_attend_stages",
+    "ltri_set_stream", "ltri_set_attend_stages", "ltri_set_step_reserve",
     "ltri_append_chunk", "ltri_append_chunk_with_spans", "ltri_retrieve", "ltri_retrieve_persistent",
     "ltri_retrieve_collaborative",
     "ltri_sel_capacity",
-    "ltri_force_selection", "ltri_attend", "ltri_gather_pack", "ltri_list_capacity",
+    "ltri_force_selection", "ltri_attend", "ltri_step", "ltri_gather_pack", "ltri_list_capacity",
     "ltri_sync_status", "ltri_token_count", "ltri_span_count", "ltri_get_spans",
     "ltri_get_rep_keys", "ltri_get_selection", "ltri_get_token_list", "ltri_get_index_tokens", "ltri_strerror",
     "ltri_last_error", "ltri_version", "ltri_measure_mfma_peak", "ltri_measure_copy_peak",
@@ -84,6 +84,8 @@ def load_library() -> C.CDLL:
         "ltri_retrieve_collaborative": [vp, i32, i32, i32, vp, i32, C.POINTER(C.c_float), vp, vp],
         "ltri_force_selection": [vp, i32, i32, i32, pi32, i32],
         "ltri_attend": [vp, i32, i32, i32, vp, i32, vp, vp],
+        "ltri_set_step_reserve": [vp, i32],
+        "ltri_step": [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp],
         "ltri_gather_pack": [vp, i32, i32, vp, vp, vp],
         "ltri_list_capacity": [vp],
         "ltri_sync_status": [vp],
@@ -198,6 +200,9 @@ class LtriContext:
         self._check(self.lib.ltri_set_stream(self.handle, stream.cuda_stream), None)
         self.stream = stream
 
+    def set_step_reserve(self, compute_units: int) -> None:
+        self._check(self.lib.ltri_set_step_reserve(self.handle, compute_units), None)
+
     def set_attend_stages(self, stages: int) -> None:
         self._check(self.lib.ltri_set_attend_stages(self.handle, stages), None)
 
@@ -249,6 +254,17 @@ class LtriContext:
                               device=q.device)
         self._check(self.lib.ltri_attend(self.handle, layer, seq_begin, seq_count, q.data_ptr(), n_q,
                                          _ptr(out) if out is not None else 1, _ptr(lse)), None)
+        return out
+
+    def step(self, layer: int, seq_begin: int, seq_count: int, k_chunk: Optional[torch.Tensor],
+             v_chunk: Optional[torch.Tensor], q: torch.Tensor, q_seg: Optional[torch.Tensor] = None,
+             out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None) -> torch.Tensor:
+        n_new = q.shape[-3]
+        if out is None and not self.dry:
+            out = torch.empty((seq_count, n_new, self.cfg.n_q_heads, self.cfg.head_dim), dtype=self.tdtype,
+                              device=q.device)
+        self._check(self.lib.ltri_step(self.handle, layer, seq_begin, seq_count, _ptr(k_chunk), _ptr(v_chunk),
+                                       _ptr(q_seg), q.data_ptr(), n_new, _ptr(out) if out is not None else 1, _ptr(lse)), None)
         return out
 
     def gather_pack(self, layer: int, seq: int, k_packed: torch.Tensor, v_packed: torch.Tensor,

@@ -17,8 +17,16 @@ struct AttArgs {
   Dims D; DevState st; const void* k_arena; const void* v_arena; const void* q;
   void* out; float* lse; int layer; int seq_count; int n_q;
   int n_splits; float* part;             // short query blocks: the key range is split over workgroups
+  int part_mode;                         // ATT_ALL, or one of the two parts of an overlapped step
+  const int32_t* loclist; int loc_cap;   // ATT_LOCAL: initial | window tokens per sequence [seq_count][loc_cap]
+  int rb_off;                            // first block of query rows of this launch (a launch may take a range of them)
   BatchPos bp;
 };
+
+// An overlapped step attends in two parts that a third kernel merges: the part that does not
+// depend on the retrieval (initial and window tokens and the chunk itself) can run while the chunk
+// is still being segmented and its spans scored; the retrieved tokens follow.
+enum : int { ATT_ALL = 0, ATT_LOCAL = 1, ATT_RETRIEVED = 2 };
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -131,17 +139,27 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   const int l32 = lane & 31, hf = lane >> 5;
   const int head = h * D.G + gsub * HG + (wave % HG);
   const int split = a.n_splits > 1 ? blockIdx.y : 0;
-  const int rb0 = a.n_splits > 1 ? 0 : blockIdx.y * RPB;   // first row of the block
+  const int rb0 = a.n_splits > 1 ? 0 : (blockIdx.y + a.rb_off) * RPB;   // first row of the block
   const int r0 = rb0 + (wave / HG) * 32;            // first row of this wave
   const int slot = slot_of(D, a.layer, seq, h);
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.k_arena) + arena_off(D, slot) * 2;
   const unsigned char* Vb = reinterpret_cast<const unsigned char*>(a.v_arena) + arena_off(D, slot) * 2;
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
-  const int list_len = meta[META_LIST_LEN];
+  // the context list is initial | retrieved | window; the two parts of an overlapped step read
+  // initial | window from a list of their own, or the retrieved slice of the full list
+  const int n_init = min(D.n_sink, c0), n_win = c0 - max(n_init, c0 - D.window);
+  int list_len = meta[META_LIST_LEN];
   const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
+  if (a.part_mode == ATT_LOCAL) {
+    list_len = n_init + n_win;
+    list = a.loclist + (size_t)bi * a.loc_cap;
+  } else if (a.part_mode == ATT_RETRIEVED) {
+    list_len = max(list_len - n_init - n_win, 0);
+    list += n_init;
+  }
   const int n_ctx_tiles = (list_len + 63) / 64;
   const int rb_end = min(L, rb0 + RPB);
-  const int n_chunk_tiles = (rb_end + 63) / 64;
+  const int n_chunk_tiles = a.part_mode == ATT_RETRIEVED ? 0 : (rb_end + 63) / 64;
   const int n_tiles = n_ctx_tiles + n_chunk_tiles;
   // with splits, this workgroup takes the context tiles [tile0, tile1); the last split also takes the chunk's tiles
   const int tile0 = a.n_splits > 1 ? (int)((long long)split * n_ctx_tiles / a.n_splits) : 0;
@@ -421,7 +439,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
     return;
   }
   if (qi < L) {
-    const float inv = 1.f / lt;
+    const float inv = lt > 0.f ? 1.f / lt : 0.f;     // no key at all (an empty retrieved part): O = 0, lse = -inf
     uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
@@ -455,6 +473,44 @@ __global__ __launch_bounds__(128) void attend_merge_kernel(AttArgs a) {
   uint16_t* orow = reinterpret_cast<uint16_t*>(a.out) + (((size_t)bi * L + qi) * D.Hq + head) * d;
   orow[c] = f32_to_bf16(acc / l);
   if (a.lse && c == 0) a.lse[((size_t)bi * L + qi) * D.Hq + head] = (mmax + log2f(l)) * 0.6931471805599453f;
+}
+
+// ---- the two parts of an overlapped step ----
+// initial | window tokens of every sequence of the batch, padded with token 0 to whole tiles
+__global__ __launch_bounds__(256) void local_list_kernel(Dims D, BatchPos bp, int32_t* loclist, int loc_cap) {
+  const int bi = blockIdx.y, c0 = bp.c0[bi];
+  const int n_init = min(D.n_sink, c0), w0 = max(n_init, c0 - D.window), len = n_init + c0 - w0;
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r < loc_cap) loclist[(size_t)bi * loc_cap + r] = r < n_init ? r : (r < len ? w0 + r - n_init : 0);
+}
+
+// O = (w_a O_a + w_b O_b) / (w_a + w_b), w = exp(lse - max lse) (the log-sum-exp identity), in place
+// in O_a; eight values per thread. A part without keys has lse = -inf and weight 0.
+__global__ __launch_bounds__(256) void attend_merge_parts_kernel(uint16_t* out, const uint16_t* o_b, const float* lse_a,
+                                                                 const float* lse_b, float* lse_out, long long n_rows) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long rh = idx >> 4;
+  const int piece = (int)(idx & 15);
+  if (rh >= n_rows) return;
+  const float la = lse_a[rh], lb = lse_b[rh];
+  if (lb == -INFINITY) {
+    if (lse_out && piece == 0) lse_out[rh] = la;
+    return;
+  }
+  const float m = fmaxf(la, lb);
+  const float wa = expf(la - m), wb = expf(lb - m);
+  const float inv = 1.f / (wa + wb), fa = wa * inv, fb = wb * inv;
+  uint4* pa = reinterpret_cast<uint4*>(out) + rh * 16 + piece;
+  const uint4 ua = *pa, ub = *(reinterpret_cast<const uint4*>(o_b) + rh * 16 + piece);
+  auto mix = [&](uint32_t x, uint32_t y) {
+    const float lo = fa * __uint_as_float(x << 16) + fb * __uint_as_float(y << 16);
+    const float hi = fa * __uint_as_float(x & 0xFFFF0000u) + fb * __uint_as_float(y & 0xFFFF0000u);
+    return pack_bf16x2(lo, hi);
+  };
+  uint4 r;
+  r.x = mix(ua.x, ub.x); r.y = mix(ua.y, ub.y); r.z = mix(ua.z, ub.z); r.w = mix(ua.w, ub.w);
+  *pa = r;
+  if (lse_out && piece == 0) lse_out[rh] = m + logf(wa + wb);
 }
 
 // ---- fp32 kernel: one wavefront per (query row, head); keys across lanes ----
@@ -555,18 +611,26 @@ __global__ __launch_bounds__(256) void gather_pack_kernel(GatherArgs a) {
 
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
-                         void* out, float* lse, int stages, float* part, hipStream_t s) {
+                         void* out, float* lse, int stages, float* part, int part_mode, const int32_t* loclist,
+                         int loc_cap, int rb_first, int rb_count, hipStream_t s) {
   AttArgs a;
   a.D = D; a.st = st; a.k_arena = k_arena; a.v_arena = v_arena; a.q = q; a.out = out; a.lse = lse;
   a.layer = layer; a.seq_count = seq_count; a.n_q = n_q; a.bp = bp;
   a.n_splits = 1; a.part = part;
-  const bool mfma_ok = D.dtype == LTRI_BF16 && D.d == 128 && (D.G == 1 || D.G == 2 || D.G % 4 == 0);
+  a.part_mode = part_mode; a.loclist = loclist; a.loc_cap = loc_cap; a.rb_off = 0;
+  const bool mfma_ok = attend_on_matrix_cores(D);
+  if (part_mode != ATT_ALL && (!mfma_ok || n_q <= ATT_SPLIT_MAX_ROWS)) return hipErrorInvalidValue;
   if (mfma_ok) {
     const int HG = D.G < 4 ? D.G : 4;
     const int gpk = D.G / HG;
     constexpr int NW = ATT_NW;
     const int RPB = 32 * (NW / HG);
     dim3 g(D.Hkv * gpk, (n_q + RPB - 1) / RPB, seq_count);
+    if (rb_count >= 0) {                 // a range of the row blocks only
+      if (rb_first < 0 || rb_first + rb_count > (int)g.y) return hipErrorInvalidValue;
+      if (rb_count == 0) return hipSuccess;
+      a.rb_off = rb_first; g.y = rb_count;
+    }
     // a short query block (decode) on few workgroups: split the key range so that every compute
     // unit streams a share of it; the partial results are merged by a second kernel
     const int blocks = D.Hkv * gpk * seq_count;
@@ -593,6 +657,33 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
     if (D.dtype == LTRI_BF16) attend_simple_kernel<LTRI_BF16><<<g, 64, 0, s>>>(a);
     else                      attend_simple_kernel<LTRI_F32><<<g, 64, 0, s>>>(a);
   }
+  return hipGetLastError();
+}
+
+bool attend_on_matrix_cores(const Dims& D) {
+  return D.dtype == LTRI_BF16 && D.d == 128 && (D.G == 1 || D.G == 2 || D.G % 4 == 0);
+}
+
+void attend_launch_shape(const Dims& D, int seq_count, int n_q, int* wgs_per_row_block, int* row_blocks) {
+  const int HG = D.G < 4 ? D.G : 4;
+  const int RPB = 32 * (ATT_NW / HG);
+  *wgs_per_row_block = D.Hkv * (D.G / HG) * seq_count;
+  *row_blocks = (n_q + RPB - 1) / RPB;
+}
+
+hipError_t launch_local_list(const Dims& D, const BatchPos& bp, int seq_count, int32_t* loclist, int loc_cap,
+                             hipStream_t s) {
+  local_list_kernel<<<dim3((loc_cap + 255) / 256, seq_count), 256, 0, s>>>(D, bp, loclist, loc_cap);
+  return hipGetLastError();
+}
+
+hipError_t launch_attend_merge_parts(const Dims& D, int seq_count, int n_q, void* out, const void* o_b,
+                                     const float* lse_a, const float* lse_b, float* lse_out, hipStream_t s) {
+  const long long n_rows = (long long)seq_count * n_q * D.Hq;
+  const long long blocks = (n_rows * 16 + 255) / 256;
+  attend_merge_parts_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(reinterpret_cast<uint16_t*>(out),
+                                                                  reinterpret_cast<const uint16_t*>(o_b), lse_a, lse_b,
+                                                                  lse_out, n_rows);
   return hipGetLastError();
 }
 

@@ -22,6 +22,10 @@ struct ltri_ctx {
   DevScratch dc;
   bool dry;
   int attend_stages;                     // LDS ring depth of the bf16 attention kernel (3 or 4)
+  int step_stages;                       // the same for the two parts of an overlapped step
+  // second stream and the fork / join events of an overlapped step
+  hipStream_t side; hipEvent_t ev_fork, ev_join;
+  int n_cus, reserve_cus;                // compute units of the device; those an overlapped step keeps free of long workgroups
   // host mirror of the stream positions, per (layer, seq)
   std::vector<long long> n_tokens;       // tokens appended
   std::vector<int> last_len;             // length of the chunk appended last (0 = none)
@@ -135,6 +139,10 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.qhist = o;   o = align_up(o + (size_t)P * QUANT_BINS * 4, 256);
   CL.qstate = o;  o = align_up(o + (size_t)P * 4 * 8, 256);
   CL.lpart = o;   o = align_up(o + (c.rep_mode == LTRI_REP_DYNAMIC || c.seg_map == LTRI_MAP_SOFTMAX ? (size_t)P * G * nb * Lp * 16 : 0), 256);
+  CL.loc_cap = (int)align_up((size_t)c.n_sink + c.window, ATT_BN) + ATT_BN;
+  CL.att_o2 = o;    o = align_up(o + (size_t)c.n_seqs * c.chunk_max * c.n_q_heads * c.head_dim * D.elt, 256);
+  CL.att_lse2 = o;  o = align_up(o + 2 * (size_t)c.n_seqs * c.chunk_max * c.n_q_heads * 4, 256);
+  CL.loclist = o;   o = align_up(o + (size_t)c.n_seqs * CL.loc_cap * 4, 256);
   CL.total = o;
   CL.max_problems = P;
   return LTRI_OK;
@@ -184,6 +192,9 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->stream = (hipStream_t)hip_stream;
   c->dry = dry;
   c->attend_stages = 4;
+  c->step_stages = 3;
+  c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
+  c->n_cus = 0; c->reserve_cus = 0;
   char* s = c->state;
   c->ds = DevState{(int32_t*)(s + SL.meta), (int32_t*)(s + SL.span_start), (int32_t*)(s + SL.span_len),
                    (void*)(s + SL.krep), (double*)(s + SL.scores), (int32_t*)(s + SL.sel_ids),
@@ -194,7 +205,8 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
                      (int32_t*)(t + CL.px), (uint64_t*)(t + CL.ckey), (uint32_t*)(t + CL.cxy), (double*)(t + CL.lse), (void*)(t + CL.qrep),
                      (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds), (uint8_t*)(t + CL.selflag), (float*)(t + CL.att_part),
                      (int32_t*)(t + CL.tokspan), (double*)(t + CL.dyn), (double*)(t + CL.lpart),
-                     (uint32_t*)(t + CL.qhist), (unsigned long long*)(t + CL.qstate)};
+                     (uint32_t*)(t + CL.qhist), (unsigned long long*)(t + CL.qstate),
+                     (void*)(t + CL.att_o2), (float*)(t + CL.att_lse2), (int32_t*)(t + CL.loclist)};
   const size_t n = (size_t)D.n_layers * D.n_seqs;
   c->n_tokens.assign(n, 0);
   c->last_len.assign(n, 0);
@@ -202,8 +214,15 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->have_sel.assign(n, 0u);
   c->ever_sel.assign(n, 0u);
   if (!dry) {
-    const hipError_t e = launch_fill_zero(c->state, SL.total, c->stream);
-    if (e != hipSuccess) { delete c; return LTRI_EHIP; }
+    hipError_t e = launch_fill_zero(c->state, SL.total, c->stream);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+    int dev = 0;
+    if (e == hipSuccess) e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, dev);
+    c->reserve_cus = 0;
+    if (e != hipSuccess) { ltri_destroy(c); return LTRI_EHIP; }
   }
   *out = c;
   return LTRI_OK;
@@ -220,6 +239,12 @@ int32_t ltri_create_dry(const ltri_config* cfg, ltri_ctx** out) {
 
 int32_t ltri_destroy(ltri_ctx* c) {
   if (!c) return LTRI_EINVAL;
+  if (c->side) {      // work of an overlapped step may still be queued there
+    (void)hipStreamSynchronize(c->side);
+    (void)hipStreamDestroy(c->side);
+  }
+  if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+  if (c->ev_join) (void)hipEventDestroy(c->ev_join);
   delete c;
   return LTRI_OK;
 }
@@ -234,6 +259,16 @@ int32_t ltri_set_attend_stages(ltri_ctx* c, int32_t stages) {
   if (!c) return LTRI_EINVAL;
   if (stages != 3 && stages != 4) return fail(c, LTRI_EINVAL, "attend stages must be 3 or 4");
   c->attend_stages = stages;
+  c->step_stages = stages;
+  return LTRI_OK;
+}
+
+int32_t ltri_set_step_reserve(ltri_ctx* c, int32_t compute_units) {
+  if (!c) return LTRI_EINVAL;
+  if (c->dry) return LTRI_OK;
+  if (compute_units < 0 || compute_units > c->n_cus)
+    return fail(c, LTRI_EINVAL, "reserve %d outside [0, %d compute units]", compute_units, c->n_cus);
+  c->reserve_cus = compute_units;
   return LTRI_OK;
 }
 
@@ -311,6 +346,44 @@ static void append_commit(ltri_ctx* c, int layer, int seq_begin, int seq_count, 
   }
 }
 
+// Step 1 of a chunk whose rows are already in the arenas: segmentation and index vectors. `fork` (or NULL)
+// is recorded on the context's stream behind the last kernel that fills the chip; what follows it there
+// are kernels of a few workgroups each.
+static int32_t append_spans(ltri_ctx* c, int layer, const BatchPos& bp, int seq_count, const void* q_seg, int n_new,
+                            hipEvent_t fork) {
+  int32_t r;
+  if (n_new == 1) {
+    r = check_hip(c, launch_append_single(c->D, c->ds, c->k_arena, layer, bp, seq_count, c->stream),
+                  "append (single token)");
+    if (r == LTRI_OK && fork) r = check_hip(c, hipEventRecord(fork, c->stream), "fork");
+    return r;
+  }
+  const int per = c->CL.max_problems / c->D.Hkv;     // sequences per segmentation launch
+  const bool dynamic = c->D.rep_mode == LTRI_REP_DYNAMIC;
+  for (int off = 0; off < seq_count; off += per) {
+    const int cnt = std::min(per, seq_count - off);
+    const bool last = off + per >= seq_count;
+    r = check_hip(c, launch_segment(c->D, c->ds, c->dc, c->k_arena, q_seg, layer, bp, off, cnt, n_new,
+                                    last && !dynamic ? fork : nullptr, c->stream), "segment");
+    if (r != LTRI_OK) return r;
+    if (dynamic) {
+      r = check_hip(c, launch_dynamic_reps(c->D, c->ds, c->dc, c->k_arena, q_seg, layer, bp, off, cnt, n_new,
+                                           c->D.seg_map == LTRI_MAP_SOFTMAX, c->stream), "index vectors");
+      if (r != LTRI_OK) return r;
+    }
+  }
+  if (dynamic && fork) {
+    r = check_hip(c, hipEventRecord(fork, c->stream), "fork");
+    if (r != LTRI_OK) return r;
+  }
+  if (c->D.rep_mode == LTRI_REP_MEAN) {
+    r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, seq_count, n_new, c->stream),
+                  "representative keys");
+    if (r != LTRI_OK) return r;
+  }
+  return LTRI_OK;
+}
+
 int32_t ltri_append_chunk(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count,
                           const void* k_chunk, const void* v_chunk, const void* q_seg, int32_t n_new) {
   BatchPos bp;
@@ -318,29 +391,8 @@ int32_t ltri_append_chunk(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t
   int32_t r = append_common(c, layer, seq_begin, seq_count, k_chunk, v_chunk, n_new, bp);
   if (r != LTRI_OK) return r;
   if (!c->dry) {
-    if (n_new == 1) {
-      r = check_hip(c, launch_append_single(c->D, c->ds, c->k_arena, layer, bp, seq_count, c->stream),
-                    "append (single token)");
-      if (r != LTRI_OK) return r;
-    } else {
-      const int per = c->CL.max_problems / c->D.Hkv;     // sequences per segmentation launch
-      for (int off = 0; off < seq_count; off += per) {
-        const int cnt = std::min(per, seq_count - off);
-        r = check_hip(c, launch_segment(c->D, c->ds, c->dc, c->k_arena, q_seg, layer, bp, off, cnt, n_new,
-                                        c->stream), "segment");
-        if (r != LTRI_OK) return r;
-        if (c->D.rep_mode == LTRI_REP_DYNAMIC) {
-          r = check_hip(c, launch_dynamic_reps(c->D, c->ds, c->dc, c->k_arena, q_seg, layer, bp, off, cnt, n_new,
-                                               c->D.seg_map == LTRI_MAP_SOFTMAX, c->stream), "index vectors");
-          if (r != LTRI_OK) return r;
-        }
-      }
-      if (c->D.rep_mode == LTRI_REP_MEAN) {
-        r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, seq_count, n_new, c->stream),
-                      "representative keys");
-        if (r != LTRI_OK) return r;
-      }
-    }
+    r = append_spans(c, layer, bp, seq_count, q_seg, n_new, nullptr);
+    if (r != LTRI_OK) return r;
   }
   append_commit(c, layer, seq_begin, seq_count, n_new);
   return LTRI_OK;
@@ -540,10 +592,75 @@ int32_t ltri_attend(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_c
                   seq_begin + s);
   if (!c->dry) {
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_q, out, lse,
-                                   c->attend_stages, c->dc.att_part, c->stream), "attend");
+                                   c->attend_stages, c->dc.att_part, 0, nullptr, 0, 0, -1, c->stream), "attend");
     if (r != LTRI_OK) return r;
   }
   return LTRI_OK;
+}
+
+int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* k_chunk,
+                  const void* v_chunk, const void* q_seg, const void* q, int32_t n_new, void* out, float* lse) {
+  if (!c) return LTRI_EINVAL;
+  if (!q) return fail(c, LTRI_EINVAL, "q is NULL");
+  if (!out) return fail(c, LTRI_EINVAL, "out is NULL");
+  // Short query blocks (decode) and shapes the matrix-core kernel does not take go through the three calls.
+  int wgs_per_rb = 0, n_rb = 0, rb_side = 0;
+  bool overlap = !c->dry && n_new > ATT_SPLIT_MAX_ROWS && attend_on_matrix_cores(c->D) && seq_count >= 1 &&
+                 seq_count <= LTRI_MAX_BATCH;
+  if (overlap) {
+    // Row blocks of the first part that start early, on the second stream: as many as leave `reserve`
+    // compute units to the small kernels of steps 1 and 2 (one workgroup of the attention kernel fills a unit).
+    // Measured on the 128K workload, reserving none is fastest: the small kernels then wait for the first
+    // attention workgroups to retire, but the attention never waits for them.
+    attend_launch_shape(c->D, seq_count, n_new, &wgs_per_rb, &n_rb);
+    rb_side = std::min(n_rb, (c->n_cus - c->reserve_cus) / wgs_per_rb);
+    overlap = rb_side > 0;
+  }
+  if (!overlap) {
+    int32_t r = ltri_append_chunk(c, layer, seq_begin, seq_count, k_chunk, v_chunk, q_seg, n_new);
+    if (r != LTRI_OK) return r;
+    r = ltri_retrieve(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr);
+    if (r != LTRI_OK) return r;
+    return ltri_attend(c, layer, seq_begin, seq_count, q, n_new, out, lse);
+  }
+  BatchPos bp;
+  memset(&bp, 0, sizeof bp);
+  int32_t r = append_common(c, layer, seq_begin, seq_count, k_chunk, v_chunk, n_new, bp);
+  if (r != LTRI_OK) return r;
+  const size_t plane = (size_t)c->D.n_seqs * c->D.chunk_max * c->D.Hq;
+  float* lse_a = c->dc.att_lse2;
+  float* lse_b = c->dc.att_lse2 + plane;
+  // Context's stream: the kernels of step 1 that fill the chip, the fork, then the small kernels of steps 1 and 2.
+  r = check_hip(c, launch_local_list(c->D, bp, seq_count, c->dc.loclist, c->CL.loc_cap, c->stream), "local list");
+  if (r != LTRI_OK) return r;
+  r = append_spans(c, layer, bp, seq_count, q_seg, n_new, c->ev_fork);
+  if (r != LTRI_OK) return r;
+  append_commit(c, layer, seq_begin, seq_count, n_new);
+  // Second stream, behind the fork: attention over initial | window | chunk for the later (longer) row blocks.
+  r = check_hip(c, hipStreamWaitEvent(c->side, c->ev_fork, 0), "fork");
+  if (r == LTRI_OK)
+    r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse_a,
+                                   c->step_stages, nullptr, 1, c->dc.loclist, c->CL.loc_cap, n_rb - rb_side, rb_side,
+                                   c->side), "attend (initial, window, chunk)");
+  if (r == LTRI_OK) r = check_hip(c, hipEventRecord(c->ev_join, c->side), "join");
+  if (r != LTRI_OK) return r;
+  r = ltri_retrieve(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr);
+  // Context's stream again: the remaining row blocks of the first part and the retrieved tokens; their
+  // workgroups take the compute units as the second stream's workgroups leave them.
+  if (r == LTRI_OK)
+    r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse_a,
+                                   c->step_stages, nullptr, 1, c->dc.loclist, c->CL.loc_cap, 0, n_rb - rb_side,
+                                   c->stream), "attend (initial, window, chunk)");
+  if (r == LTRI_OK)
+    r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, c->dc.att_o2,
+                                   lse_b, c->step_stages, nullptr, 2, nullptr, 0, 0, -1, c->stream),
+                  "attend (retrieved)");
+  // join even after an error, so that the context's stream never runs ahead of the second stream's writes to out
+  const int32_t rj = check_hip(c, hipStreamWaitEvent(c->stream, c->ev_join, 0), "join");
+  if (r != LTRI_OK) return r;
+  if (rj != LTRI_OK) return rj;
+  return check_hip(c, launch_attend_merge_parts(c->D, seq_count, n_new, out, c->dc.att_o2, lse_a, lse_b, lse,
+                                                c->stream), "merge of the two parts");
 }
 
 int32_t ltri_gather_pack(ltri_ctx* c, int32_t layer, int32_t seq, void* k_packed, void* v_packed,

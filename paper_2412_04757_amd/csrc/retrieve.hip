@@ -319,8 +319,10 @@ __device__ void emit_selection(const Dims& D, const DevState& st, int slot, cons
   }
   if (fits) {
     for (int t = tid; t < n_win; t += blockDim.x) list[ns + n_ret + t] = ws + t;
-    const int padded = min(D.list_cap, (len + ATT_BN - 1) / ATT_BN * ATT_BN);
-    for (int t = len + tid; t < padded; t += blockDim.x) list[t] = 0;      // padding: a valid token, masked by position
+    // padding: a valid token, masked by position. One tile more than the list's own last tile, because the
+    // attention over the retrieved slice alone starts its tiles at the end of the initial tokens.
+    const int padded = min(D.list_cap, (len + ATT_BN - 1) / ATT_BN * ATT_BN + ATT_BN);
+    for (int t = len + tid; t < padded; t += blockDim.x) list[t] = 0;
   }
   if (tid == 0) {
     if (!fits) atomicCAS(&st.err[0], 0, LTRI_ECAPACITY);

@@ -1004,7 +1004,7 @@ hipError_t launch_dynamic_reps(const Dims& D, const DevState& st, const DevScrat
 
 hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& sc, const void* k_arena,
                           const void* q_seg, int layer, const BatchPos& bp, int batch_off, int seq_count,
-                          int n_new, hipStream_t s) {
+                          int n_new, hipEvent_t after_tiles, hipStream_t s) {
   SegArgs a;
   a.D = D; a.st = st; a.sc = sc; a.k_arena = k_arena; a.q_seg = q_seg; a.layer = layer;
   a.batch_off = batch_off; a.n_new = n_new;
@@ -1041,6 +1041,11 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
   else if (bf)        tiles(integral_constant<int, LTRI_BF16>{}, integral_constant<int, LTRI_MAP_SOFTMAX>{});
   else if (lg)        tiles(integral_constant<int, LTRI_F32>{}, integral_constant<int, LTRI_MAP_LOGIT>{});
   else                tiles(integral_constant<int, LTRI_F32>{}, integral_constant<int, LTRI_MAP_SOFTMAX>{});
+  // the kernels from here on use a few compute units each
+  if (after_tiles) {
+    const hipError_t e = hipEventRecord(after_tiles, s);
+    if (e != hipSuccess) return e;
+  }
   dim3 gm((2 * n_new - 1 + 255) / 256, P);
   seg_merge_kernel<<<gm, 256, 0, s>>>(a);
   seg_select_kernel<<<P, 1024, 0, s>>>(a);

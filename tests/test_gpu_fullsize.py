@@ -125,6 +125,41 @@ def test_cfg3_full_size_retrieve_and_attend(gpu_device):
     assert ctx.sync_status() == 0
 
 
+def test_cfg3_whole_step_full_size(gpu_device):
+    """ltri_step (the benchmark's default schedule: attention over initial | window | chunk on a second
+    stream beside steps 1 and 2, retrieved tokens after, merged) over the whole 128K stream, against the three
+    plain calls on a second context fed the same stream: spans, selections and token lists identical on
+    sampled chunks, outputs within the bf16 bar, log-sum-exp within 2e-3."""
+    w = CONFIGS["cfg3"]
+    T, L = w.context, w.chunk
+    K, V, Q, _ = planted_stream(w, 3, device=str(gpu_device))
+    cfg = config_from_workload(w, theta=theta_default(w.head_dim), n_layers=1, n_seqs=1)
+    ctxs = [LtriContext(cfg, gpu_device) for _ in range(2)]
+    for ctx in ctxs:
+        ka, va = ctx.arena_views()
+        ka[0, 0].copy_(K)
+        va[0, 0].copy_(V)
+    outs = [torch.empty((1, L, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=gpu_device) for _ in range(2)]
+    lses = [torch.empty((1, L, w.n_q_heads), dtype=torch.float32, device=gpu_device) for _ in range(2)]
+    for c in range(T // L):
+        q = Q[c * L:(c + 1) * L]
+        ctxs[0].step(0, 0, 1, None, None, q, out=outs[0], lse=lses[0])
+        ctxs[1].append_chunk(0, 0, 1, L)
+        ctxs[1].retrieve(0, 0, 1, q)
+        ctxs[1].attend(0, 0, 1, q, out=outs[1], lse=lses[1])
+        if c in (0, 1, 2, 3, 7, 31, 62, 63):
+            for h in range(w.n_kv_heads):
+                assert list(ctxs[0].get_selection(0, 0, h)[0]) == list(ctxs[1].get_selection(0, 0, h)[0]), (c, h)
+                assert list(ctxs[0].get_token_list(0, 0, h)) == list(ctxs[1].get_token_list(0, 0, h)), (c, h)
+            assert torch.isfinite(outs[0].float()).all()
+            assert float((outs[0].float() - outs[1].float()).abs().max()) <= 2e-2, c
+            assert float((lses[0] - lses[1]).abs().max()) <= 2e-3, c
+    for h in range(w.n_kv_heads):
+        a, b = ctxs[0].get_spans(0, 0, h), ctxs[1].get_spans(0, 0, h)
+        assert list(a[0]) == list(b[0]) and list(a[1]) == list(b[1])
+    assert ctxs[0].sync_status() == 0 and ctxs[1].sync_status() == 0
+
+
 def test_cfg3_dynamic_index_vectors_full_size(gpu_device):
     """Dynamic span index vectors at the benchmark's sizes (chunks of 2048, 8 KV heads, the whole 128K
     stream): on sampled chunks and heads the index tokens and the stored vectors of the chunk's spans

@@ -19,9 +19,11 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 
 
 def _stream_parity(w, seed, T, device, *, seg_map=O.MAP_LOGIT, theta=None, phi=0.0, use_q_seg=False,
-                   rows=None, chunk_sizes=None, **kw):
+                   rows=None, chunk_sizes=None, whole_step=False, **kw):
     K, V, Q, _ = planted_stream(w, seed, device=str(device), context=T)
     ctx, st = make_pair(w, K, V, device, max_tokens=T, seg_map=seg_map, theta=theta, phi=phi, **kw)
+    if whole_step is not True and whole_step is not False:
+        ctx.set_step_reserve(int(whole_step))       # compute units kept free: decides how many row blocks start early
     Kn = K.double().cpu().numpy()
     Qn = Q.double().cpu().numpy()
     c0 = 0
@@ -31,7 +33,11 @@ def _stream_parity(w, seed, T, device, *, seg_map=O.MAP_LOGIT, theta=None, phi=0
     for n in sizes:
         q = Q[c0:c0 + n].contiguous()
         qn = Qn[c0:c0 + n]
-        ctx.append_chunk(0, 0, 1, n, q_seg=q if use_q_seg else None)
+        if whole_step:      # the three steps in one call, on the library's own schedule
+            lse = torch.empty((1, n, w.n_q_heads), dtype=torch.float32, device=device)
+            out = ctx.step(0, 0, 1, None, None, q, q_seg=q if use_q_seg else None, lse=lse)
+        else:
+            ctx.append_chunk(0, 0, 1, n, q_seg=q if use_q_seg else None)
         st.append_chunk(n, q_seg=qn if use_q_seg else None)
         for h in range(w.n_kv_heads):
             if not spans_equal(ctx, st, h):
@@ -57,15 +63,17 @@ def _stream_parity(w, seed, T, device, *, seg_map=O.MAP_LOGIT, theta=None, phi=0
                     st.starts[h].append(int(a)); st.lens[h].append(int(ln)); st.krep[h].append(reps[k])
                 st.last_bounds[h] = b
             assert rep_keys_diff(ctx, st, h) == 0.0, f"representative keys differ (chunk at {c0}, head {h})"
-        ctx.retrieve(0, 0, 1, q)
+        if not whole_step:
+            ctx.retrieve(0, 0, 1, q)
         sel = st.retrieve(qn)
         for h in range(w.n_kv_heads):
             ids, scores = ctx.get_selection(0, 0, h)
             np.testing.assert_allclose(scores, st.sel_scores[h][:len(scores)], rtol=1e-12, atol=1e-12)
             assert list(ids) == list(sel[h]), f"selection differs (chunk at {c0}, head {h})"
             assert list(ctx.get_token_list(0, 0, h)) == list(st.context_tokens(h))
-        lse = torch.empty((1, n, w.n_q_heads), dtype=torch.float32, device=device)
-        out = ctx.attend(0, 0, 1, q, lse=lse)
+        if not whole_step:
+            lse = torch.empty((1, n, w.n_q_heads), dtype=torch.float32, device=device)
+            out = ctx.attend(0, 0, 1, q, lse=lse)
         rr = list(range(n)) if rows is None else sorted({r for r in rows if r < n} | {0, n - 1})
         want, want_lse = st.attend(qn, rows=rr)
         got = out[0].double().cpu().numpy()[rr]
@@ -136,6 +144,62 @@ def test_bf16_ragged_and_all_rows(gpu_device):
     # a short stream with every row and every head checked
     w2 = Workload("mini", 8, 2, 128, "bf16", 768, 256, 4, 128, 0, 200, "uniform", 16, 64)
     _stream_parity(w2, 3, 768, gpu_device)
+
+
+def test_whole_step_on_two_streams(gpu_device):
+    """ltri_step: the three steps in one call, with the attention over initial | window | chunk on a second
+    stream beside steps 1 and 2 and the two parts merged. Same bars as the three calls; ragged chunks, a
+    one-token chunk (takes the plain path), chunks before anything is evicted, query-driven maps."""
+    w = CONFIGS["cfg2"]
+    worst, n_unstable, ctx, st = _stream_parity(w, 1, 8192, gpu_device, window=2048, budget_tokens=2048,
+                                                rows=[0, 1, 31, 32, 63, 64, 500, 1000, 1023], whole_step=True)
+    assert n_unstable <= 1
+    sizes = [1024, 300, 1, 65, 511, 1000, 64, 1024, 2]
+    # 216 of 256 compute units reserved: 5 of a full chunk's 16 row blocks start early, the rest follow step 2
+    _stream_parity(w, 2, sum(sizes), gpu_device, chunk_sizes=sizes, window=700, budget_tokens=900,
+                   rows=range(0, 1024, 37), whole_step=216, use_q_seg=True)
+    w2 = Workload("mini", 8, 2, 128, "bf16", 768, 256, 4, 128, 0, 200, "uniform", 16, 64)
+    _stream_parity(w2, 3, 768, gpu_device, whole_step=True)
+    # fp32 contexts take the three calls in order
+    _stream_parity(CONFIGS["cfg1"], 4, 1024, gpu_device, whole_step=True)
+
+
+@pytest.mark.parametrize("variant", ["mean", "dynamic", "units"])
+def test_whole_step_equals_three_calls_batched(gpu_device, variant):
+    """Two sequences at different positions in one batch: ltri_step against append + retrieve + attend on a
+    second context (same spans, selection and token lists; outputs within the bf16 bar). Also with dynamic
+    index vectors (the fork then sits behind their kernels) and with retrieval by memory units."""
+    w = Workload("mini2", 8, 2, 128, "bf16", 2048, 256, 4, 256, 0, 300, "uniform", 16, 64)
+    extra = {"mean": {}, "dynamic": dict(rep_mode=1, lam=3.0), "units": dict(unit_tokens=64, k_max=3)}[variant]
+    cfg = config_from_workload(w, max_tokens=2048, theta=theta_default(w.head_dim), n_layers=1, n_seqs=2, **extra)
+    ctxs = [LtriContext(cfg, gpu_device) for _ in range(2)]
+    streams = [planted_stream(w, 20 + s, device=str(gpu_device), context=2048) for s in range(2)]
+    for ctx in ctxs:
+        ka, va = ctx.arena_views()
+        for s, (K, V, Q, _) in enumerate(streams):
+            ka[0, s].copy_(K); va[0, s].copy_(V)
+        # sequence 1 runs one chunk ahead of sequence 0
+        q1 = streams[1][2][:256].contiguous()
+        ctx.append_chunk(0, 1, 1, 256, q_seg=q1)
+        ctx.retrieve(0, 1, 1, q1)
+    for step in range(6):
+        q = torch.stack([streams[0][2][step * 256:(step + 1) * 256],
+                         streams[1][2][(step + 1) * 256:(step + 2) * 256]]).contiguous()
+        lse_a = torch.empty((2, 256, w.n_q_heads), dtype=torch.float32, device=gpu_device)
+        lse_b = torch.empty_like(lse_a)
+        out_a = ctxs[0].step(0, 0, 2, None, None, q, q_seg=q, lse=lse_a)
+        ctxs[1].append_chunk(0, 0, 2, 256, q_seg=q)
+        ctxs[1].retrieve(0, 0, 2, q)
+        out_b = ctxs[1].attend(0, 0, 2, q, lse=lse_b)
+        for s in range(2):
+            for h in range(w.n_kv_heads):
+                a, b = ctxs[0].get_spans(0, s, h), ctxs[1].get_spans(0, s, h)
+                assert list(a[0]) == list(b[0]) and list(a[1]) == list(b[1])
+                assert list(ctxs[0].get_selection(0, s, h)[0]) == list(ctxs[1].get_selection(0, s, h)[0])
+                assert list(ctxs[0].get_token_list(0, s, h)) == list(ctxs[1].get_token_list(0, s, h))
+        assert float((out_a.float() - out_b.float()).abs().max()) <= 2e-2
+        assert float((lse_a - lse_b).abs().max()) <= 2e-3      # the sums run over probabilities rounded to bf16
+    assert ctxs[0].sync_status() == 0 and ctxs[1].sync_status() == 0
 
 
 def test_given_spans_forced_selection_and_gather(gpu_device):
