@@ -188,9 +188,12 @@ def run_layers(args, torch, dev):
     for layer in range(n_layers):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
-        ctx.append_chunk(layer, 0, 1, L)
-        ctx.retrieve(layer, 0, 1, qs[layer])
-        ctx.attend(layer, 0, 1, qs[layer], out=out)
+        if args.schedule == "step":
+            ctx.step(layer, 0, 1, None, None, qs[layer], out=out)
+        else:
+            ctx.append_chunk(layer, 0, 1, L)
+            ctx.retrieve(layer, 0, 1, qs[layer])
+            ctx.attend(layer, 0, 1, qs[layer], out=out)
         e1.record()
         times.append((e0, e1))
     torch.cuda.synchronize()
@@ -203,7 +206,8 @@ def run_layers(args, torch, dev):
         "metric": "last-chunk time per layer with all layers resident", "value": round(float(np.median(us[1:])), 1), "unit": "us",
         "n_gpus": 1, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"cfg4: {n_layers} layers x {T} tokens resident, 32 query / 8 KV heads, head_dim 128, bf16, "
-                               f"chunk {L}, window {w.window}, budget {w.budget_tokens}"},
+                               f"chunk {L}, window {w.window}, budget {w.budget_tokens}",
+                   "schedule": "ltri_step" if args.schedule == "step" else "three calls"},
         "per_layer_us": {"first_layer_incl_warmup": round(float(us[0]), 1), "min": round(float(us[1:].min()), 1),
                          "median": round(float(np.median(us[1:])), 1), "max": round(float(us[1:].max()), 1)},
         "resident_bytes": {"kv_arenas": int(ka.numel() * ka.element_size() * 2), "index_state": int(ctx.state.numel()),

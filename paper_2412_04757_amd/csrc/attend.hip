@@ -20,12 +20,14 @@ struct AttArgs {
   int part_mode;                         // ATT_ALL, or one of the two parts of an overlapped step
   const int32_t* loclist; int loc_cap;   // ATT_LOCAL: initial | window tokens per sequence [seq_count][loc_cap]
   int rb_off;                            // first block of query rows of this launch (a launch may take a range of them)
+  const float* lse_a;                    // ATT_RETRIEVED: log-sum-exp of the first part, whose output is in `out`
   BatchPos bp;
 };
 
-// An overlapped step attends in two parts that a third kernel merges: the part that does not
-// depend on the retrieval (initial and window tokens and the chunk itself) can run while the chunk
-// is still being segmented and its spans scored; the retrieved tokens follow.
+// An overlapped step attends in two parts: the one that does not depend on the retrieval (initial
+// and window tokens and the chunk itself) can run while the chunk is still being segmented and
+// its spans scored; the retrieved tokens follow, and that launch folds the first part's result
+// (already in `out`, with its log-sum-exp) into its own when it writes.
 enum : int { ATT_ALL = 0, ATT_LOCAL = 1, ATT_RETRIEVED = 2 };
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -438,8 +440,42 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
     }
     return;
   }
+  if (a.part_mode == ATT_RETRIEVED) {
+    // O = (w_a O_a + w_b O_b) / (w_a + w_b) with w = 2^(lse - max lse) (the log-sum-exp identity, log2 domain);
+    // O_b = o / lt and lse_b = m_run + log2(lt), so w_b / lt = 2^(m_run - max). Every lane rewrites the
+    // elements of O_a it reads. Without a retrieved key the first part stands as it is.
+    if (qi < L) {
+      const size_t rh = ((size_t)bi * L + qi) * D.Hq + head;
+      const float la = a.lse_a[rh];
+      if (lt > 0.f) {
+        const float la2 = la * 1.4426950408889634f, lb2 = m_run + log2f(lt);
+        const float mx = fmaxf(la2, lb2);
+        const float wa = __builtin_amdgcn_exp2f(la2 - mx), wb = __builtin_amdgcn_exp2f(lb2 - mx);
+        const float inv = 1.f / (wa + wb);
+        const float fa = wa * inv, fb = __builtin_amdgcn_exp2f(m_run - mx) * inv;
+        uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
+#pragma unroll
+        for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+          for (int a4 = 0; a4 < 4; ++a4) {
+            uint2* p = reinterpret_cast<uint2*>(orow + mb * 32 + 8 * a4 + 4 * hf);
+            const uint2 ua = *p;
+            uint2 u;
+            u.x = pack_bf16x2(fa * __uint_as_float(ua.x << 16) + fb * o[mb][4 * a4 + 0],
+                              fa * __uint_as_float(ua.x & 0xFFFF0000u) + fb * o[mb][4 * a4 + 1]);
+            u.y = pack_bf16x2(fa * __uint_as_float(ua.y << 16) + fb * o[mb][4 * a4 + 2],
+                              fa * __uint_as_float(ua.y & 0xFFFF0000u) + fb * o[mb][4 * a4 + 3]);
+            *p = u;
+          }
+        if (a.lse && hf == 0) a.lse[rh] = (mx + log2f(wa + wb)) * 0.6931471805599453f;
+      } else if (a.lse && hf == 0) {
+        a.lse[rh] = la;
+      }
+    }
+    return;
+  }
   if (qi < L) {
-    const float inv = lt > 0.f ? 1.f / lt : 0.f;     // no key at all (an empty retrieved part): O = 0, lse = -inf
+    const float inv = 1.f / lt;
     uint16_t* orow = Ob + ((size_t)qi * D.Hq + head) * d;
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
@@ -475,42 +511,13 @@ __global__ __launch_bounds__(128) void attend_merge_kernel(AttArgs a) {
   if (a.lse && c == 0) a.lse[((size_t)bi * L + qi) * D.Hq + head] = (mmax + log2f(l)) * 0.6931471805599453f;
 }
 
-// ---- the two parts of an overlapped step ----
+// ---- first part of an overlapped step: its token list ----
 // initial | window tokens of every sequence of the batch, padded with token 0 to whole tiles
 __global__ __launch_bounds__(256) void local_list_kernel(Dims D, BatchPos bp, int32_t* loclist, int loc_cap) {
   const int bi = blockIdx.y, c0 = bp.c0[bi];
   const int n_init = min(D.n_sink, c0), w0 = max(n_init, c0 - D.window), len = n_init + c0 - w0;
   const int r = blockIdx.x * 256 + threadIdx.x;
   if (r < loc_cap) loclist[(size_t)bi * loc_cap + r] = r < n_init ? r : (r < len ? w0 + r - n_init : 0);
-}
-
-// O = (w_a O_a + w_b O_b) / (w_a + w_b), w = exp(lse - max lse) (the log-sum-exp identity), in place
-// in O_a; eight values per thread. A part without keys has lse = -inf and weight 0.
-__global__ __launch_bounds__(256) void attend_merge_parts_kernel(uint16_t* out, const uint16_t* o_b, const float* lse_a,
-                                                                 const float* lse_b, float* lse_out, long long n_rows) {
-  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
-  const long long rh = idx >> 4;
-  const int piece = (int)(idx & 15);
-  if (rh >= n_rows) return;
-  const float la = lse_a[rh], lb = lse_b[rh];
-  if (lb == -INFINITY) {
-    if (lse_out && piece == 0) lse_out[rh] = la;
-    return;
-  }
-  const float m = fmaxf(la, lb);
-  const float wa = expf(la - m), wb = expf(lb - m);
-  const float inv = 1.f / (wa + wb), fa = wa * inv, fb = wb * inv;
-  uint4* pa = reinterpret_cast<uint4*>(out) + rh * 16 + piece;
-  const uint4 ua = *pa, ub = *(reinterpret_cast<const uint4*>(o_b) + rh * 16 + piece);
-  auto mix = [&](uint32_t x, uint32_t y) {
-    const float lo = fa * __uint_as_float(x << 16) + fb * __uint_as_float(y << 16);
-    const float hi = fa * __uint_as_float(x & 0xFFFF0000u) + fb * __uint_as_float(y & 0xFFFF0000u);
-    return pack_bf16x2(lo, hi);
-  };
-  uint4 r;
-  r.x = mix(ua.x, ub.x); r.y = mix(ua.y, ub.y); r.z = mix(ua.z, ub.z); r.w = mix(ua.w, ub.w);
-  *pa = r;
-  if (lse_out && piece == 0) lse_out[rh] = m + logf(wa + wb);
 }
 
 // ---- fp32 kernel: one wavefront per (query row, head); keys across lanes ----
@@ -612,12 +619,13 @@ __global__ __launch_bounds__(256) void gather_pack_kernel(GatherArgs a) {
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
                          void* out, float* lse, int stages, float* part, int part_mode, const int32_t* loclist,
-                         int loc_cap, int rb_first, int rb_count, hipStream_t s) {
+                         int loc_cap, int rb_first, int rb_count, const float* lse_a, hipStream_t s) {
   AttArgs a;
   a.D = D; a.st = st; a.k_arena = k_arena; a.v_arena = v_arena; a.q = q; a.out = out; a.lse = lse;
   a.layer = layer; a.seq_count = seq_count; a.n_q = n_q; a.bp = bp;
   a.n_splits = 1; a.part = part;
-  a.part_mode = part_mode; a.loclist = loclist; a.loc_cap = loc_cap; a.rb_off = 0;
+  a.part_mode = part_mode; a.loclist = loclist; a.loc_cap = loc_cap; a.rb_off = 0; a.lse_a = lse_a;
+  if (part_mode == ATT_RETRIEVED && !lse_a) return hipErrorInvalidValue;
   const bool mfma_ok = attend_on_matrix_cores(D);
   if (part_mode != ATT_ALL && (!mfma_ok || n_q <= ATT_SPLIT_MAX_ROWS)) return hipErrorInvalidValue;
   if (mfma_ok) {
@@ -674,16 +682,6 @@ void attend_launch_shape(const Dims& D, int seq_count, int n_q, int* wgs_per_row
 hipError_t launch_local_list(const Dims& D, const BatchPos& bp, int seq_count, int32_t* loclist, int loc_cap,
                              hipStream_t s) {
   local_list_kernel<<<dim3((loc_cap + 255) / 256, seq_count), 256, 0, s>>>(D, bp, loclist, loc_cap);
-  return hipGetLastError();
-}
-
-hipError_t launch_attend_merge_parts(const Dims& D, int seq_count, int n_q, void* out, const void* o_b,
-                                     const float* lse_a, const float* lse_b, float* lse_out, hipStream_t s) {
-  const long long n_rows = (long long)seq_count * n_q * D.Hq;
-  const long long blocks = (n_rows * 16 + 255) / 256;
-  attend_merge_parts_kernel<<<dim3((unsigned)blocks), 256, 0, s>>>(reinterpret_cast<uint16_t*>(out),
-                                                                  reinterpret_cast<const uint16_t*>(o_b), lse_a, lse_b,
-                                                                  lse_out, n_rows);
   return hipGetLastError();
 }
 

@@ -140,8 +140,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.qstate = o;  o = align_up(o + (size_t)P * 4 * 8, 256);
   CL.lpart = o;   o = align_up(o + (c.rep_mode == LTRI_REP_DYNAMIC || c.seg_map == LTRI_MAP_SOFTMAX ? (size_t)P * G * nb * Lp * 16 : 0), 256);
   CL.loc_cap = (int)align_up((size_t)c.n_sink + c.window, ATT_BN) + ATT_BN;
-  CL.att_o2 = o;    o = align_up(o + (size_t)c.n_seqs * c.chunk_max * c.n_q_heads * c.head_dim * D.elt, 256);
-  CL.att_lse2 = o;  o = align_up(o + 2 * (size_t)c.n_seqs * c.chunk_max * c.n_q_heads * 4, 256);
+  CL.att_lse2 = o;  o = align_up(o + (size_t)c.n_seqs * c.chunk_max * c.n_q_heads * 4, 256);
   CL.loclist = o;   o = align_up(o + (size_t)c.n_seqs * CL.loc_cap * 4, 256);
   CL.total = o;
   CL.max_problems = P;
@@ -206,7 +205,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
                      (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds), (uint8_t*)(t + CL.selflag), (float*)(t + CL.att_part),
                      (int32_t*)(t + CL.tokspan), (double*)(t + CL.dyn), (double*)(t + CL.lpart),
                      (uint32_t*)(t + CL.qhist), (unsigned long long*)(t + CL.qstate),
-                     (void*)(t + CL.att_o2), (float*)(t + CL.att_lse2), (int32_t*)(t + CL.loclist)};
+                     (float*)(t + CL.att_lse2), (int32_t*)(t + CL.loclist)};
   const size_t n = (size_t)D.n_layers * D.n_seqs;
   c->n_tokens.assign(n, 0);
   c->last_len.assign(n, 0);
@@ -592,7 +591,7 @@ int32_t ltri_attend(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_c
                   seq_begin + s);
   if (!c->dry) {
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_q, out, lse,
-                                   c->attend_stages, c->dc.att_part, 0, nullptr, 0, 0, -1, c->stream), "attend");
+                                   c->attend_stages, c->dc.att_part, 0, nullptr, 0, 0, -1, nullptr, c->stream), "attend");
     if (r != LTRI_OK) return r;
   }
   return LTRI_OK;
@@ -627,40 +626,40 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   memset(&bp, 0, sizeof bp);
   int32_t r = append_common(c, layer, seq_begin, seq_count, k_chunk, v_chunk, n_new, bp);
   if (r != LTRI_OK) return r;
-  const size_t plane = (size_t)c->D.n_seqs * c->D.chunk_max * c->D.Hq;
   float* lse_a = c->dc.att_lse2;
-  float* lse_b = c->dc.att_lse2 + plane;
+  const bool rest = rb_side < n_rb;        // row blocks of the first part that do not start early
   // Context's stream: the kernels of step 1 that fill the chip, the fork, then the small kernels of steps 1 and 2.
-  r = check_hip(c, launch_local_list(c->D, bp, seq_count, c->dc.loclist, c->CL.loc_cap, c->stream), "local list");
-  if (r != LTRI_OK) return r;
+  if (rest) {
+    r = check_hip(c, launch_local_list(c->D, bp, seq_count, c->dc.loclist, c->CL.loc_cap, c->stream), "local list");
+    if (r != LTRI_OK) return r;
+  }
   r = append_spans(c, layer, bp, seq_count, q_seg, n_new, c->ev_fork);
   if (r != LTRI_OK) return r;
   append_commit(c, layer, seq_begin, seq_count, n_new);
   // Second stream, behind the fork: attention over initial | window | chunk for the later (longer) row blocks.
   r = check_hip(c, hipStreamWaitEvent(c->side, c->ev_fork, 0), "fork");
+  if (r == LTRI_OK && !rest)
+    r = check_hip(c, launch_local_list(c->D, bp, seq_count, c->dc.loclist, c->CL.loc_cap, c->side), "local list");
   if (r == LTRI_OK)
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse_a,
                                    c->step_stages, nullptr, 1, c->dc.loclist, c->CL.loc_cap, n_rb - rb_side, rb_side,
-                                   c->side), "attend (initial, window, chunk)");
+                                   nullptr, c->side), "attend (initial, window, chunk)");
   if (r == LTRI_OK) r = check_hip(c, hipEventRecord(c->ev_join, c->side), "join");
   if (r != LTRI_OK) return r;
   r = ltri_retrieve(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr);
-  // Context's stream again: the remaining row blocks of the first part and the retrieved tokens; their
-  // workgroups take the compute units as the second stream's workgroups leave them.
-  if (r == LTRI_OK)
+  // Context's stream again: the remaining row blocks of the first part, the join, and the retrieved tokens,
+  // whose launch folds the first part's result into its own.
+  if (r == LTRI_OK && rest)
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse_a,
                                    c->step_stages, nullptr, 1, c->dc.loclist, c->CL.loc_cap, 0, n_rb - rb_side,
-                                   c->stream), "attend (initial, window, chunk)");
-  if (r == LTRI_OK)
-    r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, c->dc.att_o2,
-                                   lse_b, c->step_stages, nullptr, 2, nullptr, 0, 0, -1, c->stream),
-                  "attend (retrieved)");
+                                   nullptr, c->stream), "attend (initial, window, chunk)");
   // join even after an error, so that the context's stream never runs ahead of the second stream's writes to out
   const int32_t rj = check_hip(c, hipStreamWaitEvent(c->stream, c->ev_join, 0), "join");
   if (r != LTRI_OK) return r;
   if (rj != LTRI_OK) return rj;
-  return check_hip(c, launch_attend_merge_parts(c->D, seq_count, n_new, out, c->dc.att_o2, lse_a, lse_b, lse,
-                                                c->stream), "merge of the two parts");
+  return check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse,
+                                    c->step_stages, nullptr, 2, nullptr, 0, 0, -1, lse_a, c->stream),
+                   "attend (retrieved)");
 }
 
 int32_t ltri_gather_pack(ltri_ctx* c, int32_t layer, int32_t seq, void* k_packed, void* v_packed,

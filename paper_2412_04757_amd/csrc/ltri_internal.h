@@ -67,8 +67,7 @@ struct ScratchLayout {
   size_t qhist;    // uint32 [P][QUANT_BINS]  histogram of one digit of the map cells' order keys (percentile theta)
   size_t qstate;   // uint64 [P][4]   key prefix found so far, rank still to go, theta (double bits), unused
   size_t lpart;    // double [P][G][nb][Lp][2]  per tile: row maximum and sum of exponentials (row log-sum-exp in pieces)
-  size_t att_o2;   // dtype  [n_seqs][chunk_max][Hq][d]  attention over the retrieved tokens alone (overlapped step)
-  size_t att_lse2; // float  [2][n_seqs][chunk_max][Hq]  log-sum-exp of the two parts of an overlapped step
+  size_t att_lse2; // float  [n_seqs][chunk_max][Hq]  log-sum-exp of the first part of an overlapped step
   size_t loclist;  // int32  [n_seqs][loc_cap]  initial | window tokens (overlapped step)
   size_t total;
   int    loc_cap;       // entries of one sequence's initial | window list, whole tiles plus one
@@ -115,7 +114,7 @@ struct DevScratch {
   double* rowsum; double* csuf; double* tsum; double* rcar; double* ccar;
   double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds; uint8_t* selflag; float* att_part;
   int32_t* tokspan; double* dyn; double* lpart; uint32_t* qhist; unsigned long long* qstate;
-  void* att_o2; float* att_lse2; int32_t* loclist;
+  float* att_lse2; int32_t* loclist;
 };
 
 // ---- launchers (each returns the hipError_t of the launch) ----
@@ -145,14 +144,13 @@ hipError_t launch_force_list(const Dims& D, const DevState& st, int layer, int s
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
                          void* out, float* lse, int stages, float* part, int part_mode, const int32_t* loclist,
-                         int loc_cap, int rb_first, int rb_count, hipStream_t s);   // rb_count < 0: every row block
+                         int loc_cap, int rb_first, int rb_count, const float* lse_a,
+                         hipStream_t s);   // rb_count < 0: every row block; lse_a: first part's, for the retrieved part
 // workgroups per block of query rows and number of such blocks of the matrix-core kernel's launch
 void attend_launch_shape(const Dims& D, int seq_count, int n_q, int* wgs_per_row_block, int* row_blocks);
 bool attend_on_matrix_cores(const Dims& D);      // the bf16 kernel takes this shape (else one wavefront per query row)
 hipError_t launch_local_list(const Dims& D, const BatchPos& bp, int seq_count, int32_t* loclist, int loc_cap,
                              hipStream_t s);
-hipError_t launch_attend_merge_parts(const Dims& D, int seq_count, int n_q, void* out, const void* o_b,
-                                     const float* lse_a, const float* lse_b, float* lse_out, hipStream_t s);
 hipError_t launch_gather_pack(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                               int layer, int seq, void* k_packed, void* v_packed, int32_t* n_tokens,
                               hipStream_t s);
