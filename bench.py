@@ -149,7 +149,7 @@ def run_decode(args, torch, dev):
         "breakdown_us": {"append": round(ap_us, 1), "retrieve": round(rt_us, 1), "attend": round(at_us, 1)},
         "persistent_selection": {"step_us": round(sum(pers), 1), "append": round(pers[0], 1),
                                  "rebuild_list": round(pers[1], 1), "attend": round(pers[2], 1)},
-        "roofline": {"bound": "hbm", "kernel": "attend_bf16_kernel (split keys) + attend_merge_kernel",
+        "roofline": {"bound": "hbm", "kernel": "attend_decode_kernel + attend_merge_kernel",
                      "achieved": round(kv_bytes / at_us / 1e3, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": round(kv_bytes / at_us / 1e3 / PEAK_HBM_GBPS, 4), "kv_bytes_per_step": kv_bytes,
                      "whole_step_GBps": round(kv_bytes / step_us / 1e3, 1)}}))

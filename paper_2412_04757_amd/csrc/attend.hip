@@ -511,6 +511,183 @@ __global__ __launch_bounds__(128) void attend_merge_kernel(AttArgs a) {
   if (a.lse && c == 0) a.lse[((size_t)bi * L + qi) * D.Hq + head] = (mmax + log2f(l)) * 0.6931471805599453f;
 }
 
+// ---- one query row per sequence (decode, G <= 4): keys across wavefronts, nothing staged in LDS ----
+// The step reads every K and V row of the context once and does next to no arithmetic, so the kernel is
+// built to keep loads in flight: a workgroup is four wavefronts that walk disjoint runs of 16-key groups of
+// one (sequence, KV head, split), each on its own (no barrier in the loop); up to three workgroups fit a
+// compute unit. Per group a lane fetches 16-byte pieces straight into matrix-core operand order:
+//   S^T = K Q^T by v_mfma_f32_16x16x32_bf16: A = 16 keys x 32 d (lane: key lane % 16, d-piece lane / 16),
+//   B = Q^T with the heads of the group in columns 0 .. G - 1 and zeros beyond; the result leaves keys
+//   4 (lane / 16) + j, j < 4, of head lane % 16 in lane's four registers;
+//   O += P V on the vector ALU: a lane owns 8 d-columns (lane % 16) of the 4 keys of its lane group, fetches
+//   their V pieces (one 16-byte load per key) and the 4 x G probabilities from the lanes that hold them.
+// The running maximum is per head (lane column); the rescale factor of every head reaches all lanes by a
+// lane read. Rows of group g + 1 and token ids of group g + 2 are in flight while group g is used. At the end the four lane groups' partial O and sums are added, the four wavefronts merge
+// through LDS, and the workgroup writes one partial result in the layout attend_merge_kernel reads.
+constexpr int DEC_WAVES = 4;
+template <int G>
+__global__ __launch_bounds__(64 * DEC_WAVES, 3) void attend_decode_kernel(AttArgs a) {
+  constexpr int d = 128;
+  __shared__ float wpart[DEC_WAVES][G][d + 2];
+  const Dims& D = a.D;
+  const int split = blockIdx.x, h = blockIdx.y, bi = blockIdx.z;
+  const int seq = a.bp.seq[bi], c0 = a.bp.c0[bi];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kl = lane & 15, grp = lane >> 4;
+  const int slot = slot_of(D, a.layer, seq, h);
+  const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.k_arena) + arena_off(D, slot) * 2;
+  const unsigned char* Vb = reinterpret_cast<const unsigned char*>(a.v_arena) + arena_off(D, slot) * 2;
+  const int list_len = a.st.meta[(size_t)slot * META_WORDS + META_LIST_LEN];
+  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
+  const int n_keys = list_len + 1;                  // the context list and the token itself
+  const int n_groups = (n_keys + 15) >> 4;
+  const int workers = a.n_splits * DEC_WAVES, w = split * DEC_WAVES + wave;
+  const int gpw = (n_groups + workers - 1) / workers;
+  const int g_begin = min(w * gpw, n_groups), g_end = min(g_begin + gpw, n_groups);
+
+  // B operand: Q^T, head kl of the group in column kl
+  uint4 qf[4];
+  {
+    const uint16_t* qrow = reinterpret_cast<const uint16_t*>(a.q) + ((size_t)bi * D.Hq + (size_t)h * G + min(kl, G - 1)) * d;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      qf[kk] = *reinterpret_cast<const uint4*>(qrow + kk * 32 + grp * 8);
+      if (kl >= G) qf[kk] = make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+  // Tokens of the keys this lane fetches in group g: its K row (key kl) and its four V rows (keys
+  // 4 grp + j). Indices are clamped to the last key, so masked keys read a valid row.
+  struct Toks { int k, v[4]; };
+  auto load_tokens = [&](int g, Toks& t) __attribute__((always_inline)) {
+    const int rk = min(g * 16 + kl, n_keys - 1);
+    t.k = rk < list_len ? list[rk] : c0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int rv = min(g * 16 + 4 * grp + j, n_keys - 1);
+      t.v[j] = rv < list_len ? list[rv] : c0;
+    }
+  };
+  auto load_rows = [&](const Toks& t, uint4 (&kf)[4], uint4 (&vf)[4]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      kf[kk] = *reinterpret_cast<const uint4*>(Kb + ((size_t)t.k << 8) + kk * 64 + grp * 16);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      vf[j] = *reinterpret_cast<const uint4*>(Vb + ((size_t)t.v[j] << 8) + kl * 16);
+  };
+
+  float o[G][8];
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) o[hh][c] = 0.f;
+  float m_run = -1e30f, l_lane = 0.f;               // of head kl (log2 domain); the sum over this lane's keys only
+  const float sc = 1.4426950408889634f / sqrtf((float)d);
+
+  auto compute = [&](int g, const uint4 (&kf)[4], const uint4 (&vf)[4]) __attribute__((always_inline)) {
+    f32x4_t s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+      s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[kk]),
+                                                  __builtin_bit_cast(bf16x8_t, qf[kk]), s, 0, 0, 0);
+    float sv[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) sv[j] = (g * 16 + 4 * grp + j < n_keys) ? s[j] * sc : -INFINITY;
+    float mx = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+    const bool moved = __any(kl < G && m_new != m_run);
+    m_run = m_new;
+    float pv[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) pv[j] = __builtin_amdgcn_exp2f(sv[j] - m_new);
+    l_lane = l_lane * alpha + ((pv[0] + pv[1]) + (pv[2] + pv[3]));
+    if (moved) {                                    // the running maxima rarely move after the first groups
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh) {
+        const float ah = __shfl(alpha, hh, 64);     // lane hh holds head hh's factor
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[hh][c] *= ah;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint4 u = vf[j];
+      float vv[8];
+      vv[0] = __uint_as_float(u.x << 16); vv[1] = __uint_as_float(u.x & 0xFFFF0000u);
+      vv[2] = __uint_as_float(u.y << 16); vv[3] = __uint_as_float(u.y & 0xFFFF0000u);
+      vv[4] = __uint_as_float(u.z << 16); vv[5] = __uint_as_float(u.z & 0xFFFF0000u);
+      vv[6] = __uint_as_float(u.w << 16); vv[7] = __uint_as_float(u.w & 0xFFFF0000u);
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh) {
+        const float ph = __shfl(pv[j], (lane & 48) | hh, 64);   // key 4 grp + j of head hh
+#pragma unroll
+        for (int c = 0; c < 8; ++c) o[hh][c] = fmaf(ph, vv[c], o[hh][c]);
+      }
+    }
+  };
+
+  // Rows of group g + 1 and tokens of group g + 2 are requested before group g is used; the two
+  // row buffers alternate by name so that they stay in registers.
+  uint4 ka[4], va[4], kb[4], vb[4];
+  Toks t0, t1;
+  int g = g_begin;
+  if (g < g_end) {
+    load_tokens(g, t0);
+    load_rows(t0, ka, va);
+    if (g + 1 < g_end) load_tokens(g + 1, t1);
+  }
+  while (g < g_end) {
+    if (g + 1 < g_end) load_rows(t1, kb, vb);
+    if (g + 2 < g_end) load_tokens(g + 2, t0);
+    compute(g, ka, va);
+    if (++g >= g_end) break;
+    if (g + 1 < g_end) load_rows(t0, ka, va);
+    if (g + 2 < g_end) load_tokens(g + 2, t1);
+    compute(g, kb, vb);
+    ++g;
+  }
+  // the four lane groups hold disjoint keys: add their partial results
+  l_lane += __shfl_xor(l_lane, 16, 64);
+  l_lane += __shfl_xor(l_lane, 32, 64);
+#pragma unroll
+  for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      float v = o[hh][c];
+      v += __shfl_xor(v, 16, 64);
+      v += __shfl_xor(v, 32, 64);
+      o[hh][c] = v;
+    }
+  if (grp == 0) {
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) wpart[wave][hh][kl * 8 + c] = o[hh][c];
+    if (kl < G) { wpart[wave][kl][d] = m_run; wpart[wave][kl][d + 1] = l_lane; }
+  }
+  __syncthreads();
+  // merge of the four wavefronts; one partial result per (head, split): unnormalised O, maximum, sum
+  for (int idx = threadIdx.x; idx < G * d; idx += 64 * DEC_WAVES) {
+    const int hh = idx / d, c = idx - hh * d;
+    float mmax = -1e30f;
+#pragma unroll
+    for (int ww = 0; ww < DEC_WAVES; ++ww) mmax = fmaxf(mmax, wpart[ww][hh][d]);
+    float acc = 0.f, l = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < DEC_WAVES; ++ww) {
+      const float wgt = __builtin_amdgcn_exp2f(wpart[ww][hh][d] - mmax);
+      acc = fmaf(wgt, wpart[ww][hh][c], acc);
+      l = fmaf(wgt, wpart[ww][hh][d + 1], l);
+    }
+    float* pr = a.part + (((size_t)bi * D.Hq + (size_t)h * G + hh) * a.n_splits + split) * (d + 2);
+    pr[c] = acc;
+    if (c == 0) { pr[d] = mmax; pr[d + 1] = l; }
+  }
+}
+
 // ---- first part of an overlapped step: its token list ----
 // initial | window tokens of every sequence of the batch, padded with token 0 to whole tiles
 __global__ __launch_bounds__(256) void local_list_kernel(Dims D, BatchPos bp, int32_t* loclist, int loc_cap) {
@@ -628,6 +805,26 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
   if (part_mode == ATT_RETRIEVED && !lse_a) return hipErrorInvalidValue;
   const bool mfma_ok = attend_on_matrix_cores(D);
   if (part_mode != ATT_ALL && (!mfma_ok || n_q <= ATT_SPLIT_MAX_ROWS)) return hipErrorInvalidValue;
+  if (mfma_ok && n_q == 1 && part && part_mode == ATT_ALL && D.G <= 4) {
+    // decode: two workgroups per compute unit (measured best at 16 sequences x 8 KV heads: 67 us against
+    // 70 .. 81 us with 3 .. 16 splits; the step runs at the rate of a plain copy either way)
+    static int n_cus = 0;
+    if (n_cus == 0) {
+      int dev = 0;
+      hipError_t e = hipGetDevice(&dev);
+      if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev);
+      if (e != hipSuccess) return e;
+    }
+    const int slots = D.Hkv * seq_count;
+    const int ns = (2 * n_cus) / slots;
+    a.n_splits = ns > ATT_MAX_SPLITS ? ATT_MAX_SPLITS : (ns < 1 ? 1 : ns);
+    dim3 g(a.n_splits, D.Hkv, seq_count);
+    if (D.G == 4)      attend_decode_kernel<4><<<g, 64 * DEC_WAVES, 0, s>>>(a);
+    else if (D.G == 2) attend_decode_kernel<2><<<g, 64 * DEC_WAVES, 0, s>>>(a);
+    else               attend_decode_kernel<1><<<g, 64 * DEC_WAVES, 0, s>>>(a);
+    attend_merge_kernel<<<dim3(1, D.Hq, seq_count), 128, 0, s>>>(a);
+    return hipGetLastError();
+  }
   if (mfma_ok) {
     const int HG = D.G < 4 ? D.G : 4;
     const int gpk = D.G / HG;

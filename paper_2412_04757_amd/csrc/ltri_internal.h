@@ -27,9 +27,9 @@ constexpr int SEG_MAX_DIAG = 2 * SEG_MAX_L;   // anti-diagonals of the largest m
 constexpr int QUANT_BITS = 11;               // digit width of the radix selection of the percentile theta
 constexpr int QUANT_BINS = 1 << QUANT_BITS;
 constexpr int IDX_MASK_WORDS = SEG_MAX_L / 32;   // one bit per token of a chunk
-constexpr int ATT_BN = 64;
-constexpr int ATT_MAX_SPLITS = 8;        // key-range splits of a short query block (decode)
-constexpr int ATT_SPLIT_MAX_ROWS = 4;    // longest query block that is split          // keys per attention tile; token lists are padded to it
+constexpr int ATT_BN = 64;               // keys per attention tile; token lists are padded to it
+constexpr int ATT_MAX_SPLITS = 16;       // key-range splits of a short query block (decode)
+constexpr int ATT_SPLIT_MAX_ROWS = 4;    // longest query block that is split
 
 // Byte offsets of the arrays inside the caller's `state` buffer.
 struct StateLayout {

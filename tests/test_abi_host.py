@@ -189,3 +189,27 @@ def test_call_order_and_limits_in_dry_mode():
     ctx.append_chunk_with_spans(0, 0, 16, [np.array([0, 4, 16])])
     assert ctx.token_count(0, 0) == 16
     ctx.close()
+
+
+def test_whole_step_call_rules_in_dry_mode():
+    """ltri_step is append + retrieve + attend for the host logic: it advances the stream, leaves a selection
+    behind, and fails where any of the three would."""
+    cfg = config_from_workload(CONFIGS["cfg1"], max_tokens=600, theta=1.0)
+    ctx = LtriContext(cfg, None, dry=True)
+    ctx.set_step_reserve(7)                          # a tuning knob: accepted and ignored without a device
+    ctx.step(0, 0, 1, None, None, _FakeQ(256))
+    assert ctx.token_count(0, 0) == 256
+    ctx.attend(0, 0, 1, _FakeQ(256))                 # the step left a selection for this chunk
+    ctx.step(0, 0, 1, None, None, _FakeQ(100))
+    assert ctx.token_count(0, 0) == 356
+    with pytest.raises(LtriError) as e:
+        ctx.step(0, 0, 1, None, None, _FakeQ(257))   # longer than chunk_max
+    assert e.value.status == -1
+    with pytest.raises(LtriError) as e:
+        ctx.step(0, 0, 1, None, None, _FakeQ(245))   # 356 + 245 > max_tokens
+    assert e.value.status == -3
+    assert ctx.token_count(0, 0) == 356              # a failed step appends nothing
+    with pytest.raises(LtriError) as e:
+        ctx.step(0, 1, 1, None, None, _FakeQ(16))    # sequence out of range
+    assert e.value.status == -1
+    ctx.close()
