@@ -221,18 +221,19 @@ int32_t ltri_attend(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq
 
 /* One whole step of the path for one chunk (Sec. 3.4, the three steps): the same results as
  * ltri_append_chunk(k_chunk, v_chunk, q_seg) + ltri_retrieve(q) + ltri_attend(q), arguments as there
- * (k_chunk / v_chunk may both be NULL when the rows are already in the arenas; q_seg and lse may be NULL;
- * the selection is not copied out, read it with ltri_get_selection). What this
- * call adds is the schedule: the attention over initial tokens, window and the chunk itself depends on
- * neither step 1 nor step 2. Most of its blocks of query rows are queued on a second stream the context
- * owns, behind the kernels of step 1 that fill the chip, and run while the many small kernels of steps 1
- * and 2 (candidate selection, index vectors, scoring, top-k) use the compute units left free for them; the
- * remaining row blocks and the attention over the retrieved tokens follow on the context's stream, and a
- * last kernel there merges the two parts by their log-sum-exp. The context's stream waits for the second one before the merge, so for the caller
- * everything is ordered on the context's stream as with the three calls; `out` and `lse` hold the result
- * once that stream reaches the end of this call's work. The two parts are rounded to the dtype before the
- * merge, so `out` can differ from ltri_attend's by one more rounding of the dtype. Chunks of at most 4
- * rows, fp32 contexts and group sizes the matrix-core kernel does not take run the three calls in order.
+ * (k_chunk / v_chunk may both be NULL when the rows are already in the arenas; q_seg and lse may be
+ * NULL; the selection is not copied out, read it with ltri_get_selection).
+ * What this call adds is the schedule. The attention over initial tokens, window and the chunk itself
+ * depends on neither step 1 nor step 2: it is queued on a second stream the context owns, behind the
+ * kernels of step 1 that fill the chip, and runs while the many small kernels of steps 1 and 2
+ * (candidate selection, index vectors, scoring, top-k) take the compute units its shorter workgroups
+ * leave. The attention over the retrieved tokens follows on the context's stream once the first part
+ * is done, and folds the first part's output in by the two log-sum-exps as it writes. The context's
+ * stream waits for the second stream before that launch, so for the caller everything is ordered on
+ * the context's stream as with the three calls: `out` and `lse` hold the result once that stream
+ * reaches the end of this call's work. The first part is rounded to the dtype before it is folded in,
+ * so `out` can differ from ltri_attend's by one more rounding of the dtype. Chunks of at most 4 rows,
+ * fp32 contexts and group sizes the matrix-core kernel does not take run the three calls in order.
  * Errors: those of the three calls. */
 int32_t ltri_step(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* k_chunk,
                   const void* v_chunk, const void* q_seg, const void* q, int32_t n_new, void* out, float* lse);
