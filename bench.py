@@ -94,7 +94,7 @@ def run_decode(args, torch, dev):
     w = CONFIGS["cfg5"]
     T0 = args.context or w.context
     n_seqs, L, steps, warm = 16, 2048, max(8, args.steps * 8), 4
-    T = T0 + 2 * steps + warm                   # the second half of the steps keeps the selection (persistent mechanism)
+    T = T0 + 3 * steps + warm                   # a third of the steps keeps the selection (persistent mechanism), a third goes through ltri_step
     cfg = config_from_workload(w, max_tokens=T, theta=theta_default(w.head_dim), n_layers=1, n_seqs=n_seqs)
     ctx = LtriContext(cfg, dev)
     ka, va = ctx.arena_views()
@@ -111,7 +111,7 @@ def run_decode(args, torch, dev):
             ctx.append_chunk_with_spans(0, s, n, b)
         del K, V, Q
     out = torch.empty((n_seqs, 1, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
-    qsteps = [torch.stack([Qs[s][k:k + 1] for s in range(n_seqs)]).contiguous() for k in range(2 * steps + warm)]
+    qsteps = [torch.stack([Qs[s][k:k + 1] for s in range(n_seqs)]).contiguous() for k in range(3 * steps + warm)]
     for k in range(warm):
         ctx.append_chunk(0, 0, n_seqs, 1)
         ctx.retrieve(0, 0, n_seqs, qsteps[k])
@@ -132,6 +132,11 @@ def run_decode(args, torch, dev):
         e[1].record(); ctx.retrieve_persistent(0, 0, n_seqs)
         e[2].record(); ctx.attend(0, 0, n_seqs, qsteps[k], out=out)
         e[3].record(); pevs.append(e)
+    sevs = []                                   # ltri_step: steps 1 and 2 in one launch, then step 3
+    for k in range(warm + 2 * steps, warm + 3 * steps):
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        e[0].record(); ctx.step(0, 0, n_seqs, None, None, qsteps[k], out=out)
+        e[1].record(); sevs.append(e)
     torch.cuda.synchronize()
     if ctx.sync_status() != 0:
         print("bench.py: device status", ctx.sync_status(), file=sys.stderr)
@@ -140,12 +145,15 @@ def run_decode(args, torch, dev):
     ap_us, rt_us, at_us = med(0), med(1), med(2)
     pers = [med(i, pevs) for i in range(3)]
     kv_bytes = n_att * w.head_dim * 2 * 2
-    step_us = ap_us + rt_us + at_us
+    calls_us = ap_us + rt_us + at_us
+    step_us = med(0, sevs) if args.schedule == "step" else calls_us
     print(json.dumps({
         "metric": "decode step time per layer", "value": round(step_us, 1), "unit": "us", "n_gpus": 1, "steps": steps,
         "warmup": warm, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"cfg5: 16 sequences x {T0} tokens, 32 query / 8 KV heads, head_dim 128, bf16, 4 sink tokens, "
                                f"window {w.window}, retrieval budget {w.budget_tokens} tokens, one token per step"},
+        "schedule": "ltri_step (append and retrieve in one launch, then attend)" if args.schedule == "step" else "three calls",
+        "three_calls_us": round(calls_us, 1),
         "breakdown_us": {"append": round(ap_us, 1), "retrieve": round(rt_us, 1), "attend": round(at_us, 1)},
         "persistent_selection": {"step_us": round(sum(pers), 1), "append": round(pers[0], 1),
                                  "rebuild_list": round(pers[1], 1), "attend": round(pers[2], 1)},

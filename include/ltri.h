@@ -232,8 +232,10 @@ int32_t ltri_attend(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq
  * stream waits for the second stream before that launch, so for the caller everything is ordered on
  * the context's stream as with the three calls: `out` and `lse` hold the result once that stream
  * reaches the end of this call's work. The first part is rounded to the dtype before it is folded in,
- * so `out` can differ from ltri_attend's by one more rounding of the dtype. Chunks of at most 4 rows,
- * fp32 contexts and group sizes the matrix-core kernel does not take run the three calls in order.
+ * so `out` can differ from ltri_attend's by one more rounding of the dtype. A one-token chunk (decode)
+ * runs steps 1 and 2 in one kernel launch and then step 3, all on the context's stream, with results
+ * identical to the three calls. Chunks of 2 to 4 rows, fp32 contexts and group sizes the matrix-core
+ * kernel does not take run the three calls in order.
  * Errors: those of the three calls. */
 int32_t ltri_step(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* k_chunk,
                   const void* v_chunk, const void* q_seg, const void* q, int32_t n_new, void* out, float* lse);

@@ -470,7 +470,7 @@ int32_t ltri_retrieve(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq
     long long bound = 0;
     for (int s = 0; s < seq_count; ++s) bound = std::max(bound, c->span_bound[ls_index(c, layer, seq_begin + s)]);
     r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound, sel_ids,
-                                     sel_cnt, nullptr, c->stream), "retrieve");
+                                     sel_cnt, nullptr, nullptr, c->stream), "retrieve");
     if (r != LTRI_OK) return r;
   }
   for (int s = 0; s < seq_count; ++s) {
@@ -512,7 +512,7 @@ int32_t ltri_retrieve_collaborative(ltri_ctx* c, int32_t layer, int32_t seq_begi
     long long bound = 0;
     for (int s = 0; s < seq_count; ++s) bound = std::max(bound, c->span_bound[ls_index(c, layer, seq_begin + s)]);
     r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound,
-                                     sel_ids, sel_cnt, &v, c->stream), "collaborative retrieve");
+                                     sel_ids, sel_cnt, &v, nullptr, c->stream), "collaborative retrieve");
     if (r != LTRI_OK) return r;
   }
   for (int s = 0; s < seq_count; ++s) {
@@ -614,6 +614,33 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
     attend_launch_shape(c->D, seq_count, n_new, &wgs_per_rb, &n_rb);
     rb_side = std::min(n_rb, (c->n_cus - c->reserve_cus) / wgs_per_rb);
     overlap = rb_side > 0;
+  }
+  if (!overlap && !c->dry && n_new == 1) {
+    // Decode: steps 1 and 2 of a one-token chunk in one launch where that kernel applies, then step 3.
+    BatchPos bp;
+    memset(&bp, 0, sizeof bp);
+    int32_t r = append_common(c, layer, seq_begin, seq_count, k_chunk, v_chunk, 1, bp);
+    if (r != LTRI_OK) return r;
+    long long bound = 0;
+    for (int s = 0; s < seq_count; ++s)
+      bound = std::max(bound, std::min<long long>(c->span_bound[ls_index(c, layer, seq_begin + s)] + 1, c->D.max_spans));
+    if (retrieve_is_one_launch(c->D, 1, (int)bound)) {
+      append_commit(c, layer, seq_begin, seq_count, 1);
+      r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, 1, (int)bound,
+                                       nullptr, nullptr, nullptr, c->k_arena, c->stream), "append and retrieve (one token)");
+      if (r != LTRI_OK) return r;
+      for (int s = 0; s < seq_count; ++s) {
+        c->have_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
+        c->ever_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
+      }
+    } else {
+      r = append_spans(c, layer, bp, seq_count, q_seg, 1, nullptr);
+      if (r != LTRI_OK) return r;
+      append_commit(c, layer, seq_begin, seq_count, 1);
+      r = ltri_retrieve(c, layer, seq_begin, seq_count, q, 1, nullptr, nullptr);
+      if (r != LTRI_OK) return r;
+    }
+    return ltri_attend(c, layer, seq_begin, seq_count, q, 1, out, lse);
   }
   if (!overlap) {
     int32_t r = ltri_append_chunk(c, layer, seq_begin, seq_count, k_chunk, v_chunk, q_seg, n_new);

@@ -17,6 +17,7 @@ struct RetArgs {
   int layer; int seq_count; int n_q; int Lp;
   int batch_off; int units_cap;          // two-stage query representatives (long chunks)
   int32_t* sel_ids_out; int32_t* sel_cnt_out;
+  const void* k_arena; int append_first;  // one-token chunk: step 1 (the token becomes a span of its own) in the same launch
   BatchPos bp;
 };
 
@@ -544,9 +545,39 @@ __global__ __launch_bounds__(1024) void retrieve_one_token_kernel(RetArgs a, int
   const Dims& D = a.D;
   const int p = blockIdx.x, bi = p / D.Hkv, h = p - bi * D.Hkv;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
-  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
-  const int n = min(meta[META_N_SPANS], bound), c0 = meta[META_CHUNK_START];
+  int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int d = D.d, tid = threadIdx.x;
+  int n = meta[META_N_SPANS], c0 = meta[META_CHUNK_START];
+  // Step 1 of a one-token chunk, if asked for: the token is appended as a span of one, its key is the
+  // stored vector (what append_single_kernel does). The table entry written here is read back below by
+  // other threads of this workgroup, so a barrier stands on either side of the writes.
+  if (a.append_first) {
+    const int base = n;
+    c0 = a.bp.c0[bi];
+    const bool fits = base + 1 <= D.max_spans;
+    __syncthreads();                                    // every thread has read the old count
+    if (fits && tid < d) {
+      const T* row = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * d;
+      (reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + base) * d)[tid] = row[tid];
+    }
+    if (tid == 0) {
+      if (fits) {
+        a.st.span_start[(size_t)slot * D.max_spans + base] = c0;
+        a.st.span_len[(size_t)slot * D.max_spans + base] = 1;
+      } else {
+        atomicCAS(&a.st.err[0], 0, LTRI_ECAPACITY);
+      }
+      meta[META_N_SPANS] = fits ? base + 1 : base;
+      meta[META_CHUNK_FIRST] = base;
+      meta[META_CHUNK_NSP] = fits ? 1 : 0;
+      meta[META_CHUNK_START] = c0;
+      meta[META_CHUNK_LEN] = 1;
+    }
+    n = fits ? base + 1 : base;
+    __threadfence_block();
+    __syncthreads();
+  }
+  n = min(n, bound);
   const int npow = rt1_pow2(n);
   uint64_t* skey = reinterpret_cast<uint64_t*>(rt1_lds);
   uint32_t* sidx = reinterpret_cast<uint32_t*>(rt1_lds + (size_t)rt1_pow2(bound) * 8);
@@ -789,17 +820,24 @@ __global__ __launch_bounds__(1024) void force_list_kernel(ForceArgs a) {
   emit_selection(D, a.st, slot, selmask, n, nullptr, nullptr);
 }
 
+bool retrieve_is_one_launch(const Dims& D, int n_q, int span_bound) {
+  return n_q == 1 && span_bound >= 1 && span_bound <= RT1_MAX_SPANS && D.d == 128 && D.unit == 0;
+}
+
 hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,
                            const void* q, int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
-                           int32_t* sel_ids_out, int32_t* sel_cnt_out, const VoteArgs* votes, hipStream_t s) {
+                           int32_t* sel_ids_out, int32_t* sel_cnt_out, const VoteArgs* votes, const void* append_k_arena,
+                           hipStream_t s) {
   RetArgs a;
   a.D = D; a.st = st; a.sc = sc; a.q = q; a.layer = layer; a.seq_count = seq_count; a.n_q = n_q;
+  a.k_arena = append_k_arena; a.append_first = append_k_arena != nullptr;
+  if (a.append_first && !retrieve_is_one_launch(D, n_q, span_bound)) return hipErrorInvalidValue;
   a.Lp = (n_q + SEG_TB - 1) / SEG_TB * SEG_TB;
   a.sel_ids_out = sel_ids_out; a.sel_cnt_out = sel_cnt_out; a.bp = bp;
   const int P = seq_count * D.Hkv;
   const bool bf = D.dtype == LTRI_BF16;
   a.batch_off = 0;
-  if (n_q == 1 && span_bound >= 1 && span_bound <= RT1_MAX_SPANS && D.d == 128 && D.unit == 0) {
+  if (retrieve_is_one_launch(D, n_q, span_bound)) {
     // decode: the whole step in one launch
     static bool attr_set = false;
     if (!attr_set) {

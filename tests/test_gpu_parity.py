@@ -288,20 +288,65 @@ def test_one_token_step_edges(gpu_device):
             pos = T0 + k
             q = Q[pos:pos + 1].contiguous()
             qn = q.double().cpu().numpy()
-            ctx.append_chunk(0, 0, 1, 1)
+            whole = k == steps - 1          # the last step through ltri_step: append and retrieve in one launch
+            if whole:
+                out = ctx.step(0, 0, 1, None, None, q)[0].double().cpu().numpy()
+            else:
+                ctx.append_chunk(0, 0, 1, 1)
+                ctx.retrieve(0, 0, 1, q)
             st.append_chunk(1)
-            ctx.retrieve(0, 0, 1, q)
             sel = st.retrieve(qn)
             for h in range(w.n_kv_heads):
                 ids, scores = ctx.get_selection(0, 0, h)
                 np.testing.assert_allclose(scores, st.sel_scores[h], rtol=1e-12, atol=1e-12)
                 assert list(ids) == list(sel[h]), f"{kw}, step {k}, head {h}"
                 assert list(ctx.get_token_list(0, 0, h)) == list(st.context_tokens(h))
-            out = ctx.attend(0, 0, 1, q)[0].double().cpu().numpy()
+            if not whole:
+                out = ctx.attend(0, 0, 1, q)[0].double().cpu().numpy()
             want, _ = st.attend(qn)
             assert np.abs(out - want).max() <= 2e-2
         assert ctx.span_count(0, 0, 0) == 1536 + steps
+        for h in range(w.n_kv_heads):
+            assert spans_equal(ctx, st, h) and rep_keys_diff(ctx, st, h) == 0.0
         assert ctx.sync_status() == 0
+
+
+def test_one_token_steps_in_one_call_batched(gpu_device):
+    """Batched decode through ltri_step (steps 1 and 2 of a one-token chunk in one launch) against the three
+    calls on a second context: span tables, stored vectors, scores, selections, token lists and outputs
+    identical bit for bit over 24 steps; sequences of different lengths."""
+    w = Workload("mini-decode2", 8, 2, 128, "bf16", 2048 + 32, 512, 4, 128, 0, 256, "uniform", 16, 64)
+    n_seqs, steps = 3, 24
+    cfg = config_from_workload(w, max_tokens=2048 + 32, theta=theta_default(w.head_dim), n_layers=1, n_seqs=n_seqs)
+    ctxs = [LtriContext(cfg, gpu_device) for _ in range(2)]
+    streams = [planted_stream(w, 40 + s, device=str(gpu_device), context=2048 + 32) for s in range(n_seqs)]
+    T0 = [2048, 1024, 512]
+    for ctx in ctxs:
+        ka, va = ctx.arena_views()
+        for s, (K, V, Q, _) in enumerate(streams):
+            ka[0, s].copy_(K); va[0, s].copy_(V)
+            for c0 in range(0, T0[s], 512):
+                ctx.append_chunk(0, s, 1, 512)
+    for k in range(steps):
+        q = torch.stack([streams[s][2][T0[s] + k:T0[s] + k + 1] for s in range(n_seqs)]).contiguous()
+        out_a = ctxs[0].step(0, 0, n_seqs, None, None, q)
+        ctxs[1].append_chunk(0, 0, n_seqs, 1)
+        ctxs[1].retrieve(0, 0, n_seqs, q)
+        out_b = ctxs[1].attend(0, 0, n_seqs, q)
+        assert torch.equal(out_a, out_b), f"step {k}"
+        for s in range(n_seqs):
+            for h in range(w.n_kv_heads):
+                ia, sa = ctxs[0].get_selection(0, s, h)
+                ib, sb = ctxs[1].get_selection(0, s, h)
+                assert list(ia) == list(ib) and np.array_equal(sa, sb), (k, s, h)
+                assert list(ctxs[0].get_token_list(0, s, h)) == list(ctxs[1].get_token_list(0, s, h))
+    for s in range(n_seqs):
+        assert ctxs[0].token_count(0, s) == T0[s] + steps
+        for h in range(w.n_kv_heads):
+            a, b = ctxs[0].get_spans(0, s, h), ctxs[1].get_spans(0, s, h)
+            assert list(a[0]) == list(b[0]) and list(a[1]) == list(b[1])
+            assert torch.equal(ctxs[0].get_rep_keys(0, s, h), ctxs[1].get_rep_keys(0, s, h))
+    assert ctxs[0].sync_status() == 0 and ctxs[1].sync_status() == 0
 
 
 def test_persistent_selection_decode(gpu_device):
