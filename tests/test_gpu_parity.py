@@ -165,8 +165,9 @@ def test_whole_step_on_two_streams(gpu_device):
 
 
 def test_whole_step_copies_the_chunk_rows(gpu_device):
-    """ltri_step with k_chunk / v_chunk: the rows reach the arenas before either stream reads them. Arenas
-    start as NaN patterns, so a row read before its copy would poison the output."""
+    """ltri_step with k_chunk / v_chunk, on a stream of the caller's: the rows reach the arenas before either
+    of the library's streams reads them, and a consumer queued on the caller's stream right after the call
+    sees the finished output. Arenas start as NaN, so a row read before its copy would poison the output."""
     w = Workload("mini3", 8, 2, 128, "bf16", 1536, 256, 4, 256, 0, 300, "uniform", 16, 64)
     K, V, Q, _ = planted_stream(w, 31, device=str(gpu_device), context=1536)
     cfg = config_from_workload(w, max_tokens=1536, theta=theta_default(w.head_dim), n_layers=1, n_seqs=1)
@@ -176,16 +177,23 @@ def test_whole_step_copies_the_chunk_rows(gpu_device):
             arena.fill_(float("nan"))
     ka, va = b.arena_views()
     ka[0, 0].copy_(K); va[0, 0].copy_(V)
+    mine = torch.cuda.Stream(gpu_device)
+    torch.cuda.synchronize()
+    a.set_stream(mine)
     for c0 in range(0, 1536, 256):
         q = Q[c0:c0 + 256].contiguous()
         kc = K[:, c0:c0 + 256].unsqueeze(0).contiguous()              # [1][Hkv][n][d]
         vc = V[:, c0:c0 + 256].unsqueeze(0).contiguous()
-        out_a = a.step(0, 0, 1, kc, vc, q)
+        mine.wait_stream(torch.cuda.current_stream(gpu_device))
+        with torch.cuda.stream(mine):
+            out_a = a.step(0, 0, 1, kc, vc, q)
+            seen = out_a.float().clone()                              # the consumer: queued behind the call
         b.append_chunk(0, 0, 1, 256)
         b.retrieve(0, 0, 1, q)
         out_b = b.attend(0, 0, 1, q)
-        assert torch.isfinite(out_a.float()).all()
-        assert float((out_a.float() - out_b.float()).abs().max()) <= 2e-2
+        mine.synchronize()
+        assert torch.isfinite(seen).all()
+        assert float((seen - out_b.float()).abs().max()) <= 2e-2
         for h in range(w.n_kv_heads):
             assert list(a.get_token_list(0, 0, h)) == list(b.get_token_list(0, 0, h))
     ka2, va2 = a.arena_views()
