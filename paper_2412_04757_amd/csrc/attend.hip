@@ -7,7 +7,10 @@
 // group (GQA) times two 32-row sub-tiles, each wavefront with its 32 query rows in registers.
 // Scores are computed transposed (S^T = K Q^T) so that one lane owns one query: the softmax
 // statistics need a single cross-lane exchange and the probabilities are already laid out as
-// the B operand of O^T = V^T P^T.
+// the B operand of O^T = V^T P^T. The same kernel also attends over a part of the context
+// only (the two parts of a step that overlaps steps 1 and 2), and splits the key range of
+// a block of 2 to 4 query rows. One-token chunks (decode) have a kernel without LDS staging
+// further down; fp32 contexts a plain one-wavefront-per-row kernel.
 #include "device_common.h"
 #include <type_traits>
 
@@ -522,8 +525,9 @@ __global__ __launch_bounds__(128) void attend_merge_kernel(AttArgs a) {
 //   O += P V on the vector ALU: a lane owns 8 d-columns (lane % 16) of the 4 keys of its lane group, fetches
 //   their V pieces (one 16-byte load per key) and the 4 x G probabilities from the lanes that hold them.
 // The running maximum is per head (lane column); the rescale factor of every head reaches all lanes by a
-// lane read. Rows of group g + 1 and token ids of group g + 2 are in flight while group g is used. At the end the four lane groups' partial O and sums are added, the four wavefronts merge
-// through LDS, and the workgroup writes one partial result in the layout attend_merge_kernel reads.
+// lane read. Rows of group g + 1 and token ids of group g + 2 are in flight while group g is used. At the
+// end the four lane groups' partial O and sums are added, the four wavefronts merge through LDS, and the
+// workgroup writes one partial result in the layout attend_merge_kernel reads.
 constexpr int DEC_WAVES = 4;
 template <int G>
 __global__ __launch_bounds__(64 * DEC_WAVES, 3) void attend_decode_kernel(AttArgs a) {
