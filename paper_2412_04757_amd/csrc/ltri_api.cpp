@@ -367,13 +367,10 @@ static int32_t append_spans(ltri_ctx* c, int layer, const BatchPos& bp, int seq_
     if (r != LTRI_OK) return r;
     if (dynamic) {
       r = check_hip(c, launch_dynamic_reps(c->D, c->ds, c->dc, c->k_arena, q_seg, layer, bp, off, cnt, n_new,
-                                           c->D.seg_map == LTRI_MAP_SOFTMAX, c->stream), "index vectors");
+                                           c->D.seg_map == LTRI_MAP_SOFTMAX, last ? fork : nullptr, c->stream),
+                    "index vectors");
       if (r != LTRI_OK) return r;
     }
-  }
-  if (dynamic && fork) {
-    r = check_hip(c, hipEventRecord(fork, c->stream), "fork");
-    if (r != LTRI_OK) return r;
   }
   if (c->D.rep_mode == LTRI_REP_MEAN) {
     r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, seq_count, n_new, c->stream),
@@ -433,7 +430,7 @@ int32_t ltri_append_chunk_with_spans(ltri_ctx* c, int32_t layer, int32_t seq, co
     if (r != LTRI_OK) return r;
     if (c->D.rep_mode == LTRI_REP_DYNAMIC && n_new > 1)
       r = check_hip(c, launch_dynamic_reps(c->D, c->ds, c->dc, c->k_arena, nullptr, layer, bp, 0, 1, n_new, false,
-                                           c->stream), "index vectors");
+                                           nullptr, c->stream), "index vectors");
     else
       r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, 1, n_new, c->stream),
                     "representative keys");

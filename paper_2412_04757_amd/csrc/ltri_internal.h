@@ -131,7 +131,7 @@ hipError_t launch_append_bounds(const Dims& D, const DevState& st, const DevScra
                                 int seq, int c0, int n_new, hipStream_t s);
 hipError_t launch_dynamic_reps(const Dims& D, const DevState& st, const DevScratch& sc, const void* k_arena,
                                const void* q_seg, int layer, const BatchPos& bp, int batch_off, int seq_count,
-                               int n_new, bool lse_ready, hipStream_t s);
+                               int n_new, bool lse_ready, hipEvent_t after_tiles, hipStream_t s);   // event as in launch_segment
 hipError_t launch_rep_keys(const Dims& D, const DevState& st, const void* k_arena, int layer,
                            const BatchPos& bp, int seq_count, int n_new, hipStream_t s);
 hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,

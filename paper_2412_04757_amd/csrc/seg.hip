@@ -977,7 +977,7 @@ hipError_t launch_copy_chunk(const Dims& D, void* k_arena, void* v_arena, const 
 
 hipError_t launch_dynamic_reps(const Dims& D, const DevState& st, const DevScratch& sc, const void* k_arena,
                                const void* q_seg, int layer, const BatchPos& bp, int batch_off, int seq_count,
-                               int n_new, bool lse_ready, hipStream_t s) {
+                               int n_new, bool lse_ready, hipEvent_t after_tiles, hipStream_t s) {
   SegArgs a;
   a.D = D; a.st = st; a.sc = sc; a.k_arena = k_arena; a.q_seg = q_seg; a.layer = layer;
   a.batch_off = batch_off; a.n_new = n_new;
@@ -995,6 +995,10 @@ hipError_t launch_dynamic_reps(const Dims& D, const DevState& st, const DevScrat
   dyn_token_span_kernel<<<gl, 256, 0, s>>>(a);
   if (bf) dyn_tile_kernel<LTRI_BF16><<<gt, 256, 0, s>>>(a);
   else    dyn_tile_kernel<LTRI_F32><<<gt, 256, 0, s>>>(a);
+  if (after_tiles) {                     // the last kernel that fills the chip is queued
+    const hipError_t e = hipEventRecord(after_tiles, s);
+    if (e != hipSuccess) return e;
+  }
   dyn_reduce_kernel<<<gl, 256, 0, s>>>(a);
   dim3 gs(64, P);
   if (bf) dyn_span_kernel<LTRI_BF16><<<gs, 1024, 0, s>>>(a);
