@@ -25,6 +25,9 @@ PEAK_HBM_GBPS = 8000.0
 # HBM bytes per attend launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE counters
 # calibrated against copy kernels (profiles/attend_gather_hbm_traffic_cfg3.txt): (35419.5 * 2.00 + 16384.0) KiB
 ATTEND_TRAFFIC_BYTES_CFG3 = int((35419.5 * 2.00 + 16384.0) * 1024)
+# the same for the decode attention at the cfg5 shape, attend_decode_kernel + attend_merge_kernel
+# (profiles/attend_decode_cfg5_hbm_traffic.txt): ((158382.2 + 687.5) * 2.00 + 1088.0 + 128.0) KiB
+DECODE_TRAFFIC_BYTES_CFG5 = int(((158382.2 + 687.5) * 2.00 + 1088.0 + 128.0) * 1024)
 
 
 def log(*a):
@@ -160,6 +163,7 @@ def run_decode(args, torch, dev):
         "roofline": {"bound": "hbm", "kernel": "attend_decode_kernel + attend_merge_kernel",
                      "achieved": round(kv_bytes / at_us / 1e3, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                      "frac": round(kv_bytes / at_us / 1e3 / PEAK_HBM_GBPS, 4), "kv_bytes_per_step": kv_bytes,
+                     "traffic": DECODE_TRAFFIC_BYTES_CFG5 if not args.context else None,
                      "whole_step_GBps": round(kv_bytes / step_us / 1e3, 1)}}))
 
 
