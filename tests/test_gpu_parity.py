@@ -144,6 +144,10 @@ def test_bf16_ragged_and_all_rows(gpu_device):
     # a short stream with every row and every head checked
     w2 = Workload("mini", 8, 2, 128, "bf16", 768, 256, 4, 128, 0, 200, "uniform", 16, 64)
     _stream_parity(w2, 3, 768, gpu_device)
+    # streams that begin with one-token chunks (an empty context list), by the three calls and by ltri_step
+    tiny = [1, 1, 3, 64, 1, 200, 2, 1]
+    _stream_parity(w2, 4, sum(tiny), gpu_device, chunk_sizes=tiny, window=40, budget_tokens=60)
+    _stream_parity(w2, 4, sum(tiny), gpu_device, chunk_sizes=tiny, window=40, budget_tokens=60, whole_step=True)
 
 
 def test_whole_step_on_two_streams(gpu_device):
