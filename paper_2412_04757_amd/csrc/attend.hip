@@ -74,13 +74,15 @@ constexpr int DMA_STAGE_BYTES = 32768;          // K tile 16 KB + V tile 16 KB
 constexpr int TOK_SLOTS = 8;                    // ring of token-id tiles (> tokens-ahead distance)
 constexpr int att_lds_bytes(int ns, int nw) { return ns * DMA_STAGE_BYTES + TOK_SLOTS * nw * 32; }
 
-// 16 bytes per lane from base + off into LDS at lds_wave_base + 16 * lane
+// 16 bytes per lane from base + off into LDS at lds_wave_base + 16 * lane. The idle cycle between the write of
+// M0 and the load that uses it is the wait state the instruction set asks for; inside an assembly block the
+// compiler does not add it.
 __device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds_wave_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_wave_base), "v"(off), "s"(base) : "m0");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_wave_base), "v"(off), "s"(base) : "m0");
 }
 // 4 bytes per lane
 __device__ __forceinline__ void dma4(const void* base, uint32_t off, uint32_t lds_wave_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_wave_base), "v"(off), "s"(base) : "m0");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_wave_base), "v"(off), "s"(base) : "m0");
 }
 
 enum : int { MASK_NONE = 0, MASK_LIST_END = 1, MASK_CAUSAL = 2 };
@@ -89,6 +91,16 @@ enum : int { MASK_NONE = 0, MASK_LIST_END = 1, MASK_CAUSAL = 2 };
 __device__ __forceinline__ float max3(float a, float b, float c) {
   float r;
   asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+// The same, followed by two idle cycles. The compiler cannot see that the assembly writes a vector
+// register on the vector ALU, so it does not insert the wait states that a lane-permute reading that
+// register right afterwards needs; without them the permute can read the register's old value whenever
+// no other wavefront's instruction happens to fall in between.
+__device__ __forceinline__ float max3_settled(float a, float b, float c) {
+  float r;
+  asm volatile("v_max3_f32 %0, %1, %2, %3\n\ts_nop 1" : "=v"(r) : "v"(a), "v"(b), "v"(c));
   return r;
 }
 
@@ -328,6 +340,13 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
           if (kr >= nvalid) s[kb][v] = -INFINITY;
         }
     }
+    // The maxima below are taken by instructions written in assembly, which the compiler does not
+    // recognise as vector-ALU readers of the matrix cores' results: it would not insert the wait states
+    // such a read needs after the last product, and the maximum could then be taken over registers the
+    // product has not written yet (the probabilities further down are compiler-generated and wait
+    // properly, so only the rounding would change, from launch to launch). These idle cycles, tied to
+    // both accumulators, stand in for them.
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+v"(s[0]), "+v"(s[1]));
     float m4[4];                                     // four independent max chains, then a tree
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -336,7 +355,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
       m4[c] = max3(m4[c], s[kb][v0 + 3], s[kb][v0 + 4]);
       m4[c] = max3(m4[c], s[kb][v0 + 5], s[kb][v0 + 6]);
     }
-    float mx = max3(max3(m4[0], s[0][7], s[0][15]), max3(m4[1], s[1][7], s[1][15]), max3(m4[2], m4[3], m4[2]));
+    float mx = max3_settled(max3(m4[0], s[0][7], s[0][15]), max3(m4[1], s[1][7], s[1][15]), max3(m4[2], m4[3], m4[2]));
     mx = pair_max(mx);
     const float m_new = max3(m_run, mx * sc, mx * sc);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);

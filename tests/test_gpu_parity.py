@@ -661,6 +661,48 @@ def test_collaborative_voting_across_layers(gpu_device):
     assert ctx.sync_status() == 0
 
 
+@pytest.mark.parametrize("mode", ["calls", "step", "dynamic-step", "percentile-units"])
+def test_runs_are_bitwise_reproducible(gpu_device, mode):
+    """The same stream twice on two fresh contexts: outputs, log-sum-exps, span tables, stored vectors, scores,
+    selections and token lists identical bit for bit. No kernel's result depends on the order in which
+    workgroups or streams happen to run (the only atomics are integer counts and bit masks)."""
+    w = Workload("mini4", 8, 2, 128, "bf16", 2048, 512, 4, 256, 0, 400, "uniform", 16, 96)
+    extra = {"calls": {}, "step": {}, "dynamic-step": dict(rep_mode=1, lam=3.0),
+             "percentile-units": dict(theta_quantile=0.9, unit_tokens=64, k_max=4, max_spans=2048)}[mode]
+    K, V, Q, _ = planted_stream(w, 50, device=str(gpu_device), context=2048)
+    cfg = config_from_workload(w, max_tokens=2048, theta=theta_default(w.head_dim), n_layers=1, n_seqs=1, **extra)
+    runs = []
+    for _ in range(2):
+        ctx = LtriContext(cfg, gpu_device)
+        ka, va = ctx.arena_views()
+        ka[0, 0].copy_(K); va[0, 0].copy_(V)
+        outs, lses, tables = [], [], []
+        for c0 in range(0, 2048, 512):
+            q = Q[c0:c0 + 512].contiguous()
+            lse = torch.empty((1, 512, w.n_q_heads), dtype=torch.float32, device=gpu_device)
+            if mode == "calls" or mode == "percentile-units":
+                ctx.append_chunk(0, 0, 1, 512, q_seg=q)
+                ctx.retrieve(0, 0, 1, q)
+                out = ctx.attend(0, 0, 1, q, lse=lse)
+            else:
+                out = ctx.step(0, 0, 1, None, None, q, q_seg=q, lse=lse)
+            outs.append(out.clone()); lses.append(lse)
+            for h in range(w.n_kv_heads):
+                ids, scores = ctx.get_selection(0, 0, h)
+                tables.append((list(ids), scores.tobytes(), list(ctx.get_token_list(0, 0, h))))
+        for h in range(w.n_kv_heads):
+            s_, l_ = ctx.get_spans(0, 0, h)
+            tables.append((list(s_), list(l_), ctx.get_rep_keys(0, 0, h).view(torch.int16).numpy().tobytes()))
+        assert ctx.sync_status() == 0
+        runs.append((outs, lses, tables))
+        ctx.close()
+    for a, b in zip(runs[0][0], runs[1][0]):
+        assert torch.equal(a, b)
+    for a, b in zip(runs[0][1], runs[1][1]):
+        assert torch.equal(a, b)
+    assert runs[0][2] == runs[1][2]
+
+
 def test_span_table_overflow_is_reported(gpu_device):
     w = CONFIGS["cfg1"]
     K, V, Q, _ = planted_stream(w, 1, device=str(gpu_device), context=1024)
