@@ -116,6 +116,7 @@ def test_cfg3_full_size_retrieve_and_attend(gpu_device):
                 assert list(ids) == list(sel[h]), f"chunk {c}, head {h}"
                 assert list(ctx.get_token_list(0, 0, h)) == list(st.context_tokens(h))
             out = ctx.attend(0, 0, 1, q)
+            assert torch.equal(out, ctx.attend(0, 0, 1, q)), f"chunk {c}: two launches on the same state differ"
             want, _ = st.attend(qn, rows=rows)
             got = out[0].double().cpu().numpy()[rows]
             worst = max(worst, float(np.abs(got - want).max()))
