@@ -703,6 +703,47 @@ def test_runs_are_bitwise_reproducible(gpu_device, mode):
     assert runs[0][2] == runs[1][2]
 
 
+def test_results_do_not_depend_on_ring_depth_or_schedule(gpu_device):
+    """Tuning knobs change timing, never a bit of the output: the attention kernel with a 3- and a 4-stage LDS
+    ring, and ltri_step with every row block on the second stream or only some of them."""
+    w = CONFIGS["cfg2"]
+    T = 6144
+    K, V, Q, _ = planted_stream(w, 9, device=str(gpu_device), context=T)
+    cfg = config_from_workload(w, max_tokens=T, theta=theta_default(w.head_dim), n_layers=1, n_seqs=1, window=2048,
+                               budget_tokens=2048)
+
+    def run(kind):
+        ctx = LtriContext(cfg, gpu_device)
+        ka, va = ctx.arena_views()
+        ka[0, 0].copy_(K); va[0, 0].copy_(V)
+        if kind in ("calls, 3 stages", "step, 3 stages"):
+            ctx.set_attend_stages(3)
+        if kind in ("calls, 4 stages", "step, 4 stages"):
+            ctx.set_attend_stages(4)
+        if kind == "step, 216 units reserved":
+            ctx.set_step_reserve(216)
+        outs = []
+        for c0 in range(0, T, w.chunk):
+            q = Q[c0:c0 + w.chunk].contiguous()
+            if kind.startswith("calls"):
+                ctx.append_chunk(0, 0, 1, w.chunk)
+                ctx.retrieve(0, 0, 1, q)
+                outs.append(ctx.attend(0, 0, 1, q).clone())
+            else:
+                outs.append(ctx.step(0, 0, 1, None, None, q).clone())
+        assert ctx.sync_status() == 0
+        ctx.close()
+        return outs
+
+    def same(a, b):
+        return all(torch.equal(x, y) for x, y in zip(a, b))
+
+    assert same(run("calls, 3 stages"), run("calls, 4 stages"))
+    base = run("step, 3 stages")
+    assert same(base, run("step, 4 stages"))
+    assert same(base, run("step, 216 units reserved"))
+
+
 def test_span_table_overflow_is_reported(gpu_device):
     w = CONFIGS["cfg1"]
     K, V, Q, _ = planted_stream(w, 1, device=str(gpu_device), context=1024)
