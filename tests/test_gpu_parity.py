@@ -243,6 +243,20 @@ def test_whole_step_equals_three_calls_batched(gpu_device, variant):
     assert ctxs[0].sync_status() == 0 and ctxs[1].sync_status() == 0
 
 
+@pytest.mark.parametrize("heads", [(2, 2), (4, 2), (16, 2), (12, 1)])
+def test_bf16_group_sizes(gpu_device, heads):
+    """Query groups of 1, 2, 8 and 12 heads per KV head on the matrix-core kernels (the workgroup shape and the
+    number of workgroups per KV head differ with the group size; other group sizes are refused at creation).
+    Prefill chunks, ragged ones, one-token chunks (the decode kernel takes groups up to 4, larger ones split
+    the key range of the general kernel), by the three calls and by ltri_step."""
+    n_q, n_kv = heads
+    w = Workload(f"g{n_q // n_kv}", n_q, n_kv, 128, "bf16", 1280, 256, 4, 200, 0, 300, "uniform", 16, 64)
+    sizes = [256, 256, 1, 100, 256, 1, 1, 256, 153]
+    assert sum(sizes) == 1280
+    _stream_parity(w, 61, 1280, gpu_device, chunk_sizes=sizes, rows=range(0, 256, 13))
+    _stream_parity(w, 61, 1280, gpu_device, chunk_sizes=sizes, rows=range(0, 256, 13), whole_step=True, use_q_seg=True)
+
+
 def test_given_spans_forced_selection_and_gather(gpu_device):
     """Test seams: caller-supplied boundaries, forced selection (every stored span -> equals
     full causal attention), and the standalone gather."""
