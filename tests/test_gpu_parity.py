@@ -257,6 +257,19 @@ def test_bf16_group_sizes(gpu_device, heads):
     _stream_parity(w, 61, 1280, gpu_device, chunk_sizes=sizes, rows=range(0, 256, 13), whole_step=True, use_q_seg=True)
 
 
+def test_fp32_head_dim_128(gpu_device):
+    """fp32 with 128-wide heads (config 1 has 64): rows of two 256-byte pieces in the map tiles, two output
+    columns per lane in the fp32 attention, the one-token retrieve at this width; query-driven and key-driven
+    maps, ragged and one-token chunks, both schedules (ltri_step runs the three calls for fp32)."""
+    w = Workload("f32-d128", 4, 2, 128, "f32", 1100, 256, 4, 150, 6, 0, "uniform", 16, 64)
+    sizes = [256, 200, 1, 256, 1, 1, 129, 256]
+    assert sum(sizes) == 1100
+    _stream_parity(w, 71, 1100, gpu_device, chunk_sizes=sizes)
+    # the softmax map with this theta cuts far finer than the planted spans: room for every token as a span
+    _stream_parity(w, 72, 1100, gpu_device, chunk_sizes=sizes, use_q_seg=True, seg_map=O.MAP_SOFTMAX, theta=0.0113,
+                   phi=0.2, whole_step=True, rows=range(0, 256, 7), max_spans=1100)
+
+
 def test_given_spans_forced_selection_and_gather(gpu_device):
     """Test seams: caller-supplied boundaries, forced selection (every stored span -> equals
     full causal attention), and the standalone gather."""
