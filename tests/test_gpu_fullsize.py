@@ -286,9 +286,12 @@ def test_layers_resident_cfg4_shape(gpu_device):
             Q, st = data[layer]
             q = Q[c0:c0 + L].contiguous()
             qn = q.double().cpu().numpy()
-            ctx.append_chunk(layer, 0, 1, L)
-            ctx.retrieve(layer, 0, 1, q)
-            out = ctx.attend(layer, 0, 1, q)
+            if layer == 1:          # the middle layer through ltri_step, its neighbours by the three calls
+                out = ctx.step(layer, 0, 1, None, None, q)
+            else:
+                ctx.append_chunk(layer, 0, 1, L)
+                ctx.retrieve(layer, 0, 1, q)
+                out = ctx.attend(layer, 0, 1, q)
             st.append_chunk(L)
             sel = st.retrieve(qn)
             for h in range(w.n_kv_heads):
