@@ -245,6 +245,16 @@ int32_t ltri_attend(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq
 int32_t ltri_step(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* k_chunk,
                   const void* v_chunk, const void* q_seg, const void* q, int32_t n_new, void* out, float* lse);
 
+/* Measurement aid for ltri_step (Sec. 3.4 third step, the attention, is where the time goes): with timing on,
+ * every ltri_step that takes the two-stream schedule records HIP events around its two attention launches, each
+ * on the stream the launch runs on (the first part on the context's second stream, beside the kernels of steps 1
+ * and 2; the retrieved part on the context's stream). ltri_read_step_timing synchronises the context's stream,
+ * writes the two durations (milliseconds) of up to `cap` steps since the last read, oldest first, to the host
+ * arrays, sets *n to the count and forgets the records. Steps that run the plain calls (one-token chunks, fp32)
+ * leave no record. Turning timing on or off also forgets pending records. */
+int32_t ltri_set_step_timing(ltri_ctx* ctx, int32_t on);
+int32_t ltri_read_step_timing(ltri_ctx* ctx, float* local_ms_host, float* retrieved_ms_host, int32_t cap, int32_t* n);
+
 /* Compute units ltri_step keeps free of the attention's long workgroups while the small kernels of steps 1
  * and 2 run: only as many blocks of query rows start early as leave that many units idle (one attention
  * workgroup fills a unit); the other row blocks follow step 2. Default 0 (every row block starts early; the
@@ -252,8 +262,9 @@ int32_t ltri_step(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_c
  * results do not depend on it beyond rounding. EINVAL outside [0, units of the device]. */
 int32_t ltri_set_step_reserve(ltri_ctx* ctx, int32_t compute_units);
 
-/* The gather on its own: copies the K and V rows of the attended context set
- * (initial | retrieved | window, in that order) of every KV head of one sequence into
+/* The gather on its own (Sec. 3.4 third step: the keys and values of the initial tokens, the retrieved
+ * tokens and the local window are concatenated before the attention): copies the K and V rows of the
+ * attended context set (initial | retrieved | window, in that order) of every KV head of one sequence into
  * k_packed / v_packed, device [n_kv_heads][list_cap][head_dim] (list_cap from
  * ltri_list_capacity()); n_tokens: device int32 [n_kv_heads] or NULL. */
 int32_t ltri_gather_pack(ltri_ctx* ctx, int32_t layer, int32_t seq, void* k_packed, void* v_packed,
@@ -276,20 +287,6 @@ int32_t ltri_get_selection(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv
 /* Context token list of the last retrieve: tokens_host[cap], *n = length. */
 int32_t ltri_get_token_list(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,
                             int32_t* tokens_host, int32_t cap, int32_t* n);
-
-/* Measured ceilings of this GPU, to be read next to the published peaks (the attend step is a
- * dense bf16 contraction, Sec. 3.4 third step; the gather is a pure copy). Both launch a small
- * kernel on hip_stream, time it with events and synchronise; no context is needed.
- * ltri_measure_mfma_peak: rate of back-to-back v_mfma_f32_32x32x16_bf16 on every SIMD, in
- *   TFLOP/s. sink: device buffer of at least 512 KiB that the kernel may overwrite.
- *   random_operands: 0 = all operands 1.0, 1 = pseudo-random operands; the clock the chip
- *   sustains depends on the operand data, real inputs behave like the random case.
- * ltri_measure_copy_peak: read + write rate of a plain 16-byte-per-lane copy of `bytes` bytes
- *   (a multiple of 16, at least 1 MiB) from src to dst (device, disjoint), in GB/s.
- * Errors: LTRI_EINVAL (NULL pointers, sizes), LTRI_EHIP. */
-int32_t ltri_measure_mfma_peak(void* sink, size_t sink_bytes, int32_t random_operands, void* hip_stream,
-                               double* tflops);
-int32_t ltri_measure_copy_peak(void* dst, const void* src, size_t bytes, void* hip_stream, double* gbps);
 
 const char* ltri_strerror(int32_t status);
 const char* ltri_last_error(const ltri_ctx* ctx);

@@ -239,6 +239,30 @@ def segmentation_is_stable(K: np.ndarray, Q: Optional[np.ndarray], kind: int, th
     return True
 
 
+def segmentation_reachable(K: np.ndarray, Q: Optional[np.ndarray], kind: int, theta: float,
+                           phi: float, target: Sequence[int], max_keep: int = 0, rel: float = 2.0 ** -16,
+                           draws: int = 32, seed: int = 1, theta_quantile: float = 0.0,
+                           unit: int = 0, c0: int = 0) -> bool:
+    """Validity check for a chunk that fails the audit above: is `target` (boundaries found by an
+    implementation whose map cells carry a relative error below `rel`) what this procedure yields
+    for SOME map within that error?  True if the unperturbed map or one of `draws` random relative
+    perturbations bounded by `rel` gives exactly `target`.  A tiling that no admissible map
+    produces is a bug, not a near-tie."""
+    target = [int(t) for t in target]
+    base = segment_chunk(K, Q, kind, theta, phi, max_keep, theta_quantile=theta_quantile, unit=unit, c0=c0)
+    if [int(t) for t in base] == target:
+        return True
+    rng = np.random.default_rng(seed)
+    L = K.shape[0]
+    for _ in range(draws):
+        p = rng.uniform(-rel, rel, size=(L, L))
+        b = segment_chunk(K, Q, kind, theta, phi, max_keep, z_perturb=p, theta_quantile=theta_quantile,
+                          unit=unit, c0=c0)
+        if [int(t) for t in b] == target:
+            return True
+    return False
+
+
 # ----------------------------------------------------------------------------
 # representative vectors (mean pooling, Sec. 3.3.1) and similarity (Eq. 8)
 # ----------------------------------------------------------------------------

@@ -23,14 +23,17 @@ RATIO_ROW, RATIO_COL, RATIO_ROWCOL = 0, 1, 2
 
 EXPORTED_SYMBOLS = [
     "ltri_workspace_bytes", "ltri_create", "ltri_create_dry", "ltri_destroy", "ltri_reset",
-    "ltri_set_stream", "ltri_set_attend_stages", "ltri_set_step_reserve",
+    "ltri_set_stream", "ltri_set_attend_stages", "ltri_set_step_reserve", "ltri_set_step_timing",
+    "ltri_read_step_timing",
     "ltri_append_chunk", "ltri_append_chunk_with_spans", "ltri_retrieve", "ltri_retrieve_persistent",
     "ltri_retrieve_collaborative",
     "ltri_sel_capacity",
     "ltri_force_selection", "ltri_attend", "ltri_step", "ltri_gather_pack", "ltri_list_capacity",
     "ltri_sync_status", "ltri_token_count", "ltri_span_count", "ltri_get_spans",
     "ltri_get_rep_keys", "ltri_get_selection", "ltri_get_token_list", "ltri_get_index_tokens", "ltri_strerror",
-    "ltri_last_error", "ltri_version", "ltri_measure_mfma_peak", "ltri_measure_copy_peak",
+    "ltri_last_error", "ltri_version",
+    # include/ltri_bench.h: measurement helpers, not part of the product boundary
+    "ltri_measure_mfma_peak", "ltri_measure_copy_peak", "ltri_measure_read_peak",
 ]
 
 
@@ -85,6 +88,8 @@ def load_library() -> C.CDLL:
         "ltri_force_selection": [vp, i32, i32, i32, pi32, i32],
         "ltri_attend": [vp, i32, i32, i32, vp, i32, vp, vp],
         "ltri_set_step_reserve": [vp, i32],
+        "ltri_set_step_timing": [vp, i32],
+        "ltri_read_step_timing": [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), i32, pi32],
         "ltri_step": [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp],
         "ltri_gather_pack": [vp, i32, i32, vp, vp, vp],
         "ltri_list_capacity": [vp],
@@ -98,6 +103,7 @@ def load_library() -> C.CDLL:
         "ltri_get_index_tokens": [vp, i32, i32, i32, C.POINTER(C.c_uint32), i32],
         "ltri_measure_mfma_peak": [vp, C.c_size_t, i32, vp, C.POINTER(C.c_double)],
         "ltri_measure_copy_peak": [vp, vp, C.c_size_t, vp, C.POINTER(C.c_double)],
+        "ltri_measure_read_peak": [vp, C.c_size_t, vp, C.c_size_t, vp, C.POINTER(C.c_double)],
     }
     for name, args in sig.items():
         fn = getattr(lib, name)
@@ -138,8 +144,17 @@ def config_from_workload(w, max_tokens: Optional[int] = None, theta: float = 0.0
         ratio_mode=ratio_mode, theta_quantile=theta_quantile, unit_tokens=unit_tokens)
 
 
-def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
-    return None if t is None else t.data_ptr()
+def _ptr(t: Optional[torch.Tensor], dtype: Optional[torch.dtype] = None) -> Optional[int]:
+    """Device address of a dense tensor (the C ABI takes plain pointers to row-major buffers)."""
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor):      # a stand-in with an address (dry contexts in the host tests)
+        return t.data_ptr()
+    if not t.is_contiguous():
+        raise ValueError(f"libltri takes dense row-major buffers; got strides {tuple(t.stride())} for shape {tuple(t.shape)}")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected a {dtype} tensor, got {t.dtype}")
+    return t.data_ptr()
 
 
 class LtriContext:
@@ -203,6 +218,18 @@ class LtriContext:
     def set_step_reserve(self, compute_units: int) -> None:
         self._check(self.lib.ltri_set_step_reserve(self.handle, compute_units), None)
 
+    def set_step_timing(self, on: bool) -> None:
+        self._check(self.lib.ltri_set_step_timing(self.handle, int(on)), None)
+
+    def read_step_timing(self, cap: int = 4096) -> Tuple[np.ndarray, np.ndarray]:
+        """Durations (ms) of the two attention launches of every ltri_step since the last read."""
+        a = np.zeros(cap, np.float32)
+        b = np.zeros(cap, np.float32)
+        n = C.c_int32()
+        self._check(self.lib.ltri_read_step_timing(self.handle, a.ctypes.data_as(C.POINTER(C.c_float)),
+                                                   b.ctypes.data_as(C.POINTER(C.c_float)), cap, C.byref(n)), None)
+        return a[:n.value], b[:n.value]
+
     def set_attend_stages(self, stages: int) -> None:
         self._check(self.lib.ltri_set_attend_stages(self.handle, stages), None)
 
@@ -212,8 +239,9 @@ class LtriContext:
     def append_chunk(self, layer: int, seq_begin: int, seq_count: int, n_new: int,
                      k_chunk: Optional[torch.Tensor] = None, v_chunk: Optional[torch.Tensor] = None,
                      q_seg: Optional[torch.Tensor] = None) -> None:
-        self._check(self.lib.ltri_append_chunk(self.handle, layer, seq_begin, seq_count, _ptr(k_chunk),
-                                               _ptr(v_chunk), _ptr(q_seg), n_new), None)
+        t = self.tdtype
+        self._check(self.lib.ltri_append_chunk(self.handle, layer, seq_begin, seq_count, _ptr(k_chunk, t),
+                                               _ptr(v_chunk, t), _ptr(q_seg, t), n_new), None)
 
     def append_chunk_with_spans(self, layer: int, seq: int, n_new: int, bounds: List[np.ndarray],
                                 k_chunk: Optional[torch.Tensor] = None,
@@ -221,22 +249,22 @@ class LtriContext:
         flat = np.concatenate([np.asarray(b, np.int32) for b in bounds]).astype(np.int32)
         nb = np.asarray([len(b) for b in bounds], np.int32)
         self._check(self.lib.ltri_append_chunk_with_spans(
-            self.handle, layer, seq, _ptr(k_chunk), _ptr(v_chunk), n_new,
+            self.handle, layer, seq, _ptr(k_chunk, self.tdtype), _ptr(v_chunk, self.tdtype), n_new,
             flat.ctypes.data_as(C.POINTER(C.c_int32)), nb.ctypes.data_as(C.POINTER(C.c_int32))), None)
 
     def retrieve(self, layer: int, seq_begin: int, seq_count: int, q: torch.Tensor,
                  sel_ids: Optional[torch.Tensor] = None, sel_cnt: Optional[torch.Tensor] = None) -> None:
         n_q = q.shape[-3]
-        self._check(self.lib.ltri_retrieve(self.handle, layer, seq_begin, seq_count, q.data_ptr(), n_q,
-                                           _ptr(sel_ids), _ptr(sel_cnt)), None)
+        self._check(self.lib.ltri_retrieve(self.handle, layer, seq_begin, seq_count, _ptr(q, self.tdtype), n_q,
+                                           _ptr(sel_ids, torch.int32), _ptr(sel_cnt, torch.int32)), None)
 
     def retrieve_collaborative(self, layer: int, seq_begin: int, seq_count: int, q: torch.Tensor, layer_weights,
                                sel_ids: Optional[torch.Tensor] = None, sel_cnt: Optional[torch.Tensor] = None) -> None:
         w = np.asarray(list(layer_weights), np.float32)
         n_q = q.shape[-3]
-        self._check(self.lib.ltri_retrieve_collaborative(self.handle, layer, seq_begin, seq_count, q.data_ptr(), n_q,
-                                                         w.ctypes.data_as(C.POINTER(C.c_float)), _ptr(sel_ids),
-                                                         _ptr(sel_cnt)), None)
+        self._check(self.lib.ltri_retrieve_collaborative(self.handle, layer, seq_begin, seq_count, _ptr(q, self.tdtype), n_q,
+                                                         w.ctypes.data_as(C.POINTER(C.c_float)), _ptr(sel_ids, torch.int32),
+                                                         _ptr(sel_cnt, torch.int32)), None)
 
     def retrieve_persistent(self, layer: int, seq_begin: int, seq_count: int) -> None:
         self._check(self.lib.ltri_retrieve_persistent(self.handle, layer, seq_begin, seq_count), None)
@@ -252,8 +280,8 @@ class LtriContext:
         if out is None and not self.dry:
             out = torch.empty((seq_count, n_q, self.cfg.n_q_heads, self.cfg.head_dim), dtype=self.tdtype,
                               device=q.device)
-        self._check(self.lib.ltri_attend(self.handle, layer, seq_begin, seq_count, q.data_ptr(), n_q,
-                                         _ptr(out) if out is not None else 1, _ptr(lse)), None)
+        self._check(self.lib.ltri_attend(self.handle, layer, seq_begin, seq_count, _ptr(q, self.tdtype), n_q,
+                                         _ptr(out, self.tdtype) if out is not None else 1, _ptr(lse, torch.float32)), None)
         return out
 
     def step(self, layer: int, seq_begin: int, seq_count: int, k_chunk: Optional[torch.Tensor],
@@ -263,14 +291,16 @@ class LtriContext:
         if out is None and not self.dry:
             out = torch.empty((seq_count, n_new, self.cfg.n_q_heads, self.cfg.head_dim), dtype=self.tdtype,
                               device=q.device)
-        self._check(self.lib.ltri_step(self.handle, layer, seq_begin, seq_count, _ptr(k_chunk), _ptr(v_chunk),
-                                       _ptr(q_seg), q.data_ptr(), n_new, _ptr(out) if out is not None else 1, _ptr(lse)), None)
+        t = self.tdtype
+        self._check(self.lib.ltri_step(self.handle, layer, seq_begin, seq_count, _ptr(k_chunk, t), _ptr(v_chunk, t),
+                                       _ptr(q_seg, t), _ptr(q, t), n_new, _ptr(out, t) if out is not None else 1,
+                                       _ptr(lse, torch.float32)), None)
         return out
 
     def gather_pack(self, layer: int, seq: int, k_packed: torch.Tensor, v_packed: torch.Tensor,
                     n_tokens: Optional[torch.Tensor] = None) -> None:
-        self._check(self.lib.ltri_gather_pack(self.handle, layer, seq, k_packed.data_ptr(),
-                                              v_packed.data_ptr(), _ptr(n_tokens)), None)
+        self._check(self.lib.ltri_gather_pack(self.handle, layer, seq, _ptr(k_packed, self.tdtype),
+                                              _ptr(v_packed, self.tdtype), _ptr(n_tokens, torch.int32)), None)
 
     def sync_status(self) -> int:
         return int(self.lib.ltri_sync_status(self.handle))
@@ -349,6 +379,20 @@ def measure_copy_peak(device, n_bytes: int = 1 << 30) -> float:
     out = C.c_double()
     st = lib.ltri_measure_copy_peak(dst.data_ptr(), src.data_ptr(), n_bytes, torch.cuda.current_stream(device).cuda_stream,
                                     C.byref(out))
+    if st != 0:
+        raise LtriError(st, lib.ltri_strerror(st).decode())
+    return out.value
+
+
+def measure_read_peak(device, n_bytes: int = 1 << 30) -> float:
+    """GB/s of a streaming read of n_bytes on `device` (ltri_measure_read_peak)."""
+    lib = load_library()
+    src = torch.empty(n_bytes, dtype=torch.uint8, device=device)
+    src.zero_()
+    sink = torch.empty(1 << 17, dtype=torch.int32, device=device)
+    out = C.c_double()
+    st = lib.ltri_measure_read_peak(src.data_ptr(), n_bytes, sink.data_ptr(), sink.numel() * 4,
+                                    torch.cuda.current_stream(device).cuda_stream, C.byref(out))
     if st != 0:
         raise LtriError(st, lib.ltri_strerror(st).decode())
     return out.value

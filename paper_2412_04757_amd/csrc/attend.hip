@@ -67,9 +67,7 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // body of each segment is straight-line code, with the masks compiled in or out.
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 
-#ifndef ATT_NW
-#define ATT_NW 8
-#endif
+constexpr int ATT_NW = 8;                       // wavefronts per workgroup of the bf16 kernel
 constexpr int DMA_STAGE_BYTES = 32768;          // K tile 16 KB + V tile 16 KB
 constexpr int TOK_SLOTS = 8;                    // ring of token-id tiles (> tokens-ahead distance)
 constexpr int att_lds_bytes(int ns, int nw) { return ns * DMA_STAGE_BYTES + TOK_SLOTS * nw * 32; }
@@ -288,9 +286,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
         kf[2 * kk] = lds_read16<0>(sbase + koff[kk]);
         kf[2 * kk + 1] = lds_read16<8192>(sbase + koff[kk]);
       }
-#ifndef ATT_NOPRIO
       __builtin_amdgcn_s_setprio(2);               // matrix-core phases go first when both waves of a SIMD are ready
-#endif
       const f32x16_t zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       auto group = [&](int g) {
 #pragma unroll
@@ -309,9 +305,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
       request_rows(t + NS - 1, 1, tokreg[1]);
       lds_wait<4>(kf[8], kf[9], kf[10], kf[11]);    group(2); __builtin_amdgcn_sched_barrier(0);
       lds_wait<0>(kf[12], kf[13], kf[14], kf[15]);  group(3);
-#ifndef ATT_NOPRIO
       __builtin_amdgcn_s_setprio(0);
-#endif
     } else {
       request_tokens(t + TOK_AHEAD);
       request_rows(t + NS - 1, 0, tokreg[0]);
@@ -816,6 +810,49 @@ __global__ __launch_bounds__(256) void gather_pack_kernel(GatherArgs a) {
   if (a.n_tokens && blockIdx.x == 0 && threadIdx.x == 0) a.n_tokens[h] = list_len;
 }
 
+// ---- how a launch splits the key range of a short query block, and what its partial results need ----
+// kind: 0 = no partial results, 1 = the one-token kernel, 2 = the matrix-core kernel with splits
+static int attend_split_count(const Dims& D, int seq_count, int n_q, int n_cus, int* kind) {
+  *kind = 0;
+  if (!attend_on_matrix_cores(D) || n_q > ATT_SPLIT_MAX_ROWS) return 1;
+  if (n_q == 1 && D.G <= 4) {
+    // decode: two workgroups per compute unit (measured best at 16 sequences x 8 KV heads: 67 us against
+    // 70 .. 81 us with 3 .. 16 splits; the step runs at the rate of a plain copy either way)
+    const int slots = D.Hkv * seq_count;
+    const int ns = (2 * n_cus) / slots;
+    *kind = 1;
+    return ns > ATT_MAX_SPLITS ? ATT_MAX_SPLITS : (ns < 1 ? 1 : ns);
+  }
+  // a short query block on few workgroups: split the key range so that every compute unit streams a
+  // share of it; the partial results are merged by a second kernel
+  const int HG = D.G < 4 ? D.G : 4;
+  const int blocks = D.Hkv * (D.G / HG) * seq_count;
+  if (blocks >= 256) return 1;
+  const int ns = 256 / blocks;
+  if (ns <= 1) return 1;
+  *kind = 2;
+  return ns > ATT_MAX_SPLITS ? ATT_MAX_SPLITS : ns;
+}
+
+static hipError_t device_cus(int* n_cus) {
+  static int cached = 0;
+  if (cached == 0) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cached, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) { cached = 0; return e; }
+  }
+  *n_cus = cached;
+  return hipSuccess;
+}
+
+size_t attend_partial_bytes(const Dims& D, int seq_count, int n_q, int n_cus) {
+  int kind = 0;
+  const int ns = attend_split_count(D, seq_count, n_q, n_cus, &kind);
+  if (kind == 0) return 0;
+  return (size_t)seq_count * D.Hq * ns * (kind == 1 ? 1 : n_q) * (D.d + 2) * sizeof(float);
+}
+
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
                          void* out, float* lse, int stages, float* part, int part_mode, const int32_t* loclist,
@@ -828,19 +865,11 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
   if (part_mode == ATT_RETRIEVED && !lse_a) return hipErrorInvalidValue;
   const bool mfma_ok = attend_on_matrix_cores(D);
   if (part_mode != ATT_ALL && (!mfma_ok || n_q <= ATT_SPLIT_MAX_ROWS)) return hipErrorInvalidValue;
-  if (mfma_ok && n_q == 1 && part && part_mode == ATT_ALL && D.G <= 4) {
-    // decode: two workgroups per compute unit (measured best at 16 sequences x 8 KV heads: 67 us against
-    // 70 .. 81 us with 3 .. 16 splits; the step runs at the rate of a plain copy either way)
-    static int n_cus = 0;
-    if (n_cus == 0) {
-      int dev = 0;
-      hipError_t e = hipGetDevice(&dev);
-      if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev);
-      if (e != hipSuccess) return e;
-    }
-    const int slots = D.Hkv * seq_count;
-    const int ns = (2 * n_cus) / slots;
-    a.n_splits = ns > ATT_MAX_SPLITS ? ATT_MAX_SPLITS : (ns < 1 ? 1 : ns);
+  int n_cus = 0, kind = 0;
+  if (hipError_t e = device_cus(&n_cus); e != hipSuccess) return e;
+  const int ns_short = (part && part_mode == ATT_ALL) ? attend_split_count(D, seq_count, n_q, n_cus, &kind) : 1;
+  if (kind == 1) {
+    a.n_splits = ns_short;
     dim3 g(a.n_splits, D.Hkv, seq_count);
     if (D.G == 4)      attend_decode_kernel<4><<<g, 64 * DEC_WAVES, 0, s>>>(a);
     else if (D.G == 2) attend_decode_kernel<2><<<g, 64 * DEC_WAVES, 0, s>>>(a);
@@ -859,13 +888,9 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
       if (rb_count == 0) return hipSuccess;
       a.rb_off = rb_first; g.y = rb_count;
     }
-    // a short query block (decode) on few workgroups: split the key range so that every compute
-    // unit streams a share of it; the partial results are merged by a second kernel
-    const int blocks = D.Hkv * gpk * seq_count;
-    if (n_q <= ATT_SPLIT_MAX_ROWS && part && blocks < 256) {
-      int ns = 256 / blocks;
-      a.n_splits = ns > ATT_MAX_SPLITS ? ATT_MAX_SPLITS : ns;
-      if (a.n_splits > 1) g.y = a.n_splits;
+    if (kind == 2) {
+      a.n_splits = ns_short;
+      g.y = a.n_splits;
     }
     static bool attr_set = false;
     if (!attr_set) {

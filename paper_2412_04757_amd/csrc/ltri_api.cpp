@@ -26,6 +26,11 @@ struct ltri_ctx {
   // second stream and the fork / join events of an overlapped step
   hipStream_t side; hipEvent_t ev_fork, ev_join;
   int n_cus, reserve_cus;                // compute units of the device; those an overlapped step keeps free of long workgroups
+  // optional timing of the attention launches of ltri_step: four events per step (first part on the second stream,
+  // retrieved part on the context's stream), reused after every read
+  bool step_timing;
+  std::vector<hipEvent_t> tev;
+  size_t tev_used;
   // host mirror of the stream positions, per (layer, seq)
   std::vector<long long> n_tokens;       // tokens appended
   std::vector<int> last_len;             // length of the chunk appended last (0 = none)
@@ -194,6 +199,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->step_stages = 3;
   c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
   c->n_cus = 0; c->reserve_cus = 0;
+  c->step_timing = false; c->tev_used = 0;
   char* s = c->state;
   c->ds = DevState{(int32_t*)(s + SL.meta), (int32_t*)(s + SL.span_start), (int32_t*)(s + SL.span_len),
                    (void*)(s + SL.krep), (double*)(s + SL.scores), (int32_t*)(s + SL.sel_ids),
@@ -215,9 +221,9 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   if (!dry) {
     hipError_t e = launch_fill_zero(c->state, SL.total, c->stream);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
-    // the two events order streams of this device only: no timing, no system-scope fence when they are recorded
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming | hipEventDisableSystemFence);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming | hipEventDisableSystemFence);
+    // the two events order streams of this device only: no timing, and a device-scope release when they are recorded
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming | hipEventReleaseToDevice);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming | hipEventReleaseToDevice);
     int dev = 0;
     if (e == hipSuccess) e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, dev);
@@ -245,6 +251,7 @@ int32_t ltri_destroy(ltri_ctx* c) {
   }
   if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
   if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+  for (hipEvent_t e : c->tev) (void)hipEventDestroy(e);
   delete c;
   return LTRI_OK;
 }
@@ -595,6 +602,47 @@ int32_t ltri_attend(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_c
   return LTRI_OK;
 }
 
+// Next timing event of the context (created on first use), recorded on `s`; a no-op while timing is off.
+static int32_t timing_mark(ltri_ctx* c, hipStream_t s) {
+  if (!c->step_timing) return LTRI_OK;
+  if (c->tev_used == c->tev.size()) {
+    hipEvent_t e = nullptr;
+    const int32_t r = check_hip(c, hipEventCreate(&e), "timing event");
+    if (r != LTRI_OK) return r;
+    c->tev.push_back(e);
+  }
+  return check_hip(c, hipEventRecord(c->tev[c->tev_used++], s), "timing event");
+}
+
+int32_t ltri_set_step_timing(ltri_ctx* c, int32_t on) {
+  if (!c) return LTRI_EINVAL;
+  if (c->dry) return LTRI_OK;
+  if (c->tev_used) {                      // drop the records of steps that were never read
+    const int32_t r = check_hip(c, hipStreamSynchronize(c->stream), "synchronise");
+    if (r != LTRI_OK) return r;
+    c->tev_used = 0;
+  }
+  c->step_timing = on != 0;
+  return LTRI_OK;
+}
+
+int32_t ltri_read_step_timing(ltri_ctx* c, float* local_ms, float* retrieved_ms, int32_t cap, int32_t* n) {
+  if (!c || !n || cap < 0 || (cap > 0 && (!local_ms || !retrieved_ms))) return LTRI_EINVAL;
+  *n = 0;
+  if (c->dry) return LTRI_OK;
+  int32_t r = check_hip(c, hipStreamSynchronize(c->stream), "synchronise");
+  if (r != LTRI_OK) return r;
+  const size_t steps = c->tev_used / 4;
+  for (size_t i = 0; i < steps && (int32_t)i < cap; ++i) {
+    r = check_hip(c, hipEventElapsedTime(&local_ms[i], c->tev[4 * i], c->tev[4 * i + 1]), "timing");
+    if (r == LTRI_OK) r = check_hip(c, hipEventElapsedTime(&retrieved_ms[i], c->tev[4 * i + 2], c->tev[4 * i + 3]), "timing");
+    if (r != LTRI_OK) return r;
+    ++*n;
+  }
+  c->tev_used = 0;
+  return LTRI_OK;
+}
+
 int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* k_chunk,
                   const void* v_chunk, const void* q_seg, const void* q, int32_t n_new, void* out, float* lse) {
   if (!c) return LTRI_EINVAL;
@@ -665,10 +713,12 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   r = check_hip(c, hipStreamWaitEvent(c->side, c->ev_fork, 0), "fork");
   if (r == LTRI_OK && !rest)
     r = check_hip(c, launch_local_list(c->D, bp, seq_count, c->dc.loclist, c->CL.loc_cap, c->side), "local list");
+  if (r == LTRI_OK) r = timing_mark(c, c->side);
   if (r == LTRI_OK)
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse_a,
                                    c->step_stages, nullptr, 1, c->dc.loclist, c->CL.loc_cap, n_rb - rb_side, rb_side,
                                    nullptr, c->side), "attend (initial, window, chunk)");
+  if (r == LTRI_OK) r = timing_mark(c, c->side);
   if (r == LTRI_OK) r = check_hip(c, hipEventRecord(c->ev_join, c->side), "join");
   if (r != LTRI_OK) return r;
   r = ltri_retrieve(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr);
@@ -682,9 +732,13 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   const int32_t rj = check_hip(c, hipStreamWaitEvent(c->stream, c->ev_join, 0), "join");
   if (r != LTRI_OK) return r;
   if (rj != LTRI_OK) return rj;
-  return check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse,
-                                    c->step_stages, nullptr, 2, nullptr, 0, 0, -1, lse_a, c->stream),
-                   "attend (retrieved)");
+  r = timing_mark(c, c->stream);
+  if (r != LTRI_OK) return r;
+  r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse,
+                                 c->step_stages, nullptr, 2, nullptr, 0, 0, -1, lse_a, c->stream),
+                "attend (retrieved)");
+  if (r != LTRI_OK) return r;
+  return timing_mark(c, c->stream);
 }
 
 int32_t ltri_gather_pack(ltri_ctx* c, int32_t layer, int32_t seq, void* k_packed, void* v_packed,

@@ -150,6 +150,8 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
                          hipStream_t s);   // rb_count < 0: every row block; lse_a: first part's, for the retrieved part
 // workgroups per block of query rows and number of such blocks of the matrix-core kernel's launch
 void attend_launch_shape(const Dims& D, int seq_count, int n_q, int* wgs_per_row_block, int* row_blocks);
+// bytes of partial results a launch over seq_count sequences with n_q query rows needs (0: the key range is not split)
+size_t attend_partial_bytes(const Dims& D, int seq_count, int n_q, int n_cus);
 bool attend_on_matrix_cores(const Dims& D);      // the bf16 kernel takes this shape (else one wavefront per query row)
 hipError_t launch_local_list(const Dims& D, const BatchPos& bp, int seq_count, int32_t* loclist, int loc_cap,
                              hipStream_t s);

@@ -667,6 +667,39 @@ def test_stability_audit_flags_a_planted_near_tie():
     assert not O.segmentation_is_stable(K, None, O.MAP_LOGIT, theta * (1 - 1e-9), 0.0)
 
 
+def test_near_tie_validity_check_accepts_reachable_tilings_only():
+    """A chunk that fails the audit has several tilings that some map within the error bound
+    produces; the validity check must accept each of those and nothing else."""
+    L = 8
+    K = np.zeros((L, 2)); K[:, 0] = 1.0
+    theta = float((K @ K.T / math.sqrt(2))[0, 0]) * (1 - 1e-9)
+    rel = 2.0 ** -16
+    base = list(O.segment_chunk(K, None, O.MAP_LOGIT, theta, 0.0))
+    rng = np.random.default_rng(5)
+    seen = {tuple(base): 1}
+    for _ in range(60):
+        p = rng.uniform(-rel, rel, size=(L, L))
+        t = tuple(int(t) for t in O.segment_chunk(K, None, O.MAP_LOGIT, theta, 0.0, z_perturb=p))
+        seen[t] = seen.get(t, 0) + 1
+    assert len(seen) > 1                                   # it is a near-tie: perturbations move the cuts
+    assert O.segmentation_reachable(K, None, O.MAP_LOGIT, theta, 0.0, base, rel=rel)
+    common = [t for t, n in seen.items() if n >= 4]        # tilings a fair share of the admissible maps give
+    assert len(common) >= 2
+    for t in common:
+        assert O.segmentation_reachable(K, None, O.MAP_LOGIT, theta, 0.0, list(t), rel=rel, draws=400)
+    # a tiling no admissible map gives: cuts in a stable chunk's interior, or an arbitrary one here
+    never = [0, 3, L]
+    if tuple(never) in seen:
+        never = [0, 1, 2, 3, 4, 5, 6, 7, L]
+    assert tuple(never) not in seen
+    assert not O.segmentation_reachable(K, None, O.MAP_LOGIT, theta, 0.0, never, rel=rel, draws=64)
+    # on a stable chunk only the oracle's own tiling is reachable
+    Ks = K * 3.0
+    good = list(O.segment_chunk(Ks, None, O.MAP_LOGIT, 0.1, 0.0))
+    assert O.segmentation_reachable(Ks, None, O.MAP_LOGIT, 0.1, 0.0, good, rel=rel)
+    assert not O.segmentation_reachable(Ks, None, O.MAP_LOGIT, 0.1, 0.0, [0, 4, L], rel=rel)
+
+
 # ---------------------------------------------------------------- stored fixtures (tests/golden)
 def _golden(name):
     import json
