@@ -224,6 +224,19 @@ int32_t ltri_force_selection(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t 
 int32_t ltri_attend(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count,
                     const void* q, int32_t n_q, void* out, float* lse);
 
+/* ltri_attend for callers that cannot allocate device memory and bring no scratch for this call: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments, same
+ * results. Where ltri_attend keeps the partial results of a split key range (query blocks of 1 to 4 rows:
+ * decoding) in the context's scratch buffer, this call keeps them in a buffer of 2 MiB that the library
+ * itself holds on every GPU it runs on, from load until the process ends. The call allocates and frees
+ * nothing. LTRI_ECAPACITY if the partial results of this call need more than 2 MiB (they take
+ * seq_count * n_q_heads * splits * n_q * (head_dim + 2) * 4 bytes; 16 sequences of one token at 32 query
+ * heads take 1.1 MB); other errors as ltri_attend. All contexts on one GPU share the buffer: calls that
+ * overlap on one GPU (different streams or contexts) race; on one stream they are ordered. Nothing in the
+ * buffer has to start at zero, every word a call reads was written by that call. */
+int32_t ltri_attend_static(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count,
+                           const void* q, int32_t n_q, void* out, float* lse);
+
 /* One whole step of the path for one chunk (Sec. 3.4, the three steps): the same results as
  * ltri_append_chunk(k_chunk, v_chunk, q_seg) + ltri_retrieve(q) + ltri_attend(q), arguments as there
  * (k_chunk / v_chunk may both be NULL when the rows are already in the arenas; q_seg and lse may be

@@ -28,7 +28,7 @@ EXPORTED_SYMBOLS = [
     "ltri_append_chunk", "ltri_append_chunk_with_spans", "ltri_retrieve", "ltri_retrieve_persistent",
     "ltri_retrieve_collaborative",
     "ltri_sel_capacity",
-    "ltri_force_selection", "ltri_attend", "ltri_step", "ltri_gather_pack", "ltri_list_capacity",
+    "ltri_force_selection", "ltri_attend", "ltri_attend_static", "ltri_step", "ltri_gather_pack", "ltri_list_capacity",
     "ltri_sync_status", "ltri_token_count", "ltri_span_count", "ltri_get_spans",
     "ltri_get_rep_keys", "ltri_get_selection", "ltri_get_token_list", "ltri_get_index_tokens", "ltri_strerror",
     "ltri_last_error", "ltri_version",
@@ -87,6 +87,7 @@ def load_library() -> C.CDLL:
         "ltri_retrieve_collaborative": [vp, i32, i32, i32, vp, i32, C.POINTER(C.c_float), vp, vp],
         "ltri_force_selection": [vp, i32, i32, i32, pi32, i32],
         "ltri_attend": [vp, i32, i32, i32, vp, i32, vp, vp],
+        "ltri_attend_static": [vp, i32, i32, i32, vp, i32, vp, vp],
         "ltri_set_step_reserve": [vp, i32],
         "ltri_set_step_timing": [vp, i32],
         "ltri_read_step_timing": [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), i32, pi32],
@@ -282,6 +283,15 @@ class LtriContext:
                               device=q.device)
         self._check(self.lib.ltri_attend(self.handle, layer, seq_begin, seq_count, _ptr(q, self.tdtype), n_q,
                                          _ptr(out, self.tdtype) if out is not None else 1, _ptr(lse, torch.float32)), None)
+        return out
+
+    def attend_static(self, layer: int, seq_begin: int, seq_count: int, q: torch.Tensor, out: torch.Tensor,
+                      lse: Optional[torch.Tensor] = None) -> torch.Tensor:
+        """ltri_attend_static: the caller passes `out`; nothing is allocated by the call."""
+        n_q = q.shape[-3]
+        self._check(self.lib.ltri_attend_static(self.handle, layer, seq_begin, seq_count, _ptr(q, self.tdtype), n_q,
+                                                _ptr(out, self.tdtype) if out is not None else 1,
+                                                _ptr(lse, torch.float32)), None)
         return out
 
     def step(self, layer: int, seq_begin: int, seq_count: int, k_chunk: Optional[torch.Tensor],

@@ -853,6 +853,30 @@ size_t attend_partial_bytes(const Dims& D, int seq_count, int n_q, int n_cus) {
   return (size_t)seq_count * D.Hq * ns * (kind == 1 ? 1 : n_q) * (D.d + 2) * sizeof(float);
 }
 
+// ---- partial results for callers that bring no buffer ----
+// One array per GPU, held from the moment the library is loaded until the process ends. In host code the
+// array's name is only a handle for hipGetSymbolAddress; the address the kernels get is the one that call
+// returns, looked up once per device with that device current.
+static __device__ __align__(256) unsigned char scratch[ATT_STATIC_SCRATCH_BYTES];
+
+hipError_t attend_static_scratch(float** ptr) {
+  constexpr int MAX_DEVICES = 64;
+  static void* per_device[MAX_DEVICES] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  if (!per_device[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    per_device[dev] = p;
+  }
+  *ptr = static_cast<float*>(per_device[dev]);
+  return hipSuccess;
+}
+
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
                          void* out, float* lse, int stages, float* part, int part_mode, const int32_t* loclist,

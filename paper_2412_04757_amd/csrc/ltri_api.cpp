@@ -26,6 +26,7 @@ struct ltri_ctx {
   // second stream and the fork / join events of an overlapped step
   hipStream_t side; hipEvent_t ev_fork, ev_join;
   int n_cus, reserve_cus;                // compute units of the device; those an overlapped step keeps free of long workgroups
+  float* static_part;                    // the library's own buffer for partial attention results on this context's device
   // optional timing of the attention launches of ltri_step: four events per step (first part on the second stream,
   // retrieved part on the context's stream), reused after every read
   bool step_timing;
@@ -199,6 +200,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->step_stages = 3;
   c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
   c->n_cus = 0; c->reserve_cus = 0;
+  c->static_part = nullptr;
   c->step_timing = false; c->tev_used = 0;
   char* s = c->state;
   c->ds = DevState{(int32_t*)(s + SL.meta), (int32_t*)(s + SL.span_start), (int32_t*)(s + SL.span_len),
@@ -227,6 +229,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
     int dev = 0;
     if (e == hipSuccess) e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess) e = attend_static_scratch(&c->static_part);   // set-up: the device address of the library's own buffer
     c->reserve_cus = 0;
     if (e != hipSuccess) { ltri_destroy(c); return LTRI_EHIP; }
   }
@@ -582,8 +585,8 @@ int32_t ltri_force_selection(ltri_ctx* c, int32_t layer, int32_t seq, int32_t kv
   return LTRI_OK;
 }
 
-int32_t ltri_attend(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q, int32_t n_q,
-                    void* out, float* lse) {
+static int32_t attend_impl(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q, int32_t n_q,
+                           void* out, float* lse, bool own_buffer) {
   BatchPos bp;
   memset(&bp, 0, sizeof bp);
   int32_t r = check_query_chunk(c, layer, seq_begin, seq_count, q, n_q, bp);
@@ -594,12 +597,31 @@ int32_t ltri_attend(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_c
     if ((c->have_sel[ls_index(c, layer, seq_begin + s)] & need) != need)
       return fail(c, LTRI_ESTATE, "sequence %d: no selection for the last chunk (call ltri_retrieve first)",
                   seq_begin + s);
+  float* part = c->dc.att_part;
+  if (own_buffer) {
+    // a dry context sizes the request for a device of 256 compute units
+    const size_t bytes = attend_partial_bytes(c->D, seq_count, n_q, c->dry ? 256 : c->n_cus);
+    if (bytes > ATT_STATIC_SCRATCH_BYTES)
+      return fail(c, LTRI_ECAPACITY, "partial results of %d sequences x %d query rows take %zu bytes, the library's own buffer "
+                  "holds %zu (use ltri_attend with the context's scratch)", seq_count, n_q, bytes, (size_t)ATT_STATIC_SCRATCH_BYTES);
+    part = c->static_part;
+  }
   if (!c->dry) {
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_q, out, lse,
-                                   c->attend_stages, c->dc.att_part, 0, nullptr, 0, 0, -1, nullptr, c->stream), "attend");
+                                   c->attend_stages, part, 0, nullptr, 0, 0, -1, nullptr, c->stream), "attend");
     if (r != LTRI_OK) return r;
   }
   return LTRI_OK;
+}
+
+int32_t ltri_attend(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q, int32_t n_q,
+                    void* out, float* lse) {
+  return attend_impl(c, layer, seq_begin, seq_count, q, n_q, out, lse, false);
+}
+
+int32_t ltri_attend_static(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q, int32_t n_q,
+                           void* out, float* lse) {
+  return attend_impl(c, layer, seq_begin, seq_count, q, n_q, out, lse, true);
 }
 
 // Next timing event of the context (created on first use), recorded on `s`; a no-op while timing is off.

@@ -30,6 +30,7 @@ constexpr int IDX_MASK_WORDS = SEG_MAX_L / 32;   // one bit per token of a chunk
 constexpr int ATT_BN = 64;               // keys per attention tile; token lists are padded to it
 constexpr int ATT_MAX_SPLITS = 16;       // key-range splits of a short query block (decode)
 constexpr int ATT_SPLIT_MAX_ROWS = 4;    // longest query block that is split
+constexpr size_t ATT_STATIC_SCRATCH_BYTES = 2u << 20;   // the library's own buffer for such partial results (ltri_attend_static)
 
 // Byte offsets of the arrays inside the caller's `state` buffer.
 struct StateLayout {
@@ -152,6 +153,8 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
 void attend_launch_shape(const Dims& D, int seq_count, int n_q, int* wgs_per_row_block, int* row_blocks);
 // bytes of partial results a launch over seq_count sequences with n_q query rows needs (0: the key range is not split)
 size_t attend_partial_bytes(const Dims& D, int seq_count, int n_q, int n_cus);
+// device address, on the current device, of the library's own buffer of ATT_STATIC_SCRATCH_BYTES for partial results
+hipError_t attend_static_scratch(float** ptr);
 bool attend_on_matrix_cores(const Dims& D);      // the bf16 kernel takes this shape (else one wavefront per query row)
 hipError_t launch_local_list(const Dims& D, const BatchPos& bp, int seq_count, int32_t* loclist, int loc_cap,
                              hipStream_t s);

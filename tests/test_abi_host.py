@@ -220,3 +220,34 @@ def test_whole_step_call_rules_in_dry_mode():
     assert e.value.status == -1
     ctx.close()
 
+
+def test_attend_static_rules_in_dry_mode():
+    """ltri_attend_static: the call order rules of ltri_attend, and LTRI_ECAPACITY when the partial results of the
+    call would not fit the library's own 2 MiB (checked on the host, before anything is enqueued)."""
+    class Q:
+        def __init__(self, n_seqs, n_q):
+            self.shape = (n_seqs, n_q, 32, 128)
+
+        def data_ptr(self):
+            return 4096
+    w = CONFIGS["cfg5"]
+    ctx = LtriContext(config_from_workload(w, max_tokens=4096, theta=1.0, n_seqs=16), None, dry=True)
+    with pytest.raises(LtriError) as e:
+        ctx.attend_static(0, 0, 16, Q(16, 1), None)
+    assert e.value.status == -2                      # nothing appended yet
+    ctx.append_chunk(0, 0, 16, 1)
+    with pytest.raises(LtriError) as e:
+        ctx.attend_static(0, 0, 16, Q(16, 1), None)
+    assert e.value.status == -2                      # no selection for the chunk
+    ctx.retrieve(0, 0, 16, Q(16, 1))
+    ctx.attend_static(0, 0, 16, Q(16, 1), None)      # the decode batch of config 5 fits (1.1 MB)
+    ctx.append_chunk(0, 0, 2, 4)
+    ctx.retrieve(0, 0, 2, Q(2, 4))
+    with pytest.raises(LtriError) as e:
+        ctx.attend_static(0, 0, 2, Q(2, 4), None)    # 2 x 32 heads x 16 splits x 4 rows x 130 floats = 2.13 MB
+    assert e.value.status == -3 and "2097152" in str(e.value)
+    ctx.attend(0, 0, 2, Q(2, 4))                     # the context's scratch takes it
+    ctx.append_chunk(0, 0, 16, 2048)
+    ctx.retrieve(0, 0, 16, Q(16, 2048))
+    ctx.attend_static(0, 0, 16, Q(16, 2048), None)   # long chunks keep no partial results
+    ctx.close()
