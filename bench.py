@@ -345,8 +345,6 @@ def main():
                          "attention over initial | window | chunk runs beside steps 1 and 2 on a second stream)")
     ap.add_argument("--attend-stages", type=int, default=0, choices=[0, 3, 4],
                     help="LDS ring depth of the attention kernel (default: the library's)")
-    ap.add_argument("--step-reserve", type=int, default=-1,
-                    help="compute units ltri_step keeps free for the small kernels (default: the library's)")
     ap.add_argument("--index-vectors", choices=["mean", "dynamic"], default="mean",
                     help="what a span stores: the mean key (headline) or the sum of its index tokens' keys\n"
                          "(dynamic span index vectors, row ratio, lambda 3); not the headline configuration")
@@ -416,8 +414,6 @@ def main():
         ctx.set_attend_stages(3)          # leaves LDS for the segmentation kernels on every compute unit
 
     step_schedule = args.schedule == "step" and not overlap
-    if args.step_reserve >= 0:
-        ctx.set_step_reserve(args.step_reserve)
     if args.attend_stages:
         ctx.set_attend_stages(args.attend_stages)
 

@@ -268,13 +268,6 @@ int32_t ltri_step(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_c
 int32_t ltri_set_step_timing(ltri_ctx* ctx, int32_t on);
 int32_t ltri_read_step_timing(ltri_ctx* ctx, float* local_ms_host, float* retrieved_ms_host, int32_t cap, int32_t* n);
 
-/* Compute units ltri_step keeps free of the attention's long workgroups while the small kernels of steps 1
- * and 2 run: only as many blocks of query rows start early as leave that many units idle (one attention
- * workgroup fills a unit); the other row blocks follow step 2. Default 0 (every row block starts early; the
- * fastest setting measured); with the whole device reserved the call runs the three plain calls. Tuning knob;
- * results do not depend on it beyond rounding. EINVAL outside [0, units of the device]. */
-int32_t ltri_set_step_reserve(ltri_ctx* ctx, int32_t compute_units);
-
 /* The gather on its own (Sec. 3.4 third step: the keys and values of the initial tokens, the retrieved
  * tokens and the local window are concatenated before the attention): copies the K and V rows of the
  * attended context set (initial | retrieved | window, in that order) of every KV head of one sequence into

@@ -23,7 +23,7 @@ RATIO_ROW, RATIO_COL, RATIO_ROWCOL = 0, 1, 2
 
 EXPORTED_SYMBOLS = [
     "ltri_workspace_bytes", "ltri_create", "ltri_create_dry", "ltri_destroy", "ltri_reset",
-    "ltri_set_stream", "ltri_set_attend_stages", "ltri_set_step_reserve", "ltri_set_step_timing",
+    "ltri_set_stream", "ltri_set_attend_stages", "ltri_set_step_timing",
     "ltri_read_step_timing",
     "ltri_append_chunk", "ltri_append_chunk_with_spans", "ltri_retrieve", "ltri_retrieve_persistent",
     "ltri_retrieve_collaborative",
@@ -88,7 +88,6 @@ def load_library() -> C.CDLL:
         "ltri_force_selection": [vp, i32, i32, i32, pi32, i32],
         "ltri_attend": [vp, i32, i32, i32, vp, i32, vp, vp],
         "ltri_attend_static": [vp, i32, i32, i32, vp, i32, vp, vp],
-        "ltri_set_step_reserve": [vp, i32],
         "ltri_set_step_timing": [vp, i32],
         "ltri_read_step_timing": [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), i32, pi32],
         "ltri_step": [vp, i32, i32, i32, vp, vp, vp, vp, i32, vp, vp],
@@ -215,9 +214,6 @@ class LtriContext:
     def set_stream(self, stream: "torch.cuda.Stream") -> None:
         self._check(self.lib.ltri_set_stream(self.handle, stream.cuda_stream), None)
         self.stream = stream
-
-    def set_step_reserve(self, compute_units: int) -> None:
-        self._check(self.lib.ltri_set_step_reserve(self.handle, compute_units), None)
 
     def set_step_timing(self, on: bool) -> None:
         self._check(self.lib.ltri_set_step_timing(self.handle, int(on)), None)

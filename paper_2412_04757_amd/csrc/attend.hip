@@ -22,7 +22,6 @@ struct AttArgs {
   int n_splits; float* part;             // short query blocks: the key range is split over workgroups
   int part_mode;                         // ATT_ALL, or one of the two parts of an overlapped step
   const int32_t* loclist; int loc_cap;   // ATT_LOCAL: initial | window tokens per sequence [seq_count][loc_cap]
-  int rb_off;                            // first block of query rows of this launch (a launch may take a range of them)
   const float* lse_a;                    // ATT_RETRIEVED: log-sum-exp of the first part, whose output is in `out`
   BatchPos bp;
 };
@@ -154,8 +153,17 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   const int l32 = lane & 31, hf = lane >> 5;
   const int head = h * D.G + gsub * HG + (wave % HG);
   const int split = a.n_splits > 1 ? blockIdx.y : 0;
-  const int rb0 = a.n_splits > 1 ? 0 : (blockIdx.y + a.rb_off) * RPB;   // first row of the block
-  const int r0 = rb0 + (wave / HG) * 32;            // first row of this wave
+  // Query rows of the workgroup. The chunk's rows are cut into sub-tiles of 32; workgroup y takes RS / 2 of them
+  // from the low end and RS / 2 from the high end (sub-tiles y RS / 2 .. and their mirror images), so that under
+  // the causal mask every workgroup has about the same number of (sub-tile, chunk tile) pairs to compute: the
+  // low sub-tiles stop early at their diagonal, the high ones walk on alone. With one sub-tile per workgroup
+  // (RS == 1) rows are taken in order.
+  const int nsub = (RPB == 32) ? (L + 31) / 32 : ((L + RPB - 1) / RPB) * RS;    // sub-tiles, padded to whole workgroups
+  const int yb = a.n_splits > 1 ? 0 : (int)blockIdx.y;
+  const int rs = wave / HG;
+  const int sub = (RS == 1) ? yb : (rs < RS / 2 ? yb * (RS / 2) + rs : nsub - (yb + 1) * (RS / 2) + (rs - RS / 2));
+  const int r0 = sub * 32;                          // first row of this wave
+  const int rb_end = (RS == 1) ? min(L, r0 + 32) : min(L, (nsub - yb * (RS / 2)) * 32);   // past the last row of the workgroup
   const int slot = slot_of(D, a.layer, seq, h);
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.k_arena) + arena_off(D, slot) * 2;
   const unsigned char* Vb = reinterpret_cast<const unsigned char*>(a.v_arena) + arena_off(D, slot) * 2;
@@ -173,7 +181,6 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
     list += n_init;
   }
   const int n_ctx_tiles = (list_len + 63) / 64;
-  const int rb_end = min(L, rb0 + RPB);
   const int n_chunk_tiles = a.part_mode == ATT_RETRIEVED ? 0 : (rb_end + 63) / 64;
   const int n_tiles = n_ctx_tiles + n_chunk_tiles;
   // with splits, this workgroup takes the context tiles [tile0, tile1); the last split also takes the chunk's tiles
@@ -880,12 +887,12 @@ hipError_t attend_static_scratch(float** ptr) {
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
                          void* out, float* lse, int stages, float* part, int part_mode, const int32_t* loclist,
-                         int loc_cap, int rb_first, int rb_count, const float* lse_a, hipStream_t s) {
+                         int loc_cap, const float* lse_a, hipStream_t s) {
   AttArgs a;
   a.D = D; a.st = st; a.k_arena = k_arena; a.v_arena = v_arena; a.q = q; a.out = out; a.lse = lse;
   a.layer = layer; a.seq_count = seq_count; a.n_q = n_q; a.bp = bp;
   a.n_splits = 1; a.part = part;
-  a.part_mode = part_mode; a.loclist = loclist; a.loc_cap = loc_cap; a.rb_off = 0; a.lse_a = lse_a;
+  a.part_mode = part_mode; a.loclist = loclist; a.loc_cap = loc_cap; a.lse_a = lse_a;
   if (part_mode == ATT_RETRIEVED && !lse_a) return hipErrorInvalidValue;
   const bool mfma_ok = attend_on_matrix_cores(D);
   if (part_mode != ATT_ALL && (!mfma_ok || n_q <= ATT_SPLIT_MAX_ROWS)) return hipErrorInvalidValue;
@@ -907,11 +914,6 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
     constexpr int NW = ATT_NW;
     const int RPB = 32 * (NW / HG);
     dim3 g(D.Hkv * gpk, (n_q + RPB - 1) / RPB, seq_count);
-    if (rb_count >= 0) {                 // a range of the row blocks only
-      if (rb_first < 0 || rb_first + rb_count > (int)g.y) return hipErrorInvalidValue;
-      if (rb_count == 0) return hipSuccess;
-      a.rb_off = rb_first; g.y = rb_count;
-    }
     if (kind == 2) {
       a.n_splits = ns_short;
       g.y = a.n_splits;
@@ -939,13 +941,6 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
 
 bool attend_on_matrix_cores(const Dims& D) {
   return D.dtype == LTRI_BF16 && D.d == 128 && (D.G == 1 || D.G == 2 || D.G % 4 == 0);
-}
-
-void attend_launch_shape(const Dims& D, int seq_count, int n_q, int* wgs_per_row_block, int* row_blocks) {
-  const int HG = D.G < 4 ? D.G : 4;
-  const int RPB = 32 * (ATT_NW / HG);
-  *wgs_per_row_block = D.Hkv * (D.G / HG) * seq_count;
-  *row_blocks = (n_q + RPB - 1) / RPB;
 }
 
 hipError_t launch_local_list(const Dims& D, const BatchPos& bp, int seq_count, int32_t* loclist, int loc_cap,

@@ -25,7 +25,7 @@ struct ltri_ctx {
   int step_stages;                       // the same for the two parts of an overlapped step
   // second stream and the fork / join events of an overlapped step
   hipStream_t side; hipEvent_t ev_fork, ev_join;
-  int n_cus, reserve_cus;                // compute units of the device; those an overlapped step keeps free of long workgroups
+  int n_cus;                             // compute units of the device
   float* static_part;                    // the library's own buffer for partial attention results on this context's device
   // optional timing of the attention launches of ltri_step: four events per step (first part on the second stream,
   // retrieved part on the context's stream), reused after every read
@@ -199,7 +199,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->attend_stages = 4;
   c->step_stages = 3;
   c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
-  c->n_cus = 0; c->reserve_cus = 0;
+  c->n_cus = 0;
   c->static_part = nullptr;
   c->step_timing = false; c->tev_used = 0;
   char* s = c->state;
@@ -230,7 +230,6 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
     if (e == hipSuccess) e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e == hipSuccess) e = attend_static_scratch(&c->static_part);   // set-up: the device address of the library's own buffer
-    c->reserve_cus = 0;
     if (e != hipSuccess) { ltri_destroy(c); return LTRI_EHIP; }
   }
   *out = c;
@@ -270,15 +269,6 @@ int32_t ltri_set_attend_stages(ltri_ctx* c, int32_t stages) {
   if (stages != 3 && stages != 4) return fail(c, LTRI_EINVAL, "attend stages must be 3 or 4");
   c->attend_stages = stages;
   c->step_stages = stages;
-  return LTRI_OK;
-}
-
-int32_t ltri_set_step_reserve(ltri_ctx* c, int32_t compute_units) {
-  if (!c) return LTRI_EINVAL;
-  if (c->dry) return LTRI_OK;
-  if (compute_units < 0 || compute_units > c->n_cus)
-    return fail(c, LTRI_EINVAL, "reserve %d outside [0, %d compute units]", compute_units, c->n_cus);
-  c->reserve_cus = compute_units;
   return LTRI_OK;
 }
 
@@ -608,7 +598,7 @@ static int32_t attend_impl(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_
   }
   if (!c->dry) {
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_q, out, lse,
-                                   c->attend_stages, part, 0, nullptr, 0, 0, -1, nullptr, c->stream), "attend");
+                                   c->attend_stages, part, 0, nullptr, 0, nullptr, c->stream), "attend");
     if (r != LTRI_OK) return r;
   }
   return LTRI_OK;
@@ -671,18 +661,8 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   if (!q) return fail(c, LTRI_EINVAL, "q is NULL");
   if (!out) return fail(c, LTRI_EINVAL, "out is NULL");
   // Short query blocks (decode) and shapes the matrix-core kernel does not take go through the three calls.
-  int wgs_per_rb = 0, n_rb = 0, rb_side = 0;
-  bool overlap = !c->dry && n_new > ATT_SPLIT_MAX_ROWS && attend_on_matrix_cores(c->D) && seq_count >= 1 &&
-                 seq_count <= LTRI_MAX_BATCH;
-  if (overlap) {
-    // Row blocks of the first part that start early, on the second stream: as many as leave `reserve`
-    // compute units to the small kernels of steps 1 and 2 (one workgroup of the attention kernel fills a unit).
-    // Measured on the 128K workload, reserving none is fastest: the small kernels then wait for the first
-    // attention workgroups to retire, but the attention never waits for them.
-    attend_launch_shape(c->D, seq_count, n_new, &wgs_per_rb, &n_rb);
-    rb_side = std::min(n_rb, (c->n_cus - c->reserve_cus) / wgs_per_rb);
-    overlap = rb_side > 0;
-  }
+  const bool overlap = !c->dry && n_new > ATT_SPLIT_MAX_ROWS && attend_on_matrix_cores(c->D) && seq_count >= 1 &&
+                       seq_count <= LTRI_MAX_BATCH;
   if (!overlap && !c->dry && n_new == 1) {
     // Decode: steps 1 and 2 of a one-token chunk in one launch where that kernel applies, then step 3.
     BatchPos bp;
@@ -722,42 +702,33 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   int32_t r = append_common(c, layer, seq_begin, seq_count, k_chunk, v_chunk, n_new, bp);
   if (r != LTRI_OK) return r;
   float* lse_a = c->dc.att_lse2;
-  const bool rest = rb_side < n_rb;        // row blocks of the first part that do not start early
   // Context's stream: the kernels of step 1 that fill the chip, the fork, then the small kernels of steps 1 and 2.
-  if (rest) {
-    r = check_hip(c, launch_local_list(c->D, bp, seq_count, c->dc.loclist, c->CL.loc_cap, c->stream), "local list");
-    if (r != LTRI_OK) return r;
-  }
   r = append_spans(c, layer, bp, seq_count, q_seg, n_new, c->ev_fork);
   if (r != LTRI_OK) return r;
   append_commit(c, layer, seq_begin, seq_count, n_new);
-  // Second stream, behind the fork: attention over initial | window | chunk for the later (longer) row blocks.
+  // Second stream, behind the fork: attention over initial | window | chunk.
   r = check_hip(c, hipStreamWaitEvent(c->side, c->ev_fork, 0), "fork");
-  if (r == LTRI_OK && !rest)
+  if (r == LTRI_OK)
     r = check_hip(c, launch_local_list(c->D, bp, seq_count, c->dc.loclist, c->CL.loc_cap, c->side), "local list");
   if (r == LTRI_OK) r = timing_mark(c, c->side);
   if (r == LTRI_OK)
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse_a,
-                                   c->step_stages, nullptr, 1, c->dc.loclist, c->CL.loc_cap, n_rb - rb_side, rb_side,
-                                   nullptr, c->side), "attend (initial, window, chunk)");
+                                   c->step_stages, nullptr, 1, c->dc.loclist, c->CL.loc_cap, nullptr, c->side),
+                  "attend (initial, window, chunk)");
   if (r == LTRI_OK) r = timing_mark(c, c->side);
   if (r == LTRI_OK) r = check_hip(c, hipEventRecord(c->ev_join, c->side), "join");
   if (r != LTRI_OK) return r;
   r = ltri_retrieve(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr);
-  // Context's stream again: the remaining row blocks of the first part, the join, and the retrieved tokens,
-  // whose launch folds the first part's result into its own.
-  if (r == LTRI_OK && rest)
-    r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse_a,
-                                   c->step_stages, nullptr, 1, c->dc.loclist, c->CL.loc_cap, 0, n_rb - rb_side,
-                                   nullptr, c->stream), "attend (initial, window, chunk)");
-  // join even after an error, so that the context's stream never runs ahead of the second stream's writes to out
+  // Context's stream again: the join, then the retrieved tokens, whose launch folds the first part's result into
+  // its own. Join even after an error, so that the context's stream never runs ahead of the second stream's writes
+  // to out.
   const int32_t rj = check_hip(c, hipStreamWaitEvent(c->stream, c->ev_join, 0), "join");
   if (r != LTRI_OK) return r;
   if (rj != LTRI_OK) return rj;
   r = timing_mark(c, c->stream);
   if (r != LTRI_OK) return r;
   r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse,
-                                 c->step_stages, nullptr, 2, nullptr, 0, 0, -1, lse_a, c->stream),
+                                 c->step_stages, nullptr, 2, nullptr, 0, lse_a, c->stream),
                 "attend (retrieved)");
   if (r != LTRI_OK) return r;
   return timing_mark(c, c->stream);

@@ -147,10 +147,8 @@ hipError_t launch_force_list(const Dims& D, const DevState& st, int layer, int s
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
                          void* out, float* lse, int stages, float* part, int part_mode, const int32_t* loclist,
-                         int loc_cap, int rb_first, int rb_count, const float* lse_a,
-                         hipStream_t s);   // rb_count < 0: every row block; lse_a: first part's, for the retrieved part
-// workgroups per block of query rows and number of such blocks of the matrix-core kernel's launch
-void attend_launch_shape(const Dims& D, int seq_count, int n_q, int* wgs_per_row_block, int* row_blocks);
+                         int loc_cap, const float* lse_a,
+                         hipStream_t s);   // lse_a: the first part's log-sum-exp, for the retrieved part
 // bytes of partial results a launch over seq_count sequences with n_q query rows needs (0: the key range is not split)
 size_t attend_partial_bytes(const Dims& D, int seq_count, int n_q, int n_cus);
 // device address, on the current device, of the library's own buffer of ATT_STATIC_SCRATCH_BYTES for partial results

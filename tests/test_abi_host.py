@@ -202,7 +202,6 @@ def test_whole_step_call_rules_in_dry_mode():
     behind, and fails where any of the three would."""
     cfg = config_from_workload(CONFIGS["cfg1"], max_tokens=600, theta=1.0)
     ctx = LtriContext(cfg, None, dry=True)
-    ctx.set_step_reserve(7)                          # a tuning knob: accepted and ignored without a device
     ctx.step(0, 0, 1, None, None, _FakeQ(256))
     assert ctx.token_count(0, 0) == 256
     ctx.attend(0, 0, 1, _FakeQ(256))                 # the step left a selection for this chunk

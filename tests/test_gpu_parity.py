@@ -22,8 +22,6 @@ def _stream_parity(w, seed, T, device, *, seg_map=O.MAP_LOGIT, theta=None, phi=0
                    rows=None, chunk_sizes=None, whole_step=False, **kw):
     K, V, Q, _ = planted_stream(w, seed, device=str(device), context=T)
     ctx, st = make_pair(w, K, V, device, max_tokens=T, seg_map=seg_map, theta=theta, phi=phi, **kw)
-    if whole_step is not True and whole_step is not False:
-        ctx.set_step_reserve(int(whole_step))       # compute units kept free: decides how many row blocks start early
     Kn = K.double().cpu().numpy()
     Qn = Q.double().cpu().numpy()
     c0 = 0
@@ -180,9 +178,8 @@ def test_whole_step_on_two_streams(gpu_device):
                                                 rows=[0, 1, 31, 32, 63, 64, 500, 1000, 1023], whole_step=True)
     assert n_unstable <= 1
     sizes = [1024, 300, 1, 65, 511, 1000, 64, 1024, 2]
-    # 216 of 256 compute units reserved: 5 of a full chunk's 16 row blocks start early, the rest follow step 2
     _stream_parity(w, 2, sum(sizes), gpu_device, chunk_sizes=sizes, window=700, budget_tokens=900,
-                   rows=range(0, 1024, 37), whole_step=216, use_q_seg=True)
+                   rows=range(0, 1024, 37), whole_step=True, use_q_seg=True)
     w2 = Workload("mini", 8, 2, 128, "bf16", 768, 256, 4, 128, 0, 200, "uniform", 16, 64)
     _stream_parity(w2, 3, 768, gpu_device, whole_step=True)
     # fp32 contexts take the three calls in order
@@ -753,7 +750,7 @@ def test_runs_are_bitwise_reproducible(gpu_device, mode):
 
 def test_results_do_not_depend_on_ring_depth_or_schedule(gpu_device):
     """Tuning knobs change timing, never a bit of the output: the attention kernel with a 3- and a 4-stage LDS
-    ring, and ltri_step with every row block on the second stream or only some of them."""
+    ring, by the three calls and by ltri_step."""
     w = CONFIGS["cfg2"]
     T = 6144
     K, V, Q, _ = planted_stream(w, 9, device=str(gpu_device), context=T)
@@ -768,8 +765,6 @@ def test_results_do_not_depend_on_ring_depth_or_schedule(gpu_device):
             ctx.set_attend_stages(3)
         if kind in ("calls, 4 stages", "step, 4 stages"):
             ctx.set_attend_stages(4)
-        if kind == "step, 216 units reserved":
-            ctx.set_step_reserve(216)
         outs = []
         for c0 in range(0, T, w.chunk):
             q = Q[c0:c0 + w.chunk].contiguous()
@@ -789,7 +784,6 @@ def test_results_do_not_depend_on_ring_depth_or_schedule(gpu_device):
     assert same(run("calls, 3 stages"), run("calls, 4 stages"))
     base = run("step, 3 stages")
     assert same(base, run("step, 4 stages"))
-    assert same(base, run("step, 216 units reserved"))
 
 
 def test_span_table_overflow_is_reported(gpu_device):
