@@ -354,6 +354,10 @@ def main():
     ap.add_argument("--unit-tokens", type=int, default=0,
                     help="retrieve whole memory units of this many tokens (Eq. 9 as written) instead of spans;\n"
                          "not the headline configuration")
+    ap.add_argument("--kv-offload", action="store_true",
+                    help="host-offloaded KV (Sec. 3.4 first step): the arenas are pinned host memory, the device keeps\n"
+                         "initial tokens, a ring of the latest tokens and the rows fetched for each selection; not the\n"
+                         "headline configuration")
     ap.add_argument("--seed", type=int, default=1)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -392,11 +396,16 @@ def main():
     log(f"[bench] inputs generated in {time.time() - t0:.1f}s")
     cfg = config_from_workload(w, theta=theta, n_layers=1, n_seqs=1,
                                rep_mode=1 if args.index_vectors == "dynamic" else 0, lam=3.0,
-                               theta_quantile=args.theta_quantile, unit_tokens=args.unit_tokens)
+                               theta_quantile=args.theta_quantile, unit_tokens=args.unit_tokens,
+                               kv_offload=int(args.kv_offload))
     ctx = LtriContext(cfg, dev)
     ka, va = ctx.arena_views()
-    ka[0, 0].copy_(K)
-    va[0, 0].copy_(V)
+    if not args.kv_offload:
+        ka[0, 0].copy_(K)
+        va[0, 0].copy_(V)
+    # host-offloaded KV: the rows come with every call
+    kcs = [K[:, c * L:(c + 1) * L].unsqueeze(0).contiguous() if args.kv_offload else None for c in range(n_chunks)]
+    vcs = [V[:, c * L:(c + 1) * L].unsqueeze(0).contiguous() if args.kv_offload else None for c in range(n_chunks)]
     out = torch.empty((1, L, w.n_q_heads, w.head_dim), dtype=w.torch_dtype, device=dev)
     qs = [Q[c * L:(c + 1) * L] for c in range(n_chunks)]          # contiguous views
 
@@ -420,14 +429,14 @@ def main():
     def one_stream_steps():
         ctx.reset(0)
         for c in range(n_chunks):
-            ctx.step(0, 0, 1, None, None, qs[c], out=out)
+            ctx.step(0, 0, 1, kcs[c], vcs[c], qs[c], out=out)
 
     def one_stream(record_lens=False, events=None):
         if step_schedule and events is not None and events is not SEPARATE:
             one_stream_steps()
             return
         ctx.reset(0)
-        ctx.append_chunk(0, 0, 1, L)
+        ctx.append_chunk(0, 0, 1, L, k_chunk=kcs[0], v_chunk=vcs[0])
         for c in range(n_chunks):
             ctx.retrieve(0, 0, 1, qs[c])
             nxt = c + 1 < n_chunks
@@ -447,12 +456,12 @@ def main():
                 if overlap:
                     side.wait_event(ev_r[c])
                     ctx.set_stream(side)
-                    ctx.append_chunk(0, 0, 1, L)
+                    ctx.append_chunk(0, 0, 1, L, k_chunk=kcs[c + 1], v_chunk=vcs[c + 1])
                     ev_a[c].record(side)
                     ctx.set_stream(main)
                     main.wait_event(ev_a[c])
                 else:
-                    ctx.append_chunk(0, 0, 1, L)
+                    ctx.append_chunk(0, 0, 1, L, k_chunk=kcs[c + 1], v_chunk=vcs[c + 1])
 
     # warmup (the first pass also records the list lengths, which need a synchronising read-back)
     one_stream(record_lens=True)
@@ -599,6 +608,17 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(w, K, V, Q, bounds, theta)
 
+    host_link = None
+    if args.kv_offload:
+        elt = 2 if w.dtype == "bf16" else 4
+        row = w.head_dim * elt * 2                                            # K and V
+        n_init_win = [min(w.n_sink, c * L) + (c * L - max(min(w.n_sink, c * L), c * L - w.window)) for c in range(n_chunks)]
+        h2d = sum(sum(n - n_init_win[c] for n in list_lens[c]) for c in range(n_chunks)) * row
+        d2h = T * w.n_kv_heads * row
+        host_link = {"fetched_bytes_per_stream": int(h2d), "written_back_bytes_per_stream": int(d2h),
+                     "sustained_GBps": round((h2d + d2h) / (ms_per_step * 1e-3) / 1e9, 2),
+                     "note": "bytes crossing the host link per stream over the stream's wall time (reads and writes share "
+                             "the time, the link is full duplex)"}
     result = {
         "metric": "prefill tokens/s per layer", "value": round(value, 1), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
@@ -612,12 +632,14 @@ def main():
                    "seg_map": "logit", "theta": theta if not args.theta_quantile else f"percentile {args.theta_quantile}",
                    "phi": 0.0,
                    "retrieval_unit": "span" if not args.unit_tokens else f"memory units of {args.unit_tokens} tokens",
+                   "kv": ("host-offloaded: pinned host arenas, device ring + fetched rows" if args.kv_offload
+                          else "resident in HBM"),
                    "index_vectors": "mean key per span" if args.index_vectors == "mean"
                    else "dynamic (row ratio, lambda 3): sum of the keys of each span's index tokens",
                    "schedule": "append(c+1) on a second stream next to attend(c)" if overlap else
                    ("ltri_step per chunk: attention over initial | window | chunk on a second stream beside "
                     "steps 1 and 2, retrieved tokens after, merged" if step_schedule else "three calls per chunk, serial")},
-        "roofline": roofline, "gather": gather, "cpu_baseline": cpu,
+        "roofline": roofline, "gather": gather, "cpu_baseline": cpu, "host_link": host_link,
         "breakdown_ms": {"attend": round(tot_ms / args.steps, 3), "rest_of_step": round(other_ms, 3),
                          "note": ("attend = sum of the two attention launches of every step; the first one overlaps the "
                                   "small kernels of steps 1 and 2" if step_schedule else "serial calls"),

@@ -112,6 +112,16 @@ typedef struct {
    * persistent ones) then hold unit ids and the context set holds whole units' evicted parts.
    * At most chunk_max, and max_tokens / unit_tokens + 1 <= 8192. 0: spans are retrieved. */
   int32_t unit_tokens;
+  /* 1: host-offloaded KV (Sec. 3.4 first step: the keys and values of evicted tokens live in CPU memory, only
+   * their index vectors stay on the GPU). k_arena / v_arena given to ltri_create are then HOST arenas of the
+   * usual layout in pinned, device-visible memory (hipHostMalloc, or torch's pin_memory): every appended row is
+   * written there. On the device the context keeps, inside `state`, per (layer, sequence, KV head) only the
+   * initial tokens, a ring of the latest tokens (a power of two >= window + 2 chunk_max rows) and room for the
+   * rows of one selection; step 2 ends by fetching the selected tokens' rows from the host arenas into that room
+   * (a kernel reading host memory; no host synchronisation), and step 3 reads initial | fetched | ring rows.
+   * Results are those of the resident layout bit for bit. The chunk's rows must be passed to the append
+   * (k_chunk / v_chunk non-NULL). 0: everything resident in the device arenas. */
+  int32_t kv_offload;
 } ltri_config;
 
 /* Sizes (bytes) of the two device buffers a context needs: `state` holds the index
@@ -121,8 +131,8 @@ typedef struct {
 int32_t ltri_workspace_bytes(const ltri_config* cfg, size_t* state_bytes, size_t* scratch_bytes);
 
 /* Creates a context. k_arena / v_arena / state / scratch are device pointers owned by the
- * caller (256-byte aligned), hip_stream is a hipStream_t (NULL = default stream). The call
- * enqueues a kernel that clears `state`. */
+ * caller (256-byte aligned; with kv_offload the two arenas are pinned host memory instead),
+ * hip_stream is a hipStream_t (NULL = default stream). The call enqueues a kernel that clears `state`. */
 int32_t ltri_create(const ltri_config* cfg, void* k_arena, void* v_arena, void* state, void* scratch,
                     void* hip_stream, ltri_ctx** out);
 int32_t ltri_destroy(ltri_ctx* ctx);

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   // initial | window from a list of their own, or the retrieved slice of the full list
   const int n_init = min(D.n_sink, c0), n_win = c0 - max(n_init, c0 - D.window);
   int list_len = meta[META_LIST_LEN];
-  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
+  const int32_t* list = a.st.row_list + (size_t)slot * D.list_cap;
   if (a.part_mode == ATT_LOCAL) {
     list_len = n_init + n_win;
     list = a.loclist + (size_t)bi * a.loc_cap;
@@ -181,6 +181,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
     list += n_init;
   }
   const int n_ctx_tiles = (list_len + 63) / 64;
+  const int crow0 = chunk_tok_row(D, c0, c0);       // row of the chunk's first token (the chunk's rows are consecutive)
   const int n_chunk_tiles = a.part_mode == ATT_RETRIEVED ? 0 : (rb_end + 63) / 64;
   const int n_tiles = n_ctx_tiles + n_chunk_tiles;
   // with splits, this workgroup takes the context tiles [tile0, tile1); the last split also takes the chunk's tiles
@@ -219,7 +220,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
       for (int i = 0; i < NI; ++i) tok[i] = tokring[(t % TOK_SLOTS) * (NW * 8) + 4 * i + lq];
     } else {
 #pragma unroll
-      for (int i = 0; i < NI; ++i) tok[i] = c0 + min((t - n_ctx_tiles) * 64 + 4 * NW * i + 4 * wave + lq, L - 1);
+      for (int i = 0; i < NI; ++i) tok[i] = crow0 + min((t - n_ctx_tiles) * 64 + 4 * NW * i + 4 * wave + lq, L - 1);
     }
   };
   auto request_rows = [&](int t, int i, int tok) {
@@ -562,8 +563,9 @@ __global__ __launch_bounds__(64 * DEC_WAVES, 3) void attend_decode_kernel(AttArg
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.k_arena) + arena_off(D, slot) * 2;
   const unsigned char* Vb = reinterpret_cast<const unsigned char*>(a.v_arena) + arena_off(D, slot) * 2;
   const int list_len = a.st.meta[(size_t)slot * META_WORDS + META_LIST_LEN];
-  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
+  const int32_t* list = a.st.row_list + (size_t)slot * D.list_cap;
   const int n_keys = list_len + 1;                  // the context list and the token itself
+  const int crow0 = chunk_tok_row(D, c0, c0);
   const int n_groups = (n_keys + 15) >> 4;
   const int workers = a.n_splits * DEC_WAVES, w = split * DEC_WAVES + wave;
   const int gpw = (n_groups + workers - 1) / workers;
@@ -584,11 +586,11 @@ __global__ __launch_bounds__(64 * DEC_WAVES, 3) void attend_decode_kernel(AttArg
   struct Toks { int k, v[4]; };
   auto load_tokens = [&](int g, Toks& t) __attribute__((always_inline)) {
     const int rk = min(g * 16 + kl, n_keys - 1);
-    t.k = rk < list_len ? list[rk] : c0;
+    t.k = rk < list_len ? list[rk] : crow0;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int rv = min(g * 16 + 4 * grp + j, n_keys - 1);
-      t.v[j] = rv < list_len ? list[rv] : c0;
+      t.v[j] = rv < list_len ? list[rv] : crow0;
     }
   };
   auto load_rows = [&](const Toks& t, uint4 (&kf)[4], uint4 (&vf)[4]) __attribute__((always_inline)) {
@@ -718,7 +720,7 @@ __global__ __launch_bounds__(256) void local_list_kernel(Dims D, BatchPos bp, in
   const int bi = blockIdx.y, c0 = bp.c0[bi];
   const int n_init = min(D.n_sink, c0), w0 = max(n_init, c0 - D.window), len = n_init + c0 - w0;
   const int r = blockIdx.x * 256 + threadIdx.x;
-  if (r < loc_cap) loclist[(size_t)bi * loc_cap + r] = r < n_init ? r : (r < len ? w0 + r - n_init : 0);
+  if (r < loc_cap) loclist[(size_t)bi * loc_cap + r] = r < n_init ? r : (r < len ? window_tok_row(D, w0 + r - n_init) : 0);
 }
 
 // ---- fp32 kernel: one wavefront per (query row, head); keys across lanes ----
@@ -738,7 +740,7 @@ __global__ __launch_bounds__(64) void attend_simple_kernel(AttArgs a) {
   const T* Vb = reinterpret_cast<const T*>(a.v_arena) + arena_off(D, slot);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int list_len = meta[META_LIST_LEN];
-  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
+  const int32_t* list = a.st.row_list + (size_t)slot * D.list_cap;
   const T* qrow = reinterpret_cast<const T*>(a.q) + (((size_t)bi * L + qi) * D.Hq + head) * d;
   for (int c = lane; c < d; c += 64) qs[c] = Elt<DT>::to_f32(qrow[c]);
   __syncthreads();
@@ -749,7 +751,7 @@ __global__ __launch_bounds__(64) void attend_simple_kernel(AttArgs a) {
     const int k = k0 + lane;
     int tok = -1;
     if (k < list_len) tok = list[k];
-    else if (k < n_keys) tok = c0 + (k - list_len);
+    else if (k < n_keys) tok = chunk_tok_row(D, c0, c0) + (k - list_len);
     float z = -INFINITY;
     if (tok >= 0) {
       const T* krow = Kb + (size_t)tok * d;
@@ -799,7 +801,7 @@ __global__ __launch_bounds__(256) void gather_pack_kernel(GatherArgs a) {
   const int slot = slot_of(D, a.layer, a.seq, h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int list_len = meta[META_LIST_LEN];
-  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap;
+  const int32_t* list = a.st.row_list + (size_t)slot * D.list_cap;
   const int row16 = D.d * D.elt / 16;                        // 16-byte pieces per row
   const int rows_per_pass = 256 / row16;
   const int r_in = threadIdx.x / row16, piece = threadIdx.x - r_in * row16;

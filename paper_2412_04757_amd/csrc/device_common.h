@@ -59,7 +59,15 @@ __device__ __forceinline__ int slot_of(const Dims& D, int layer, int seq, int h)
 }
 // Element offset of token 0 of a slot inside a KV arena.
 __device__ __forceinline__ size_t arena_off(const Dims& D, int slot) {
-  return (size_t)slot * (size_t)D.max_tokens * (size_t)D.d;
+  return (size_t)slot * (size_t)D.arena_rows * (size_t)D.d;
+}
+// Row, inside its slot, of token `tok` of the chunk that starts at token c0 (the chunk's rows are consecutive).
+__device__ __forceinline__ int chunk_tok_row(const Dims& D, int c0, int tok) {
+  return D.ring0 + (c0 & D.ring_mask) + (tok - c0);
+}
+// Row of a token of the local window (any token among the latest ring_mask + 1 ones).
+__device__ __forceinline__ int window_tok_row(const Dims& D, int tok) {
+  return D.ring0 + (tok & D.ring_mask);
 }
 
 __device__ __forceinline__ double wave_sum_f64(double v) {

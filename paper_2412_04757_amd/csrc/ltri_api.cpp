@@ -16,7 +16,8 @@ struct ltri_ctx {
   Dims D;
   StateLayout SL;
   ScratchLayout CL;
-  char* k_arena; char* v_arena; char* state; char* scratch;
+  char* k_arena; char* v_arena; char* state; char* scratch;   // k_arena / v_arena: where the kernels read K/V rows (offloaded KV: the device pools inside `state`)
+  char* k_host; char* v_host;                                  // offloaded KV: the caller's host arenas, else NULL
   hipStream_t stream;
   DevState ds;
   DevScratch dc;
@@ -89,6 +90,8 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   D.ratio_mode = c.ratio_mode;
   D.theta_quantile = (double)c.theta_quantile;
   D.unit = c.unit_tokens;
+  if (c.kv_offload != 0 && c.kv_offload != 1) return LTRI_EINVAL;
+  D.offload = c.kv_offload;
   if (c.max_spans > 65536) return LTRI_EINVAL;
   long long ms = c.max_spans ? c.max_spans : std::min<long long>(c.max_tokens / 32 + 64, 65536);
   if (ms > c.max_tokens) ms = c.max_tokens;
@@ -106,6 +109,20 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   if (lc > (1ll << 30)) return LTRI_EINVAL;
   D.list_cap = (int)lc;
   D.elt = c.dtype == LTRI_F32 ? 4 : 2;
+  if (D.offload) {
+    // device pool of a slot: initial tokens | ring (a power of two of at least window + 2 chunks, so that the next
+    // chunk can be appended while the last one is still attended) + one chunk of mirror rows | retrieved rows
+    long long ring = 64;
+    while (ring < (long long)c.window + 2ll * c.chunk_max) ring <<= 1;
+    if (ring > (1ll << 24)) return LTRI_EINVAL;
+    D.ring0 = c.n_sink;
+    D.ring_mask = (int)(ring - 1);
+    D.stage0 = (int)(c.n_sink + ring + c.chunk_max);
+    D.arena_rows = (long long)D.stage0 + D.list_cap;
+  } else {
+    D.ring0 = 0; D.ring_mask = -1; D.stage0 = 0;
+    D.arena_rows = c.max_tokens;
+  }
 
   const size_t n_slots = (size_t)c.n_layers * c.n_seqs * c.n_kv_heads;
   size_t o = 0;
@@ -118,6 +135,9 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   SL.tok_list = o;   o = align_up(o + n_slots * (size_t)D.list_cap * 4, 256);
   SL.err = o;        o = align_up(o + 16, 256);
   SL.idx_mask = o;   o = align_up(o + n_slots * IDX_MASK_WORDS * 4, 256);
+  SL.row_list = o;   o = align_up(o + (D.offload ? n_slots * (size_t)D.list_cap * 4 : 0), 256);
+  SL.k_pool = o;     o = align_up(o + (D.offload ? n_slots * (size_t)D.arena_rows * D.d * D.elt : 0), 256);
+  SL.v_pool = o;     o = align_up(o + (D.offload ? n_slots * (size_t)D.arena_rows * D.d * D.elt : 0), 256);
   SL.total = o;
 
   // scratch: segmentation temporaries for up to 4 sequences at a time
@@ -193,7 +213,28 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   ltri_ctx* c = new (std::nothrow) ltri_ctx();
   if (!c) return LTRI_EINVAL;
   c->cfg = *cfg; c->D = D; c->SL = SL; c->CL = CL;
-  c->k_arena = (char*)k_arena; c->v_arena = (char*)v_arena; c->state = (char*)state; c->scratch = (char*)scratch;
+  c->state = (char*)state; c->scratch = (char*)scratch;
+  if (D.offload && !dry) {
+    // the host arenas must be pinned memory the device can address: the kernels use the device's view of them
+    void* dev_view[2] = {nullptr, nullptr};
+    void* given[2] = {k_arena, v_arena};
+    for (int i = 0; i < 2; ++i) {
+      hipPointerAttribute_t at;
+      memset(&at, 0, sizeof at);
+      const hipError_t e = hipPointerGetAttributes(&at, given[i]);
+      if (e != hipSuccess || at.type != hipMemoryTypeHost || !at.devicePointer) {
+        (void)hipGetLastError();
+        delete c;
+        return LTRI_EINVAL;
+      }
+      dev_view[i] = at.devicePointer;
+    }
+    c->k_host = (char*)dev_view[0]; c->v_host = (char*)dev_view[1];
+    c->k_arena = c->state + SL.k_pool; c->v_arena = c->state + SL.v_pool;
+  } else {
+    c->k_host = nullptr; c->v_host = nullptr;
+    c->k_arena = (char*)k_arena; c->v_arena = (char*)v_arena;
+  }
   c->stream = (hipStream_t)hip_stream;
   c->dry = dry;
   c->attend_stages = 4;
@@ -205,7 +246,8 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   char* s = c->state;
   c->ds = DevState{(int32_t*)(s + SL.meta), (int32_t*)(s + SL.span_start), (int32_t*)(s + SL.span_len),
                    (void*)(s + SL.krep), (double*)(s + SL.scores), (int32_t*)(s + SL.sel_ids),
-                   (int32_t*)(s + SL.tok_list), (int32_t*)(s + SL.err), (uint32_t*)(s + SL.idx_mask)};
+                   (int32_t*)(s + SL.tok_list), (int32_t*)(s + SL.err), (uint32_t*)(s + SL.idx_mask),
+                   (int32_t*)(s + (D.offload ? SL.row_list : SL.tok_list))};
   char* t = c->scratch;
   c->dc = DevScratch{(double*)(t + CL.rowsum), (double*)(t + CL.csuf), (double*)(t + CL.tsum),
                      (double*)(t + CL.rcar), (double*)(t + CL.ccar), (double*)(t + CL.pscore),
@@ -293,6 +335,14 @@ static int32_t check_range(ltri_ctx* c, int layer, int seq_begin, int seq_count)
 
 static size_t ls_index(const ltri_ctx* c, int layer, int seq) { return (size_t)layer * c->D.n_seqs + seq; }
 
+// Host-offloaded KV: once a selection's token list is written, the rows of its retrieved tokens are fetched from
+// the host arenas into the device pool, on the context's stream, before anything attends.
+static int32_t fetch_retrieved(ltri_ctx* c, int layer, const BatchPos& bp, int seq_count) {
+  if (!c->D.offload || c->dry) return LTRI_OK;
+  return check_hip(c, launch_fetch_retrieved(c->D, c->ds, c->k_arena, c->v_arena, c->k_host, c->v_host, layer, bp,
+                                             seq_count, c->stream), "fetch retrieved rows");
+}
+
 extern "C" {
 
 int32_t ltri_reset(ltri_ctx* c, int32_t seq) {
@@ -320,6 +370,8 @@ static int32_t append_common(ltri_ctx* c, int layer, int seq_begin, int seq_coun
     return fail(c, LTRI_EINVAL, "n_new %d outside [1, chunk_max %d]", n_new, c->D.chunk_max);
   if ((k_chunk == nullptr) != (v_chunk == nullptr))
     return fail(c, LTRI_EINVAL, "k_chunk and v_chunk must both be given or both be NULL");
+  if (c->D.offload && !k_chunk)
+    return fail(c, LTRI_EINVAL, "host-offloaded KV: the chunk's rows must be passed (k_chunk / v_chunk), the device holds no arena to find them in");
   for (int s = 0; s < seq_count; ++s) {
     const size_t i = ls_index(c, layer, seq_begin + s);
     if (c->n_tokens[i] + n_new > c->D.max_tokens)
@@ -330,7 +382,7 @@ static int32_t append_common(ltri_ctx* c, int layer, int seq_begin, int seq_coun
   }
   if (k_chunk && !c->dry) {
     r = check_hip(c, launch_copy_chunk(c->D, c->k_arena, c->v_arena, k_chunk, v_chunk, layer, bp, seq_count,
-                                       n_new, c->stream), "copy chunk");
+                                       n_new, c->k_host, c->v_host, c->stream), "copy chunk");
     if (r != LTRI_OK) return r;
   }
   return LTRI_OK;
@@ -470,6 +522,8 @@ int32_t ltri_retrieve(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq
     r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound, sel_ids,
                                      sel_cnt, nullptr, nullptr, c->stream), "retrieve");
     if (r != LTRI_OK) return r;
+    r = fetch_retrieved(c, layer, bp, seq_count);
+    if (r != LTRI_OK) return r;
   }
   for (int s = 0; s < seq_count; ++s) {
     c->have_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
@@ -512,6 +566,8 @@ int32_t ltri_retrieve_collaborative(ltri_ctx* c, int32_t layer, int32_t seq_begi
     r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound,
                                      sel_ids, sel_cnt, &v, nullptr, c->stream), "collaborative retrieve");
     if (r != LTRI_OK) return r;
+    r = fetch_retrieved(c, layer, bp, seq_count);
+    if (r != LTRI_OK) return r;
   }
   for (int s = 0; s < seq_count; ++s) {
     c->have_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
@@ -537,6 +593,8 @@ int32_t ltri_retrieve_persistent(ltri_ctx* c, int32_t layer, int32_t seq_begin, 
   }
   if (!c->dry) {
     r = check_hip(c, launch_persist_list(c->D, c->ds, layer, bp, seq_count, c->stream), "persistent selection");
+    if (r != LTRI_OK) return r;
+    r = fetch_retrieved(c, layer, bp, seq_count);
     if (r != LTRI_OK) return r;
   }
   for (int s = 0; s < seq_count; ++s) c->have_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
@@ -568,6 +626,12 @@ int32_t ltri_force_selection(ltri_ctx* c, int32_t layer, int32_t seq, int32_t kv
     }
     r = check_hip(c, launch_force_list(c->D, c->ds, layer, seq, kv_head, (int)ids.size(), c->stream),
                   "forced selection");
+    if (r != LTRI_OK) return r;
+    BatchPos fb;
+    memset(&fb, 0, sizeof fb);
+    fb.seq[0] = seq;
+    fb.c0[0] = (int32_t)(c->n_tokens[i] - c->last_len[i]);
+    r = fetch_retrieved(c, layer, fb, 1);                 // every KV head of the sequence: the others' rows are fetched again
     if (r != LTRI_OK) return r;
   }
   c->have_sel[i] |= 1u << (kv_head & 31);
@@ -676,6 +740,8 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
       append_commit(c, layer, seq_begin, seq_count, 1);
       r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, 1, (int)bound,
                                        nullptr, nullptr, nullptr, c->k_arena, c->stream), "append and retrieve (one token)");
+      if (r != LTRI_OK) return r;
+      r = fetch_retrieved(c, layer, bp, seq_count);
       if (r != LTRI_OK) return r;
       for (int s = 0; s < seq_count; ++s) {
         c->have_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;

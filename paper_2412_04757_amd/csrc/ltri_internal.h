@@ -43,6 +43,10 @@ struct StateLayout {
   size_t tok_list;    // int32  [n_slots][list_cap]
   size_t err;         // int32  [4]
   size_t idx_mask;    // uint32 [n_slots][IDX_MASK_WORDS]  index tokens of the chunk appended last (dynamic index vectors)
+  // host-offloaded KV only (else row_list == tok_list and the pools are empty):
+  size_t row_list;    // int32  [n_slots][list_cap]  the context list as rows of the device pool
+  size_t k_pool;      // dtype  [n_slots][pool_rows][d]  initial tokens | ring of the latest tokens | retrieved rows
+  size_t v_pool;      // dtype  [n_slots][pool_rows][d]
   size_t total;
 };
 
@@ -89,6 +93,15 @@ struct Dims {
   double lambda;
   double theta_quantile;                            // > 0: theta is this percentile of the chunk's map
   int unit;                                         // > 0: retrieval by memory units of this many tokens (Eq. 9)
+  // Where the kernels find K/V rows. Resident KV: a slot's rows are its tokens, arena_rows = max_tokens, and
+  // ring_mask = -1, ring0 = stage0 = 0. Host-offloaded KV (Sec. 3.4 first step: evicted tokens live in CPU
+  // memory): a slot's rows on the device are a pool of arena_rows rows = the initial tokens [0, n_sink) | a
+  // ring of ring_mask + 1 rows plus chunk_max mirror rows from ring0 (token t at ring0 + (t & ring_mask); a
+  // chunk is written without a break, its part past the ring's end again at the ring's start) | the rows
+  // fetched for the retrieved tokens from stage0 on.
+  int offload;
+  long long arena_rows;
+  int ring0, ring_mask, stage0;
 };
 
 struct BatchPos {            // per-sequence values of one batched call
@@ -110,6 +123,7 @@ struct VoteArgs {
 struct DevState {
   int32_t* meta; int32_t* span_start; int32_t* span_len; void* krep; double* scores;
   int32_t* sel_ids; int32_t* tok_list; int32_t* err; uint32_t* idx_mask;
+  int32_t* row_list;       // what the attention walks: tok_list itself, or (host-offloaded KV) the same list as pool rows
 };
 struct DevScratch {
   double* rowsum; double* csuf; double* tsum; double* rcar; double* ccar;
@@ -122,7 +136,10 @@ struct DevScratch {
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_copy_chunk(const Dims& D, void* k_arena, void* v_arena, const void* k_chunk,
                              const void* v_chunk, int layer, const BatchPos& bp, int seq_count,
-                             int n_new, hipStream_t s);
+                             int n_new, void* k_host, void* v_host, hipStream_t s);   // k_host / v_host: the host arenas of an offloaded context, else NULL
+// host-offloaded KV: rows of the retrieved tokens of the current list, host arenas -> device pool
+hipError_t launch_fetch_retrieved(const Dims& D, const DevState& st, void* k_pool, void* v_pool, const void* k_host,
+                                  const void* v_host, int layer, const BatchPos& bp, int seq_count, hipStream_t s);
 hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& sc, const void* k_arena,
                           const void* q_seg, int layer, const BatchPos& bp, int batch_off, int seq_count,
                           int n_new, hipEvent_t after_tiles, hipStream_t s);   // event (or NULL): recorded behind the last kernel that fills the chip

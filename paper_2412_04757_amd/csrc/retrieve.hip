@@ -261,9 +261,12 @@ __device__ void emit_selection(const Dims& D, const DevState& st, int slot, cons
   const int32_t* slen = st.span_len + (size_t)slot * D.max_spans;
   int32_t* sel = st.sel_ids + (size_t)slot * D.sel_cap;
   int32_t* list = st.tok_list + (size_t)slot * D.list_cap;
+  // host-offloaded KV: the same list as rows of the device pool (initial tokens in place, retrieved token j at
+  // stage0 + j, window tokens in the ring), which is what the attention walks
+  int32_t* rows = D.offload ? st.row_list + (size_t)slot * D.list_cap : nullptr;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   if (tid == 0) { s_base_cnt = 0; s_base_tok = 0; }
-  for (int t = tid; t < ns; t += blockDim.x) list[t] = t;
+  for (int t = tid; t < ns; t += blockDim.x) { list[t] = t; if (rows) rows[t] = t; }
   __syncthreads();
   for (int i0 = 0; i0 < n; i0 += blockDim.x) {
     const int i = i0 + tid;
@@ -319,11 +322,16 @@ __device__ void emit_selection(const Dims& D, const DevState& st, int slot, cons
       if (o + t < D.list_cap) list[o + t] = a + t;
   }
   if (fits) {
-    for (int t = tid; t < n_win; t += blockDim.x) list[ns + n_ret + t] = ws + t;
+    for (int t = tid; t < n_win; t += blockDim.x) {
+      list[ns + n_ret + t] = ws + t;
+      if (rows) rows[ns + n_ret + t] = window_tok_row(D, ws + t);
+    }
+    if (rows)
+      for (int t = tid; t < n_ret; t += blockDim.x) rows[ns + t] = D.stage0 + t;
     // padding: a valid token, masked by position. One tile more than the list's own last tile, because the
     // attention over the retrieved slice alone starts its tiles at the end of the initial tokens.
     const int padded = min(D.list_cap, (len + ATT_BN - 1) / ATT_BN * ATT_BN + ATT_BN);
-    for (int t = len + tid; t < padded; t += blockDim.x) list[t] = 0;
+    for (int t = len + tid; t < padded; t += blockDim.x) { list[t] = 0; if (rows) rows[t] = 0; }
   }
   if (tid == 0) {
     if (!fits) atomicCAS(&st.err[0], 0, LTRI_ECAPACITY);
@@ -557,7 +565,7 @@ __global__ __launch_bounds__(1024) void retrieve_one_token_kernel(RetArgs a, int
     const bool fits = base + 1 <= D.max_spans;
     __syncthreads();                                    // every thread has read the old count
     if (fits && tid < d) {
-      const T* row = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * d;
+      const T* row = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)chunk_tok_row(D, c0, c0) * d;
       (reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + base) * d)[tid] = row[tid];
     }
     if (tid == 0) {

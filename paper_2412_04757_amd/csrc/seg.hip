@@ -100,7 +100,7 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wi = wave >> 1, wj = wave & 1, hf = lane >> 5, l32 = lane & 31;
   const int slot = slot_of(D, a.layer, seq, h);
-  const T* Kc = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * d;
+  const T* Kc = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)chunk_tok_row(D, c0, c0) * d;
   const T* Qb = a.q_seg ? reinterpret_cast<const T*>(a.q_seg) + (size_t)bi * L * D.Hq * d + (size_t)h * D.G * d : nullptr;
   const int n_h = a.q_seg ? D.G : 1;
   const int nkc = d * (int)sizeof(T) / 256;                  // 256-byte pieces per row
@@ -616,7 +616,7 @@ __global__ __launch_bounds__(256) void lse_tile_kernel(SegArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wi = wave >> 1, wj = wave & 1, hf = lane >> 5, l32 = lane & 31;
   const int slot = slot_of(D, a.layer, seq, h);
-  const T* Kc = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * d;
+  const T* Kc = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)chunk_tok_row(D, c0, c0) * d;
   const T* Qb = a.q_seg ? reinterpret_cast<const T*>(a.q_seg) + (size_t)bi * L * D.Hq * d + (size_t)h * D.G * d : nullptr;
   const int n_h = a.q_seg ? D.G : 1;
   const int nkc = d * (int)sizeof(T) / 256;
@@ -858,7 +858,7 @@ __global__ __launch_bounds__(1024) void dyn_span_kernel(SegArgs a) {
       }
     }
     T* rep = reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + sid) * D.d;
-    span_mean_block<DT>(Kb + (size_t)start * D.d, (size_t)D.d, 1, len, D.d, rep, part, nullptr, smask, 0);
+    span_mean_block<DT>(Kb + (size_t)chunk_tok_row(D, c0, start) * D.d, (size_t)D.d, 1, len, D.d, rep, part, nullptr, smask, 0);
   }
 }
 
@@ -876,7 +876,7 @@ __global__ __launch_bounds__(64) void append_single_kernel(SingleArgs a) {
   const int base = meta[META_N_SPANS];
   const bool fits = base + 1 <= D.max_spans;
   if (fits) {
-    const T* krow = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)c0 * D.d;
+    const T* krow = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot) + (size_t)chunk_tok_row(D, c0, c0) * D.d;
     T* rep = reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + base) * D.d;
     for (int c = threadIdx.x; c < D.d; c += 64) rep[c] = krow[c];
   }
@@ -917,36 +917,95 @@ __global__ __launch_bounds__(1024) void rep_keys_kernel(RepArgs a) {
   const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
-  const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP];
+  const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP], c0 = meta[META_CHUNK_START];
   const T* Kb = reinterpret_cast<const T*>(a.k_arena) + arena_off(D, slot);
   for (int q = blockIdx.x; q < nsp; q += gridDim.x) {
     const int sid = first + q;
     const int start = a.st.span_start[(size_t)slot * D.max_spans + sid];
     const int len = a.st.span_len[(size_t)slot * D.max_spans + sid];
     T* rep = reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + sid) * D.d;
-    span_mean_block<DT>(Kb + (size_t)start * D.d, (size_t)D.d, 1, len, D.d, rep, part);
+    span_mean_block<DT>(Kb + (size_t)chunk_tok_row(D, c0, start) * D.d, (size_t)D.d, 1, len, D.d, rep, part);
   }
 }
 
 // ---- copies of a caller's chunk into the arenas ----
+// Resident KV: the rows go to their tokens' places. Host-offloaded KV (Sec. 3.4 first step): the device keeps
+// only the initial tokens and a ring of the latest tokens; every row is also written to the host arenas
+// (device-visible pinned memory), from which step 3 fetches the rows it retrieves.
 struct CopyArgs { Dims D; void* k_arena; void* v_arena; const void* k_chunk; const void* v_chunk;
-                  int layer; int seq_count; int n_new; BatchPos bp; };
+                  int layer; int seq_count; int n_new; BatchPos bp; void* k_host; void* v_host; };
 
 __global__ __launch_bounds__(256) void copy_chunk_kernel(CopyArgs a) {
   const Dims& D = a.D;
   const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int c0 = a.bp.c0[bi];
   const size_t row_bytes = (size_t)D.d * D.elt;
-  const size_t n16 = (size_t)a.n_new * row_bytes / 16;
-  const size_t dst_off = (arena_off(D, slot) + (size_t)a.bp.c0[bi] * D.d) * D.elt;
+  const int r16 = (int)(row_bytes / 16);                     // 16-byte pieces per row
+  const size_t n16 = (size_t)a.n_new * r16;
+  const size_t dst_off = (arena_off(D, slot) + (size_t)chunk_tok_row(D, c0, c0) * D.d) * D.elt;
   const size_t src_off = (size_t)p * a.n_new * row_bytes;
   const uint4* ks = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.k_chunk) + src_off);
   const uint4* vs = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.v_chunk) + src_off);
   uint4* kd = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.k_arena) + dst_off);
   uint4* vd = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.v_arena) + dst_off);
+  if (!D.offload) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) {
+      kd[i] = ks[i];
+      vd[i] = vs[i];
+    }
+    return;
+  }
+  const size_t slot_bytes = arena_off(D, slot) * D.elt;
+  uint4* kp = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.k_arena) + slot_bytes);     // row 0 of the slot's pool
+  uint4* vp = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.v_arena) + slot_bytes);
+  const size_t host_off = ((size_t)slot * (size_t)D.max_tokens + (size_t)c0) * row_bytes;
+  uint4* kh = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.k_host) + host_off);
+  uint4* vh = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.v_host) + host_off);
+  const int ring = D.ring_mask + 1, pos0 = c0 & D.ring_mask;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += (size_t)gridDim.x * blockDim.x) {
-    kd[i] = ks[i];
-    vd[i] = vs[i];
+    const uint4 kv = ks[i], vv = vs[i];
+    const int r = (int)(i / r16), piece = (int)(i - (size_t)r * r16);
+    kd[i] = kv; vd[i] = vv;                                  // ring (running on into its mirror rows)
+    if (pos0 + r >= ring) {                                  // the part past the ring's end, again at its start
+      const size_t w = (size_t)(D.ring0 + pos0 + r - ring) * r16 + piece;
+      kp[w] = kv; vp[w] = vv;
+    }
+    if (c0 + r < D.n_sink) {                                 // initial tokens keep rows of their own
+      const size_t w = (size_t)(c0 + r) * r16 + piece;
+      kp[w] = kv; vp[w] = vv;
+    }
+    kh[i] = kv; vh[i] = vv;                                  // host arenas: every token, in place
+  }
+}
+
+// ---- host-offloaded KV: rows of the retrieved tokens, host arenas -> the staging rows of the device pool ----
+// The context list is initial | retrieved | window; entry ns + j of the token list goes to pool row stage0 + j.
+struct FetchArgs { Dims D; DevState st; void* k_pool; void* v_pool; const void* k_host; const void* v_host;
+                   int layer; BatchPos bp; };
+
+__global__ __launch_bounds__(256) void fetch_retrieved_kernel(FetchArgs a) {
+  const Dims& D = a.D;
+  const int p = blockIdx.y, bi = p / D.Hkv, h = p - bi * D.Hkv;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int c0 = meta[META_CHUNK_START];
+  const int ns = min(D.n_sink, c0), n_win = c0 - max(ns, c0 - D.window);
+  const int n_ret = max(meta[META_LIST_LEN] - ns - n_win, 0);
+  const int32_t* list = a.st.tok_list + (size_t)slot * D.list_cap + ns;
+  const int r16 = D.d * D.elt / 16, rows_per_pass = 256 / r16;
+  const int r_in = threadIdx.x / r16, piece = threadIdx.x - r_in * r16;
+  const size_t row_bytes = (size_t)D.d * D.elt;
+  const uint4* kh = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.k_host) + (size_t)slot * (size_t)D.max_tokens * row_bytes);
+  const uint4* vh = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.v_host) + (size_t)slot * (size_t)D.max_tokens * row_bytes);
+  uint4* kp = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.k_pool) + arena_off(D, slot) * D.elt) + (size_t)D.stage0 * r16;
+  uint4* vp = reinterpret_cast<uint4*>(reinterpret_cast<char*>(a.v_pool) + arena_off(D, slot) * D.elt) + (size_t)D.stage0 * r16;
+  for (int j = blockIdx.x * rows_per_pass + r_in; j < n_ret; j += gridDim.x * rows_per_pass) {
+    const int tok = list[j];
+    const uint4 kv = kh[(size_t)tok * r16 + piece];
+    const uint4 vv = vh[(size_t)tok * r16 + piece];
+    kp[(size_t)j * r16 + piece] = kv;
+    vp[(size_t)j * r16 + piece] = vv;
   }
 }
 
@@ -967,11 +1026,21 @@ hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
 
 hipError_t launch_copy_chunk(const Dims& D, void* k_arena, void* v_arena, const void* k_chunk,
                              const void* v_chunk, int layer, const BatchPos& bp, int seq_count,
-                             int n_new, hipStream_t s) {
-  CopyArgs a{D, k_arena, v_arena, k_chunk, v_chunk, layer, seq_count, n_new, bp};
+                             int n_new, void* k_host, void* v_host, hipStream_t s) {
+  if (D.offload && (!k_host || !v_host)) return hipErrorInvalidValue;
+  CopyArgs a{D, k_arena, v_arena, k_chunk, v_chunk, layer, seq_count, n_new, bp, k_host, v_host};
   const size_t n16 = (size_t)n_new * D.d * D.elt / 16;
   const int bx = (int)((n16 + 255) / 256 < 64 ? (n16 + 255) / 256 : 64);
   copy_chunk_kernel<<<dim3(bx > 0 ? bx : 1, seq_count * D.Hkv), 256, 0, s>>>(a);
+  return hipGetLastError();
+}
+
+hipError_t launch_fetch_retrieved(const Dims& D, const DevState& st, void* k_pool, void* v_pool, const void* k_host,
+                                  const void* v_host, int layer, const BatchPos& bp, int seq_count, hipStream_t s) {
+  if (!D.offload || !k_host || !v_host) return hipErrorInvalidValue;
+  FetchArgs a{D, st, k_pool, v_pool, k_host, v_host, layer, bp};
+  // 16 workgroups per (sequence, KV head): 128 or more in all keep enough 16-byte reads in flight on the host link
+  fetch_retrieved_kernel<<<dim3(16, seq_count * D.Hkv), 256, 0, s>>>(a);
   return hipGetLastError();
 }
 

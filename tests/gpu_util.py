@@ -12,7 +12,7 @@ from workloads import theta_default
 def make_pair(w, K, V, device, *, max_tokens, seg_map=O.MAP_LOGIT, theta=None, phi=0.0,
               max_spans_per_chunk=0, window=None, n_sink=None, k_max=None, budget_tokens=None,
               chunk_max=None, max_spans=0, rep_mode=0, lam=3.0, index_min=1, index_max=0, ratio_mode=0,
-              theta_quantile=0.0, unit_tokens=0):
+              theta_quantile=0.0, unit_tokens=0, kv_offload=0):
     """A library context with K/V resident in its arenas and the matching oracle stream."""
     theta = theta_default(w.head_dim) if theta is None else theta
     cfg = config_from_workload(w, max_tokens=max_tokens, theta=theta, phi=phi, seg_map=seg_map,
@@ -20,12 +20,15 @@ def make_pair(w, K, V, device, *, max_tokens, seg_map=O.MAP_LOGIT, theta=None, p
                                window=window, n_sink=n_sink, k_max=k_max, budget_tokens=budget_tokens,
                                chunk_max=chunk_max, max_spans=max_spans, rep_mode=rep_mode,
                                lam=lam, index_min=index_min, index_max=index_max, ratio_mode=ratio_mode,
-                               theta_quantile=theta_quantile, unit_tokens=unit_tokens)
+                               theta_quantile=theta_quantile, unit_tokens=unit_tokens, kv_offload=kv_offload)
     ctx = LtriContext(cfg, device)
     ka, va = ctx.arena_views()
     T = K.shape[1]
-    ka[0, 0, :, :T].copy_(K)
-    va[0, 0, :, :T].copy_(V)
+    if kv_offload:          # the arenas are host memory that the appends fill: poison them so that a row read before
+        ka.fill_(float("nan")); va.fill_(float("nan"))          # its append would show
+    else:
+        ka[0, 0, :, :T].copy_(K)
+        va[0, 0, :, :T].copy_(V)
     ocfg = O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, cfg.n_sink, cfg.window,
                           k_max=cfg.k_max, budget_tokens=cfg.budget_tokens, seg_map=seg_map,
                           theta=float(np.float32(theta)), phi=float(np.float32(phi)),

@@ -250,3 +250,33 @@ def test_attend_static_rules_in_dry_mode():
     ctx.retrieve(0, 0, 16, Q(16, 2048))
     ctx.attend_static(0, 0, 16, Q(16, 2048), None)   # long chunks keep no partial results
     ctx.close()
+
+
+def test_host_offloaded_kv_rules_in_dry_mode():
+    """kv_offload: the device pools are part of `state`, the flag is 0 or 1, and an append must bring the rows."""
+    lib = load_library()
+    w = CONFIGS["cfg3"]
+    sb0, sb1, cb = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    cfg = config_from_workload(w, theta=1.0)
+    assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb0), C.byref(cb)) == 0
+    cfg = config_from_workload(w, theta=1.0, kv_offload=1)
+    assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb1), C.byref(cb)) == 0
+    # per KV head: 4 initial rows + a ring of 8192 (>= 4096 + 2 x 2048) + 2048 mirror rows + the list capacity, K and V
+    rows = 4 + 8192 + 2048 + (((4 + 8192 + 4096 + 63) // 64) * 64 + 64)
+    assert sb1.value - sb0.value >= 2 * 8 * rows * 256
+    assert sb1.value - sb0.value <= 2 * 8 * rows * 256 + 8 * rows * 4 + 4096
+    cfg.kv_offload = 2
+    assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb1), C.byref(cb)) == -1
+    ctx = LtriContext(config_from_workload(CONFIGS["cfg1"], max_tokens=1024, theta=1.0, kv_offload=1), None, dry=True)
+    with pytest.raises(LtriError) as e:
+        ctx.append_chunk(0, 0, 1, 256)                   # rows "already in the arena": there is no device arena
+    assert e.value.status == -1
+    with pytest.raises(LtriError) as e:
+        ctx.step(0, 0, 1, None, None, _FakeQ(256))
+    assert e.value.status == -1
+    ctx.append_chunk(0, 0, 1, 256, k_chunk=_FakeQ(256), v_chunk=_FakeQ(256))
+    ctx.retrieve(0, 0, 1, _FakeQ(256))
+    ctx.attend(0, 0, 1, _FakeQ(256))
+    ctx.step(0, 0, 1, _FakeQ(256), _FakeQ(256), _FakeQ(256))
+    assert ctx.token_count(0, 0) == 512
+    ctx.close()

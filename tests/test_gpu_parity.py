@@ -28,14 +28,18 @@ def _stream_parity(w, seed, T, device, *, seg_map=O.MAP_LOGIT, theta=None, phi=0
     n_unstable = 0
     worst = 0.0
     sizes = chunk_sizes or [w.chunk] * (T // w.chunk)
+    offload = bool(kw.get("kv_offload", 0))
     for n in sizes:
         q = Q[c0:c0 + n].contiguous()
         qn = Qn[c0:c0 + n]
+        # host-offloaded KV: the rows come with the call (the device has no arena to find them in)
+        kc = K[:, c0:c0 + n].unsqueeze(0).contiguous() if offload else None
+        vc = V[:, c0:c0 + n].unsqueeze(0).contiguous() if offload else None
         if whole_step:      # the three steps in one call, on the library's own schedule
             lse = torch.empty((1, n, w.n_q_heads), dtype=torch.float32, device=device)
-            out = ctx.step(0, 0, 1, None, None, q, q_seg=q if use_q_seg else None, lse=lse)
+            out = ctx.step(0, 0, 1, kc, vc, q, q_seg=q if use_q_seg else None, lse=lse)
         else:
-            ctx.append_chunk(0, 0, 1, n, q_seg=q if use_q_seg else None)
+            ctx.append_chunk(0, 0, 1, n, k_chunk=kc, v_chunk=vc, q_seg=q if use_q_seg else None)
         st.append_chunk(n, q_seg=qn if use_q_seg else None)
         for h in range(w.n_kv_heads):
             if not spans_equal(ctx, st, h):
@@ -153,6 +157,31 @@ def test_cfg2_full_stream(gpu_device):
     del ctx, st
     worst, n_unstable, ctx, st = _stream_parity(w, 1, w.context, gpu_device, rows=rows, whole_step=True)
     assert n_unstable == 0
+
+
+def test_host_offloaded_kv(gpu_device):
+    """Host-offloaded KV (Sec. 3.4 first step: evicted keys and values live in CPU memory): the arenas are pinned
+    host memory filled by the appends, the device keeps initial tokens, a ring of the latest tokens and the rows
+    fetched for the current selection. Same bars against the oracle as the resident layout; config 2 at its stated
+    size through ltri_step, ragged chunks with one-token steps through the three calls (the ring wraps several
+    times in both), fp32; the host arenas end up holding the whole stream."""
+    w = CONFIGS["cfg2"]
+    rows = [0, 1, 31, 32, 63, 64, 500, 777, 1000, 1023]
+    worst, n_unstable, ctx, st = _stream_parity(w, 1, w.context, gpu_device, rows=rows, whole_step=True, kv_offload=1)
+    assert n_unstable == 0
+    K, V, _, _ = planted_stream(w, 1, device=str(gpu_device), context=w.context)
+    ka, va = ctx.arena_views()
+    assert ka.device.type == "cpu" and ka.is_pinned()
+    torch.cuda.synchronize()
+    assert torch.equal(ka[0, 0], K.cpu()) and torch.equal(va[0, 0], V.cpu())
+    del ctx, st
+    sizes = [1024, 300, 1, 65, 511, 1000, 64, 1, 1, 777, 1024, 1024, 2, 1024, 513, 1024, 1024, 90]
+    _stream_parity(w, 2, sum(sizes), gpu_device, chunk_sizes=sizes, window=700, budget_tokens=900,
+                   rows=range(0, 1024, 37), kv_offload=1)
+    _stream_parity(w, 2, sum(sizes), gpu_device, chunk_sizes=sizes, window=700, budget_tokens=900,
+                   rows=range(0, 1024, 37), kv_offload=1, whole_step=True, use_q_seg=True)
+    sizes1 = [256, 1, 100, 63, 65, 129, 256, 7, 200, 256, 256, 256, 31, 256]
+    _stream_parity(CONFIGS["cfg1"], 4, sum(sizes1), gpu_device, chunk_sizes=sizes1, window=100, k_max=5, kv_offload=1)
 
 
 def test_bf16_ragged_and_all_rows(gpu_device):
