@@ -327,15 +327,61 @@ def span_index_tokens(v: np.ndarray, a: int, b: int, count: int) -> np.ndarray:
     return np.asarray(sorted(order[:count]), np.int64)
 
 
+def share_block_budget(counts: Sequence[int], budget: int) -> List[int]:
+    """The paper's cap of M index vectors per memory block (Sec. 4, "Compression Ratio": up to M span index
+    vectors per block of 128 tokens), shared out over the block's spans. The paper does not say how; the
+    reading taken here: if the spans' own counts (Eq. 7, clamped) add up to more than M, the largest counts
+    are levelled down -- every span keeps min(count, level) for the highest level that fits, and what is left
+    of M goes, one vector each, to the earliest spans still below their own count. Every span keeps at least
+    one vector, so a block of more than M spans exceeds M by as many."""
+    counts = [int(c) for c in counts]
+    if budget <= 0 or sum(counts) <= budget:
+        return counts
+    level = 1
+    while sum(min(c, level + 1) for c in counts) <= budget:
+        level += 1
+    out = [min(c, level) for c in counts]
+    left = budget - sum(out)
+    for i, c in enumerate(counts):
+        if left <= 0:
+            break
+        if c > out[i]:
+            out[i] += 1
+            left -= 1
+    return out
+
+
+def dynamic_index_counts(A: np.ndarray, bounds: np.ndarray, lam: float, n_min: int, n_max: int, mode: int,
+                         block_max: int = 0, unit: int = 0, c0: int = 0) -> List[int]:
+    """Index vectors kept by every span of a chunk: Eq. 7 per span, then (block_max > 0) the budget of
+    block_max vectors per memory block, a block being the part of a unit of `unit` tokens (absolute
+    positions, the chunk starts at c0) that lies in this chunk; spans are cut at unit edges."""
+    counts = []
+    for s in range(len(bounds) - 1):
+        a, b = int(bounds[s]), int(bounds[s + 1])
+        counts.append(index_vector_count(b - a, span_area_ratio(A, a, b, mode), lam, n_min, n_max))
+    if block_max > 0:
+        if unit <= 0:
+            raise ValueError("a budget per block needs memory units")
+        blocks = {}
+        for s in range(len(bounds) - 1):
+            blocks.setdefault((c0 + int(bounds[s])) // unit, []).append(s)
+        for members in blocks.values():
+            shared = share_block_budget([counts[s] for s in members], block_max)
+            for s, n in zip(members, shared):
+                counts[s] = n
+    return counts
+
+
 def dynamic_index_tokens(A: np.ndarray, bounds: np.ndarray, lam: float, n_min: int, n_max: int,
-                         mode: int) -> List[np.ndarray]:
+                         mode: int, block_max: int = 0, unit: int = 0, c0: int = 0) -> List[np.ndarray]:
     """Index tokens (chunk-local, ascending) of every span of a chunk."""
     v = token_votes(A)
+    counts = dynamic_index_counts(A, bounds, lam, n_min, n_max, mode, block_max, unit, c0)
     out = []
     for s in range(len(bounds) - 1):
         a, b = int(bounds[s]), int(bounds[s + 1])
-        n = index_vector_count(b - a, span_area_ratio(A, a, b, mode), lam, n_min, n_max)
-        out.append(span_index_tokens(v, a, b, n))
+        out.append(span_index_tokens(v, a, b, counts[s]))
     return out
 
 
@@ -351,13 +397,14 @@ def index_vector_sums(X: np.ndarray, tokens: Sequence[np.ndarray], dtype: str) -
 
 
 def dynamic_index_is_stable(A: np.ndarray, bounds: np.ndarray, lam: float, n_min: int, n_max: int,
-                            mode: int, rel: float = 2.0 ** -18, draws: int = 2, seed: int = 0) -> bool:
+                            mode: int, rel: float = 2.0 ** -18, draws: int = 2, seed: int = 0,
+                            block_max: int = 0, unit: int = 0, c0: int = 0) -> bool:
     """Audit: are the index tokens the same when every map cell moves by a relative `rel`?"""
-    base = dynamic_index_tokens(A, bounds, lam, n_min, n_max, mode)
+    base = dynamic_index_tokens(A, bounds, lam, n_min, n_max, mode, block_max, unit, c0)
     rng = np.random.default_rng(seed)
     for _ in range(draws):
         p = rng.uniform(-rel, rel, size=A.shape)
-        t = dynamic_index_tokens(A * (1.0 + p), bounds, lam, n_min, n_max, mode)
+        t = dynamic_index_tokens(A * (1.0 + p), bounds, lam, n_min, n_max, mode, block_max, unit, c0)
         if any(len(x) != len(y) or np.any(x != y) for x, y in zip(base, t)):
             return False
     return True
@@ -502,6 +549,7 @@ class OracleConfig:
     n_min: int = 1             # fewest / most index vectors per span (0 = no upper limit)
     n_max: int = 0
     ratio_mode: int = RATIO_ROW
+    block_max: int = 0         # > 0: at most this many index vectors per memory block (the paper's M), needs unit_tokens
 
     @property
     def group(self) -> int:
@@ -554,7 +602,8 @@ class OracleStream:
                 if q_seg is not None:
                     Qg = np.transpose(np.asarray(q_seg, np.float64)[:, h * c.group:(h + 1) * c.group, :], (1, 0, 2))
                 A, _ = chunk_map(Kc, Qg, MAP_SOFTMAX)            # votes and areas come from the softmax map
-                toks = dynamic_index_tokens(A, b, c.lam, c.n_min, c.n_max, c.ratio_mode)
+                toks = dynamic_index_tokens(A, b, c.lam, c.n_min, c.n_max, c.ratio_mode, c.block_max,
+                                            c.unit_tokens, c0)
                 self.last_index_tokens[h] = toks
                 reps = index_vector_sums(Kc, toks, c.dtype)
             else:

@@ -559,6 +559,84 @@ def test_dynamic_index_on_planted_keys_and_in_the_stream():
         assert 1 <= len(tk) <= min(16, ln) and tk.min() >= a and tk.max() < a + ln and np.all(np.diff(tk) > 0)
 
 
+def test_block_budget_of_index_vectors_is_shared_max_min_fairly():
+    """The cap of M index vectors per memory block: brute force over every allocation on small tables. The rule
+    must keep the total at min(M, sum), never give a span more than its own count or less than one, and among
+    all such allocations pick the max-min fair one (the sorted counts are lexicographically largest), extras
+    going to the earliest spans."""
+    rng = np.random.default_rng(11)
+    for _ in range(300):
+        k = int(rng.integers(1, 6))
+        counts = [int(x) for x in rng.integers(1, 9, size=k)]
+        M = int(rng.integers(1, 16))
+        got = O.share_block_budget(counts, M)
+        assert len(got) == k and all(1 <= g <= c for g, c in zip(got, counts))
+        if sum(counts) <= M:
+            assert got == counts
+            continue
+        target = max(M, k)                                # a block of more spans than M keeps one vector each
+        assert sum(got) == target
+        best = None
+        for alloc in itertools.product(*[range(1, c + 1) for c in counts]):
+            if sum(alloc) != target:
+                continue
+            if best is None or sorted(alloc) > best[0]:
+                best = (sorted(alloc), [alloc])
+            elif sorted(alloc) == best[0]:
+                best[1].append(alloc)
+        assert sorted(got) == best[0]
+        # among the fair allocations, the larger shares sit at the earliest spans that can take them
+        assert tuple(got) == max(best[1])
+    assert O.share_block_budget([5, 1, 7, 2], 0) == [5, 1, 7, 2]
+    assert O.share_block_budget([5, 1, 7, 2], 12) == [5, 1, 4, 2]
+    assert O.share_block_budget([4, 4, 4], 7) == [3, 2, 2]
+    assert O.share_block_budget([9, 1, 9], 7) == [3, 1, 3]
+    assert O.share_block_budget([2, 2, 2, 2], 3) == [1, 1, 1, 1]
+
+
+def test_block_budget_in_the_chunk_and_in_the_stream():
+    """Counts of a chunk under a budget per block: blocks are the pieces of the memory units inside the chunk,
+    every block's total obeys the budget, spans in blocks under the budget keep Eq. 7's count, and the index
+    tokens are still each span's most voted ones."""
+    rng = np.random.default_rng(3)
+    L, d, unit, c0, M = 96, 8, 32, 16, 5
+    K = rng.standard_normal((L, d)) * 0.4
+    A, _ = O.chunk_map(K, None, O.MAP_SOFTMAX)
+    cuts = sorted({0, L} | {i for i in range(1, L) if (c0 + i) % unit == 0} | {5, 11, 23, 30, 41, 60, 70, 77, 90})
+    bounds = np.asarray(cuts, np.int64)
+    free = O.dynamic_index_counts(A, bounds, 0.5, 1, 0, O.RATIO_ROW)
+    capped = O.dynamic_index_counts(A, bounds, 0.5, 1, 0, O.RATIO_ROW, block_max=M, unit=unit, c0=c0)
+    blocks = {}
+    for s in range(len(bounds) - 1):
+        blocks.setdefault((c0 + int(bounds[s])) // unit, []).append(s)
+    assert len(blocks) == 4                               # units 0 (half), 1, 2, 3 (half) of the stream
+    hit = 0
+    for members in blocks.values():
+        f = [free[s] for s in members]
+        g = [capped[s] for s in members]
+        assert g == O.share_block_budget(f, M)
+        assert sum(g) == min(sum(f), max(M, len(members)))
+        hit += sum(f) > M
+    assert hit >= 2
+    toks = O.dynamic_index_tokens(A, bounds, 0.5, 1, 0, O.RATIO_ROW, block_max=M, unit=unit, c0=c0)
+    v = O.token_votes(A)
+    for s, t in enumerate(toks):
+        a, b = int(bounds[s]), int(bounds[s + 1])
+        assert len(t) == capped[s] and list(t) == sorted(sorted(range(a, b), key=lambda x: (-v[x], x))[:capped[s]])
+    with pytest.raises(ValueError):
+        O.dynamic_index_counts(A, bounds, 0.5, 1, 0, O.RATIO_ROW, block_max=M)
+    # in the stream: the configuration reaches dynamic_index_tokens with the chunk's absolute start
+    cfg = O.OracleConfig(1, 1, d, "f32", 2, 16, budget_tokens=40, theta=0.3, rep_mode=O.REP_DYNAMIC, lam=0.5,
+                         unit_tokens=unit, block_max=M)
+    V = rng.standard_normal((1, 16 + L, d))
+    st = O.OracleStream(cfg, np.concatenate([rng.standard_normal((16, d)) * 0.4, K])[None], V)
+    st.append_chunk(16)
+    st.append_chunk(L)
+    b = st.last_bounds[0]
+    want = O.dynamic_index_tokens(A, b, 0.5, 1, 0, O.RATIO_ROW, block_max=M, unit=unit, c0=16)
+    assert all(list(x) == list(y) for x, y in zip(st.last_index_tokens[0], want))
+
+
 def test_theta_as_a_percentile_of_the_map():
     """Nearest-rank percentile over the cells on and below the diagonal; closed form on constant keys,
     where row i of the softmax map holds i + 1 copies of 1 / (i + 1)."""
