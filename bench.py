@@ -354,6 +354,9 @@ def main():
     ap.add_argument("--unit-tokens", type=int, default=0,
                     help="retrieve whole memory units of this many tokens (Eq. 9 as written) instead of spans;\n"
                          "not the headline configuration")
+    ap.add_argument("--index-block-max", type=int, default=0,
+                    help="with --index-vectors dynamic and --unit-tokens U: at most this many index vectors per block of\n"
+                         "U tokens (the paper's M, 12 or 24), shared over the block's spans")
     ap.add_argument("--kv-offload", action="store_true",
                     help="host-offloaded KV (Sec. 3.4 first step): the arenas are pinned host memory, the device keeps\n"
                          "initial tokens, a ring of the latest tokens and the rows fetched for each selection; not the\n"
@@ -397,7 +400,7 @@ def main():
     cfg = config_from_workload(w, theta=theta, n_layers=1, n_seqs=1,
                                rep_mode=1 if args.index_vectors == "dynamic" else 0, lam=3.0,
                                theta_quantile=args.theta_quantile, unit_tokens=args.unit_tokens,
-                               kv_offload=int(args.kv_offload))
+                               kv_offload=int(args.kv_offload), index_block_max=args.index_block_max)
     ctx = LtriContext(cfg, dev)
     ka, va = ctx.arena_views()
     if not args.kv_offload:
@@ -410,6 +413,7 @@ def main():
     qs = [Q[c * L:(c + 1) * L] for c in range(n_chunks)]          # contiguous views
 
     list_lens = []          # per chunk: context-list length of every KV head
+    n_index_tokens = [0]    # dynamic index vectors: index tokens of all chunks and KV heads (first pass)
     SEPARATE = []           # events of the pass that times the attention kernel alone (--schedule step)
 
     # The segmentation of chunk c + 1 does not depend on the attention of chunk c; with --overlap it is
@@ -452,6 +456,8 @@ def main():
                 events.append((e0, e1))
             if record_lens:
                 list_lens.append([len(ctx.get_token_list(0, 0, h)) for h in range(w.n_kv_heads)])
+                if args.index_vectors == "dynamic":
+                    n_index_tokens[0] += sum(len(ctx.get_index_tokens(0, 0, h, L)) for h in range(w.n_kv_heads))
             if nxt:
                 if overlap:
                     side.wait_event(ev_r[c])
@@ -608,6 +614,23 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(w, K, V, Q, bounds, theta)
 
+    index_footprint = None
+    if args.index_vectors == "dynamic":
+        # What the index of the evicted tokens takes (Sec. 4, "Compression Ratio" and the table of occupied GPU
+        # memory): the paper keeps every index vector (up to M per block of 128 tokens); this build keeps their sum,
+        # one vector per span (Eq. 8 is bilinear). Bytes per token and KV head, next to the paper's figure.
+        blk = args.unit_tokens or 128
+        elt = 2 if w.dtype == "bf16" else 4
+        per_block = n_index_tokens[0] / (w.n_kv_heads * T / blk)
+        spans_per_block = sum(n_spans) / (w.n_kv_heads * T / blk)
+        index_footprint = {
+            "block_tokens": blk, "index_block_max": args.index_block_max or None,
+            "index_vectors_per_block": round(per_block, 2), "spans_per_block": round(spans_per_block, 2),
+            "bytes_per_token_and_head_if_every_index_vector_were_stored": round(per_block * w.head_dim * elt / blk, 2),
+            "bytes_per_token_and_head_stored_here": round(spans_per_block * w.head_dim * elt / blk, 2),
+            "paper": "0.027 GiB for the index of 100K tokens (M = 12, lambda = 3, 16-bit, 32 layers with one retrieval "
+                     "head each; window 4096 and 128 initial tokens stay out): 9.5 bytes per evicted token and head, "
+                     "i.e. 4.7 index vectors per block of 128 tokens on the real model's maps"}
     host_link = None
     if args.kv_offload:
         elt = 2 if w.dtype == "bf16" else 4
@@ -639,7 +662,7 @@ def main():
                    "schedule": "append(c+1) on a second stream next to attend(c)" if overlap else
                    ("ltri_step per chunk: attention over initial | window | chunk on a second stream beside "
                     "steps 1 and 2, retrieved tokens after, merged" if step_schedule else "three calls per chunk, serial")},
-        "roofline": roofline, "gather": gather, "cpu_baseline": cpu, "host_link": host_link,
+        "roofline": roofline, "gather": gather, "cpu_baseline": cpu, "host_link": host_link, "index_footprint": index_footprint,
         "breakdown_ms": {"attend": round(tot_ms / args.steps, 3), "rest_of_step": round(other_ms, 3),
                          "note": ("attend = sum of the two attention launches of every step; the first one overlaps the "
                                   "small kernels of steps 1 and 2" if step_schedule else "serial calls"),

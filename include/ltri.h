@@ -122,6 +122,13 @@ typedef struct {
    * Results are those of the resident layout bit for bit. The chunk's rows must be passed to the append
    * (k_chunk / v_chunk non-NULL). 0: everything resident in the device arenas. */
   int32_t kv_offload;
+  /* > 0, with LTRI_REP_DYNAMIC and unit_tokens > 0: the paper's M (Sec. 4, "Compression Ratio": up to M span
+   * index vectors per block of 128 tokens; 12 or 24 in its configurations). A block is the part of a memory unit
+   * that lies in the appended chunk. If the Eq. 7 counts of a block's spans (after index_min / index_max) add up
+   * to more than M, the largest are levelled down: every span keeps min(count, level) for the highest level that
+   * fits, and what is left of M goes, one vector each, to the earliest spans still below their own count; no
+   * span drops below one. 0: no block budget. EINVAL without dynamic index vectors or without units. */
+  int32_t index_block_max;
 } ltri_config;
 
 /* Sizes (bytes) of the two device buffers a context needs: `state` holds the index

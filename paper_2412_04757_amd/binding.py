@@ -53,6 +53,7 @@ class LtriConfig(C.Structure):
         ("max_spans_per_chunk", C.c_int32), ("rep_mode", C.c_int32), ("max_spans", C.c_int32),
         ("lam", C.c_float), ("index_min", C.c_int32), ("index_max", C.c_int32), ("ratio_mode", C.c_int32),
         ("theta_quantile", C.c_float), ("unit_tokens", C.c_int32), ("kv_offload", C.c_int32),
+        ("index_block_max", C.c_int32),
     ]
 
 
@@ -127,7 +128,7 @@ def config_from_workload(w, max_tokens: Optional[int] = None, theta: float = 0.0
                          budget_tokens: Optional[int] = None, chunk_max: Optional[int] = None,
                          rep_mode: int = REP_MEAN, lam: float = 3.0, index_min: int = 1, index_max: int = 0,
                          ratio_mode: int = RATIO_ROW, theta_quantile: float = 0.0,
-                         unit_tokens: int = 0, kv_offload: int = 0) -> LtriConfig:
+                         unit_tokens: int = 0, kv_offload: int = 0, index_block_max: int = 0) -> LtriConfig:
     return LtriConfig(
         n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim,
         dtype=LTRI_F32 if w.dtype == "f32" else LTRI_BF16,
@@ -141,7 +142,8 @@ def config_from_workload(w, max_tokens: Optional[int] = None, theta: float = 0.0
         budget_tokens=w.budget_tokens if budget_tokens is None else budget_tokens,
         seg_map=seg_map, theta=theta, phi=phi, max_spans_per_chunk=max_spans_per_chunk,
         rep_mode=rep_mode, max_spans=max_spans, lam=lam, index_min=index_min, index_max=index_max,
-        ratio_mode=ratio_mode, theta_quantile=theta_quantile, unit_tokens=unit_tokens, kv_offload=kv_offload)
+        ratio_mode=ratio_mode, theta_quantile=theta_quantile, unit_tokens=unit_tokens, kv_offload=kv_offload,
+        index_block_max=index_block_max)
 
 
 def _ptr(t: Optional[torch.Tensor], dtype: Optional[torch.dtype] = None) -> Optional[int]:

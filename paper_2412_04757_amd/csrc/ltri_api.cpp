@@ -90,6 +90,9 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   D.ratio_mode = c.ratio_mode;
   D.theta_quantile = (double)c.theta_quantile;
   D.unit = c.unit_tokens;
+  if (c.index_block_max < 0) return LTRI_EINVAL;
+  if (c.index_block_max > 0 && (c.rep_mode != LTRI_REP_DYNAMIC || c.unit_tokens <= 0)) return LTRI_EINVAL;
+  D.index_block_max = c.index_block_max;
   if (c.kv_offload != 0 && c.kv_offload != 1) return LTRI_EINVAL;
   D.offload = c.kv_offload;
   if (c.max_spans > 65536) return LTRI_EINVAL;

@@ -90,6 +90,7 @@ struct Dims {
   int max_spans, sel_cap, list_cap;
   int elt;  // bytes per element
   int rep_mode, index_min, index_max, ratio_mode;   // dynamic index vectors (Sec. 3.3.2)
+  int index_block_max;                              // > 0: at most this many index vectors per memory block, shared over its spans
   double lambda;
   double theta_quantile;                            // > 0: theta is this percentile of the chunk's map
   int unit;                                         // > 0: retrieval by memory units of this many tokens (Eq. 9)

@@ -781,7 +781,8 @@ __global__ __launch_bounds__(1024) void dyn_span_kernel(SegArgs a) {
   __shared__ uint16_t spos[SEG_MAX_L];
   __shared__ uint32_t smask[IDX_MASK_WORDS + 1];
   __shared__ double red[3][16];
-  __shared__ int s_count;
+  __shared__ int s_count, s_mlo, s_mhi;
+  __shared__ int s_cnt[SEG_MAX_L];                     // Eq. 7 counts of the spans of one memory block
   const Dims& D = a.D;
   const int p = blockIdx.y, sl = p / D.Hkv, h = p - sl * D.Hkv, bi = a.batch_off + sl;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
@@ -817,6 +818,67 @@ __global__ __launch_bounds__(1024) void dyn_span_kernel(SegArgs a) {
       n = max(n, D.index_min);
       if (D.index_max > 0) n = min(n, D.index_max);
       s_count = max(1, min(n, len));
+    }
+    if (D.index_block_max > 0) {
+      // A budget of index vectors per memory block (the piece of a unit inside this chunk), shared over the
+      // block's spans: every span of the block gets its own count by one and the same routine (one wavefront
+      // per span, so that all workgroups of a block agree to the bit), then the largest counts are levelled
+      // down to the highest level that fits and what is left goes to the earliest spans still short.
+      __syncthreads();
+      if (tid == 0) {
+        const int blk = start / D.unit;
+        int lo = q, hi = q;
+        while (lo > 0 && a.st.span_start[(size_t)slot * D.max_spans + first + lo - 1] / D.unit == blk) --lo;
+        while (hi + 1 < nsp && a.st.span_start[(size_t)slot * D.max_spans + first + hi + 1] / D.unit == blk) ++hi;
+        s_mlo = lo; s_mhi = hi;
+      }
+      __syncthreads();
+      const int mlo = s_mlo, mhi = s_mhi;
+      for (int m = mlo + wave; m <= mhi; m += 16) {
+        const int ms = a.st.span_start[(size_t)slot * D.max_spans + first + m] - c0;
+        const int ml = a.st.span_len[(size_t)slot * D.max_spans + first + m];
+        double v0 = 0.0, v1 = 0.0, v2 = 0.0;
+        for (int t = lane; t < ml; t += 64) { v0 += dyn[ms + t]; v1 += dyn[a.Lp + ms + t]; v2 += dyn[2 * a.Lp + ms + t]; }
+        v0 = wave_sum_f64(v0); v1 = wave_sum_f64(v1); v2 = wave_sum_f64(v2);
+        if (lane == 0) {
+          const double den = D.ratio_mode == LTRI_RATIO_ROW ? v2 : D.ratio_mode == LTRI_RATIO_COL ? v0 : v2 + v0 - v1;
+          const double r_v = 1.0 / exp(D.lambda * (1.0 - v1 / den));
+          int n = (int)rint((double)ml * r_v);
+          n = max(n, D.index_min);
+          if (D.index_max > 0) n = min(n, D.index_max);
+          s_cnt[m - mlo] = max(1, min(n, ml));
+        }
+      }
+      __syncthreads();
+      if (tid == 0) {
+        const int nm = mhi - mlo + 1, budget = D.index_block_max;
+        long long total = 0;
+        int cmax = 1;
+        for (int m = 0; m < nm; ++m) { total += s_cnt[m]; cmax = max(cmax, s_cnt[m]); }
+        int mine = s_cnt[q - mlo];
+        if (total > budget) {
+          int lvl_lo = 1, lvl_hi = cmax;                  // the largest level whose levelled total fits (1 if none does)
+          while (lvl_lo < lvl_hi) {
+            const int mid = (lvl_lo + lvl_hi + 1) >> 1;
+            long long sum = 0;
+            for (int m = 0; m < nm; ++m) sum += min(s_cnt[m], mid);
+            if (sum <= budget) lvl_lo = mid; else lvl_hi = mid - 1;
+          }
+          const int level = lvl_lo;
+          long long sum = 0;
+          for (int m = 0; m < nm; ++m) sum += min(s_cnt[m], level);
+          long long left = budget - sum;
+          int share = min(mine, level);
+          for (int m = 0; m < nm && left > 0; ++m) {
+            if (s_cnt[m] > level) {
+              if (m == q - mlo) ++share;
+              --left;
+            }
+          }
+          mine = share;
+        }
+        s_count = mine;
+      }
     }
     // tokens by votes: bitonic network over (key, position), ascending
     int npow = 2;

@@ -80,6 +80,11 @@ def test_workspace_sizes_and_bad_configs():
     assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == 0
     cfg.theta_quantile = 1.5
     assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == -1
+    # a budget of index vectors per block needs dynamic index vectors and memory units
+    for kw, ok in ((dict(rep_mode=1, unit_tokens=128, index_block_max=12), True), (dict(rep_mode=1, index_block_max=12), False),
+                   (dict(unit_tokens=128, index_block_max=12), False), (dict(rep_mode=1, unit_tokens=128, index_block_max=-1), False)):
+        cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0, **kw)
+        assert (lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == 0) == ok, kw
     cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0, lam=-5.0, ratio_mode=9)    # ignored with mean keys
     assert lib.ltri_workspace_bytes(C.byref(cfg), C.byref(sb), C.byref(cb)) == 0
     cfg = config_from_workload(CONFIGS["cfg1"], theta=1.0)

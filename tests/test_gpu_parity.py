@@ -512,7 +512,8 @@ def _dynamic_stream(gpu_device, w, seed, T, L, q_seg, key_scale=0.35, given_span
                     Qg = np.transpose(qn[:, h * g:(h + 1) * g, :], (1, 0, 2))
                 A, _ = O.chunk_map(Kn[h, c0:c0 + n], Qg, O.MAP_SOFTMAX)
                 assert not O.dynamic_index_is_stable(A, st.last_bounds[h], st.cfg.lam, st.cfg.n_min, st.cfg.n_max,
-                                                     st.cfg.ratio_mode, rel=2.0 ** -16), f"chunk at {c0}, head {h}"
+                                                     st.cfg.ratio_mode, rel=2.0 ** -16, block_max=st.cfg.block_max,
+                                                     unit=st.cfg.unit_tokens, c0=c0), f"chunk at {c0}, head {h}"
                 stable = False
                 n_unstable += 1
             n_audited += 1
@@ -560,6 +561,30 @@ def test_dynamic_index_vectors_bf16(gpu_device):
     _dynamic_stream(gpu_device, w, 6, 1024, 512, True, decode_steps=3, lam=3.0, ratio_mode=0)
     _, n_partial = _dynamic_stream(gpu_device, w, 7, 1024, 512, False, given_spans=True, lam=3.0, ratio_mode=0)
     assert n_partial >= 6
+
+
+def test_index_vector_budget_per_block(gpu_device):
+    """The paper's M: at most M index vectors per memory block, shared over the block's spans (levelling of the
+    largest Eq. 7 counts). Units of 128 and of 64 tokens with chunks of several units, ragged chunks whose edges
+    cut units in two, bf16 and fp32; index tokens and stored vectors against the oracle on every chunk, and the
+    budget must actually bind in a good share of the blocks."""
+    w = Workload("mini-budget", 8, 2, 128, "bf16", 2048, 512, 4, 128, 0, 300, "uniform", 16, 96)
+    for unit, M, sizes in ((128, 12, None), (64, 5, [512, 200, 333, 512, 491])):
+        T = sum(sizes) if sizes else 2048
+        n_aud, _ = _dynamic_stream(gpu_device, w, 21, T, 512, False, chunk_sizes=sizes, lam=1.0, ratio_mode=0,
+                                   unit_tokens=unit, index_block_max=M, k_max=4, budget_tokens=0)
+        assert n_aud > 0
+    # how often the budget binds, from the oracle's own counts on one chunk of that stream
+    K, _, _, _ = planted_stream(w, 21, device="cpu", context=2048)
+    Kc = (K.float() * 0.35).to(K.dtype)[0, :512].double().numpy()
+    A, _ = O.chunk_map(Kc, None, O.MAP_SOFTMAX)
+    b = O.segment_chunk(Kc, None, O.MAP_LOGIT, float(np.float32(theta_default(128) * 0.35 ** 2)), 0.0, unit=128, c0=0)
+    free = O.dynamic_index_counts(A, b, 1.0, 1, 0, O.RATIO_ROW)
+    capped = O.dynamic_index_counts(A, b, 1.0, 1, 0, O.RATIO_ROW, block_max=12, unit=128, c0=0)
+    assert sum(free) > sum(capped) and sum(capped) <= 4 * 12
+    w1 = Workload("mini-budget-f32", 4, 1, 64, "f32", 1024, 256, 4, 64, 0, 100, "uniform", 8, 48)
+    _dynamic_stream(gpu_device, w1, 22, 1024 - 37, 256, True, lam=1.0, ratio_mode=2, unit_tokens=128, index_block_max=9,
+                    index_min=2, k_max=3, budget_tokens=0)
 
 
 def test_dynamic_index_vectors_fp32(gpu_device):
@@ -685,6 +710,11 @@ def test_paper_literal_configuration(gpu_device):
     assert len(st.sel[0]) == 3 and len(st.starts[0]) > 32
     _, n_unstable, ctx, st = _stream_parity(w, 6, 1024, gpu_device, use_q_seg=True, rows=range(0, 128, 9), **kw)
     assert n_unstable == 0
+    # and with the paper's budget of M = 12 index vectors per block in place of the cap per span
+    kw.update(index_max=0, index_block_max=12)
+    _, n_unstable, ctx, st = _stream_parity(w, 5, 2048, gpu_device, rows=range(0, 128, 9), **kw)
+    assert n_unstable == 0
+    assert sum(len(t) for t in st.last_index_tokens[0]) <= 12
 
 
 def test_collaborative_voting_across_layers(gpu_device):
