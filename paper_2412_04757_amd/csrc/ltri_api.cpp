@@ -405,7 +405,7 @@ static void append_commit(ltri_ctx* c, int layer, int seq_begin, int seq_count, 
 // is recorded on the context's stream behind the last kernel that fills the chip; what follows it there
 // are kernels of a few workgroups each.
 static int32_t append_spans(ltri_ctx* c, int layer, const BatchPos& bp, int seq_count, const void* q_seg, int n_new,
-                            hipEvent_t fork) {
+                            hipEvent_t fork, bool rep_keys_later = false) {
   int32_t r;
   if (n_new == 1) {
     r = check_hip(c, launch_append_single(c->D, c->ds, c->k_arena, layer, bp, seq_count, c->stream),
@@ -428,7 +428,7 @@ static int32_t append_spans(ltri_ctx* c, int layer, const BatchPos& bp, int seq_
       if (r != LTRI_OK) return r;
     }
   }
-  if (c->D.rep_mode == LTRI_REP_MEAN) {
+  if (c->D.rep_mode == LTRI_REP_MEAN && !rep_keys_later) {   // later: step 2's first launch stores them as well
     r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, seq_count, n_new, c->stream),
                   "representative keys");
     if (r != LTRI_OK) return r;
@@ -513,8 +513,8 @@ static int32_t check_query_chunk(ltri_ctx* c, int layer, int seq_begin, int seq_
   return LTRI_OK;
 }
 
-int32_t ltri_retrieve(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q,
-                      int32_t n_q, int32_t* sel_ids, int32_t* sel_cnt) {
+static int32_t retrieve_impl(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q,
+                             int32_t n_q, int32_t* sel_ids, int32_t* sel_cnt, bool store_rep_keys) {
   BatchPos bp;
   memset(&bp, 0, sizeof bp);
   int32_t r = check_query_chunk(c, layer, seq_begin, seq_count, q, n_q, bp);
@@ -523,7 +523,7 @@ int32_t ltri_retrieve(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq
     long long bound = 0;
     for (int s = 0; s < seq_count; ++s) bound = std::max(bound, c->span_bound[ls_index(c, layer, seq_begin + s)]);
     r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound, sel_ids,
-                                     sel_cnt, nullptr, nullptr, c->stream), "retrieve");
+                                     sel_cnt, nullptr, nullptr, store_rep_keys ? c->k_arena : nullptr, c->stream), "retrieve");
     if (r != LTRI_OK) return r;
     r = fetch_retrieved(c, layer, bp, seq_count);
     if (r != LTRI_OK) return r;
@@ -533,6 +533,11 @@ int32_t ltri_retrieve(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq
     c->ever_sel[ls_index(c, layer, seq_begin + s)] = 0xFFFFFFFFu;
   }
   return LTRI_OK;
+}
+
+int32_t ltri_retrieve(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q,
+                      int32_t n_q, int32_t* sel_ids, int32_t* sel_cnt) {
+  return retrieve_impl(c, layer, seq_begin, seq_count, q, n_q, sel_ids, sel_cnt, false);
 }
 
 int32_t ltri_retrieve_collaborative(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q,
@@ -567,7 +572,7 @@ int32_t ltri_retrieve_collaborative(ltri_ctx* c, int32_t layer, int32_t seq_begi
     long long bound = 0;
     for (int s = 0; s < seq_count; ++s) bound = std::max(bound, c->span_bound[ls_index(c, layer, seq_begin + s)]);
     r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound,
-                                     sel_ids, sel_cnt, &v, nullptr, c->stream), "collaborative retrieve");
+                                     sel_ids, sel_cnt, &v, nullptr, nullptr, c->stream), "collaborative retrieve");
     if (r != LTRI_OK) return r;
     r = fetch_retrieved(c, layer, bp, seq_count);
     if (r != LTRI_OK) return r;
@@ -742,7 +747,7 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
     if (retrieve_is_one_launch(c->D, 1, (int)bound)) {
       append_commit(c, layer, seq_begin, seq_count, 1);
       r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, 1, (int)bound,
-                                       nullptr, nullptr, nullptr, c->k_arena, c->stream), "append and retrieve (one token)");
+                                       nullptr, nullptr, nullptr, c->k_arena, nullptr, c->stream), "append and retrieve (one token)");
       if (r != LTRI_OK) return r;
       r = fetch_retrieved(c, layer, bp, seq_count);
       if (r != LTRI_OK) return r;
@@ -772,7 +777,8 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   if (r != LTRI_OK) return r;
   float* lse_a = c->dc.att_lse2;
   // Context's stream: the kernels of step 1 that fill the chip, the fork, then the small kernels of steps 1 and 2.
-  r = append_spans(c, layer, bp, seq_count, q_seg, n_new, c->ev_fork);
+  const bool keys_with_step2 = retrieve_stores_rep_keys(c->D, n_new);
+  r = append_spans(c, layer, bp, seq_count, q_seg, n_new, c->ev_fork, keys_with_step2);
   if (r != LTRI_OK) return r;
   append_commit(c, layer, seq_begin, seq_count, n_new);
   // Second stream, behind the fork: attention over initial | window | chunk.
@@ -787,7 +793,7 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   if (r == LTRI_OK) r = timing_mark(c, c->side);
   if (r == LTRI_OK) r = check_hip(c, hipEventRecord(c->ev_join, c->side), "join");
   if (r != LTRI_OK) return r;
-  r = ltri_retrieve(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr);
+  r = retrieve_impl(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr, keys_with_step2);
   // Context's stream again: the join, then the retrieved tokens, whose launch folds the first part's result into
   // its own. Join even after an error, so that the context's stream never runs ahead of the second stream's writes
   // to out.

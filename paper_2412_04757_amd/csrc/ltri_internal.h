@@ -156,7 +156,10 @@ hipError_t launch_rep_keys(const Dims& D, const DevState& st, const void* k_aren
 hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,
                            const void* q, int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
                            int32_t* sel_ids_out, int32_t* sel_cnt_out, const VoteArgs* votes, const void* append_k_arena,
-                           hipStream_t s);   // append_k_arena (or NULL): a one-token chunk's step 1 runs in the same launch
+                           const void* rep_k_arena, hipStream_t s);
+// append_k_arena (or NULL): a one-token chunk's step 1 runs in the same launch; rep_k_arena (or NULL): the launch of
+// the query-span pieces also stores the chunk's mean keys (only where retrieve_stores_rep_keys says so)
+bool retrieve_stores_rep_keys(const Dims& D, int n_q);
 bool retrieve_is_one_launch(const Dims& D, int n_q, int span_bound);   // step 2 of a one-token chunk as a single kernel
 hipError_t launch_persist_list(const Dims& D, const DevState& st, int layer, const BatchPos& bp, int seq_count,
                                hipStream_t s);

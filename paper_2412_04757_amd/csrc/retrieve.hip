@@ -18,6 +18,7 @@ struct RetArgs {
   int batch_off; int units_cap;          // two-stage query representatives (long chunks)
   int32_t* sel_ids_out; int32_t* sel_cnt_out;
   const void* k_arena; int append_first;  // one-token chunk: step 1 (the token becomes a span of its own) in the same launch
+  const void* rep_k_arena;                // not NULL: the launch of the query-span pieces also stores the chunk's mean keys
   BatchPos bp;
 };
 
@@ -100,6 +101,8 @@ __device__ __forceinline__ int qrep_first_unit(const int32_t* slen, int q) {
   return base;
 }
 
+constexpr int QREP_GRID_X = 64;            // workgroups per problem that walk the pieces
+
 template <int DT>
 __global__ __launch_bounds__(1024) void qrep_partial_kernel(RetArgs a) {
   typedef typename Elt<DT>::type T;
@@ -110,11 +113,25 @@ __global__ __launch_bounds__(1024) void qrep_partial_kernel(RetArgs a) {
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int first = meta[META_CHUNK_FIRST], nsp = meta[META_CHUNK_NSP], c0 = meta[META_CHUNK_START];
   const int d = D.d;
+  if (blockIdx.x >= QREP_GRID_X) {
+    // The workgroups beyond the pieces' own: the mean keys of the chunk's spans (Sec. 3.3.1), which nothing in
+    // this step reads (the chunk's spans lie inside the window), so they ride along instead of taking a launch.
+    if (!a.rep_k_arena) return;
+    const T* Kb = reinterpret_cast<const T*>(a.rep_k_arena) + arena_off(D, slot);
+    for (int q = blockIdx.x - QREP_GRID_X; q < nsp; q += gridDim.x - QREP_GRID_X) {
+      const int sid = first + q;
+      const int start = a.st.span_start[(size_t)slot * D.max_spans + sid];
+      const int len = a.st.span_len[(size_t)slot * D.max_spans + sid];
+      T* rep = reinterpret_cast<T*>(a.st.krep) + ((size_t)slot * D.max_spans + sid) * d;
+      span_mean_block<DT>(Kb + (size_t)chunk_tok_row(D, c0, start) * d, (size_t)d, 1, len, d, rep, part);
+    }
+    return;
+  }
   const T* Qb = reinterpret_cast<const T*>(a.q) + (size_t)bi * a.n_q * D.Hq * d + (size_t)h * D.G * d;
   const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans + first;
   const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans + first;
   double* psum = a.sc.qpart + (size_t)p * a.units_cap * d;
-  for (int u = blockIdx.x; u < a.units_cap; u += gridDim.x) {
+  for (int u = blockIdx.x; u < a.units_cap; u += QREP_GRID_X) {
     int q, t0, nt;
     if (!qrep_unit(slen, nsp, u, q, t0, nt)) break;            // uniform over the block
     const int start = sstart[q] - c0 + t0;                      // chunk-local
@@ -217,6 +234,61 @@ __global__ __launch_bounds__(256) void score_kernel(RetArgs a) {
     }
   }
   if (i < n && part == 0) scores[i] = best;
+}
+
+// ---- scores on the matrix cores, in fp64 ----
+// best[v] = max_j Q^R_j . K^R_i for the four spans i = i0 + 4 v + lane / 16 of a tile of 16 spans, by one
+// wavefront: D (16 spans x 16 query spans) = A (16 x d) B (d x 16) as d / 4 products v_mfma_f64_16x16x4f64.
+// The stored values are converted to fp64 exactly and their products are exact in fp64, so the scores differ
+// from any other fp64 evaluation only by the order of the 128 additions (Eq. 8; the selection is compared at
+// 1e-12). A lane (r = lane % 16, g = lane / 16) feeds row r of A (span i0 + r) and column r of B (query span
+// j0 + r): both fetch the 16-byte pieces g, g + 4, ... of their row, and product step (t, e) takes element e of
+// piece g + 4 t from either side, i.e. the same k on both sides in a permuted order. Rows past n and columns
+// past nqs read a valid row and are masked. All 64 lanes must call it together.
+typedef double f64x4_t __attribute__((ext_vector_type(4)));
+template <int DT>
+__device__ __forceinline__ void score_tile_f64(const typename Elt<DT>::type* krep, int n, int i0,
+                                               const typename Elt<DT>::type* qrep, int nqs, int d, double (&best)[4]) {
+  typedef typename Elt<DT>::type T;
+  constexpr int N = 16 / (int)sizeof(T);                // elements per 16-byte piece
+  constexpr int TMAX = 128 * (int)sizeof(T) / 16 / 4;   // pieces per lane at d = 128
+  const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+  const int nt = d / N / 4;                             // pieces per lane
+  const uint4* arow = reinterpret_cast<const uint4*>(krep + (size_t)max(min(i0 + r, n - 1), 0) * d);
+  uint4 av[TMAX];
+#pragma unroll
+  for (int t = 0; t < TMAX; ++t) av[t] = t < nt ? arow[g + 4 * t] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+  for (int v = 0; v < 4; ++v) best[v] = -INFINITY;
+  auto elem = [](const uint4& u, int e) -> double {
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+    if constexpr (DT == LTRI_BF16) return (double)__uint_as_float((e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16));
+    else return (double)__uint_as_float(w[e]);
+  };
+  for (int j0 = 0; j0 < nqs; j0 += 16) {
+    const uint4* brow = reinterpret_cast<const uint4*>(qrep + (size_t)min(j0 + r, nqs - 1) * d);
+    uint4 bv[TMAX];
+#pragma unroll
+    for (int t = 0; t < TMAX; ++t) bv[t] = t < nt ? brow[g + 4 * t] : make_uint4(0u, 0u, 0u, 0u);
+    f64x4_t acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int t = 0; t < TMAX; ++t) {
+      if (t < nt) {
+#pragma unroll
+        for (int e = 0; e < N; ++e) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(elem(av[t], e), elem(bv[t], e), acc, 0, 0, 0);
+      }
+    }
+    // acc[v] = score of span i0 + 4 v + g against query span j0 + r: maximum over the 16 lanes of a group
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      double m = (j0 + r < nqs) ? acc[v] : -INFINITY;
+      m = fmax(m, __shfl_xor(m, 1, 64));
+      m = fmax(m, __shfl_xor(m, 2, 64));
+      m = fmax(m, __shfl_xor(m, 4, 64));
+      m = fmax(m, __shfl_xor(m, 8, 64));
+      best[v] = fmax(best[v], m);
+    }
+  }
 }
 
 // Evicted part [a, b) of a stored span for a chunk starting at c0.
@@ -672,6 +744,80 @@ __global__ __launch_bounds__(1024) void retrieve_one_token_kernel(RetArgs a, int
   emit_selection(D, a.st, slot, selmask, n, ids_out, cnt_out);
 }
 
+// ---- step 2 of a long chunk after the pieces of its query spans are summed, in one launch: Q^R of every query
+//      span, the scores of all stored spans (Eq. 8, maximum over the query spans as in Eq. 9), the budgeted
+//      selection by sorting and the lists. One workgroup per (sequence, KV head); head_dim 128, spans
+//      retrieved (not units), at most RT1_MAX_SPANS stored spans (the launcher checks). ----
+template <int DT>
+__global__ __launch_bounds__(1024) void retrieve_chunk_kernel(RetArgs a, int bound) {
+  typedef typename Elt<DT>::type T;
+  extern __shared__ __attribute__((aligned(16))) unsigned char rt1_lds[];
+  __shared__ uint32_t selmask[RT1_MAX_SPANS / 32 + 2];
+  __shared__ long long wave_tot[16];
+  const Dims& D = a.D;
+  const int pl = blockIdx.x, bi = a.batch_off + pl / D.Hkv, h = pl % D.Hkv, pg = bi * D.Hkv + h;
+  const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
+  const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
+  const int d = 128, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = min(meta[META_N_SPANS], bound), c0 = meta[META_CHUNK_START];
+  const int first = meta[META_CHUNK_FIRST], nqs = meta[META_CHUNK_NSP];
+  // Q^R of the chunk's spans: the pieces of a span are added in ascending order, one wavefront per span
+  T* qrep = reinterpret_cast<T*>(a.sc.qrep) + (size_t)pg * a.Lp * d;
+  {
+    const int32_t* slen_c = a.st.span_len + (size_t)slot * D.max_spans + first;
+    const double* psum = a.sc.qpart + (size_t)pl * a.units_cap * d;
+    const bool summed = index_mask(D, a.st, slot, meta) != nullptr;
+    for (int q = wave; q < nqs; q += 16) {
+      const int u0 = qrep_first_unit(slen_c, q);
+      const int len = slen_c[q];
+      const int parts = (len + QREP_PIECE - 1) / QREP_PIECE;
+      for (int c = lane; c < d; c += 64) {
+        double s = 0.0;
+        for (int k = 0; k < parts; ++k) s += psum[(size_t)(u0 + k) * d + c];
+        qrep[(size_t)q * d + c] = Elt<DT>::from_f64(summed ? s : s / (double)len);
+      }
+    }
+  }
+  const int npow = rt1_pow2(n);
+  uint64_t* skey = reinterpret_cast<uint64_t*>(rt1_lds);
+  uint32_t* sidx = reinterpret_cast<uint32_t*>(rt1_lds + (size_t)rt1_pow2(bound) * 8);
+  int* clip = reinterpret_cast<int*>(rt1_lds + (size_t)rt1_pow2(bound) * 12);
+  const T* krep = reinterpret_cast<const T*>(a.st.krep) + (size_t)slot * D.max_spans * d;
+  double* scores = a.st.scores + (size_t)slot * D.max_spans;
+  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
+  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
+  for (int w = tid; w < (n + 31) / 32 + 2; w += blockDim.x) selmask[w] = 0u;
+  __threadfence_block();
+  __syncthreads();                                      // the query representatives are in place for the whole workgroup
+  for (int i = n + tid; i < npow; i += blockDim.x) { skey[i] = ~0ull; sidx[i] = RT1_PAD; }    // padding of the sort
+  for (int i0 = 16 * wave; i0 < n; i0 += 256) {         // a tile of 16 spans per wavefront
+    double best[4];
+    score_tile_f64<DT>(krep, n, i0, qrep, nqs, d, best);
+    if ((lane & 15) == 0) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int i = i0 + 4 * v + (lane >> 4);
+        if (i < n) {
+          int lo, hi;
+          clip_span(D, c0, sstart[i], slen[i], lo, hi);
+          const int c = max(hi - lo, 0);
+          scores[i] = best[v];
+          clip[i] = c;
+          // spans that cannot be retrieved go to the end of the order with the padding
+          skey[i] = c > 0 ? score_key(best[v]) : ~0ull;
+          sidx[i] = c > 0 ? (uint32_t)i : RT1_PAD;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  select_sorted_prefix(D, skey, sidx, clip, npow, selmask, wave_tot);
+  __syncthreads();
+  int32_t* ids_out = a.sel_ids_out ? a.sel_ids_out + (size_t)pg * D.sel_cap : nullptr;
+  int32_t* cnt_out = a.sel_cnt_out ? a.sel_cnt_out + pg : nullptr;
+  emit_selection(D, a.st, slot, selmask, n, ids_out, cnt_out);
+}
+
 // ---- retrieval by memory units (Eq. 9 as written): a unit scores the maximum over its spans; the
 //      top units within k_max and the token budget are retrieved whole. One workgroup per
 //      (sequence, KV head); the spans' scores are already in place. ----
@@ -832,13 +978,19 @@ bool retrieve_is_one_launch(const Dims& D, int n_q, int span_bound) {
   return n_q == 1 && span_bound >= 1 && span_bound <= RT1_MAX_SPANS && D.d == 128 && D.unit == 0;
 }
 
+bool retrieve_stores_rep_keys(const Dims& D, int n_q) {
+  return n_q > QREP_PIECE && D.rep_mode == LTRI_REP_MEAN;
+}
+
 hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,
                            const void* q, int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
                            int32_t* sel_ids_out, int32_t* sel_cnt_out, const VoteArgs* votes, const void* append_k_arena,
-                           hipStream_t s) {
+                           const void* rep_k_arena, hipStream_t s) {
   RetArgs a;
   a.D = D; a.st = st; a.sc = sc; a.q = q; a.layer = layer; a.seq_count = seq_count; a.n_q = n_q;
   a.k_arena = append_k_arena; a.append_first = append_k_arena != nullptr;
+  a.rep_k_arena = rep_k_arena;
+  if (rep_k_arena && !retrieve_stores_rep_keys(D, n_q)) return hipErrorInvalidValue;
   if (a.append_first && !retrieve_is_one_launch(D, n_q, span_bound)) return hipErrorInvalidValue;
   a.Lp = (n_q + SEG_TB - 1) / SEG_TB * SEG_TB;
   a.sel_ids_out = sel_ids_out; a.sel_cnt_out = sel_cnt_out; a.bp = bp;
@@ -863,16 +1015,43 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
     return hipGetLastError();
   }
   a.units_cap = n_q / QREP_PIECE + n_q;                  // pieces of all spans of a chunk, at most
+  // Long chunks of 128-wide heads with spans as the retrieval unit: after the pieces' sums everything else of the
+  // step is one launch per batch of sequences (retrieve_chunk_kernel).
+  // (its sort arrays share the 160 KB of LDS with 42 KB of staging and list scratch)
+  const bool one_tail = n_q > QREP_PIECE && D.d == 128 && D.unit == 0 && !votes && span_bound >= 1 &&
+                        span_bound <= RT1_MAX_SPANS && rt1_lds_bytes(span_bound) <= 116 * 1024;
+  if (one_tail) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&retrieve_chunk_kernel<LTRI_BF16>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 116 * 1024);
+      if (e != hipSuccess) return e;
+      e = hipFuncSetAttribute(reinterpret_cast<const void*>(&retrieve_chunk_kernel<LTRI_F32>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, 116 * 1024);
+      if (e != hipSuccess) return e;
+      attr_set = true;
+    }
+  }
   if (n_q > QREP_PIECE) {
     const int per = sc_max_problems / D.Hkv;               // sequences the piece buffer holds
+    const int gx = QREP_GRID_X + (rep_k_arena ? QREP_GRID_X : 0);
+    const size_t lds = rt1_lds_bytes(span_bound);
     for (int off = 0; off < seq_count; off += per) {
       const int cnt = seq_count - off < per ? seq_count - off : per;
       a.batch_off = off;
-      dim3 gp(64, cnt * D.Hkv), gf(n_q < 64 ? n_q : 64, cnt * D.Hkv);
-      if (bf) { qrep_partial_kernel<LTRI_BF16><<<gp, 1024, 0, s>>>(a); qrep_final_kernel<LTRI_BF16><<<gf, 128, 0, s>>>(a); }
-      else    { qrep_partial_kernel<LTRI_F32><<<gp, 1024, 0, s>>>(a);  qrep_final_kernel<LTRI_F32><<<gf, 128, 0, s>>>(a); }
+      dim3 gp(gx, cnt * D.Hkv), gf(n_q < 64 ? n_q : 64, cnt * D.Hkv);
+      if (bf) qrep_partial_kernel<LTRI_BF16><<<gp, 1024, 0, s>>>(a);
+      else    qrep_partial_kernel<LTRI_F32><<<gp, 1024, 0, s>>>(a);
+      if (one_tail) {
+        if (bf) retrieve_chunk_kernel<LTRI_BF16><<<cnt * D.Hkv, 1024, lds, s>>>(a, span_bound);
+        else    retrieve_chunk_kernel<LTRI_F32><<<cnt * D.Hkv, 1024, lds, s>>>(a, span_bound);
+      } else {
+        if (bf) qrep_final_kernel<LTRI_BF16><<<gf, 128, 0, s>>>(a);
+        else    qrep_final_kernel<LTRI_F32><<<gf, 128, 0, s>>>(a);
+      }
     }
     a.batch_off = 0;
+    if (one_tail) return hipGetLastError();
   } else {
     dim3 gq(n_q < 64 ? n_q : 64, P);
     if (bf) qrep_kernel<LTRI_BF16><<<gq, 1024, 0, s>>>(a);
