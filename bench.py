@@ -484,7 +484,7 @@ def main():
 
     events = []
     if step_schedule:
-        ctx.set_step_timing(True)     # events around the two attention launches of every step, on their own streams
+        ctx.set_step_timing(True)     # events around the attention launches of every step, on their own streams
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -496,18 +496,21 @@ def main():
 
     traffic = None
     if step_schedule:
-        # The attention of a step is two launches of attend_bf16_kernel (initial | window | chunk on the library's
-        # second stream beside steps 1 and 2, then the retrieved tokens): the library brackets each with events on
-        # the stream it runs on, inside the timed region above. Achieved = the chunk's algorithmic flops over the
-        # sum of the two durations.
+        # The library brackets the attention launches of every step with events on the stream each runs on, inside
+        # the timed region above. Resident keys and values: one launch of attend_bf16_kernel per chunk. Host-offloaded:
+        # two (initial | window | chunk on the library's second stream beside steps 1 and 2 and the fetch, then the
+        # retrieved tokens); achieved = the chunk's algorithmic flops over the sum of the two durations.
         t_loc, t_ret = ctx.read_step_timing(cap=args.steps * n_chunks + 8)
         ctx.set_step_timing(False)
         assert len(t_loc) == args.steps * n_chunks, (len(t_loc), args.steps * n_chunks)
-        att_ms = [float(a + b) for a, b in zip(t_loc, t_ret)]
-        part_ms = {"initial_window_chunk": float(sum(t_loc)) / len(t_loc), "retrieved": float(sum(t_ret)) / len(t_ret)}
-        if args.workload == "cfg3" and not args.context:
-            traffic = profile_traffic_bytes("attend_step_hbm_traffic_cfg3.txt",
-                                            ["attend_bf16_kernel(first_part)", "attend_bf16_kernel(retrieved_part)"])
+        if args.kv_offload:
+            att_ms = [float(a + b) for a, b in zip(t_loc, t_ret)]
+            part_ms = {"initial_window_chunk": float(sum(t_loc)) / len(t_loc), "retrieved": float(sum(t_ret)) / len(t_ret)}
+        else:
+            att_ms = [float(a) for a in t_loc]
+            part_ms = None
+            if args.workload == "cfg3" and not args.context:
+                traffic = profile_traffic_bytes("attend_gather_hbm_traffic_cfg3.txt", ["attend_bf16_kernel"])
     else:
         att_ms = [e0.elapsed_time(e1) for e0, e1 in events]
         part_ms = None
@@ -522,8 +525,11 @@ def main():
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                 "traffic": traffic,
                 "avg_launch_us": round(tot_ms / len(att_ms) * 1e3, 1),
-                "launches_timed": ("the two attention launches of every ltri_step of the timed streams (events recorded by "
-                                   "the library on the streams the launches run on); durations summed per chunk"
+                "launches_timed": (("the two attention launches of every ltri_step of the timed streams (events recorded by "
+                                    "the library on the streams the launches run on); durations summed per chunk"
+                                    if args.kv_offload else
+                                    "the attention launch of every ltri_step of the timed streams (events recorded by the "
+                                    "library around the launch)")
                                    if step_schedule else "every launch of the timed streams"),
                 "avg_part_us": {k: round(v * 1e3, 1) for k, v in part_ms.items()} if part_ms else None,
                 "full_context_launch_us": round(sum(att_ms[i] for i in last) / len(last) * 1e3, 1),

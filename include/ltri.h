@@ -258,30 +258,36 @@ int32_t ltri_attend_static(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int3
  * ltri_append_chunk(k_chunk, v_chunk, q_seg) + ltri_retrieve(q) + ltri_attend(q), arguments as there
  * (k_chunk / v_chunk may both be NULL when the rows are already in the arenas; q_seg and lse may be
  * NULL; the selection is not copied out, read it with ltri_get_selection).
- * What this call adds is the schedule. The attention over initial tokens, window and the chunk itself
- * depends on neither step 1 nor step 2: it is queued on a second stream the context owns, behind the
- * kernels of step 1 that fill the chip, and runs while the many small kernels of steps 1 and 2
- * (candidate selection, index vectors, scoring, top-k) take the compute units its shorter workgroups
- * leave. The attention over the retrieved tokens follows on the context's stream once the first part
- * is done, and folds the first part's output in by the two log-sum-exps as it writes. The context's
- * stream waits for the second stream before that launch, so for the caller everything is ordered on
- * the context's stream as with the three calls: `out` and `lse` hold the result once that stream
- * reaches the end of this call's work. The first part is rounded to the dtype before it is folded in,
- * so `out` can differ from ltri_attend's by one more rounding of the dtype. A one-token chunk (decode)
- * runs steps 1 and 2 in one kernel launch and then step 3, all on the context's stream, with results
- * identical to the three calls. Chunks of 2 to 4 rows, fp32 contexts and group sizes the matrix-core
- * kernel does not take run the three calls in order.
+ * What this call adds is the schedule, which depends on where the evicted keys and values live.
+ * Resident on the device (kv_offload = 0): the kernels of the three steps follow each other on the context's
+ * stream without a return to the host, the chunk's mean keys are stored by the launch that sums the pieces of
+ * its query spans, step 2 is two launches, and the attention is one launch over initial | retrieved | window |
+ * chunk; results identical to the three calls.
+ * In host memory (kv_offload = 1): the attention over initial tokens, window and the chunk itself depends on
+ * neither step 1 nor step 2; it is queued on a second stream the context owns, behind the kernels of step 1
+ * that fill the chip, and runs while the small kernels of steps 1 and 2 run and the retrieved rows cross the
+ * host link. The attention over the retrieved tokens follows on the context's stream once the first part is
+ * done, and folds the first part's output in by the two log-sum-exps as it writes. The context's stream waits
+ * for the second stream before that launch, so for the caller everything is ordered on the context's stream as
+ * with the three calls: `out` and `lse` hold the result once that stream reaches the end of this call's work.
+ * The first part is rounded to the dtype before it is folded in, so `out` can differ from ltri_attend's by one
+ * more rounding of the dtype.
+ * A one-token chunk (decode) runs steps 1 and 2 in one kernel launch and then step 3, all on the context's
+ * stream, with results identical to the three calls. Chunks of 2 to 4 rows, fp32 contexts and group sizes the
+ * matrix-core kernel does not take run the three calls in order.
  * Errors: those of the three calls. */
 int32_t ltri_step(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* k_chunk,
                   const void* v_chunk, const void* q_seg, const void* q, int32_t n_new, void* out, float* lse);
 
 /* Measurement aid for ltri_step (Sec. 3.4 third step, the attention, is where the time goes): with timing on,
- * every ltri_step that takes the two-stream schedule records HIP events around its two attention launches, each
- * on the stream the launch runs on (the first part on the context's second stream, beside the kernels of steps 1
- * and 2; the retrieved part on the context's stream). ltri_read_step_timing synchronises the context's stream,
- * writes the two durations (milliseconds) of up to `cap` steps since the last read, oldest first, to the host
- * arrays, sets *n to the count and forgets the records. Steps that run the plain calls (one-token chunks, fp32)
- * leave no record. Turning timing on or off also forgets pending records. */
+ * every ltri_step of a chunk of more than 4 rows on a bf16 context records HIP events around its attention
+ * launches, each on the stream the launch runs on. ltri_read_step_timing synchronises the context's stream,
+ * writes two durations (milliseconds) per step for up to `cap` steps since the last read, oldest first, to the
+ * host arrays, sets *n to the count and forgets the records. With resident keys and values the first array
+ * holds the one attention launch and the second an empty interval (about 0); with kv_offload = 1 the first holds
+ * the launch over initial | window | chunk on the second stream and the second the launch over the retrieved
+ * rows. Steps that run the plain calls (one-token chunks, fp32) leave no record. Turning timing on or off also
+ * forgets pending records. */
 int32_t ltri_set_step_timing(ltri_ctx* ctx, int32_t on);
 int32_t ltri_read_step_timing(ltri_ctx* ctx, float* local_ms_host, float* retrieved_ms_host, int32_t cap, int32_t* n);
 

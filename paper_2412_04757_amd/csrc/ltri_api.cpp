@@ -171,6 +171,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.loc_cap = (int)align_up((size_t)c.n_sink + c.window, ATT_BN) + ATT_BN;
   CL.att_lse2 = o;  o = align_up(o + (size_t)c.n_seqs * c.chunk_max * c.n_q_heads * 4, 256);
   CL.loclist = o;   o = align_up(o + (size_t)c.n_seqs * CL.loc_cap * 4, 256);
+  CL.tickets = o;   o = align_up(o + (size_t)2 * P * 4, 256);
   CL.total = o;
   CL.max_problems = P;
   return LTRI_OK;
@@ -258,7 +259,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
                      (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds), (uint8_t*)(t + CL.selflag), (float*)(t + CL.att_part),
                      (int32_t*)(t + CL.tokspan), (double*)(t + CL.dyn), (double*)(t + CL.lpart),
                      (uint32_t*)(t + CL.qhist), (unsigned long long*)(t + CL.qstate),
-                     (float*)(t + CL.att_lse2), (int32_t*)(t + CL.loclist)};
+                     (float*)(t + CL.att_lse2), (int32_t*)(t + CL.loclist), (int32_t*)(t + CL.tickets)};
   const size_t n = (size_t)D.n_layers * D.n_seqs;
   c->n_tokens.assign(n, 0);
   c->last_len.assign(n, 0);
@@ -267,6 +268,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->ever_sel.assign(n, 0u);
   if (!dry) {
     hipError_t e = launch_fill_zero(c->state, SL.total, c->stream);
+    if (e == hipSuccess) e = launch_fill_zero(c->scratch + CL.tickets, align_up((size_t)2 * CL.max_problems * 4, 256), c->stream);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     // the two events order streams of this device only: no timing, and a device-scope release when they are recorded
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming | hipEventReleaseToDevice);
@@ -775,9 +777,32 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   memset(&bp, 0, sizeof bp);
   int32_t r = append_common(c, layer, seq_begin, seq_count, k_chunk, v_chunk, n_new, bp);
   if (r != LTRI_OK) return r;
+  const bool keys_with_step2 = retrieve_stores_rep_keys(c->D, n_new);
+  if (!c->D.offload) {
+    // Keys and values resident on the device: the three steps follow each other on the context's stream and the
+    // attention is one launch over initial | retrieved | window | chunk. Its workgroups are equal in work (row
+    // sub-tiles paired from both ends of the chunk) and fill every compute unit, so a split that runs the first
+    // part beside the small kernels of steps 1 and 2 only makes those wait for a free compute unit.
+    r = append_spans(c, layer, bp, seq_count, q_seg, n_new, nullptr, keys_with_step2);
+    if (r != LTRI_OK) return r;
+    append_commit(c, layer, seq_begin, seq_count, n_new);
+    r = retrieve_impl(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr, keys_with_step2);
+    if (r != LTRI_OK) return r;
+    r = timing_mark(c, c->stream);
+    if (r != LTRI_OK) return r;
+    r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse,
+                                   c->attend_stages, c->dc.att_part, 0, nullptr, 0, nullptr, c->stream), "attend");
+    if (r != LTRI_OK) return r;
+    r = timing_mark(c, c->stream);
+    if (r == LTRI_OK) r = timing_mark(c, c->stream);        // no second launch: an empty interval
+    if (r == LTRI_OK) r = timing_mark(c, c->stream);
+    return r;
+  }
+  // Keys and values in host memory: the retrieved rows cross the host link after step 2, so the attention over
+  // initial | window | chunk runs on a second stream meanwhile and the launch over the retrieved rows folds its
+  // result in.
   float* lse_a = c->dc.att_lse2;
   // Context's stream: the kernels of step 1 that fill the chip, the fork, then the small kernels of steps 1 and 2.
-  const bool keys_with_step2 = retrieve_stores_rep_keys(c->D, n_new);
   r = append_spans(c, layer, bp, seq_count, q_seg, n_new, c->ev_fork, keys_with_step2);
   if (r != LTRI_OK) return r;
   append_commit(c, layer, seq_begin, seq_count, n_new);

@@ -74,6 +74,7 @@ struct ScratchLayout {
   size_t lpart;    // double [P][G][nb][Lp][2]  per tile: row maximum and sum of exponentials (row log-sum-exp in pieces)
   size_t att_lse2; // float  [n_seqs][chunk_max][Hq]  log-sum-exp of the first part of an overlapped step
   size_t loclist;  // int32  [n_seqs][loc_cap]  initial | window tokens (overlapped step)
+  size_t tickets;  // int32  [2][P]  finished workgroups per problem (step 2 of long chunks); zero between launches
   size_t total;
   int    loc_cap;       // entries of one sequence's initial | window list, whole tiles plus one
   int    max_problems;  // P the buffer was sized for
@@ -131,6 +132,7 @@ struct DevScratch {
   double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds; uint8_t* selflag; float* att_part;
   int32_t* tokspan; double* dyn; double* lpart; uint32_t* qhist; unsigned long long* qstate;
   float* att_lse2; int32_t* loclist;
+  int32_t* tickets;   // [2][max_problems] counters of finished workgroups; zero between launches
 };
 
 // ---- launchers (each returns the hipError_t of the launch) ----

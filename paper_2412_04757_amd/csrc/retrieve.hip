@@ -19,6 +19,8 @@ struct RetArgs {
   int32_t* sel_ids_out; int32_t* sel_cnt_out;
   const void* k_arena; int append_first;  // one-token chunk: step 1 (the token becomes a span of its own) in the same launch
   const void* rep_k_arena;                // not NULL: the launch of the query-span pieces also stores the chunk's mean keys
+  int qrep_by_last;                       // the last workgroup of the pieces' launch adds them up into Q^R
+  int ticket_base;                        // first ticket counter of retrieve_chunk_kernel's problems
   BatchPos bp;
 };
 
@@ -138,6 +140,32 @@ __global__ __launch_bounds__(1024) void qrep_partial_kernel(RetArgs a) {
     span_mean_block<DT>(Qb + (size_t)start * D.Hq * d, (size_t)D.Hq * d, D.G, nt, d, nullptr, part,
                         psum + (size_t)u * d, index_mask(D, a.st, slot, meta), start);
   }
+  if (!a.qrep_by_last) return;
+  // The workgroup of a problem that finishes last adds the pieces up into Q^R and leaves the ticket counter at
+  // zero for the next launch. The sums are stored and loaded at device scope (they bypass the caches that the
+  // compute units of one die do not share with the others), every store of a workgroup has completed at the
+  // barrier before its ticket is taken, and the ticket is a device-scope atomic: no device-wide fence, which
+  // would write back and invalidate the whole level-2 cache, is needed.
+  __shared__ int s_last;
+  __syncthreads();
+  if (threadIdx.x == 0) s_last = atomicAdd(&a.sc.tickets[p], 1) == QREP_GRID_X - 1;
+  __syncthreads();
+  if (!s_last) return;
+  T* qrep = reinterpret_cast<T*>(a.sc.qrep) + (size_t)(bi * D.Hkv + h) * a.Lp * d;
+  const bool summed = index_mask(D, a.st, slot, meta) != nullptr;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int q = wave; q < nsp; q += 16) {                  // the pieces of a span in ascending order, one wavefront per span
+    const int u0 = qrep_first_unit(slen, q);
+    const int len = slen[q];
+    const int parts = (len + QREP_PIECE - 1) / QREP_PIECE;
+    for (int c = lane; c < d; c += 64) {
+      double sum = 0.0;
+      for (int k = 0; k < parts; ++k)
+        sum += __hip_atomic_load(psum + (size_t)(u0 + k) * d + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      qrep[(size_t)q * d + c] = Elt<DT>::from_f64(summed ? sum : sum / (double)len);
+    }
+  }
+  if (threadIdx.x == 0) a.sc.tickets[p] = 0;
 }
 
 template <int DT>
@@ -744,71 +772,68 @@ __global__ __launch_bounds__(1024) void retrieve_one_token_kernel(RetArgs a, int
   emit_selection(D, a.st, slot, selmask, n, ids_out, cnt_out);
 }
 
-// ---- step 2 of a long chunk after the pieces of its query spans are summed, in one launch: Q^R of every query
-//      span, the scores of all stored spans (Eq. 8, maximum over the query spans as in Eq. 9), the budgeted
-//      selection by sorting and the lists. One workgroup per (sequence, KV head); head_dim 128, spans
-//      retrieved (not units), at most RT1_MAX_SPANS stored spans (the launcher checks). ----
+// ---- step 2 of a long chunk once Q^R of its query spans is in place, in one launch: the scores of all stored
+//      spans (Eq. 8, maximum over the query spans as in Eq. 9), the budgeted selection by sorting and the lists.
+//      gridDim.x workgroups per (sequence, KV head) share the scoring, 256 spans at a time each, so that the
+//      stored vectors stream in through many compute units; the one that finishes last (a ticket counter, left at
+//      zero again) sorts and writes the lists. head_dim 128, spans retrieved (not units), at most RT1_MAX_SPANS
+//      stored spans (the launcher checks). ----
 template <int DT>
 __global__ __launch_bounds__(1024) void retrieve_chunk_kernel(RetArgs a, int bound) {
   typedef typename Elt<DT>::type T;
   extern __shared__ __attribute__((aligned(16))) unsigned char rt1_lds[];
   __shared__ uint32_t selmask[RT1_MAX_SPANS / 32 + 2];
   __shared__ long long wave_tot[16];
+  __shared__ int s_last;
   const Dims& D = a.D;
-  const int pl = blockIdx.x, bi = a.batch_off + pl / D.Hkv, h = pl % D.Hkv, pg = bi * D.Hkv + h;
+  const int pl = blockIdx.y, bi = a.batch_off + pl / D.Hkv, h = pl % D.Hkv, pg = bi * D.Hkv + h;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int d = 128, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = min(meta[META_N_SPANS], bound), c0 = meta[META_CHUNK_START];
-  const int first = meta[META_CHUNK_FIRST], nqs = meta[META_CHUNK_NSP];
-  // Q^R of the chunk's spans: the pieces of a span are added in ascending order, one wavefront per span
-  T* qrep = reinterpret_cast<T*>(a.sc.qrep) + (size_t)pg * a.Lp * d;
-  {
-    const int32_t* slen_c = a.st.span_len + (size_t)slot * D.max_spans + first;
-    const double* psum = a.sc.qpart + (size_t)pl * a.units_cap * d;
-    const bool summed = index_mask(D, a.st, slot, meta) != nullptr;
-    for (int q = wave; q < nqs; q += 16) {
-      const int u0 = qrep_first_unit(slen_c, q);
-      const int len = slen_c[q];
-      const int parts = (len + QREP_PIECE - 1) / QREP_PIECE;
-      for (int c = lane; c < d; c += 64) {
-        double s = 0.0;
-        for (int k = 0; k < parts; ++k) s += psum[(size_t)(u0 + k) * d + c];
-        qrep[(size_t)q * d + c] = Elt<DT>::from_f64(summed ? s : s / (double)len);
-      }
-    }
-  }
-  const int npow = rt1_pow2(n);
-  uint64_t* skey = reinterpret_cast<uint64_t*>(rt1_lds);
-  uint32_t* sidx = reinterpret_cast<uint32_t*>(rt1_lds + (size_t)rt1_pow2(bound) * 8);
-  int* clip = reinterpret_cast<int*>(rt1_lds + (size_t)rt1_pow2(bound) * 12);
+  const int nqs = meta[META_CHUNK_NSP];
+  const T* qrep = reinterpret_cast<const T*>(a.sc.qrep) + (size_t)pg * a.Lp * d;
   const T* krep = reinterpret_cast<const T*>(a.st.krep) + (size_t)slot * D.max_spans * d;
   double* scores = a.st.scores + (size_t)slot * D.max_spans;
-  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
-  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
-  for (int w = tid; w < (n + 31) / 32 + 2; w += blockDim.x) selmask[w] = 0u;
-  __threadfence_block();
-  __syncthreads();                                      // the query representatives are in place for the whole workgroup
-  for (int i = n + tid; i < npow; i += blockDim.x) { skey[i] = ~0ull; sidx[i] = RT1_PAD; }    // padding of the sort
-  for (int i0 = 16 * wave; i0 < n; i0 += 256) {         // a tile of 16 spans per wavefront
+  for (int i0 = 256 * (int)blockIdx.x + 16 * wave; i0 < n; i0 += 256 * (int)gridDim.x) {   // a tile of 16 spans per wavefront
     double best[4];
     score_tile_f64<DT>(krep, n, i0, qrep, nqs, d, best);
     if ((lane & 15) == 0) {
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
         const int i = i0 + 4 * v + (lane >> 4);
-        if (i < n) {
-          int lo, hi;
-          clip_span(D, c0, sstart[i], slen[i], lo, hi);
-          const int c = max(hi - lo, 0);
-          scores[i] = best[v];
-          clip[i] = c;
-          // spans that cannot be retrieved go to the end of the order with the padding
-          skey[i] = c > 0 ? score_key(best[v]) : ~0ull;
-          sidx[i] = c > 0 ? (uint32_t)i : RT1_PAD;
-        }
+        // stored and (below) loaded at device scope, as the pieces of Q^R are in qrep_partial_kernel
+        if (i < n) __hip_atomic_store(scores + i, best[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
+  }
+  __syncthreads();                                        // the workgroup's stores have completed
+  if (gridDim.x > 1) {
+    if (tid == 0) s_last = atomicAdd(&a.sc.tickets[a.ticket_base + pl], 1) == (int)gridDim.x - 1;
+    __syncthreads();
+    if (!s_last) return;
+    if (tid == 0) a.sc.tickets[a.ticket_base + pl] = 0;
+  }
+  const int npow = rt1_pow2(n);
+  uint64_t* skey = reinterpret_cast<uint64_t*>(rt1_lds);
+  uint32_t* sidx = reinterpret_cast<uint32_t*>(rt1_lds + (size_t)rt1_pow2(bound) * 8);
+  int* clip = reinterpret_cast<int*>(rt1_lds + (size_t)rt1_pow2(bound) * 12);
+  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
+  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
+  for (int w = tid; w < (n + 31) / 32 + 2; w += blockDim.x) selmask[w] = 0u;
+  for (int i = tid; i < npow; i += blockDim.x) {
+    int c = 0;
+    double sc = 0.0;
+    if (i < n) {
+      int lo, hi;
+      clip_span(D, c0, sstart[i], slen[i], lo, hi);
+      c = max(hi - lo, 0);
+      sc = __hip_atomic_load(scores + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      clip[i] = c;
+    }
+    // spans that cannot be retrieved go to the end of the order with the padding
+    skey[i] = c > 0 ? score_key(sc) : ~0ull;
+    sidx[i] = c > 0 ? (uint32_t)i : RT1_PAD;
   }
   __syncthreads();
   select_sorted_prefix(D, skey, sidx, clip, npow, selmask, wave_tot);
@@ -990,6 +1015,7 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
   a.D = D; a.st = st; a.sc = sc; a.q = q; a.layer = layer; a.seq_count = seq_count; a.n_q = n_q;
   a.k_arena = append_k_arena; a.append_first = append_k_arena != nullptr;
   a.rep_k_arena = rep_k_arena;
+  a.qrep_by_last = false; a.ticket_base = 0;
   if (rep_k_arena && !retrieve_stores_rep_keys(D, n_q)) return hipErrorInvalidValue;
   if (a.append_first && !retrieve_is_one_launch(D, n_q, span_bound)) return hipErrorInvalidValue;
   a.Lp = (n_q + SEG_TB - 1) / SEG_TB * SEG_TB;
@@ -1040,11 +1066,14 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
       const int cnt = seq_count - off < per ? seq_count - off : per;
       a.batch_off = off;
       dim3 gp(gx, cnt * D.Hkv), gf(n_q < 64 ? n_q : 64, cnt * D.Hkv);
+      a.qrep_by_last = one_tail;
+      a.ticket_base = sc_max_problems;                      // the second half of the counters
       if (bf) qrep_partial_kernel<LTRI_BF16><<<gp, 1024, 0, s>>>(a);
       else    qrep_partial_kernel<LTRI_F32><<<gp, 1024, 0, s>>>(a);
       if (one_tail) {
-        if (bf) retrieve_chunk_kernel<LTRI_BF16><<<cnt * D.Hkv, 1024, lds, s>>>(a, span_bound);
-        else    retrieve_chunk_kernel<LTRI_F32><<<cnt * D.Hkv, 1024, lds, s>>>(a, span_bound);
+        const dim3 gt((span_bound + 255) / 256, cnt * D.Hkv);
+        if (bf) retrieve_chunk_kernel<LTRI_BF16><<<gt, 1024, lds, s>>>(a, span_bound);
+        else    retrieve_chunk_kernel<LTRI_F32><<<gt, 1024, lds, s>>>(a, span_bound);
       } else {
         if (bf) qrep_final_kernel<LTRI_BF16><<<gf, 128, 0, s>>>(a);
         else    qrep_final_kernel<LTRI_F32><<<gf, 128, 0, s>>>(a);

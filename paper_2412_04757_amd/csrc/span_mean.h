@@ -65,7 +65,9 @@ __device__ __forceinline__ void span_mean_block(const typename Elt<DT>::type* ba
     double s = 0.0;
 #pragma unroll
     for (int w = 0; w < 16; ++w) s += part[w][threadIdx.x];
-    if (out_sum) out_sum[threadIdx.x] = s;          // raw sum of a piece of a span
+    // raw sum of a piece of a span, stored through to device scope: another workgroup of the same launch may
+    // add the pieces up (the one that takes the last ticket)
+    if (out_sum) __hip_atomic_store(out_sum + threadIdx.x, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     else         out[threadIdx.x] = Elt<DT>::from_f64(tokmask ? s : s / (double)n_tokens);
   }
   __syncthreads();
