@@ -231,20 +231,19 @@ template <int DT, int KIND>
 __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
   __shared__ double Ms[64 * 65];
   __shared__ double cpart[4][64];
+  __shared__ double rpart[4][64];
   const int p = blockIdx.y;
   int I, J;
   tile_decode(blockIdx.x, I, J);
   compute_tile<DT, KIND>(a, p, I, J, Ms);
   __syncthreads();
   const int tid = threadIdx.x;
-  {                                       // row sums: four threads per row, 16 columns each
-    const int r = tid >> 2, qd = tid & 3;
+  {                                       // row sums: four threads per row, 16 columns each; a wavefront takes
+    const int r = tid & 63, qd = tid >> 6;  // 64 consecutive rows (row pitch 65: no bank conflicts)
     double s = 0.0;
 #pragma unroll
     for (int c = 0; c < 16; ++c) s += Ms[r * 65 + qd * 16 + c];
-    s += __shfl_xor(s, 1, 64);
-    s += __shfl_xor(s, 2, 64);
-    if (qd == 0) a.sc.rowsum[((size_t)p * a.nb + J) * a.Lp + I * 64 + r] = s;
+    rpart[qd][r] = s;
   }
   {                                       // column sums: four threads per column, 16 rows each
     const int c = tid & 63, qd = tid >> 6;
@@ -254,6 +253,10 @@ __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
     cpart[qd][c] = s;
   }
   __syncthreads();
+  if (tid >= 64 && tid < 128) {
+    const int r = tid - 64;
+    a.sc.rowsum[((size_t)p * a.nb + J) * a.Lp + I * 64 + r] = ((rpart[0][r] + rpart[1][r]) + rpart[2][r]) + rpart[3][r];
+  }
   if (tid < 64) {                         // suffix scan over the 64 columns inside one wavefront
     double v = ((cpart[0][tid] + cpart[1][tid]) + cpart[2][tid]) + cpart[3][tid];
 #pragma unroll
@@ -323,7 +326,7 @@ template <int DT, int KIND>
 __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   __shared__ double Ms[64 * 65];
   __shared__ double rc[64];
-  __shared__ double qsum[64][4];       // sums of the four 16-wide pieces of a row / of a column
+  __shared__ double qsum[4][64];       // sums of the four 16-wide pieces of a row / of a column
   const int p = blockIdx.y;
   int I, J;
   tile_decode(blockIdx.x, I, J);
@@ -334,18 +337,18 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   compute_tile<DT, KIND>(a, p, I, J, Ms);
   if (tid < 64) rc[tid] = rc_pre;
   __syncthreads();
-  {                                     // rows: suffix sums towards the left, four threads per row
-    const int r = tid >> 2, qd = tid & 3;
+  {                                     // rows: suffix sums towards the left, four threads per row; a wavefront
+    const int r = tid & 63, qd = tid >> 6;   // takes 64 consecutive rows (row pitch 65: no bank conflicts)
     double v[16];                       // the thread's cells stay in registers between the two steps
 #pragma unroll
     for (int c = 0; c < 16; ++c) v[c] = Ms[r * 65 + qd * 16 + c];
     double s = 0.0;
 #pragma unroll
     for (int c = 0; c < 16; ++c) s += v[c];
-    qsum[r][qd] = s;
+    qsum[qd][r] = s;
     __syncthreads();
     double run = 0.0;
-    for (int q2 = 3; q2 > qd; --q2) run += qsum[r][q2];
+    for (int q2 = 3; q2 > qd; --q2) run += qsum[q2][r];
 #pragma unroll
     for (int c = 15; c >= 0; --c) { run += v[c]; Ms[r * 65 + qd * 16 + c] = run; }
   }
@@ -358,7 +361,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
     double s = 0.0;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s += w[r];
-    qsum[c][qd] = s;
+    qsum[qd][c] = s;
     __syncthreads();
     const int x = J * 64 + c;
     const int n_h = a.q_seg ? a.D.G : 1;
@@ -366,7 +369,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
     const double th = a.D.theta_quantile > 0.0 ? __longlong_as_double((long long)a.sc.qstate[p * 4 + 2])
                                                : (double)a.D.theta * (double)n_h;
     double run = cc_pre;
-    for (int q2 = 0; q2 < qd; ++q2) run += qsum[c][q2];
+    for (int q2 = 0; q2 < qd; ++q2) run += qsum[q2][c];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int rl = qd * 16 + r, y = I * 64 + rl;
@@ -377,8 +380,8 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
     }
   }
   __syncthreads();
-  {                                     // anti-diagonal xl + yl = s of the tile, two threads each
-    const int sd = tid >> 1, half = tid & 1;
+  {                                     // anti-diagonal xl + yl = s of the tile, two threads each: a wavefront
+    const int sd = tid & 127, half = tid >> 7;      // takes 64 consecutive anti-diagonals (no bank conflicts)
     double best = -INFINITY;
     int bx = -1;
     if (sd < 127) {
@@ -390,14 +393,17 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
         if (v >= best && v > -INFINITY) { best = v; bx = J * 64 + xl; }   // ties: larger x
       }
     }
-    const double ob = __shfl_xor(best, 1, 64);
-    const int ox = __shfl_xor(bx, 1, 64);
+    double* hb = &qsum[0][0];           // free by now: the upper halves' results, 128 scores and 128 columns
+    int* hx = reinterpret_cast<int*>(hb + 128);
+    __syncthreads();
+    if (half) { hb[sd] = best; hx[sd] = bx; }
+    __syncthreads();
     if (half == 0) {                    // the partner holds the larger x: it wins ties
+      const double ob = hb[sd];
+      const int ox = hx[sd];
       if (ox >= 0 && (bx < 0 || ob >= best)) { best = ob; bx = ox; }
-      if (sd < 128) {
-        a.sc.pscore[((size_t)p * a.ntiles + blockIdx.x) * 128 + sd] = best;
-        a.sc.px[((size_t)p * a.ntiles + blockIdx.x) * 128 + sd] = bx;
-      }
+      a.sc.pscore[((size_t)p * a.ntiles + blockIdx.x) * 128 + sd] = best;
+      a.sc.px[((size_t)p * a.ntiles + blockIdx.x) * 128 + sd] = bx;
     }
   }
 }
@@ -512,30 +518,29 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
 #pragma unroll
     for (int r = 1; r < 4; ++r)
       if (key_less(e1[r], e2[r], b1, b2)) { b1 = e1[r]; b2 = e2[r]; }
-    auto step = [&](auto mc) {
+    auto step = [](auto mc, uint64_t& k1, uint32_t& k2) {
       constexpr int M = decltype(mc)::value;
-      const uint32_t lo = lane_xor_c<M>((uint32_t)b1), hi = lane_xor_c<M>((uint32_t)(b1 >> 32));
-      const uint32_t o2 = lane_xor_c<M>(b2);
+      const uint32_t lo = lane_xor_c<M>((uint32_t)k1), hi = lane_xor_c<M>((uint32_t)(k1 >> 32));
+      const uint32_t o2 = lane_xor_c<M>(k2);
       const uint64_t o1 = ((uint64_t)hi << 32) | lo;
-      if (key_less(o1, o2, b1, b2)) { b1 = o1; b2 = o2; }
+      if (key_less(o1, o2, k1, k2)) { k1 = o1; k2 = o2; }
     };
-    step(std::integral_constant<int, 1>{});
-    step(std::integral_constant<int, 2>{});
-    step(std::integral_constant<int, 4>{});
-    step(std::integral_constant<int, 8>{});
-    step(std::integral_constant<int, 16>{});
-    step(std::integral_constant<int, 32>{});
+    step(std::integral_constant<int, 1>{}, b1, b2);
+    step(std::integral_constant<int, 2>{}, b1, b2);
+    step(std::integral_constant<int, 4>{}, b1, b2);
+    step(std::integral_constant<int, 8>{}, b1, b2);
+    step(std::integral_constant<int, 16>{}, b1, b2);
+    step(std::integral_constant<int, 32>{}, b1, b2);
     const int buf = round & 1;                   // two buffers: one barrier per round
     if (lane == 0) { s_w1[buf][wave] = b1; s_w2[buf][wave] = b2; }
     __syncthreads();
-    uint64_t w1 = s_w1[buf][0];
-    uint32_t w2 = s_w2[buf][0];
-#pragma unroll
-    for (int w = 1; w < 16; ++w) {
-      const uint64_t o1 = s_w1[buf][w];
-      const uint32_t o2 = s_w2[buf][w];
-      if (key_less(o1, o2, w1, w2)) { w1 = o1; w2 = o2; }
-    }
+    // the best of the 16 wavefronts: one entry per lane of every row of 16 lanes, four exchange steps
+    uint64_t w1 = s_w1[buf][lane & 15];
+    uint32_t w2 = s_w2[buf][lane & 15];
+    step(std::integral_constant<int, 1>{}, w1, w2);
+    step(std::integral_constant<int, 2>{}, w1, w2);
+    step(std::integral_constant<int, 4>{}, w1, w2);
+    step(std::integral_constant<int, 8>{}, w1, w2);
     if (w1 == ~0ull) break;                      // nothing alive (uniform)
     if (tid == 0) kept[nkept] = w2;
     ++nkept;
