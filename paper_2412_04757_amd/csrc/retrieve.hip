@@ -350,7 +350,7 @@ __device__ __forceinline__ void item_range(const Dims& D, const int32_t* sstart,
 // the token list and their lengths. Called by all 1024 threads of the block.
 constexpr int EMIT_CAP = 2048;     // selected spans whose tokens are written cooperatively
 
-__device__ void emit_selection(const Dims& D, const DevState& st, int slot, const uint32_t* selmask,
+__device__ __forceinline__ void emit_selection(const Dims& D, const DevState& st, int slot, const uint32_t* selmask,
                                int n, int32_t* ids_out, int32_t* cnt_out) {
   __shared__ int s_wcnt[16], s_wtok[16], s_base_cnt, s_base_tok;
   __shared__ int e_a[EMIT_CAP], e_len[EMIT_CAP], e_off[EMIT_CAP];
@@ -556,7 +556,7 @@ __host__ __device__ constexpr size_t rt1_lds_bytes(int bound) { return (size_t)r
 // their clipped lengths; npow is a power of two. Items are sorted by (key, id), the clipped
 // lengths are scanned in that order, and the longest prefix within k_max items and the token
 // budget is marked in selmask (zeroed by the caller). wave_tot: 16 words of LDS.
-__device__ void select_sorted_prefix(const Dims& D, uint64_t* skey, uint32_t* sidx, const int* clip, int npow,
+__device__ __forceinline__ void select_sorted_prefix(const Dims& D, uint64_t* skey, uint32_t* sidx, const int* clip, int npow,
                                      uint32_t* selmask, long long* wave_tot) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // bitonic network, ascending in (key, id)
