@@ -582,13 +582,31 @@ def main():
     torch.cuda.synchronize()
     import statistics
     g_cold_us = statistics.median(a.elapsed_time(b) for a, b in cold) * 1e3
-    del flush
     elt = 2 if w.dtype == "bf16" else 4
     g_bytes = sum(list_lens[-1]) * w.head_dim * elt * 2 * 2            # K and V, read + write
+    # what a plain contiguous device copy of the same size reaches in the same cold state (torch's copy kernel):
+    # a launch this short spends a good part of its time ramping up and draining
+    ref_src = torch.empty(g_bytes // 2, dtype=torch.uint8, device=dev)
+    ref_dst = torch.empty_like(ref_src)
+    ref_src.zero_()
+    ref_dst.copy_(ref_src)
+    cold_ref = []
+    for _ in range(10):
+        flush.add_(1.0)
+        c0e, c1e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0e.record()
+        ref_dst.copy_(ref_src)
+        c1e.record()
+        cold_ref.append((c0e, c1e))
+    torch.cuda.synchronize()
+    ref_cold_us = statistics.median(a.elapsed_time(b) for a, b in cold_ref) * 1e3
+    del flush, ref_src, ref_dst
     gather = {"bound": "hbm", "kernel": "gather_pack_kernel", "achieved": round(g_bytes / g_cold_us / 1e3, 1),
               "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(g_bytes / g_cold_us / 1e3 / PEAK_HBM_GBPS, 4),
               "launch_us": round(g_cold_us, 2), "bytes": g_bytes,
               "state": "cold: timed alone after a pass over 1 GiB of other memory (median of 10)",
+              "plain_copy_same_size_cold": {"achieved": round(g_bytes / ref_cold_us / 1e3, 1), "launch_us": round(ref_cold_us, 2),
+                                            "note": "contiguous device-to-device copy of the same bytes in the same cold state"},
               "warm": {"achieved": round(g_bytes / g_us / 1e3, 1), "frac": round(g_bytes / g_us / 1e3 / PEAK_HBM_GBPS, 4),
                        "launch_us": round(g_us, 2),
                        "state": "back-to-back launches: the working set stays in the last-level cache"}}

@@ -84,22 +84,10 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t off, uint32_t ld
 
 enum : int { MASK_NONE = 0, MASK_LIST_END = 1, MASK_CAUSAL = 2 };
 
-// max of three without the NaN-quieting copies fmaxf() carries (scores are never NaN here)
-__device__ __forceinline__ float max3(float a, float b, float c) {
-  float r;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
-}
-
-// The same, followed by two idle cycles. The compiler cannot see that the assembly writes a vector
-// register on the vector ALU, so it does not insert the wait states that a lane-permute reading that
-// register right afterwards needs; without them the permute can read the register's old value whenever
-// no other wavefront's instruction happens to fall in between.
-__device__ __forceinline__ float max3_settled(float a, float b, float c) {
-  float r;
-  asm volatile("v_max3_f32 %0, %1, %2, %3\n\ts_nop 1" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-  return r;
-}
+// max of three. This file is compiled with -fno-honor-nans (scores are never NaN here), so fmaxf() carries no
+// NaN-quieting copies and the compiler folds the pair into one v_max3_f32; being the compiler's own
+// instruction, it gets the wait states it needs after matrix-core results and before lane permutes.
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
 // acc + lo + hi of a packed bf16 pair (one v_dot2c_f32_bf16)
 __device__ __forceinline__ float pair_sum(uint32_t packed, float acc) {
@@ -111,7 +99,7 @@ __device__ __forceinline__ float pair_sum(uint32_t packed, float acc) {
 // both halves of r[0] and the high half in both halves of r[1]
 __device__ __forceinline__ float pair_max(float v) {
   const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return max3(__uint_as_float(r[0]), __uint_as_float(r[1]), __uint_as_float(r[1]));
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
 // 16-byte LDS read issued by hand; LDS reads return in order, and the loop holds no scalar loads
@@ -342,13 +330,6 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
           if (kr >= nvalid) s[kb][v] = -INFINITY;
         }
     }
-    // The maxima below are taken by instructions written in assembly, which the compiler does not
-    // recognise as vector-ALU readers of the matrix cores' results: it would not insert the wait states
-    // such a read needs after the last product, and the maximum could then be taken over registers the
-    // product has not written yet (the probabilities further down are compiler-generated and wait
-    // properly, so only the rounding would change, from launch to launch). These idle cycles, tied to
-    // both accumulators, stand in for them.
-    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 3" : "+v"(s[0]), "+v"(s[1]));
     float m4[4];                                     // four independent max chains, then a tree
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -357,9 +338,9 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
       m4[c] = max3(m4[c], s[kb][v0 + 3], s[kb][v0 + 4]);
       m4[c] = max3(m4[c], s[kb][v0 + 5], s[kb][v0 + 6]);
     }
-    float mx = max3_settled(max3(m4[0], s[0][7], s[0][15]), max3(m4[1], s[1][7], s[1][15]), max3(m4[2], m4[3], m4[2]));
+    float mx = max3(max3(m4[0], s[0][7], s[0][15]), max3(m4[1], s[1][7], s[1][15]), fmaxf(m4[2], m4[3]));
     mx = pair_max(mx);
-    const float m_new = max3(m_run, mx * sc, mx * sc);
+    const float m_new = fmaxf(m_run, mx * sc);
     const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     const bool changed = m_new != m_run;
     m_run = m_new;
@@ -795,6 +776,7 @@ __global__ __launch_bounds__(64) void attend_simple_kernel(AttArgs a) {
 struct GatherArgs { Dims D; DevState st; const void* k_arena; const void* v_arena; int layer, seq;
                     void* k_packed; void* v_packed; int32_t* n_tokens; };
 
+constexpr int GATHER_ROWS = 4;
 __global__ __launch_bounds__(256) void gather_pack_kernel(GatherArgs a) {
   const Dims& D = a.D;
   const int h = blockIdx.y;
@@ -805,16 +787,32 @@ __global__ __launch_bounds__(256) void gather_pack_kernel(GatherArgs a) {
   const int row16 = D.d * D.elt / 16;                        // 16-byte pieces per row
   const int rows_per_pass = 256 / row16;
   const int r_in = threadIdx.x / row16, piece = threadIdx.x - r_in * row16;
-  const uint4* Kb = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.k_arena) + arena_off(D, slot) * D.elt);
-  const uint4* Vb = reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(a.v_arena) + arena_off(D, slot) * D.elt);
-  uint4* Kp = reinterpret_cast<uint4*>(a.k_packed) + (size_t)h * D.list_cap * row16;
-  uint4* Vp = reinterpret_cast<uint4*>(a.v_packed) + (size_t)h * D.list_cap * row16;
-  for (int r = blockIdx.x * rows_per_pass + r_in; r < list_len; r += gridDim.x * rows_per_pass) {
-    const int tok = list[r];
-    const uint4 kv = Kb[(size_t)tok * row16 + piece];
-    const uint4 vv = Vb[(size_t)tok * row16 + piece];
-    Kp[(size_t)r * row16 + piece] = kv;
-    Vp[(size_t)r * row16 + piece] = vv;
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4* Kb = reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(a.k_arena) + arena_off(D, slot) * D.elt);
+  const u32x4* Vb = reinterpret_cast<const u32x4*>(reinterpret_cast<const char*>(a.v_arena) + arena_off(D, slot) * D.elt);
+  u32x4* Kp = reinterpret_cast<u32x4*>(a.k_packed) + (size_t)h * D.list_cap * row16;
+  u32x4* Vp = reinterpret_cast<u32x4*>(a.v_packed) + (size_t)h * D.list_cap * row16;
+  // GATHER_ROWS rows per thread and trip: the token ids first, then all the row pieces (2 x GATHER_ROWS independent
+  // 16-byte loads in flight per lane), then the stores, which nothing reads again soon (non-temporal)
+  const int stride = gridDim.x * rows_per_pass;
+  for (int r0 = blockIdx.x * rows_per_pass + r_in; r0 < list_len; r0 += GATHER_ROWS * stride) {
+    int tok[GATHER_ROWS];
+#pragma unroll
+    for (int u = 0; u < GATHER_ROWS; ++u) tok[u] = list[min(r0 + u * stride, list_len - 1)];
+    u32x4 kv[GATHER_ROWS], vv[GATHER_ROWS];
+#pragma unroll
+    for (int u = 0; u < GATHER_ROWS; ++u) {
+      kv[u] = Kb[(size_t)tok[u] * row16 + piece];
+      vv[u] = Vb[(size_t)tok[u] * row16 + piece];
+    }
+#pragma unroll
+    for (int u = 0; u < GATHER_ROWS; ++u) {
+      const int r = r0 + u * stride;
+      if (r < list_len) {
+        __builtin_nontemporal_store(kv[u], Kp + (size_t)r * row16 + piece);
+        __builtin_nontemporal_store(vv[u], Vp + (size_t)r * row16 + piece);
+      }
+    }
   }
   if (a.n_tokens && blockIdx.x == 0 && threadIdx.x == 0) a.n_tokens[h] = list_len;
 }
@@ -957,7 +955,7 @@ hipError_t launch_gather_pack(const Dims& D, const DevState& st, const void* k_a
   GatherArgs a{D, st, k_arena, v_arena, layer, seq, k_packed, v_packed, n_tokens};
   const int row16 = D.d * D.elt / 16;
   const int rows_per_pass = 256 / row16;
-  int gx = (D.list_cap + rows_per_pass * 4 - 1) / (rows_per_pass * 4);
+  int gx = (D.list_cap + rows_per_pass * GATHER_ROWS - 1) / (rows_per_pass * GATHER_ROWS);
   if (gx < 1) gx = 1;
   dim3 g(gx, D.Hkv);
   gather_pack_kernel<<<g, 256, 0, s>>>(a);
