@@ -10,9 +10,9 @@
 //   - the tile-local corner sum,
 //   - a row carry    RC[J][i] = sum of row i over the tiles to the right of J,
 //   - a column carry  A[I][x] = sum over all rows above block I of their sum from column x on.
-// Pass 1 emits per-tile row sums / suffix-scanned column sums / totals, pass 2 turns them into
-// the carries, pass 3 recomputes each tile, finishes S = S* - theta * n_h * tri(y - x + 1)
-// (Eq. 5) and reduces every anti-diagonal x + y = s inside the tile; pass 4 merges the tile
+// Pass 1 emits per-tile row sums / suffix-scanned column sums / totals; pass 2 recomputes each tile,
+// adds up its two carries from those sums, finishes S = S* - theta * n_h * tri(y - x + 1)
+// (Eq. 5) and reduces every anti-diagonal x + y = s inside the tile; pass 3 merges the tile
 // results per anti-diagonal, runs the greedy NMS (best live candidate first) and cuts the chunk.
 // All sums are fp64 in a fixed order, so the result is deterministic.
 #include "device_common.h"
@@ -270,105 +270,87 @@ __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
   }
 }
 
-// ---- pass 2: carries ----
-// One thread per row (row carries) or column (column carries); per problem SEG_CARRY_PARTS
-// workgroups share the rows and as many share the columns (they run side by side; each column
-// workgroup rebuilds the small table of tile-total sums it needs).
-constexpr int SEG_CARRY_PARTS = 8;
-__global__ __launch_bounds__(256) void seg_carries_kernel(SegArgs a) {
-  __shared__ double TS[SEG_MAX_NB * SEG_MAX_NB];   // TS[I][J] = sum_{J < J' <= I} tsum[I][J']
-  const int p = blockIdx.y, nb = a.nb, Lp = a.Lp;
-  const double* rowsum = a.sc.rowsum + (size_t)p * nb * Lp;
-  const double* csuf = a.sc.csuf + (size_t)p * nb * Lp;
-  const double* tsum = a.sc.tsum + (size_t)p * nb * nb;
-  double* rcar = a.sc.rcar + (size_t)p * nb * Lp;
-  double* ccar = a.sc.ccar + (size_t)p * nb * Lp;
-  const bool rows = blockIdx.x < SEG_CARRY_PARTS;
-  const int first = (blockIdx.x % SEG_CARRY_PARTS) * blockDim.x + threadIdx.x, stride = SEG_CARRY_PARTS * blockDim.x;
-  for (int i = first; rows && i < Lp; i += stride) {
-    const int I = i / 64;
-    double v[SEG_MAX_NB];
-#pragma unroll
-    for (int J = 0; J < SEG_MAX_NB; ++J) v[J] = (J <= I) ? rowsum[(size_t)J * Lp + i] : 0.0;   // loads in flight together
-    double run = 0.0;
-#pragma unroll
-    for (int J = SEG_MAX_NB - 1; J >= 0; --J) {
-      if (J <= I) { rcar[(size_t)J * Lp + i] = run; run += v[J]; }
-    }
-  }
-  if (rows) return;
-  for (int I = threadIdx.x; I < nb; I += blockDim.x) {
-    double v[SEG_MAX_NB];
-#pragma unroll
-    for (int J = 0; J < SEG_MAX_NB; ++J) v[J] = (J <= I) ? tsum[I * nb + J] : 0.0;     // loads in flight together
-    double run = 0.0;
-#pragma unroll
-    for (int J = SEG_MAX_NB - 1; J >= 0; --J) {
-      if (J <= I) { TS[I * SEG_MAX_NB + J] = run; run += v[J]; }
-    }
-  }
-  __syncthreads();
-  for (int x = first; x < Lp; x += stride) {
-    const int J = x / 64;
-    double v[SEG_MAX_NB];
-#pragma unroll
-    for (int I = 0; I < SEG_MAX_NB; ++I) v[I] = (I >= J && I < nb) ? csuf[(size_t)I * Lp + x] : 0.0;
-    double run = 0.0;
-#pragma unroll
-    for (int I = 0; I < SEG_MAX_NB; ++I) {
-      if (I >= J && I < nb) { ccar[(size_t)I * Lp + x] = run; run += v[I] + TS[I * SEG_MAX_NB + J]; }
-    }
-  }
-}
-
-// ---- pass 3: finish S inside each tile, reduce its anti-diagonals ----
+// ---- pass 2: the tile's carries from the sums of pass 1, then finish S inside the tile and reduce its
+//      anti-diagonals ----
 template <int DT, int KIND>
 __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   __shared__ double Ms[64 * 65];
-  __shared__ double rc[64];
   __shared__ double qsum[4][64];       // sums of the four 16-wide pieces of a row / of a column
+  __shared__ double cpart[4][64];      // the four threads' shares of a row's / a column's carry
+  __shared__ double tpart[4];
   const int p = blockIdx.y;
   int I, J;
   tile_decode(blockIdx.x, I, J);
   const int tid = threadIdx.x, L = a.n_new;
-  // carries are requested before the tile is computed so that their latency hides behind it
-  const double rc_pre = tid < 64 ? a.sc.rcar[((size_t)p * a.nb + J) * a.Lp + I * 64 + tid] : 0.0;
-  const double cc_pre = a.sc.ccar[((size_t)p * a.nb + I) * a.Lp + J * 64 + (tid & 63)];
   compute_tile<DT, KIND>(a, p, I, J, Ms);
-  if (tid < 64) rc[tid] = rc_pre;
+  // The carries of this tile, from the sums of pass 1:
+  //   row carry of row i        = sum of the tile row sums of row i over the tiles right of J (J < J' <= I),
+  //   column carry of column x  = sum over the block rows above I (J <= I' < I) of their suffix-scanned column
+  //                               sum at x, plus the totals of their tiles right of J (one number per tile).
+  // Four threads share a row / a column, each every fourth term, with the same (row or column, quarter) a thread
+  // has in the two scans below; the loads are requested here and used after the scans' first steps.
+  const int li = tid & 63, part = tid >> 6;
+  double rv[SEG_MAX_NB / 4], cv[SEG_MAX_NB / 4], tv[SEG_MAX_NB * SEG_MAX_NB / 256];
+  {
+    const double* rowsum = a.sc.rowsum + (size_t)p * a.nb * a.Lp + I * 64 + li + (J + 1 + part) * a.Lp;
+    const double* csuf = a.sc.csuf + (size_t)p * a.nb * a.Lp + J * 64 + li + (J + part) * a.Lp;
+    const double* tsum = a.sc.tsum + (size_t)p * a.nb * a.nb;
+    const int step = 4 * a.Lp;
+#pragma unroll
+    for (int k = 0; k < SEG_MAX_NB / 4; ++k) {
+      rv[k] = J + 1 + part + 4 * k <= I ? rowsum[k * step] : 0.0;
+      cv[k] = J + part + 4 * k < I ? csuf[k * step] : 0.0;
+    }
+#pragma unroll
+    for (int k = 0; k < SEG_MAX_NB * SEG_MAX_NB / 256; ++k) {      // tiles (I', J'') with J < J'' <= I' < I
+      const int e = tid + 256 * k, Ip = e / SEG_MAX_NB, Jpp = e % SEG_MAX_NB;
+      tv[k] = (Jpp > J && Jpp <= Ip && Ip < I) ? tsum[Ip * a.nb + Jpp] : 0.0;
+    }
+  }
   __syncthreads();
   {                                     // rows: suffix sums towards the left, four threads per row; a wavefront
-    const int r = tid & 63, qd = tid >> 6;   // takes 64 consecutive rows (row pitch 65: no bank conflicts)
+    const int r = li, qd = part;        // takes 64 consecutive rows (row pitch 65: no bank conflicts)
     double v[16];                       // the thread's cells stay in registers between the two steps
 #pragma unroll
     for (int c = 0; c < 16; ++c) v[c] = Ms[r * 65 + qd * 16 + c];
     double s = 0.0;
 #pragma unroll
     for (int c = 0; c < 16; ++c) s += v[c];
+    double rs = 0.0;
+#pragma unroll
+    for (int k = 0; k < SEG_MAX_NB / 4; ++k) rs += rv[k];
     qsum[qd][r] = s;
+    cpart[qd][r] = rs;
     __syncthreads();
-    double run = 0.0;
+    double run = ((cpart[0][r] + cpart[1][r]) + cpart[2][r]) + cpart[3][r];      // the row carry
     for (int q2 = 3; q2 > qd; --q2) run += qsum[q2][r];
 #pragma unroll
     for (int c = 15; c >= 0; --c) { run += v[c]; Ms[r * 65 + qd * 16 + c] = run; }
   }
   __syncthreads();
   {                                     // columns: prefix sums downwards, four threads per column
-    const int c = tid & 63, qd = tid >> 6;
-    double w[16];                       // cell + row carry, kept in registers between the two steps
+    const int c = li, qd = part;
+    double w[16];                       // kept in registers between the two steps
 #pragma unroll
-    for (int r = 0; r < 16; ++r) w[r] = Ms[(qd * 16 + r) * 65 + c] + rc[qd * 16 + r];
+    for (int r = 0; r < 16; ++r) w[r] = Ms[(qd * 16 + r) * 65 + c];
     double s = 0.0;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s += w[r];
+    double cs = 0.0;
+#pragma unroll
+    for (int k = 0; k < SEG_MAX_NB / 4; ++k) cs += cv[k];
+    const double ts = wave_sum_f64((tv[0] + tv[1]) + (tv[2] + tv[3]));
     qsum[qd][c] = s;
+    cpart[qd][c] = cs;
+    if (c == 0) tpart[qd] = ts;
     __syncthreads();
     const int x = J * 64 + c;
     const int n_h = a.q_seg ? a.D.G : 1;
     // Eq. 5's theta per head, times the heads summed; a percentile of the map is already per summed cell
     const double th = a.D.theta_quantile > 0.0 ? __longlong_as_double((long long)a.sc.qstate[p * 4 + 2])
                                                : (double)a.D.theta * (double)n_h;
-    double run = cc_pre;
+    double run = (((cpart[0][c] + cpart[1][c]) + cpart[2][c]) + cpart[3][c]) +
+                 (((tpart[0] + tpart[1]) + tpart[2]) + tpart[3]);      // the column carry
     for (int q2 = 0; q2 < qd; ++q2) run += qsum[q2][c];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -408,7 +390,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   }
 }
 
-// ---- pass 4: candidates -> greedy NMS -> cuts -> span table ----
+// ---- pass 3: candidates -> greedy NMS -> cuts -> span table ----
 
 // Appends the spans cut at cutlist[0..n_cuts) (chunk-local, first 0, last L) to the slot's table.
 __device__ void append_spans(const Dims& D, const DevState& st, int slot, int c0, int L,
@@ -437,7 +419,7 @@ __device__ void append_spans(const Dims& D, const DevState& st, int slot, int c0
   }
 }
 
-// Pass 4a: per anti-diagonal s = x + y, merge the tiles' partial results (ties: larger x =
+// Pass 3a: per anti-diagonal s = x + y, merge the tiles' partial results (ties: larger x =
 // shorter span) and keep the span if S > 0 (appendix "NMS Input Filtration"). One thread per
 // anti-diagonal, many workgroups per problem: the partial results are ~100 bytes per
 // anti-diagonal and tile, far more than one CU reads quickly. Output: an order key (ascending
@@ -481,7 +463,7 @@ __global__ __launch_bounds__(256) void seg_merge_kernel(SegArgs a) {
   a.sc.cxy[(size_t)p * SEG_MAX_DIAG + s] = is_cand ? (((uint32_t)bx << 16) | (uint32_t)(s - bx)) : 0xFFFFFFFFu;
 }
 
-// Pass 4b: greedy NMS (Sec. 3.2) over the candidates in the order (score descending, x ascending,
+// Pass 3b: greedy NMS (Sec. 3.2) over the candidates in the order (score descending, x ascending,
 // y ascending), then the partition. Taking the candidates in sorted order and skipping the
 // suppressed ones is the same as repeatedly taking the best candidate still alive, and the number
 // of kept spans is small, so no sort is done: every thread holds four candidates in registers;
@@ -1172,7 +1154,6 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
       }
     }
     seg_tile_sums_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
-    seg_carries_kernel<<<dim3(2 * SEG_CARRY_PARTS, P), 256, 0, s>>>(a);
     seg_tile_scan_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
   };
   using std::integral_constant;
