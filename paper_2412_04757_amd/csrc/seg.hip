@@ -139,6 +139,11 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
 #pragma unroll
     for (int v = 0; v < 16; ++v) m[v] = (double)acc[v] * scale;
   }
+  if (I > J && (I + 1) * 64 <= L) {             // a whole tile below the diagonal: nothing to mask (uniform)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) Ms[(wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3)) * 65 + wj * 32 + l32] = m[v];
+    return;
+  }
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int rl = wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
@@ -292,19 +297,22 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   const int li = tid & 63, part = tid >> 6;
   double rv[SEG_MAX_NB / 4], cv[SEG_MAX_NB / 4], tv[SEG_MAX_NB * SEG_MAX_NB / 256];
   {
-    const double* rowsum = a.sc.rowsum + (size_t)p * a.nb * a.Lp + I * 64 + li + (J + 1 + part) * a.Lp;
-    const double* csuf = a.sc.csuf + (size_t)p * a.nb * a.Lp + J * 64 + li + (J + part) * a.Lp;
+    // every load is unconditional on a clamped (valid) index and masked afterwards: no branches, all in flight
+    const double* rowsum = a.sc.rowsum + (size_t)p * a.nb * a.Lp + I * 64 + li;
+    const double* csuf = a.sc.csuf + (size_t)p * a.nb * a.Lp + J * 64 + li;
     const double* tsum = a.sc.tsum + (size_t)p * a.nb * a.nb;
-    const int step = 4 * a.Lp;
 #pragma unroll
     for (int k = 0; k < SEG_MAX_NB / 4; ++k) {
-      rv[k] = J + 1 + part + 4 * k <= I ? rowsum[k * step] : 0.0;
-      cv[k] = J + part + 4 * k < I ? csuf[k * step] : 0.0;
+      const int Jp = J + 1 + part + 4 * k, Ip = J + part + 4 * k;
+      const double r = rowsum[min(Jp, I) * a.Lp], c = csuf[min(Ip, I) * a.Lp];
+      rv[k] = Jp <= I ? r : 0.0;
+      cv[k] = Ip < I ? c : 0.0;
     }
 #pragma unroll
     for (int k = 0; k < SEG_MAX_NB * SEG_MAX_NB / 256; ++k) {      // tiles (I', J'') with J < J'' <= I' < I
       const int e = tid + 256 * k, Ip = e / SEG_MAX_NB, Jpp = e % SEG_MAX_NB;
-      tv[k] = (Jpp > J && Jpp <= Ip && Ip < I) ? tsum[Ip * a.nb + Jpp] : 0.0;
+      const double t = tsum[min(Ip, a.nb - 1) * a.nb + min(Jpp, a.nb - 1)];
+      tv[k] = (Jpp > J && Jpp <= Ip && Ip < I) ? t : 0.0;
     }
   }
   __syncthreads();
@@ -352,40 +360,58 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
     double run = (((cpart[0][c] + cpart[1][c]) + cpart[2][c]) + cpart[3][c]) +
                  (((tpart[0] + tpart[1]) + tpart[2]) + tpart[3]);      // the column carry
     for (int q2 = 0; q2 < qd; ++q2) run += qsum[q2][c];
+    // tri(n) = n (n + 1) / 2 of n = y - x + 1 by increments, tri(n + 1) = tri(n) + n + 1: small integers, exact
+    // in fp64 (cells with n <= 0 lie above the diagonal and are masked)
+    const int n0 = I * 64 + qd * 16 - x;                            // n - 1 of the thread's first row
+    double nd = (double)n0, tri = (double)(n0 * (n0 + 1) / 2);      // |n0| <= 2048: the product fits 32 bits
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int rl = qd * 16 + r, y = I * 64 + rl;
       run += w[r];
-      const int n = y - x + 1;                                      // |n| <= 2048: n (n + 1) / 2 fits 32 bits
-      const double sv = run - th * (double)(n * (n + 1) / 2);       // Eq. 5
+      nd += 1.0;
+      tri += nd;
+      const double sv = run - th * tri;                             // Eq. 5
       Ms[rl * 65 + c] = (x <= y && y < L) ? sv : -INFINITY;
     }
   }
   __syncthreads();
-  {                                     // anti-diagonal xl + yl = s of the tile, two threads each: a wavefront
-    const int sd = tid & 127, half = tid >> 7;      // takes 64 consecutive anti-diagonals (no bank conflicts)
-    double best = -INFINITY;
-    int bx = -1;
-    if (sd < 127) {
-      const int lo = max(0, sd - 63), hi = min(63, sd);
-      const int mid = (lo + hi + 1) >> 1;
-      const int b0 = half ? mid : lo, b1 = half ? hi : mid - 1;
-      for (int xl = b0; xl <= b1; ++xl) {
-        const double v = Ms[(sd - xl) * 65 + xl];
-        if (v >= best && v > -INFINITY) { best = v; bx = J * 64 + xl; }   // ties: larger x
-      }
+  {
+    // Anti-diagonals xl + yl = t and t + 64 of the tile hold t + 1 and 63 - t cells: together one cell per
+    // column xl, in row (t - xl) mod 64 (no wrap: the first of the two). Four threads share such a pair, 16
+    // columns each, so every thread reads exactly 16 cells, all requested at once; a wavefront takes 64
+    // consecutive t (row pitch 65: no bank conflicts). Ties go to the larger x.
+    const int t = li, q = part;
+    double v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) { const int xl = 16 * q + j; v[j] = Ms[((t - xl) & 63) * 65 + xl]; }
+    double bestA = -INFINITY, bestB = -INFINITY;
+    int xA = -1, xB = -1;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int xl = 16 * q + j;
+      const bool first = xl <= t, live = v[j] > -INFINITY;
+      const bool upA = first && live && v[j] >= bestA, upB = !first && live && v[j] >= bestB;
+      bestA = upA ? v[j] : bestA; xA = upA ? xl : xA;
+      bestB = upB ? v[j] : bestB; xB = upB ? xl : xB;
     }
-    double* hb = &qsum[0][0];           // free by now: the upper halves' results, 128 scores and 128 columns
-    int* hx = reinterpret_cast<int*>(hb + 128);
+    double* hb = &Ms[0];                // the tile is consumed: [2][4][64] partial maxima, then their columns
+    int* hx = reinterpret_cast<int*>(hb + 512);
     __syncthreads();
-    if (half) { hb[sd] = best; hx[sd] = bx; }
+    hb[q * 64 + t] = bestA; hb[256 + q * 64 + t] = bestB;
+    hx[q * 64 + t] = xA;    hx[256 + q * 64 + t] = xB;
     __syncthreads();
-    if (half == 0) {                    // the partner holds the larger x: it wins ties
-      const double ob = hb[sd];
-      const int ox = hx[sd];
-      if (ox >= 0 && (bx < 0 || ob >= best)) { best = ob; bx = ox; }
-      a.sc.pscore[((size_t)p * a.ntiles + blockIdx.x) * 128 + sd] = best;
-      a.sc.px[((size_t)p * a.ntiles + blockIdx.x) * 128 + sd] = bx;
+    if (tid < 128) {                    // anti-diagonal tid: its four quarters, larger columns last
+      const int o = (tid >> 6) * 256 + (tid & 63);
+      double best = hb[o];
+      int bx = hx[o];
+#pragma unroll
+      for (int k = 1; k < 4; ++k) {
+        const double ob = hb[o + 64 * k];
+        const int ox = hx[o + 64 * k];
+        if (ox >= 0 && (bx < 0 || ob >= best)) { best = ob; bx = ox; }
+      }
+      a.sc.pscore[((size_t)p * a.ntiles + blockIdx.x) * 128 + tid] = best;
+      a.sc.px[((size_t)p * a.ntiles + blockIdx.x) * 128 + tid] = bx >= 0 ? J * 64 + bx : -1;
     }
   }
 }
