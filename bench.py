@@ -684,12 +684,15 @@ def main():
                    "index_vectors": "mean key per span" if args.index_vectors == "mean"
                    else "dynamic (row ratio, lambda 3): sum of the keys of each span's index tokens",
                    "schedule": "append(c+1) on a second stream next to attend(c)" if overlap else
-                   ("ltri_step per chunk: attention over initial | window | chunk on a second stream beside "
-                    "steps 1 and 2, retrieved tokens after, merged" if step_schedule else "three calls per chunk, serial")},
+                   (("ltri_step per chunk: attention over initial | window | chunk on a second stream beside "
+                     "steps 1 and 2 and the fetch of the retrieved rows, retrieved tokens after, merged" if args.kv_offload else
+                     "ltri_step per chunk: the kernels of the three steps on one stream, one attention launch")
+                    if step_schedule else "three calls per chunk, serial")},
         "roofline": roofline, "gather": gather, "cpu_baseline": cpu, "host_link": host_link, "index_footprint": index_footprint,
         "breakdown_ms": {"attend": round(tot_ms / args.steps, 3), "rest_of_step": round(other_ms, 3),
-                         "note": ("attend = sum of the two attention launches of every step; the first one overlaps the "
-                                  "small kernels of steps 1 and 2" if step_schedule else "serial calls"),
+                         "note": (("attend = sum of the two attention launches of every step; the first one overlaps the "
+                                   "small kernels of steps 1 and 2" if args.kv_offload else
+                                   "attend = the attention launch of every step") if step_schedule else "serial calls"),
                          "ms_per_step_three_calls": round(calls_ms_per_step, 3) if calls_ms_per_step else None},
     }
     print(json.dumps(result), flush=True)

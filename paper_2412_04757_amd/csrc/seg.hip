@@ -512,7 +512,9 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
   uint32_t e2[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
-    const int sd = tid + 1024 * r;
+    // consecutive anti-diagonals per thread and wavefront: spans that are kept cover the chunk region by region,
+    // so whole wavefronts run out of live candidates and skip most of a round
+    const int sd = 4 * tid + r;
     e1[r] = sd < n_diag ? a.sc.ckey[(size_t)p * SEG_MAX_DIAG + sd] : ~0ull;
     e2[r] = sd < n_diag ? a.sc.cxy[(size_t)p * SEG_MAX_DIAG + sd] : 0xFFFFFFFFu;
   }
@@ -533,12 +535,15 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
       const uint64_t o1 = ((uint64_t)hi << 32) | lo;
       if (key_less(o1, o2, k1, k2)) { k1 = o1; k2 = o2; }
     };
-    step(std::integral_constant<int, 1>{}, b1, b2);
-    step(std::integral_constant<int, 2>{}, b1, b2);
-    step(std::integral_constant<int, 4>{}, b1, b2);
-    step(std::integral_constant<int, 8>{}, b1, b2);
-    step(std::integral_constant<int, 16>{}, b1, b2);
-    step(std::integral_constant<int, 32>{}, b1, b2);
+    const bool wave_alive = __ballot(b1 != ~0ull) != 0ull;       // uniform over the wavefront
+    if (wave_alive) {
+      step(std::integral_constant<int, 1>{}, b1, b2);
+      step(std::integral_constant<int, 2>{}, b1, b2);
+      step(std::integral_constant<int, 4>{}, b1, b2);
+      step(std::integral_constant<int, 8>{}, b1, b2);
+      step(std::integral_constant<int, 16>{}, b1, b2);
+      step(std::integral_constant<int, 32>{}, b1, b2);
+    }
     const int buf = round & 1;                   // two buffers: one barrier per round
     if (lane == 0) { s_w1[buf][wave] = b1; s_w2[buf][wave] = b2; }
     __syncthreads();
@@ -554,6 +559,7 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
     ++nkept;
     if (max_keep > 0 && nkept >= max_keep) break;
     const int kx = (int)(w2 >> 16), ky = (int)(w2 & 0xFFFFu);
+    if (!wave_alive) continue;                   // nothing left to suppress in this wavefront
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int x = (int)(e2[r] >> 16), y = (int)(e2[r] & 0xFFFFu);
