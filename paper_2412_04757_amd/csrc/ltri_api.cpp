@@ -166,7 +166,8 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.tokspan = o; o = align_up(o + (size_t)P * Lp * 4, 256);
   CL.dyn = o;     o = align_up(o + (size_t)P * 3 * Lp * 8, 256);
   CL.qhist = o;   o = align_up(o + (size_t)P * QUANT_BINS * 4, 256);
-  CL.qstate = o;  o = align_up(o + (size_t)P * 4 * 8, 256);
+  CL.qstate = o;  o = align_up(o + (size_t)P * QUANT_STATE_WORDS * 8, 256);
+  CL.qlist = o;   o = align_up(o + (c.theta_quantile > 0.0 ? (size_t)P * QUANT_LISTS * QUANT_LIST_CAP * 8 : 0), 256);
   CL.lpart = o;   o = align_up(o + (c.rep_mode == LTRI_REP_DYNAMIC || c.seg_map == LTRI_MAP_SOFTMAX ? (size_t)P * G * nb * Lp * 16 : 0), 256);
   CL.loc_cap = (int)align_up((size_t)c.n_sink + c.window, ATT_BN) + ATT_BN;
   CL.att_lse2 = o;  o = align_up(o + (size_t)c.n_seqs * c.chunk_max * c.n_q_heads * 4, 256);
@@ -259,7 +260,8 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
                      (double*)(t + CL.qpart), (int32_t*)(t + CL.bounds), (uint8_t*)(t + CL.selflag), (float*)(t + CL.att_part),
                      (int32_t*)(t + CL.tokspan), (double*)(t + CL.dyn), (double*)(t + CL.lpart),
                      (uint32_t*)(t + CL.qhist), (unsigned long long*)(t + CL.qstate),
-                     (float*)(t + CL.att_lse2), (int32_t*)(t + CL.loclist), (int32_t*)(t + CL.tickets)};
+                     (float*)(t + CL.att_lse2), (int32_t*)(t + CL.loclist), (unsigned long long*)(t + CL.qlist),
+                     (int32_t*)(t + CL.tickets)};
   const size_t n = (size_t)D.n_layers * D.n_seqs;
   c->n_tokens.assign(n, 0);
   c->last_len.assign(n, 0);

@@ -26,6 +26,9 @@ constexpr int SEG_MAX_NB = SEG_MAX_L / SEG_TB;
 constexpr int SEG_MAX_DIAG = 2 * SEG_MAX_L;   // anti-diagonals of the largest map (2 L - 1), rounded up
 constexpr int QUANT_BITS = 11;               // digit width of the radix selection of the percentile theta
 constexpr int QUANT_BINS = 1 << QUANT_BITS;
+constexpr int QUANT_LISTS = 16;               // sub-lists per problem (a tile appends to list tile % 16: fewer atomics per counter)
+constexpr int QUANT_STATE_WORDS = 8 + QUANT_LISTS;   // per problem: key prefix, rank to go, theta (double bits), status, -, -, -, -, list lengths
+constexpr int QUANT_LIST_CAP = 1 << 14;      // cells collected for the final exact selection, at most
 constexpr int IDX_MASK_WORDS = SEG_MAX_L / 32;   // one bit per token of a chunk
 constexpr int ATT_BN = 64;               // keys per attention tile; token lists are padded to it
 constexpr int ATT_MAX_SPLITS = 16;       // key-range splits of a short query block (decode)
@@ -70,7 +73,8 @@ struct ScratchLayout {
   size_t tokspan;  // int32  [P][Lp]      span (within the chunk) of every token (dynamic index vectors)
   size_t dyn;      // double [P][3][Lp]   votes, in-span row sums, whole row sums of the softmax map
   size_t qhist;    // uint32 [P][QUANT_BINS]  histogram of one digit of the map cells' order keys (percentile theta)
-  size_t qstate;   // uint64 [P][4]   key prefix found so far, rank still to go, theta (double bits), unused
+  size_t qstate;   // uint64 [P][QUANT_STATE_WORDS]   key prefix found so far, rank still to go, theta (double bits), status, list length
+  size_t qlist;    // uint64 [P][QUANT_LISTS][QUANT_LIST_CAP]  order keys of the cells that share the prefix (percentile theta only)
   size_t lpart;    // double [P][G][nb][Lp][2]  per tile: row maximum and sum of exponentials (row log-sum-exp in pieces)
   size_t att_lse2; // float  [n_seqs][chunk_max][Hq]  log-sum-exp of the first part of an overlapped step
   size_t loclist;  // int32  [n_seqs][loc_cap]  initial | window tokens (overlapped step)
@@ -132,6 +136,7 @@ struct DevScratch {
   double* pscore; int32_t* px; uint64_t* ckey; uint32_t* cxy; double* lse; void* qrep; double* qpart; int32_t* bounds; uint8_t* selflag; float* att_part;
   int32_t* tokspan; double* dyn; double* lpart; uint32_t* qhist; unsigned long long* qstate;
   float* att_lse2; int32_t* loclist;
+  unsigned long long* qlist;
   int32_t* tickets;   // [2][max_problems] counters of finished workgroups; zero between launches
 };
 

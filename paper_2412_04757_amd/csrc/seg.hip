@@ -154,11 +154,19 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
 }
 
 // ---- theta as a percentile of the map (Sec. 4, "Hyperparameter Tuning") ----
-// Exact selection of the cell of a given rank by digits of an order-preserving 64-bit key, most
-// significant digit first: every pass recomputes the tiles, counts the cells that share the key
-// prefix found so far by their next digit (LDS histogram, then integer atomics, so the result does
-// not depend on the order of execution), and a one-workgroup kernel picks the digit that holds the
-// rank. qstate[p] = {prefix, rank still to go, theta as double bits, -}.
+// Exact selection of the cell of a given rank, without storing the map. The cells are ordered by an
+// order-preserving 64-bit key. A pass over the recomputed tiles either counts the cells that share the key prefix
+// found so far by their next 11-bit digit (LDS histogram, then integer atomics, so the result does not depend on
+// the order of execution), after which a one-workgroup step picks the digit that holds the rank; or, once at
+// most QUANT_LIST_CAP cells share the prefix, appends their keys to a list, and the one-workgroup step finishes
+// the selection on the list. Three (tile pass, pick) pairs are launched: for maps whose cells are not massively
+// tied that is two counting passes and one collecting pass (one collecting pass for chunks of up to 180 tokens).
+// A last kernel, one workgroup per problem, finishes whatever is left by walking the tiles itself (it returns at
+// once when the selection is done): ties of more than QUANT_LIST_CAP cells within 2^-10 relative cost time there,
+// not correctness.
+// qstate[p] = {prefix, rank still to go, theta as double bits, status, -, -, -, -, lengths of the 16 sub-lists};
+// status = cells that share the prefix | digits fixed << 32 | done << 63. The state is read and written at
+// device scope: in the last kernel the same workgroup writes it and reads it back.
 __device__ __forceinline__ uint64_t ascending_key(double v) {
   const uint64_t u = (uint64_t)__double_as_longlong(v + 0.0);        // -0.0 -> +0.0
   return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
@@ -167,67 +175,242 @@ __device__ __forceinline__ double key_to_double(uint64_t k) {
   const uint64_t u = (k >> 63) ? (k & 0x7fffffffffffffffull) : ~k;
   return __longlong_as_double((long long)u);
 }
-__host__ __device__ constexpr int quant_shift(int pass) { return 64 - QUANT_BITS * (pass + 1) > 0 ? 64 - QUANT_BITS * (pass + 1) : 0; }
-__host__ __device__ constexpr int quant_width(int pass) { return 64 - QUANT_BITS * pass >= QUANT_BITS ? QUANT_BITS : 64 - QUANT_BITS * pass; }
+__host__ __device__ constexpr int quant_shift(int digit) { return 64 - QUANT_BITS * (digit + 1) > 0 ? 64 - QUANT_BITS * (digit + 1) : 0; }
+__host__ __device__ constexpr int quant_width(int digit) { return 64 - QUANT_BITS * digit >= QUANT_BITS ? QUANT_BITS : 64 - QUANT_BITS * digit; }
 constexpr int QUANT_PASSES = (64 + QUANT_BITS - 1) / QUANT_BITS;
+constexpr int QUANT_TILE_PASSES = 3;                      // (tile pass, pick) pairs launched before the last kernel
+constexpr unsigned long long QUANT_DONE = 1ull << 63;
+__device__ __forceinline__ int quant_digits(unsigned long long status) { return (int)((status >> 32) & 0xFFull); }
+__device__ __forceinline__ unsigned long long quant_count(unsigned long long status) { return status & 0xFFFFFFFFull; }
+__device__ __forceinline__ unsigned long long qload(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void qstore(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
-__global__ __launch_bounds__(256) void quant_init_kernel(SegArgs a, unsigned long long rank) {
+struct QuantShared {
+  uint32_t hist[QUANT_BINS];
+  unsigned long long part[256];
+  unsigned long long prefix, rank, base, count;
+  unsigned long long wtot[4];
+  uint32_t len[QUANT_LISTS];
+  uint32_t cnt;
+  int digit;
+};
+
+__global__ __launch_bounds__(256) void quant_init_kernel(SegArgs a, unsigned long long rank, unsigned long long n_cells) {
   const int p = blockIdx.x;
   for (int b = threadIdx.x; b < QUANT_BINS; b += blockDim.x) a.sc.qhist[(size_t)p * QUANT_BINS + b] = 0u;
   if (threadIdx.x == 0) {
-    a.sc.qstate[p * 4 + 0] = 0ull;
-    a.sc.qstate[p * 4 + 1] = rank;
+    unsigned long long* st = a.sc.qstate + (size_t)p * QUANT_STATE_WORDS;
+    st[0] = 0ull;
+    st[1] = rank;
+    st[3] = n_cells;          // no digit fixed yet, not done
+    for (int j = 0; j < QUANT_LISTS; ++j) st[8 + j] = 0ull;
+  }
+}
+
+// One tile of a tile pass (all 256 threads; Ms holds the tile on return from compute_tile). status: the problem's
+// status word as read by the caller.
+template <int DT, int KIND>
+__device__ __forceinline__ void quant_tile_step(const SegArgs& a, int p, int I, int J, unsigned long long status,
+                                                double* Ms, QuantShared& S) {
+  unsigned long long* st = a.sc.qstate + (size_t)p * QUANT_STATE_WORDS;
+  const bool collect = quant_count(status) <= (unsigned long long)QUANT_LIST_CAP;
+  const int digit = quant_digits(status);
+  const int tid = threadIdx.x;
+  for (int b = tid; b < QUANT_BINS; b += blockDim.x) S.hist[b] = 0u;
+  if (tid == 0) S.cnt = 0u;
+  compute_tile<DT, KIND>(a, p, I, J, Ms);
+  __syncthreads();
+  const uint64_t prefix = qload(st + 0);
+  const int hi = 64 - QUANT_BITS * digit;                 // bits from here up are the prefix (64: none yet)
+  // a thread takes 16 consecutive cells of one row; a wavefront 64 consecutive rows (row pitch 65: no bank conflicts)
+  const int r = tid & 63, c0 = (tid >> 6) * 16, y = I * 64 + r;
+  auto matches = [&](int c, uint64_t& k) -> bool {
+    const int x = J * 64 + c;
+    if (!(x <= y && y < a.n_new)) return false;
+    k = ascending_key(Ms[r * 65 + c]);
+    return hi >= 64 || (k >> hi) == (prefix >> hi);
+  };
+  if (!collect) {
+    // neighbouring cells often share the digit (the first digit is sign and exponent): runs are counted in a
+    // register and added once
+    const int shift = quant_shift(digit), width = quant_width(digit);
+    uint32_t run_bin = 0xFFFFFFFFu, run = 0;
+    for (int c = c0; c < c0 + 16; ++c) {
+      uint64_t k;
+      if (!matches(c, k)) continue;
+      const uint32_t b = (uint32_t)(k >> shift) & ((1u << width) - 1u);
+      if (b != run_bin) {
+        if (run) atomicAdd(&S.hist[run_bin], run);
+        run_bin = b; run = 0;
+      }
+      ++run;
+    }
+    if (run) atomicAdd(&S.hist[run_bin], run);
+    __syncthreads();
+    for (int b = tid; b < QUANT_BINS; b += blockDim.x)
+      if (S.hist[b]) atomicAdd(&a.sc.qhist[(size_t)p * QUANT_BINS + b], S.hist[b]);
+    return;
+  }
+  // the cells that share the prefix go to the list: count, reserve a run of the list, write
+  uint32_t mine = 0;
+  for (int c = c0; c < c0 + 16; ++c) { uint64_t k; mine += matches(c, k) ? 1u : 0u; }
+  const uint32_t off = mine ? atomicAdd(&S.cnt, mine) : 0u;
+  __syncthreads();
+  const int sub = (I * (I + 1) / 2 + J) % QUANT_LISTS;   // the tile's sub-list
+  if (tid == 0) S.base = S.cnt ? atomicAdd(&st[8 + sub], (unsigned long long)S.cnt) : 0ull;
+  __syncthreads();
+  unsigned long long at = S.base + off;
+  unsigned long long* list = a.sc.qlist + ((size_t)p * QUANT_LISTS + sub) * QUANT_LIST_CAP;
+  for (int c = c0; c < c0 + 16 && mine; ++c) {
+    uint64_t k;
+    if (matches(c, k)) { if (at < (unsigned long long)QUANT_LIST_CAP) list[at] = k; ++at; }
+  }
+}
+
+// The step after a tile pass (all 256 threads of one workgroup per problem): after a counting pass, the digit
+// that holds the rank; after a collecting pass, the rest of the selection on the list (the same digit steps, over
+// the list's keys instead of the tiles).
+__device__ __forceinline__ void quant_pick_step(const SegArgs& a, int p, unsigned long long status, QuantShared& S) {
+  const int tid = threadIdx.x;
+  constexpr int PER = QUANT_BINS / 256;
+  unsigned long long* st = a.sc.qstate + (size_t)p * QUANT_STATE_WORDS;
+  const bool collected = quant_count(status) <= (unsigned long long)QUANT_LIST_CAP;
+  uint32_t* gh = a.sc.qhist + (size_t)p * QUANT_BINS;
+  // One digit step on the histogram in S.hist with S.part[t] = the sum of thread t's PER bins (all threads call
+  // it after a barrier; S.prefix / S.rank hold the state and are updated, S.count gets the picked bin's count):
+  // a scan of S.part over the workgroup finds the thread whose bins hold the rank, that thread walks its bins.
+  auto pick_digit = [&](int digit) {
+    const int lane = tid & 63, wave = tid >> 6;
+    const unsigned long long own = S.part[tid], rank = S.rank;
+    unsigned long long incl = own;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned long long v = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += v;
+    }
+    if (lane == 63) S.wtot[wave] = incl;
+    __syncthreads();
+    for (int w = 0; w < wave; ++w) incl += S.wtot[w];
+    const unsigned long long excl = incl - own;
+    // exactly one thread holds the rank; the last one also takes a rank beyond the total (cannot happen with
+    // consistent counts)
+    if (rank >= excl && (rank < incl || tid == 255)) {
+      unsigned long long below = excl;
+      int b = tid * PER;
+      while (b < tid * PER + PER - 1 && below + S.hist[b] <= rank) { below += S.hist[b]; ++b; }
+      S.prefix |= (uint64_t)b << quant_shift(digit);
+      S.rank = rank - below;
+      S.count = S.hist[b];
+    }
+    __syncthreads();
+  };
+  __syncthreads();
+  if (tid == 0) { S.prefix = qload(st + 0); S.rank = qload(st + 1); S.digit = quant_digits(status); }
+  if (!collected) {
+    unsigned long long mine = 0;
+    for (int e = 0; e < PER; ++e) {
+      const uint32_t v = atomicExch(&gh[tid * PER + e], 0u);        // read and clear for the next pass
+      S.hist[tid * PER + e] = v;
+      mine += v;
+    }
+    S.part[tid] = mine;
+    __syncthreads();
+    const int digit = S.digit;
+    pick_digit(digit);
+    if (tid == 0) {
+      qstore(st + 0, S.prefix);
+      qstore(st + 1, S.rank);
+      const bool last = digit + 1 == QUANT_PASSES;
+      if (last) qstore(st + 2, (unsigned long long)__double_as_longlong(key_to_double(S.prefix)));
+      qstore(st + 3, S.count | ((unsigned long long)(digit + 1) << 32) | (last ? QUANT_DONE : 0ull));
+    }
+    return;
+  }
+  // the lists hold every cell that shares the prefix: the remaining digits on the lists
+  // (plain loads: nothing of the lists was in this compute unit's cache before they were written)
+  const unsigned long long* lists = a.sc.qlist + (size_t)p * QUANT_LISTS * QUANT_LIST_CAP;
+  if (tid < QUANT_LISTS) {
+    const unsigned long long n_raw = qload(st + 8 + tid);
+    S.len[tid] = (uint32_t)(n_raw < (unsigned long long)QUANT_LIST_CAP ? n_raw : (unsigned long long)QUANT_LIST_CAP);
+  }
+  __syncthreads();
+  const int first_digit = S.digit;
+  // the first 256 entries of every sub-list stay in registers over the digit steps (one independent load each);
+  // longer sub-lists are walked again per digit
+  unsigned long long kreg[QUANT_LISTS];
+#pragma unroll
+  for (int j = 0; j < QUANT_LISTS; ++j) kreg[j] = (uint32_t)tid < S.len[j] ? lists[(size_t)j * QUANT_LIST_CAP + tid] : 0ull;
+  for (int digit = first_digit; digit < QUANT_PASSES; ++digit) {
+    for (int e = 0; e < PER; ++e) S.hist[tid * PER + e] = 0u;
+    __syncthreads();
+    const unsigned long long prefix = S.prefix;
+    const int shift = quant_shift(digit), width = quant_width(digit), hi = 64 - QUANT_BITS * digit;
+    auto count_key = [&](unsigned long long k) {
+      if (hi >= 64 || (k >> hi) == (prefix >> hi)) atomicAdd(&S.hist[(uint32_t)(k >> shift) & ((1u << width) - 1u)], 1u);
+    };
+#pragma unroll
+    for (int j = 0; j < QUANT_LISTS; ++j)
+      if ((uint32_t)tid < S.len[j]) count_key(kreg[j]);
+    for (int j = 0; j < QUANT_LISTS; ++j) {
+      const unsigned long long* list = lists + (size_t)j * QUANT_LIST_CAP;
+      for (uint32_t i = tid + 256; i < S.len[j]; i += 256) count_key(list[i]);
+    }
+    __syncthreads();
+    unsigned long long mine = 0;
+    for (int e = 0; e < PER; ++e) mine += S.hist[tid * PER + e];
+    S.part[tid] = mine;
+    __syncthreads();
+    pick_digit(digit);
+  }
+  if (tid == 0) {
+    qstore(st + 0, S.prefix);
+    qstore(st + 1, S.rank);
+    qstore(st + 2, (unsigned long long)__double_as_longlong(key_to_double(S.prefix)));
+    qstore(st + 3, QUANT_DONE);
   }
 }
 
 template <int DT, int KIND>
-__global__ __launch_bounds__(256) void quant_hist_kernel(SegArgs a, int pass) {
+__global__ __launch_bounds__(256) void quant_tile_kernel(SegArgs a) {
   __shared__ double Ms[64 * 65];
-  __shared__ uint32_t hist[QUANT_BINS];
+  __shared__ QuantShared S;
   const int p = blockIdx.y;
+  const unsigned long long status = qload(a.sc.qstate + (size_t)p * QUANT_STATE_WORDS + 3);
+  if (status & QUANT_DONE) return;                        // the same for every workgroup of the problem
   int I, J;
   tile_decode(blockIdx.x, I, J);
-  const int tid = threadIdx.x;
-  for (int b = tid; b < QUANT_BINS; b += blockDim.x) hist[b] = 0u;
-  compute_tile<DT, KIND>(a, p, I, J, Ms);
-  __syncthreads();
-  const int shift = quant_shift(pass), width = quant_width(pass);
-  const uint64_t prefix = a.sc.qstate[p * 4 + 0];
-  const int hi = shift + width;                         // bits above the digit are the prefix
-  for (int q = tid; q < 64 * 64; q += blockDim.x) {
-    const int r = q >> 6, c = q & 63;
-    const int y = I * 64 + r, x = J * 64 + c;
-    if (x <= y && y < a.n_new) {
-      const uint64_t k = ascending_key(Ms[r * 65 + c]);
-      const bool match = hi >= 64 || (k >> hi) == (prefix >> hi);
-      if (match) atomicAdd(&hist[(uint32_t)(k >> shift) & ((1u << width) - 1u)], 1u);
-    }
-  }
-  __syncthreads();
-  for (int b = tid; b < QUANT_BINS; b += blockDim.x)
-    if (hist[b]) atomicAdd(&a.sc.qhist[(size_t)p * QUANT_BINS + b], hist[b]);
+  quant_tile_step<DT, KIND>(a, p, I, J, status, Ms, S);
 }
 
-__global__ __launch_bounds__(256) void quant_pick_kernel(SegArgs a, int pass) {
-  __shared__ uint32_t h[QUANT_BINS];
-  __shared__ unsigned long long part[256];
-  const int p = blockIdx.x, tid = threadIdx.x;
-  constexpr int PER = QUANT_BINS / 256;
-  uint32_t* gh = a.sc.qhist + (size_t)p * QUANT_BINS;
-  unsigned long long mine = 0;
-  for (int e = 0; e < PER; ++e) { h[tid * PER + e] = gh[tid * PER + e]; mine += h[tid * PER + e]; gh[tid * PER + e] = 0u; }
-  part[tid] = mine;
-  __syncthreads();
-  if (tid == 0) {
-    unsigned long long rank = a.sc.qstate[p * 4 + 1], below = 0;
-    int t = 0;
-    while (t < 255 && below + part[t] <= rank) { below += part[t]; ++t; }
-    int b = t * PER;
-    while (b < QUANT_BINS - 1 && below + h[b] <= rank) { below += h[b]; ++b; }
-    const uint64_t prefix = a.sc.qstate[p * 4 + 0] | ((uint64_t)b << quant_shift(pass));
-    a.sc.qstate[p * 4 + 0] = prefix;
-    a.sc.qstate[p * 4 + 1] = rank - below;
-    if (pass == QUANT_PASSES - 1) a.sc.qstate[p * 4 + 2] = (unsigned long long)__double_as_longlong(key_to_double(prefix));
+__global__ __launch_bounds__(256) void quant_pick_kernel(SegArgs a) {
+  __shared__ QuantShared S;
+  const int p = blockIdx.x;
+  const unsigned long long status = qload(a.sc.qstate + (size_t)p * QUANT_STATE_WORDS + 3);
+  if (status & QUANT_DONE) return;
+  quant_pick_step(a, p, status, S);
+}
+
+// Whatever the three launched pairs left undone, one workgroup per problem walking all tiles itself.
+template <int DT, int KIND>
+__global__ __launch_bounds__(256) void quant_finish_kernel(SegArgs a) {
+  __shared__ double Ms[64 * 65];
+  __shared__ QuantShared S;
+  const int p = blockIdx.x;
+  for (int it = 0; it < QUANT_PASSES; ++it) {
+    const unsigned long long status = qload(a.sc.qstate + (size_t)p * QUANT_STATE_WORDS + 3);
+    if (status & QUANT_DONE) return;                      // uniform: every thread reads the same word
+    for (int t = 0; t < a.ntiles; ++t) {
+      int I, J;
+      tile_decode(t, I, J);
+      quant_tile_step<DT, KIND>(a, p, I, J, status, Ms, S);
+      __syncthreads();
+    }
+    quant_pick_step(a, p, status, S);
+    __syncthreads();
   }
 }
 
@@ -355,7 +538,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
     const int x = J * 64 + c;
     const int n_h = a.q_seg ? a.D.G : 1;
     // Eq. 5's theta per head, times the heads summed; a percentile of the map is already per summed cell
-    const double th = a.D.theta_quantile > 0.0 ? __longlong_as_double((long long)a.sc.qstate[p * 4 + 2])
+    const double th = a.D.theta_quantile > 0.0 ? __longlong_as_double((long long)a.sc.qstate[(size_t)p * QUANT_STATE_WORDS + 2])
                                                : (double)a.D.theta * (double)n_h;
     double run = (((cpart[0][c] + cpart[1][c]) + cpart[2][c]) + cpart[3][c]) +
                  (((tpart[0] + tpart[1]) + tpart[2]) + tpart[3]);      // the column carry
@@ -1179,11 +1362,12 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
     if (D.theta_quantile > 0.0) {
       const double n_cells = (double)n_new * (double)(n_new + 1) / 2.0;
       const unsigned long long rank = (unsigned long long)floor(D.theta_quantile * (n_cells - 1.0));
-      quant_init_kernel<<<P, 256, 0, s>>>(a, rank);
-      for (int pass = 0; pass < QUANT_PASSES; ++pass) {
-        quant_hist_kernel<DT, KIND><<<gt, 256, 0, s>>>(a, pass);
-        quant_pick_kernel<<<P, 256, 0, s>>>(a, pass);
+      quant_init_kernel<<<P, 256, 0, s>>>(a, rank, (unsigned long long)n_cells);
+      for (int pass = 0; pass < QUANT_TILE_PASSES; ++pass) {
+        quant_tile_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
+        quant_pick_kernel<<<P, 256, 0, s>>>(a);
       }
+      quant_finish_kernel<DT, KIND><<<P, 256, 0, s>>>(a);
     }
     seg_tile_sums_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
     seg_tile_scan_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
