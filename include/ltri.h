@@ -202,6 +202,14 @@ int32_t ltri_sel_capacity(const ltri_ctx* ctx);
 int32_t ltri_get_index_tokens(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head,
                               uint32_t* mask_host, int32_t cap_words);
 
+/* theta_quantile > 0, introspection (synchronises the stream): the threshold that the segmentation of the chunk
+ * appended last used for (layer, seq, kv_head), i.e. the cell of rank floor(q (n - 1)) of the chunk's head-summed
+ * map in ascending order (Sec. 4, "Hyperparameter Tuning": the threshold as a percentile of the map). The device
+ * keeps it only for the sequences of the last segmentation launch (up to four sequences of the last
+ * ltri_append_chunk / ltri_step call, the last ones of a larger batch). ESTATE in a dry context, without
+ * theta_quantile, for a one-token chunk, or for another layer or sequence than those. */
+int32_t ltri_get_theta(ltri_ctx* ctx, int32_t layer, int32_t seq, int32_t kv_head, double* theta_host);
+
 /* Collaborative voting (Sec. 3.5, Collaborative Voting), with retrieval by memory units
  * (unit_tokens > 0, EINVAL otherwise). Step 2 of `layer` in which the earlier layers take part:
  * the layer first selects units on its own as ltri_retrieve does; then every earlier layer l with

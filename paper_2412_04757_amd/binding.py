@@ -30,7 +30,8 @@ EXPORTED_SYMBOLS = [
     "ltri_sel_capacity",
     "ltri_force_selection", "ltri_attend", "ltri_attend_static", "ltri_step", "ltri_gather_pack", "ltri_list_capacity",
     "ltri_sync_status", "ltri_token_count", "ltri_span_count", "ltri_get_spans",
-    "ltri_get_rep_keys", "ltri_get_selection", "ltri_get_token_list", "ltri_get_index_tokens", "ltri_strerror",
+    "ltri_get_rep_keys", "ltri_get_selection", "ltri_get_token_list", "ltri_get_index_tokens", "ltri_get_theta",
+    "ltri_strerror",
     "ltri_last_error", "ltri_version",
     # include/ltri_bench.h: measurement helpers, not part of the product boundary
     "ltri_measure_mfma_peak", "ltri_measure_copy_peak", "ltri_measure_read_peak",
@@ -102,6 +103,7 @@ def load_library() -> C.CDLL:
         "ltri_get_selection": [vp, i32, i32, i32, pi32, i32, pi32, C.POINTER(C.c_double)],
         "ltri_get_token_list": [vp, i32, i32, i32, pi32, i32, pi32],
         "ltri_get_index_tokens": [vp, i32, i32, i32, C.POINTER(C.c_uint32), i32],
+        "ltri_get_theta": [vp, i32, i32, i32, C.POINTER(C.c_double)],
         "ltri_measure_mfma_peak": [vp, C.c_size_t, i32, vp, C.POINTER(C.c_double)],
         "ltri_measure_copy_peak": [vp, vp, C.c_size_t, vp, C.POINTER(C.c_double)],
         "ltri_measure_read_peak": [vp, C.c_size_t, vp, C.c_size_t, vp, C.POINTER(C.c_double)],
@@ -367,6 +369,12 @@ class LtriContext:
                                                    words.ctypes.data_as(C.POINTER(C.c_uint32)), len(words)), None)
         bits = np.unpackbits(words.view(np.uint8), bitorder="little")[:chunk_len]
         return np.flatnonzero(bits).astype(np.int64)
+
+    def get_theta(self, layer: int, seq: int, kv_head: int) -> float:
+        """The percentile threshold the last append used for (layer, seq, kv_head) (ltri_get_theta)."""
+        out = C.c_double()
+        self._check(self.lib.ltri_get_theta(self.handle, layer, seq, kv_head, C.byref(out)), None)
+        return out.value
 
 
 def measure_mfma_peak(device, random_operands: bool = False) -> float:

@@ -39,6 +39,8 @@ struct ltri_ctx {
   std::vector<long long> span_bound;     // upper bound on the spans stored per KV head
   std::vector<uint32_t> have_sel;        // bit h set: KV head h has a selection for the last chunk
   std::vector<uint32_t> ever_sel;        // bit h set: KV head h has had a selection since the last reset
+  // sequences whose percentile threshold the device still holds (the last segmentation launch): layer, first, count
+  int theta_layer = -1, theta_seq0 = 0, theta_seqs = 0;
   std::string err;
 };
 
@@ -431,6 +433,7 @@ static int32_t append_spans(ltri_ctx* c, int layer, const BatchPos& bp, int seq_
                     "index vectors");
       if (r != LTRI_OK) return r;
     }
+    c->theta_layer = layer; c->theta_seq0 = bp.seq[off]; c->theta_seqs = cnt;
   }
   if (c->D.rep_mode == LTRI_REP_MEAN && !rep_keys_later) {   // later: step 2's first launch stores them as well
     r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, seq_count, n_new, c->stream),
@@ -972,6 +975,20 @@ int32_t ltri_get_index_tokens(ltri_ctx* c, int32_t layer, int32_t seq, int32_t h
   if (len == 1) { mask_host[0] = 1u; return LTRI_OK; }     // a one-token chunk is its own index token
   const int slot = (layer * c->D.n_seqs + seq) * c->D.Hkv + h;
   return read_dev(c, mask_host, c->ds.idx_mask + (size_t)slot * IDX_MASK_WORDS, (size_t)words * 4);
+}
+
+int32_t ltri_get_theta(ltri_ctx* c, int32_t layer, int32_t seq, int32_t h, double* theta_host) {
+  int32_t r = check_slot(c, layer, seq, h);
+  if (r != LTRI_OK) return r;
+  if (!theta_host) return fail(c, LTRI_EINVAL, "theta_host is NULL");
+  if (c->dry) return fail(c, LTRI_ESTATE, "a dry context runs no kernels");
+  if (!(c->D.theta_quantile > 0.0)) return fail(c, LTRI_ESTATE, "the context uses an absolute threshold");
+  if (c->last_len[ls_index(c, layer, seq)] <= 1) return fail(c, LTRI_ESTATE, "no chunk of more than one token appended last");
+  if (layer != c->theta_layer || seq < c->theta_seq0 || seq >= c->theta_seq0 + c->theta_seqs)
+    return fail(c, LTRI_ESTATE, "the device holds the thresholds of layer %d, sequences %d .. %d only", c->theta_layer,
+                c->theta_seq0, c->theta_seq0 + c->theta_seqs - 1);
+  const size_t p = (size_t)(seq - c->theta_seq0) * c->D.Hkv + h;
+  return read_dev(c, theta_host, c->dc.qstate + p * QUANT_STATE_WORDS + 2, sizeof(double));
 }
 
 }  // extern "C"

@@ -199,6 +199,12 @@ def test_call_order_and_limits_in_dry_mode():
         assert e.value.status == -1, bad
     ctx.append_chunk_with_spans(0, 0, 16, [np.array([0, 4, 16])])
     assert ctx.token_count(0, 0) == 16
+    with pytest.raises(LtriError) as e:
+        ctx.get_theta(0, 0, 0)
+    assert e.value.status == -2                      # a dry context selects no threshold
+    with pytest.raises(LtriError) as e:
+        ctx.get_theta(0, 0, 9)
+    assert e.value.status == -1                      # KV head out of range
     ctx.close()
 
 

@@ -613,6 +613,35 @@ def test_theta_as_a_percentile_of_the_map(gpu_device):
     assert n_unstable == 0 and len(st.starts[0]) > 8
 
 
+def test_percentile_theta_value(gpu_device):
+    """The threshold the device selects (ltri_get_theta) against the oracle's sort of the map's cells, where the
+    spans cannot tell: ordinary planted chunks (two counting passes and a collecting pass at 512 tokens, one
+    collecting pass at 150), and maps that are massively tied, where the counting passes never narrow the bucket
+    down to the collecting size and the one-workgroup kernel finishes by walking the tiles itself: every cell equal
+    (constant keys), and two constant halves (three cell values, tens of thousands of cells each). The device's
+    cells carry fp32 matrix-core error, so the values agree to 1e-5 relative; on the tied maps that is what tells a
+    right digit from a wrong one."""
+    w = Workload("mini-tied", 8, 2, 128, "bf16", 1024, 512, 4, 128, 0, 300, "uniform", 16, 128)
+    T = 1024
+    K0, V, _, _ = planted_stream(w, 5, device=str(gpu_device), context=T)
+    const = K0[:, :1, :].expand(-1, T, -1).contiguous()        # one key row per KV head, repeated
+    halves = torch.cat([K0[:, :1, :].expand(-1, 300, -1), K0[:, 1:2, :].expand(-1, T - 300, -1)], dim=1).contiguous()
+    for K, sizes, q in ((K0, [512, 150, 362], 0.9), (const, [512, 512], 0.9), (halves, [512, 512], 0.5),
+                        (halves, [512, 512], 0.97)):
+        ctx, st = make_pair(w, K, V, gpu_device, max_tokens=T, theta=99.0, theta_quantile=q, max_spans=1024)
+        Kn = K.double().cpu().numpy()
+        c0 = 0
+        for n in sizes:
+            ctx.append_chunk(0, 0, 1, n)
+            for h in range(w.n_kv_heads):
+                M = O.chunk_map(Kn[h, c0:c0 + n], None, O.MAP_LOGIT)[0]
+                want = O.map_quantile(M, q)
+                got = ctx.get_theta(0, 0, h)
+                assert abs(got - want) <= 1e-5 * max(1.0, abs(want)), (q, c0, n, h, got, want)
+            c0 += n
+        assert ctx.sync_status() in (0, -3)                    # a tied map may cut into more spans than the table holds
+
+
 def test_dynamic_index_vectors_batched_sequences(gpu_device):
     """Six sequences appended in one call (the segmentation scratch holds four at a time): index
     tokens and stored vectors of the first and the last sequence against the oracle."""
