@@ -291,3 +291,11 @@ def test_host_offloaded_kv_rules_in_dry_mode():
     ctx.step(0, 0, 1, _FakeQ(256), _FakeQ(256), _FakeQ(256))
     assert ctx.token_count(0, 0) == 512
     ctx.close()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N > 1 exits with a message before it touches a device."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
