@@ -341,8 +341,9 @@ def main():
                     help="segment chunk c+1 on a second stream next to attend(c) (measured: no gain, the kernels\n"
                          "compete for the same compute units)")
     ap.add_argument("--schedule", choices=["calls", "step"], default="step",
-                    help="calls: append, retrieve, attend one after the other; step: ltri_step per chunk (the "
-                         "attention over initial | window | chunk runs beside steps 1 and 2 on a second stream)")
+                    help="calls: append, retrieve, attend one after the other; step: ltri_step per chunk (one stream "
+                         "and fused step-2 kernels; with --kv-offload the attention over initial | window | chunk "
+                         "runs beside steps 1 and 2 on a second stream)")
     ap.add_argument("--attend-stages", type=int, default=0, choices=[0, 3, 4],
                     help="LDS ring depth of the attention kernel (default: the library's)")
     ap.add_argument("--index-vectors", choices=["mean", "dynamic"], default="mean",

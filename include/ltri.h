@@ -11,9 +11,10 @@
  *                               representatives (Eq. 8) and pick the top spans (Eq. 9);
  *   step 3  ltri_attend         exact attention of the query chunk over
  *                               initial | retrieved | window | current tokens.
- *   all     ltri_step           the three in one call, scheduled on two streams so that the
- *                               part of step 3 that does not depend on step 2 runs beside
- *                               steps 1 and 2.
+ *   all     ltri_step           the three in one call: fused kernels on one stream when the
+ *                               keys and values are resident on the device; with evicted rows
+ *                               in host memory the part of step 3 that does not depend on
+ *                               step 2 runs on a second stream beside steps 1 and 2.
  *
  * Conventions
  *   - Every function returns an int32 status: 0 = LTRI_OK, negative = error. Nothing
@@ -25,9 +26,9 @@
  *     allocator) and keeps them alive until ltri_destroy(). The library owns only the
  *     host-side ltri_ctx.
  *   - All device work is enqueued on the stream given at creation and the call returns
- *     without waiting, except the introspection calls marked "synchronises". ltri_step also
- *     uses a second stream and two events that the context creates and owns; its results are
- *     ordered on the context's stream like everyone else's.
+ *     without waiting, except the introspection calls marked "synchronises". With kv_offload
+ *     ltri_step also uses a second stream and two events that the context creates and owns; its
+ *     results are ordered on the context's stream like everyone else's.
  *   - Tensors are dense, row-major, in the configured dtype (fp32 or bf16):
  *       KV arenas  [n_layers][n_seqs][n_kv_heads][max_tokens][head_dim]
  *       queries    [seq_count][n_q][n_q_heads][head_dim]

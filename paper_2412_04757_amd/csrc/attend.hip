@@ -20,15 +20,15 @@ struct AttArgs {
   Dims D; DevState st; const void* k_arena; const void* v_arena; const void* q;
   void* out; float* lse; int layer; int seq_count; int n_q;
   int n_splits; float* part;             // short query blocks: the key range is split over workgroups
-  int part_mode;                         // ATT_ALL, or one of the two parts of an overlapped step
+  int part_mode;                         // ATT_ALL, or one of the two parts of a two-part step
   const int32_t* loclist; int loc_cap;   // ATT_LOCAL: initial | window tokens per sequence [seq_count][loc_cap]
   const float* lse_a;                    // ATT_RETRIEVED: log-sum-exp of the first part, whose output is in `out`
   BatchPos bp;
 };
 
-// An overlapped step attends in two parts: the one that does not depend on the retrieval (initial
-// and window tokens and the chunk itself) can run while the chunk is still being segmented and
-// its spans scored; the retrieved tokens follow, and that launch folds the first part's result
+// A step whose retrieved rows first have to come from host memory attends in two parts: the one that does
+// not depend on the retrieval (initial and window tokens and the chunk itself) runs while the chunk is being
+// segmented, its spans scored and the rows fetched; the retrieved tokens follow, and that launch folds the first part's result
 // (already in `out`, with its log-sum-exp) into its own when it writes.
 enum : int { ATT_ALL = 0, ATT_LOCAL = 1, ATT_RETRIEVED = 2 };
 
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(AttArgs a) {
   const unsigned char* Kb = reinterpret_cast<const unsigned char*>(a.k_arena) + arena_off(D, slot) * 2;
   const unsigned char* Vb = reinterpret_cast<const unsigned char*>(a.v_arena) + arena_off(D, slot) * 2;
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
-  // the context list is initial | retrieved | window; the two parts of an overlapped step read
+  // the context list is initial | retrieved | window; the two parts of a two-part step read
   // initial | window from a list of their own, or the retrieved slice of the full list
   const int n_init = min(D.n_sink, c0), n_win = c0 - max(n_init, c0 - D.window);
   int list_len = meta[META_LIST_LEN];
@@ -695,7 +695,7 @@ __global__ __launch_bounds__(64 * DEC_WAVES, 3) void attend_decode_kernel(AttArg
   }
 }
 
-// ---- first part of an overlapped step: its token list ----
+// ---- first part of a two-part step: its token list ----
 // initial | window tokens of every sequence of the batch, padded with token 0 to whole tiles
 __global__ __launch_bounds__(256) void local_list_kernel(Dims D, BatchPos bp, int32_t* loclist, int loc_cap) {
   const int bi = blockIdx.y, c0 = bp.c0[bi];

@@ -23,13 +23,14 @@ struct ltri_ctx {
   DevScratch dc;
   bool dry;
   int attend_stages;                     // LDS ring depth of the bf16 attention kernel (3 or 4)
-  int step_stages;                       // the same for the two parts of an overlapped step
-  // second stream and the fork / join events of an overlapped step
+  int step_stages;                       // the same for the two parts of a step with host-offloaded keys and values
+  // second stream and the fork / join events of such a step
   hipStream_t side; hipEvent_t ev_fork, ev_join;
   int n_cus;                             // compute units of the device
   float* static_part;                    // the library's own buffer for partial attention results on this context's device
-  // optional timing of the attention launches of ltri_step: four events per step (first part on the second stream,
-  // retrieved part on the context's stream), reused after every read
+  // optional timing of the attention launches of ltri_step: four events per step (around the one launch and an
+  // empty interval, or around the first part on the second stream and the retrieved part on the context's
+  // stream), reused after every read
   bool step_timing;
   std::vector<hipEvent_t> tev;
   size_t tev_used;
@@ -298,7 +299,7 @@ int32_t ltri_create_dry(const ltri_config* cfg, ltri_ctx** out) {
 
 int32_t ltri_destroy(ltri_ctx* c) {
   if (!c) return LTRI_EINVAL;
-  if (c->side) {      // work of an overlapped step may still be queued there
+  if (c->side) {      // work of a two-part step may still be queued there
     (void)hipStreamSynchronize(c->side);
     (void)hipStreamDestroy(c->side);
   }

@@ -76,8 +76,8 @@ struct ScratchLayout {
   size_t qstate;   // uint64 [P][QUANT_STATE_WORDS]   key prefix found so far, rank still to go, theta (double bits), status, list length
   size_t qlist;    // uint64 [P][QUANT_LISTS][QUANT_LIST_CAP]  order keys of the cells that share the prefix (percentile theta only)
   size_t lpart;    // double [P][G][nb][Lp][2]  per tile: row maximum and sum of exponentials (row log-sum-exp in pieces)
-  size_t att_lse2; // float  [n_seqs][chunk_max][Hq]  log-sum-exp of the first part of an overlapped step
-  size_t loclist;  // int32  [n_seqs][loc_cap]  initial | window tokens (overlapped step)
+  size_t att_lse2; // float  [n_seqs][chunk_max][Hq]  log-sum-exp of the first part of a two-part step
+  size_t loclist;  // int32  [n_seqs][loc_cap]  initial | window tokens (two-part step)
   size_t tickets;  // int32  [2][P]  finished workgroups per problem (step 2 of long chunks); zero between launches
   size_t total;
   int    loc_cap;       // entries of one sequence's initial | window list, whole tiles plus one
