@@ -87,6 +87,11 @@ template <> struct TileDot<LTRI_F32> {
   }
 };
 
+// e^x of a softmax cell in fp32 (hardware exponential of x log2 e): the logits come off the matrix cores with
+// fp32 accumulation, so a cell carries a relative error of about 1e-6 already, and an fp64 exponential (some forty
+// instructions) bought nothing. -inf gives 0.
+__device__ __forceinline__ float exp2_f32(double x) { return __builtin_amdgcn_exp2f((float)(x * 1.4426950408889634)); }
+
 // Leaves the head-summed map tile (rows I*64.., columns J*64..) in Ms[r * 65 + c] as doubles;
 // cells above the diagonal or outside the chunk are 0. Called by all 256 threads; Ms doubles as
 // the staging area of the operands (2 x 16 KB) before the tile values are written.
@@ -131,7 +136,7 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int i = I * 64 + wi * 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-        m[v] += exp((double)acc[v] * scale - lse[min(i, L - 1)]);
+        m[v] += (double)exp2_f32((double)acc[v] * scale - lse[min(i, L - 1)]);
       }
     }
   }
@@ -808,6 +813,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void lse_tile_kernel(SegArgs a) {
   typedef typename Elt<DT>::type T;
   __shared__ double Ms[64 * 65];
+  __shared__ double rmax[4][64], rsum[4][64];
   const Dims& D = a.D;
   const int p = blockIdx.y;
   int I, J;
@@ -843,24 +849,25 @@ __global__ __launch_bounds__(256) void lse_tile_kernel(SegArgs a) {
       Ms[rl * 65 + wj * 32 + l32] = (jcol <= i && i < L) ? (double)acc[v] * scale : -INFINITY;
     }
     __syncthreads();
-    {                                     // four threads per row, 16 columns each
-      const int r = tid >> 2, qd = tid & 3;
+    {                                     // four threads per row, 16 columns each; a wavefront takes 64
+      const int r = tid & 63, qd = tid >> 6;    // consecutive rows (row pitch 65: no bank conflicts)
       double z[16];
       double mx = -INFINITY;
 #pragma unroll
       for (int c = 0; c < 16; ++c) { z[c] = Ms[r * 65 + qd * 16 + c]; mx = fmax(mx, z[c]); }
-      mx = fmax(mx, __shfl_xor(mx, 1, 64));
-      mx = fmax(mx, __shfl_xor(mx, 2, 64));
+      rmax[qd][r] = mx;
+      __syncthreads();
+      mx = fmax(fmax(rmax[0][r], rmax[1][r]), fmax(rmax[2][r], rmax[3][r]));
       double sm = 0.0;
       if (mx > -INFINITY) {
 #pragma unroll
-        for (int c = 0; c < 16; ++c) sm += exp(z[c] - mx);
+        for (int c = 0; c < 16; ++c) sm += (double)exp2_f32(z[c] - mx);
       }
-      sm += __shfl_xor(sm, 1, 64);
-      sm += __shfl_xor(sm, 2, 64);
+      rsum[qd][r] = sm;
+      __syncthreads();
       if (qd == 0) {
         double* o = a.sc.lpart + ((((size_t)p * n_h + g) * a.nb + J) * a.Lp + I * 64 + r) * 2;
-        o[0] = mx; o[1] = sm;
+        o[0] = mx; o[1] = ((rsum[0][r] + rsum[1][r]) + rsum[2][r]) + rsum[3][r];
       }
     }
     __syncthreads();
@@ -909,7 +916,7 @@ __global__ __launch_bounds__(256) void dyn_token_span_kernel(SegArgs a) {
 template <int DT>
 __global__ __launch_bounds__(256) void dyn_tile_kernel(SegArgs a) {
   __shared__ double Ms[64 * 65];
-  __shared__ double cpart[4][64];
+  __shared__ double cpart[4][64], rpart[4][64], ipart[4][64];
   __shared__ int rspan[64], cspan[64];
   const int p = blockIdx.y;
   int I, J;
@@ -919,8 +926,8 @@ __global__ __launch_bounds__(256) void dyn_tile_kernel(SegArgs a) {
   if (tid < 64) rspan[tid] = a.sc.tokspan[(size_t)p * a.Lp + I * 64 + tid];
   else if (tid < 128) cspan[tid - 64] = a.sc.tokspan[(size_t)p * a.Lp + J * 64 + tid - 64];
   __syncthreads();
-  {                                       // rows: four threads per row, 16 columns each
-    const int r = tid >> 2, qd = tid & 3;
+  {                                       // rows: four threads per row, 16 columns each; a wavefront takes 64
+    const int r = tid & 63, qd = tid >> 6;  // consecutive rows (row pitch 65: no bank conflicts)
     const int mine = rspan[r];
     double s = 0.0, sin = 0.0;
 #pragma unroll
@@ -929,12 +936,8 @@ __global__ __launch_bounds__(256) void dyn_tile_kernel(SegArgs a) {
       s += v;
       sin += cspan[qd * 16 + c] == mine ? v : 0.0;
     }
-    s += __shfl_xor(s, 1, 64);   sin += __shfl_xor(sin, 1, 64);
-    s += __shfl_xor(s, 2, 64);   sin += __shfl_xor(sin, 2, 64);
-    if (qd == 0) {
-      a.sc.rowsum[((size_t)p * a.nb + J) * a.Lp + I * 64 + r] = s;
-      a.sc.rcar[((size_t)p * a.nb + J) * a.Lp + I * 64 + r] = sin;
-    }
+    rpart[qd][r] = s;
+    ipart[qd][r] = sin;
   }
   {                                       // columns: four threads per column, 16 rows each
     const int c = tid & 63, qd = tid >> 6;
@@ -944,9 +947,14 @@ __global__ __launch_bounds__(256) void dyn_tile_kernel(SegArgs a) {
     cpart[qd][c] = s;
   }
   __syncthreads();
-  if (tid < 64)
+  if (tid < 64) {
     a.sc.csuf[((size_t)p * a.nb + I) * a.Lp + J * 64 + tid] =
         ((cpart[0][tid] + cpart[1][tid]) + cpart[2][tid]) + cpart[3][tid];
+  } else if (tid < 128) {
+    const int r = tid - 64;
+    a.sc.rowsum[((size_t)p * a.nb + J) * a.Lp + I * 64 + r] = ((rpart[0][r] + rpart[1][r]) + rpart[2][r]) + rpart[3][r];
+    a.sc.rcar[((size_t)p * a.nb + J) * a.Lp + I * 64 + r] = ((ipart[0][r] + ipart[1][r]) + ipart[2][r]) + ipart[3][r];
+  }
 }
 
 // per token: vote (column sum over the tiles below), row sum inside its span, whole row sum
