@@ -291,6 +291,52 @@ def test_whole_step_equals_three_calls_batched(gpu_device, variant):
     assert ctxs[0].sync_status() == 0 and ctxs[1].sync_status() == 0
 
 
+def test_whole_step_layers_and_sequences_against_oracle(gpu_device):
+    """Two layers, five sequences at staggered positions (more than one batch of the segmentation scratch, and
+    selection tickets reused across the batches): ltri_step per layer over all sequences, every (layer, sequence)
+    against an oracle stream of its own — span tables, selections, token lists, sampled output rows."""
+    w = Workload("mini-batch", 8, 2, 128, "bf16", 2048, 256, 4, 256, 0, 300, "uniform", 16, 64)
+    n_layers, n_seqs, L, T = 2, 5, 256, 2048
+    theta = theta_default(w.head_dim)
+    cfg = config_from_workload(w, max_tokens=T, theta=theta, n_layers=n_layers, n_seqs=n_seqs)
+    ctx = LtriContext(cfg, gpu_device)
+    ka, va = ctx.arena_views()
+    ocfg = O.OracleConfig(w.n_q_heads, w.n_kv_heads, w.head_dim, w.dtype, cfg.n_sink, cfg.window,
+                          k_max=cfg.k_max, budget_tokens=cfg.budget_tokens, theta=float(np.float32(theta)))
+    pairs, queries = {}, {}
+    for layer in range(n_layers):
+        for s in range(n_seqs):
+            K, V, Q, _ = planted_stream(w, 60 + layer, device=str(gpu_device), context=T, seq=s)
+            ka[layer, s].copy_(K); va[layer, s].copy_(V)
+            pairs[layer, s] = O.OracleStream(ocfg, K.double().cpu().numpy(), V.double().cpu().numpy())
+            queries[layer, s] = Q
+            for c in range(s):                                  # sequence s starts s chunks ahead
+                ctx.append_chunk(layer, s, 1, L)
+                pairs[layer, s].append_chunk(L)
+    rows = [0, 1, 63, 64, 127, 200, 255]
+    worst = 0.0
+    for step in range(3):
+        for layer in range(n_layers):
+            q = torch.stack([queries[layer, s][(s + step) * L:(s + step + 1) * L] for s in range(n_seqs)]).contiguous()
+            out = ctx.step(layer, 0, n_seqs, None, None, q)
+            for s in range(n_seqs):
+                st = pairs[layer, s]
+                qn = q[s].double().cpu().numpy()
+                st.append_chunk(L)
+                sel = st.retrieve(qn)
+                for h in range(w.n_kv_heads):
+                    sp, ln = ctx.get_spans(layer, s, h)
+                    assert list(sp) == st.starts[h] and list(ln) == st.lens[h], (step, layer, s, h)
+                    ids, scores = ctx.get_selection(layer, s, h)
+                    assert list(ids) == list(sel[h]), (step, layer, s, h)
+                    np.testing.assert_allclose(scores, st.sel_scores[h][:len(scores)], rtol=1e-12, atol=1e-12)
+                    assert list(ctx.get_token_list(layer, s, h)) == list(st.context_tokens(h))
+                want, _ = st.attend(qn, rows=rows)
+                worst = max(worst, float(np.abs(out[s].double().cpu().numpy()[rows] - want).max()))
+    assert worst <= TOL["bf16"], worst
+    assert ctx.sync_status() == 0
+
+
 @pytest.mark.parametrize("heads", [(2, 2), (4, 2), (16, 2), (12, 1)])
 def test_bf16_group_sizes(gpu_device, heads):
     """Query groups of 1, 2, 8 and 12 heads per KV head on the matrix-core kernels (the workgroup shape and the
