@@ -293,7 +293,7 @@ int32_t ltri_step(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_c
  * launches, each on the stream the launch runs on. ltri_read_step_timing synchronises the context's stream,
  * writes two durations (milliseconds) per step for up to `cap` steps since the last read, oldest first, to the
  * host arrays, sets *n to the count and forgets the records. With resident keys and values the first array
- * holds the one attention launch and the second an empty interval (about 0); with kv_offload = 1 the first holds
+ * holds the one attention launch (two events per step) and the second 0; with kv_offload = 1 the first holds
  * the launch over initial | window | chunk on the second stream and the second the launch over the retrieved
  * rows. Steps that run the plain calls (one-token chunks, fp32) leave no record. Turning timing on or off also
  * forgets pending records. */

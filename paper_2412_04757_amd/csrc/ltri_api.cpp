@@ -34,6 +34,7 @@ struct ltri_ctx {
   bool step_timing;
   std::vector<hipEvent_t> tev;
   size_t tev_used;
+  std::vector<uint8_t> tev_parts;     // events of each recorded step: 2 (one attention launch) or 4 (two)
   // host mirror of the stream positions, per (layer, seq)
   std::vector<long long> n_tokens;       // tokens appended
   std::vector<int> last_len;             // length of the chunk appended last (0 = none)
@@ -162,7 +163,7 @@ static int32_t derive(const ltri_config* cfg, Dims& D, StateLayout& SL, ScratchL
   CL.lse = o;    o = align_up(o + (size_t)P * G * Lp * 8, 256);
   // query-span representatives are needed for every sequence of a batched retrieve
   CL.qrep = o;   o = align_up(o + (size_t)c.n_seqs * c.n_kv_heads * Lp * D.d * D.elt, 256);
-  CL.qpart = o;  o = align_up(o + (size_t)P * (Lp / 128 + Lp) * D.d * 8, 256);
+  CL.qpart = o;  o = align_up(o + (size_t)2 * P * (Lp / 128 + Lp) * D.d * 8, 256);
   CL.bounds = o; o = align_up(o + (size_t)c.n_kv_heads * (c.chunk_max + 2) * 4, 256);
   CL.selflag = o; o = align_up(o + (size_t)c.n_seqs * c.n_kv_heads * D.max_spans, 256);
   CL.att_part = o; o = align_up(o + (size_t)c.n_seqs * c.n_q_heads * ATT_MAX_SPLITS * ATT_SPLIT_MAX_ROWS * (D.d + 2) * 4, 256);
@@ -411,9 +412,13 @@ static void append_commit(ltri_ctx* c, int layer, int seq_begin, int seq_count, 
 // Step 1 of a chunk whose rows are already in the arenas: segmentation and index vectors. `fork` (or NULL)
 // is recorded on the context's stream behind the last kernel that fills the chip; what follows it there
 // are kernels of a few workgroups each.
+// q_step2 (or NULL): the query rows that step 2 will be called with right after; *sums_ready then says whether the
+// running sums it reads were taken along by the segmentation's first launch.
 static int32_t append_spans(ltri_ctx* c, int layer, const BatchPos& bp, int seq_count, const void* q_seg, int n_new,
-                            hipEvent_t fork, bool rep_keys_later = false) {
+                            hipEvent_t fork, bool rep_keys_later = false, const void* q_step2 = nullptr,
+                            bool* sums_ready = nullptr) {
   int32_t r;
+  if (sums_ready) *sums_ready = false;
   if (n_new == 1) {
     r = check_hip(c, launch_append_single(c->D, c->ds, c->k_arena, layer, bp, seq_count, c->stream),
                   "append (single token)");
@@ -422,11 +427,16 @@ static int32_t append_spans(ltri_ctx* c, int layer, const BatchPos& bp, int seq_
   }
   const int per = c->CL.max_problems / c->D.Hkv;     // sequences per segmentation launch
   const bool dynamic = c->D.rep_mode == LTRI_REP_DYNAMIC;
+  // one batch of sequences only: the sums of a second batch would take the place of the first one's
+  const bool with_sums = q_step2 && sums_ready && seq_count <= per && retrieve_reads_running_sums(c->D, n_new);
+  RunSums sums;
+  if (with_sums)
+    sums = running_sums_of(c->D, c->dc, c->CL.max_problems, q_step2, rep_keys_later ? c->k_arena : nullptr, n_new);
   for (int off = 0; off < seq_count; off += per) {
     const int cnt = std::min(per, seq_count - off);
     const bool last = off + per >= seq_count;
     r = check_hip(c, launch_segment(c->D, c->ds, c->dc, c->k_arena, q_seg, layer, bp, off, cnt, n_new,
-                                    last && !dynamic ? fork : nullptr, c->stream), "segment");
+                                    last && !dynamic ? fork : nullptr, with_sums ? &sums : nullptr, c->stream), "segment");
     if (r != LTRI_OK) return r;
     if (dynamic) {
       r = check_hip(c, launch_dynamic_reps(c->D, c->ds, c->dc, c->k_arena, q_seg, layer, bp, off, cnt, n_new,
@@ -436,6 +446,7 @@ static int32_t append_spans(ltri_ctx* c, int layer, const BatchPos& bp, int seq_
     }
     c->theta_layer = layer; c->theta_seq0 = bp.seq[off]; c->theta_seqs = cnt;
   }
+  if (with_sums) *sums_ready = true;
   if (c->D.rep_mode == LTRI_REP_MEAN && !rep_keys_later) {   // later: step 2's first launch stores them as well
     r = check_hip(c, launch_rep_keys(c->D, c->ds, c->k_arena, layer, bp, seq_count, n_new, c->stream),
                   "representative keys");
@@ -522,7 +533,8 @@ static int32_t check_query_chunk(ltri_ctx* c, int layer, int seq_begin, int seq_
 }
 
 static int32_t retrieve_impl(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q,
-                             int32_t n_q, int32_t* sel_ids, int32_t* sel_cnt, bool store_rep_keys) {
+                             int32_t n_q, int32_t* sel_ids, int32_t* sel_cnt, bool store_rep_keys,
+                             bool sums_ready = false) {
   BatchPos bp;
   memset(&bp, 0, sizeof bp);
   int32_t r = check_query_chunk(c, layer, seq_begin, seq_count, q, n_q, bp);
@@ -531,7 +543,8 @@ static int32_t retrieve_impl(ltri_ctx* c, int32_t layer, int32_t seq_begin, int3
     long long bound = 0;
     for (int s = 0; s < seq_count; ++s) bound = std::max(bound, c->span_bound[ls_index(c, layer, seq_begin + s)]);
     r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound, sel_ids,
-                                     sel_cnt, nullptr, nullptr, store_rep_keys ? c->k_arena : nullptr, c->stream), "retrieve");
+                                     sel_cnt, nullptr, nullptr, store_rep_keys ? c->k_arena : nullptr, sums_ready, c->stream),
+                  "retrieve");
     if (r != LTRI_OK) return r;
     r = fetch_retrieved(c, layer, bp, seq_count);
     if (r != LTRI_OK) return r;
@@ -580,7 +593,7 @@ int32_t ltri_retrieve_collaborative(ltri_ctx* c, int32_t layer, int32_t seq_begi
     long long bound = 0;
     for (int s = 0; s < seq_count; ++s) bound = std::max(bound, c->span_bound[ls_index(c, layer, seq_begin + s)]);
     r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, n_q, (int)bound,
-                                     sel_ids, sel_cnt, &v, nullptr, nullptr, c->stream), "collaborative retrieve");
+                                     sel_ids, sel_cnt, &v, nullptr, nullptr, false, c->stream), "collaborative retrieve");
     if (r != LTRI_OK) return r;
     r = fetch_retrieved(c, layer, bp, seq_count);
     if (r != LTRI_OK) return r;
@@ -699,12 +712,26 @@ static int32_t timing_mark(ltri_ctx* c, hipStream_t s) {
   if (!c->step_timing) return LTRI_OK;
   if (c->tev_used == c->tev.size()) {
     hipEvent_t e = nullptr;
-    const int32_t r = check_hip(c, hipEventCreate(&e), "timing event");
+    // a device-scope release when recorded: nothing the host reads hangs on these events
+    const int32_t r = check_hip(c, hipEventCreateWithFlags(&e, hipEventReleaseToDevice), "timing event");
     if (r != LTRI_OK) return r;
     c->tev.push_back(e);
   }
   return check_hip(c, hipEventRecord(c->tev[c->tev_used++], s), "timing event");
 }
+
+// The timing events of one step: kept, with their count, when the step was queued whole; dropped otherwise.
+struct StepTiming {
+  ltri_ctx* c;
+  size_t first;
+  bool kept;
+  explicit StepTiming(ltri_ctx* ctx) : c(ctx), first(ctx->tev_used), kept(false) {}
+  void keep() {
+    if (c->tev_used > first) c->tev_parts.push_back((uint8_t)(c->tev_used - first));
+    kept = true;
+  }
+  ~StepTiming() { if (!kept) c->tev_used = first; }
+};
 
 int32_t ltri_set_step_timing(ltri_ctx* c, int32_t on) {
   if (!c) return LTRI_EINVAL;
@@ -714,6 +741,7 @@ int32_t ltri_set_step_timing(ltri_ctx* c, int32_t on) {
     if (r != LTRI_OK) return r;
     c->tev_used = 0;
   }
+  c->tev_parts.clear();
   c->step_timing = on != 0;
   return LTRI_OK;
 }
@@ -724,14 +752,18 @@ int32_t ltri_read_step_timing(ltri_ctx* c, float* local_ms, float* retrieved_ms,
   if (c->dry) return LTRI_OK;
   int32_t r = check_hip(c, hipStreamSynchronize(c->stream), "synchronise");
   if (r != LTRI_OK) return r;
-  const size_t steps = c->tev_used / 4;
-  for (size_t i = 0; i < steps && (int32_t)i < cap; ++i) {
-    r = check_hip(c, hipEventElapsedTime(&local_ms[i], c->tev[4 * i], c->tev[4 * i + 1]), "timing");
-    if (r == LTRI_OK) r = check_hip(c, hipEventElapsedTime(&retrieved_ms[i], c->tev[4 * i + 2], c->tev[4 * i + 3]), "timing");
+  size_t e = 0;
+  for (size_t i = 0; i < c->tev_parts.size() && (int32_t)i < cap; ++i) {
+    r = check_hip(c, hipEventElapsedTime(&local_ms[i], c->tev[e], c->tev[e + 1]), "timing");
+    retrieved_ms[i] = 0.0f;
+    if (r == LTRI_OK && c->tev_parts[i] == 4)
+      r = check_hip(c, hipEventElapsedTime(&retrieved_ms[i], c->tev[e + 2], c->tev[e + 3]), "timing");
     if (r != LTRI_OK) return r;
+    e += c->tev_parts[i];
     ++*n;
   }
   c->tev_used = 0;
+  c->tev_parts.clear();
   return LTRI_OK;
 }
 
@@ -755,7 +787,7 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
     if (retrieve_is_one_launch(c->D, 1, (int)bound)) {
       append_commit(c, layer, seq_begin, seq_count, 1);
       r = check_hip(c, launch_retrieve(c->D, c->ds, c->dc, c->CL.max_problems, q, layer, bp, seq_count, 1, (int)bound,
-                                       nullptr, nullptr, nullptr, c->k_arena, nullptr, c->stream), "append and retrieve (one token)");
+                                       nullptr, nullptr, nullptr, c->k_arena, nullptr, false, c->stream), "append and retrieve (one token)");
       if (r != LTRI_OK) return r;
       r = fetch_retrieved(c, layer, bp, seq_count);
       if (r != LTRI_OK) return r;
@@ -784,15 +816,17 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   int32_t r = append_common(c, layer, seq_begin, seq_count, k_chunk, v_chunk, n_new, bp);
   if (r != LTRI_OK) return r;
   const bool keys_with_step2 = retrieve_stores_rep_keys(c->D, n_new);
+  StepTiming timing(c);
+  bool sums_ready = false;               // step 2's running sums of the query and key rows ride in step 1's first launch
   if (!c->D.offload) {
     // Keys and values resident on the device: the three steps follow each other on the context's stream and the
     // attention is one launch over initial | retrieved | window | chunk. Its workgroups are equal in work (row
     // sub-tiles paired from both ends of the chunk) and fill every compute unit, so a split that runs the first
     // part beside the small kernels of steps 1 and 2 only makes those wait for a free compute unit.
-    r = append_spans(c, layer, bp, seq_count, q_seg, n_new, nullptr, keys_with_step2);
+    r = append_spans(c, layer, bp, seq_count, q_seg, n_new, nullptr, keys_with_step2, q, &sums_ready);
     if (r != LTRI_OK) return r;
     append_commit(c, layer, seq_begin, seq_count, n_new);
-    r = retrieve_impl(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr, keys_with_step2);
+    r = retrieve_impl(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr, keys_with_step2, sums_ready);
     if (r != LTRI_OK) return r;
     r = timing_mark(c, c->stream);
     if (r != LTRI_OK) return r;
@@ -800,8 +834,7 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
                                    c->attend_stages, c->dc.att_part, 0, nullptr, 0, nullptr, c->stream), "attend");
     if (r != LTRI_OK) return r;
     r = timing_mark(c, c->stream);
-    if (r == LTRI_OK) r = timing_mark(c, c->stream);        // no second launch: an empty interval
-    if (r == LTRI_OK) r = timing_mark(c, c->stream);
+    if (r == LTRI_OK) timing.keep();
     return r;
   }
   // Keys and values in host memory: the retrieved rows cross the host link after step 2, so the attention over
@@ -809,7 +842,7 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   // result in.
   float* lse_a = c->dc.att_lse2;
   // Context's stream: the kernels of step 1 that fill the chip, the fork, then the small kernels of steps 1 and 2.
-  r = append_spans(c, layer, bp, seq_count, q_seg, n_new, c->ev_fork, keys_with_step2);
+  r = append_spans(c, layer, bp, seq_count, q_seg, n_new, c->ev_fork, keys_with_step2, q, &sums_ready);
   if (r != LTRI_OK) return r;
   append_commit(c, layer, seq_begin, seq_count, n_new);
   // Second stream, behind the fork: attention over initial | window | chunk.
@@ -824,7 +857,7 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
   if (r == LTRI_OK) r = timing_mark(c, c->side);
   if (r == LTRI_OK) r = check_hip(c, hipEventRecord(c->ev_join, c->side), "join");
   if (r != LTRI_OK) return r;
-  r = retrieve_impl(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr, keys_with_step2);
+  r = retrieve_impl(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr, keys_with_step2, sums_ready);
   // Context's stream again: the join, then the retrieved tokens, whose launch folds the first part's result into
   // its own. Join even after an error, so that the context's stream never runs ahead of the second stream's writes
   // to out.
@@ -837,7 +870,9 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
                                  c->step_stages, nullptr, 2, nullptr, 0, lse_a, c->stream),
                 "attend (retrieved)");
   if (r != LTRI_OK) return r;
-  return timing_mark(c, c->stream);
+  r = timing_mark(c, c->stream);
+  if (r == LTRI_OK) timing.keep();
+  return r;
 }
 
 int32_t ltri_gather_pack(ltri_ctx* c, int32_t layer, int32_t seq, void* k_packed, void* v_packed,

@@ -66,7 +66,8 @@ struct ScratchLayout {
   size_t cxy;      // uint32 [P][SEG_MAX_DIAG]  x << 16 | y
   size_t lse;      // double [P][G][Lp]    (SOFTMAX map only)
   size_t qrep;     // dtype  [n_seqs * Hkv][Lp][d]
-  size_t qpart;    // double [P][Lp / 128 + Lp][d]  sums of 128-token pieces of query spans
+  size_t qpart;    // double [2][P][Lp / 128 + Lp][d]  sums of 128-token pieces of query spans, or running sums of the
+                   //        chunk's query rows [0] and key rows [1]
   size_t bounds;   // int32  [Hkv][chunk_max + 1] + int32 [Hkv]  (append_with_spans)
   size_t selflag;  // uint8  [n_seqs * Hkv][max_spans]  1 = span selected (between the two selection kernels)
   size_t att_part; // float  [n_seqs][Hq][ATT_MAX_SPLITS][ATT_SPLIT_MAX_ROWS][d + 2]  partial attention results
@@ -140,6 +141,28 @@ struct DevScratch {
   int32_t* tickets;   // [2][max_problems] counters of finished workgroups; zero between launches
 };
 
+// Running sums of a chunk's query and key rows (running_sums.h), which step 2 of long chunks with mean
+// representatives reads instead of summing the rows of every span.
+struct RunSums {
+  const void* q;         // [seq][n_q][Hq][128] query rows of the chunk
+  const void* k_arena;   // key rows (the chunk's are in place), or NULL: no running sums of keys
+  double* out;           // [problem][rows][128]
+  size_t keys_off;       // elements from the query rows' sums to the key rows'
+  int n_q;
+  int rows;              // rows per problem in `out`
+};
+// Whether step 2 of a chunk of n_q tokens can read running sums (launch_retrieve decides with the span count at hand).
+bool retrieve_reads_running_sums(const Dims& D, int n_q);
+// Where they go: the buffer of the query-span pieces, which such a step does not use.
+inline RunSums running_sums_of(const Dims& D, const DevScratch& sc, int sc_max_problems, const void* q,
+                               const void* k_arena, int n_q) {
+  RunSums r;
+  r.q = q; r.k_arena = k_arena; r.out = sc.qpart; r.n_q = n_q;
+  r.rows = n_q / 128 + n_q;
+  r.keys_off = (size_t)sc_max_problems * r.rows * D.d;
+  return r;
+}
+
 // ---- launchers (each returns the hipError_t of the launch) ----
 hipError_t launch_fill_zero(void* p, size_t bytes, hipStream_t s);
 hipError_t launch_copy_chunk(const Dims& D, void* k_arena, void* v_arena, const void* k_chunk,
@@ -150,7 +173,9 @@ hipError_t launch_fetch_retrieved(const Dims& D, const DevState& st, void* k_poo
                                   const void* v_host, int layer, const BatchPos& bp, int seq_count, hipStream_t s);
 hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& sc, const void* k_arena,
                           const void* q_seg, int layer, const BatchPos& bp, int batch_off, int seq_count,
-                          int n_new, hipEvent_t after_tiles, hipStream_t s);   // event (or NULL): recorded behind the last kernel that fills the chip
+                          int n_new, hipEvent_t after_tiles, const RunSums* sums, hipStream_t s);
+// event (or NULL): recorded behind the last kernel that fills the chip; sums (or NULL): further workgroups of the
+// first tile launch take these running sums
 hipError_t launch_append_single(const Dims& D, const DevState& st, const void* k_arena, int layer,
                                 const BatchPos& bp, int seq_count, hipStream_t s);
 hipError_t launch_append_bounds(const Dims& D, const DevState& st, const DevScratch& sc, int layer,
@@ -163,9 +188,10 @@ hipError_t launch_rep_keys(const Dims& D, const DevState& st, const void* k_aren
 hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,
                            const void* q, int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
                            int32_t* sel_ids_out, int32_t* sel_cnt_out, const VoteArgs* votes, const void* append_k_arena,
-                           const void* rep_k_arena, hipStream_t s);
-// append_k_arena (or NULL): a one-token chunk's step 1 runs in the same launch; rep_k_arena (or NULL): the launch of
-// the query-span pieces also stores the chunk's mean keys (only where retrieve_stores_rep_keys says so)
+                           const void* rep_k_arena, bool sums_ready, hipStream_t s);
+// append_k_arena (or NULL): a one-token chunk's step 1 runs in the same launch; rep_k_arena (or NULL): the step
+// also stores the chunk's mean keys (only where retrieve_stores_rep_keys says so); sums_ready: the running sums of
+// running_sums_of(D, sc, sc_max_problems, q, rep_k_arena, n_q) are in place (one batch of sequences only)
 bool retrieve_stores_rep_keys(const Dims& D, int n_q);
 bool retrieve_is_one_launch(const Dims& D, int n_q, int span_bound);   // step 2 of a one-token chunk as a single kernel
 hipError_t launch_persist_list(const Dims& D, const DevState& st, int layer, const BatchPos& bp, int seq_count,

@@ -9,6 +9,7 @@
 #include <type_traits>
 #include "device_common.h"
 #include "span_mean.h"
+#include "running_sums.h"
 
 namespace ltri {
 
@@ -21,6 +22,8 @@ struct RetArgs {
   const void* rep_k_arena;                // not NULL: the launch of the query-span pieces also stores the chunk's mean keys
   int qrep_by_last;                       // the last workgroup of the pieces' launch adds them up into Q^R
   int ticket_base;                        // first ticket counter of retrieve_chunk_kernel's problems
+  int qrep_from_sums;                     // retrieve_chunk_kernel builds Q^R (and, with rs.k_arena, the chunk's mean keys)
+  RunSums rs;                             // itself from these running sums
   BatchPos bp;
 };
 
@@ -166,6 +169,14 @@ __global__ __launch_bounds__(1024) void qrep_partial_kernel(RetArgs a) {
     }
   }
   if (threadIdx.x == 0) a.sc.tickets[p] = 0;
+}
+
+// ---- long chunks, mean representatives: the running sums as a launch of their own (when the segmentation's
+//      first launch has not taken them along) ----
+template <int DT>
+__global__ __launch_bounds__(1024) void running_sums_kernel(RetArgs a) {
+  __shared__ double wt[16 * 16 * 8];
+  running_sums_block<DT, 16>(a.D, a.bp, a.layer, a.batch_off, a.rs, blockIdx.x, blockIdx.y, wt);
 }
 
 template <int DT>
@@ -772,12 +783,15 @@ __global__ __launch_bounds__(1024) void retrieve_one_token_kernel(RetArgs a, int
   emit_selection(D, a.st, slot, selmask, n, ids_out, cnt_out);
 }
 
-// ---- step 2 of a long chunk once Q^R of its query spans is in place, in one launch: the scores of all stored
-//      spans (Eq. 8, maximum over the query spans as in Eq. 9), the budgeted selection by sorting and the lists.
-//      gridDim.x workgroups per (sequence, KV head) share the scoring, 256 spans at a time each, so that the
-//      stored vectors stream in through many compute units; the one that finishes last (a ticket counter, left at
-//      zero again) sorts and writes the lists. head_dim 128, spans retrieved (not units), at most RT1_MAX_SPANS
-//      stored spans (the launcher checks). ----
+// ---- step 2 of a long chunk in one launch: the scores of all stored spans (Eq. 8, maximum over the query spans as
+//      in Eq. 9), the budgeted selection by sorting and the lists. gridDim.x = (sequence, KV head) problems;
+//      the gridDim.y workgroups of a problem share its scoring, 256 spans at a time each, so that the stored vectors
+//      stream in through many compute units, and the one that finishes last (a ticket counter, left at zero again)
+//      sorts and writes the lists. Q^R is either in place (qrep_partial_kernel) or, with qrep_from_sums, built
+//      here from the running sums of the chunk's query rows, two rows per query span, and so are, with rs.k_arena, the
+//      mean keys of the chunk's own spans (Sec. 3.3.1): every workgroup of a problem writes the same values to
+//      the same places and reads its own copy back after a barrier. head_dim 128, spans retrieved (not units), at
+//      most RT1_MAX_SPANS stored spans (the launcher checks). ----
 template <int DT>
 __global__ __launch_bounds__(1024) void retrieve_chunk_kernel(RetArgs a, int bound) {
   typedef typename Elt<DT>::type T;
@@ -786,16 +800,62 @@ __global__ __launch_bounds__(1024) void retrieve_chunk_kernel(RetArgs a, int bou
   __shared__ long long wave_tot[16];
   __shared__ int s_last;
   const Dims& D = a.D;
-  const int pl = blockIdx.y, bi = a.batch_off + pl / D.Hkv, h = pl % D.Hkv, pg = bi * D.Hkv + h;
+  const int pl = blockIdx.x, bi = a.batch_off + pl / D.Hkv, h = pl % D.Hkv, pg = bi * D.Hkv + h;
   const int slot = slot_of(D, a.layer, a.bp.seq[bi], h);
   const int32_t* meta = a.st.meta + (size_t)slot * META_WORDS;
   const int d = 128, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = min(meta[META_N_SPANS], bound), c0 = meta[META_CHUNK_START];
-  const int nqs = meta[META_CHUNK_NSP];
-  const T* qrep = reinterpret_cast<const T*>(a.sc.qrep) + (size_t)pg * a.Lp * d;
+  const int nqs = meta[META_CHUNK_NSP], first = meta[META_CHUNK_FIRST];
+  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
+  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
+  T* qrep = reinterpret_cast<T*>(a.sc.qrep) + (size_t)pg * a.Lp * d;
+  T* krep_w = reinterpret_cast<T*>(a.st.krep) + (size_t)slot * D.max_spans * d;
+  if (a.qrep_from_sums && 256 * (int)blockIdx.y < n) {      // (a workgroup without spans to score needs none of it)
+    // representative = (running sum at the span's end - running sum at its start) / length, rounded to the dtype
+    const int n_q = a.rs.n_q, nblk = (n_q + RUNSUM_BLOCK - 1) / RUNSUM_BLOCK;
+    double* carry = reinterpret_cast<double*>(rt1_lds);   // [2][blocks][128]: sum of the rows of all earlier blocks
+    const double* qpre = a.rs.out + (size_t)pl * a.rs.rows * d;
+    const double* kpre = qpre + a.rs.keys_off;
+    const bool with_keys = a.rs.k_arena != nullptr;
+    if (tid < 2 * d && (tid < d || with_keys)) {
+      const int c = tid & 127;
+      const double* src = tid < d ? qpre : kpre;
+      double* dst = carry + (tid < d ? 0 : nblk * d);
+      double run = 0.0;
+      for (int b0 = 0; b0 < nblk; b0 += 16) {
+        double v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+          v[u] = src[(size_t)min((b0 + u) * RUNSUM_BLOCK + RUNSUM_BLOCK - 1, n_q - 1) * d + c];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          if (b0 + u < nblk) dst[(b0 + u) * d + c] = run;
+          run += v[u];
+        }
+      }
+    }
+    __syncthreads();
+    const int c = tid & 127;
+    for (int q = tid >> 7; q < nqs; q += 8) {
+      const int len = slen[first + q];
+      const int x0 = min(max(sstart[first + q] - c0, 0), n_q), x1 = min(x0 + len, n_q);
+      const int b0 = (max(x0, 1) - 1) / RUNSUM_BLOCK, b1 = (max(x1, 1) - 1) / RUNSUM_BLOCK;
+      const size_t o0 = (size_t)(max(x0, 1) - 1) * d + c, o1 = (size_t)(max(x1, 1) - 1) * d + c;
+      const double q0 = x0 > 0 ? carry[b0 * d + c] + qpre[o0] : 0.0;
+      const double q1 = x1 > 0 ? carry[b1 * d + c] + qpre[o1] : 0.0;
+      qrep[(size_t)q * d + c] = Elt<DT>::from_f64((q1 - q0) / (double)len);
+      if (with_keys) {
+        const double k0 = x0 > 0 ? carry[(nblk + b0) * d + c] + kpre[o0] : 0.0;
+        const double k1 = x1 > 0 ? carry[(nblk + b1) * d + c] + kpre[o1] : 0.0;
+        krep_w[(size_t)(first + q) * d + c] = Elt<DT>::from_f64((k1 - k0) / (double)len);
+      }
+    }
+    __syncthreads();
+  }
+  const int n_score = (int)gridDim.y;
   const T* krep = reinterpret_cast<const T*>(a.st.krep) + (size_t)slot * D.max_spans * d;
   double* scores = a.st.scores + (size_t)slot * D.max_spans;
-  for (int i0 = 256 * (int)blockIdx.x + 16 * wave; i0 < n; i0 += 256 * (int)gridDim.x) {   // a tile of 16 spans per wavefront
+  for (int i0 = 256 * (int)blockIdx.y + 16 * wave; i0 < n; i0 += 256 * n_score) {   // a tile of 16 spans per wavefront
     double best[4];
     score_tile_f64<DT>(krep, n, i0, qrep, nqs, d, best);
     if ((lane & 15) == 0) {
@@ -808,8 +868,8 @@ __global__ __launch_bounds__(1024) void retrieve_chunk_kernel(RetArgs a, int bou
     }
   }
   __syncthreads();                                        // the workgroup's stores have completed
-  if (gridDim.x > 1) {
-    if (tid == 0) s_last = atomicAdd(&a.sc.tickets[a.ticket_base + pl], 1) == (int)gridDim.x - 1;
+  if (n_score > 1) {
+    if (tid == 0) s_last = atomicAdd(&a.sc.tickets[a.ticket_base + pl], 1) == n_score - 1;
     __syncthreads();
     if (!s_last) return;
     if (tid == 0) a.sc.tickets[a.ticket_base + pl] = 0;
@@ -818,8 +878,6 @@ __global__ __launch_bounds__(1024) void retrieve_chunk_kernel(RetArgs a, int bou
   uint64_t* skey = reinterpret_cast<uint64_t*>(rt1_lds);
   uint32_t* sidx = reinterpret_cast<uint32_t*>(rt1_lds + (size_t)rt1_pow2(bound) * 8);
   int* clip = reinterpret_cast<int*>(rt1_lds + (size_t)rt1_pow2(bound) * 12);
-  const int32_t* sstart = a.st.span_start + (size_t)slot * D.max_spans;
-  const int32_t* slen = a.st.span_len + (size_t)slot * D.max_spans;
   for (int w = tid; w < (n + 31) / 32 + 2; w += blockDim.x) selmask[w] = 0u;
   for (int i = tid; i < npow; i += blockDim.x) {
     int c = 0;
@@ -1003,6 +1061,11 @@ bool retrieve_is_one_launch(const Dims& D, int n_q, int span_bound) {
   return n_q == 1 && span_bound >= 1 && span_bound <= RT1_MAX_SPANS && D.d == 128 && D.unit == 0;
 }
 
+bool retrieve_reads_running_sums(const Dims& D, int n_q) {
+  return n_q > QREP_PIECE && D.d == 128 && D.unit == 0 && D.dtype == LTRI_BF16 && D.rep_mode == LTRI_REP_MEAN &&
+         (size_t)n_q * 16 + 2048 <= 116 * 1024;     // the readers' table of block sums shares the LDS of the sort
+}
+
 bool retrieve_stores_rep_keys(const Dims& D, int n_q) {
   return n_q > QREP_PIECE && D.rep_mode == LTRI_REP_MEAN;
 }
@@ -1010,12 +1073,13 @@ bool retrieve_stores_rep_keys(const Dims& D, int n_q) {
 hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& sc, int sc_max_problems,
                            const void* q, int layer, const BatchPos& bp, int seq_count, int n_q, int span_bound,
                            int32_t* sel_ids_out, int32_t* sel_cnt_out, const VoteArgs* votes, const void* append_k_arena,
-                           const void* rep_k_arena, hipStream_t s) {
+                           const void* rep_k_arena, bool sums_ready, hipStream_t s) {
   RetArgs a;
   a.D = D; a.st = st; a.sc = sc; a.q = q; a.layer = layer; a.seq_count = seq_count; a.n_q = n_q;
   a.k_arena = append_k_arena; a.append_first = append_k_arena != nullptr;
   a.rep_k_arena = rep_k_arena;
-  a.qrep_by_last = false; a.ticket_base = 0;
+  a.qrep_by_last = false; a.ticket_base = 0; a.qrep_from_sums = 0;
+  a.rs = RunSums{};
   if (rep_k_arena && !retrieve_stores_rep_keys(D, n_q)) return hipErrorInvalidValue;
   if (a.append_first && !retrieve_is_one_launch(D, n_q, span_bound)) return hipErrorInvalidValue;
   a.Lp = (n_q + SEG_TB - 1) / SEG_TB * SEG_TB;
@@ -1061,17 +1125,31 @@ hipError_t launch_retrieve(const Dims& D, const DevState& st, const DevScratch& 
   if (n_q > QREP_PIECE) {
     const int per = sc_max_problems / D.Hkv;               // sequences the piece buffer holds
     const int gx = QREP_GRID_X + (rep_k_arena ? QREP_GRID_X : 0);
-    const size_t lds = rt1_lds_bytes(span_bound);
+    // Mean representatives in bf16 (whose sums are exact in fp64): Q^R and the chunk's mean keys come from running
+    // sums of the query and key rows, which need no span boundaries (no piece sums, no ticket).
+    const bool from_sums = one_tail && retrieve_reads_running_sums(D, n_q);
+    size_t lds = rt1_lds_bytes(span_bound);
+    if (from_sums) {
+      const size_t carry_bytes = (size_t)((n_q + RUNSUM_BLOCK - 1) / RUNSUM_BLOCK) * 2 * 128 * 8;
+      if (lds < carry_bytes) lds = carry_bytes;
+      a.rs = running_sums_of(D, sc, sc_max_problems, q, rep_k_arena, n_q);
+    }
+    if (sums_ready && (!from_sums || seq_count > per)) sums_ready = false;     // not usable: taken here
     for (int off = 0; off < seq_count; off += per) {
       const int cnt = seq_count - off < per ? seq_count - off : per;
       a.batch_off = off;
       dim3 gp(gx, cnt * D.Hkv), gf(n_q < 64 ? n_q : 64, cnt * D.Hkv);
       a.qrep_by_last = one_tail;
       a.ticket_base = sc_max_problems;                      // the second half of the counters
-      if (bf) qrep_partial_kernel<LTRI_BF16><<<gp, 1024, 0, s>>>(a);
-      else    qrep_partial_kernel<LTRI_F32><<<gp, 1024, 0, s>>>(a);
+      if (from_sums) {
+        if (!sums_ready) running_sums_kernel<LTRI_BF16><<<dim3(running_sums_blocks(a.rs, 16), cnt * D.Hkv), 1024, 0, s>>>(a);
+        a.qrep_from_sums = 1;
+      } else {
+        if (bf) qrep_partial_kernel<LTRI_BF16><<<gp, 1024, 0, s>>>(a);
+        else    qrep_partial_kernel<LTRI_F32><<<gp, 1024, 0, s>>>(a);
+      }
       if (one_tail) {
-        const dim3 gt((span_bound + 255) / 256, cnt * D.Hkv);
+        const dim3 gt(cnt * D.Hkv, (span_bound + 255) / 256);
         if (bf) retrieve_chunk_kernel<LTRI_BF16><<<gt, 1024, lds, s>>>(a, span_bound);
         else    retrieve_chunk_kernel<LTRI_F32><<<gt, 1024, lds, s>>>(a, span_bound);
       } else {

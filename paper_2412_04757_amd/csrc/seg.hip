@@ -18,6 +18,7 @@
 #include "device_common.h"
 #include <type_traits>
 #include "span_mean.h"
+#include "running_sums.h"
 
 namespace ltri {
 
@@ -26,6 +27,8 @@ struct SegArgs {
   const void* k_arena; const void* q_seg;
   int layer; int batch_off; int n_new; int nb; int Lp; int ntiles;
   BatchPos bp;
+  int sum_wgs;     // further workgroups per problem of seg_select_kernel's launch that take running sums for step 2
+  RunSums rs;
 };
 
 __device__ __forceinline__ void tile_decode(int t, int& I, int& J) {
@@ -684,7 +687,16 @@ __global__ __launch_bounds__(256) void seg_merge_kernel(SegArgs a) {
 // one round = a workgroup-wide minimum of the order key over the live candidates, the winner is
 // kept, every candidate it suppresses (and the winner itself) dies. One workgroup per problem.
 __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
-  __shared__ uint32_t kept[SEG_MAX_DIAG + 1];
+  __shared__ __attribute__((aligned(16))) uint32_t kept[SEG_MAX_DIAG + 1];
+  if (blockIdx.y > 0) {
+    // Not a selection: running sums of the chunk's query and key rows (bf16, head_dim 128), which step 2 reads once
+    // the spans are known. They need nothing of the segmentation, and this launch leaves all but a few compute
+    // units idle, so they ride along here (gridDim.y - 1 workgroups per problem, dispatched after the selections).
+    static_assert(sizeof(kept) >= 16 * 16 * 8 * sizeof(double), "staging of the running sums");
+    running_sums_block<LTRI_BF16, 16>(a.D, a.bp, a.layer, a.batch_off, a.rs, (int)blockIdx.y - 1, blockIdx.x,
+                                      reinterpret_cast<double*>(kept));
+    return;
+  }
   __shared__ uint64_t s_w1[2][16];
   __shared__ uint32_t s_w2[2][16];
   __shared__ uint8_t flags[SEG_MAX_L + 64];
@@ -1324,6 +1336,8 @@ hipError_t launch_dynamic_reps(const Dims& D, const DevState& st, const DevScrat
   a.batch_off = batch_off; a.n_new = n_new;
   a.nb = (n_new + SEG_TB - 1) / SEG_TB; a.Lp = a.nb * SEG_TB; a.ntiles = a.nb * (a.nb + 1) / 2;
   a.bp = bp;
+  a.sum_wgs = 0;
+  a.rs = RunSums{};
   const int P = seq_count * D.Hkv;
   const bool bf = D.dtype == LTRI_BF16;
   dim3 gl((a.Lp + 255) / 256, P), gt(a.ntiles, P);
@@ -1349,12 +1363,19 @@ hipError_t launch_dynamic_reps(const Dims& D, const DevState& st, const DevScrat
 
 hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& sc, const void* k_arena,
                           const void* q_seg, int layer, const BatchPos& bp, int batch_off, int seq_count,
-                          int n_new, hipEvent_t after_tiles, hipStream_t s) {
+                          int n_new, hipEvent_t after_tiles, const RunSums* sums, hipStream_t s) {
   SegArgs a;
   a.D = D; a.st = st; a.sc = sc; a.k_arena = k_arena; a.q_seg = q_seg; a.layer = layer;
   a.batch_off = batch_off; a.n_new = n_new;
   a.nb = (n_new + SEG_TB - 1) / SEG_TB; a.Lp = a.nb * SEG_TB; a.ntiles = a.nb * (a.nb + 1) / 2;
   a.bp = bp;
+  a.sum_wgs = 0;
+  a.rs = RunSums{};
+  if (sums) {
+    if (D.d != 128 || D.dtype != LTRI_BF16 || sums->n_q != n_new) return hipErrorInvalidValue;
+    a.rs = *sums;
+    a.sum_wgs = running_sums_blocks(a.rs, 16);
+  }
   const int P = seq_count * D.Hkv;
   const bool bf = D.dtype == LTRI_BF16;
   dim3 gt(a.ntiles, P);
@@ -1393,7 +1414,7 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
   }
   dim3 gm((2 * n_new - 1 + 255) / 256, P);
   seg_merge_kernel<<<gm, 256, 0, s>>>(a);
-  seg_select_kernel<<<P, 1024, 0, s>>>(a);
+  seg_select_kernel<<<dim3(P, 1 + a.sum_wgs), 1024, 0, s>>>(a);
   return hipGetLastError();
 }
 
