@@ -11,6 +11,7 @@
 // only (the two parts of a step that overlaps steps 1 and 2), and splits the key range of
 // a block of 2 to 4 query rows. One-token chunks (decode) have a kernel without LDS staging
 // further down; fp32 contexts a plain one-wavefront-per-row kernel.
+#include <hip/hip_ext.h>
 #include "device_common.h"
 #include <type_traits>
 
@@ -887,7 +888,8 @@ hipError_t attend_static_scratch(float** ptr) {
 hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena, const void* v_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
                          void* out, float* lse, int stages, float* part, int part_mode, const int32_t* loclist,
-                         int loc_cap, const float* lse_a, hipStream_t s) {
+                         int loc_cap, const float* lse_a, hipStream_t s, hipEvent_t t_begin, hipEvent_t t_end) {
+  if ((t_begin == nullptr) != (t_end == nullptr)) return hipErrorInvalidValue;
   AttArgs a;
   a.D = D; a.st = st; a.k_arena = k_arena; a.v_arena = v_arena; a.q = q; a.out = out; a.lse = lse;
   a.layer = layer; a.seq_count = seq_count; a.n_q = n_q; a.bp = bp;
@@ -902,10 +904,12 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
   if (kind == 1) {
     a.n_splits = ns_short;
     dim3 g(a.n_splits, D.Hkv, seq_count);
+    if (t_begin) { if (hipError_t e = hipEventRecord(t_begin, s); e != hipSuccess) return e; }
     if (D.G == 4)      attend_decode_kernel<4><<<g, 64 * DEC_WAVES, 0, s>>>(a);
     else if (D.G == 2) attend_decode_kernel<2><<<g, 64 * DEC_WAVES, 0, s>>>(a);
     else               attend_decode_kernel<1><<<g, 64 * DEC_WAVES, 0, s>>>(a);
     attend_merge_kernel<<<dim3(1, D.Hq, seq_count), 128, 0, s>>>(a);
+    if (t_end) { if (hipError_t e = hipEventRecord(t_end, s); e != hipSuccess) return e; }
     return hipGetLastError();
   }
   if (mfma_ok) {
@@ -928,13 +932,28 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
       if (e != hipSuccess) return e;
       attr_set = true;
     }
-    if (stages == 3) attend_bf16_kernel<NW, 3><<<g, 64 * NW, att_lds_bytes(3, NW), s>>>(a);
-    else             attend_bf16_kernel<NW, 4><<<g, 64 * NW, att_lds_bytes(4, NW), s>>>(a);
-    if (a.n_splits > 1) attend_merge_kernel<<<dim3(n_q, D.Hq, seq_count), 128, 0, s>>>(a);
+    if (t_begin) {
+      // the events ride in the kernel's own dispatch; with a merge behind it the end is recorded after that
+      const hipEvent_t stop = a.n_splits > 1 ? nullptr : t_end;
+      if (stages == 3)
+        hipExtLaunchKernelGGL((attend_bf16_kernel<NW, 3>), g, dim3(64 * NW), (uint32_t)att_lds_bytes(3, NW), s, t_begin, stop, 0, a);
+      else
+        hipExtLaunchKernelGGL((attend_bf16_kernel<NW, 4>), g, dim3(64 * NW), (uint32_t)att_lds_bytes(4, NW), s, t_begin, stop, 0, a);
+    } else if (stages == 3) {
+      attend_bf16_kernel<NW, 3><<<g, 64 * NW, att_lds_bytes(3, NW), s>>>(a);
+    } else {
+      attend_bf16_kernel<NW, 4><<<g, 64 * NW, att_lds_bytes(4, NW), s>>>(a);
+    }
+    if (a.n_splits > 1) {
+      attend_merge_kernel<<<dim3(n_q, D.Hq, seq_count), 128, 0, s>>>(a);
+      if (t_end) { if (hipError_t e = hipEventRecord(t_end, s); e != hipSuccess) return e; }
+    }
   } else {
     dim3 g(n_q, D.Hq, seq_count);
+    if (t_begin) { if (hipError_t e = hipEventRecord(t_begin, s); e != hipSuccess) return e; }
     if (D.dtype == LTRI_BF16) attend_simple_kernel<LTRI_BF16><<<g, 64, 0, s>>>(a);
     else                      attend_simple_kernel<LTRI_F32><<<g, 64, 0, s>>>(a);
+    if (t_end) { if (hipError_t e = hipEventRecord(t_end, s); e != hipSuccess) return e; }
   }
   return hipGetLastError();
 }

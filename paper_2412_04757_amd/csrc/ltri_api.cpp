@@ -247,7 +247,7 @@ static int32_t create_impl(const ltri_config* cfg, void* k_arena, void* v_arena,
   c->stream = (hipStream_t)hip_stream;
   c->dry = dry;
   c->attend_stages = 4;
-  c->step_stages = 3;
+  c->step_stages = 4;
   c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
   c->n_cus = 0;
   c->static_part = nullptr;
@@ -348,10 +348,10 @@ static size_t ls_index(const ltri_ctx* c, int layer, int seq) { return (size_t)l
 
 // Host-offloaded KV: once a selection's token list is written, the rows of its retrieved tokens are fetched from
 // the host arenas into the device pool, on the context's stream, before anything attends.
-static int32_t fetch_retrieved(ltri_ctx* c, int layer, const BatchPos& bp, int seq_count) {
+static int32_t fetch_retrieved(ltri_ctx* c, int layer, const BatchPos& bp, int seq_count, hipStream_t s = nullptr) {
   if (!c->D.offload || c->dry) return LTRI_OK;
   return check_hip(c, launch_fetch_retrieved(c->D, c->ds, c->k_arena, c->v_arena, c->k_host, c->v_host, layer, bp,
-                                             seq_count, c->stream), "fetch retrieved rows");
+                                             seq_count, s ? s : c->stream), "fetch retrieved rows");
 }
 
 extern "C" {
@@ -532,9 +532,11 @@ static int32_t check_query_chunk(ltri_ctx* c, int layer, int seq_begin, int seq_
   return LTRI_OK;
 }
 
+// fork and fetch_stream (both or neither; host-offloaded KV): the fetch of the retrieved rows is queued on that
+// stream behind the event, which is recorded behind the kernels of step 2.
 static int32_t retrieve_impl(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_count, const void* q,
                              int32_t n_q, int32_t* sel_ids, int32_t* sel_cnt, bool store_rep_keys,
-                             bool sums_ready = false) {
+                             bool sums_ready = false, hipEvent_t fork = nullptr, hipStream_t fetch_stream = nullptr) {
   BatchPos bp;
   memset(&bp, 0, sizeof bp);
   int32_t r = check_query_chunk(c, layer, seq_begin, seq_count, q, n_q, bp);
@@ -546,7 +548,12 @@ static int32_t retrieve_impl(ltri_ctx* c, int32_t layer, int32_t seq_begin, int3
                                      sel_cnt, nullptr, nullptr, store_rep_keys ? c->k_arena : nullptr, sums_ready, c->stream),
                   "retrieve");
     if (r != LTRI_OK) return r;
-    r = fetch_retrieved(c, layer, bp, seq_count);
+    if (fork) {
+      r = check_hip(c, hipEventRecord(fork, c->stream), "fork");
+      if (r == LTRI_OK) r = check_hip(c, hipStreamWaitEvent(fetch_stream, fork, 0), "fork");
+      if (r != LTRI_OK) return r;
+    }
+    r = fetch_retrieved(c, layer, bp, seq_count, fetch_stream);
     if (r != LTRI_OK) return r;
   }
   for (int s = 0; s < seq_count; ++s) {
@@ -707,8 +714,9 @@ int32_t ltri_attend_static(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_
   return attend_impl(c, layer, seq_begin, seq_count, q, n_q, out, lse, true);
 }
 
-// Next timing event of the context (created on first use), recorded on `s`; a no-op while timing is off.
-static int32_t timing_mark(ltri_ctx* c, hipStream_t s) {
+// Next timing event of the context (created on first use), not recorded yet; NULL while timing is off.
+static int32_t timing_event(ltri_ctx* c, hipEvent_t* ev) {
+  *ev = nullptr;
   if (!c->step_timing) return LTRI_OK;
   if (c->tev_used == c->tev.size()) {
     hipEvent_t e = nullptr;
@@ -717,7 +725,14 @@ static int32_t timing_mark(ltri_ctx* c, hipStream_t s) {
     if (r != LTRI_OK) return r;
     c->tev.push_back(e);
   }
-  return check_hip(c, hipEventRecord(c->tev[c->tev_used++], s), "timing event");
+  *ev = c->tev[c->tev_used++];
+  return LTRI_OK;
+}
+static int32_t timing_mark(ltri_ctx* c, hipStream_t s) {
+  hipEvent_t e = nullptr;
+  const int32_t r = timing_event(c, &e);
+  if (r != LTRI_OK || !e) return r;
+  return check_hip(c, hipEventRecord(e, s), "timing event");
 }
 
 // The timing events of one step: kept, with their count, when the step was queued whole; dropped otherwise.
@@ -828,40 +843,52 @@ int32_t ltri_step(ltri_ctx* c, int32_t layer, int32_t seq_begin, int32_t seq_cou
     append_commit(c, layer, seq_begin, seq_count, n_new);
     r = retrieve_impl(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr, keys_with_step2, sums_ready);
     if (r != LTRI_OK) return r;
-    r = timing_mark(c, c->stream);
+    hipEvent_t t_begin = nullptr, t_end = nullptr;     // the attention launch carries its timing events itself
+    r = timing_event(c, &t_begin);
+    if (r == LTRI_OK) r = timing_event(c, &t_end);
     if (r != LTRI_OK) return r;
     r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse,
-                                   c->attend_stages, c->dc.att_part, 0, nullptr, 0, nullptr, c->stream), "attend");
-    if (r != LTRI_OK) return r;
-    r = timing_mark(c, c->stream);
+                                   c->attend_stages, c->dc.att_part, 0, nullptr, 0, nullptr, c->stream, t_begin, t_end),
+                  "attend");
     if (r == LTRI_OK) timing.keep();
     return r;
   }
-  // Keys and values in host memory: the retrieved rows cross the host link after step 2, so the attention over
-  // initial | window | chunk runs on a second stream meanwhile and the launch over the retrieved rows folds its
-  // result in.
+  // Keys and values in host memory: the rows of the retrieved tokens cross the host link after step 2, which takes
+  // longer than anything else in the step. That fetch runs on a second stream; the attention over initial | window
+  // | chunk follows step 2 on the context's stream, beside the fetch, and the launch over the retrieved rows, behind
+  // the join, folds its result in. (The attention stays on the stream whose kernels precede it: once the fetch
+  // fills the host link, a launch on another stream starts 100-200 us late. Measured alternatives: beside the small
+  // kernels of steps 1 and 2 the first part holds every compute unit's LDS and step 2's last launch waits for it to
+  // end; and the chunk's rows written out to the host beside step 1, by a kernel of any size or by copies, slow
+  // step 1's kernels by as much as the overlap gains: 21 -> 140 us for the first tile kernel.)
   float* lse_a = c->dc.att_lse2;
-  // Context's stream: the kernels of step 1 that fill the chip, the fork, then the small kernels of steps 1 and 2.
-  r = append_spans(c, layer, bp, seq_count, q_seg, n_new, c->ev_fork, keys_with_step2, q, &sums_ready);
-  if (r != LTRI_OK) return r;
-  append_commit(c, layer, seq_begin, seq_count, n_new);
-  // Second stream, behind the fork: attention over initial | window | chunk.
-  r = check_hip(c, hipStreamWaitEvent(c->side, c->ev_fork, 0), "fork");
-  if (r == LTRI_OK)
-    r = check_hip(c, launch_local_list(c->D, bp, seq_count, c->dc.loclist, c->CL.loc_cap, c->side), "local list");
-  if (r == LTRI_OK) r = timing_mark(c, c->side);
-  if (r == LTRI_OK)
-    r = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse_a,
-                                   c->step_stages, nullptr, 1, c->dc.loclist, c->CL.loc_cap, nullptr, c->side),
-                  "attend (initial, window, chunk)");
-  if (r == LTRI_OK) r = timing_mark(c, c->side);
-  if (r == LTRI_OK) r = check_hip(c, hipEventRecord(c->ev_join, c->side), "join");
-  if (r != LTRI_OK) return r;
-  r = retrieve_impl(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr, keys_with_step2, sums_ready);
-  // Context's stream again: the join, then the retrieved tokens, whose launch folds the first part's result into
-  // its own. Join even after an error, so that the context's stream never runs ahead of the second stream's writes
-  // to out.
-  const int32_t rj = check_hip(c, hipStreamWaitEvent(c->stream, c->ev_join, 0), "join");
+  bool side_queued = false;
+  auto both_streams = [&]() -> int32_t {
+    int32_t e = check_hip(c, launch_local_list(c->D, bp, seq_count, c->dc.loclist, c->CL.loc_cap, c->stream), "local list");
+    if (e != LTRI_OK) return e;
+    e = append_spans(c, layer, bp, seq_count, q_seg, n_new, nullptr, keys_with_step2, q, &sums_ready);
+    if (e != LTRI_OK) return e;
+    append_commit(c, layer, seq_begin, seq_count, n_new);
+    side_queued = true;                  // (from here on the second stream may hold work of this step)
+    e = retrieve_impl(c, layer, seq_begin, seq_count, q, n_new, nullptr, nullptr, keys_with_step2, sums_ready, c->ev_fork,
+                      c->side);
+    if (e != LTRI_OK) return e;
+    e = timing_mark(c, c->stream);
+    if (e == LTRI_OK)
+      e = check_hip(c, launch_attend(c->D, c->ds, c->k_arena, c->v_arena, q, layer, bp, seq_count, n_new, out, lse_a,
+                                     c->step_stages, nullptr, 1, c->dc.loclist, c->CL.loc_cap, nullptr, c->stream),
+                    "attend (initial, window, chunk)");
+    if (e == LTRI_OK) e = timing_mark(c, c->stream);
+    return e;
+  };
+  r = both_streams();
+  // The join, then the retrieved tokens, whose launch folds the first part's result into its own. Join even after an
+  // error, so that the context's stream never runs ahead of the second stream's writes.
+  int32_t rj = LTRI_OK;
+  if (side_queued) {
+    rj = check_hip(c, hipEventRecord(c->ev_join, c->side), "join");
+    if (rj == LTRI_OK) rj = check_hip(c, hipStreamWaitEvent(c->stream, c->ev_join, 0), "join");
+  }
   if (r != LTRI_OK) return r;
   if (rj != LTRI_OK) return rj;
   r = timing_mark(c, c->stream);

@@ -202,7 +202,10 @@ hipError_t launch_attend(const Dims& D, const DevState& st, const void* k_arena,
                          const void* q, int layer, const BatchPos& bp, int seq_count, int n_q,
                          void* out, float* lse, int stages, float* part, int part_mode, const int32_t* loclist,
                          int loc_cap, const float* lse_a,
-                         hipStream_t s);   // lse_a: the first part's log-sum-exp, for the retrieved part
+                         hipStream_t s, hipEvent_t t_begin = nullptr, hipEvent_t t_end = nullptr);
+// lse_a: the first part's log-sum-exp, for the retrieved part. t_begin / t_end (both or neither): timing events. The
+// matrix-core kernel carries them in its own dispatch (they take the kernel's start and end time stamps, and no
+// marker is queued that the neighbouring launches would wait behind); other shapes record them around the launches.
 // bytes of partial results a launch over seq_count sequences with n_q query rows needs (0: the key range is not split)
 size_t attend_partial_bytes(const Dims& D, int seq_count, int n_q, int n_cus);
 // device address, on the current device, of the library's own buffer of ATT_STATIC_SCRATCH_BYTES for partial results

@@ -216,6 +216,47 @@ def test_whole_step_in_one_call(gpu_device):
     _stream_parity(CONFIGS["cfg1"], 4, 1024, gpu_device, whole_step=True)
 
 
+@pytest.mark.parametrize("kv_offload", [0, 1])
+def test_step_timing_records(gpu_device, kv_offload):
+    """The step timing aid: one record per ltri_step of a long bf16 chunk (none for a one-token chunk), plausible
+    durations (resident: the one attention launch, carried by its own dispatch, and 0; host-offloaded: two
+    launches), records forgotten by a read, and outputs bit for bit those of the same stream without timing."""
+    w = Workload("mini-timing", 8, 2, 128, "bf16", 2048, 256, 4, 256, 0, 300, "uniform", 16, 64)
+    sizes = [256, 256, 1, 200, 256, 256]
+    K, V, Q, _ = planted_stream(w, 71, device=str(gpu_device), context=sum(sizes))
+    outs = {}
+    for timed in (False, True):
+        cfg = config_from_workload(w, max_tokens=sum(sizes), theta=theta_default(w.head_dim), n_layers=1, n_seqs=1,
+                                   kv_offload=kv_offload)
+        ctx = LtriContext(cfg, gpu_device)
+        if not kv_offload:
+            ka, va = ctx.arena_views()
+            ka[0, 0, :, :sum(sizes)].copy_(K); va[0, 0, :, :sum(sizes)].copy_(V)
+        ctx.set_step_timing(timed)
+        c0, got = 0, []
+        for n in sizes:
+            kc = K[:, c0:c0 + n].unsqueeze(0).contiguous() if kv_offload else None
+            vc = V[:, c0:c0 + n].unsqueeze(0).contiguous() if kv_offload else None
+            got.append(ctx.step(0, 0, 1, kc, vc, Q[c0:c0 + n].contiguous()).clone())
+            c0 += n
+        outs[timed] = got
+        a, b = ctx.read_step_timing()
+        if timed:
+            assert len(a) == len(b) == len([n for n in sizes if n > 4])
+            assert np.all(a > 0.0) and np.all(a < 50.0), a
+            if kv_offload:
+                assert np.all(b > 0.0) and np.all(b < 50.0), b
+            else:
+                assert np.all(b == 0.0), b
+            a2, _ = ctx.read_step_timing()
+            assert len(a2) == 0
+        else:
+            assert len(a) == 0
+        assert ctx.sync_status() == 0
+    for x, y in zip(outs[False], outs[True]):
+        assert torch.equal(x, y)
+
+
 def test_whole_step_copies_the_chunk_rows(gpu_device):
     """ltri_step with k_chunk / v_chunk, on a stream of the caller's: the rows reach the arenas before either
     of the library's streams reads them, and a consumer queued on the caller's stream right after the call
