@@ -497,10 +497,11 @@ def main():
 
     traffic = None
     if step_schedule:
-        # The library brackets the attention launches of every step with events on the stream each runs on, inside
-        # the timed region above. Resident keys and values: one launch of attend_bf16_kernel per chunk. Host-offloaded:
-        # two (initial | window | chunk on the library's second stream beside steps 1 and 2 and the fetch, then the
-        # retrieved tokens); achieved = the chunk's algorithmic flops over the sum of the two durations.
+        # The library brackets the attention launches of every step with events on the context's stream, inside the
+        # timed region above. Resident keys and values: one launch of attend_bf16_kernel per chunk (the events ride in
+        # its dispatch). Host-offloaded: two (initial | window | chunk beside the fetch of the retrieved rows, which a
+        # second stream carries and which slows it, then the retrieved tokens); achieved = the chunk's algorithmic
+        # flops over the sum of the two durations.
         t_loc, t_ret = ctx.read_step_timing(cap=args.steps * n_chunks + 8)
         ctx.set_step_timing(False)
         assert len(t_loc) == args.steps * n_chunks, (len(t_loc), args.steps * n_chunks)
@@ -527,7 +528,7 @@ def main():
                 "traffic": traffic,
                 "avg_launch_us": round(tot_ms / len(att_ms) * 1e3, 1),
                 "launches_timed": (("the two attention launches of every ltri_step of the timed streams (events recorded by "
-                                    "the library on the streams the launches run on); durations summed per chunk"
+                                    "the library on the context's stream); durations summed per chunk"
                                     if args.kv_offload else
                                     "the attention launch of every ltri_step of the timed streams (events recorded by the "
                                     "library around the launch)")
@@ -685,14 +686,14 @@ def main():
                    "index_vectors": "mean key per span" if args.index_vectors == "mean"
                    else "dynamic (row ratio, lambda 3): sum of the keys of each span's index tokens",
                    "schedule": "append(c+1) on a second stream next to attend(c)" if overlap else
-                   (("ltri_step per chunk: attention over initial | window | chunk on a second stream beside "
-                     "steps 1 and 2 and the fetch of the retrieved rows, retrieved tokens after, merged" if args.kv_offload else
+                   (("ltri_step per chunk: steps 1 and 2, then the fetch of the retrieved rows on a second stream beside "
+                     "the attention over initial | window | chunk, retrieved tokens after, merged" if args.kv_offload else
                      "ltri_step per chunk: the kernels of the three steps on one stream, one attention launch")
                     if step_schedule else "three calls per chunk, serial")},
         "roofline": roofline, "gather": gather, "cpu_baseline": cpu, "host_link": host_link, "index_footprint": index_footprint,
         "breakdown_ms": {"attend": round(tot_ms / args.steps, 3), "rest_of_step": round(other_ms, 3),
-                         "note": (("attend = sum of the two attention launches of every step; the first one overlaps the "
-                                   "small kernels of steps 1 and 2" if args.kv_offload else
+                         "note": (("attend = sum of the two attention launches of every step; the first one shares the "
+                                   "chip with the fetch over the host link and lasts about as long" if args.kv_offload else
                                    "attend = the attention launch of every step") if step_schedule else "serial calls"),
                          "ms_per_step_three_calls": round(calls_ms_per_step, 3) if calls_ms_per_step else None},
     }

@@ -14,7 +14,8 @@
  *   all     ltri_step           the three in one call: fused kernels on one stream when the
  *                               keys and values are resident on the device; with evicted rows
  *                               in host memory the part of step 3 that does not depend on
- *                               step 2 runs on a second stream beside steps 1 and 2.
+ *                               step 2 runs beside the fetch of the retrieved rows, which a
+ *                               second stream carries.
  *
  * Conventions
  *   - Every function returns an int32 status: 0 = LTRI_OK, negative = error. Nothing
@@ -269,13 +270,16 @@ int32_t ltri_attend_static(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int3
  * NULL; the selection is not copied out, read it with ltri_get_selection).
  * What this call adds is the schedule, which depends on where the evicted keys and values live.
  * Resident on the device (kv_offload = 0): the kernels of the three steps follow each other on the context's
- * stream without a return to the host, the chunk's mean keys are stored by the launch that sums the pieces of
- * its query spans, step 2 is two launches, and the attention is one launch over initial | retrieved | window |
+ * stream without a return to the host. With mean representatives in bf16 (head_dim 128) step 2 is one launch:
+ * running sums of the chunk's query and key rows, which need no span boundaries, are taken by further workgroups
+ * of step 1's last launch, and step 2 forms Q^R of every query span and the mean keys of the chunk's spans as
+ * differences of two of their rows before it scores, selects and writes the lists. Other configurations sum the
+ * rows per span in a launch of their own. The attention is one launch over initial | retrieved | window |
  * chunk; results identical to the three calls.
- * In host memory (kv_offload = 1): the attention over initial tokens, window and the chunk itself depends on
- * neither step 1 nor step 2; it is queued on a second stream the context owns, behind the kernels of step 1
- * that fill the chip, and runs while the small kernels of steps 1 and 2 run and the retrieved rows cross the
- * host link. The attention over the retrieved tokens follows on the context's stream once the first part is
+ * In host memory (kv_offload = 1): the fetch of the retrieved rows over the host link is the longest part of the
+ * step. It is queued on a second stream the context owns, behind step 2; the attention over initial tokens,
+ * window and the chunk itself, which needs none of those rows, follows step 2 on the context's stream and runs
+ * beside the fetch. The attention over the retrieved tokens follows on the context's stream once the fetch is
  * done, and folds the first part's output in by the two log-sum-exps as it writes. The context's stream waits
  * for the second stream before that launch, so for the caller everything is ordered on the context's stream as
  * with the three calls: `out` and `lse` hold the result once that stream reaches the end of this call's work.
@@ -290,12 +294,12 @@ int32_t ltri_step(ltri_ctx* ctx, int32_t layer, int32_t seq_begin, int32_t seq_c
 
 /* Measurement aid for ltri_step (Sec. 3.4 third step, the attention, is where the time goes): with timing on,
  * every ltri_step of a chunk of more than 4 rows on a bf16 context records HIP events around its attention
- * launches, each on the stream the launch runs on. ltri_read_step_timing synchronises the context's stream,
+ * launches, on the context's stream. ltri_read_step_timing synchronises that stream,
  * writes two durations (milliseconds) per step for up to `cap` steps since the last read, oldest first, to the
  * host arrays, sets *n to the count and forgets the records. With resident keys and values the first array
- * holds the one attention launch (two events per step) and the second 0; with kv_offload = 1 the first holds
- * the launch over initial | window | chunk on the second stream and the second the launch over the retrieved
- * rows. Steps that run the plain calls (one-token chunks, fp32) leave no record. Turning timing on or off also
+ * holds the one attention launch (two events per step, carried by the launch's own dispatch: they take the
+ * kernel's start and end) and the second 0; with kv_offload = 1 the first holds the launch over initial | window
+ * | chunk (which shares the chip with the fetch) and the second the launch over the retrieved rows. Steps that run the plain calls (one-token chunks, fp32) leave no record. Turning timing on or off also
  * forgets pending records. */
 int32_t ltri_set_step_timing(ltri_ctx* ctx, int32_t on);
 int32_t ltri_read_step_timing(ltri_ctx* ctx, float* local_ms_host, float* retrieved_ms_host, int32_t cap, int32_t* n);

@@ -21,8 +21,7 @@ __host__ __device__ inline int running_sums_blocks(const RunSums& r, int cg) {
 // Workgroup `w` (0 .. running_sums_blocks - 1) of problem p = (sequence batch_off + p / Hkv, KV head p % Hkv): one
 // block of tokens, query or key rows, and CG of the 16 groups of 8 columns. Called by all 64 * CG threads of a
 // workgroup (CG = 4 or 16); wt: LDS, CG x CG x 8 doubles. A thread takes two tokens and 8 columns, the lanes of a
-// wavefront CG pairs of columns groups and 64 / CG pairs of tokens, so that every row is read in pieces of CG * 16
-// bytes.
+// wavefront CG column groups and 64 / CG pairs of tokens, so that every row is read in pieces of CG * 16 bytes.
 template <int DT, int CG>
 __device__ __forceinline__ void running_sums_block(const Dims& D, const BatchPos& bp, int layer, int batch_off,
                                                    const RunSums& r, int w, int p, double* wt) {
