@@ -735,25 +735,62 @@ __global__ __launch_bounds__(1024) void seg_select_kernel(SegArgs a) {
       const uint64_t o1 = ((uint64_t)hi << 32) | lo;
       if (key_less(o1, o2, k1, k2)) { k1 = o1; k2 = o2; }
     };
+    // The minimum over lanes goes by the keys' upper 32 bits first (one exchange and one minimum per step instead
+    // of three exchanges and a 96-bit comparison); when exactly one lane holds that minimum its whole key is read
+    // from that lane, otherwise (a tie in the upper bits: rare) the full keys are reduced.
+    auto hi_min = [](auto steps, uint32_t m) {
+      constexpr int S = decltype(steps)::value;
+      m = min(m, lane_xor_c<1>(m));
+      m = min(m, lane_xor_c<2>(m));
+      m = min(m, lane_xor_c<4>(m));
+      m = min(m, lane_xor_c<8>(m));
+      if constexpr (S > 4) {
+        m = min(m, lane_xor_c<16>(m));
+        m = min(m, lane_xor_c<32>(m));
+      }
+      return m;
+    };
     const bool wave_alive = __ballot(b1 != ~0ull) != 0ull;       // uniform over the wavefront
     if (wave_alive) {
-      step(std::integral_constant<int, 1>{}, b1, b2);
-      step(std::integral_constant<int, 2>{}, b1, b2);
-      step(std::integral_constant<int, 4>{}, b1, b2);
-      step(std::integral_constant<int, 8>{}, b1, b2);
-      step(std::integral_constant<int, 16>{}, b1, b2);
-      step(std::integral_constant<int, 32>{}, b1, b2);
+      const uint32_t hi = (uint32_t)(b1 >> 32);
+      const uint32_t m = hi_min(std::integral_constant<int, 6>{}, hi);
+      const uint64_t tie = __ballot(hi == m);
+      if (__popcll(tie) == 1) {
+        const int src = __ffsll((long long)tie) - 1;
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)b1, src);
+        b2 = (uint32_t)__builtin_amdgcn_readlane((int)b2, src);
+        b1 = ((uint64_t)m << 32) | lo;
+      } else {
+        step(std::integral_constant<int, 1>{}, b1, b2);
+        step(std::integral_constant<int, 2>{}, b1, b2);
+        step(std::integral_constant<int, 4>{}, b1, b2);
+        step(std::integral_constant<int, 8>{}, b1, b2);
+        step(std::integral_constant<int, 16>{}, b1, b2);
+        step(std::integral_constant<int, 32>{}, b1, b2);
+      }
     }
     const int buf = round & 1;                   // two buffers: one barrier per round
     if (lane == 0) { s_w1[buf][wave] = b1; s_w2[buf][wave] = b2; }
     __syncthreads();
-    // the best of the 16 wavefronts: one entry per lane of every row of 16 lanes, four exchange steps
+    // the best of the 16 wavefronts: one entry per lane of every row of 16 lanes
     uint64_t w1 = s_w1[buf][lane & 15];
     uint32_t w2 = s_w2[buf][lane & 15];
-    step(std::integral_constant<int, 1>{}, w1, w2);
-    step(std::integral_constant<int, 2>{}, w1, w2);
-    step(std::integral_constant<int, 4>{}, w1, w2);
-    step(std::integral_constant<int, 8>{}, w1, w2);
+    {
+      const uint32_t hi = (uint32_t)(w1 >> 32);
+      const uint32_t m = hi_min(std::integral_constant<int, 4>{}, hi);
+      const uint64_t tie = __ballot(hi == m) & 0xFFFFull;         // the first row of 16 lanes
+      if (__popcll(tie) == 1) {
+        const int src = __ffsll((long long)tie) - 1;
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)w1, src);
+        w2 = (uint32_t)__builtin_amdgcn_readlane((int)w2, src);
+        w1 = ((uint64_t)m << 32) | lo;
+      } else {
+        step(std::integral_constant<int, 1>{}, w1, w2);
+        step(std::integral_constant<int, 2>{}, w1, w2);
+        step(std::integral_constant<int, 4>{}, w1, w2);
+        step(std::integral_constant<int, 8>{}, w1, w2);
+      }
+    }
     if (w1 == ~0ull) break;                      // nothing alive (uniform)
     if (tid == 0) kept[nkept] = w2;
     ++nkept;
