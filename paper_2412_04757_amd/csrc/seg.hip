@@ -653,7 +653,7 @@ __global__ __launch_bounds__(256) void seg_merge_kernel(SegArgs a) {
   const int b = s >> 6;
   for (int bb = b; bb >= b - 1 && bb >= 0; --bb) {
     const int sloc = s - 64 * bb;
-    if (sloc > 126) continue;
+    if (sloc > 126 || bb > 2 * (nb - 1)) continue;          // (no tile has I + J > 2 (nb - 1))
     // at most 16 tiles lie on one block anti-diagonal; all their entries are loaded before
     // the comparison chain so that the loads are in flight together
     const int J0 = max(0, bb - (nb - 1));
