@@ -13,27 +13,25 @@ namespace ltri {
 
 constexpr int RUNSUM_BLOCK = 128;
 
-// Workgroups per problem that running_sums_block<DT, CG> is to be called by.
+// Workgroups per problem that running_sums_block<DT, CG> is to be called by: one per block of query rows and
+// column slab, one per two blocks of key rows (a key block is a quarter of the rows of a query block of the
+// paper's model) and column slab.
 __host__ __device__ inline int running_sums_blocks(const RunSums& r, int cg) {
-  return (r.n_q + RUNSUM_BLOCK - 1) / RUNSUM_BLOCK * (r.k_arena ? 2 : 1) * (16 / cg);
+  const int nblk = (r.n_q + RUNSUM_BLOCK - 1) / RUNSUM_BLOCK;
+  return (nblk + (r.k_arena ? (nblk + 1) / 2 : 0)) * (16 / cg);
 }
 
-// Workgroup `w` (0 .. running_sums_blocks - 1) of problem p = (sequence batch_off + p / Hkv, KV head p % Hkv): one
-// block of tokens, query or key rows, and CG of the 16 groups of 8 columns. Called by all 64 * CG threads of a
-// workgroup (CG = 4 or 16); wt: LDS, CG x CG x 8 doubles. A thread takes two tokens and 8 columns, the lanes of a
-// wavefront CG column groups and 64 / CG pairs of tokens, so that every row is read in pieces of CG * 16 bytes.
+// One block of tokens (query or key rows) and CG of the 16 groups of 8 columns, for problem p = (sequence
+// batch_off + p / Hkv, KV head p % Hkv). Called by all 64 * CG threads of a workgroup (CG = 4 or 16); wt: LDS,
+// CG x CG x 8 doubles. A thread takes two tokens and 8 columns, the lanes of a wavefront CG column groups and
+// 64 / CG pairs of tokens, so that every row is read in pieces of CG * 16 bytes.
 template <int DT, int CG>
-__device__ __forceinline__ void running_sums_block(const Dims& D, const BatchPos& bp, int layer, int batch_off,
-                                                   const RunSums& r, int w, int p, double* wt) {
+__device__ __forceinline__ void running_sums_one(const Dims& D, const BatchPos& bp, int layer, int batch_off,
+                                                 const RunSums& r, int blk, int slab, bool keys, int p, double* wt) {
   typedef typename Elt<DT>::type T;
   constexpr int N = 16 / (int)sizeof(T);                // elements per 16-byte piece
   constexpr int NP = 8 / N;                             // pieces per 8 columns
-  constexpr int SLABS = 16 / CG;                        // workgroups that share a block's columns
   const int d = 128, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int nblk = (r.n_q + RUNSUM_BLOCK - 1) / RUNSUM_BLOCK;
-  const int slab = w % SLABS, wb = w / SLABS;
-  const bool keys = wb >= nblk;
-  const int blk = keys ? wb - nblk : wb;
   const int cgl = tid % CG, tp = tid / CG;              // column group inside the slab, pair of tokens
   const int col = (slab * CG + cgl) * 8;
   const int bi = batch_off + p / D.Hkv, h = p % D.Hkv;
@@ -97,6 +95,25 @@ __device__ __forceinline__ void running_sums_block(const Dims& D, const BatchPos
     }
     if (ok0) *reinterpret_cast<double2*>(out + (size_t)t0 * d + e) = make_double2(c0 + acc0[e], c1 + acc0[e + 1]);
     if (ok1) *reinterpret_cast<double2*>(out + (size_t)(t0 + 1) * d + e) = make_double2(c0 + acc1[e], c1 + acc1[e + 1]);
+  }
+}
+
+// Workgroup `w` (0 .. running_sums_blocks - 1) of problem p.
+template <int DT, int CG>
+__device__ __forceinline__ void running_sums_block(const Dims& D, const BatchPos& bp, int layer, int batch_off,
+                                                   const RunSums& r, int w, int p, double* wt) {
+  constexpr int SLABS = 16 / CG;                        // workgroups that share a block's columns
+  const int nblk = (r.n_q + RUNSUM_BLOCK - 1) / RUNSUM_BLOCK;
+  const int slab = w % SLABS, wb = w / SLABS;
+  if (wb < nblk) {
+    running_sums_one<DT, CG>(D, bp, layer, batch_off, r, wb, slab, false, p, wt);
+    return;
+  }
+  const int b0 = 2 * (wb - nblk);
+  running_sums_one<DT, CG>(D, bp, layer, batch_off, r, b0, slab, true, p, wt);
+  if (b0 + 1 < nblk) {                                  // uniform over the workgroup
+    __syncthreads();                                    // wt is written again
+    running_sums_one<DT, CG>(D, bp, layer, batch_off, r, b0 + 1, slab, true, p, wt);
   }
 }
 
