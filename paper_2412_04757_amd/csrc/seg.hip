@@ -167,7 +167,8 @@ __device__ __forceinline__ void compute_tile(const SegArgs& a, int p, int I, int
 // found so far by their next 11-bit digit (LDS histogram, then integer atomics, so the result does not depend on
 // the order of execution), after which a one-workgroup step picks the digit that holds the rank; or, once at
 // most QUANT_LIST_CAP cells share the prefix, appends their keys to a list, and the one-workgroup step finishes
-// the selection on the list. Three (tile pass, pick) pairs are launched: for maps whose cells are not massively
+// the selection on the list. Three (tile pass, pick) pairs are launched, the first tile pass inside pass 1 of the
+// segmentation (seg_tile_sums_kernel, whose sums do not depend on theta): for maps whose cells are not massively
 // tied that is two counting passes and one collecting pass (one collecting pass for chunks of up to 180 tokens).
 // A last kernel, one workgroup per problem, finishes whatever is left by walking the tiles itself (it returns at
 // once when the selection is done): ties of more than QUANT_LIST_CAP cells within 2^-10 relative cost time there,
@@ -219,19 +220,19 @@ __global__ __launch_bounds__(256) void quant_init_kernel(SegArgs a, unsigned lon
   }
 }
 
-// One tile of a tile pass (all 256 threads; Ms holds the tile on return from compute_tile). status: the problem's
-// status word as read by the caller.
-template <int DT, int KIND>
-__device__ __forceinline__ void quant_tile_step(const SegArgs& a, int p, int I, int J, unsigned long long status,
-                                                double* Ms, QuantShared& S) {
+// One tile of a tile pass (all 256 threads), in two parts: quant_tile_clear before the tile is computed (a barrier
+// lies between the two), quant_tile_cells once it is in Ms (which it only reads). status: the problem's status
+// word as read by the caller.
+__device__ __forceinline__ void quant_tile_clear(QuantShared& S) {
+  for (int b = threadIdx.x; b < QUANT_BINS; b += blockDim.x) S.hist[b] = 0u;
+  if (threadIdx.x == 0) S.cnt = 0u;
+}
+__device__ __forceinline__ void quant_tile_cells(const SegArgs& a, int p, int I, int J, unsigned long long status,
+                                                 const double* Ms, QuantShared& S) {
   unsigned long long* st = a.sc.qstate + (size_t)p * QUANT_STATE_WORDS;
   const bool collect = quant_count(status) <= (unsigned long long)QUANT_LIST_CAP;
   const int digit = quant_digits(status);
   const int tid = threadIdx.x;
-  for (int b = tid; b < QUANT_BINS; b += blockDim.x) S.hist[b] = 0u;
-  if (tid == 0) S.cnt = 0u;
-  compute_tile<DT, KIND>(a, p, I, J, Ms);
-  __syncthreads();
   const uint64_t prefix = qload(st + 0);
   const int hi = 64 - QUANT_BITS * digit;                 // bits from here up are the prefix (64: none yet)
   // a thread takes 16 consecutive cells of one row; a wavefront 64 consecutive rows (row pitch 65: no bank conflicts)
@@ -277,6 +278,15 @@ __device__ __forceinline__ void quant_tile_step(const SegArgs& a, int p, int I, 
     uint64_t k;
     if (matches(c, k)) { if (at < (unsigned long long)QUANT_LIST_CAP) list[at] = k; ++at; }
   }
+}
+
+template <int DT, int KIND>
+__device__ __forceinline__ void quant_tile_step(const SegArgs& a, int p, int I, int J, unsigned long long status,
+                                                double* Ms, QuantShared& S) {
+  quant_tile_clear(S);
+  compute_tile<DT, KIND>(a, p, I, J, Ms);
+  __syncthreads();
+  quant_tile_cells(a, p, I, J, status, Ms, S);
 }
 
 // The step after a tile pass (all 256 threads of one workgroup per problem): after a counting pass, the digit
@@ -423,16 +433,24 @@ __global__ __launch_bounds__(256) void quant_finish_kernel(SegArgs a) {
 }
 
 // ---- pass 1: per-tile row sums, suffix-scanned column sums, total ----
-template <int DT, int KIND>
+// QUANT (theta as a percentile of the map): the first tile pass of the selection rides here, on the same tile; the
+// sums do not depend on theta.
+template <int DT, int KIND, bool QUANT>
 __global__ __launch_bounds__(256) void seg_tile_sums_kernel(SegArgs a) {
   __shared__ double Ms[64 * 65];
   __shared__ double cpart[4][64];
   __shared__ double rpart[4][64];
+  __shared__ typename std::conditional<QUANT, QuantShared, int>::type S;
   const int p = blockIdx.y;
   int I, J;
   tile_decode(blockIdx.x, I, J);
+  if constexpr (QUANT) quant_tile_clear(S);
   compute_tile<DT, KIND>(a, p, I, J, Ms);
   __syncthreads();
+  if constexpr (QUANT) {
+    const unsigned long long status = qload(a.sc.qstate + (size_t)p * QUANT_STATE_WORDS + 3);
+    quant_tile_cells(a, p, I, J, status, Ms, S);       // (reads the tile; the sums below read it too)
+  }
   const int tid = threadIdx.x;
   {                                       // row sums: four threads per row, 16 columns each; a wavefront takes
     const int r = tid & 63, qd = tid >> 6;  // 64 consecutive rows (row pitch 65: no bank conflicts)
@@ -1429,13 +1447,16 @@ hipError_t launch_segment(const Dims& D, const DevState& st, const DevScratch& s
       const double n_cells = (double)n_new * (double)(n_new + 1) / 2.0;
       const unsigned long long rank = (unsigned long long)floor(D.theta_quantile * (n_cells - 1.0));
       quant_init_kernel<<<P, 256, 0, s>>>(a, rank, (unsigned long long)n_cells);
-      for (int pass = 0; pass < QUANT_TILE_PASSES; ++pass) {
+      seg_tile_sums_kernel<DT, KIND, true><<<gt, 256, 0, s>>>(a);      // pass 1 and the selection's first tile pass
+      quant_pick_kernel<<<P, 256, 0, s>>>(a);
+      for (int pass = 1; pass < QUANT_TILE_PASSES; ++pass) {
         quant_tile_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
         quant_pick_kernel<<<P, 256, 0, s>>>(a);
       }
       quant_finish_kernel<DT, KIND><<<P, 256, 0, s>>>(a);
+    } else {
+      seg_tile_sums_kernel<DT, KIND, false><<<gt, 256, 0, s>>>(a);
     }
-    seg_tile_sums_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
     seg_tile_scan_kernel<DT, KIND><<<gt, 256, 0, s>>>(a);
   };
   using std::integral_constant;
