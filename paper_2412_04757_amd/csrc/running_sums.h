@@ -5,7 +5,9 @@
 // Layout: out[problem][token][128] (fp64, `rows` rows per problem) holds, for token t, the sum of the rows of the
 // tokens of t's block of RUNSUM_BLOCK tokens up to and including t; the reader adds the last rows of the earlier
 // blocks. The key rows' sums follow `keys_off` elements behind the query rows'. head_dim 128 only. Sums of bf16
-// values in fp64 are exact, so the result does not depend on the order of the additions.
+// values in fp64 are exact while the values of a column span less than 2^30 in magnitude over the chunk (8 bits
+// each, 13 for the row count, 53 in all), so the result does not depend on the order of the additions and a
+// difference of two running sums is the sum over the rows between them.
 #pragma once
 #include "device_common.h"
 
