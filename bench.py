@@ -537,6 +537,16 @@ def main():
                 "full_context_launch_us": round(sum(att_ms[i] for i in last) / len(last) * 1e3, 1),
                 "full_context_achieved": round(last_tflops, 2)}
 
+    # what the timing events of the timed region cost: the same streams once more without them (not the headline)
+    untimed_ms_per_step = None
+    if step_schedule and not args.no_single_launch:
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            one_stream_steps()
+        torch.cuda.synchronize()
+        untimed_ms_per_step = (time.perf_counter() - t1) / args.steps * 1e3
+
     calls_ms_per_step = None
     single = None
     if step_schedule and not args.no_single_launch:
@@ -633,7 +643,9 @@ def main():
     # share of the step spent outside attend (append + retrieve + launch gaps)
     other_ms = ms_per_step - tot_ms / args.steps
     log(f"[bench] {ms_per_step:.2f} ms per stream" +
-        (f" (with the three plain calls {calls_ms_per_step:.2f} ms)" if calls_ms_per_step else "") +
+        (f" (with the three plain calls {calls_ms_per_step:.2f} ms" +
+         (f", without the timing events {untimed_ms_per_step:.2f} ms" if untimed_ms_per_step else "") + ")"
+         if calls_ms_per_step else "") +
         f": attend {tot_ms / args.steps:.2f} ms, rest {other_ms:.2f} ms; roofline frac {achieved / PEAK_BF16_TFLOPS:.4f}")
 
     cpu = None
@@ -695,7 +707,8 @@ def main():
                          "note": (("attend = sum of the two attention launches of every step; the first one shares the "
                                    "chip with the fetch over the host link and lasts about as long" if args.kv_offload else
                                    "attend = the attention launch of every step") if step_schedule else "serial calls"),
-                         "ms_per_step_three_calls": round(calls_ms_per_step, 3) if calls_ms_per_step else None},
+                         "ms_per_step_three_calls": round(calls_ms_per_step, 3) if calls_ms_per_step else None,
+                         "ms_per_step_without_timing_events": round(untimed_ms_per_step, 3) if untimed_ms_per_step else None},
     }
     print(json.dumps(result), flush=True)
 
