@@ -49,7 +49,7 @@ def _stream_parity(w, seed, T, device, *, seg_map=O.MAP_LOGIT, theta=None, phi=0
                 stable = O.segmentation_is_stable(Kn[h, c0:c0 + n], Qg, seg_map, st.cfg.theta, st.cfg.phi,
                                                   st.cfg.max_spans_per_chunk, rel=2.0 ** -16,
                                                   theta_quantile=st.cfg.theta_quantile,
-                                                  unit=st.cfg.unit_tokens, c0=c0)
+                                                  unit=st.cfg.unit_tokens, c0=c0, draws=8)
                 s, l = ctx.get_spans(0, 0, h)
                 assert not stable, (f"chunk at {c0}, head {h}: spans differ on an audited chunk\n"
                                     f"gpu {list(zip(s, l))[-12:]}\noracle {list(zip(st.starts[h], st.lens[h]))[-12:]}")
