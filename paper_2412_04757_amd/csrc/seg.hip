@@ -496,6 +496,7 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
   int I, J;
   tile_decode(blockIdx.x, I, J);
   const int tid = threadIdx.x, L = a.n_new;
+  const bool whole = I > J && (I + 1) * 64 <= L;      // the tile lies below the diagonal and inside the chunk
   compute_tile<DT, KIND>(a, p, I, J, Ms);
   // The carries of this tile, from the sums of pass 1:
   //   row carry of row i        = sum of the tile row sums of row i over the tiles right of J (J < J' <= I),
@@ -573,14 +574,24 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
     // in fp64 (cells with n <= 0 lie above the diagonal and are masked)
     const int n0 = I * 64 + qd * 16 - x;                            // n - 1 of the thread's first row
     double nd = (double)n0, tri = (double)(n0 * (n0 + 1) / 2);      // |n0| <= 2048: the product fits 32 bits
+    if (whole) {                                                    // (uniform) nothing to mask
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int rl = qd * 16 + r, y = I * 64 + rl;
-      run += w[r];
-      nd += 1.0;
-      tri += nd;
-      const double sv = run - th * tri;                             // Eq. 5
-      Ms[rl * 65 + c] = (x <= y && y < L) ? sv : -INFINITY;
+      for (int r = 0; r < 16; ++r) {
+        run += w[r];
+        nd += 1.0;
+        tri += nd;
+        Ms[(qd * 16 + r) * 65 + c] = run - th * tri;                // Eq. 5
+      }
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int rl = qd * 16 + r, y = I * 64 + rl;
+        run += w[r];
+        nd += 1.0;
+        tri += nd;
+        const double sv = run - th * tri;                           // Eq. 5
+        Ms[rl * 65 + c] = (x <= y && y < L) ? sv : -INFINITY;
+      }
     }
   }
   __syncthreads();
@@ -595,13 +606,24 @@ __global__ __launch_bounds__(256) void seg_tile_scan_kernel(SegArgs a) {
     for (int j = 0; j < 16; ++j) { const int xl = 16 * q + j; v[j] = Ms[((t - xl) & 63) * 65 + xl]; }
     double bestA = -INFINITY, bestB = -INFINITY;
     int xA = -1, xB = -1;
+    if (whole) {                                                    // (uniform) every cell is a cell of the map
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      const int xl = 16 * q + j;
-      const bool first = xl <= t, live = v[j] > -INFINITY;
-      const bool upA = first && live && v[j] >= bestA, upB = !first && live && v[j] >= bestB;
-      bestA = upA ? v[j] : bestA; xA = upA ? xl : xA;
-      bestB = upB ? v[j] : bestB; xB = upB ? xl : xB;
+      for (int j = 0; j < 16; ++j) {
+        const int xl = 16 * q + j;
+        const bool first = xl <= t;
+        const bool upA = first && v[j] >= bestA, upB = !first && v[j] >= bestB;
+        bestA = upA ? v[j] : bestA; xA = upA ? xl : xA;
+        bestB = upB ? v[j] : bestB; xB = upB ? xl : xB;
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int xl = 16 * q + j;
+        const bool first = xl <= t, live = v[j] > -INFINITY;
+        const bool upA = first && live && v[j] >= bestA, upB = !first && live && v[j] >= bestB;
+        bestA = upA ? v[j] : bestA; xA = upA ? xl : xA;
+        bestB = upB ? v[j] : bestB; xB = upB ? xl : xB;
+      }
     }
     double* hb = &Ms[0];                // the tile is consumed: [2][4][64] partial maxima, then their columns
     int* hx = reinterpret_cast<int*>(hb + 512);
