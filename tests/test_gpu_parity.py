@@ -159,6 +159,25 @@ def test_cfg2_full_stream(gpu_device):
     assert n_unstable == 0
 
 
+@pytest.mark.parametrize("seed", [100, 101, 102])
+def test_more_seeds_and_shapes(gpu_device, seed):
+    """Seeds that nobody looked at beforehand, three shapes each (head counts, chunk sizes, budgets), even and ragged
+    chunks, through the three calls and through ltri_step: a chunk whose tiling differs must fail the audit and be one
+    the oracle reaches (the helper's rule), everything else to the usual bars."""
+    for (hq, hkv, chunk, window, budget, T) in [(8, 2, 256, 128, 300, 2048), (32, 8, 512, 700, 900, 3072),
+                                                 (16, 2, 2048, 1024, 2048, 8192)]:
+        w = Workload(f"seed{seed}", hq, hkv, 128, "bf16", T, chunk, 4, window, 0, budget, "uniform", 16, 128)
+        sizes = None
+        if seed % 2 == 0:
+            g = torch.Generator().manual_seed(seed)
+            sizes, left = [], T
+            while left > 0:
+                n = min(int(torch.randint(1, chunk + 1, (1,), generator=g)), left)
+                sizes.append(n); left -= n
+        for whole in (False, True):
+            _stream_parity(w, seed, T, gpu_device, rows=range(0, chunk, 53), whole_step=whole, chunk_sizes=sizes)
+
+
 def test_host_offloaded_kv(gpu_device):
     """Host-offloaded KV (Sec. 3.4 first step: evicted keys and values live in CPU memory): the arenas are pinned
     host memory filled by the appends, the device keeps initial tokens, a ring of the latest tokens and the rows
